@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the incremental RTEC hot path on one MI355X.
+
+A step = one nrt_apply_batch (validate + ingest, frontier expansion, delta gather/fold, affected-row update
+with write-back, all layers) over one synthetic update batch; batches are chained (each step sees the graph
+and caches the previous step left).  Inputs (graph, caches, every batch) are resident in HBM before the timed
+region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default: configs[1])")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (caches resident in one MI355X's HBM, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_20622_amd import workloads as wl
+    from paper_2603_20622_amd import session as S
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+
+    cfg = wl.config(args.config, args.scale)
+    if args.batch_edges:
+        frac = cfg.n_ins / max(1, cfg.n_ins + cfg.n_del)
+        cfg.n_ins = int(round(args.batch_edges * frac))
+        cfg.n_del = args.batch_edges - cfg.n_ins
+    t0 = time.time()
+    src, dst, w, x, params, stream = wl.build(cfg, args.seed)
+    n_total = args.steps + args.warmup
+    batches = [stream.next_batch(cfg.n_ins, cfg.n_del, cfg.n_feat) for _ in range(n_total)]
+    final_edges = stream.edges()
+    t_gen = time.time() - t0
+    print("[bench] %s: generated graph %d/%d and %d batches in %.1fs" % (cfg.name, cfg.n, cfg.e, n_total, t_gen),
+          file=sys.stderr, flush=True)
+
+    ses = S.Session(cfg.spec, params, cfg.n, src, dst, w, x,
+                    max_batch_edges=max(1024, 2 * (cfg.n_ins + cfg.n_del)), max_batch_feats=max(64, 2 * cfg.n_feat))
+    dev_batches = [S.DeviceBatch(b) for b in batches]
+    ses.profiling(True)
+    torch.cuda.synchronize()
+    print("[bench] caches initialised, running %d warmup + %d timed steps" % (args.warmup, args.steps),
+          file=sys.stderr, flush=True)
+
+    for b in dev_batches[:args.warmup]:
+        ses.apply(b)
+    torch.cuda.synchronize()
+
+    L = cfg.spec.n_layers
+    lat = []
+    agg = {"gather_ms": 0.0, "gather_bytes": 0.0, "gather_launches": 0, "update_ms": 0.0, "update_flop": 0.0,
+           "ingest_ms": 0.0, "expand_ms": 0.0, "compact_ms": 0.0, "items_ms": 0.0, "combine_ms": 0.0}
+    per_layer = [dict(n_src=0, n_aff=0, n_pairs=0, n_in=0, gather_ms=0.0, update_ms=0.0, bytes=0.0) for _ in range(L)]
+    dims = cfg.spec.dims
+    edge_updates = 0
+    t_start = time.perf_counter()
+    for b in dev_batches[args.warmup:]:
+        t1 = time.perf_counter()
+        ses.apply(b)
+        lat.append((time.perf_counter() - t1) * 1e3)
+        edge_updates += b.n_edge_updates
+        st = ses.stats()
+        agg["ingest_ms"] += st.ms_ingest
+        for l in range(L):
+            ls = st.layer[l]
+            d_in = dims[l]
+            # algorithmic bytes of the gather launch: per delta message its in-list id and slot-map entry (8 B),
+            # every changed source row once (4*d), every affected aggregate row read and written (8*d)
+            gbytes = ls.n_pairs * 8.0 + ls.n_src * 4.0 * d_in + ls.n_affected * 8.0 * d_in if ls.n_src else 0.0
+            kin = (2 if cfg.spec.kind == wl.SAGE_MEAN else 1) * d_in
+            flop = 2.0 * ls.n_affected * kin * dims[l + 1]
+            if cfg.spec.kind == wl.GIN:
+                flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]
+            if ls.n_src:
+                agg["gather_ms"] += ls.ms_gather
+                agg["gather_bytes"] += gbytes
+                agg["gather_launches"] += 1
+            agg["update_ms"] += ls.ms_update
+            agg["update_flop"] += flop
+            agg["expand_ms"] += ls.ms_expand
+            agg["compact_ms"] += ls.ms_compact
+            agg["items_ms"] += ls.ms_items
+            agg["combine_ms"] += ls.ms_combine
+            pl = per_layer[l]
+            pl["n_src"] += ls.n_src; pl["n_aff"] += ls.n_affected; pl["n_pairs"] += ls.n_pairs
+            pl["n_in"] += ls.n_in_edges; pl["gather_ms"] += ls.ms_gather; pl["update_ms"] += ls.ms_update
+            pl["bytes"] += gbytes
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    K = args.steps
+    ms_per_step = elapsed * 1e3 / K
+    value = edge_updates / elapsed
+
+    nl = max(1, agg["gather_launches"])
+    g_avg_ms = agg["gather_ms"] / nl
+    g_avg_bytes = agg["gather_bytes"] / nl
+    achieved = (g_avg_bytes / 1e9) / (g_avg_ms / 1e3) if g_avg_ms > 0 else 0.0
+    roofline = {"kernel": "gather_kernel (delta-message gather + fold)", "bound": "hbm",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "avg_launch_ms": round(g_avg_ms, 4), "avg_launch_bytes": round(g_avg_bytes),
+                "launches_per_step": agg["gather_launches"] / K}
+    upd_tflops = (agg["update_flop"] / 1e12) / (agg["update_ms"] / 1e3) if agg["update_ms"] > 0 else 0.0
+
+    out = {
+        "metric": "edge_updates_per_s", "value": round(value, 1), "unit": "edge updates/s", "n_gpus": 1,
+        "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name, "model": wl.KIND_NAMES[cfg.spec.kind], "dims": dims, "vertices": cfg.n,
+                   "edges": cfg.e, "batch_inserts": cfg.n_ins, "batch_deletes": cfg.n_del,
+                   "batch_feature_rows": cfg.n_feat, "chained_batches": K, "seed": args.seed, "scale": args.scale},
+        "latency_ms": {"median": round(float(np.median(lat)), 4), "mean": round(float(np.mean(lat)), 4),
+                       "p95": round(float(np.percentile(lat, 95)), 4), "min": round(float(np.min(lat)), 4)},
+        "roofline": roofline,
+        "update_gemm": {"bound": "mfma", "achieved": round(upd_tflops, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
+                        "unit": "TFLOP/s", "frac": round(upd_tflops / FP32_MFMA_PEAK_TFLOPS, 4)},
+        "phase_ms_per_step": {k[:-3]: round(v / K, 4) for k, v in agg.items() if k.endswith("_ms")},
+        "per_layer_avg": [{"layer": l + 1, "n_src": pl["n_src"] / K, "n_affected": pl["n_aff"] / K,
+                           "delta_messages": pl["n_pairs"] / K, "in_edges_scanned": pl["n_in"] / K,
+                           "gather_ms": round(pl["gather_ms"] / K, 4), "update_ms": round(pl["update_ms"] / K, 4),
+                           "gather_GBps": round((pl["bytes"] / 1e9) / (pl["gather_ms"] / 1e3), 1) if pl["gather_ms"] > 0 else 0.0}
+                          for l, pl in enumerate(per_layer)],
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import rtec_oracle as orc
+        fs, fd, fw = final_edges
+        xf = np.array(x, copy=True)
+        for b in batches:
+            if len(b.feat_ids):
+                xf[b.feat_ids] = b.feat_rows
+        t2 = time.perf_counter()
+        ref = orc.forward(cfg.spec, params, cfg.n, fs, fd, fw, xf)
+        t_cpu = time.perf_counter() - t2
+        per_batch = cfg.n_ins + cfg.n_del
+        out["cpu_baseline"] = {"value": round(per_batch / t_cpu, 2), "unit": "edge updates/s",
+                               "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": "one fp64 full-neighbour %d-layer recomputation of the final snapshot "
+                                         "(%.2f s), i.e. the cost per batch without any cache" % (L, t_cpu),
+                               "seconds_per_recompute": round(t_cpu, 3)}
+        got = ses.layer(L).cpu().numpy()
+        err = float(np.max(np.abs(got.astype(np.float64) - ref[-1]) / np.maximum(np.abs(ref[-1]), 1.0)))
+        out["parity_after_chain"] = {"max_rel_err_elementwise": err, "batches_applied": n_total}
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,190 @@
+/*
+ * nrt.h -- C ABI of the incremental runtime-embedding-computation (RTEC) library for one MI355X.
+ *
+ * The library keeps, resident in HBM, a mutable directed graph (out-lists and in-lists) and, for an
+ * L-layer GNN, the per-layer caches the paper's incremental layer needs (Algorithm 1 "Require":
+ * the previous aggregated neighbour embedding and the previous neighbour context), plus the layer
+ * outputs.  nrt_cache_init runs the ordinary full-neighbour forward (Eq. 1) once; nrt_apply_batch
+ * then applies a batch of edge insertions, edge deletions and feature replacements by
+ *   (1) expanding the affected vertex set hop by hop (Algorithm 4),
+ *   (2) gathering delta messages over the affected edges only and folding them into the cached
+ *       aggregates (Algorithm 1 lines 1-6, Algorithm 3 lines 1-8 for GAT),
+ *   (3) re-running the dense update on the affected rows only (Algorithm 1 line 7),
+ *   (4) writing the refreshed rows back into the caches,
+ * and returns the refreshed final-layer rows with the sorted list of affected vertex ids.
+ * By Theorem 1 the result equals a full recomputation on the post-update snapshot.
+ *
+ * Conventions
+ *   - Every call returns an nrt_status.  Nothing throws or aborts.  nrt_last_error() gives a
+ *     message for the last failing call on the calling thread (borrowed, valid until the next call).
+ *   - "device" pointers are HIP device memory of the current device, "host" pointers ordinary
+ *     host memory.  All matrices are dense row-major fp32.  Vertex ids are int32 in [0, N).
+ *   - The library allocates no device memory: the caller queries *_workspace_bytes and passes a
+ *     device buffer (256-byte aligned) that the handle then owns the use of until it is destroyed.
+ *     Inputs are borrowed only for the duration of a call (they are copied into the workspace).
+ *   - stream is the caller's hipStream_t passed as void* (NULL = default stream).  Calls that
+ *     return counts to the host synchronise that stream before returning.
+ *   - Handles are not thread-safe; calls on one handle (and on a cache and its graph) must not overlap.
+ *   - Messages flow source -> destination: an edge <u,v> makes u an in-neighbour of v (N(v) in Eq. 1).
+ *   - The graph is simple and directed: no duplicate edges, no explicit self-loops (GCN and GAT add
+ *     their own implicit self-loop, GraphSAGE and GIN their own self term).
+ */
+#ifndef NRT_H
+#define NRT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NRT_MAX_LAYERS 4
+
+typedef enum {
+    NRT_OK = 0,
+    NRT_ERR_INVALID_ARG = 1, /* null pointer, bad size, bad enum, misaligned or undersized workspace */
+    NRT_ERR_BAD_BATCH = 2,   /* the batch violates its contract; graph and caches are unchanged      */
+    NRT_ERR_STATE = 3,       /* call order misuse                                                     */
+    NRT_ERR_OOM = 4,         /* adjacency pool exhausted (batch not applied) or host allocation failed */
+    NRT_ERR_DEVICE = 5,      /* a HIP call failed                                                     */
+    NRT_ERR_UNSUPPORTED = 6  /* model shape outside what the kernels cover                            */
+} nrt_status;
+
+typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4 } nrt_model_kind;
+
+typedef struct nrt_graph nrt_graph;
+typedef struct nrt_cache nrt_cache;
+
+/*
+ * Model description.  Layer l = 1..L maps width dims[l-1] to dims[l]; hidden layers are activated
+ * (ReLU; ELU for GAT), the last layer is linear.  All widths must be multiples of 4 and <= 1024.
+ *   NRT_GCN       (Eq. 2; Table II row GCN)   d_v = indeg(v)+1;
+ *                 h_v = act( (sum_{u in N(v) U {v}} x_u / sqrt(d_u d_v)) W[l][0] + b[l][0] )
+ *   NRT_SAGE_MEAN (Table II row GraphSAGE, update on the concatenation as in the PinSAGE row)
+ *                 h_v = act( [x_v || mean_{u in N(v)} x_u] W[l][0] + b[l][0] ),  W is [2 d_{l-1}][d_l]
+ *   NRT_GIN       (Fig. 4)  t_v = (1+gin_eps) x_v + sum_u w_uv x_u;
+ *                 h_v = act( ReLU(t_v W[l][0] + b[l][0]) W[l][1] + b[l][1] ),  W[l][1] is [d_l][d_l]
+ *   NRT_GAT       (Eq. 3-4, Algorithms 2-3)  z = x W[l][0] viewed [heads][head_dim], dims[l] = heads*head_dim;
+ *                 e_uv = LeakyReLU_slope(att_dst[l][k] . z_v^k + att_src[l][k] . z_u^k), softmax over
+ *                 N(v) U {v}, h_v = act( sum_u alpha_uv z_u + b[l][0] )
+ * W, b, att_* are device pointers, row-major [in][out] / [heads][head_dim]; b entries may be NULL (zero).
+ * They are copied at nrt_cache_init.
+ */
+typedef struct {
+    int32_t kind;                       /* nrt_model_kind */
+    int32_t n_layers;                   /* 1..NRT_MAX_LAYERS */
+    int32_t dims[NRT_MAX_LAYERS + 1];   /* d_0..d_L */
+    int32_t heads, head_dim;            /* GAT only */
+    float gin_eps;                      /* GIN only */
+    float leaky_slope;                  /* GAT only */
+    const float* W[NRT_MAX_LAYERS][2];  /* device */
+    const float* b[NRT_MAX_LAYERS][2];  /* device or NULL */
+    const float* att_src[NRT_MAX_LAYERS]; /* device, GAT only */
+    const float* att_dst[NRT_MAX_LAYERS]; /* device, GAT only */
+} nrt_model_desc;
+
+/*
+ * One update batch, applied atomically as three sets (Section IV-B: an inserted element contributes
+ * a positive message, a deleted one a negative message, a replaced one both).  All arrays are device
+ * pointers (may be NULL when the matching count is 0).
+ * Contract: ids in range, no self-loops, no entry repeated inside a list, inserted edges absent from
+ * the graph, deleted edges present, feature ids distinct.  ins_w is required iff the graph is weighted.
+ */
+typedef struct {
+    int64_t n_ins; const int32_t* ins_src; const int32_t* ins_dst; const float* ins_w;
+    int64_t n_del; const int32_t* del_src; const int32_t* del_dst;
+    int64_t n_feat; const int32_t* feat_ids; const float* feat_rows; /* [n_feat][d_0] */
+} nrt_batch;
+
+/* Per-layer counters and timings of the last nrt_apply_batch (timings only when profiling is on). */
+typedef struct {
+    int64_t n_src;        /* |sources of change| entering the layer                        */
+    int64_t n_affected;   /* |A_l|                                                         */
+    int64_t n_items;      /* work items (destination, in-list chunk) of the gather         */
+    int64_t n_in_edges;   /* in-edges of A_l scanned by the gather                         */
+    int64_t n_pairs;      /* (source, destination) delta messages folded (profiling only)  */
+    float ms_expand, ms_compact, ms_items, ms_gather /* the gather kernel alone */, ms_combine, ms_update;
+} nrt_layer_stats;
+
+typedef struct {
+    int32_t n_layers;
+    nrt_layer_stats layer[NRT_MAX_LAYERS];
+    float ms_ingest;      /* validate + structural fold + graph mutation + layer-0 deltas */
+    float ms_total;       /* first to last event of the call                              */
+} nrt_stats;
+
+/* ---- graph -------------------------------------------------------------------------------- */
+
+/* Bytes of device workspace for a graph of n vertices that may grow to e_capacity edges. */
+nrt_status nrt_graph_workspace_bytes(int64_t n_vertices, int64_t e_capacity, int32_t weighted, size_t* bytes /*host*/);
+
+/*
+ * Build the device graph from CSR (out-edges grouped by source) and/or CSC (in-edges grouped by
+ * destination); at least one of the two must be given, the other is derived on the device.
+ *   csr_indptr int64[n+1], csr_indices int32[e] (destinations), csr_weights float[e] or NULL   -- device
+ *   csc_indptr int64[n+1], csc_indices int32[e] (sources),      csc_weights float[e] or NULL   -- device
+ * weighted != 0 requires weights for every given form.  e_capacity >= n_edges bounds later growth.
+ * Errors: NRT_ERR_INVALID_ARG (sizes, ids out of range or self-loops found on the device, workspace too
+ * small).  *out is written only on success.
+ */
+nrt_status nrt_graph_create(int64_t n_vertices, int64_t n_edges, int64_t e_capacity, int32_t weighted,
+                            const int64_t* csr_indptr, const int32_t* csr_indices, const float* csr_weights,
+                            const int64_t* csc_indptr, const int32_t* csc_indices, const float* csc_weights,
+                            void* workspace, size_t workspace_bytes, void* stream, nrt_graph** out);
+void nrt_graph_destroy(nrt_graph*);
+nrt_status nrt_graph_num_edges(const nrt_graph*, int64_t* n_edges /*host*/);
+
+/*
+ * Copy the current in-lists out (tests): indptr int64[n+1], indices int32[cap] device buffers with
+ * cap >= current edge count; weights may be NULL.  Order inside a list is the storage order.
+ */
+nrt_status nrt_graph_export_csc(const nrt_graph*, int64_t* indptr, int32_t* indices, float* weights,
+                                int64_t cap, void* stream);
+
+/* ---- caches ------------------------------------------------------------------------------- */
+
+nrt_status nrt_cache_workspace_bytes(const nrt_graph*, const nrt_model_desc*, int64_t max_batch_edges,
+                                     int64_t max_batch_feats, size_t* bytes /*host*/);
+
+/*
+ * Full L-layer forward over the current graph (Eq. 1 per layer); fills every per-layer cache.
+ * features: device float[n][d_0], copied.  The cache borrows the graph for its lifetime.
+ */
+nrt_status nrt_cache_init(nrt_graph*, const nrt_model_desc*, const float* features, int64_t max_batch_edges,
+                          int64_t max_batch_feats, void* workspace, size_t workspace_bytes, void* stream,
+                          nrt_cache** out);
+void nrt_cache_destroy(nrt_cache*);
+
+/*
+ * Apply one batch incrementally (Algorithms 1, 3, 4).
+ *   affected_ids  device int32[capacity]: the vertices whose final-layer embedding may have changed,
+ *                 ascending, no repeats (the structural affected set of Algorithm 4).
+ *   affected_rows device float[capacity][d_L] or NULL: their refreshed final-layer embeddings.
+ *   n_affected    host: number of entries written.
+ * Errors: NRT_ERR_BAD_BATCH (contract violated, or batch larger than the sizes given at init; state
+ * unchanged), NRT_ERR_OOM (adjacency pool exhausted; state unchanged), NRT_ERR_INVALID_ARG (capacity
+ * smaller than the affected count: caches ARE updated, only the copy-out is skipped, *n_affected holds the
+ * needed capacity).  Synchronises the stream before returning.
+ */
+nrt_status nrt_apply_batch(nrt_cache*, const nrt_batch*, int32_t* affected_ids, float* affected_rows,
+                           int64_t capacity, int64_t* n_affected, void* stream);
+
+/* Borrowed device view of the cached layer output h^l (l = 0: current features), row-major, ld floats per row. */
+nrt_status nrt_get_layer(const nrt_cache*, int32_t layer, const float** rows, int64_t* n_rows, int64_t* ld);
+/* Borrowed device view of the cached aggregate of layer l = 1..L in context-free form (the sum before
+ * msg_cbn is applied: Algorithm 1's a-hat), width floats per row. */
+nrt_status nrt_get_aggregate(const nrt_cache*, int32_t layer, const float** rows, int64_t* n_rows, int64_t* width);
+/* Per-layer affected list A_l (l = 1..L) of the last batch: borrowed device int32 array, ascending. */
+nrt_status nrt_get_layer_affected(const nrt_cache*, int32_t layer, const int32_t** ids, int64_t* n);
+
+nrt_status nrt_set_profiling(nrt_cache*, int32_t on);
+nrt_status nrt_get_stats(const nrt_cache*, nrt_stats* out /*host*/);
+
+const char* nrt_last_error(void);
+const char* nrt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NRT_H */

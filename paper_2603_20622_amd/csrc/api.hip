@@ -1,0 +1,691 @@
+// C ABI of libnrt: handle management and the per-batch orchestration of the kernels.
+#include "common.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+// ------------------------------------------------------------------ errors
+static thread_local char g_err[512] = "";
+void nrt_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+extern "C" const char* nrt_last_error(void) { return g_err; }
+extern "C" const char* nrt_version(void) { return "nrt 0.1 (gfx950)"; }
+
+#define REQUIRE(cond, msg)                     \
+    do {                                       \
+        if (!(cond)) {                         \
+            nrt_set_error("%s", msg);          \
+            return NRT_ERR_INVALID_ARG;        \
+        }                                      \
+    } while (0)
+
+// ------------------------------------------------------------------ cache handle
+constexpr int MAX_EVENTS = 16 + 8 * NRT_MAX_LAYERS;
+
+struct nrt_cache {
+    nrt_graph* g;
+    int kind, L;
+    int dims[NRT_MAX_LAYERS + 1];
+    int dagg[NRT_MAX_LAYERS + 1];       // width of the cached aggregate of layer l
+    int heads, head_dim;
+    float gin_eps, leaky_slope;
+    int64_t max_edges, max_feats;
+    int maxd;
+    float* H[NRT_MAX_LAYERS + 1];
+    float* S[NRT_MAX_LAYERS + 1];
+    float* Wt[NRT_MAX_LAYERS][2];
+    float* bias[NRT_MAX_LAYERS][2];
+    int32_t* indeg_old;
+    uint32_t *bm_ddst, *bm_feat, *bm[2];
+    int32_t* list[NRT_MAX_LAYERS + 1];
+    int64_t n_list[NRT_MAX_LAYERS + 1];
+    int32_t* slot[2];
+    float* DP[2];
+    float* mid;
+    uint64_t* item_off;
+    int32_t *item_slot, *item_chunk, *multi_list;
+    int64_t item_cap, partial_rows;
+    float* partial;
+    int64_t* hub_scratch;
+    int64_t hub_cap;
+    BatchScratch sc;
+    unsigned long long* pair_ctr;
+    // profiling
+    int profiling;
+    hipEvent_t ev[MAX_EVENTS];
+    int ev_tag[MAX_EVENTS];
+    int n_ev;
+    bool events_made;
+    nrt_stats stats;
+};
+
+enum { TAG_START = 0, TAG_INGEST = 1, TAG_EXPAND = 2, TAG_COMPACT = 3, TAG_ITEMS = 4, TAG_GATHER = 5, TAG_UPDATE = 6, TAG_COMBINE = 7 };
+
+static nrt_status prof_mark(nrt_cache* c, int tag, int layer, hipStream_t s) {
+    if (!c->profiling) return NRT_OK;
+    if (c->n_ev >= MAX_EVENTS) return NRT_OK;
+    HIP_TRY(hipEventRecord(c->ev[c->n_ev], s));
+    c->ev_tag[c->n_ev] = tag | (layer << 8);
+    c->n_ev++;
+    return NRT_OK;
+}
+
+static nrt_status prof_collect(nrt_cache* c) {
+    if (!c->profiling || c->n_ev < 2) return NRT_OK;
+    for (int i = 1; i < c->n_ev; ++i) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, c->ev[i - 1], c->ev[i]));
+        const int tag = c->ev_tag[i] & 0xff, l = c->ev_tag[i] >> 8;
+        nrt_layer_stats* ls = (l >= 1 && l <= NRT_MAX_LAYERS) ? &c->stats.layer[l - 1] : nullptr;
+        switch (tag) {
+        case TAG_INGEST: c->stats.ms_ingest += ms; break;
+        case TAG_EXPAND: if (ls) ls->ms_expand += ms; break;
+        case TAG_COMPACT: if (ls) ls->ms_compact += ms; break;
+        case TAG_ITEMS: if (ls) ls->ms_items += ms; break;
+        case TAG_GATHER: if (ls) ls->ms_gather += ms; break;
+        case TAG_UPDATE: if (ls) ls->ms_update += ms; break;
+        case TAG_COMBINE: if (ls) ls->ms_combine += ms; break;
+        default: break;
+        }
+    }
+    float tot = 0.f;
+    HIP_TRY(hipEventElapsedTime(&tot, c->ev[0], c->ev[c->n_ev - 1]));
+    c->stats.ms_total = tot;
+    return NRT_OK;
+}
+
+// ------------------------------------------------------------------ graph
+static void graph_fill(nrt_graph* g, int64_t n, int64_t e, int64_t ecap, int weighted) {
+    memset(g, 0, sizeof(*g));
+    g->n = n;
+    g->e = e;
+    g->e_capacity = ecap;
+    g->weighted = weighted ? 1 : 0;
+}
+
+extern "C" nrt_status nrt_graph_workspace_bytes(int64_t n, int64_t e_capacity, int32_t weighted, size_t* bytes) {
+    REQUIRE(bytes, "bytes is null");
+    REQUIRE(n > 0 && n < (int64_t(1) << 31) - 64, "n_vertices out of range");
+    REQUIRE(e_capacity >= 0 && e_capacity < (int64_t(1) << 40), "e_capacity out of range");
+    nrt_graph g;
+    graph_fill(&g, n, 0, e_capacity, weighted);
+    Bump b{nullptr, 0};
+    graph_layout(b, &g);
+    *bytes = b.used + 256;
+    return NRT_OK;
+}
+
+extern "C" nrt_status nrt_graph_create(int64_t n, int64_t e, int64_t e_capacity, int32_t weighted,
+                                       const int64_t* csr_indptr, const int32_t* csr_indices, const float* csr_weights,
+                                       const int64_t* csc_indptr, const int32_t* csc_indices, const float* csc_weights,
+                                       void* workspace, size_t workspace_bytes, void* stream, nrt_graph** out) {
+    REQUIRE(out, "out is null");
+    REQUIRE(n > 0 && n < (int64_t(1) << 31) - 64, "n_vertices out of range");
+    REQUIRE(e >= 0 && e_capacity >= e, "need 0 <= n_edges <= e_capacity");
+    REQUIRE(csr_indptr || csc_indptr, "need CSR or CSC");
+    REQUIRE(!csr_indptr || csr_indices || e == 0, "csr_indices is null");
+    REQUIRE(!csc_indptr || csc_indices || e == 0, "csc_indices is null");
+    if (weighted) {
+        REQUIRE(!csr_indptr || csr_weights || e == 0, "weighted graph needs csr_weights");
+        REQUIRE(!csc_indptr || csc_weights || e == 0, "weighted graph needs csc_weights");
+    }
+    REQUIRE(workspace && (reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "workspace must be 256-byte aligned");
+    size_t need = 0;
+    NRT_TRY(nrt_graph_workspace_bytes(n, e_capacity, weighted, &need));
+    REQUIRE(workspace_bytes >= need, "graph workspace too small");
+    nrt_graph* g = new (std::nothrow) nrt_graph;
+    if (!g) { nrt_set_error("host allocation failed"); return NRT_ERR_OOM; }
+    graph_fill(g, n, e, e_capacity, weighted);
+    Bump b{static_cast<char*>(workspace), 0};
+    graph_layout(b, g);
+    if (hipHostMalloc((void**)&g->host_pinned, NRT_NCTRS * sizeof(int64_t), hipHostMallocDefault) != hipSuccess) {
+        delete g;
+        nrt_set_error("pinned host allocation failed");
+        return NRT_ERR_OOM;
+    }
+    nrt_status st = graph_build(g, csr_indptr, csr_indices, weighted ? csr_weights : nullptr, csc_indptr, csc_indices,
+                                weighted ? csc_weights : nullptr, static_cast<hipStream_t>(stream));
+    if (st != NRT_OK) {
+        (void)hipHostFree(g->host_pinned);
+        delete g;
+        return st;
+    }
+    *out = g;
+    return NRT_OK;
+}
+
+extern "C" void nrt_graph_destroy(nrt_graph* g) {
+    if (!g) return;
+    if (g->host_pinned) (void)hipHostFree(g->host_pinned);
+    delete g;
+}
+
+extern "C" nrt_status nrt_graph_num_edges(const nrt_graph* g, int64_t* n_edges) {
+    REQUIRE(g && n_edges, "null argument");
+    *n_edges = g->e;
+    return NRT_OK;
+}
+
+__global__ void export_deg_kernel(const int32_t* deg, int64_t n, uint64_t* out) {
+    int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n) out[v] = (uint64_t)deg[v];
+    if (v == n) out[v] = 0;
+}
+__global__ void export_lists_kernel(Adj a, int64_t n, const int64_t* indptr, int32_t* indices, float* weights) {
+    const int64_t v = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (v >= n) return;
+    const int64_t o = a.off[v], b = indptr[v];
+    const int32_t d = a.deg[v];
+    for (int32_t j = lane; j < d; j += 64) {
+        indices[b + j] = a.idx[o + j];
+        if (weights) weights[b + j] = a.wts ? a.wts[o + j] : 1.0f;
+    }
+}
+
+extern "C" nrt_status nrt_graph_export_csc(const nrt_graph* g, int64_t* indptr, int32_t* indices, float* weights,
+                                           int64_t cap, void* stream) {
+    REQUIRE(g && indptr && (indices || g->e == 0), "null argument");
+    REQUIRE(cap >= g->e, "export capacity too small");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t n = g->n;
+    export_deg_kernel<<<(int)cdiv(n + 1, 256), 256, 0, s>>>(g->in.deg, n, (uint64_t*)indptr);
+    LAUNCH_CHECK();
+    NRT_TRY(k_exclusive_scan_u64((uint64_t*)indptr, n + 1, g->scan_tmp, g->scan_tmp_len,
+                                 (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
+    export_lists_kernel<<<(int)cdiv(n * 64, 256), 256, 0, s>>>(g->in, n, indptr, indices, weights);
+    LAUNCH_CHECK();
+    HIP_TRY(hipStreamSynchronize(s));
+    return NRT_OK;
+}
+
+// ------------------------------------------------------------------ cache layout
+static nrt_status check_desc(const nrt_model_desc* d) {
+    REQUIRE(d, "model desc is null");
+    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_GAT, "unknown model kind");
+    REQUIRE(d->n_layers >= 1 && d->n_layers <= NRT_MAX_LAYERS, "n_layers out of range");
+    for (int l = 0; l <= d->n_layers; ++l) {
+        if (d->dims[l] <= 0 || d->dims[l] % 4 || d->dims[l] > 1024) {
+            nrt_set_error("layer widths must be multiples of 4 in [4, 1024]");
+            return NRT_ERR_UNSUPPORTED;
+        }
+    }
+    if (d->kind == NRT_GAT) {
+        nrt_set_error("GAT is not built yet");
+        return NRT_ERR_UNSUPPORTED;
+    }
+    return NRT_OK;
+}
+
+static void cache_layout(Bump& b, nrt_cache* c) {
+    const nrt_graph* g = c->g;
+    const int64_t n = g->n;
+    const int64_t nw = cdiv(n, 32);
+    int maxd = 0;
+    for (int l = 0; l <= c->L; ++l) maxd = c->dims[l] > maxd ? c->dims[l] : maxd;
+    c->maxd = maxd;
+    for (int l = 0; l <= c->L; ++l) c->H[l] = b.take<float>(n * c->dims[l]);
+    c->S[0] = nullptr;
+    for (int l = 1; l <= c->L; ++l) {
+        c->dagg[l] = c->dims[l - 1];
+        c->S[l] = b.take<float>(n * c->dagg[l]);
+    }
+    for (int l = 0; l < c->L; ++l) {
+        const int kin = (c->kind == NRT_SAGE_MEAN ? 2 : 1) * c->dims[l];
+        c->Wt[l][0] = b.take<float>((size_t)kin * c->dims[l + 1]);
+        c->bias[l][0] = b.take<float>(c->dims[l + 1]);
+        if (c->kind == NRT_GIN) {
+            c->Wt[l][1] = b.take<float>((size_t)c->dims[l + 1] * c->dims[l + 1]);
+            c->bias[l][1] = b.take<float>(c->dims[l + 1]);
+        } else {
+            c->Wt[l][1] = nullptr;
+            c->bias[l][1] = nullptr;
+        }
+    }
+    c->indeg_old = b.take<int32_t>(n);
+    c->bm_ddst = b.take<uint32_t>(nw);
+    c->bm_feat = b.take<uint32_t>(nw);
+    c->bm[0] = b.take<uint32_t>(nw);
+    c->bm[1] = b.take<uint32_t>(nw);
+    for (int l = 0; l <= c->L; ++l) c->list[l] = b.take<int32_t>(n);
+    c->slot[0] = b.take<int32_t>(n);
+    c->slot[1] = b.take<int32_t>(n);
+    c->DP[0] = b.take<float>(n * maxd);
+    c->DP[1] = b.take<float>(n * maxd);
+    c->mid = c->kind == NRT_GIN ? b.take<float>(n * maxd) : nullptr;
+    c->item_cap = n + g->e_capacity / NRT_CHUNK + 64;
+    c->partial_rows = 2 * (g->e_capacity / NRT_CHUNK) + 64;
+    c->item_off = b.take<uint64_t>(n + 1);
+    c->item_slot = b.take<int32_t>(c->item_cap);
+    c->item_chunk = b.take<int32_t>(c->item_cap);
+    c->multi_list = b.take<int32_t>(g->e_capacity / NRT_CHUNK + 64);
+    c->partial = b.take<float>(c->partial_rows * maxd);
+    c->hub_cap = g->e_capacity / 2048 + 64;
+    c->hub_scratch = b.take<int64_t>(c->hub_cap / 2 + 8);
+    c->sc.max_edges = c->max_edges;
+    int64_t hc = 16;
+    while (hc < 2 * (c->max_edges + 1)) hc <<= 1;
+    c->sc.hash_cap = hc;
+    c->sc.hash_keys = b.take<uint64_t>(hc);
+    c->sc.pos_out = b.take<int64_t>(c->max_edges + 1);
+    c->sc.pos_in = b.take<int64_t>(c->max_edges + 1);
+    c->sc.del_w = b.take<float>(c->max_edges + 1);
+    c->sc.feat_index = b.take<int32_t>(n);
+    c->sc.feat_stamp = b.take<int32_t>(n);
+    c->sc.err = g->dev_ctrs ? (int32_t*)(g->dev_ctrs + CTR_ERR) : nullptr;
+    c->pair_ctr = b.take<unsigned long long>(1024 * NRT_MAX_LAYERS);
+}
+
+static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_desc* d, int64_t max_edges,
+                             int64_t max_feats) {
+    memset(c, 0, sizeof(*c));
+    c->g = const_cast<nrt_graph*>(g);
+    c->kind = d->kind;
+    c->L = d->n_layers;
+    for (int l = 0; l <= c->L; ++l) c->dims[l] = d->dims[l];
+    c->heads = d->heads;
+    c->head_dim = d->head_dim;
+    c->gin_eps = d->gin_eps;
+    c->leaky_slope = d->leaky_slope;
+    c->max_edges = max_edges;
+    c->max_feats = max_feats;
+    return NRT_OK;
+}
+
+extern "C" nrt_status nrt_cache_workspace_bytes(const nrt_graph* g, const nrt_model_desc* d, int64_t max_batch_edges,
+                                                int64_t max_batch_feats, size_t* bytes) {
+    REQUIRE(g && bytes, "null argument");
+    NRT_TRY(check_desc(d));
+    REQUIRE(max_batch_edges >= 0 && max_batch_feats >= 0, "negative batch bound");
+    nrt_cache c;
+    cache_fill(&c, g, d, max_batch_edges, max_batch_feats);
+    Bump b{nullptr, 0};
+    cache_layout(b, &c);
+    *bytes = b.used + 256;
+    return NRT_OK;
+}
+
+// ------------------------------------------------------------------ shared layer steps
+static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
+    HIP_TRY(hipMemcpyAsync(g->host_pinned, g->dev_ctrs, NRT_NCTRS * sizeof(int64_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    return NRT_OK;
+}
+
+// aggregate layer l for the destinations in list (null: all), then run the dense update
+static nrt_status run_gather(nrt_cache* c, int l, const int32_t* dst_list, int64_t n_dst, bool incremental,
+                             int prev, hipStream_t s) {
+    nrt_graph* g = c->g;
+    NRT_TRY(k_build_items(dst_list, n_dst, g->in.deg, c->item_off, c->item_slot, c->item_chunk, c->multi_list,
+                          g->scan_tmp, g->scan_tmp_len, g->dev_ctrs, s));
+    NRT_TRY(read_ctrs(g, s));
+    const uint64_t packed = (uint64_t)g->host_pinned[CTR_ITEMS];
+    const int64_t n_items = (int64_t)(packed & 0xffffffffu), n_part = (int64_t)(packed >> 32);
+    const int64_t n_multi = g->host_pinned[CTR_MULTI];
+    if (n_items > c->item_cap || n_part > c->partial_rows) {
+        nrt_set_error("internal: item buffers too small (%lld items, %lld partial rows)", (long long)n_items, (long long)n_part);
+        return NRT_ERR_STATE;
+    }
+    if (incremental) {
+        c->stats.layer[l - 1].n_items = n_items;
+        c->stats.layer[l - 1].n_in_edges = g->host_pinned[CTR_INEDGES];
+    }
+    GatherArgs a;
+    memset(&a, 0, sizeof(a));
+    a.dst_list = dst_list;
+    a.n_dst = n_dst;
+    a.item_slot = c->item_slot;
+    a.item_chunk = c->item_chunk;
+    a.item_off = c->item_off;
+    a.n_items_dev = (const uint64_t*)(g->dev_ctrs + CTR_ITEMS);
+    a.in = g->in;
+    a.D = c->dagg[l];
+    a.use_weights = (c->kind == NRT_GIN && g->weighted) ? 1 : 0;
+    a.self_pair = c->kind == NRT_GCN;
+    a.S = c->S[l];
+    a.partial = c->partial;
+    if (incremental) {
+        a.P = c->DP[prev];
+        a.src_bitmap = c->bm[prev];
+        a.src_slot = c->slot[prev];
+        a.src_scale_gcn = 0;
+        a.accumulate = 1;
+        if (c->profiling) {
+            a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
+            NRT_TRY(k_fill_u64((uint64_t*)a.pair_ctr, 1024, 0, s));
+        }
+    } else {
+        a.P = c->H[l - 1];
+        a.src_scale_gcn = c->kind == NRT_GCN;
+        a.accumulate = 0;
+    }
+    NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
+    NRT_TRY(k_gather(a, n_items, s));
+    NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
+    NRT_TRY(k_combine_partials(a, c->multi_list, n_multi, s));
+    NRT_TRY(prof_mark(c, TAG_COMBINE, l, s));
+    return NRT_OK;
+}
+
+static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M, bool incremental, int cur,
+                             float* out_rows, hipStream_t s) {
+    nrt_graph* g = c->g;
+    const bool last = l == c->L;
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = M;
+    a.rows = rows;
+    a.indeg = g->in.deg;
+    a.indeg_old = c->indeg_old;
+    a.ldp = c->dims[l - 1];
+    a.N = c->dims[l];
+    float* dp = (incremental && !last) ? c->DP[cur] : nullptr;
+    if (c->kind == NRT_GCN || c->kind == NRT_SAGE_MEAN) {
+        if (c->kind == NRT_GCN) {
+            a.a_mode = A_SCALE_GCN;
+            a.P0 = c->S[l];
+            a.K = c->dims[l - 1];
+        } else {
+            a.a_mode = A_CONCAT_MEAN;
+            a.P0 = c->H[l - 1];
+            a.P1 = c->S[l];
+            a.K = 2 * c->dims[l - 1];
+        }
+        a.Wt = c->Wt[l - 1][0];
+        a.bias = c->bias[l - 1][0];
+        a.act = last ? 0 : 1;
+        a.H = c->H[l];
+        a.DP = dp;
+        a.dp_scale_gcn = c->kind == NRT_GCN;
+        a.out_compact = last ? out_rows : nullptr;
+        NRT_TRY(k_gemm(a, s));
+    } else {   // GIN: two chained products
+        a.a_mode = A_AXPY;
+        a.P0 = c->H[l - 1];
+        a.P1 = c->S[l];
+        a.axpy_c = 1.0f + c->gin_eps;
+        a.K = c->dims[l - 1];
+        a.Wt = c->Wt[l - 1][0];
+        a.bias = c->bias[l - 1][0];
+        a.act = 1;
+        a.out_compact = c->mid;
+        NRT_TRY(k_gemm(a, s));
+        GemmArgs b2;
+        memset(&b2, 0, sizeof(b2));
+        b2.M = M;
+        b2.rows = rows;
+        b2.a_is_compact = 1;
+        b2.a_mode = A_PLAIN;
+        b2.P0 = c->mid;
+        b2.ldp = c->dims[l];
+        b2.K = c->dims[l];
+        b2.N = c->dims[l];
+        b2.Wt = c->Wt[l - 1][1];
+        b2.bias = c->bias[l - 1][1];
+        b2.act = last ? 0 : 1;
+        b2.H = c->H[l];
+        b2.DP = dp;
+        b2.out_compact = last ? out_rows : nullptr;
+        NRT_TRY(k_gemm(b2, s));
+    }
+    return NRT_OK;
+}
+
+// ------------------------------------------------------------------ cache init
+extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, const float* features,
+                                     int64_t max_batch_edges, int64_t max_batch_feats, void* workspace,
+                                     size_t workspace_bytes, void* stream, nrt_cache** out) {
+    REQUIRE(g && out && features, "null argument");
+    NRT_TRY(check_desc(d));
+    REQUIRE(workspace && (reinterpret_cast<uintptr_t>(workspace) & 255) == 0, "workspace must be 256-byte aligned");
+    size_t need = 0;
+    NRT_TRY(nrt_cache_workspace_bytes(g, d, max_batch_edges, max_batch_feats, &need));
+    REQUIRE(workspace_bytes >= need, "cache workspace too small");
+    if (g->has_cache) { nrt_set_error("graph already has a cache"); return NRT_ERR_STATE; }
+    for (int l = 0; l < d->n_layers; ++l) {
+        REQUIRE(d->W[l][0], "W[l][0] is null");
+        if (d->kind == NRT_GIN) REQUIRE(d->W[l][1], "GIN needs W[l][1]");
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    nrt_cache* c = new (std::nothrow) nrt_cache;
+    if (!c) { nrt_set_error("host allocation failed"); return NRT_ERR_OOM; }
+    cache_fill(c, g, d, max_batch_edges, max_batch_feats);
+    Bump b{static_cast<char*>(workspace), 0};
+    cache_layout(b, c);
+    const int64_t n = g->n;
+    nrt_status st = NRT_OK;
+    auto run = [&]() -> nrt_status {
+        NRT_TRY(k_copy_f32(c->H[0], features, n * c->dims[0], s));
+        NRT_TRY(k_fill_u32((uint32_t*)c->sc.feat_stamp, n, 0, s));
+        for (int l = 0; l < c->L; ++l) {
+            const int kin = (c->kind == NRT_SAGE_MEAN ? 2 : 1) * c->dims[l];
+            NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
+            if (d->b[l][0]) NRT_TRY(k_copy_f32(c->bias[l][0], d->b[l][0], c->dims[l + 1], s));
+            else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][0], c->dims[l + 1], 0, s));
+            if (c->kind == NRT_GIN) {
+                NRT_TRY(k_transpose(d->W[l][1], c->Wt[l][1], c->dims[l + 1], c->dims[l + 1], s));
+                if (d->b[l][1]) NRT_TRY(k_copy_f32(c->bias[l][1], d->b[l][1], c->dims[l + 1], s));
+                else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][1], c->dims[l + 1], 0, s));
+            }
+        }
+        for (int l = 1; l <= c->L; ++l) {
+            NRT_TRY(run_gather(c, l, nullptr, n, false, 0, s));
+            NRT_TRY(run_update(c, l, nullptr, n, false, 0, nullptr, s));
+        }
+        HIP_TRY(hipStreamSynchronize(s));
+        return NRT_OK;
+    };
+    st = run();
+    if (st != NRT_OK) { delete c; return st; }
+    g->has_cache = true;
+    *out = c;
+    return NRT_OK;
+}
+
+extern "C" void nrt_cache_destroy(nrt_cache* c) {
+    if (!c) return;
+    if (c->events_made)
+        for (int i = 0; i < MAX_EVENTS; ++i) (void)hipEventDestroy(c->ev[i]);
+    if (c->g) c->g->has_cache = false;
+    delete c;
+}
+
+// ------------------------------------------------------------------ apply batch
+extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t* affected_ids, float* affected_rows,
+                                      int64_t capacity, int64_t* n_affected, void* stream) {
+    REQUIRE(c && b && n_affected, "null argument");
+    REQUIRE(b->n_ins >= 0 && b->n_del >= 0 && b->n_feat >= 0, "negative batch count");
+    REQUIRE(capacity >= 0 && (capacity == 0 || affected_ids), "affected_ids is null");
+    nrt_graph* g = c->g;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t n = g->n, nw = cdiv(n, 32);
+    if (b->n_ins + b->n_del > c->max_edges || b->n_feat > c->max_feats) {
+        nrt_set_error("batch larger than the bounds given to nrt_cache_init");
+        return NRT_ERR_BAD_BATCH;
+    }
+    if ((b->n_ins && (!b->ins_src || !b->ins_dst)) || (b->n_del && (!b->del_src || !b->del_dst)) ||
+        (b->n_feat && (!b->feat_ids || !b->feat_rows)) || (b->n_ins && g->weighted && !b->ins_w)) {
+        nrt_set_error("batch array is null");
+        return NRT_ERR_BAD_BATCH;
+    }
+    if (g->e + b->n_ins - b->n_del > g->e_capacity) {
+        nrt_set_error("batch would exceed e_capacity");
+        return NRT_ERR_OOM;
+    }
+    memset(&c->stats, 0, sizeof(c->stats));
+    c->stats.n_layers = c->L;
+    c->n_ev = 0;
+    for (int l = 0; l <= c->L; ++l) c->n_list[l] = 0;
+    NRT_TRY(prof_mark(c, TAG_START, 0, s));
+
+    // ---- validate (no state change yet)
+    NRT_TRY(graph_validate_batch(g, b, c->sc, s));
+    NRT_TRY(read_ctrs(g, s));
+    {
+        const int32_t* err = (const int32_t*)(g->host_pinned + CTR_ERR);
+        const char* msg = nullptr;
+        if (err[0]) msg = "vertex id out of range";
+        else if (err[1]) msg = "self-loop in batch";
+        else if (err[4]) msg = "edge repeated inside the batch";
+        else if (err[5]) msg = "feature id repeated inside the batch";
+        else if (err[2]) msg = "inserted edge already present";
+        else if (err[3]) msg = "deleted edge not present";
+        nrt_status bad = NRT_OK;
+        if (msg) { nrt_set_error("%s", msg); bad = NRT_ERR_BAD_BATCH; }
+        else if (g->host_pinned[CTR_HEAD_OUT] + g->host_pinned[CTR_GROW] > g->out.pool_cap ||
+                 g->host_pinned[CTR_HEAD_IN] + g->host_pinned[CTR_GROW + 1] > g->in.pool_cap) {
+            nrt_set_error("adjacency pool exhausted");
+            bad = NRT_ERR_OOM;
+        }
+        if (bad != NRT_OK) {
+            NRT_TRY(graph_cancel_batch(g, b, s));
+            HIP_TRY(hipStreamSynchronize(s));
+            return bad;
+        }
+    }
+    if (b->n_ins + b->n_del + b->n_feat == 0) {
+        NRT_TRY(graph_mutate(g, b, c->sc, s));
+        *n_affected = 0;
+        return NRT_OK;
+    }
+
+    // ---- sets of the batch
+    NRT_TRY(k_fill_u32(c->bm_ddst, nw, 0, s));
+    NRT_TRY(k_fill_u32(c->bm_feat, nw, 0, s));
+    NRT_TRY(k_mark_ids(c->bm_ddst, b->ins_dst, b->n_ins, s));
+    NRT_TRY(k_mark_ids(c->bm_ddst, b->del_dst, b->n_del, s));
+    NRT_TRY(k_mark_ids(c->bm_feat, b->feat_ids, b->n_feat, s));
+    const bool gcn = c->kind == NRT_GCN;
+    if (gcn) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
+
+    // ---- structural terms on the old caches, all layers
+    for (int l = 1; l <= c->L; ++l) {
+        FoldArgs f;
+        memset(&f, 0, sizeof(f));
+        f.n_ins = b->n_ins; f.n_del = b->n_del;
+        f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
+        if (c->kind == NRT_GIN && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
+        f.Hprev = c->H[l - 1];
+        f.indeg_old = gcn ? g->in.deg : nullptr;
+        f.S = c->S[l];
+        f.D = c->dagg[l];
+        NRT_TRY(k_structural_fold(f, s));
+    }
+
+    // ---- graph mutation
+    NRT_TRY(graph_mutate(g, b, c->sc, s));
+
+    // ---- sources of change for layer 1 and their delta payloads
+    NRT_TRY(k_or_words(c->bm[0], c->bm_feat, gcn ? c->bm_ddst : nullptr, nw, s));
+    NRT_TRY(k_compact_bitmap(c->bm[0], n, c->list[0], c->slot[0], g->scan_tmp, g->scan_tmp_len,
+                             (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
+    NRT_TRY(read_ctrs(g, s));
+    c->n_list[0] = g->host_pinned[CTR_COUNT];
+    {
+        DeltaArgs da;
+        memset(&da, 0, sizeof(da));
+        da.list = c->list[0];
+        da.n = c->n_list[0];
+        da.feat_bitmap = c->bm_feat;
+        da.feat_index = c->sc.feat_index;
+        da.feat_rows = b->feat_rows;
+        da.H0 = c->H[0];
+        da.DP = c->DP[0];
+        da.D = c->dims[0];
+        if (gcn) { da.indeg_new = g->in.deg; da.indeg_old = c->indeg_old; }
+        NRT_TRY(k_layer0_delta(da, s));
+    }
+    NRT_TRY(prof_mark(c, TAG_INGEST, 0, s));
+
+    // ---- layers
+    int prev = 0;
+    const bool want_rows = affected_rows != nullptr;
+    nrt_status copy_out = NRT_OK;
+    for (int l = 1; l <= c->L; ++l) {
+        const int cur = 1 - prev;
+        nrt_layer_stats* ls = &c->stats.layer[l - 1];
+        ls->n_src = c->n_list[l - 1];
+        NRT_TRY(k_or_words(c->bm[cur], c->bm_ddst, c->bm[prev], nw, s));
+        NRT_TRY(k_expand_frontier(g->out, c->list[l - 1], c->n_list[l - 1], c->bm[cur], c->hub_scratch, c->hub_cap, s));
+        NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
+        NRT_TRY(k_compact_bitmap(c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp, g->scan_tmp_len,
+                                 (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
+        NRT_TRY(read_ctrs(g, s));
+        c->n_list[l] = g->host_pinned[CTR_COUNT];
+        ls->n_affected = c->n_list[l];
+        NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
+        if (c->n_list[l - 1] > 0) NRT_TRY(run_gather(c, l, c->list[l], c->n_list[l], true, prev, s));
+        float* out_rows = nullptr;
+        if (l == c->L && want_rows) {
+            if (c->n_list[l] <= capacity) out_rows = affected_rows;
+            else copy_out = NRT_ERR_INVALID_ARG;
+        }
+        NRT_TRY(run_update(c, l, c->list[l], c->n_list[l], true, cur, out_rows, s));
+        NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
+        prev = cur;
+    }
+    const int64_t na = c->n_list[c->L];
+    *n_affected = na;
+    if (na <= capacity) NRT_TRY(k_copy_i32(affected_ids, c->list[c->L], na, s));
+    else copy_out = NRT_ERR_INVALID_ARG;
+    HIP_TRY(hipStreamSynchronize(s));
+    NRT_TRY(prof_collect(c));
+    if (c->profiling) {
+        static thread_local unsigned long long host_ctr[1024];
+        for (int l = 1; l <= c->L; ++l) {
+            if (c->n_list[l - 1] == 0) continue;
+            HIP_TRY(hipMemcpy(host_ctr, c->pair_ctr + (size_t)(l - 1) * 1024, sizeof(host_ctr), hipMemcpyDeviceToHost));
+            unsigned long long tot = 0;
+            for (int i = 0; i < 1024; ++i) tot += host_ctr[i];
+            c->stats.layer[l - 1].n_pairs = (int64_t)tot;
+        }
+    }
+    if (copy_out != NRT_OK) nrt_set_error("capacity %lld is smaller than the affected count %lld", (long long)capacity, (long long)na);
+    return copy_out;
+}
+
+// ------------------------------------------------------------------ views, stats
+extern "C" nrt_status nrt_get_layer(const nrt_cache* c, int32_t layer, const float** rows, int64_t* n_rows, int64_t* ld) {
+    REQUIRE(c && rows && n_rows && ld, "null argument");
+    REQUIRE(layer >= 0 && layer <= c->L, "layer out of range");
+    *rows = c->H[layer];
+    *n_rows = c->g->n;
+    *ld = c->dims[layer];
+    return NRT_OK;
+}
+extern "C" nrt_status nrt_get_aggregate(const nrt_cache* c, int32_t layer, const float** rows, int64_t* n_rows,
+                                        int64_t* width) {
+    REQUIRE(c && rows && n_rows && width, "null argument");
+    REQUIRE(layer >= 1 && layer <= c->L, "layer out of range");
+    *rows = c->S[layer];
+    *n_rows = c->g->n;
+    *width = c->dagg[layer];
+    return NRT_OK;
+}
+extern "C" nrt_status nrt_get_layer_affected(const nrt_cache* c, int32_t layer, const int32_t** ids, int64_t* n) {
+    REQUIRE(c && ids && n, "null argument");
+    REQUIRE(layer >= 1 && layer <= c->L, "layer out of range");
+    *ids = c->list[layer];
+    *n = c->n_list[layer];
+    return NRT_OK;
+}
+extern "C" nrt_status nrt_set_profiling(nrt_cache* c, int32_t on) {
+    REQUIRE(c, "null argument");
+    if (on && !c->events_made) {
+        for (int i = 0; i < MAX_EVENTS; ++i) HIP_TRY(hipEventCreate(&c->ev[i]));
+        c->events_made = true;
+    }
+    c->profiling = on ? 1 : 0;
+    return NRT_OK;
+}
+extern "C" nrt_status nrt_get_stats(const nrt_cache* c, nrt_stats* out) {
+    REQUIRE(c && out, "null argument");
+    *out = c->stats;
+    return NRT_OK;
+}

@@ -1,0 +1,183 @@
+// Internal declarations shared by the HIP sources of libnrt (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "nrt.h"
+
+#define NRT_WAVE 64
+// layout of the device counter block (int64 cells) mirrored to pinned host memory in one copy
+enum { CTR_GROW = 0 /*2*/, CTR_HEAD_OUT = 8, CTR_HEAD_IN = 9, CTR_ERR = 16 /*8 x int32*/, CTR_COUNT = 24,
+       CTR_ITEMS = 25 /* low 32 items, high 32 partial rows */, CTR_MULTI = 26, CTR_INEDGES = 27, NRT_NCTRS = 64 };
+#define NRT_CHUNK 256          // in-list entries per gather work item (one wave each)
+
+// ---------------------------------------------------------------- error plumbing (api.hip)
+void nrt_set_error(const char* fmt, ...);
+#define HIP_TRY(expr)                                                                      \
+    do {                                                                                   \
+        hipError_t _e = (expr);                                                            \
+        if (_e != hipSuccess) {                                                            \
+            nrt_set_error("%s failed: %s (%s:%d)", #expr, hipGetErrorString(_e), __FILE__, __LINE__); \
+            return NRT_ERR_DEVICE;                                                         \
+        }                                                                                  \
+    } while (0)
+#define NRT_TRY(expr)                     \
+    do {                                  \
+        nrt_status _s = (expr);           \
+        if (_s != NRT_OK) return _s;      \
+    } while (0)
+#define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
+
+static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---------------------------------------------------------------- workspace bump allocator
+struct Bump {
+    char* base;      // may be null when only sizing
+    size_t used;
+    template <typename T>
+    T* take(size_t count) {
+        used = (used + 255) & ~size_t(255);
+        T* p = base ? reinterpret_cast<T*>(base + used) : nullptr;
+        used += count * sizeof(T);
+        return p;
+    }
+};
+
+// ---------------------------------------------------------------- adjacency in one direction
+// Vertex v owns pool[off[v] .. off[v]+cap[v]) of which the first deg[v] entries are live.
+struct Adj {
+    int64_t* off;
+    int32_t* deg;
+    int32_t* cap;
+    int32_t* idx;      // pool of neighbour ids
+    float* wts;        // pool of weights or null
+    int64_t pool_cap;
+    int64_t* head;     // device counter: first free pool entry
+};
+
+struct nrt_graph {
+    int64_t n, e, e_capacity;
+    int weighted;
+    Adj out, in;       // out: keyed by source, holds destinations; in: keyed by destination, holds sources
+    // scan scratch shared by graph and cache kernels
+    uint64_t* scan_tmp;   // block sums
+    int64_t scan_tmp_len;
+    int32_t* stamp[2];    // per-direction ownership stamps for batch mutation
+    int32_t* inscnt[2];   // per-direction per-vertex pending insert counts (zero between batches)
+    int32_t* delcnt[2];
+    int32_t epoch;
+    int64_t* host_pinned; // small pinned read-back area (64 int64)
+    int64_t* dev_ctrs;    // device counters mirrored into host_pinned (64 int64)
+    bool has_cache;
+};
+
+// ---------------------------------------------------------------- prims.hip
+nrt_status k_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
+nrt_status k_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
+nrt_status k_or_words(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t nwords, hipStream_t s);
+nrt_status k_copy_i32(int32_t* dst, const int32_t* src, int64_t n, hipStream_t s);
+nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
+// exclusive scan of n uint64 values in place; writes the total to *total (device)
+nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_t tmp_len, uint64_t* total, hipStream_t s);
+// sorted ids of the set bits of bitmap (n bits) -> list, slot[id] = position, *count (device) = number
+nrt_status k_compact_bitmap(const uint32_t* bitmap, int64_t n, int32_t* list, int32_t* slot, uint64_t* tmp,
+                            int64_t tmp_len, uint64_t* count, hipStream_t s);
+nrt_status k_mark_ids(uint32_t* bitmap, const int32_t* ids, int64_t n, hipStream_t s);
+
+// ---------------------------------------------------------------- frontier.hip
+// bitmap |= { v : <u,v> in out-lists, u in src_list[0..ns) }
+nrt_status k_expand_frontier(const Adj& out, const int32_t* src_list, int64_t ns, uint32_t* bitmap,
+                             int64_t* hub_scratch, int64_t hub_cap, hipStream_t s);
+
+// ---------------------------------------------------------------- gather.hip
+struct GatherArgs {
+    // destinations
+    const int32_t* dst_list;   // null: destination = slot index (all vertices)
+    int64_t n_dst;
+    // items
+    const int32_t* item_slot;  // [n_items]
+    const int32_t* item_chunk;
+    const uint64_t* item_off;  // per slot: packed (low 32: first item, high 32: first partial row)
+    int64_t n_items_bound;     // launch bound; real count on device
+    const uint64_t* n_items_dev;
+    // graph
+    Adj in;
+    // source rows
+    const float* P;            // rows of width D
+    int D;
+    const uint32_t* src_bitmap; // null: every source contributes and row index = vertex id
+    const int32_t* src_slot;
+    int src_scale_gcn;         // multiply each source row by rsqrt(indeg[u]+1) (full forward, GCN)
+    int use_weights;           // multiply by edge weight
+    int self_pair;             // GCN: add the destination's own row as one more neighbour
+    int accumulate;            // 1: S[v] += sum, 0: S[v] = sum
+    float* S;                  // [N][D]
+    float* partial;            // partial rows for multi-chunk destinations
+    unsigned long long* pair_ctr; // null or 1024 counters
+};
+nrt_status k_build_items(const int32_t* dst_list, int64_t n_dst, const int32_t* indeg, uint64_t* item_off,
+                         int32_t* item_slot, int32_t* item_chunk, int32_t* multi_list, uint64_t* scan_tmp,
+                         int64_t scan_tmp_len, int64_t* dev_ctrs /* fills CTR_ITEMS, CTR_MULTI, CTR_INEDGES */,
+                         hipStream_t s);
+nrt_status k_gather(const GatherArgs& a, int64_t n_items, hipStream_t s);
+nrt_status k_combine_partials(const GatherArgs& a, const int32_t* multi_list, int64_t n_multi, hipStream_t s);
+
+struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update caches
+    int64_t n_ins, n_del;
+    const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
+    const float *ins_w, *del_w;  // null when unweighted
+    const float* Hprev;          // h^{l-1} (old)
+    const int32_t* indeg_old;    // for the GCN payload scale, else null
+    float* S;
+    int D;
+};
+nrt_status k_structural_fold(const FoldArgs& a, hipStream_t s);
+
+struct DeltaArgs {  // layer-0 delta payloads and feature scatter
+    const int32_t* list; int64_t n;
+    const uint32_t* feat_bitmap; const int32_t* feat_index; const float* feat_rows;
+    float* H0; float* DP; int D;
+    const int32_t* indeg_new; const int32_t* indeg_old;   // GCN payload scale, else null
+};
+nrt_status k_layer0_delta(const DeltaArgs& a, hipStream_t s);
+
+// ---------------------------------------------------------------- gemm.hip
+enum { A_PLAIN = 0, A_SCALE_GCN = 1, A_CONCAT_MEAN = 2, A_AXPY = 3 };
+struct GemmArgs {
+    int64_t M; int K; int N;        // K = total inner width (CONCAT: 2*K0)
+    const int32_t* rows;            // null: row m is vertex m
+    int a_is_compact;               // A rows are already compact (row m), rows[] only addresses the write-back
+    int a_mode;
+    const float* P0; const float* P1; int ldp;   // source rows (width ldp each)
+    float axpy_c;                   // A_AXPY: c*P0 + P1
+    const int32_t* indeg;           // for A_SCALE_GCN / A_CONCAT_MEAN
+    const float* Wt;                // transposed weights [N][K]
+    const float* bias;              // [N] or null
+    int act;                        // 0 none, 1 relu, 2 elu
+    // epilogue
+    float* out_compact;             // [M][N] or null
+    float* H;                       // [.][N] scattered by vertex or null
+    float* DP;                      // [M][N] delta payload for the next layer or null
+    const int32_t* indeg_old;       // GCN payload scale for DP (with indeg as new), else null
+    int dp_scale_gcn;
+};
+nrt_status k_gemm(const GemmArgs& a, hipStream_t s);
+nrt_status k_transpose(const float* W, float* Wt, int K, int N, hipStream_t s);   // Wt[n][k] = W[k][n]
+
+// ---------------------------------------------------------------- graph.hip
+nrt_status graph_layout(Bump& b, nrt_graph* g);
+nrt_status graph_build(nrt_graph* g, const int64_t* csr_indptr, const int32_t* csr_indices, const float* csr_w,
+                       const int64_t* csc_indptr, const int32_t* csc_indices, const float* csc_w, hipStream_t s);
+struct BatchScratch {
+    int64_t max_edges;
+    uint64_t* hash_keys; int64_t hash_cap;     // open-addressing set of (src<<32|dst), tag in bit 63 for deletes
+    int64_t* pos_out; int64_t* pos_in;          // per deleted edge: pool positions in both directions
+    float* del_w;                               // per deleted edge: its weight before deletion
+    int32_t* err;                               // device error flags [8] (inside the counter block)
+    int32_t* feat_index;                        // [N] position of a vertex in the batch's feature list
+    int32_t* feat_stamp;                        // [N] epoch stamps that detect repeated feature ids
+};
+// validate (no state change); err flags and growth need are read back by the caller
+nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipStream_t s);
+nrt_status graph_cancel_batch(nrt_graph* g, const nrt_batch* b, hipStream_t s);   // undo counters after a failed validation
+nrt_status graph_mutate(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipStream_t s);

@@ -1,0 +1,436 @@
+// Device-resident mutable directed graph: out-lists and in-lists with per-vertex slack.
+//
+// The paper keeps a packed-memory-array CSR in host memory (Section IV "Packed-memory-array-based CSR
+// structure"); here both directions live in HBM.  Each vertex owns a segment [off, off+cap) of a pool, the
+// first deg entries are live.  A batch (a) turns deleted entries into tombstones, (b) lets one workgroup per
+// touched vertex squeeze its list and, if the pending inserts do not fit, move the list to a fresh, larger
+// segment at the pool head, (c) appends the inserted entries.
+#include "common.h"
+
+namespace {
+
+constexpr int RB_THREADS = 1024;   // threads of a list-rebuild workgroup
+constexpr int RB_EPT = 4;
+
+__device__ inline int32_t new_cap_for(int32_t need) { return need + need / 2 + 4; }
+__device__ inline int32_t initial_cap_for(int32_t deg) { return deg + deg / 8 + 2; }
+
+// ------------------------------------------------------------------ build
+__global__ void deg_from_indptr_kernel(const int64_t* indptr, int64_t n, int32_t* deg) {
+    int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n) deg[v] = (int32_t)(indptr[v + 1] - indptr[v]);
+}
+__global__ void count_other_kernel(const int32_t* indices, int64_t e, int64_t n, int32_t* deg, int32_t* err) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < e; i += stride) {
+        int32_t v = indices[i];
+        if (v < 0 || v >= n) { err[0] = 1; continue; }
+        atomicAdd(&deg[v], 1);
+    }
+}
+__global__ void caps_kernel(const int32_t* deg, int64_t n, int32_t* cap, uint64_t* off_as_counts) {
+    int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n) {
+        int32_t c = initial_cap_for(deg[v]);
+        cap[v] = c;
+        off_as_counts[v] = (uint64_t)c;
+    }
+}
+// one wave per vertex: copy its list from the caller's compressed form into its segment
+__global__ void copy_lists_kernel(const int64_t* indptr, const int32_t* indices, const float* w, int64_t n,
+                                  Adj a, int32_t* err) {
+    const int64_t v = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (v >= n) return;
+    const int64_t b = indptr[v], e = indptr[v + 1], o = a.off[v];
+    for (int64_t j = b + lane; j < e; j += 64) {
+        int32_t u = indices[j];
+        if (u < 0 || u >= n) err[0] = 1;
+        if (u == v) err[1] = 1;
+        a.idx[o + (j - b)] = u;
+        if (a.wts) a.wts[o + (j - b)] = w[j];
+    }
+}
+// one wave per key vertex of the given direction: scatter into the other direction with cursors
+__global__ void transpose_fill_kernel(const int64_t* indptr, const int32_t* indices, const float* w, int64_t n,
+                                      Adj other, int32_t* cursor) {
+    const int64_t k = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (k >= n) return;
+    const int64_t b = indptr[k], e = indptr[k + 1];
+    for (int64_t j = b + lane; j < e; j += 64) {
+        int32_t t = indices[j];
+        if (t < 0 || t >= n) continue;
+        int32_t p = atomicAdd(&cursor[t], 1);
+        other.idx[other.off[t] + p] = (int32_t)k;
+        if (other.wts) other.wts[other.off[t] + p] = w[j];
+    }
+}
+
+// ------------------------------------------------------------------ validation
+__device__ inline uint64_t mix64(uint64_t x) {
+    x ^= x >> 33; x *= 0xff51afd7ed558ccdULL; x ^= x >> 33; x *= 0xc4ceb9fe1a85ec53ULL; x ^= x >> 33;
+    return x;
+}
+
+// wave-cooperative search of `target` in the live part of vertex k's list; returns pool position or -1
+__device__ inline int64_t find_in_list(const Adj& a, int32_t k, int32_t target, int lane) {
+    const int64_t o = a.off[k];
+    const int32_t d = a.deg[k];
+    for (int32_t j = 0; j < d; j += 64) {
+        int32_t jj = j + lane;
+        bool hit = jj < d && a.idx[o + jj] == target;
+        unsigned long long m = __ballot(hit);
+        if (m) return o + j + (__ffsll((long long)m) - 1);
+    }
+    return -1;
+}
+
+// err: [0] id out of range  [1] self-loop  [2] inserted edge present  [3] deleted edge absent
+//      [4] repeated entry   [5] repeated feature id
+__global__ void validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins, int64_t n_del,
+                                      const int32_t* ins_src, const int32_t* ins_dst, const int32_t* del_src,
+                                      const int32_t* del_dst, uint64_t* hash, int64_t hash_cap, int64_t* pos_out,
+                                      int64_t* pos_in, float* del_w, int32_t* err, int32_t* inscnt0,
+                                      int32_t* inscnt1, int32_t* delcnt0, int32_t* delcnt1) {
+    const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (op >= n_ins + n_del) return;
+    const bool is_del = op >= n_ins;
+    const int64_t i = is_del ? op - n_ins : op;
+    const int32_t u = is_del ? del_src[i] : ins_src[i];
+    const int32_t v = is_del ? del_dst[i] : ins_dst[i];
+    if (u < 0 || u >= n || v < 0 || v >= n) { if (lane == 0) err[0] = 1; return; }
+    if (u == v) { if (lane == 0) err[1] = 1; return; }
+    if (lane == 0) {
+        const uint64_t key = (((uint64_t)(uint32_t)u) << 32 | (uint32_t)v) + 1;   // 0 marks an empty cell
+        uint64_t h = mix64(key) & (uint64_t)(hash_cap - 1);
+        for (int64_t probe = 0; probe < hash_cap; ++probe) {
+            unsigned long long prev = atomicCAS((unsigned long long*)&hash[h], 0ULL, (unsigned long long)key);
+            if (prev == 0ULL) break;
+            if (prev == key) { err[4] = 1; break; }
+            h = (h + 1) & (uint64_t)(hash_cap - 1);
+        }
+    }
+    if (is_del) {
+        int64_t po = find_in_list(out, u, v, lane);
+        int64_t pi = find_in_list(in, v, u, lane);
+        if (po < 0 || pi < 0) { if (lane == 0) err[3] = 1; return; }
+        if (lane == 0) {
+            pos_out[i] = po;
+            pos_in[i] = pi;
+            if (del_w) del_w[i] = out.wts ? out.wts[po] : 1.0f;
+            atomicAdd(&delcnt0[u], 1);
+            atomicAdd(&delcnt1[v], 1);
+        }
+    } else {
+        const bool use_out = out.deg[u] <= in.deg[v];
+        int64_t p = use_out ? find_in_list(out, u, v, lane) : find_in_list(in, v, u, lane);
+        if (p >= 0) { if (lane == 0) err[2] = 1; return; }
+        if (lane == 0) {
+            atomicAdd(&inscnt0[u], 1);
+            atomicAdd(&inscnt1[v], 1);
+        }
+    }
+}
+
+__global__ void validate_feats_kernel(int64_t n, int64_t n_feat, const int32_t* ids, int32_t* feat_index,
+                                      int32_t* feat_stamp, int32_t epoch, int32_t* err) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_feat) return;
+    int32_t v = ids[i];
+    if (v < 0 || v >= n) { err[0] = 1; return; }
+    int32_t old = atomicMax(&feat_stamp[v], epoch);
+    if (old >= epoch) { err[5] = 1; return; }
+    feat_index[v] = (int32_t)i;
+}
+
+// thread per (op, direction): the first to stamp a key vertex sums what its list would need
+__global__ void plan_growth_kernel(Adj out, Adj in, int64_t n, int64_t n_ins, int64_t n_del, const int32_t* ins_src,
+                                   const int32_t* ins_dst, const int32_t* del_src, const int32_t* del_dst,
+                                   int32_t* stamp0, int32_t* stamp1, int32_t epoch, const int32_t* inscnt0,
+                                   const int32_t* inscnt1, const int32_t* delcnt0, const int32_t* delcnt1,
+                                   unsigned long long* grow /* [2] */) {
+    const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t nops = n_ins + n_del;
+    if (t >= 2 * nops) return;
+    const int dir = t >= nops;
+    const int64_t op = dir ? t - nops : t;
+    const bool is_del = op >= n_ins;
+    const int64_t i = is_del ? op - n_ins : op;
+    int32_t k = dir == 0 ? (is_del ? del_src[i] : ins_src[i]) : (is_del ? del_dst[i] : ins_dst[i]);
+    if (k < 0 || k >= n) return;
+    int32_t* stamp = dir ? stamp1 : stamp0;
+    if (atomicMax(&stamp[k], epoch) >= epoch) return;
+    const Adj& a = dir ? in : out;
+    int32_t need = a.deg[k] - (dir ? delcnt1 : delcnt0)[k] + (dir ? inscnt1 : inscnt0)[k];
+    if (need > a.cap[k]) atomicAdd(&grow[dir], (unsigned long long)new_cap_for(need));
+}
+
+__global__ void cancel_counts_kernel(int64_t n, int64_t n_ins, int64_t n_del, const int32_t* ins_src,
+                                     const int32_t* ins_dst, const int32_t* del_src, const int32_t* del_dst,
+                                     int32_t* inscnt0, int32_t* inscnt1, int32_t* delcnt0, int32_t* delcnt1) {
+    const int64_t op = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (op >= n_ins + n_del) return;
+    const bool is_del = op >= n_ins;
+    const int64_t i = is_del ? op - n_ins : op;
+    const int32_t u = is_del ? del_src[i] : ins_src[i];
+    const int32_t v = is_del ? del_dst[i] : ins_dst[i];
+    if (u >= 0 && u < n) { inscnt0[u] = 0; delcnt0[u] = 0; }
+    if (v >= 0 && v < n) { inscnt1[v] = 0; delcnt1[v] = 0; }
+}
+
+// ------------------------------------------------------------------ mutation
+__global__ void tombstone_kernel(Adj out, Adj in, int64_t n_del, const int64_t* pos_out, const int64_t* pos_in) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_del) return;
+    out.idx[pos_out[i]] = -1;
+    in.idx[pos_in[i]] = -1;
+}
+
+__device__ inline uint32_t block_excl_scan_u32(uint32_t v, uint32_t* total, uint32_t* wsum /* [RB_THREADS/64] shared */) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t o = __shfl_up(inc, d, 64);
+        if (lane >= d) inc += o;
+    }
+    if (lane == 63) wsum[w] = inc;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+    for (int i = 0; i < RB_THREADS / 64; ++i) {
+        uint32_t t = wsum[i];
+        if (i < w) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+// One workgroup per (op, direction); only the first to stamp the key vertex works on its list.
+__global__ void __launch_bounds__(RB_THREADS)
+rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_t* ins_src, const int32_t* ins_dst,
+                     const int32_t* del_src, const int32_t* del_dst, int32_t* stamp0, int32_t* stamp1,
+                     int32_t epoch, int32_t* inscnt0, int32_t* inscnt1, int32_t* delcnt0, int32_t* delcnt1) {
+    __shared__ uint32_t wsum[RB_THREADS / 64];
+    __shared__ int32_t s_owner;
+    __shared__ int64_t s_newoff;
+    const int dir = blockIdx.y;
+    const int64_t op = blockIdx.x;
+    const bool is_del = op >= n_ins;
+    const int64_t i = is_del ? op - n_ins : op;
+    const int32_t k = dir == 0 ? (is_del ? del_src[i] : ins_src[i]) : (is_del ? del_dst[i] : ins_dst[i]);
+    int32_t* stamp = dir ? stamp1 : stamp0;
+    if (threadIdx.x == 0) s_owner = atomicMax(&stamp[k], epoch) < epoch;
+    __syncthreads();
+    if (!s_owner) return;
+    Adj a = dir ? in : out;
+    int32_t* inscnt = dir ? inscnt1 : inscnt0;
+    int32_t* delcnt = dir ? delcnt1 : delcnt0;
+    const int64_t base = a.off[k];
+    const int32_t deg0 = a.deg[k];
+    const int32_t dc = delcnt[k], ic = inscnt[k];
+    int32_t live = deg0;
+    if (dc > 0) {
+        uint32_t outpos = 0;
+        for (int32_t start = 0; start < deg0; start += RB_THREADS * RB_EPT) {
+            int32_t e[RB_EPT];
+            float w[RB_EPT];
+            uint32_t cnt = 0;
+#pragma unroll
+            for (int j = 0; j < RB_EPT; ++j) {
+                int32_t p = start + (int32_t)threadIdx.x * RB_EPT + j;
+                e[j] = p < deg0 ? a.idx[base + p] : -1;
+                w[j] = (p < deg0 && a.wts) ? a.wts[base + p] : 0.f;
+                cnt += e[j] >= 0;
+            }
+            uint32_t tot;
+            uint32_t ex = block_excl_scan_u32(cnt, &tot, wsum);   // barriers inside: all reads precede all writes
+            uint32_t q = outpos + ex;
+#pragma unroll
+            for (int j = 0; j < RB_EPT; ++j) {
+                if (e[j] >= 0) {
+                    a.idx[base + q] = e[j];
+                    if (a.wts) a.wts[base + q] = w[j];
+                    ++q;
+                }
+            }
+            outpos += tot;
+        }
+        live = (int32_t)outpos;
+    }
+    const int32_t need = live + ic;
+    if (need > a.cap[k]) {
+        const int32_t nc = new_cap_for(need);
+        __syncthreads();
+        if (threadIdx.x == 0) s_newoff = (int64_t)atomicAdd((unsigned long long*)a.head, (unsigned long long)nc);
+        __syncthreads();
+        const int64_t no = s_newoff;
+        for (int32_t p = threadIdx.x; p < live; p += RB_THREADS) {
+            a.idx[no + p] = a.idx[base + p];
+            if (a.wts) a.wts[no + p] = a.wts[base + p];
+        }
+        if (threadIdx.x == 0) { a.off[k] = no; a.cap[k] = nc; }
+    }
+    if (threadIdx.x == 0) { a.deg[k] = live; inscnt[k] = 0; delcnt[k] = 0; }
+}
+
+__global__ void append_kernel(Adj out, Adj in, int64_t n_ins, const int32_t* ins_src, const int32_t* ins_dst,
+                              const float* ins_w) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_ins) return;
+    const int32_t u = ins_src[i], v = ins_dst[i];
+    const float w = ins_w ? ins_w[i] : 1.0f;
+    int32_t p = atomicAdd(&out.deg[u], 1);
+    out.idx[out.off[u] + p] = v;
+    if (out.wts) out.wts[out.off[u] + p] = w;
+    int32_t q = atomicAdd(&in.deg[v], 1);
+    in.idx[in.off[v] + q] = u;
+    if (in.wts) in.wts[in.off[v] + q] = w;
+}
+
+void layout_adj(Bump& b, Adj& a, int64_t n, int64_t pool_cap, int weighted) {
+    a.off = b.take<int64_t>(n);
+    a.deg = b.take<int32_t>(n);
+    a.cap = b.take<int32_t>(n);
+    a.idx = b.take<int32_t>(pool_cap);
+    a.wts = weighted ? b.take<float>(pool_cap) : nullptr;
+    a.head = nullptr;   // set by graph_layout: the pool heads live in the shared counter block
+    a.pool_cap = pool_cap;
+}
+
+}  // namespace
+
+nrt_status graph_layout(Bump& b, nrt_graph* g) {
+    const int64_t n = g->n;
+    const int64_t pool_cap = g->e_capacity + g->e_capacity / 2 + 8 * n + 1024;
+    layout_adj(b, g->out, n, pool_cap, g->weighted);
+    layout_adj(b, g->in, n, pool_cap, g->weighted);
+    g->scan_tmp_len = cdiv(n, 1024) + 64;
+    g->scan_tmp = b.take<uint64_t>(g->scan_tmp_len);
+    for (int d = 0; d < 2; ++d) {
+        g->stamp[d] = b.take<int32_t>(n);
+        g->inscnt[d] = b.take<int32_t>(n);
+        g->delcnt[d] = b.take<int32_t>(n);
+    }
+    g->dev_ctrs = b.take<int64_t>(NRT_NCTRS);
+    g->out.head = g->dev_ctrs ? g->dev_ctrs + CTR_HEAD_OUT : nullptr;
+    g->in.head = g->dev_ctrs ? g->dev_ctrs + CTR_HEAD_IN : nullptr;
+    return NRT_OK;
+}
+
+static nrt_status build_direction(nrt_graph* g, Adj& a, const int64_t* indptr, const int32_t* indices, const float* w,
+                                  int32_t* err, hipStream_t s) {
+    const int64_t n = g->n;
+    const int nb = (int)cdiv(n, 256);
+    deg_from_indptr_kernel<<<nb, 256, 0, s>>>(indptr, n, a.deg);
+    LAUNCH_CHECK();
+    caps_kernel<<<nb, 256, 0, s>>>(a.deg, n, a.cap, (uint64_t*)a.off);
+    LAUNCH_CHECK();
+    NRT_TRY(k_exclusive_scan_u64((uint64_t*)a.off, n, g->scan_tmp, g->scan_tmp_len, (uint64_t*)a.head, s));
+    copy_lists_kernel<<<(int)cdiv(n * 64, 256), 256, 0, s>>>(indptr, indices, w, n, a, err);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+static nrt_status derive_direction(nrt_graph* g, Adj& other, const int64_t* indptr, const int32_t* indices,
+                                   const float* w, int32_t* err, hipStream_t s) {
+    const int64_t n = g->n;
+    const int nb = (int)cdiv(n, 256);
+    NRT_TRY(k_fill_u32((uint32_t*)other.deg, n, 0, s));
+    if (g->e > 0) {
+        int64_t grid = cdiv(g->e, 256);
+        if (grid > 65536) grid = 65536;
+        count_other_kernel<<<(int)grid, 256, 0, s>>>(indices, g->e, n, other.deg, err);
+        LAUNCH_CHECK();
+    }
+    caps_kernel<<<nb, 256, 0, s>>>(other.deg, n, other.cap, (uint64_t*)other.off);
+    LAUNCH_CHECK();
+    NRT_TRY(k_exclusive_scan_u64((uint64_t*)other.off, n, g->scan_tmp, g->scan_tmp_len, (uint64_t*)other.head, s));
+    int32_t* cursor = g->inscnt[0];   // zero between batches; restored to zero below
+    transpose_fill_kernel<<<(int)cdiv(n * 64, 256), 256, 0, s>>>(indptr, indices, w, n, other, cursor);
+    LAUNCH_CHECK();
+    NRT_TRY(k_fill_u32((uint32_t*)cursor, n, 0, s));
+    return NRT_OK;
+}
+
+nrt_status graph_build(nrt_graph* g, const int64_t* csr_indptr, const int32_t* csr_indices, const float* csr_w,
+                       const int64_t* csc_indptr, const int32_t* csc_indices, const float* csc_w, hipStream_t s) {
+    const int64_t n = g->n;
+    for (int d = 0; d < 2; ++d) {
+        NRT_TRY(k_fill_u32((uint32_t*)g->stamp[d], n, 0, s));
+        NRT_TRY(k_fill_u32((uint32_t*)g->inscnt[d], n, 0, s));
+        NRT_TRY(k_fill_u32((uint32_t*)g->delcnt[d], n, 0, s));
+    }
+    NRT_TRY(k_fill_u64((uint64_t*)g->dev_ctrs, NRT_NCTRS, 0, s));
+    int32_t* err = (int32_t*)(g->dev_ctrs + CTR_ERR);
+    if (csr_indptr) NRT_TRY(build_direction(g, g->out, csr_indptr, csr_indices, csr_w, err, s));
+    if (csc_indptr) NRT_TRY(build_direction(g, g->in, csc_indptr, csc_indices, csc_w, err, s));
+    if (!csc_indptr) NRT_TRY(derive_direction(g, g->in, csr_indptr, csr_indices, csr_w, err, s));
+    if (!csr_indptr) NRT_TRY(derive_direction(g, g->out, csc_indptr, csc_indices, csc_w, err, s));
+    HIP_TRY(hipMemcpyAsync(g->host_pinned, g->dev_ctrs, NRT_NCTRS * sizeof(int64_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    const int32_t* herr = (const int32_t*)(g->host_pinned + CTR_ERR);
+    if (herr[0]) { nrt_set_error("graph has a vertex id outside [0, n)"); return NRT_ERR_INVALID_ARG; }
+    if (herr[1]) { nrt_set_error("graph has an explicit self-loop"); return NRT_ERR_INVALID_ARG; }
+    g->epoch = 2;
+    return NRT_OK;
+}
+
+nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipStream_t s) {
+    const int64_t nops = b->n_ins + b->n_del;
+    NRT_TRY(k_fill_u64((uint64_t*)(g->dev_ctrs + CTR_ERR), 4, 0, s));      // 8 int32 flags
+    NRT_TRY(k_fill_u64((uint64_t*)(g->dev_ctrs + CTR_GROW), 2, 0, s));
+    if (b->n_feat > 0) {
+        validate_feats_kernel<<<(int)cdiv(b->n_feat, 256), 256, 0, s>>>(g->n, b->n_feat, b->feat_ids, sc.feat_index,
+                                                                       sc.feat_stamp, g->epoch, sc.err);
+        LAUNCH_CHECK();
+    }
+    if (nops == 0) return NRT_OK;
+    NRT_TRY(k_fill_u64(sc.hash_keys, sc.hash_cap, 0, s));
+    validate_edges_kernel<<<(int)cdiv(nops * 64, 256), 256, 0, s>>>(
+        g->out, g->in, g->n, b->n_ins, b->n_del, b->ins_src, b->ins_dst, b->del_src, b->del_dst, sc.hash_keys,
+        sc.hash_cap, sc.pos_out, sc.pos_in, sc.del_w, sc.err, g->inscnt[0], g->inscnt[1], g->delcnt[0], g->delcnt[1]);
+    LAUNCH_CHECK();
+    plan_growth_kernel<<<(int)cdiv(2 * nops, 256), 256, 0, s>>>(
+        g->out, g->in, g->n, b->n_ins, b->n_del, b->ins_src, b->ins_dst, b->del_src, b->del_dst, g->stamp[0],
+        g->stamp[1], g->epoch, g->inscnt[0], g->inscnt[1], g->delcnt[0], g->delcnt[1],
+        (unsigned long long*)(g->dev_ctrs + CTR_GROW));
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status graph_cancel_batch(nrt_graph* g, const nrt_batch* b, hipStream_t s) {
+    const int64_t nops = b->n_ins + b->n_del;
+    g->epoch += 2;   // stamps of the failed attempt must not look current to the next batch
+    if (nops == 0) return NRT_OK;
+    cancel_counts_kernel<<<(int)cdiv(nops, 256), 256, 0, s>>>(g->n, b->n_ins, b->n_del, b->ins_src, b->ins_dst,
+                                                             b->del_src, b->del_dst, g->inscnt[0], g->inscnt[1],
+                                                             g->delcnt[0], g->delcnt[1]);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status graph_mutate(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipStream_t s) {
+    const int64_t nops = b->n_ins + b->n_del;
+    if (nops == 0) { g->epoch += 2; return NRT_OK; }
+    if (b->n_del > 0) {
+        tombstone_kernel<<<(int)cdiv(b->n_del, 256), 256, 0, s>>>(g->out, g->in, b->n_del, sc.pos_out, sc.pos_in);
+        LAUNCH_CHECK();
+    }
+    dim3 grid((unsigned)nops, 2, 1);
+    rebuild_lists_kernel<<<grid, RB_THREADS, 0, s>>>(g->out, g->in, b->n_ins, b->n_del, b->ins_src, b->ins_dst,
+                                                     b->del_src, b->del_dst, g->stamp[0], g->stamp[1], g->epoch + 1,
+                                                     g->inscnt[0], g->inscnt[1], g->delcnt[0], g->delcnt[1]);
+    LAUNCH_CHECK();
+    if (b->n_ins > 0) {
+        append_kernel<<<(int)cdiv(b->n_ins, 256), 256, 0, s>>>(g->out, g->in, b->n_ins, b->ins_src, b->ins_dst, b->ins_w);
+        LAUNCH_CHECK();
+    }
+    g->epoch += 2;
+    g->e += b->n_ins - b->n_del;
+    return NRT_OK;
+}

@@ -1,0 +1,211 @@
+// Small device primitives: fills, word-wise OR, exclusive scan, bitmap -> sorted id list compaction.
+#include "common.h"
+
+namespace {
+
+constexpr int TPB = 256;     // threads per block of the scan kernels
+constexpr int EPT = 4;       // elements per thread
+constexpr int EPB = TPB * EPT;
+
+__device__ inline uint64_t wave_incl_scan(uint64_t v) {
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint64_t o = __shfl_up((unsigned long long)v, d, 64);
+        if (lane >= d) v += o;
+    }
+    return v;
+}
+
+// exclusive scan of one value per thread over the block; returns exclusive prefix, *block_total = sum
+__device__ inline uint64_t block_excl_scan(uint64_t v, uint64_t* block_total) {
+    __shared__ uint64_t wsum[TPB / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint64_t inc = wave_incl_scan(v);
+    if (lane == 63) wsum[w] = inc;
+    __syncthreads();
+    uint64_t base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < TPB / 64; ++i) {
+        uint64_t t = wsum[i];
+        if (i < w) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *block_total = tot;
+    return base + inc - v;
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+__global__ void fill_u64_kernel(uint64_t* p, int64_t n, uint64_t v) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = v;
+}
+__global__ void or_words_kernel(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = a[i] | (b ? b[i] : 0u);
+}
+__global__ void copy_u32_kernel(uint32_t* dst, const uint32_t* src, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+__global__ void mark_ids_kernel(uint32_t* bitmap, const int32_t* ids, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        int32_t v = ids[i];
+        atomicOr(&bitmap[v >> 5], 1u << (v & 31));
+    }
+}
+
+// ---- scan ----
+__global__ void scan_reduce_kernel(const uint64_t* data, int64_t n, uint64_t* tmp) {
+    const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
+    uint64_t s = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j)
+        if (base + j < n) s += data[base + j];
+    uint64_t tot;
+    block_excl_scan(s, &tot);
+    if (threadIdx.x == 0) tmp[blockIdx.x] = tot;
+}
+// one block: exclusive scan of tmp[0..nb) in place, total out
+__global__ void scan_top_kernel(uint64_t* tmp, int64_t nb, uint64_t* total) {
+    uint64_t carry = 0;
+    for (int64_t start = 0; start < nb; start += TPB) {
+        int64_t i = start + threadIdx.x;
+        uint64_t v = i < nb ? tmp[i] : 0;
+        uint64_t tot;
+        uint64_t ex = block_excl_scan(v, &tot);
+        if (i < nb) tmp[i] = carry + ex;
+        carry += tot;
+    }
+    if (threadIdx.x == 0) *total = carry;
+}
+__global__ void scan_apply_kernel(uint64_t* data, int64_t n, const uint64_t* tmp) {
+    const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
+    uint64_t v[EPT];
+    uint64_t s = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        v[j] = base + j < n ? data[base + j] : 0;
+        s += v[j];
+    }
+    uint64_t tot;
+    uint64_t ex = block_excl_scan(s, &tot) + tmp[blockIdx.x];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        if (base + j < n) data[base + j] = ex;
+        ex += v[j];
+    }
+}
+
+// ---- bitmap compaction ----
+__global__ void bm_count_kernel(const uint32_t* bm, int64_t nw, uint64_t* tmp) {
+    const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
+    uint64_t s = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j)
+        if (base + j < nw) s += __popc(bm[base + j]);
+    uint64_t tot;
+    block_excl_scan(s, &tot);
+    if (threadIdx.x == 0) tmp[blockIdx.x] = tot;
+}
+__global__ void bm_emit_kernel(const uint32_t* bm, int64_t nw, const uint64_t* tmp, int32_t* list, int32_t* slot) {
+    const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
+    uint32_t w[EPT];
+    uint64_t s = 0;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        w[j] = base + j < nw ? bm[base + j] : 0u;
+        s += __popc(w[j]);
+    }
+    uint64_t tot;
+    uint64_t pos = block_excl_scan(s, &tot) + tmp[blockIdx.x];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        uint32_t bits = w[j];
+        while (bits) {
+            int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            int32_t v = (int32_t)((base + j) * 32 + b);
+            list[pos] = v;
+            if (slot) slot[v] = (int32_t)pos;
+            ++pos;
+        }
+    }
+}
+
+inline int grid_for(int64_t n, int tpb, int64_t cap = 65536) {
+    int64_t g = cdiv(n, tpb);
+    if (g < 1) g = 1;
+    if (g > cap) g = cap;
+    return (int)g;
+}
+
+}  // namespace
+
+nrt_status k_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s) {
+    if (n <= 0) return NRT_OK;
+    fill_u32_kernel<<<grid_for(n, 256), 256, 0, s>>>(p, n, v);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s) {
+    if (n <= 0) return NRT_OK;
+    fill_u64_kernel<<<grid_for(n, 256), 256, 0, s>>>(p, n, v);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_or_words(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t nwords, hipStream_t s) {
+    if (nwords <= 0) return NRT_OK;
+    or_words_kernel<<<grid_for(nwords, 256), 256, 0, s>>>(dst, a, b, nwords);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_copy_i32(int32_t* dst, const int32_t* src, int64_t n, hipStream_t s) {
+    if (n <= 0) return NRT_OK;
+    copy_u32_kernel<<<grid_for(n, 256), 256, 0, s>>>((uint32_t*)dst, (const uint32_t*)src, n);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s) {
+    if (n <= 0) return NRT_OK;
+    copy_u32_kernel<<<grid_for(n, 256), 256, 0, s>>>((uint32_t*)dst, (const uint32_t*)src, n);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_mark_ids(uint32_t* bitmap, const int32_t* ids, int64_t n, hipStream_t s) {
+    if (n <= 0) return NRT_OK;
+    mark_ids_kernel<<<(int)cdiv(n, 256), 256, 0, s>>>(bitmap, ids, n);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_t tmp_len, uint64_t* total, hipStream_t s) {
+    const int64_t nb = n > 0 ? cdiv(n, EPB) : 0;
+    if (nb > tmp_len) { nrt_set_error("scan scratch too small"); return NRT_ERR_INVALID_ARG; }
+    if (nb > 0) { scan_reduce_kernel<<<(int)nb, TPB, 0, s>>>(data, n, tmp); LAUNCH_CHECK(); }
+    scan_top_kernel<<<1, TPB, 0, s>>>(tmp, nb, total);
+    LAUNCH_CHECK();
+    if (nb > 0) { scan_apply_kernel<<<(int)nb, TPB, 0, s>>>(data, n, tmp); LAUNCH_CHECK(); }
+    return NRT_OK;
+}
+
+nrt_status k_compact_bitmap(const uint32_t* bitmap, int64_t n, int32_t* list, int32_t* slot, uint64_t* tmp,
+                            int64_t tmp_len, uint64_t* count, hipStream_t s) {
+    const int64_t nw = cdiv(n, 32);
+    const int64_t nb = nw > 0 ? cdiv(nw, EPB) : 0;
+    if (nb > tmp_len) { nrt_set_error("scan scratch too small"); return NRT_ERR_INVALID_ARG; }
+    if (nb > 0) { bm_count_kernel<<<(int)nb, TPB, 0, s>>>(bitmap, nw, tmp); LAUNCH_CHECK(); }
+    scan_top_kernel<<<1, TPB, 0, s>>>(tmp, nb, count);
+    LAUNCH_CHECK();
+    if (nb > 0) { bm_emit_kernel<<<(int)nb, TPB, 0, s>>>(bitmap, nw, tmp, list, slot); LAUNCH_CHECK(); }
+    return NRT_OK;
+}

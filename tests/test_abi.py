@@ -1,0 +1,50 @@
+"""The C-ABI library builds, loads without a GPU and exports every function include/nrt.h declares."""
+import ctypes
+import os
+import re
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "nrt.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nrt_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_declared_symbols():
+    from paper_2603_20622_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2603_20622_amd import build
+        build.build()
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    names = declared_functions()
+    assert "nrt_graph_create" in names and "nrt_cache_init" in names and "nrt_apply_batch" in names
+    for name in names:
+        assert hasattr(lib, name), name
+    assert set(binding.EXPORTS) == set(names)
+    lib.nrt_version.restype = ctypes.c_char_p
+    assert b"gfx950" in lib.nrt_version()
+
+
+def test_argument_errors_without_gpu():
+    """Pure host-side argument checks: no device call is reached."""
+    from paper_2603_20622_amd import binding as nb
+    L = nb.lib()
+    out = ctypes.c_size_t()
+    assert L.nrt_graph_workspace_bytes(0, 10, 0, ctypes.byref(out)) == nb.NRT_ERR_INVALID_ARG
+    assert L.nrt_graph_workspace_bytes(10, -1, 0, ctypes.byref(out)) == nb.NRT_ERR_INVALID_ARG
+    assert L.nrt_graph_workspace_bytes(1000, 5000, 1, ctypes.byref(out)) == nb.NRT_OK
+    assert out.value > 2 * 5000 * 8
+    h = ctypes.c_void_p()
+    st = L.nrt_graph_create(10, 5, 4, 0, None, None, None, None, None, None, None, 0, None, ctypes.byref(h))
+    assert st == nb.NRT_ERR_INVALID_ARG and b"e_capacity" in L.nrt_last_error()
+    assert L.nrt_get_stats(None, None) == nb.NRT_ERR_INVALID_ARG
+
+
+def test_struct_sizes_match_header():
+    from paper_2603_20622_amd import binding as nb
+    # int32*2 + int32*5 + int32*2 + float*2 = 44 bytes, padded to 48, then 8+8+4+4 pointers
+    assert ctypes.sizeof(nb.nrt_model_desc) == 48 + 8 * (8 + 8 + 4 + 4)
+    assert ctypes.sizeof(nb.nrt_batch) == 10 * 8
+    assert ctypes.sizeof(nb.nrt_layer_stats) == 5 * 8 + 6 * 4
