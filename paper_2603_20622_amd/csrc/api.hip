@@ -43,15 +43,14 @@ struct nrt_cache {
     float* bias[NRT_MAX_LAYERS][2];
     int32_t* indeg_old;
     uint32_t *bm_ddst, *bm_feat, *bm[2];
+    int64_t nw_pad;
     int32_t* list[NRT_MAX_LAYERS + 1];
     int64_t n_list[NRT_MAX_LAYERS + 1];
     int32_t* slot[2];
     float* DP[2];
     float* mid;
-    uint64_t* item_off;
-    int32_t *item_slot, *item_chunk, *multi_list;
-    int64_t item_cap, partial_rows;
-    float* partial;
+    DstRec* recs;
+    HubWork hubs;
     int64_t* hub_scratch;
     int64_t hub_cap;
     BatchScratch sc;
@@ -249,8 +248,9 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         }
     }
     c->indeg_old = b.take<int32_t>(n);
-    c->bm_ddst = b.take<uint32_t>(nw);
-    c->bm_feat = b.take<uint32_t>(nw);
+    c->nw_pad = (nw + 63) & ~int64_t(63);
+    c->bm_ddst = b.take<uint32_t>(2 * c->nw_pad);
+    c->bm_feat = c->bm_ddst ? c->bm_ddst + c->nw_pad : nullptr;
     c->bm[0] = b.take<uint32_t>(nw);
     c->bm[1] = b.take<uint32_t>(nw);
     for (int l = 0; l <= c->L; ++l) c->list[l] = b.take<int32_t>(n);
@@ -259,13 +259,14 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->DP[0] = b.take<float>(n * maxd);
     c->DP[1] = b.take<float>(n * maxd);
     c->mid = c->kind == NRT_GIN ? b.take<float>(n * maxd) : nullptr;
-    c->item_cap = n + g->e_capacity / NRT_CHUNK + 64;
-    c->partial_rows = 2 * (g->e_capacity / NRT_CHUNK) + 64;
-    c->item_off = b.take<uint64_t>(n + 1);
-    c->item_slot = b.take<int32_t>(c->item_cap);
-    c->item_chunk = b.take<int32_t>(c->item_cap);
-    c->multi_list = b.take<int32_t>(g->e_capacity / NRT_CHUNK + 64);
-    c->partial = b.take<float>(c->partial_rows * maxd);
+    c->recs = b.take<DstRec>(n);
+    c->hubs.hub_cap = g->e_capacity / NRT_CHUNK + 64;          // a hub has more than NRT_CHUNK live in-edges
+    c->hubs.item_cap = 2 * (g->e_capacity / NRT_CHUNK) + 64;   // sum of ceil(deg/NRT_CHUNK) over hubs
+    c->hubs.hub_slot = b.take<int32_t>(c->hubs.hub_cap);
+    c->hubs.hub_first = b.take<uint64_t>(c->hubs.hub_cap);
+    c->hubs.item_hub = b.take<int32_t>(c->hubs.item_cap);
+    c->hubs.item_chunk = b.take<int32_t>(c->hubs.item_cap);
+    c->hubs.partial = b.take<float>(c->hubs.item_cap * maxd);
     c->hub_cap = g->e_capacity / 2048 + 64;
     c->hub_scratch = b.take<int64_t>(c->hub_cap / 2 + 8);
     c->sc.max_edges = c->max_edges;
@@ -318,38 +319,25 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
     return NRT_OK;
 }
 
-// aggregate layer l for the destinations in list (null: all), then run the dense update
-static nrt_status run_gather(nrt_cache* c, int l, const int32_t* dst_list, int64_t n_dst, bool incremental,
+// gather + fold of layer l over the destinations described by c->recs[0..n_dst) and the hub items built from them
+static nrt_status run_gather(nrt_cache* c, int l, int64_t n_dst, int64_t n_hubs, int64_t n_items, bool incremental,
                              int prev, hipStream_t s) {
     nrt_graph* g = c->g;
-    NRT_TRY(k_build_items(dst_list, n_dst, g->in.deg, c->item_off, c->item_slot, c->item_chunk, c->multi_list,
-                          g->scan_tmp, g->scan_tmp_len, g->dev_ctrs, s));
-    NRT_TRY(read_ctrs(g, s));
-    const uint64_t packed = (uint64_t)g->host_pinned[CTR_ITEMS];
-    const int64_t n_items = (int64_t)(packed & 0xffffffffu), n_part = (int64_t)(packed >> 32);
-    const int64_t n_multi = g->host_pinned[CTR_MULTI];
-    if (n_items > c->item_cap || n_part > c->partial_rows) {
-        nrt_set_error("internal: item buffers too small (%lld items, %lld partial rows)", (long long)n_items, (long long)n_part);
+    if (n_hubs > c->hubs.hub_cap || n_items > c->hubs.item_cap) {
+        nrt_set_error("internal: hub buffers too small (%lld hubs, %lld items)", (long long)n_hubs, (long long)n_items);
         return NRT_ERR_STATE;
-    }
-    if (incremental) {
-        c->stats.layer[l - 1].n_items = n_items;
-        c->stats.layer[l - 1].n_in_edges = g->host_pinned[CTR_INEDGES];
     }
     GatherArgs a;
     memset(&a, 0, sizeof(a));
-    a.dst_list = dst_list;
+    a.recs = c->recs;
     a.n_dst = n_dst;
-    a.item_slot = c->item_slot;
-    a.item_chunk = c->item_chunk;
-    a.item_off = c->item_off;
-    a.n_items_dev = (const uint64_t*)(g->dev_ctrs + CTR_ITEMS);
+    a.hubs = c->hubs;
+    a.dev_ctrs = g->dev_ctrs;
     a.in = g->in;
     a.D = c->dagg[l];
     a.use_weights = (c->kind == NRT_GIN && g->weighted) ? 1 : 0;
     a.self_pair = c->kind == NRT_GCN;
     a.S = c->S[l];
-    a.partial = c->partial;
     if (incremental) {
         a.P = c->DP[prev];
         a.src_bitmap = c->bm[prev];
@@ -368,7 +356,7 @@ static nrt_status run_gather(nrt_cache* c, int l, const int32_t* dst_list, int64
     NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
     NRT_TRY(k_gather(a, n_items, s));
     NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
-    NRT_TRY(k_combine_partials(a, c->multi_list, n_multi, s));
+    NRT_TRY(k_combine_partials(a, n_hubs, s));
     NRT_TRY(prof_mark(c, TAG_COMBINE, l, s));
     return NRT_OK;
 }
@@ -474,8 +462,12 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
                 else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][1], c->dims[l + 1], 0, s));
             }
         }
+        NRT_TRY(k_all_records(g->in, n, c->recs, c->hubs, g->dev_ctrs, s));
+        NRT_TRY(k_build_hub_items(c->recs, c->hubs, g->scan_tmp, g->scan_tmp_len, g->dev_ctrs, s));
+        NRT_TRY(read_ctrs(g, s));
+        const int64_t n_hubs = g->host_pinned[CTR_MULTI], n_items = g->host_pinned[CTR_ITEMS];
         for (int l = 1; l <= c->L; ++l) {
-            NRT_TRY(run_gather(c, l, nullptr, n, false, 0, s));
+            NRT_TRY(run_gather(c, l, n, n_hubs, n_items, false, 0, s));
             NRT_TRY(run_update(c, l, nullptr, n, false, 0, nullptr, s));
         }
         HIP_TRY(hipStreamSynchronize(s));
@@ -556,25 +548,25 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     }
 
     // ---- sets of the batch
-    NRT_TRY(k_fill_u32(c->bm_ddst, nw, 0, s));
-    NRT_TRY(k_fill_u32(c->bm_feat, nw, 0, s));
-    NRT_TRY(k_mark_ids(c->bm_ddst, b->ins_dst, b->n_ins, s));
-    NRT_TRY(k_mark_ids(c->bm_ddst, b->del_dst, b->n_del, s));
-    NRT_TRY(k_mark_ids(c->bm_feat, b->feat_ids, b->n_feat, s));
+    NRT_TRY(k_fill_u32(c->bm_ddst, 2 * c->nw_pad, 0, s));     // bm_ddst and bm_feat are adjacent
+    NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
     const bool gcn = c->kind == NRT_GCN;
     if (gcn) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
 
-    // ---- structural terms on the old caches, all layers
-    for (int l = 1; l <= c->L; ++l) {
+    // ---- structural terms on the old caches, all layers in one launch
+    {
         FoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
         f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
         if (c->kind == NRT_GIN && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
-        f.Hprev = c->H[l - 1];
         f.indeg_old = gcn ? g->in.deg : nullptr;
-        f.S = c->S[l];
-        f.D = c->dagg[l];
+        f.n_layers = c->L;
+        for (int l = 1; l <= c->L; ++l) {
+            f.Hprev[l - 1] = c->H[l - 1];
+            f.S[l - 1] = c->S[l];
+            f.D[l - 1] = c->dagg[l];
+        }
         NRT_TRY(k_structural_fold(f, s));
     }
 
@@ -615,12 +607,16 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(k_expand_frontier(g->out, c->list[l - 1], c->n_list[l - 1], c->bm[cur], c->hub_scratch, c->hub_cap, s));
         NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
         NRT_TRY(k_compact_bitmap(c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp, g->scan_tmp_len,
-                                 (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
+                                 (uint64_t*)(g->dev_ctrs + CTR_COUNT), s, &g->in, c->recs, &c->hubs, g->dev_ctrs));
+        NRT_TRY(k_build_hub_items(c->recs, c->hubs, g->scan_tmp, g->scan_tmp_len, g->dev_ctrs, s));
         NRT_TRY(read_ctrs(g, s));
         c->n_list[l] = g->host_pinned[CTR_COUNT];
         ls->n_affected = c->n_list[l];
+        ls->n_items = g->host_pinned[CTR_ITEMS];
+        for (int q = 0; q < 16; ++q) ls->n_in_edges += g->host_pinned[CTR_INEDGES + q];
         NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
-        if (c->n_list[l - 1] > 0) NRT_TRY(run_gather(c, l, c->list[l], c->n_list[l], true, prev, s));
+        if (c->n_list[l - 1] > 0)
+            NRT_TRY(run_gather(c, l, c->n_list[l], g->host_pinned[CTR_MULTI], g->host_pinned[CTR_ITEMS], true, prev, s));
         float* out_rows = nullptr;
         if (l == c->L && want_rows) {
             if (c->n_list[l] <= capacity) out_rows = affected_rows;

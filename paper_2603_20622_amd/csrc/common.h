@@ -80,9 +80,16 @@ nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
 // exclusive scan of n uint64 values in place; writes the total to *total (device)
 nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_t tmp_len, uint64_t* total, hipStream_t s);
 // sorted ids of the set bits of bitmap (n bits) -> list, slot[id] = position, *count (device) = number
+struct DstRec;
+struct HubWork;
+// with in/recs/hubs given, also emits the destination records and appends hubs (CTR_MULTI, CTR_INEDGES)
 nrt_status k_compact_bitmap(const uint32_t* bitmap, int64_t n, int32_t* list, int32_t* slot, uint64_t* tmp,
-                            int64_t tmp_len, uint64_t* count, hipStream_t s);
+                            int64_t tmp_len, uint64_t* count, hipStream_t s, const Adj* in = nullptr,
+                            DstRec* recs = nullptr, const HubWork* hubs = nullptr, int64_t* dev_ctrs = nullptr);
 nrt_status k_mark_ids(uint32_t* bitmap, const int32_t* ids, int64_t n, hipStream_t s);
+// bm_a |= ids of a0 and a1, bm_b |= ids of b0, one launch
+nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
+                        const int32_t* b0, int64_t nb0, hipStream_t s);
 
 // ---------------------------------------------------------------- frontier.hip
 // bitmap |= { v : <u,v> in out-lists, u in src_list[0..ns) }
@@ -90,46 +97,55 @@ nrt_status k_expand_frontier(const Adj& out, const int32_t* src_list, int64_t ns
                              int64_t* hub_scratch, int64_t hub_cap, hipStream_t s);
 
 // ---------------------------------------------------------------- gather.hip
+// What a gather wave needs to know about destination slot s, in one 16-byte load.
+struct __attribute__((aligned(16))) DstRec {
+    int64_t off;   // first pool entry of the in-list
+    int32_t deg;   // live entries
+    int32_t v;     // vertex id
+};
+// Destinations with more than NRT_CHUNK in-edges ("hubs") are cut into items of NRT_CHUNK entries.
+struct HubWork {
+    int32_t* hub_slot;     // [hub_cap] destination slots of the hubs (unordered)
+    uint64_t* hub_first;   // [hub_cap] chunk count, then (after the scan) first item of each hub
+    int32_t* item_hub;     // [item_cap] hub index of an item
+    int32_t* item_chunk;   // [item_cap] chunk index inside the hub's in-list
+    int64_t hub_cap, item_cap;
+    float* partial;        // [item_cap][D] one partial row per item
+};
 struct GatherArgs {
-    // destinations
-    const int32_t* dst_list;   // null: destination = slot index (all vertices)
+    const DstRec* recs;        // [n_dst]
     int64_t n_dst;
-    // items
-    const int32_t* item_slot;  // [n_items]
-    const int32_t* item_chunk;
-    const uint64_t* item_off;  // per slot: packed (low 32: first item, high 32: first partial row)
-    int64_t n_items_bound;     // launch bound; real count on device
-    const uint64_t* n_items_dev;
-    // graph
+    HubWork hubs;
+    const int64_t* dev_ctrs;   // CTR_MULTI = number of hubs, CTR_ITEMS = number of hub items
     Adj in;
-    // source rows
-    const float* P;            // rows of width D
+    const float* P;            // source rows of width D
     int D;
     const uint32_t* src_bitmap; // null: every source contributes and row index = vertex id
     const int32_t* src_slot;
-    int src_scale_gcn;         // multiply each source row by rsqrt(indeg[u]+1) (full forward, GCN)
-    int use_weights;           // multiply by edge weight
-    int self_pair;             // GCN: add the destination's own row as one more neighbour
+    int src_scale_gcn;         // multiply each source row by 1/sqrt(indeg[u]+1) (full forward, GCN)
+    int use_weights;           // multiply by the edge weight
+    int self_pair;             // GCN: the destination's own row is one more neighbour
     int accumulate;            // 1: S[v] += sum, 0: S[v] = sum
     float* S;                  // [N][D]
-    float* partial;            // partial rows for multi-chunk destinations
     unsigned long long* pair_ctr; // null or 1024 counters
 };
-nrt_status k_build_items(const int32_t* dst_list, int64_t n_dst, const int32_t* indeg, uint64_t* item_off,
-                         int32_t* item_slot, int32_t* item_chunk, int32_t* multi_list, uint64_t* scan_tmp,
-                         int64_t scan_tmp_len, int64_t* dev_ctrs /* fills CTR_ITEMS, CTR_MULTI, CTR_INEDGES */,
-                         hipStream_t s);
+// records + hub list for all n vertices (full forward)
+nrt_status k_all_records(const Adj& in, int64_t n, DstRec* recs, const HubWork& hubs, int64_t* dev_ctrs, hipStream_t s);
+// after the hub list is known on the device: chunk counts -> scan -> items; fills CTR_ITEMS
+nrt_status k_build_hub_items(const DstRec* recs, const HubWork& hubs, uint64_t* scan_tmp, int64_t scan_tmp_len,
+                             int64_t* dev_ctrs, hipStream_t s);
 nrt_status k_gather(const GatherArgs& a, int64_t n_items, hipStream_t s);
-nrt_status k_combine_partials(const GatherArgs& a, const int32_t* multi_list, int64_t n_multi, hipStream_t s);
+nrt_status k_combine_partials(const GatherArgs& a, int64_t n_hubs, hipStream_t s);
 
 struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update caches
     int64_t n_ins, n_del;
     const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
     const float *ins_w, *del_w;  // null when unweighted
-    const float* Hprev;          // h^{l-1} (old)
+    int n_layers;                // blockIdx.y walks the layers
+    const float* Hprev[NRT_MAX_LAYERS];   // h^{l-1} (old)
+    float* S[NRT_MAX_LAYERS];
+    int D[NRT_MAX_LAYERS];
     const int32_t* indeg_old;    // for the GCN payload scale, else null
-    float* S;
-    int D;
 };
 nrt_status k_structural_fold(const FoldArgs& a, hipStream_t s);
 

@@ -17,7 +17,7 @@ constexpr int HUB_GX = 64, HUB_GY = 32;
 __device__ inline void mark(uint32_t* bitmap, int32_t v) {
     const uint32_t bit = 1u << (v & 31);
     uint32_t* w = &bitmap[v >> 5];
-    if (!(__atomic_load_n(w, __ATOMIC_RELAXED) & bit)) atomicOr(w, bit);   // test first: most bits are already set on dense hops
+    if (!(*w & bit)) atomicOr(w, bit);   // test first (a stale 0 only costs a redundant atomic): most bits are already set on dense hops
 }
 
 __global__ void expand_kernel(Adj out, const int32_t* src_list, int64_t ns, uint32_t* bitmap,
@@ -36,6 +36,21 @@ __global__ void expand_kernel(Adj out, const int32_t* src_list, int64_t ns, uint
     }
     const int64_t o = out.off[u];
     for (int32_t j = lane; j < d; j += 64) mark(bitmap, out.idx[o + j]);
+}
+
+// few sources: a workgroup column per source, gridDim.y workgroups share a long out-list
+__global__ void expand_block_kernel(Adj out, const int32_t* src_list, uint32_t* bitmap) {
+    const int32_t u = src_list[blockIdx.x];
+    const int32_t d = out.deg[u];
+    const int64_t o = out.off[u];
+    const int32_t stride = gridDim.y * blockDim.x;
+    int32_t j = blockIdx.y * blockDim.x + threadIdx.x;
+    for (; j + 3 * stride < d; j += 4 * stride) {
+        const int32_t v0 = out.idx[o + j], v1 = out.idx[o + j + stride], v2 = out.idx[o + j + 2 * stride],
+                      v3 = out.idx[o + j + 3 * stride];
+        mark(bitmap, v0); mark(bitmap, v1); mark(bitmap, v2); mark(bitmap, v3);
+    }
+    for (; j < d; j += stride) mark(bitmap, out.idx[o + j]);
 }
 
 __global__ void expand_hubs_kernel(Adj out, uint32_t* bitmap, const unsigned long long* hub_count,
@@ -58,6 +73,11 @@ __global__ void expand_hubs_kernel(Adj out, uint32_t* bitmap, const unsigned lon
 nrt_status k_expand_frontier(const Adj& out, const int32_t* src_list, int64_t ns, uint32_t* bitmap,
                              int64_t* hub_scratch, int64_t hub_cap, hipStream_t s) {
     if (ns <= 0) return NRT_OK;
+    if (ns <= 16384) {
+        expand_block_kernel<<<dim3((unsigned)ns, 16, 1), 256, 0, s>>>(out, src_list, bitmap);
+        LAUNCH_CHECK();
+        return NRT_OK;
+    }
     unsigned long long* hub_count = (unsigned long long*)hub_scratch;
     int32_t* hub_list = (int32_t*)(hub_scratch + 1);
     NRT_TRY(k_fill_u64((uint64_t*)hub_count, 1, 0, s));

@@ -33,157 +33,302 @@ __device__ inline float4 f4_shfl_xor(float4 a, int m) {
 }
 __device__ inline float gcn_scale(int32_t indeg) { return 1.0f / sqrtf((float)(indeg + 1)); }
 
-// ------------------------------------------------------------------ items
-__global__ void item_count_kernel(const int32_t* dst_list, int64_t n_dst, const int32_t* indeg, uint64_t* item_off,
-                                  unsigned long long* inedge_sum) {
-    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    unsigned long long d = 0;
-    if (s < n_dst) {
-        const int32_t v = dst_list ? dst_list[s] : (int32_t)s;
-        d = (unsigned long long)indeg[v];
-        const uint64_t nch = d > NRT_CHUNK ? (d + NRT_CHUNK - 1) / NRT_CHUNK : 1;
-        item_off[s] = nch | ((nch > 1 ? nch : 0) << 32);
+// ------------------------------------------------------------------ records and hub items
+__global__ void all_records_kernel(Adj in, int64_t n, DstRec* recs, HubWork hubs, unsigned long long* n_hubs) {
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    DstRec r;
+    r.off = in.off[v];
+    r.deg = in.deg[v];
+    r.v = (int32_t)v;
+    recs[v] = r;
+    if (r.deg > NRT_CHUNK) {
+        unsigned long long h = atomicAdd(n_hubs, 1ULL);
+        if ((int64_t)h < hubs.hub_cap) hubs.hub_slot[h] = (int32_t)v;
     }
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) d += __shfl_xor(d, m, 64);
-    if ((threadIdx.x & 63) == 0 && d) atomicAdd(inedge_sum, d);
 }
-__global__ void item_fill_kernel(const int32_t* dst_list, int64_t n_dst, const int32_t* indeg, const uint64_t* item_off,
-                                 int32_t* item_slot, int32_t* item_chunk, int32_t* multi_list,
-                                 unsigned long long* n_multi) {
-    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (s >= n_dst) return;
-    const int32_t v = dst_list ? dst_list[s] : (int32_t)s;
-    const int32_t d = indeg[v];
-    const int32_t nch = d > NRT_CHUNK ? (d + NRT_CHUNK - 1) / NRT_CHUNK : 1;
-    const uint32_t first = (uint32_t)(item_off[s] & 0xffffffffu);
-    for (int32_t c = 0; c < nch; ++c) {
-        item_slot[first + c] = (int32_t)s;
-        item_chunk[first + c] = c;
+// launched over the whole hub capacity: entries past the hub count scan as zero
+__global__ void hub_count_kernel(const DstRec* recs, HubWork hubs, const unsigned long long* n_hubs) {
+    const int64_t h = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= hubs.hub_cap) return;
+    uint64_t c = 0;
+    if (h < (int64_t)*n_hubs) c = (uint64_t)((recs[hubs.hub_slot[h]].deg + NRT_CHUNK - 1) / NRT_CHUNK);
+    hubs.hub_first[h] = c;
+}
+// one wave per hub writes that hub's items
+__global__ void hub_fill_kernel(const DstRec* recs, HubWork hubs, const unsigned long long* n_hubs) {
+    const int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (h >= hubs.hub_cap || h >= (int64_t)*n_hubs) return;
+    const int32_t nch = (recs[hubs.hub_slot[h]].deg + NRT_CHUNK - 1) / NRT_CHUNK;
+    const int64_t first = (int64_t)hubs.hub_first[h];
+    for (int32_t c = lane; c < nch; c += 64) {
+        if (first + c < hubs.item_cap) {
+            hubs.item_hub[first + c] = (int32_t)h;
+            hubs.item_chunk[first + c] = c;
+        }
     }
-    if (nch > 1) multi_list[atomicAdd(n_multi, 1ULL)] = (int32_t)s;
 }
 
 // ------------------------------------------------------------------ gather
-template <int LPR>   // lanes per row
-__global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs a) {
-    constexpr int RPI = 64 / LPR;   // rows fetched by one wave-wide load
-    __shared__ int32_t s_row[WAVES_PER_BLOCK][NRT_CHUNK + 1];
-    __shared__ float s_coef[WAVES_PER_BLOCK][NRT_CHUNK + 1];
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int64_t item = (int64_t)blockIdx.x * WAVES_PER_BLOCK + w;
-    const int64_t n_items = (int64_t)(*a.n_items_dev & 0xffffffffu);
-    if (item >= n_items) return;
-    const int32_t s = a.item_slot[item];
-    const int32_t chunk = a.item_chunk[item];
-    const int32_t v = a.dst_list ? a.dst_list[s] : s;
-    const int32_t deg = a.in.deg[v];
-    const int64_t base = a.in.off[v] + (int64_t)chunk * NRT_CHUNK;
-    const int32_t cnt = min(NRT_CHUNK, deg - chunk * NRT_CHUNK);
-    int32_t* rows = s_row[w];
-    float* coefs = s_coef[w];
+// Work units: [0, n_dst) are the destinations themselves (those with at most NRT_CHUNK in-edges are served
+// here, hubs are skipped); [n_dst, n_dst + n_items) are the hub items, NRT_CHUNK in-list entries each, whose
+// partial row goes to partial[item].  A wave owns `upw` consecutive units and walks them as a sequence of
+// steps of 64 in-list entries (one per lane) through a four-stage software pipeline, so that the four
+// dependent memory accesses of a step (in-list entry -> bitmap word of changed sources -> slot of the
+// source's delta row -> the row itself) overlap with the accesses of the neighbouring steps instead of
+// being paid one after the other for every destination:
+//   A  load the in-list entries of step t+3
+//   B  load the bitmap words for step t+2
+//   C  test the bits, load the slots of the survivors of step t+1 (and the old aggregate row if the step
+//      closes its destination)
+//   D  walk the ballot of survivors of step t with scalar bit operations: each survivor's slot is broadcast
+//      with a lane read, so the row address is wave-uniform and the row load is one coalesced instruction
+//      (rows narrower than 256 floats put RPI = 2 or 4 survivors into one load, one per LPR-lane sub-group);
+//      on the last step of a unit reduce the sub-groups and write the row.
+struct StepMeta {
+    int valid;     // 0: pipeline bubble
+    int ui;        // unit index inside the wave
+    int j;         // first in-list entry of the step inside the unit
+    int n;         // entries in the step
+    int first, last;
+};
 
-    // stage the surviving (row, coefficient) pairs of this item
-    int nvalid = 0;
-    for (int j = 0; j < cnt; j += 64) {
-        const int jj = j + lane;
-        bool ok = jj < cnt;
-        int32_t u = 0;
-        if (ok) {
-            u = a.in.idx[base + jj];
-            if (a.src_bitmap) ok = (a.src_bitmap[u >> 5] >> (u & 31)) & 1u;
-        }
-        const unsigned long long m = __ballot(ok);
-        if (ok) {
-            const int pos = nvalid + __popcll(m & ((1ULL << lane) - 1ULL));
-            float c = a.use_weights ? a.in.wts[base + jj] : 1.0f;
-            if (a.src_scale_gcn) c *= gcn_scale(a.in.deg[u]);
-            rows[pos] = a.src_bitmap ? a.src_slot[u] : u;
-            coefs[pos] = c;
-        }
-        nvalid += __popcll(m);
-    }
-    if (a.self_pair && chunk == 0) {
-        bool ok = true;
-        if (a.src_bitmap) ok = (a.src_bitmap[v >> 5] >> (v & 31)) & 1u;
-        if (ok) {
-            if (lane == 0) {
-                rows[nvalid] = a.src_bitmap ? a.src_slot[v] : v;
-                coefs[nvalid] = a.src_scale_gcn ? gcn_scale(deg) : 1.0f;
-            }
-            nvalid += 1;
-        }
-    }
-    if (a.pair_ctr && lane == 0 && nvalid) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)nvalid);
-    __builtin_amdgcn_wave_barrier();
-    __threadfence_block();
-
-    const uint64_t off = a.item_off[s];
-    const bool multi = deg > NRT_CHUNK;
-    const int sub = lane / LPR;
+template <int LPR, int NV, bool FILTER, bool COEF>
+__global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs a, int upw) {
+    constexpr int RPI = 64 / LPR;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane / LPR, gl = lane % LPR;
     const int D = a.D;
-    for (int cb = 0; cb < D; cb += LPR * 4) {
-        const int col = cb + (lane % LPR) * 4;
-        const bool live = col < D;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        float4 old = acc;
-        float* dstp = multi ? a.partial + ((int64_t)(off >> 32) + chunk) * D + col : a.S + (int64_t)v * D + col;
-        if (live && !multi && a.accumulate) old = *reinterpret_cast<const float4*>(dstp);
-        if (live) {
-            const float* P = a.P + col;
-            int i = sub;
-            for (; i + 3 * RPI < nvalid; i += 4 * RPI) {
-                const int32_t r0 = rows[i], r1 = rows[i + RPI], r2 = rows[i + 2 * RPI], r3 = rows[i + 3 * RPI];
-                const float c0 = coefs[i], c1 = coefs[i + RPI], c2 = coefs[i + 2 * RPI], c3 = coefs[i + 3 * RPI];
-                const float4 x0 = *reinterpret_cast<const float4*>(P + (int64_t)r0 * D);
-                const float4 x1 = *reinterpret_cast<const float4*>(P + (int64_t)r1 * D);
-                const float4 x2 = *reinterpret_cast<const float4*>(P + (int64_t)r2 * D);
-                const float4 x3 = *reinterpret_cast<const float4*>(P + (int64_t)r3 * D);
-                acc = f4_fma(c0, x0, acc);
-                acc = f4_fma(c1, x1, acc);
-                acc = f4_fma(c2, x2, acc);
-                acc = f4_fma(c3, x3, acc);
-            }
-            for (; i < nvalid; i += RPI) {
-                const float4 x0 = *reinterpret_cast<const float4*>(P + (int64_t)rows[i] * D);
-                acc = f4_fma(coefs[i], x0, acc);
-            }
+    int64_t n_items = a.dev_ctrs[CTR_ITEMS];
+    if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
+    const int64_t total = a.n_dst + n_items;
+    const int64_t unit0 = ((int64_t)blockIdx.x * WAVES_PER_BLOCK + w) * upw;
+    if (unit0 >= total) return;
+    const int nu = (int)min((int64_t)upw, total - unit0);
+
+    // lane i holds the description of unit i of this wave
+    int64_t m_base = 0, m_out = 0;     // first pool entry; output row offset (floats) in S or in partial
+    int32_t m_cnt = -1, m_v = 0, m_deg = 0, m_part = 0, m_chunk = 0;
+    if (lane < nu) {
+        const int64_t unit = unit0 + lane;
+        DstRec rec;
+        if (unit < a.n_dst) {
+            rec = a.recs[unit];
+            m_cnt = rec.deg > NRT_CHUNK ? -1 : rec.deg;
+            m_out = (int64_t)rec.v * D;
+        } else {
+            const int64_t item = unit - a.n_dst;
+            m_chunk = a.hubs.item_chunk[item];
+            rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[item]]];
+            m_cnt = min(NRT_CHUNK, rec.deg - m_chunk * NRT_CHUNK);
+            m_out = item * D;
+            m_part = 1;
         }
-#pragma unroll
-        for (int m = LPR; m < 64; m <<= 1) acc = f4_add(acc, f4_shfl_xor(acc, m));
-        if (live && sub == 0) {
-            if (!multi && a.accumulate) acc = f4_add(acc, old);
-            *reinterpret_cast<float4*>(dstp) = acc;
-        }
+        m_base = rec.off + (int64_t)m_chunk * NRT_CHUNK;
+        m_v = rec.v;
+        m_deg = rec.deg;
     }
+    const int32_t m_base_lo = (int32_t)(m_base & 0xffffffff), m_base_hi = (int32_t)(m_base >> 32);
+    const int32_t m_out_lo = (int32_t)(m_out & 0xffffffff), m_out_hi = (int32_t)(m_out >> 32);
+    auto lane64 = [&](int32_t lo, int32_t hi, int i) {
+        const uint32_t l = (uint32_t)__builtin_amdgcn_readlane(lo, i);
+        const uint32_t h = (uint32_t)__builtin_amdgcn_readlane(hi, i);
+        return (int64_t)(((uint64_t)h << 32) | l);
+    };
+
+    // scalar step iterator
+    int it_ui = 0, it_j = 0;
+    auto next_step = [&]() {
+        StepMeta st;
+        st.valid = 0; st.ui = 0; st.j = 0; st.n = 0; st.first = 0; st.last = 0;
+        while (it_ui < nu) {
+            const int cnt = __builtin_amdgcn_readlane(m_cnt, it_ui);
+            if (cnt < 0) { ++it_ui; continue; }            // a hub among the destinations: served through its items
+            st.valid = 1;
+            st.ui = it_ui;
+            st.j = it_j;
+            st.n = min(64, cnt - it_j);
+            st.first = it_j == 0;
+            st.last = it_j + 64 >= cnt;
+            if (st.last) { ++it_ui; it_j = 0; } else { it_j += 64; }
+            break;
+        }
+        return st;
+    };
+
+    StepMeta stB, stC, stD;
+    stB.valid = stC.valid = stD.valid = 0;
+    stB.ui = stC.ui = stD.ui = 0; stB.j = stC.j = stD.j = 0; stB.n = stC.n = stD.n = 0;
+    stB.first = stC.first = stD.first = 0; stB.last = stC.last = stD.last = 0;
+    int32_t uB = -1, uC = -1, slD = -1;
+    float wB = 1.f, wC = 1.f, cD = 1.f;
+    uint32_t xC = 0;                 // bitmap word (FILTER) or in-degree of the source (GCN scale)
+    float4 acc[NV], oldD[NV];
+#pragma unroll
+    for (int q = 0; q < NV; ++q) { acc[q] = make_float4(0.f, 0.f, 0.f, 0.f); oldD[q] = acc[q]; }
+    const float* Pl = a.P + gl * 4;
+    long long pairs = 0;
+
+    auto take = [&](unsigned long long& m, int32_t rv, float cv) {
+        int32_t rr = -1;
+        float cc = 1.0f;
+#pragma unroll
+        for (int t = 0; t < RPI; ++t) {
+            if (m) {
+                const int bit = __ffsll((long long)m) - 1;
+                m &= m - 1;
+                const int32_t rs = __builtin_amdgcn_readlane(rv, bit);
+                if (sub == t) rr = rs;
+                if (COEF) {
+                    const float cs = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, cv), bit));
+                    if (sub == t) cc = cs;
+                }
+            }
+        }
+        return make_int2(rr, __builtin_bit_cast(int, cc));
+    };
+    auto fetch_add = [&](int2 p0, int2 p1, int2 p2, int2 p3) {
+        const float c0 = __builtin_bit_cast(float, p0.y), c1 = __builtin_bit_cast(float, p1.y);
+        const float c2 = __builtin_bit_cast(float, p2.y), c3 = __builtin_bit_cast(float, p3.y);
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            const bool live = gl * 4 + q * LPR * 4 < D;
+            float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0, x2 = x0, x3 = x0;
+            if (p0.x >= 0 && live) x0 = *reinterpret_cast<const float4*>(Pl + (int64_t)p0.x * D + q * LPR * 4);
+            if (p1.x >= 0 && live) x1 = *reinterpret_cast<const float4*>(Pl + (int64_t)p1.x * D + q * LPR * 4);
+            if (p2.x >= 0 && live) x2 = *reinterpret_cast<const float4*>(Pl + (int64_t)p2.x * D + q * LPR * 4);
+            if (p3.x >= 0 && live) x3 = *reinterpret_cast<const float4*>(Pl + (int64_t)p3.x * D + q * LPR * 4);
+            acc[q] = COEF ? f4_fma(c0, x0, acc[q]) : f4_add(acc[q], x0);
+            acc[q] = COEF ? f4_fma(c1, x1, acc[q]) : f4_add(acc[q], x1);
+            acc[q] = COEF ? f4_fma(c2, x2, acc[q]) : f4_add(acc[q], x2);
+            acc[q] = COEF ? f4_fma(c3, x3, acc[q]) : f4_add(acc[q], x3);
+        }
+    };
+
+    for (;;) {
+        // ---- stage A: in-list entries of a new step
+        const StepMeta stA = next_step();
+        if (!(stA.valid | stB.valid | stC.valid | stD.valid)) break;
+        int32_t uA = -1;
+        float wA = 1.f;
+        if (stA.valid) {
+            const int64_t base = lane64(m_base_lo, m_base_hi, stA.ui) + stA.j;
+            if (lane < stA.n) {
+                uA = a.in.idx[base + lane];
+                if (COEF && a.use_weights) wA = a.in.wts[base + lane];
+            }
+        }
+        // ---- stage B: bitmap word (or source degree) for the entries loaded one iteration ago
+        uint32_t xB = 0;
+        if (stB.valid) {
+            if (FILTER) { if (uB >= 0) xB = a.src_bitmap[uB >> 5]; }
+            else if (COEF && a.src_scale_gcn) { if (uB >= 0) xB = (uint32_t)a.in.deg[uB]; }
+        }
+        // ---- stage C: survivors, their slots; the old aggregate row if this step closes its unit
+        int32_t slC = -1;
+        float cC = wC;
+        float4 oldC[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) oldC[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (stC.valid) {
+            if (FILTER) {
+                if (uC >= 0 && ((xC >> (uC & 31)) & 1u)) slC = a.src_slot[uC];
+            } else {
+                slC = uC;
+                if (COEF && a.src_scale_gcn && uC >= 0) cC *= gcn_scale((int32_t)xC);
+            }
+            if (stC.last && a.accumulate && !__builtin_amdgcn_readlane(m_part, stC.ui)) {
+                const float* op = a.S + lane64(m_out_lo, m_out_hi, stC.ui) + gl * 4;
+#pragma unroll
+                for (int q = 0; q < NV; ++q)
+                    if (sub == 0 && gl * 4 + q * LPR * 4 < D) oldC[q] = *reinterpret_cast<const float4*>(op + q * LPR * 4);
+            }
+        }
+        // ---- stage D: stream the rows of the survivors
+        if (stD.valid) {
+            unsigned long long m = __ballot(slD >= 0);
+            pairs += __popcll(m);
+            while (m) {
+                const int2 p0 = take(m, slD, cD);
+                const int2 p1 = take(m, slD, cD);
+                const int2 p2 = take(m, slD, cD);
+                const int2 p3 = take(m, slD, cD);
+                fetch_add(p0, p1, p2, p3);
+            }
+            if (stD.first && a.self_pair && __builtin_amdgcn_readlane(m_chunk, stD.ui) == 0) {
+                const int32_t v = __builtin_amdgcn_readlane(m_v, stD.ui);
+                bool sok = true;
+                if (FILTER) sok = (a.src_bitmap[v >> 5] >> (v & 31)) & 1u;
+                if (sok) {
+                    const int32_t rs = FILTER ? a.src_slot[v] : v;
+                    const float cs = (COEF && a.src_scale_gcn) ? gcn_scale(__builtin_amdgcn_readlane(m_deg, stD.ui)) : 1.0f;
+                    fetch_add(make_int2(sub == 0 ? rs : -1, __builtin_bit_cast(int, cs)), make_int2(-1, 0),
+                              make_int2(-1, 0), make_int2(-1, 0));
+                    pairs += 1;
+                }
+            }
+            if (stD.last) {
+                const int part = __builtin_amdgcn_readlane(m_part, stD.ui);
+                float* op = (part ? a.hubs.partial : a.S) + lane64(m_out_lo, m_out_hi, stD.ui) + gl * 4;
+#pragma unroll
+                for (int q = 0; q < NV; ++q) {
+#pragma unroll
+                    for (int mm = LPR; mm < 64; mm <<= 1) acc[q] = f4_add(acc[q], f4_shfl_xor(acc[q], mm));
+                    if (sub == 0 && gl * 4 + q * LPR * 4 < D) {
+                        float4 y = acc[q];
+                        if (!part && a.accumulate) y = f4_add(y, oldD[q]);
+                        *reinterpret_cast<float4*>(op + q * LPR * 4) = y;
+                    }
+                    acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+        }
+        // ---- rotate
+        stD = stC; stC = stB; stB = stA;
+        slD = slC; cD = cC;
+#pragma unroll
+        for (int q = 0; q < NV; ++q) oldD[q] = oldC[q];
+        uC = uB; wC = wB; xC = xB;
+        uB = uA; wB = wA;
+    }
+    if (a.pair_ctr && lane == 0 && pairs) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)pairs);
 }
 
-// one wave per multi-item destination: sum its partial rows in item order
-__global__ void combine_kernel(GatherArgs a, const int32_t* multi_list, int64_t n_multi) {
-    const int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+// one wave per hub: sum its partial rows in item order into the cached aggregate
+__global__ void combine_kernel(GatherArgs a) {
+    const int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
-    if (i >= n_multi) return;
-    const int32_t s = multi_list[i];
-    const int32_t v = a.dst_list ? a.dst_list[s] : s;
-    const int32_t deg = a.in.deg[v];
-    const int32_t nch = (deg + NRT_CHUNK - 1) / NRT_CHUNK;
-    const int64_t pfirst = (int64_t)(a.item_off[s] >> 32);
+    if (h >= a.dev_ctrs[CTR_MULTI] || h >= a.hubs.hub_cap) return;
+    const DstRec rec = a.recs[a.hubs.hub_slot[h]];
+    const int32_t nch = (rec.deg + NRT_CHUNK - 1) / NRT_CHUNK;
+    const int64_t first = (int64_t)a.hubs.hub_first[h];
     const int D = a.D;
     for (int col = lane * 4; col < D; col += 256) {
+        const float* p = a.hubs.partial + first * D + col;
         float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int32_t c = 0; c < nch; ++c)
-            acc = f4_add(acc, *reinterpret_cast<const float4*>(a.partial + (pfirst + c) * D + col));
-        float4* dst = reinterpret_cast<float4*>(a.S + (int64_t)v * D + col);
+        int32_t c = 0;
+        for (; c + 3 < nch; c += 4) {
+            const float4 x0 = *reinterpret_cast<const float4*>(p + (int64_t)c * D);
+            const float4 x1 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 1) * D);
+            const float4 x2 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 2) * D);
+            const float4 x3 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 3) * D);
+            acc = f4_add(acc, x0); acc = f4_add(acc, x1); acc = f4_add(acc, x2); acc = f4_add(acc, x3);
+        }
+        for (; c < nch; ++c) acc = f4_add(acc, *reinterpret_cast<const float4*>(p + (int64_t)c * D));
+        float4* dst = reinterpret_cast<float4*>(a.S + (int64_t)rec.v * D + col);
         if (a.accumulate) acc = f4_add(acc, *dst);
         *dst = acc;
     }
 }
 
 // ------------------------------------------------------------------ structural fold
-// one wave per updated edge: S[dst] += sign * c * p_src(old)
+// one wave per (updated edge, layer): S^l[dst] += sign * c * p^{l-1}_src(old)
 __global__ void structural_fold_kernel(FoldArgs a) {
     const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
+    const int l = blockIdx.y;
     if (op >= a.n_ins + a.n_del) return;
     const bool is_del = op >= a.n_ins;
     const int64_t i = is_del ? op - a.n_ins : op;
@@ -193,9 +338,10 @@ __global__ void structural_fold_kernel(FoldArgs a) {
     if (is_del && a.del_w) c *= a.del_w[i];
     if (!is_del && a.ins_w) c *= a.ins_w[i];
     if (a.indeg_old) c *= gcn_scale(a.indeg_old[u]);
-    const float* src = a.Hprev + (int64_t)u * a.D;
-    float* dst = a.S + (int64_t)v * a.D;
-    for (int k = lane; k < a.D; k += 64) unsafeAtomicAdd(dst + k, c * src[k]);
+    const int D = a.D[l];
+    const float* src = a.Hprev[l] + (int64_t)u * D;
+    float* dst = a.S[l] + (int64_t)v * D;
+    for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, c * src[k]);
 }
 
 // ------------------------------------------------------------------ layer-0 delta payloads
@@ -223,34 +369,54 @@ __global__ void layer0_delta_kernel(DeltaArgs a) {
 
 }  // namespace
 
-nrt_status k_build_items(const int32_t* dst_list, int64_t n_dst, const int32_t* indeg, uint64_t* item_off,
-                         int32_t* item_slot, int32_t* item_chunk, int32_t* multi_list, uint64_t* scan_tmp,
-                         int64_t scan_tmp_len, int64_t* dev_ctrs, hipStream_t s) {
-    NRT_TRY(k_fill_u64((uint64_t*)(dev_ctrs + CTR_ITEMS), 3, 0, s));
-    if (n_dst <= 0) return NRT_OK;
-    const int nb = (int)cdiv(n_dst, 256);
-    item_count_kernel<<<nb, 256, 0, s>>>(dst_list, n_dst, indeg, item_off, (unsigned long long*)(dev_ctrs + CTR_INEDGES));
-    LAUNCH_CHECK();
-    NRT_TRY(k_exclusive_scan_u64(item_off, n_dst, scan_tmp, scan_tmp_len, (uint64_t*)(dev_ctrs + CTR_ITEMS), s));
-    item_fill_kernel<<<nb, 256, 0, s>>>(dst_list, n_dst, indeg, item_off, item_slot, item_chunk, multi_list,
-                                        (unsigned long long*)(dev_ctrs + CTR_MULTI));
+nrt_status k_all_records(const Adj& in, int64_t n, DstRec* recs, const HubWork& hubs, int64_t* dev_ctrs, hipStream_t s) {
+    NRT_TRY(k_fill_u64((uint64_t*)(dev_ctrs + CTR_ITEMS), 2 + 16, 0, s));
+    all_records_kernel<<<(int)cdiv(n, 256), 256, 0, s>>>(in, n, recs, hubs, (unsigned long long*)(dev_ctrs + CTR_MULTI));
     LAUNCH_CHECK();
     return NRT_OK;
 }
 
+nrt_status k_build_hub_items(const DstRec* recs, const HubWork& hubs, uint64_t* scan_tmp, int64_t scan_tmp_len,
+                             int64_t* dev_ctrs, hipStream_t s) {
+    const unsigned long long* nh = (const unsigned long long*)(dev_ctrs + CTR_MULTI);
+    hub_count_kernel<<<(int)cdiv(hubs.hub_cap, 256), 256, 0, s>>>(recs, hubs, nh);
+    LAUNCH_CHECK();
+    NRT_TRY(k_exclusive_scan_u64(hubs.hub_first, hubs.hub_cap, scan_tmp, scan_tmp_len, (uint64_t*)(dev_ctrs + CTR_ITEMS), s));
+    hub_fill_kernel<<<(int)cdiv(hubs.hub_cap * 64, 256), 256, 0, s>>>(recs, hubs, nh);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+template <int LPR, int NV>
+static void launch_gather(const GatherArgs& a, int64_t units, hipStream_t s) {
+    int upw = (int)(units / 16384);            // keep at least ~16k waves when there is enough work
+    upw = upw < 1 ? 1 : (upw > 8 ? 8 : upw);
+    const int nb = (int)cdiv(cdiv(units, upw), WAVES_PER_BLOCK);
+    const int threads = WAVES_PER_BLOCK * 64;
+    const bool filter = a.src_bitmap != nullptr;
+    const bool coef = a.use_weights || a.src_scale_gcn;
+    if (filter && coef) gather_kernel<LPR, NV, true, true><<<nb, threads, 0, s>>>(a, upw);
+    else if (filter) gather_kernel<LPR, NV, true, false><<<nb, threads, 0, s>>>(a, upw);
+    else if (coef) gather_kernel<LPR, NV, false, true><<<nb, threads, 0, s>>>(a, upw);
+    else gather_kernel<LPR, NV, false, false><<<nb, threads, 0, s>>>(a, upw);
+}
+
+// destinations [0, n_dst) and hub items [0, n_items) in one launch
 nrt_status k_gather(const GatherArgs& a, int64_t n_items, hipStream_t s) {
-    if (n_items <= 0) return NRT_OK;
-    const int nb = (int)cdiv(n_items, WAVES_PER_BLOCK);
-    if (a.D <= 64) gather_kernel<16><<<nb, WAVES_PER_BLOCK * 64, 0, s>>>(a);
-    else if (a.D <= 128) gather_kernel<32><<<nb, WAVES_PER_BLOCK * 64, 0, s>>>(a);
-    else gather_kernel<64><<<nb, WAVES_PER_BLOCK * 64, 0, s>>>(a);
+    const int64_t units = a.n_dst + n_items;
+    if (units <= 0) return NRT_OK;
+    if (a.D <= 64) launch_gather<16, 1>(a, units, s);
+    else if (a.D <= 128) launch_gather<32, 1>(a, units, s);
+    else if (a.D <= 256) launch_gather<64, 1>(a, units, s);
+    else if (a.D <= 512) launch_gather<64, 2>(a, units, s);
+    else launch_gather<64, 4>(a, units, s);
     LAUNCH_CHECK();
     return NRT_OK;
 }
 
-nrt_status k_combine_partials(const GatherArgs& a, const int32_t* multi_list, int64_t n_multi, hipStream_t s) {
-    if (n_multi <= 0) return NRT_OK;
-    combine_kernel<<<(int)cdiv(n_multi * 64, 256), 256, 0, s>>>(a, multi_list, n_multi);
+nrt_status k_combine_partials(const GatherArgs& a, int64_t n_hubs, hipStream_t s) {
+    if (n_hubs <= 0) return NRT_OK;
+    combine_kernel<<<(int)cdiv(n_hubs * 64, 256), 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }
@@ -258,7 +424,7 @@ nrt_status k_combine_partials(const GatherArgs& a, const int32_t* multi_list, in
 nrt_status k_structural_fold(const FoldArgs& a, hipStream_t s) {
     const int64_t nops = a.n_ins + a.n_del;
     if (nops <= 0) return NRT_OK;
-    structural_fold_kernel<<<(int)cdiv(nops * 64, 256), 256, 0, s>>>(a);
+    structural_fold_kernel<<<dim3((unsigned)cdiv(nops * 64, 256), (unsigned)a.n_layers, 1), 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }

@@ -22,43 +22,43 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 constexpr int BM = 128;
-constexpr int KT = 32;
-constexpr int LDS_STRIDE = KT + 4;
 
 __device__ inline float gcn_scale(int32_t indeg) { return 1.0f / sqrtf((float)(indeg + 1)); }
 
+// Branch-free on purpose: the address is clamped into the row and the value masked afterwards, so that the
+// loads of one slice are issued back to back instead of each waiting behind its own bounds branch.
+template <int AMODE>
 __device__ inline float4 load_a(const GemmArgs& g, int64_t v, float sc, int k, bool ok) {
-    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (!ok || k >= g.K) return r;
-    switch (g.a_mode) {
-    case A_PLAIN:
-        r = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + k);
-        break;
-    case A_SCALE_GCN: {
-        r = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + k);
-        r.x *= sc; r.y *= sc; r.z *= sc; r.w *= sc;
-        break;
-    }
-    case A_CONCAT_MEAN:
-        if (k < g.ldp) {
-            r = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + k);
-        } else {
-            r = *reinterpret_cast<const float4*>(g.P1 + v * g.ldp + (k - g.ldp));
-            r.x *= sc; r.y *= sc; r.z *= sc; r.w *= sc;
-        }
-        break;
-    default: {
-        const float4 p = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + k);
-        const float4 q = *reinterpret_cast<const float4*>(g.P1 + v * g.ldp + k);
+    const bool live = ok && k < g.K;
+    const int kc = k < g.K ? k : g.K - 4;
+    float4 r;
+    float m = 1.0f;
+    if (AMODE == A_PLAIN) {
+        r = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
+    } else if (AMODE == A_SCALE_GCN) {
+        r = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
+        m = sc;
+    } else if (AMODE == A_CONCAT_MEAN) {
+        const bool self = kc < g.ldp;
+        const float* p = (self ? g.P0 : g.P1) + v * g.ldp + (self ? kc : kc - g.ldp);
+        r = *reinterpret_cast<const float4*>(p);
+        m = self ? 1.0f : sc;
+    } else {
+        const float4 p = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
+        const float4 q = *reinterpret_cast<const float4*>(g.P1 + v * g.ldp + kc);
         r.x = fmaf(g.axpy_c, p.x, q.x); r.y = fmaf(g.axpy_c, p.y, q.y);
         r.z = fmaf(g.axpy_c, p.z, q.z); r.w = fmaf(g.axpy_c, p.w, q.w);
     }
-    }
+    m = live ? m : 0.0f;
+    r.x *= m; r.y *= m; r.z *= m; r.w *= m;
     return r;
 }
 
-template <int BN, int WM, int WN>
+template <int BN, int WM, int WN, int AMODE, int KT>
 __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
+    constexpr int LDS_STRIDE = KT + 4;
+    constexpr int TPR = KT / 4;            // threads that stage one row of a slice
+    constexpr int RPP = 256 / TPR;         // rows staged per pass
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
     constexpr int A_LOADS = BM * KT / 4 / 256;   // float4 per thread per slice
     constexpr int B_LOADS = BN * KT / 4 / 256;
@@ -71,18 +71,18 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
     const int col_base = blockIdx.y * BN;
 
     // rows this thread stages
-    const int lr = tid >> 3, lk = (tid & 7) * 4;
+    const int lr = tid / TPR, lk = (tid % TPR) * 4;
     int64_t av[A_LOADS];
     float asc[A_LOADS];
     bool aok[A_LOADS];
 #pragma unroll
     for (int p = 0; p < A_LOADS; ++p) {
-        const int64_t m = row_base + lr + 32 * p;
+        const int64_t m = row_base + lr + RPP * p;
         aok[p] = m < g.M;
         av[p] = aok[p] ? ((g.rows && !g.a_is_compact) ? (int64_t)g.rows[m] : m) : 0;
         asc[p] = 1.0f;
-        if (aok[p] && g.a_mode == A_SCALE_GCN) asc[p] = gcn_scale(g.indeg[av[p]]);
-        if (aok[p] && g.a_mode == A_CONCAT_MEAN) {
+        if (aok[p] && AMODE == A_SCALE_GCN) asc[p] = gcn_scale(g.indeg[av[p]]);
+        if (aok[p] && AMODE == A_CONCAT_MEAN) {
             const int32_t d = g.indeg[av[p]];
             asc[p] = d > 0 ? 1.0f / (float)d : 0.0f;
         }
@@ -99,13 +99,16 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
     float4 ra[A_LOADS], rb[B_LOADS];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int p = 0; p < A_LOADS; ++p) ra[p] = load_a(g, av[p], asc[p], k0 + lk, aok[p]);
+        for (int p = 0; p < A_LOADS; ++p) ra[p] = load_a<AMODE>(g, av[p], asc[p], k0 + lk, aok[p]);
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
-            const int n = col_base + lr + 32 * p;
+            const int n = col_base + lr + RPP * p;
             const int k = k0 + lk;
-            rb[p] = (n < g.N && k < g.K) ? *reinterpret_cast<const float4*>(g.Wt + (int64_t)n * g.K + k)
-                                          : make_float4(0.f, 0.f, 0.f, 0.f);
+            const int nc = n < g.N ? n : g.N - 1, kc = k < g.K ? k : g.K - 4;
+            float4 t = *reinterpret_cast<const float4*>(g.Wt + (int64_t)nc * g.K + kc);
+            const float m = (n < g.N && k < g.K) ? 1.0f : 0.0f;
+            t.x *= m; t.y *= m; t.z *= m; t.w *= m;
+            rb[p] = t;
         }
     };
 
@@ -114,10 +117,10 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
     for (int k0 = 0; k0 < g.K; k0 += KT) {
 #pragma unroll
         for (int p = 0; p < A_LOADS; ++p)
-            *reinterpret_cast<float4*>(&As[(lr + 32 * p) * LDS_STRIDE + lk]) = ra[p];
+            *reinterpret_cast<float4*>(&As[(lr + RPP * p) * LDS_STRIDE + lk]) = ra[p];
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p)
-            *reinterpret_cast<float4*>(&Bs[(lr + 32 * p) * LDS_STRIDE + lk]) = rb[p];
+            *reinterpret_cast<float4*>(&Bs[(lr + RPP * p) * LDS_STRIDE + lk]) = rb[p];
         __syncthreads();
         if (k0 + KT < g.K) fetch(k0 + KT);
 #pragma unroll
@@ -142,29 +145,50 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
         __syncthreads();
     }
 
-    // epilogue = write-back
+    // epilogue = write-back.  All old rows a lane needs are read before anything is stored, so the loads
+    // are independent of the stores and stay in flight together.
+    float bias[TN];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) {
+        const int n = col_base + (wn * TN + j) * 32 + l32;
+        bias[j] = (g.bias && n < g.N) ? g.bias[n] : 0.f;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            const int64_t m = row_base + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-            if (m >= g.M) continue;
-            const int64_t v = g.rows ? (int64_t)g.rows[m] : m;
-            float cn = 1.0f, co = 1.0f;
-            if (g.DP && g.dp_scale_gcn) { cn = gcn_scale(g.indeg[v]); co = gcn_scale(g.indeg_old[v]); }
+        for (int rb = 0; rb < 16; rb += 4) {
+            int64_t mrow[4], vrow[4];
+            float cn[4], co[4], oldv[4][TN];
 #pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const int n = col_base + (wn * TN + j) * 32 + l32;
-                if (n >= g.N) continue;
-                float y = acc[i][j][r];
-                if (g.bias) y += g.bias[n];
-                if (g.act == 1) y = fmaxf(y, 0.f);
-                else if (g.act == 2) y = y > 0.f ? y : expm1f(y);
-                if (g.out_compact) g.out_compact[m * g.N + n] = y;
-                if (g.H) {
-                    float* hp = g.H + v * g.N + n;
-                    if (g.DP) g.DP[m * g.N + n] = y * cn - *hp * co;
-                    *hp = y;
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = rb + rr;
+                mrow[rr] = row_base + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * half + (r % 4);
+                const bool ok = mrow[rr] < g.M;
+                vrow[rr] = ok ? (g.rows ? (int64_t)g.rows[mrow[rr]] : mrow[rr]) : 0;
+                cn[rr] = 1.0f; co[rr] = 1.0f;
+                if (ok && g.DP && g.dp_scale_gcn) { cn[rr] = gcn_scale(g.indeg[vrow[rr]]); co[rr] = gcn_scale(g.indeg_old[vrow[rr]]); }
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = col_base + (wn * TN + j) * 32 + l32;
+                    const int nc = n < g.N ? n : g.N - 1;
+                    oldv[rr][j] = g.DP ? g.H[vrow[rr] * g.N + nc] : 0.f;   // vrow is 0 for rows past M: always in range
+                }
+            }
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                if (mrow[rr] >= g.M) continue;
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    const int n = col_base + (wn * TN + j) * 32 + l32;
+                    if (n >= g.N) continue;
+                    float y = acc[i][j][rb + rr] + bias[j];
+                    if (g.act == 1) y = fmaxf(y, 0.f);
+                    else if (g.act == 2) y = y > 0.f ? y : expm1f(y);
+                    if (g.out_compact) g.out_compact[mrow[rr] * g.N + n] = y;
+                    if (g.H) {
+                        if (g.DP) g.DP[mrow[rr] * g.N + n] = y * cn[rr] - oldv[rr][j] * co[rr];
+                        g.H[vrow[rr] * g.N + n] = y;
+                    }
                 }
             }
         }
@@ -181,18 +205,23 @@ __global__ void transpose_kernel(const float* W, float* Wt, int K, int N) {
 
 }  // namespace
 
+template <int AMODE>
+static void launch_gemm(const GemmArgs& g, hipStream_t s) {
+    const unsigned gx = (unsigned)cdiv(g.M, BM);
+    if (g.N > 128) gemm_kernel<256, 2, 2, AMODE, 32><<<dim3(gx, (unsigned)cdiv(g.N, 256)), 256, 0, s>>>(g);
+    else if (g.N > 64) gemm_kernel<128, 2, 2, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
+    else if (g.N > 32) gemm_kernel<64, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
+    else gemm_kernel<32, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
+}
+
 nrt_status k_gemm(const GemmArgs& g, hipStream_t s) {
     if (g.M <= 0) return NRT_OK;
     if (g.K % 4 || g.ldp % 4) { nrt_set_error("gemm: widths must be multiples of 4"); return NRT_ERR_UNSUPPORTED; }
-    const unsigned gx = (unsigned)cdiv(g.M, BM);
-    if (g.N > 128) {
-        gemm_kernel<256, 2, 2><<<dim3(gx, (unsigned)cdiv(g.N, 256)), 256, 0, s>>>(g);
-    } else if (g.N > 64) {
-        gemm_kernel<128, 2, 2><<<dim3(gx, 1), 256, 0, s>>>(g);
-    } else if (g.N > 32) {
-        gemm_kernel<64, 4, 1><<<dim3(gx, 1), 256, 0, s>>>(g);
-    } else {
-        gemm_kernel<32, 4, 1><<<dim3(gx, 1), 256, 0, s>>>(g);
+    switch (g.a_mode) {
+    case A_PLAIN: launch_gemm<A_PLAIN>(g, s); break;
+    case A_SCALE_GCN: launch_gemm<A_SCALE_GCN>(g, s); break;
+    case A_CONCAT_MEAN: launch_gemm<A_CONCAT_MEAN>(g, s); break;
+    default: launch_gemm<A_AXPY>(g, s); break;
     }
     LAUNCH_CHECK();
     return NRT_OK;

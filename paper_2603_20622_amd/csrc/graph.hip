@@ -11,6 +11,7 @@ namespace {
 
 constexpr int RB_THREADS = 1024;   // threads of a list-rebuild workgroup
 constexpr int RB_EPT = 4;
+constexpr int VAL_THREADS = 256;  // threads of an edge-validation workgroup
 
 __device__ inline int32_t new_cap_for(int32_t need) { return need + need / 2 + 4; }
 __device__ inline int32_t initial_cap_for(int32_t deg) { return deg + deg / 8 + 2; }
@@ -74,36 +75,49 @@ __device__ inline uint64_t mix64(uint64_t x) {
     return x;
 }
 
-// wave-cooperative search of `target` in the live part of vertex k's list; returns pool position or -1
-__device__ inline int64_t find_in_list(const Adj& a, int32_t k, int32_t target, int lane) {
+// workgroup-cooperative search of `target` in the live part of vertex k's list; every thread gets the pool
+// position or -1.  The whole list is scanned with independent loads (edges are unique, so at most one hit).
+__device__ inline int64_t find_in_list(const Adj& a, int32_t k, int32_t target, int64_t* s_pos) {
     const int64_t o = a.off[k];
     const int32_t d = a.deg[k];
-    for (int32_t j = 0; j < d; j += 64) {
-        int32_t jj = j + lane;
-        bool hit = jj < d && a.idx[o + jj] == target;
-        unsigned long long m = __ballot(hit);
-        if (m) return o + j + (__ffsll((long long)m) - 1);
+    if (threadIdx.x == 0) *s_pos = -1;
+    __syncthreads();
+    for (int32_t j = threadIdx.x; j < d; j += 4 * VAL_THREADS) {
+        int32_t e[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int32_t jj = j + t * VAL_THREADS;
+            e[t] = jj < d ? a.idx[o + jj] : -2;
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+            if (e[t] == target) *s_pos = o + j + t * VAL_THREADS;
     }
-    return -1;
+    __syncthreads();
+    const int64_t r = *s_pos;
+    __syncthreads();
+    return r;
 }
 
+// One workgroup per updated edge.
 // err: [0] id out of range  [1] self-loop  [2] inserted edge present  [3] deleted edge absent
 //      [4] repeated entry   [5] repeated feature id
-__global__ void validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins, int64_t n_del,
-                                      const int32_t* ins_src, const int32_t* ins_dst, const int32_t* del_src,
-                                      const int32_t* del_dst, uint64_t* hash, int64_t hash_cap, int64_t* pos_out,
-                                      int64_t* pos_in, float* del_w, int32_t* err, int32_t* inscnt0,
-                                      int32_t* inscnt1, int32_t* delcnt0, int32_t* delcnt1) {
-    const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int lane = threadIdx.x & 63;
-    if (op >= n_ins + n_del) return;
+__global__ void __launch_bounds__(VAL_THREADS)
+validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins, int64_t n_del,
+                      const int32_t* ins_src, const int32_t* ins_dst, const int32_t* del_src,
+                      const int32_t* del_dst, uint64_t* hash, int64_t hash_cap, int64_t* pos_out,
+                      int64_t* pos_in, float* del_w, int32_t* err, int32_t* inscnt0,
+                      int32_t* inscnt1, int32_t* delcnt0, int32_t* delcnt1) {
+    __shared__ int64_t s_pos;
+    const int64_t op = blockIdx.x;
+    const bool lead = threadIdx.x == 0;
     const bool is_del = op >= n_ins;
     const int64_t i = is_del ? op - n_ins : op;
     const int32_t u = is_del ? del_src[i] : ins_src[i];
     const int32_t v = is_del ? del_dst[i] : ins_dst[i];
-    if (u < 0 || u >= n || v < 0 || v >= n) { if (lane == 0) err[0] = 1; return; }
-    if (u == v) { if (lane == 0) err[1] = 1; return; }
-    if (lane == 0) {
+    if (u < 0 || u >= n || v < 0 || v >= n) { if (lead) err[0] = 1; return; }
+    if (u == v) { if (lead) err[1] = 1; return; }
+    if (lead) {
         const uint64_t key = (((uint64_t)(uint32_t)u) << 32 | (uint32_t)v) + 1;   // 0 marks an empty cell
         uint64_t h = mix64(key) & (uint64_t)(hash_cap - 1);
         for (int64_t probe = 0; probe < hash_cap; ++probe) {
@@ -114,10 +128,10 @@ __global__ void validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins,
         }
     }
     if (is_del) {
-        int64_t po = find_in_list(out, u, v, lane);
-        int64_t pi = find_in_list(in, v, u, lane);
-        if (po < 0 || pi < 0) { if (lane == 0) err[3] = 1; return; }
-        if (lane == 0) {
+        const int64_t po = find_in_list(out, u, v, &s_pos);
+        const int64_t pi = find_in_list(in, v, u, &s_pos);
+        if (po < 0 || pi < 0) { if (lead) err[3] = 1; return; }
+        if (lead) {
             pos_out[i] = po;
             pos_in[i] = pi;
             if (del_w) del_w[i] = out.wts ? out.wts[po] : 1.0f;
@@ -126,9 +140,9 @@ __global__ void validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins,
         }
     } else {
         const bool use_out = out.deg[u] <= in.deg[v];
-        int64_t p = use_out ? find_in_list(out, u, v, lane) : find_in_list(in, v, u, lane);
-        if (p >= 0) { if (lane == 0) err[2] = 1; return; }
-        if (lane == 0) {
+        const int64_t p = use_out ? find_in_list(out, u, v, &s_pos) : find_in_list(in, v, u, &s_pos);
+        if (p >= 0) { if (lead) err[2] = 1; return; }
+        if (lead) {
             atomicAdd(&inscnt0[u], 1);
             atomicAdd(&inscnt1[v], 1);
         }
@@ -309,7 +323,7 @@ nrt_status graph_layout(Bump& b, nrt_graph* g) {
     const int64_t pool_cap = g->e_capacity + g->e_capacity / 2 + 8 * n + 1024;
     layout_adj(b, g->out, n, pool_cap, g->weighted);
     layout_adj(b, g->in, n, pool_cap, g->weighted);
-    g->scan_tmp_len = cdiv(n, 1024) + 64;
+    g->scan_tmp_len = cdiv(n > g->e_capacity / NRT_CHUNK ? n : g->e_capacity / NRT_CHUNK, 1024) + 64;
     g->scan_tmp = b.take<uint64_t>(g->scan_tmp_len);
     for (int d = 0; d < 2; ++d) {
         g->stamp[d] = b.take<int32_t>(n);
@@ -391,7 +405,7 @@ nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& 
     }
     if (nops == 0) return NRT_OK;
     NRT_TRY(k_fill_u64(sc.hash_keys, sc.hash_cap, 0, s));
-    validate_edges_kernel<<<(int)cdiv(nops * 64, 256), 256, 0, s>>>(
+    validate_edges_kernel<<<(unsigned)nops, VAL_THREADS, 0, s>>>(
         g->out, g->in, g->n, b->n_ins, b->n_del, b->ins_src, b->ins_dst, b->del_src, b->del_dst, sc.hash_keys,
         sc.hash_cap, sc.pos_out, sc.pos_in, sc.del_w, sc.err, g->inscnt[0], g->inscnt[1], g->delcnt[0], g->delcnt[1]);
     LAUNCH_CHECK();

@@ -64,6 +64,18 @@ __global__ void mark_ids_kernel(uint32_t* bitmap, const int32_t* ids, int64_t n)
     }
 }
 
+__global__ void mark_batch_kernel(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1,
+                                  uint32_t* bm_b, const int32_t* b0, int64_t nb0) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t* bm = bm_a;
+    int32_t v;
+    if (i < na0) v = a0[i];
+    else if ((i -= na0) < na1) v = a1[i];
+    else if ((i -= na1) < nb0) { v = b0[i]; bm = bm_b; }
+    else return;
+    atomicOr(&bm[v >> 5], 1u << (v & 31));
+}
+
 // ---- scan ----
 __global__ void scan_reduce_kernel(const uint64_t* data, int64_t n, uint64_t* tmp) {
     const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
@@ -142,6 +154,31 @@ __global__ void bm_emit_kernel(const uint32_t* bm, int64_t nw, const uint64_t* t
     }
 }
 
+// one thread per list entry (launched over the capacity, the count is read on the device):
+// destination record, hub list, in-edge total
+__global__ void dst_records_kernel(const int32_t* list, const uint64_t* count, Adj in, DstRec* recs, HubWork hubs,
+                                   unsigned long long* n_hubs, unsigned long long* inedge_sum) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint64_t d = 0;
+    if (i < (int64_t)*count) {
+        const int32_t v = list[i];
+        DstRec r;
+        r.off = in.off[v];
+        r.deg = in.deg[v];
+        r.v = v;
+        recs[i] = r;
+        d = (uint64_t)r.deg;
+        if (r.deg > NRT_CHUNK) {
+            unsigned long long h = atomicAdd(n_hubs, 1ULL);
+            if ((int64_t)h < hubs.hub_cap) hubs.hub_slot[h] = (int32_t)i;
+        }
+    }
+    // in-edge total (a statistic): spread over 16 cells so the adds of different workgroups do not serialise
+    uint64_t bt;
+    block_excl_scan(d, &bt);
+    if (threadIdx.x == 0 && bt) atomicAdd(inedge_sum + (blockIdx.x & 15), (unsigned long long)bt);
+}
+
 inline int grid_for(int64_t n, int tpb, int64_t cap = 65536) {
     int64_t g = cdiv(n, tpb);
     if (g < 1) g = 1;
@@ -188,6 +225,15 @@ nrt_status k_mark_ids(uint32_t* bitmap, const int32_t* ids, int64_t n, hipStream
     return NRT_OK;
 }
 
+nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
+                        const int32_t* b0, int64_t nb0, hipStream_t s) {
+    const int64_t n = na0 + na1 + nb0;
+    if (n <= 0) return NRT_OK;
+    mark_batch_kernel<<<(int)cdiv(n, 256), 256, 0, s>>>(bm_a, a0, na0, a1, na1, bm_b, b0, nb0);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
 nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_t tmp_len, uint64_t* total, hipStream_t s) {
     const int64_t nb = n > 0 ? cdiv(n, EPB) : 0;
     if (nb > tmp_len) { nrt_set_error("scan scratch too small"); return NRT_ERR_INVALID_ARG; }
@@ -199,7 +245,8 @@ nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_
 }
 
 nrt_status k_compact_bitmap(const uint32_t* bitmap, int64_t n, int32_t* list, int32_t* slot, uint64_t* tmp,
-                            int64_t tmp_len, uint64_t* count, hipStream_t s) {
+                            int64_t tmp_len, uint64_t* count, hipStream_t s, const Adj* in, DstRec* recs,
+                            const HubWork* hubs, int64_t* dev_ctrs) {
     const int64_t nw = cdiv(n, 32);
     const int64_t nb = nw > 0 ? cdiv(nw, EPB) : 0;
     if (nb > tmp_len) { nrt_set_error("scan scratch too small"); return NRT_ERR_INVALID_ARG; }
@@ -207,5 +254,12 @@ nrt_status k_compact_bitmap(const uint32_t* bitmap, int64_t n, int32_t* list, in
     scan_top_kernel<<<1, TPB, 0, s>>>(tmp, nb, count);
     LAUNCH_CHECK();
     if (nb > 0) { bm_emit_kernel<<<(int)nb, TPB, 0, s>>>(bitmap, nw, tmp, list, slot); LAUNCH_CHECK(); }
+    if (recs) {
+        NRT_TRY(k_fill_u64((uint64_t*)(dev_ctrs + CTR_ITEMS), 2 + 16, 0, s));   // CTR_ITEMS, CTR_MULTI, CTR_INEDGES[16]
+        dst_records_kernel<<<(int)cdiv(n, TPB), TPB, 0, s>>>(list, count, *in, recs, *hubs,
+                                                            (unsigned long long*)(dev_ctrs + CTR_MULTI),
+                                                            (unsigned long long*)(dev_ctrs + CTR_INEDGES));
+        LAUNCH_CHECK();
+    }
     return NRT_OK;
 }
