@@ -44,6 +44,11 @@ struct nrt_cache {
     int32_t* indeg_old;
     uint32_t *bm_ddst, *bm_feat, *bm[2];
     int64_t nw_pad;
+    uint8_t* flags;                     // one byte per vertex: the set an expansion hop is building
+    LayerCtrs* lc;                      // device, [NRT_MAX_LAYERS + 1]
+    LayerCtrs* lc_host;                 // pinned mirror
+    int32_t* xhub_list;
+    int64_t xhub_cap;
     int32_t* list[NRT_MAX_LAYERS + 1];
     int64_t n_list[NRT_MAX_LAYERS + 1];
     int32_t* slot[2];
@@ -51,8 +56,6 @@ struct nrt_cache {
     float* mid;
     DstRec* recs;
     HubWork hubs;
-    int64_t* hub_scratch;
-    int64_t hub_cap;
     BatchScratch sc;
     unsigned long long* pair_ctr;
     // profiling
@@ -267,8 +270,10 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->hubs.item_hub = b.take<int32_t>(c->hubs.item_cap);
     c->hubs.item_chunk = b.take<int32_t>(c->hubs.item_cap);
     c->hubs.partial = b.take<float>(c->hubs.item_cap * maxd);
-    c->hub_cap = g->e_capacity / 2048 + 64;
-    c->hub_scratch = b.take<int64_t>(c->hub_cap / 2 + 8);
+    c->xhub_cap = g->e_capacity / 512 + 64;                    // sources with more than 512 live out-edges
+    c->xhub_list = b.take<int32_t>(c->xhub_cap);
+    c->flags = b.take<uint8_t>(n + 64);
+    c->lc = b.take<LayerCtrs>(NRT_MAX_LAYERS + 1);
     c->sc.max_edges = c->max_edges;
     int64_t hc = 16;
     while (hc < 2 * (c->max_edges + 1)) hc <<= 1;
@@ -319,20 +324,15 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
     return NRT_OK;
 }
 
-// gather + fold of layer l over the destinations described by c->recs[0..n_dst) and the hub items built from them
-static nrt_status run_gather(nrt_cache* c, int l, int64_t n_dst, int64_t n_hubs, int64_t n_items, bool incremental,
-                             int prev, hipStream_t s) {
+// gather + fold of layer l over the destinations described by c->recs and the hub items built from them;
+// all sizes are read on the device from c->lc[l]
+static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hipStream_t s) {
     nrt_graph* g = c->g;
-    if (n_hubs > c->hubs.hub_cap || n_items > c->hubs.item_cap) {
-        nrt_set_error("internal: hub buffers too small (%lld hubs, %lld items)", (long long)n_hubs, (long long)n_items);
-        return NRT_ERR_STATE;
-    }
     GatherArgs a;
     memset(&a, 0, sizeof(a));
     a.recs = c->recs;
-    a.n_dst = n_dst;
     a.hubs = c->hubs;
-    a.dev_ctrs = g->dev_ctrs;
+    a.lc = &c->lc[l];
     a.in = g->in;
     a.D = c->dagg[l];
     a.use_weights = (c->kind == NRT_GIN && g->weighted) ? 1 : 0;
@@ -342,32 +342,32 @@ static nrt_status run_gather(nrt_cache* c, int l, int64_t n_dst, int64_t n_hubs,
         a.P = c->DP[prev];
         a.src_bitmap = c->bm[prev];
         a.src_slot = c->slot[prev];
+        a.n_src_dev = &c->lc[l - 1].count;
         a.src_scale_gcn = 0;
         a.accumulate = 1;
-        if (c->profiling) {
-            a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
-            NRT_TRY(k_fill_u64((uint64_t*)a.pair_ctr, 1024, 0, s));
-        }
+        if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     } else {
         a.P = c->H[l - 1];
         a.src_scale_gcn = c->kind == NRT_GCN;
         a.accumulate = 0;
     }
     NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
-    NRT_TRY(k_gather(a, n_items, s));
+    NRT_TRY(k_gather(a, s));
     NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
-    NRT_TRY(k_combine_partials(a, n_hubs, s));
+    NRT_TRY(k_combine_partials(a, s));
     NRT_TRY(prof_mark(c, TAG_COMBINE, l, s));
     return NRT_OK;
 }
 
-static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M, bool incremental, int cur,
-                             float* out_rows, hipStream_t s) {
+// dense update of layer l on the rows listed in `rows` (null: all n rows); M_dev: their number on the device
+static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M, const uint64_t* M_dev,
+                             bool incremental, int cur, float* out_rows, int64_t out_cap, hipStream_t s) {
     nrt_graph* g = c->g;
     const bool last = l == c->L;
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.M = M;
+    a.M_dev = M_dev;
     a.rows = rows;
     a.indeg = g->in.deg;
     a.indeg_old = c->indeg_old;
@@ -392,6 +392,7 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.DP = dp;
         a.dp_scale_gcn = c->kind == NRT_GCN;
         a.out_compact = last ? out_rows : nullptr;
+        a.out_cap = out_cap;
         NRT_TRY(k_gemm(a, s));
     } else {   // GIN: two chained products
         a.a_mode = A_AXPY;
@@ -403,10 +404,12 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.bias = c->bias[l - 1][0];
         a.act = 1;
         a.out_compact = c->mid;
+        a.out_cap = g->n;
         NRT_TRY(k_gemm(a, s));
         GemmArgs b2;
         memset(&b2, 0, sizeof(b2));
         b2.M = M;
+        b2.M_dev = M_dev;
         b2.rows = rows;
         b2.a_is_compact = 1;
         b2.a_mode = A_PLAIN;
@@ -420,6 +423,7 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         b2.H = c->H[l];
         b2.DP = dp;
         b2.out_compact = last ? out_rows : nullptr;
+        b2.out_cap = out_cap;
         NRT_TRY(k_gemm(b2, s));
     }
     return NRT_OK;
@@ -446,11 +450,17 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     cache_fill(c, g, d, max_batch_edges, max_batch_feats);
     Bump b{static_cast<char*>(workspace), 0};
     cache_layout(b, c);
+    if (hipHostMalloc((void**)&c->lc_host, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs), hipHostMallocDefault) != hipSuccess) {
+        delete c;
+        nrt_set_error("pinned host allocation failed");
+        return NRT_ERR_OOM;
+    }
     const int64_t n = g->n;
-    nrt_status st = NRT_OK;
     auto run = [&]() -> nrt_status {
         NRT_TRY(k_copy_f32(c->H[0], features, n * c->dims[0], s));
         NRT_TRY(k_fill_u32((uint32_t*)c->sc.feat_stamp, n, 0, s));
+        NRT_TRY(k_fill_u32((uint32_t*)c->flags, (n + 64) / 4, 0, s));
+        NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs) / 8, 0, s));
         for (int l = 0; l < c->L; ++l) {
             const int kin = (c->kind == NRT_SAGE_MEAN ? 2 : 1) * c->dims[l];
             NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
@@ -462,19 +472,19 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
                 else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][1], c->dims[l + 1], 0, s));
             }
         }
-        NRT_TRY(k_all_records(g->in, n, c->recs, c->hubs, g->dev_ctrs, s));
-        NRT_TRY(k_build_hub_items(c->recs, c->hubs, g->scan_tmp, g->scan_tmp_len, g->dev_ctrs, s));
-        NRT_TRY(read_ctrs(g, s));
-        const int64_t n_hubs = g->host_pinned[CTR_MULTI], n_items = g->host_pinned[CTR_ITEMS];
+        // every vertex is a destination: records and hub items once (kept in lc[1]), then layer by layer
+        NRT_TRY(k_dst_records(nullptr, n, g->in, c->recs, c->hubs, &c->lc[1], true, s));
+        NRT_TRY(k_fill_u64(&c->lc[1].count, 1, (uint64_t)n, s));
         for (int l = 1; l <= c->L; ++l) {
-            NRT_TRY(run_gather(c, l, n, n_hubs, n_items, false, 0, s));
-            NRT_TRY(run_update(c, l, nullptr, n, false, 0, nullptr, s));
+            if (l > 1) HIP_TRY(hipMemcpyAsync(&c->lc[l], &c->lc[1], sizeof(LayerCtrs), hipMemcpyDeviceToDevice, s));
+            NRT_TRY(run_gather(c, l, false, 0, s));
+            NRT_TRY(run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, s));
         }
         HIP_TRY(hipStreamSynchronize(s));
         return NRT_OK;
     };
-    st = run();
-    if (st != NRT_OK) { delete c; return st; }
+    nrt_status st = run();
+    if (st != NRT_OK) { (void)hipHostFree(c->lc_host); delete c; return st; }
     g->has_cache = true;
     *out = c;
     return NRT_OK;
@@ -484,6 +494,7 @@ extern "C" void nrt_cache_destroy(nrt_cache* c) {
     if (!c) return;
     if (c->events_made)
         for (int i = 0; i < MAX_EVENTS; ++i) (void)hipEventDestroy(c->ev[i]);
+    if (c->lc_host) (void)hipHostFree(c->lc_host);
     if (c->g) c->g->has_cache = false;
     delete c;
 }
@@ -496,7 +507,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     REQUIRE(capacity >= 0 && (capacity == 0 || affected_ids), "affected_ids is null");
     nrt_graph* g = c->g;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const int64_t n = g->n, nw = cdiv(n, 32);
+    const int64_t n = g->n;
     if (b->n_ins + b->n_del > c->max_edges || b->n_feat > c->max_feats) {
         nrt_set_error("batch larger than the bounds given to nrt_cache_init");
         return NRT_ERR_BAD_BATCH;
@@ -516,7 +527,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     for (int l = 0; l <= c->L; ++l) c->n_list[l] = 0;
     NRT_TRY(prof_mark(c, TAG_START, 0, s));
 
-    // ---- validate (no state change yet)
+    // ---- validate (no state change yet); the one synchronisation before the end of the batch
     NRT_TRY(graph_validate_batch(g, b, c->sc, s));
     NRT_TRY(read_ctrs(g, s));
     {
@@ -547,10 +558,12 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         return NRT_OK;
     }
 
-    // ---- sets of the batch
-    NRT_TRY(k_fill_u32(c->bm_ddst, 2 * c->nw_pad, 0, s));     // bm_ddst and bm_feat are adjacent
-    NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
+    // ---- sets of the batch, per-layer counters
     const bool gcn = c->kind == NRT_GCN;
+    NRT_TRY(k_fill_u32(c->bm_ddst, 2 * c->nw_pad, 0, s));     // bm_ddst and bm_feat are adjacent
+    NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs) / 8, 0, s));
+    if (c->profiling) NRT_TRY(k_fill_u64((uint64_t*)c->pair_ctr, 1024 * NRT_MAX_LAYERS, 0, s));
+    NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
     if (gcn) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
 
     // ---- structural terms on the old caches, all layers in one launch
@@ -573,17 +586,16 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     // ---- graph mutation
     NRT_TRY(graph_mutate(g, b, c->sc, s));
 
-    // ---- sources of change for layer 1 and their delta payloads
-    NRT_TRY(k_or_words(c->bm[0], c->bm_feat, gcn ? c->bm_ddst : nullptr, nw, s));
-    NRT_TRY(k_compact_bitmap(c->bm[0], n, c->list[0], c->slot[0], g->scan_tmp, g->scan_tmp_len,
-                             (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
-    NRT_TRY(read_ctrs(g, s));
-    c->n_list[0] = g->host_pinned[CTR_COUNT];
+    // ---- sources of change for layer 1 (replaced features; for GCN also the re-normalised destinations)
+    const int64_t n0_bound = b->n_feat + (gcn ? b->n_ins + b->n_del : 0);
+    NRT_TRY(k_compact(nullptr, c->bm_feat, gcn ? c->bm_ddst : nullptr, c->bm[0], n, c->list[0], c->slot[0], g->scan_tmp,
+                      g->scan_tmp_len, &c->lc[0].count, s));
     {
         DeltaArgs da;
         memset(&da, 0, sizeof(da));
         da.list = c->list[0];
-        da.n = c->n_list[0];
+        da.n_dev = &c->lc[0].count;
+        da.bound = n0_bound;
         da.feat_bitmap = c->bm_feat;
         da.feat_index = c->sc.feat_index;
         da.feat_rows = b->feat_rows;
@@ -595,42 +607,40 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     }
     NRT_TRY(prof_mark(c, TAG_INGEST, 0, s));
 
-    // ---- layers
+    // ---- layers: no host round trip, every size stays on the device
     int prev = 0;
-    const bool want_rows = affected_rows != nullptr;
-    nrt_status copy_out = NRT_OK;
     for (int l = 1; l <= c->L; ++l) {
         const int cur = 1 - prev;
-        nrt_layer_stats* ls = &c->stats.layer[l - 1];
-        ls->n_src = c->n_list[l - 1];
-        NRT_TRY(k_or_words(c->bm[cur], c->bm_ddst, c->bm[prev], nw, s));
-        NRT_TRY(k_expand_frontier(g->out, c->list[l - 1], c->n_list[l - 1], c->bm[cur], c->hub_scratch, c->hub_cap, s));
+        const int64_t src_bound = l == 1 ? n0_bound : n;
+        NRT_TRY(k_expand_frontier(g->out, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->flags, &c->lc[l - 1],
+                                  c->xhub_list, c->xhub_cap, s));
         NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
-        NRT_TRY(k_compact_bitmap(c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp, g->scan_tmp_len,
-                                 (uint64_t*)(g->dev_ctrs + CTR_COUNT), s, &g->in, c->recs, &c->hubs, g->dev_ctrs));
-        NRT_TRY(k_build_hub_items(c->recs, c->hubs, g->scan_tmp, g->scan_tmp_len, g->dev_ctrs, s));
-        NRT_TRY(read_ctrs(g, s));
-        c->n_list[l] = g->host_pinned[CTR_COUNT];
-        ls->n_affected = c->n_list[l];
-        ls->n_items = g->host_pinned[CTR_ITEMS];
-        for (int q = 0; q < 16; ++q) ls->n_in_edges += g->host_pinned[CTR_INEDGES + q];
+        NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
+                          g->scan_tmp_len, &c->lc[l].count, s));
+        NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, s));
         NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
-        if (c->n_list[l - 1] > 0)
-            NRT_TRY(run_gather(c, l, c->n_list[l], g->host_pinned[CTR_MULTI], g->host_pinned[CTR_ITEMS], true, prev, s));
-        float* out_rows = nullptr;
-        if (l == c->L && want_rows) {
-            if (c->n_list[l] <= capacity) out_rows = affected_rows;
-            else copy_out = NRT_ERR_INVALID_ARG;
-        }
-        NRT_TRY(run_update(c, l, c->list[l], c->n_list[l], true, cur, out_rows, s));
+        NRT_TRY(run_gather(c, l, true, prev, s));
+        NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, true, cur, l == c->L ? affected_rows : nullptr,
+                           capacity, s));
         NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
         prev = cur;
     }
-    const int64_t na = c->n_list[c->L];
-    *n_affected = na;
-    if (na <= capacity) NRT_TRY(k_copy_i32(affected_ids, c->list[c->L], na, s));
-    else copy_out = NRT_ERR_INVALID_ARG;
+    NRT_TRY(k_copy_counted_i32(affected_ids, c->list[c->L], &c->lc[c->L].count, capacity, n, s));
+    HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    for (int l = 0; l <= c->L; ++l) c->n_list[l] = (int64_t)c->lc_host[l].count;
+    for (int l = 1; l <= c->L; ++l) {
+        nrt_layer_stats* ls = &c->stats.layer[l - 1];
+        ls->n_src = c->n_list[l - 1];
+        ls->n_affected = c->n_list[l];
+        ls->n_items = (int64_t)c->lc_host[l].n_items;
+        for (int q = 0; q < 16; ++q) ls->n_in_edges += (int64_t)c->lc_host[l].in_edges[q];
+        if ((int64_t)c->lc_host[l].n_hubs > c->hubs.hub_cap || (int64_t)c->lc_host[l].n_items > c->hubs.item_cap ||
+            (int64_t)c->lc_host[l - 1].n_xhubs > c->xhub_cap) {
+            nrt_set_error("internal: hub buffers too small");
+            return NRT_ERR_STATE;
+        }
+    }
     NRT_TRY(prof_collect(c));
     if (c->profiling) {
         static thread_local unsigned long long host_ctr[1024];
@@ -642,8 +652,13 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             c->stats.layer[l - 1].n_pairs = (int64_t)tot;
         }
     }
-    if (copy_out != NRT_OK) nrt_set_error("capacity %lld is smaller than the affected count %lld", (long long)capacity, (long long)na);
-    return copy_out;
+    const int64_t na = c->n_list[c->L];
+    *n_affected = na;
+    if (na > capacity) {
+        nrt_set_error("capacity %lld is smaller than the affected count %lld", (long long)capacity, (long long)na);
+        return NRT_ERR_INVALID_ARG;
+    }
+    return NRT_OK;
 }
 
 // ------------------------------------------------------------------ views, stats

@@ -71,30 +71,41 @@ struct nrt_graph {
     bool has_cache;
 };
 
+// ---------------------------------------------------------------- per-layer device counters
+// Sizes that only the device knows while a batch is in flight.  Kernels read them from here and size their
+// own loops, so the host launches fixed or bounded grids and synchronises once, at the end of the batch.
+struct LayerCtrs {
+    uint64_t count;        // |list| : affected vertices of the layer (layer 0: sources of change of layer 1)
+    uint64_t n_hubs;       // destinations with more than NRT_CHUNK in-edges
+    uint64_t n_items;      // their items of NRT_CHUNK in-list entries
+    uint64_t n_xhubs;      // sources with a long out-list queued by the expansion
+    uint64_t in_edges[16]; // in-edges of the affected vertices (a statistic, spread over cells)
+    uint64_t pad[4];
+};
+
 // ---------------------------------------------------------------- prims.hip
 nrt_status k_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
 nrt_status k_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
 nrt_status k_or_words(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t nwords, hipStream_t s);
 nrt_status k_copy_i32(int32_t* dst, const int32_t* src, int64_t n, hipStream_t s);
 nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
+// dst[0 .. min(*count, cap)) = src[...]
+nrt_status k_copy_counted_i32(int32_t* dst, const int32_t* src, const uint64_t* count, int64_t cap, int64_t bound, hipStream_t s);
 // exclusive scan of n uint64 values in place; writes the total to *total (device)
 nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_t tmp_len, uint64_t* total, hipStream_t s);
-// sorted ids of the set bits of bitmap (n bits) -> list, slot[id] = position, *count (device) = number
-struct DstRec;
-struct HubWork;
-// with in/recs/hubs given, also emits the destination records and appends hubs (CTR_MULTI, CTR_INEDGES)
-nrt_status k_compact_bitmap(const uint32_t* bitmap, int64_t n, int32_t* list, int32_t* slot, uint64_t* tmp,
-                            int64_t tmp_len, uint64_t* count, hipStream_t s, const Adj* in = nullptr,
-                            DstRec* recs = nullptr, const HubWork* hubs = nullptr, int64_t* dev_ctrs = nullptr);
-nrt_status k_mark_ids(uint32_t* bitmap, const int32_t* ids, int64_t n, hipStream_t s);
 // bm_a |= ids of a0 and a1, bm_b |= ids of b0, one launch
 nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
                         const int32_t* b0, int64_t nb0, hipStream_t s);
+// Compaction of a vertex set into a sorted id list.  The set is the union of the byte flags (one byte per vertex,
+// may be null; they are cleared on the way), and up to two bitmaps or_a, or_b (may be null).  Writes the set as
+// bitmap `out_bm`, its sorted ids to `list`, slot[id] = position, *count = size.
+nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm, int64_t n,
+                     int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s);
 
 // ---------------------------------------------------------------- frontier.hip
-// bitmap |= { v : <u,v> in out-lists, u in src_list[0..ns) }
-nrt_status k_expand_frontier(const Adj& out, const int32_t* src_list, int64_t ns, uint32_t* bitmap,
-                             int64_t* hub_scratch, int64_t hub_cap, hipStream_t s);
+// flags[v] = 1 for every out-neighbour v of the sources src_list[0 .. *ns_dev)
+nrt_status k_expand_frontier(const Adj& out, const int32_t* src_list, const uint64_t* ns_dev, int64_t ns_bound,
+                             uint8_t* flags, LayerCtrs* lc, int32_t* xhub_list, int64_t xhub_cap, hipStream_t s);
 
 // ---------------------------------------------------------------- gather.hip
 // What a gather wave needs to know about destination slot s, in one 16-byte load.
@@ -106,22 +117,22 @@ struct __attribute__((aligned(16))) DstRec {
 // Destinations with more than NRT_CHUNK in-edges ("hubs") are cut into items of NRT_CHUNK entries.
 struct HubWork {
     int32_t* hub_slot;     // [hub_cap] destination slots of the hubs (unordered)
-    uint64_t* hub_first;   // [hub_cap] chunk count, then (after the scan) first item of each hub
+    uint64_t* hub_first;   // [hub_cap] first item of each hub
     int32_t* item_hub;     // [item_cap] hub index of an item
     int32_t* item_chunk;   // [item_cap] chunk index inside the hub's in-list
     int64_t hub_cap, item_cap;
     float* partial;        // [item_cap][D] one partial row per item
 };
 struct GatherArgs {
-    const DstRec* recs;        // [n_dst]
-    int64_t n_dst;
+    const DstRec* recs;        // [*count]
     HubWork hubs;
-    const int64_t* dev_ctrs;   // CTR_MULTI = number of hubs, CTR_ITEMS = number of hub items
+    const LayerCtrs* lc;       // count, n_hubs, n_items of the destination layer
     Adj in;
     const float* P;            // source rows of width D
     int D;
     const uint32_t* src_bitmap; // null: every source contributes and row index = vertex id
     const int32_t* src_slot;
+    const uint64_t* n_src_dev; // number of changed sources; the launch does nothing when it is 0 (null: not checked)
     int src_scale_gcn;         // multiply each source row by 1/sqrt(indeg[u]+1) (full forward, GCN)
     int use_weights;           // multiply by the edge weight
     int self_pair;             // GCN: the destination's own row is one more neighbour
@@ -129,13 +140,11 @@ struct GatherArgs {
     float* S;                  // [N][D]
     unsigned long long* pair_ctr; // null or 1024 counters
 };
-// records + hub list for all n vertices (full forward)
-nrt_status k_all_records(const Adj& in, int64_t n, DstRec* recs, const HubWork& hubs, int64_t* dev_ctrs, hipStream_t s);
-// after the hub list is known on the device: chunk counts -> scan -> items; fills CTR_ITEMS
-nrt_status k_build_hub_items(const DstRec* recs, const HubWork& hubs, uint64_t* scan_tmp, int64_t scan_tmp_len,
-                             int64_t* dev_ctrs, hipStream_t s);
-nrt_status k_gather(const GatherArgs& a, int64_t n_items, hipStream_t s);
-nrt_status k_combine_partials(const GatherArgs& a, int64_t n_hubs, hipStream_t s);
+// destination records of list[0 .. *count) (list null: all n vertices), hub list and hub items; fills lc
+nrt_status k_dst_records(const int32_t* list, int64_t bound, const Adj& in, DstRec* recs, const HubWork& hubs,
+                         LayerCtrs* lc, bool all_vertices, hipStream_t s);
+nrt_status k_gather(const GatherArgs& a, hipStream_t s);
+nrt_status k_combine_partials(const GatherArgs& a, hipStream_t s);
 
 struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update caches
     int64_t n_ins, n_del;
@@ -150,7 +159,7 @@ struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update 
 nrt_status k_structural_fold(const FoldArgs& a, hipStream_t s);
 
 struct DeltaArgs {  // layer-0 delta payloads and feature scatter
-    const int32_t* list; int64_t n;
+    const int32_t* list; const uint64_t* n_dev; int64_t bound;
     const uint32_t* feat_bitmap; const int32_t* feat_index; const float* feat_rows;
     float* H0; float* DP; int D;
     const int32_t* indeg_new; const int32_t* indeg_old;   // GCN payload scale, else null
@@ -160,7 +169,9 @@ nrt_status k_layer0_delta(const DeltaArgs& a, hipStream_t s);
 // ---------------------------------------------------------------- gemm.hip
 enum { A_PLAIN = 0, A_SCALE_GCN = 1, A_CONCAT_MEAN = 2, A_AXPY = 3 };
 struct GemmArgs {
-    int64_t M; int K; int N;        // K = total inner width (CONCAT: 2*K0)
+    int64_t M; int K; int N;        // K = total inner width (CONCAT: 2*K0); M is a bound when M_dev is given
+    const uint64_t* M_dev;          // number of rows on the device, or null
+    int64_t out_cap;                // rows that fit in out_compact
     const int32_t* rows;            // null: row m is vertex m
     int a_is_compact;               // A rows are already compact (row m), rows[] only addresses the write-back
     int a_mode;

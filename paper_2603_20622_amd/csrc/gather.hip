@@ -34,46 +34,88 @@ __device__ inline float4 f4_shfl_xor(float4 a, int m) {
 __device__ inline float gcn_scale(int32_t indeg) { return 1.0f / sqrtf((float)(indeg + 1)); }
 
 // ------------------------------------------------------------------ records and hub items
-__global__ void all_records_kernel(Adj in, int64_t n, DstRec* recs, HubWork hubs, unsigned long long* n_hubs) {
-    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v >= n) return;
-    DstRec r;
-    r.off = in.off[v];
-    r.deg = in.deg[v];
-    r.v = (int32_t)v;
-    recs[v] = r;
-    if (r.deg > NRT_CHUNK) {
-        unsigned long long h = atomicAdd(n_hubs, 1ULL);
-        if ((int64_t)h < hubs.hub_cap) hubs.hub_slot[h] = (int32_t)v;
+// One thread per destination slot (strided over a fixed grid; the count lives on the device): its record,
+// and for a hub its entry in the hub list and its run of items.  Hub and item numbers are handed out with one
+// atomic per workgroup (a block-wide prefix sum inside), not one per hub.
+constexpr int REC_THREADS = 256;
+
+__device__ inline uint64_t rec_block_scan(uint64_t v, uint64_t* total, uint64_t* wsum) {
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint64_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint64_t o = __shfl_up((unsigned long long)inc, d, 64);
+        if (lane >= d) inc += o;
     }
+    if (lane == 63) wsum[w] = inc;
+    __syncthreads();
+    uint64_t base = 0, tot = 0;
+#pragma unroll
+    for (int i = 0; i < REC_THREADS / 64; ++i) {
+        const uint64_t t = wsum[i];
+        if (i < w) base += t;
+        tot += t;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
 }
-// launched over the whole hub capacity: entries past the hub count scan as zero
-__global__ void hub_count_kernel(const DstRec* recs, HubWork hubs, const unsigned long long* n_hubs) {
-    const int64_t h = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (h >= hubs.hub_cap) return;
-    uint64_t c = 0;
-    if (h < (int64_t)*n_hubs) c = (uint64_t)((recs[hubs.hub_slot[h]].deg + NRT_CHUNK - 1) / NRT_CHUNK);
-    hubs.hub_first[h] = c;
-}
-// one wave per hub writes that hub's items
-__global__ void hub_fill_kernel(const DstRec* recs, HubWork hubs, const unsigned long long* n_hubs) {
-    const int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int lane = threadIdx.x & 63;
-    if (h >= hubs.hub_cap || h >= (int64_t)*n_hubs) return;
-    const int32_t nch = (recs[hubs.hub_slot[h]].deg + NRT_CHUNK - 1) / NRT_CHUNK;
-    const int64_t first = (int64_t)hubs.hub_first[h];
-    for (int32_t c = lane; c < nch; c += 64) {
-        if (first + c < hubs.item_cap) {
-            hubs.item_hub[first + c] = (int32_t)h;
-            hubs.item_chunk[first + c] = c;
+
+__global__ void __launch_bounds__(REC_THREADS)
+dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, HubWork hubs, LayerCtrs* lc) {
+    __shared__ uint64_t wsum[REC_THREADS / 64];
+    __shared__ unsigned long long s_hbase, s_ibase;
+    const int64_t count = list ? (int64_t)lc->count : n_all;
+    const int64_t stride = (int64_t)gridDim.x * REC_THREADS;
+    uint64_t degsum = 0;
+    for (int64_t i0 = (int64_t)blockIdx.x * REC_THREADS; i0 < count; i0 += stride) {   // workgroup-uniform trip count
+        const int64_t i = i0 + threadIdx.x;
+        uint64_t nch = 0;
+        DstRec r;
+        r.off = 0; r.deg = 0; r.v = 0;
+        if (i < count) {
+            const int32_t v = list ? list[i] : (int32_t)i;
+            r.off = in.off[v];
+            r.deg = in.deg[v];
+            r.v = v;
+            recs[i] = r;
+            degsum += (uint64_t)r.deg;
+            if (r.deg > NRT_CHUNK) nch = (uint64_t)((r.deg + NRT_CHUNK - 1) / NRT_CHUNK);
         }
+        // pack (hub flag, item count) into one scan: high 32 bits hubs, low 32 bits items
+        uint64_t tot;
+        const uint64_t ex = rec_block_scan(nch ? ((1ULL << 32) | nch) : 0ULL, &tot, wsum);
+        if (threadIdx.x == 0 && tot) {
+            s_hbase = atomicAdd((unsigned long long*)&lc->n_hubs, (unsigned long long)(tot >> 32));
+            s_ibase = atomicAdd((unsigned long long*)&lc->n_items, (unsigned long long)(tot & 0xffffffffu));
+        }
+        __syncthreads();
+        if (nch) {
+            const int64_t h = (int64_t)(s_hbase + (ex >> 32));
+            const int64_t first = (int64_t)(s_ibase + (ex & 0xffffffffu));
+            if (h < hubs.hub_cap) {
+                hubs.hub_slot[h] = (int32_t)i;
+                hubs.hub_first[h] = (uint64_t)first;
+                for (int64_t c = 0; c < (int64_t)nch; ++c) {
+                    if (first + c < hubs.item_cap) {
+                        hubs.item_hub[first + c] = (int32_t)h;
+                        hubs.item_chunk[first + c] = (int32_t)c;
+                    }
+                }
+            }
+        }
+        __syncthreads();
     }
+    uint64_t bt;
+    rec_block_scan(degsum, &bt, wsum);
+    if (threadIdx.x == 0 && bt) atomicAdd((unsigned long long*)&lc->in_edges[blockIdx.x & 15], (unsigned long long)bt);
 }
 
 // ------------------------------------------------------------------ gather
-// Work units: [0, n_dst) are the destinations themselves (those with at most NRT_CHUNK in-edges are served
-// here, hubs are skipped); [n_dst, n_dst + n_items) are the hub items, NRT_CHUNK in-list entries each, whose
-// partial row goes to partial[item].  A wave owns `upw` consecutive units and walks them as a sequence of
+// Work units: [0, n_items) are the hub items, NRT_CHUNK in-list entries each, whose partial row goes to
+// partial[item] (heavy units first, so they start early); [n_items, n_items + n_dst) are the destinations
+// themselves (those with at most NRT_CHUNK in-edges are served here, hubs are skipped).  All sizes are read on
+// the device; a fixed grid strides over chunks of `upw` consecutive units.  A wave owns one chunk at a time and walks them as a sequence of
 // steps of 64 in-list entries (one per lane) through a four-stage software pipeline, so that the four
 // dependent memory accesses of a step (in-list entry -> bitmap word of changed sources -> slot of the
 // source's delta row -> the row itself) overlap with the accesses of the neighbouring steps instead of
@@ -95,17 +137,24 @@ struct StepMeta {
 };
 
 template <int LPR, int NV, bool FILTER, bool COEF>
-__global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs a, int upw) {
+__global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs a) {
     constexpr int RPI = 64 / LPR;
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int sub = lane / LPR, gl = lane % LPR;
     const int D = a.D;
-    int64_t n_items = a.dev_ctrs[CTR_ITEMS];
+    if (a.n_src_dev && *a.n_src_dev == 0) return;          // nothing changed upstream of this layer
+    const int64_t n_dst = (int64_t)a.lc->count;
+    int64_t n_items = (int64_t)a.lc->n_items;
     if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
-    const int64_t total = a.n_dst + n_items;
-    const int64_t unit0 = ((int64_t)blockIdx.x * WAVES_PER_BLOCK + w) * upw;
-    if (unit0 >= total) return;
+    const int64_t total = n_dst + n_items;
+    int upw = (int)(total / 16384);                        // units per wave: keep ~16k waves when there is enough work
+    upw = upw < 1 ? 1 : (upw > 8 ? 8 : upw);
+    const int64_t n_chunks = (total + upw - 1) / upw;
+    const int64_t n_waves = (int64_t)gridDim.x * WAVES_PER_BLOCK;
+    long long pairs = 0;
+  for (int64_t chunk_id = (int64_t)blockIdx.x * WAVES_PER_BLOCK + w; chunk_id < n_chunks; chunk_id += n_waves) {
+    const int64_t unit0 = chunk_id * upw;
     const int nu = (int)min((int64_t)upw, total - unit0);
 
     // lane i holds the description of unit i of this wave
@@ -114,12 +163,12 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
     if (lane < nu) {
         const int64_t unit = unit0 + lane;
         DstRec rec;
-        if (unit < a.n_dst) {
-            rec = a.recs[unit];
+        if (unit >= n_items) {                     // hub items come first: the heavy units start early
+            rec = a.recs[unit - n_items];
             m_cnt = rec.deg > NRT_CHUNK ? -1 : rec.deg;
             m_out = (int64_t)rec.v * D;
         } else {
-            const int64_t item = unit - a.n_dst;
+            const int64_t item = unit;
             m_chunk = a.hubs.item_chunk[item];
             rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[item]]];
             m_cnt = min(NRT_CHUNK, rec.deg - m_chunk * NRT_CHUNK);
@@ -169,7 +218,6 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
 #pragma unroll
     for (int q = 0; q < NV; ++q) { acc[q] = make_float4(0.f, 0.f, 0.f, 0.f); oldD[q] = acc[q]; }
     const float* Pl = a.P + gl * 4;
-    long long pairs = 0;
 
     auto take = [&](unsigned long long& m, int32_t rv, float cv) {
         int32_t rr = -1;
@@ -293,33 +341,38 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
         uC = uB; wC = wB; xC = xB;
         uB = uA; wB = wA;
     }
+  }
     if (a.pair_ctr && lane == 0 && pairs) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)pairs);
 }
 
-// one wave per hub: sum its partial rows in item order into the cached aggregate
+// one wave per hub (strided): sum its partial rows in item order into the cached aggregate
 __global__ void combine_kernel(GatherArgs a) {
-    const int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    if (a.n_src_dev && *a.n_src_dev == 0) return;
     const int lane = threadIdx.x & 63;
-    if (h >= a.dev_ctrs[CTR_MULTI] || h >= a.hubs.hub_cap) return;
-    const DstRec rec = a.recs[a.hubs.hub_slot[h]];
-    const int32_t nch = (rec.deg + NRT_CHUNK - 1) / NRT_CHUNK;
-    const int64_t first = (int64_t)a.hubs.hub_first[h];
+    int64_t nh = (int64_t)a.lc->n_hubs;
+    if (nh > a.hubs.hub_cap) nh = a.hubs.hub_cap;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     const int D = a.D;
-    for (int col = lane * 4; col < D; col += 256) {
-        const float* p = a.hubs.partial + first * D + col;
-        float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-        int32_t c = 0;
-        for (; c + 3 < nch; c += 4) {
-            const float4 x0 = *reinterpret_cast<const float4*>(p + (int64_t)c * D);
-            const float4 x1 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 1) * D);
-            const float4 x2 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 2) * D);
-            const float4 x3 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 3) * D);
-            acc = f4_add(acc, x0); acc = f4_add(acc, x1); acc = f4_add(acc, x2); acc = f4_add(acc, x3);
+    for (int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; h < nh; h += waves) {
+        const DstRec rec = a.recs[a.hubs.hub_slot[h]];
+        const int32_t nch = (rec.deg + NRT_CHUNK - 1) / NRT_CHUNK;
+        const int64_t first = (int64_t)a.hubs.hub_first[h];
+        for (int col = lane * 4; col < D; col += 256) {
+            const float* p = a.hubs.partial + first * D + col;
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            int32_t c = 0;
+            for (; c + 3 < nch; c += 4) {
+                const float4 x0 = *reinterpret_cast<const float4*>(p + (int64_t)c * D);
+                const float4 x1 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 1) * D);
+                const float4 x2 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 2) * D);
+                const float4 x3 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 3) * D);
+                acc = f4_add(acc, x0); acc = f4_add(acc, x1); acc = f4_add(acc, x2); acc = f4_add(acc, x3);
+            }
+            for (; c < nch; ++c) acc = f4_add(acc, *reinterpret_cast<const float4*>(p + (int64_t)c * D));
+            float4* dst = reinterpret_cast<float4*>(a.S + (int64_t)rec.v * D + col);
+            if (a.accumulate) acc = f4_add(acc, *dst);
+            *dst = acc;
         }
-        for (; c < nch; ++c) acc = f4_add(acc, *reinterpret_cast<const float4*>(p + (int64_t)c * D));
-        float4* dst = reinterpret_cast<float4*>(a.S + (int64_t)rec.v * D + col);
-        if (a.accumulate) acc = f4_add(acc, *dst);
-        *dst = acc;
     }
 }
 
@@ -349,7 +402,7 @@ __global__ void structural_fold_kernel(FoldArgs a) {
 __global__ void layer0_delta_kernel(DeltaArgs a) {
     const int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
-    if (s >= a.n) return;
+    if (s >= (int64_t)*a.n_dev) return;
     const int32_t v = a.list[s];
     const bool isfeat = (a.feat_bitmap[v >> 5] >> (v & 31)) & 1u;
     float cn = 1.0f, co = 1.0f;
@@ -369,54 +422,40 @@ __global__ void layer0_delta_kernel(DeltaArgs a) {
 
 }  // namespace
 
-nrt_status k_all_records(const Adj& in, int64_t n, DstRec* recs, const HubWork& hubs, int64_t* dev_ctrs, hipStream_t s) {
-    NRT_TRY(k_fill_u64((uint64_t*)(dev_ctrs + CTR_ITEMS), 2 + 16, 0, s));
-    all_records_kernel<<<(int)cdiv(n, 256), 256, 0, s>>>(in, n, recs, hubs, (unsigned long long*)(dev_ctrs + CTR_MULTI));
-    LAUNCH_CHECK();
-    return NRT_OK;
-}
-
-nrt_status k_build_hub_items(const DstRec* recs, const HubWork& hubs, uint64_t* scan_tmp, int64_t scan_tmp_len,
-                             int64_t* dev_ctrs, hipStream_t s) {
-    const unsigned long long* nh = (const unsigned long long*)(dev_ctrs + CTR_MULTI);
-    hub_count_kernel<<<(int)cdiv(hubs.hub_cap, 256), 256, 0, s>>>(recs, hubs, nh);
-    LAUNCH_CHECK();
-    NRT_TRY(k_exclusive_scan_u64(hubs.hub_first, hubs.hub_cap, scan_tmp, scan_tmp_len, (uint64_t*)(dev_ctrs + CTR_ITEMS), s));
-    hub_fill_kernel<<<(int)cdiv(hubs.hub_cap * 64, 256), 256, 0, s>>>(recs, hubs, nh);
+nrt_status k_dst_records(const int32_t* list, int64_t bound, const Adj& in, DstRec* recs, const HubWork& hubs,
+                         LayerCtrs* lc, bool all_vertices, hipStream_t s) {
+    if (bound <= 0) return NRT_OK;
+    int64_t g = cdiv(bound, REC_THREADS);
+    if (g > 2048) g = 2048;
+    dst_records_kernel<<<(int)g, REC_THREADS, 0, s>>>(all_vertices ? nullptr : list, bound, in, recs, hubs, lc);
     LAUNCH_CHECK();
     return NRT_OK;
 }
 
 template <int LPR, int NV>
-static void launch_gather(const GatherArgs& a, int64_t units, hipStream_t s) {
-    int upw = (int)(units / 16384);            // keep at least ~16k waves when there is enough work
-    upw = upw < 1 ? 1 : (upw > 8 ? 8 : upw);
-    const int nb = (int)cdiv(cdiv(units, upw), WAVES_PER_BLOCK);
+static void launch_gather(const GatherArgs& a, hipStream_t s) {
+    const int nb = 8192;                        // a fixed grid strides over the work; sizes are read on the device
     const int threads = WAVES_PER_BLOCK * 64;
     const bool filter = a.src_bitmap != nullptr;
     const bool coef = a.use_weights || a.src_scale_gcn;
-    if (filter && coef) gather_kernel<LPR, NV, true, true><<<nb, threads, 0, s>>>(a, upw);
-    else if (filter) gather_kernel<LPR, NV, true, false><<<nb, threads, 0, s>>>(a, upw);
-    else if (coef) gather_kernel<LPR, NV, false, true><<<nb, threads, 0, s>>>(a, upw);
-    else gather_kernel<LPR, NV, false, false><<<nb, threads, 0, s>>>(a, upw);
+    if (filter && coef) gather_kernel<LPR, NV, true, true><<<nb, threads, 0, s>>>(a);
+    else if (filter) gather_kernel<LPR, NV, true, false><<<nb, threads, 0, s>>>(a);
+    else if (coef) gather_kernel<LPR, NV, false, true><<<nb, threads, 0, s>>>(a);
+    else gather_kernel<LPR, NV, false, false><<<nb, threads, 0, s>>>(a);
 }
 
-// destinations [0, n_dst) and hub items [0, n_items) in one launch
-nrt_status k_gather(const GatherArgs& a, int64_t n_items, hipStream_t s) {
-    const int64_t units = a.n_dst + n_items;
-    if (units <= 0) return NRT_OK;
-    if (a.D <= 64) launch_gather<16, 1>(a, units, s);
-    else if (a.D <= 128) launch_gather<32, 1>(a, units, s);
-    else if (a.D <= 256) launch_gather<64, 1>(a, units, s);
-    else if (a.D <= 512) launch_gather<64, 2>(a, units, s);
-    else launch_gather<64, 4>(a, units, s);
+nrt_status k_gather(const GatherArgs& a, hipStream_t s) {
+    if (a.D <= 64) launch_gather<16, 1>(a, s);
+    else if (a.D <= 128) launch_gather<32, 1>(a, s);
+    else if (a.D <= 256) launch_gather<64, 1>(a, s);
+    else if (a.D <= 512) launch_gather<64, 2>(a, s);
+    else launch_gather<64, 4>(a, s);
     LAUNCH_CHECK();
     return NRT_OK;
 }
 
-nrt_status k_combine_partials(const GatherArgs& a, int64_t n_hubs, hipStream_t s) {
-    if (n_hubs <= 0) return NRT_OK;
-    combine_kernel<<<(int)cdiv(n_hubs * 64, 256), 256, 0, s>>>(a);
+nrt_status k_combine_partials(const GatherArgs& a, hipStream_t s) {
+    combine_kernel<<<2048, 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }
@@ -430,8 +469,8 @@ nrt_status k_structural_fold(const FoldArgs& a, hipStream_t s) {
 }
 
 nrt_status k_layer0_delta(const DeltaArgs& a, hipStream_t s) {
-    if (a.n <= 0) return NRT_OK;
-    layer0_delta_kernel<<<(int)cdiv(a.n * 64, 256), 256, 0, s>>>(a);
+    if (a.bound <= 0) return NRT_OK;
+    layer0_delta_kernel<<<(int)cdiv(a.bound * 64, 256), 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }

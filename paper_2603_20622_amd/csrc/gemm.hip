@@ -67,8 +67,9 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t row_base = (int64_t)blockIdx.x * BM;
     const int col_base = blockIdx.y * BN;
+    const int64_t M = g.M_dev ? (int64_t)*g.M_dev : g.M;      // rows known only on the device: stride over the tiles
+  for (int64_t row_base = (int64_t)blockIdx.x * BM; row_base < M; row_base += (int64_t)gridDim.x * BM) {
 
     // rows this thread stages
     const int lr = tid / TPR, lk = (tid % TPR) * 4;
@@ -78,7 +79,7 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
 #pragma unroll
     for (int p = 0; p < A_LOADS; ++p) {
         const int64_t m = row_base + lr + RPP * p;
-        aok[p] = m < g.M;
+        aok[p] = m < M;
         av[p] = aok[p] ? ((g.rows && !g.a_is_compact) ? (int64_t)g.rows[m] : m) : 0;
         asc[p] = 1.0f;
         if (aok[p] && AMODE == A_SCALE_GCN) asc[p] = gcn_scale(g.indeg[av[p]]);
@@ -163,7 +164,7 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = rb + rr;
                 mrow[rr] = row_base + (wm * TM + i) * 32 + 8 * (r / 4) + 4 * half + (r % 4);
-                const bool ok = mrow[rr] < g.M;
+                const bool ok = mrow[rr] < M;
                 vrow[rr] = ok ? (g.rows ? (int64_t)g.rows[mrow[rr]] : mrow[rr]) : 0;
                 cn[rr] = 1.0f; co[rr] = 1.0f;
                 if (ok && g.DP && g.dp_scale_gcn) { cn[rr] = gcn_scale(g.indeg[vrow[rr]]); co[rr] = gcn_scale(g.indeg_old[vrow[rr]]); }
@@ -176,7 +177,7 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
             }
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
-                if (mrow[rr] >= g.M) continue;
+                if (mrow[rr] >= M) continue;
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int n = col_base + (wn * TN + j) * 32 + l32;
@@ -184,7 +185,7 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
                     float y = acc[i][j][rb + rr] + bias[j];
                     if (g.act == 1) y = fmaxf(y, 0.f);
                     else if (g.act == 2) y = y > 0.f ? y : expm1f(y);
-                    if (g.out_compact) g.out_compact[mrow[rr] * g.N + n] = y;
+                    if (g.out_compact && mrow[rr] < g.out_cap) g.out_compact[mrow[rr] * g.N + n] = y;
                     if (g.H) {
                         if (g.DP) g.DP[mrow[rr] * g.N + n] = y * cn[rr] - oldv[rr][j] * co[rr];
                         g.H[vrow[rr] * g.N + n] = y;
@@ -193,6 +194,7 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
             }
         }
     }
+  }
 }
 
 __global__ void transpose_kernel(const float* W, float* Wt, int K, int N) {
@@ -207,7 +209,9 @@ __global__ void transpose_kernel(const float* W, float* Wt, int K, int N) {
 
 template <int AMODE>
 static void launch_gemm(const GemmArgs& g, hipStream_t s) {
-    const unsigned gx = (unsigned)cdiv(g.M, BM);
+    int64_t tiles = cdiv(g.M, BM);
+    if (g.M_dev && tiles > 2048) tiles = 2048;               // device-sized problem: a fixed grid strides over the tiles
+    const unsigned gx = (unsigned)tiles;
     if (g.N > 128) gemm_kernel<256, 2, 2, AMODE, 32><<<dim3(gx, (unsigned)cdiv(g.N, 256)), 256, 0, s>>>(g);
     else if (g.N > 64) gemm_kernel<128, 2, 2, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
     else if (g.N > 32) gemm_kernel<64, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);

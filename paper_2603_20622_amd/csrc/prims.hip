@@ -56,13 +56,6 @@ __global__ void copy_u32_kernel(uint32_t* dst, const uint32_t* src, int64_t n) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) dst[i] = src[i];
 }
-__global__ void mark_ids_kernel(uint32_t* bitmap, const int32_t* ids, int64_t n) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) {
-        int32_t v = ids[i];
-        atomicOr(&bitmap[v >> 5], 1u << (v & 31));
-    }
-}
 
 __global__ void mark_batch_kernel(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1,
                                   uint32_t* bm_b, const int32_t* b0, int64_t nb0) {
@@ -118,13 +111,45 @@ __global__ void scan_apply_kernel(uint64_t* data, int64_t n, const uint64_t* tmp
     }
 }
 
-// ---- bitmap compaction ----
-__global__ void bm_count_kernel(const uint32_t* bm, int64_t nw, uint64_t* tmp) {
+// ---- set compaction ----
+// word w of the set = (byte flags 32w .. 32w+31 packed) | or_a[w] | or_b[w]; the flags are cleared on the way
+__device__ inline uint32_t pack_flags(uint8_t* flags, int64_t w, int64_t n) {
+    uint32_t bits = 0;
+    const int64_t v0 = w * 32;
+    if (v0 + 32 <= n) {
+        uint4* p = reinterpret_cast<uint4*>(flags + v0);
+        const uint4 a = p[0], b = p[1];
+        const uint32_t q[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+        uint32_t any = 0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            any |= q[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bits |= ((q[i] >> (8 * j)) & 0xffu ? 1u : 0u) << (4 * i + j);
+        }
+        if (any) { p[0] = make_uint4(0, 0, 0, 0); p[1] = make_uint4(0, 0, 0, 0); }
+    } else {
+        for (int64_t v = v0; v < n; ++v) {
+            if (flags[v]) { bits |= 1u << (v - v0); flags[v] = 0; }
+        }
+    }
+    return bits;
+}
+__global__ void set_count_kernel(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm,
+                                 int64_t n, int64_t nw, uint64_t* tmp) {
     const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
     uint64_t s = 0;
 #pragma unroll
-    for (int j = 0; j < EPT; ++j)
-        if (base + j < nw) s += __popc(bm[base + j]);
+    for (int j = 0; j < EPT; ++j) {
+        const int64_t w = base + j;
+        if (w < nw) {
+            uint32_t bits = flags ? pack_flags(flags, w, n) : 0u;
+            if (or_a) bits |= or_a[w];
+            if (or_b) bits |= or_b[w];
+            out_bm[w] = bits;
+            s += __popc(bits);
+        }
+    }
     uint64_t tot;
     block_excl_scan(s, &tot);
     if (threadIdx.x == 0) tmp[blockIdx.x] = tot;
@@ -153,30 +178,12 @@ __global__ void bm_emit_kernel(const uint32_t* bm, int64_t nw, const uint64_t* t
         }
     }
 }
-
-// one thread per list entry (launched over the capacity, the count is read on the device):
-// destination record, hub list, in-edge total
-__global__ void dst_records_kernel(const int32_t* list, const uint64_t* count, Adj in, DstRec* recs, HubWork hubs,
-                                   unsigned long long* n_hubs, unsigned long long* inedge_sum) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    uint64_t d = 0;
-    if (i < (int64_t)*count) {
-        const int32_t v = list[i];
-        DstRec r;
-        r.off = in.off[v];
-        r.deg = in.deg[v];
-        r.v = v;
-        recs[i] = r;
-        d = (uint64_t)r.deg;
-        if (r.deg > NRT_CHUNK) {
-            unsigned long long h = atomicAdd(n_hubs, 1ULL);
-            if ((int64_t)h < hubs.hub_cap) hubs.hub_slot[h] = (int32_t)i;
-        }
-    }
-    // in-edge total (a statistic): spread over 16 cells so the adds of different workgroups do not serialise
-    uint64_t bt;
-    block_excl_scan(d, &bt);
-    if (threadIdx.x == 0 && bt) atomicAdd(inedge_sum + (blockIdx.x & 15), (unsigned long long)bt);
+__global__ void copy_counted_kernel(uint32_t* dst, const uint32_t* src, const uint64_t* count, int64_t cap) {
+    int64_t n = (int64_t)*count;
+    if (n > cap) n = cap;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = src[i];
 }
 
 inline int grid_for(int64_t n, int tpb, int64_t cap = 65536) {
@@ -218,12 +225,6 @@ nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s) {
     LAUNCH_CHECK();
     return NRT_OK;
 }
-nrt_status k_mark_ids(uint32_t* bitmap, const int32_t* ids, int64_t n, hipStream_t s) {
-    if (n <= 0) return NRT_OK;
-    mark_ids_kernel<<<(int)cdiv(n, 256), 256, 0, s>>>(bitmap, ids, n);
-    LAUNCH_CHECK();
-    return NRT_OK;
-}
 
 nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
                         const int32_t* b0, int64_t nb0, hipStream_t s) {
@@ -244,22 +245,21 @@ nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_
     return NRT_OK;
 }
 
-nrt_status k_compact_bitmap(const uint32_t* bitmap, int64_t n, int32_t* list, int32_t* slot, uint64_t* tmp,
-                            int64_t tmp_len, uint64_t* count, hipStream_t s, const Adj* in, DstRec* recs,
-                            const HubWork* hubs, int64_t* dev_ctrs) {
+nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm, int64_t n,
+                     int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s) {
     const int64_t nw = cdiv(n, 32);
     const int64_t nb = nw > 0 ? cdiv(nw, EPB) : 0;
     if (nb > tmp_len) { nrt_set_error("scan scratch too small"); return NRT_ERR_INVALID_ARG; }
-    if (nb > 0) { bm_count_kernel<<<(int)nb, TPB, 0, s>>>(bitmap, nw, tmp); LAUNCH_CHECK(); }
+    if (nb > 0) { set_count_kernel<<<(int)nb, TPB, 0, s>>>(flags, or_a, or_b, out_bm, n, nw, tmp); LAUNCH_CHECK(); }
     scan_top_kernel<<<1, TPB, 0, s>>>(tmp, nb, count);
     LAUNCH_CHECK();
-    if (nb > 0) { bm_emit_kernel<<<(int)nb, TPB, 0, s>>>(bitmap, nw, tmp, list, slot); LAUNCH_CHECK(); }
-    if (recs) {
-        NRT_TRY(k_fill_u64((uint64_t*)(dev_ctrs + CTR_ITEMS), 2 + 16, 0, s));   // CTR_ITEMS, CTR_MULTI, CTR_INEDGES[16]
-        dst_records_kernel<<<(int)cdiv(n, TPB), TPB, 0, s>>>(list, count, *in, recs, *hubs,
-                                                            (unsigned long long*)(dev_ctrs + CTR_MULTI),
-                                                            (unsigned long long*)(dev_ctrs + CTR_INEDGES));
-        LAUNCH_CHECK();
-    }
+    if (nb > 0) { bm_emit_kernel<<<(int)nb, TPB, 0, s>>>(out_bm, nw, tmp, list, slot); LAUNCH_CHECK(); }
+    return NRT_OK;
+}
+
+nrt_status k_copy_counted_i32(int32_t* dst, const int32_t* src, const uint64_t* count, int64_t cap, int64_t bound, hipStream_t s) {
+    if (cap <= 0 || bound <= 0) return NRT_OK;
+    copy_counted_kernel<<<grid_for(bound < cap ? bound : cap, 256, 2048), 256, 0, s>>>((uint32_t*)dst, (const uint32_t*)src, count, cap);
+    LAUNCH_CHECK();
     return NRT_OK;
 }
