@@ -37,7 +37,8 @@ __device__ inline float gcn_scale(int32_t indeg) { return 1.0f / sqrtf((float)(i
 // One thread per destination slot (strided over a fixed grid; the count lives on the device): its record,
 // and for a hub its entry in the hub list and its run of items.  Hub and item numbers are handed out with one
 // atomic per workgroup (a block-wide prefix sum inside), not one per hub.
-constexpr int REC_THREADS = 256;
+constexpr int REC_THREADS = 1024;
+constexpr int REC_EPT = 4;          // slots per thread per round: few, large workgroups keep the shared atomics rare
 
 __device__ inline uint64_t rec_block_scan(uint64_t v, uint64_t* total, uint64_t* wsum) {
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -66,37 +67,53 @@ dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, Hub
     __shared__ uint64_t wsum[REC_THREADS / 64];
     __shared__ unsigned long long s_hbase, s_ibase;
     const int64_t count = list ? (int64_t)lc->count : n_all;
-    const int64_t stride = (int64_t)gridDim.x * REC_THREADS;
+    const int64_t per_round = (int64_t)REC_THREADS * REC_EPT;
+    const int64_t stride = (int64_t)gridDim.x * per_round;
     uint64_t degsum = 0;
-    for (int64_t i0 = (int64_t)blockIdx.x * REC_THREADS; i0 < count; i0 += stride) {   // workgroup-uniform trip count
-        const int64_t i = i0 + threadIdx.x;
-        uint64_t nch = 0;
-        DstRec r;
-        r.off = 0; r.deg = 0; r.v = 0;
-        if (i < count) {
-            const int32_t v = list ? list[i] : (int32_t)i;
-            r.off = in.off[v];
-            r.deg = in.deg[v];
-            r.v = v;
-            recs[i] = r;
-            degsum += (uint64_t)r.deg;
-            if (r.deg > NRT_CHUNK) nch = (uint64_t)((r.deg + NRT_CHUNK - 1) / NRT_CHUNK);
+    for (int64_t i0 = (int64_t)blockIdx.x * per_round; i0 < count; i0 += stride) {   // workgroup-uniform trip count
+        DstRec r[REC_EPT];
+        uint64_t nch[REC_EPT];
+        uint64_t mine = 0;
+#pragma unroll
+        for (int e = 0; e < REC_EPT; ++e) {
+            const int64_t i = i0 + (int64_t)e * REC_THREADS + threadIdx.x;
+            nch[e] = 0;
+            r[e].off = 0; r[e].deg = 0; r[e].v = 0;
+            if (i < count) {
+                const int32_t v = list ? list[i] : (int32_t)i;
+                r[e].off = in.off[v];
+                r[e].deg = in.deg[v];
+                r[e].v = v;
+            }
         }
-        // pack (hub flag, item count) into one scan: high 32 bits hubs, low 32 bits items
+#pragma unroll
+        for (int e = 0; e < REC_EPT; ++e) {
+            const int64_t i = i0 + (int64_t)e * REC_THREADS + threadIdx.x;
+            if (i < count) {
+                recs[i] = r[e];
+                degsum += (uint64_t)r[e].deg;
+                if (r[e].deg > NRT_CHUNK) nch[e] = (uint64_t)((r[e].deg + NRT_CHUNK - 1) / NRT_CHUNK);
+                mine += nch[e] ? ((1ULL << 32) | nch[e]) : 0ULL;     // high 32 bits: hubs, low 32 bits: items
+            }
+        }
         uint64_t tot;
-        const uint64_t ex = rec_block_scan(nch ? ((1ULL << 32) | nch) : 0ULL, &tot, wsum);
+        uint64_t ex = rec_block_scan(mine, &tot, wsum);
         if (threadIdx.x == 0 && tot) {
             s_hbase = atomicAdd((unsigned long long*)&lc->n_hubs, (unsigned long long)(tot >> 32));
             s_ibase = atomicAdd((unsigned long long*)&lc->n_items, (unsigned long long)(tot & 0xffffffffu));
         }
         __syncthreads();
-        if (nch) {
+#pragma unroll
+        for (int e = 0; e < REC_EPT; ++e) {
+            if (!nch[e]) continue;
+            const int64_t i = i0 + (int64_t)e * REC_THREADS + threadIdx.x;
             const int64_t h = (int64_t)(s_hbase + (ex >> 32));
             const int64_t first = (int64_t)(s_ibase + (ex & 0xffffffffu));
+            ex += (1ULL << 32) | nch[e];
             if (h < hubs.hub_cap) {
                 hubs.hub_slot[h] = (int32_t)i;
                 hubs.hub_first[h] = (uint64_t)first;
-                for (int64_t c = 0; c < (int64_t)nch; ++c) {
+                for (int64_t c = 0; c < (int64_t)nch[e]; ++c) {
                     if (first + c < hubs.item_cap) {
                         hubs.item_hub[first + c] = (int32_t)h;
                         hubs.item_chunk[first + c] = (int32_t)c;
@@ -128,17 +145,13 @@ dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, Hub
 //      with a lane read, so the row address is wave-uniform and the row load is one coalesced instruction
 //      (rows narrower than 256 floats put RPI = 2 or 4 survivors into one load, one per LPR-lane sub-group);
 //      on the last step of a unit reduce the sub-groups and write the row.
-struct StepMeta {
-    int valid;     // 0: pipeline bubble
-    int ui;        // unit index inside the wave
-    int j;         // first in-list entry of the step inside the unit
-    int n;         // entries in the step
-    int first, last;
-};
+// Step flags kept in the per-wave step table.
+enum { SF_FIRST = 1, SF_LAST = 2, SF_PART = 4, SF_SELF = 8 };
 
 template <int LPR, int NV, bool FILTER, bool COEF>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs a) {
     constexpr int RPI = 64 / LPR;
+    constexpr int MAX_UPW = 8;                       // units per wave; 8 units * 4 steps fit the 64-lane step table
     const int lane = threadIdx.x & 63;
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int sub = lane / LPR, gl = lane % LPR;
@@ -149,75 +162,11 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
     if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
     const int64_t total = n_dst + n_items;
     int upw = (int)(total / 16384);                        // units per wave: keep ~16k waves when there is enough work
-    upw = upw < 1 ? 1 : (upw > 8 ? 8 : upw);
+    upw = upw < 1 ? 1 : (upw > MAX_UPW ? MAX_UPW : upw);
     const int64_t n_chunks = (total + upw - 1) / upw;
     const int64_t n_waves = (int64_t)gridDim.x * WAVES_PER_BLOCK;
-    long long pairs = 0;
-  for (int64_t chunk_id = (int64_t)blockIdx.x * WAVES_PER_BLOCK + w; chunk_id < n_chunks; chunk_id += n_waves) {
-    const int64_t unit0 = chunk_id * upw;
-    const int nu = (int)min((int64_t)upw, total - unit0);
-
-    // lane i holds the description of unit i of this wave
-    int64_t m_base = 0, m_out = 0;     // first pool entry; output row offset (floats) in S or in partial
-    int32_t m_cnt = -1, m_v = 0, m_deg = 0, m_part = 0, m_chunk = 0;
-    if (lane < nu) {
-        const int64_t unit = unit0 + lane;
-        DstRec rec;
-        if (unit >= n_items) {                     // hub items come first: the heavy units start early
-            rec = a.recs[unit - n_items];
-            m_cnt = rec.deg > NRT_CHUNK ? -1 : rec.deg;
-            m_out = (int64_t)rec.v * D;
-        } else {
-            const int64_t item = unit;
-            m_chunk = a.hubs.item_chunk[item];
-            rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[item]]];
-            m_cnt = min(NRT_CHUNK, rec.deg - m_chunk * NRT_CHUNK);
-            m_out = item * D;
-            m_part = 1;
-        }
-        m_base = rec.off + (int64_t)m_chunk * NRT_CHUNK;
-        m_v = rec.v;
-        m_deg = rec.deg;
-    }
-    const int32_t m_base_lo = (int32_t)(m_base & 0xffffffff), m_base_hi = (int32_t)(m_base >> 32);
-    const int32_t m_out_lo = (int32_t)(m_out & 0xffffffff), m_out_hi = (int32_t)(m_out >> 32);
-    auto lane64 = [&](int32_t lo, int32_t hi, int i) {
-        const uint32_t l = (uint32_t)__builtin_amdgcn_readlane(lo, i);
-        const uint32_t h = (uint32_t)__builtin_amdgcn_readlane(hi, i);
-        return (int64_t)(((uint64_t)h << 32) | l);
-    };
-
-    // scalar step iterator
-    int it_ui = 0, it_j = 0;
-    auto next_step = [&]() {
-        StepMeta st;
-        st.valid = 0; st.ui = 0; st.j = 0; st.n = 0; st.first = 0; st.last = 0;
-        while (it_ui < nu) {
-            const int cnt = __builtin_amdgcn_readlane(m_cnt, it_ui);
-            if (cnt < 0) { ++it_ui; continue; }            // a hub among the destinations: served through its items
-            st.valid = 1;
-            st.ui = it_ui;
-            st.j = it_j;
-            st.n = min(64, cnt - it_j);
-            st.first = it_j == 0;
-            st.last = it_j + 64 >= cnt;
-            if (st.last) { ++it_ui; it_j = 0; } else { it_j += 64; }
-            break;
-        }
-        return st;
-    };
-
-    StepMeta stB, stC, stD;
-    stB.valid = stC.valid = stD.valid = 0;
-    stB.ui = stC.ui = stD.ui = 0; stB.j = stC.j = stD.j = 0; stB.n = stC.n = stD.n = 0;
-    stB.first = stC.first = stD.first = 0; stB.last = stC.last = stD.last = 0;
-    int32_t uB = -1, uC = -1, slD = -1;
-    float wB = 1.f, wC = 1.f, cD = 1.f;
-    uint32_t xC = 0;                 // bitmap word (FILTER) or in-degree of the source (GCN scale)
-    float4 acc[NV], oldD[NV];
-#pragma unroll
-    for (int q = 0; q < NV; ++q) { acc[q] = make_float4(0.f, 0.f, 0.f, 0.f); oldD[q] = acc[q]; }
     const float* Pl = a.P + gl * 4;
+    long long pairs = 0;
 
     auto take = [&](unsigned long long& m, int32_t rv, float cv) {
         int32_t rr = -1;
@@ -237,111 +186,192 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
         }
         return make_int2(rr, __builtin_bit_cast(int, cc));
     };
-    auto fetch_add = [&](int2 p0, int2 p1, int2 p2, int2 p3) {
-        const float c0 = __builtin_bit_cast(float, p0.y), c1 = __builtin_bit_cast(float, p1.y);
-        const float c2 = __builtin_bit_cast(float, p2.y), c3 = __builtin_bit_cast(float, p3.y);
-#pragma unroll
-        for (int q = 0; q < NV; ++q) {
-            const bool live = gl * 4 + q * LPR * 4 < D;
-            float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0, x2 = x0, x3 = x0;
-            if (p0.x >= 0 && live) x0 = *reinterpret_cast<const float4*>(Pl + (int64_t)p0.x * D + q * LPR * 4);
-            if (p1.x >= 0 && live) x1 = *reinterpret_cast<const float4*>(Pl + (int64_t)p1.x * D + q * LPR * 4);
-            if (p2.x >= 0 && live) x2 = *reinterpret_cast<const float4*>(Pl + (int64_t)p2.x * D + q * LPR * 4);
-            if (p3.x >= 0 && live) x3 = *reinterpret_cast<const float4*>(Pl + (int64_t)p3.x * D + q * LPR * 4);
-            acc[q] = COEF ? f4_fma(c0, x0, acc[q]) : f4_add(acc[q], x0);
-            acc[q] = COEF ? f4_fma(c1, x1, acc[q]) : f4_add(acc[q], x1);
-            acc[q] = COEF ? f4_fma(c2, x2, acc[q]) : f4_add(acc[q], x2);
-            acc[q] = COEF ? f4_fma(c3, x3, acc[q]) : f4_add(acc[q], x3);
-        }
-    };
 
-    for (;;) {
-        // ---- stage A: in-list entries of a new step
-        const StepMeta stA = next_step();
-        if (!(stA.valid | stB.valid | stC.valid | stD.valid)) break;
-        int32_t uA = -1;
-        float wA = 1.f;
-        if (stA.valid) {
-            const int64_t base = lane64(m_base_lo, m_base_hi, stA.ui) + stA.j;
-            if (lane < stA.n) {
-                uA = a.in.idx[base + lane];
-                if (COEF && a.use_weights) wA = a.in.wts[base + lane];
+    for (int64_t chunk_id = (int64_t)blockIdx.x * WAVES_PER_BLOCK + w; chunk_id < n_chunks; chunk_id += n_waves) {
+        const int64_t unit0 = chunk_id * upw;
+        const int nu = (int)min((int64_t)upw, total - unit0);
+
+        // ---- lane i < nu describes unit i of this chunk
+        int64_t u_base = 0, u_out = 0;
+        int32_t u_cnt = -1, u_v = 0, u_deg = 0, u_flags = 0;
+        if (lane < nu) {
+            const int64_t unit = unit0 + lane;
+            DstRec rec;
+            int32_t chunk = 0;
+            if (unit >= n_items) {                     // hub items come first: the heavy units start early
+                rec = a.recs[unit - n_items];
+                u_cnt = rec.deg > NRT_CHUNK ? -1 : rec.deg;
+                u_out = (int64_t)rec.v * D;
+                u_flags = SF_SELF;
+            } else {
+                chunk = a.hubs.item_chunk[unit];
+                rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[unit]]];
+                u_cnt = min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK);
+                u_out = unit * D;
+                u_flags = SF_PART | (chunk == 0 ? SF_SELF : 0);
             }
+            u_base = rec.off + (int64_t)chunk * NRT_CHUNK;
+            u_v = rec.v;
+            u_deg = rec.deg;
         }
-        // ---- stage B: bitmap word (or source degree) for the entries loaded one iteration ago
-        uint32_t xB = 0;
-        if (stB.valid) {
-            if (FILTER) { if (uB >= 0) xB = a.src_bitmap[uB >> 5]; }
-            else if (COEF && a.src_scale_gcn) { if (uB >= 0) xB = (uint32_t)a.in.deg[uB]; }
-        }
-        // ---- stage C: survivors, their slots; the old aggregate row if this step closes its unit
-        int32_t slC = -1;
-        float cC = wC;
-        float4 oldC[NV];
+        // ---- step table: lane t describes step t (64 in-list entries) of the chunk
+        const int u_steps = u_cnt < 0 ? 0 : (u_cnt + 63 > 63 ? (u_cnt + 63) >> 6 : 1);     // at least one step per served unit
+        int my_unit = 0, my_first = 0, n_steps = 0;
 #pragma unroll
-        for (int q = 0; q < NV; ++q) oldC[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (stC.valid) {
+        for (int i = 0; i < MAX_UPW; ++i) {
+            const int sc = __builtin_amdgcn_readlane(u_steps, i);      // 0 for lanes past nu (u_cnt = -1)
+            if (lane >= n_steps) { my_unit = i; my_first = n_steps; }
+            n_steps += sc;
+        }
+        const int addr = my_unit << 2;
+        const int32_t t_cnt = __builtin_amdgcn_ds_bpermute(addr, u_cnt);
+        const int32_t t_j = (lane - my_first) << 6;
+        const int32_t t_n = min(64, t_cnt - t_j);
+        const int64_t t_base = ((int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int32_t)(u_base >> 32)) << 32) |
+                                          (uint32_t)__builtin_amdgcn_ds_bpermute(addr, (int32_t)(u_base & 0xffffffff)))) + t_j;
+        const int32_t t_out_lo = __builtin_amdgcn_ds_bpermute(addr, (int32_t)(u_out & 0xffffffff));
+        const int32_t t_out_hi = __builtin_amdgcn_ds_bpermute(addr, (int32_t)(u_out >> 32));
+        const int32_t t_v = __builtin_amdgcn_ds_bpermute(addr, u_v);
+        const int32_t t_deg = __builtin_amdgcn_ds_bpermute(addr, u_deg);
+        int32_t t_flags = __builtin_amdgcn_ds_bpermute(addr, u_flags);
+        t_flags = (t_flags & SF_PART) | (t_j == 0 ? SF_FIRST | (t_flags & SF_SELF) : 0) | (t_j + 64 >= t_cnt ? SF_LAST : 0);
+        const int32_t t_base_lo = (int32_t)(t_base & 0xffffffff), t_base_hi = (int32_t)(t_base >> 32);
+
+        // ---- four-stage pipeline over the steps
+        int32_t uB = -1, uC = -1, slD = -1;
+        float wB = 1.f, wC = 1.f, cD = 1.f;
+        uint32_t xC = 0;                 // bitmap word (FILTER) or in-degree of the source (GCN scale)
+        float4 acc[NV], oldD[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) { acc[q] = make_float4(0.f, 0.f, 0.f, 0.f); oldD[q] = acc[q]; }
+
+        auto fetch_add = [&](int2 p0, int2 p1, int2 p2, int2 p3) {
+            const float c0 = __builtin_bit_cast(float, p0.y), c1 = __builtin_bit_cast(float, p1.y);
+            const float c2 = __builtin_bit_cast(float, p2.y), c3 = __builtin_bit_cast(float, p3.y);
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const bool live = gl * 4 + q * LPR * 4 < D;
+                float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0, x2 = x0, x3 = x0;
+                if (p0.x >= 0 && live) x0 = *reinterpret_cast<const float4*>(Pl + (int64_t)p0.x * D + q * LPR * 4);
+                if (p1.x >= 0 && live) x1 = *reinterpret_cast<const float4*>(Pl + (int64_t)p1.x * D + q * LPR * 4);
+                if (p2.x >= 0 && live) x2 = *reinterpret_cast<const float4*>(Pl + (int64_t)p2.x * D + q * LPR * 4);
+                if (p3.x >= 0 && live) x3 = *reinterpret_cast<const float4*>(Pl + (int64_t)p3.x * D + q * LPR * 4);
+                acc[q] = COEF ? f4_fma(c0, x0, acc[q]) : f4_add(acc[q], x0);
+                acc[q] = COEF ? f4_fma(c1, x1, acc[q]) : f4_add(acc[q], x1);
+                acc[q] = COEF ? f4_fma(c2, x2, acc[q]) : f4_add(acc[q], x2);
+                acc[q] = COEF ? f4_fma(c3, x3, acc[q]) : f4_add(acc[q], x3);
+            }
+        };
+
+        auto fetch_add2 = [&](int2 p0, int2 p1) {
+            const float c0 = __builtin_bit_cast(float, p0.y), c1 = __builtin_bit_cast(float, p1.y);
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const bool live = gl * 4 + q * LPR * 4 < D;
+                float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0;
+                if (p0.x >= 0 && live) x0 = *reinterpret_cast<const float4*>(Pl + (int64_t)p0.x * D + q * LPR * 4);
+                if (p1.x >= 0 && live) x1 = *reinterpret_cast<const float4*>(Pl + (int64_t)p1.x * D + q * LPR * 4);
+                acc[q] = COEF ? f4_fma(c0, x0, acc[q]) : f4_add(acc[q], x0);
+                acc[q] = COEF ? f4_fma(c1, x1, acc[q]) : f4_add(acc[q], x1);
+            }
+        };
+
+        for (int i = 0; i < n_steps + 3; ++i) {
+            // ---- stage A: in-list entries of step i
+            int32_t uA = -1;
+            float wA = 1.f;
+            if (i < n_steps) {
+                const int n = __builtin_amdgcn_readlane(t_n, i);
+                const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(t_base_lo, i);
+                const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(t_base_hi, i);
+                const int64_t base = (int64_t)(((uint64_t)hi << 32) | lo);
+                if (lane < n) {
+                    uA = a.in.idx[base + lane];
+                    if (COEF && a.use_weights) wA = a.in.wts[base + lane];
+                }
+            }
+            // ---- stage B (step i-1): bitmap word, or source degree for the GCN scale
+            uint32_t xB = 0;
+            if (FILTER) { if (uB >= 0) xB = a.src_bitmap[(uint32_t)uB >> 5]; }
+            else if (COEF && a.src_scale_gcn) { if (uB >= 0) xB = (uint32_t)a.in.deg[(uint32_t)uB]; }
+            // ---- stage C (step i-2): survivors and their slots; old aggregate row if the step closes its unit
+            int32_t slC = -1;
+            float cC = wC;
+            float4 oldC[NV];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) oldC[q] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (FILTER) {
-                if (uC >= 0 && ((xC >> (uC & 31)) & 1u)) slC = a.src_slot[uC];
+                if (uC >= 0 && ((xC >> (uC & 31)) & 1u)) slC = a.src_slot[(uint32_t)uC];
             } else {
                 slC = uC;
                 if (COEF && a.src_scale_gcn && uC >= 0) cC *= gcn_scale((int32_t)xC);
             }
-            if (stC.last && a.accumulate && !__builtin_amdgcn_readlane(m_part, stC.ui)) {
-                const float* op = a.S + lane64(m_out_lo, m_out_hi, stC.ui) + gl * 4;
+            if (i >= 2 && i - 2 < n_steps && a.accumulate) {
+                const int f = __builtin_amdgcn_readlane(t_flags, i - 2);
+                if ((f & (SF_LAST | SF_PART)) == SF_LAST) {
+                    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(t_out_lo, i - 2);
+                    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(t_out_hi, i - 2);
+                    const float* op = a.S + (int64_t)(((uint64_t)hi << 32) | lo) + gl * 4;
 #pragma unroll
-                for (int q = 0; q < NV; ++q)
-                    if (sub == 0 && gl * 4 + q * LPR * 4 < D) oldC[q] = *reinterpret_cast<const float4*>(op + q * LPR * 4);
-            }
-        }
-        // ---- stage D: stream the rows of the survivors
-        if (stD.valid) {
-            unsigned long long m = __ballot(slD >= 0);
-            pairs += __popcll(m);
-            while (m) {
-                const int2 p0 = take(m, slD, cD);
-                const int2 p1 = take(m, slD, cD);
-                const int2 p2 = take(m, slD, cD);
-                const int2 p3 = take(m, slD, cD);
-                fetch_add(p0, p1, p2, p3);
-            }
-            if (stD.first && a.self_pair && __builtin_amdgcn_readlane(m_chunk, stD.ui) == 0) {
-                const int32_t v = __builtin_amdgcn_readlane(m_v, stD.ui);
-                bool sok = true;
-                if (FILTER) sok = (a.src_bitmap[v >> 5] >> (v & 31)) & 1u;
-                if (sok) {
-                    const int32_t rs = FILTER ? a.src_slot[v] : v;
-                    const float cs = (COEF && a.src_scale_gcn) ? gcn_scale(__builtin_amdgcn_readlane(m_deg, stD.ui)) : 1.0f;
-                    fetch_add(make_int2(sub == 0 ? rs : -1, __builtin_bit_cast(int, cs)), make_int2(-1, 0),
-                              make_int2(-1, 0), make_int2(-1, 0));
-                    pairs += 1;
+                    for (int q = 0; q < NV; ++q)
+                        if (sub == 0 && gl * 4 + q * LPR * 4 < D) oldC[q] = *reinterpret_cast<const float4*>(op + q * LPR * 4);
                 }
             }
-            if (stD.last) {
-                const int part = __builtin_amdgcn_readlane(m_part, stD.ui);
-                float* op = (part ? a.hubs.partial : a.S) + lane64(m_out_lo, m_out_hi, stD.ui) + gl * 4;
-#pragma unroll
-                for (int q = 0; q < NV; ++q) {
-#pragma unroll
-                    for (int mm = LPR; mm < 64; mm <<= 1) acc[q] = f4_add(acc[q], f4_shfl_xor(acc[q], mm));
-                    if (sub == 0 && gl * 4 + q * LPR * 4 < D) {
-                        float4 y = acc[q];
-                        if (!part && a.accumulate) y = f4_add(y, oldD[q]);
-                        *reinterpret_cast<float4*>(op + q * LPR * 4) = y;
+            // ---- stage D (step i-3): stream the rows of the survivors
+            if (i >= 3) {
+                const int f = __builtin_amdgcn_readlane(t_flags, i - 3);
+                unsigned long long m = __ballot(slD >= 0);
+                pairs += __popcll(m);
+                while (m) {
+                    if (__popcll(m) <= 2 * RPI) {            // the common case on sparse layers: one short round
+                        const int2 p0 = take(m, slD, cD);
+                        const int2 p1 = take(m, slD, cD);
+                        fetch_add2(p0, p1);
+                    } else {
+                        const int2 p0 = take(m, slD, cD);
+                        const int2 p1 = take(m, slD, cD);
+                        const int2 p2 = take(m, slD, cD);
+                        const int2 p3 = take(m, slD, cD);
+                        fetch_add(p0, p1, p2, p3);
                     }
-                    acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+                if ((f & SF_SELF) && a.self_pair) {
+                    const int32_t v = __builtin_amdgcn_readlane(t_v, i - 3);
+                    bool sok = true;
+                    if (FILTER) sok = (a.src_bitmap[v >> 5] >> (v & 31)) & 1u;
+                    if (sok) {
+                        const int32_t rs = FILTER ? a.src_slot[v] : v;
+                        const float cs = (COEF && a.src_scale_gcn) ? gcn_scale(__builtin_amdgcn_readlane(t_deg, i - 3)) : 1.0f;
+                        fetch_add(make_int2(sub == 0 ? rs : -1, __builtin_bit_cast(int, cs)), make_int2(-1, 0),
+                                  make_int2(-1, 0), make_int2(-1, 0));
+                        pairs += 1;
+                    }
+                }
+                if (f & SF_LAST) {
+                    const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(t_out_lo, i - 3);
+                    const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(t_out_hi, i - 3);
+                    float* op = ((f & SF_PART) ? a.hubs.partial : a.S) + (int64_t)(((uint64_t)hi << 32) | lo) + gl * 4;
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) {
+#pragma unroll
+                        for (int mm = LPR; mm < 64; mm <<= 1) acc[q] = f4_add(acc[q], f4_shfl_xor(acc[q], mm));
+                        if (sub == 0 && gl * 4 + q * LPR * 4 < D) {
+                            float4 y = acc[q];
+                            if (!(f & SF_PART) && a.accumulate) y = f4_add(y, oldD[q]);
+                            *reinterpret_cast<float4*>(op + q * LPR * 4) = y;
+                        }
+                        acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    }
                 }
             }
-        }
-        // ---- rotate
-        stD = stC; stC = stB; stB = stA;
-        slD = slC; cD = cC;
+            // ---- rotate
+            slD = slC; cD = cC;
 #pragma unroll
-        for (int q = 0; q < NV; ++q) oldD[q] = oldC[q];
-        uC = uB; wC = wB; xC = xB;
-        uB = uA; wB = wA;
+            for (int q = 0; q < NV; ++q) oldD[q] = oldC[q];
+            uC = uB; wC = wB; xC = xB;
+            uB = uA; wB = wA;
+        }
     }
-  }
     if (a.pair_ctr && lane == 0 && pairs) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)pairs);
 }
 
@@ -425,8 +455,8 @@ __global__ void layer0_delta_kernel(DeltaArgs a) {
 nrt_status k_dst_records(const int32_t* list, int64_t bound, const Adj& in, DstRec* recs, const HubWork& hubs,
                          LayerCtrs* lc, bool all_vertices, hipStream_t s) {
     if (bound <= 0) return NRT_OK;
-    int64_t g = cdiv(bound, REC_THREADS);
-    if (g > 2048) g = 2048;
+    int64_t g = cdiv(bound, (int64_t)REC_THREADS * REC_EPT);
+    if (g > 1024) g = 1024;
     dst_records_kernel<<<(int)g, REC_THREADS, 0, s>>>(all_vertices ? nullptr : list, bound, in, recs, hubs, lc);
     LAUNCH_CHECK();
     return NRT_OK;

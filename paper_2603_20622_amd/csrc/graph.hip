@@ -11,7 +11,7 @@ namespace {
 
 constexpr int RB_THREADS = 1024;   // threads of a list-rebuild workgroup
 constexpr int RB_EPT = 4;
-constexpr int VAL_THREADS = 256;  // threads of an edge-validation workgroup
+constexpr int VAL_THREADS = 1024; // threads of an edge-validation workgroup
 
 __device__ inline int32_t new_cap_for(int32_t need) { return need + need / 2 + 4; }
 __device__ inline int32_t initial_cap_for(int32_t deg) { return deg + deg / 8 + 2; }
