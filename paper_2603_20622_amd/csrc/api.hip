@@ -54,6 +54,11 @@ struct nrt_cache {
     int32_t* slot[2];
     float* DP[2];
     float* mid;
+    // GAT: z = x W, attention scalars, softmax context per (vertex, head)
+    float* Z[NRT_MAX_LAYERS + 1];
+    float *AS[NRT_MAX_LAYERS + 1], *AD[NRT_MAX_LAYERS + 1], *M[NRT_MAX_LAYERS + 1], *DEN[NRT_MAX_LAYERS + 1];
+    float *att_src[NRT_MAX_LAYERS], *att_dst[NRT_MAX_LAYERS];
+    float* AS_old;
     DstRec* recs;
     HubWork hubs;
     BatchScratch sc;
@@ -219,8 +224,15 @@ static nrt_status check_desc(const nrt_model_desc* d) {
         }
     }
     if (d->kind == NRT_GAT) {
-        nrt_set_error("GAT is not built yet");
-        return NRT_ERR_UNSUPPORTED;
+        if (d->heads < 1 || d->head_dim < 4 || d->head_dim % 4) {
+            nrt_set_error("GAT needs heads >= 1 and head_dim a multiple of 4");
+            return NRT_ERR_UNSUPPORTED;
+        }
+        for (int l = 1; l <= d->n_layers; ++l)
+            if (d->dims[l] != d->heads * d->head_dim) {
+                nrt_set_error("GAT layer widths must equal heads * head_dim");
+                return NRT_ERR_UNSUPPORTED;
+            }
     }
     return NRT_OK;
 }
@@ -234,10 +246,21 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->maxd = maxd;
     for (int l = 0; l <= c->L; ++l) c->H[l] = b.take<float>(n * c->dims[l]);
     c->S[0] = nullptr;
+    const bool gat = c->kind == NRT_GAT;
     for (int l = 1; l <= c->L; ++l) {
-        c->dagg[l] = c->dims[l - 1];
+        c->dagg[l] = gat ? c->dims[l] : c->dims[l - 1];
         c->S[l] = b.take<float>(n * c->dagg[l]);
+        if (gat) {
+            c->Z[l] = b.take<float>(n * c->dims[l]);
+            c->AS[l] = b.take<float>(n * c->heads);
+            c->AD[l] = b.take<float>(n * c->heads);
+            c->M[l] = b.take<float>(n * c->heads);
+            c->DEN[l] = b.take<float>(n * c->heads);
+            c->att_src[l - 1] = b.take<float>((size_t)c->heads * c->head_dim);
+            c->att_dst[l - 1] = b.take<float>((size_t)c->heads * c->head_dim);
+        }
     }
+    c->AS_old = gat ? b.take<float>(n * c->heads) : nullptr;
     for (int l = 0; l < c->L; ++l) {
         const int kin = (c->kind == NRT_SAGE_MEAN ? 2 : 1) * c->dims[l];
         c->Wt[l][0] = b.take<float>((size_t)kin * c->dims[l + 1]);
@@ -429,6 +452,66 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
     return NRT_OK;
 }
 
+// GAT layer l: z = x W on the listed rows (null: all), attention scalars, then the attention gather + output
+static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
+                                const int32_t* dst_rows, const uint64_t* n_dst_dev, int64_t dst_bound, bool incremental,
+                                int prev, float* out_rows, int64_t out_cap, hipStream_t s) {
+    nrt_graph* g = c->g;
+    const bool last = l == c->L;
+    GemmArgs z;
+    memset(&z, 0, sizeof(z));
+    z.M = incremental ? src_bound : g->n;
+    z.M_dev = n_src_dev;
+    z.rows = src_rows;
+    z.a_mode = A_PLAIN;
+    z.P0 = c->H[l - 1];
+    z.ldp = c->dims[l - 1];
+    z.K = c->dims[l - 1];
+    z.N = c->dims[l];
+    z.Wt = c->Wt[l - 1][0];
+    z.H = c->Z[l];
+    if (incremental) { z.DP = c->DP[0]; z.dp_store_old = 1; }     // keep the old z rows, compact, for Algorithm 3
+    NRT_TRY(k_gemm(z, s));
+    GatArgs a;
+    memset(&a, 0, sizeof(a));
+    a.n = g->n;
+    a.heads = c->heads;
+    a.head_dim = c->head_dim;
+    a.slope = c->leaky_slope;
+    a.att_src = c->att_src[l - 1];
+    a.att_dst = c->att_dst[l - 1];
+    a.Z = c->Z[l];
+    a.AS = c->AS[l];
+    a.AD = c->AD[l];
+    a.rows = src_rows;
+    a.n_rows_dev = n_src_dev;
+    a.rows_bound = src_bound;
+    a.AS_old = incremental ? c->AS_old : nullptr;
+    NRT_TRY(k_gat_scalars(a, s));
+    NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
+    a.rows = dst_rows;
+    a.n_rows_dev = n_dst_dev;
+    a.rows_bound = dst_bound;
+    a.Z_old = c->DP[0];
+    a.in = g->in;
+    if (incremental) {
+        a.src_bitmap = c->bm[prev];
+        a.src_slot = c->slot[prev];
+        a.ddst_bitmap = c->bm_ddst;
+    }
+    a.M = c->M[l];
+    a.DEN = c->DEN[l];
+    a.S = c->S[l];
+    a.Hout = c->H[l];
+    a.bias = c->bias[l - 1][0];
+    a.act = last ? 0 : 2;
+    a.out_rows = last ? out_rows : nullptr;
+    a.out_cap = out_cap;
+    NRT_TRY(k_gat_gather(a, s));
+    NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
+    return NRT_OK;
+}
+
 // ------------------------------------------------------------------ cache init
 extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, const float* features,
                                      int64_t max_batch_edges, int64_t max_batch_feats, void* workspace,
@@ -443,6 +526,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     for (int l = 0; l < d->n_layers; ++l) {
         REQUIRE(d->W[l][0], "W[l][0] is null");
         if (d->kind == NRT_GIN) REQUIRE(d->W[l][1], "GIN needs W[l][1]");
+        if (d->kind == NRT_GAT) REQUIRE(d->att_src[l] && d->att_dst[l], "GAT needs att_src[l] and att_dst[l]");
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     nrt_cache* c = new (std::nothrow) nrt_cache;
@@ -466,6 +550,10 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
             NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
             if (d->b[l][0]) NRT_TRY(k_copy_f32(c->bias[l][0], d->b[l][0], c->dims[l + 1], s));
             else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][0], c->dims[l + 1], 0, s));
+            if (c->kind == NRT_GAT) {
+                NRT_TRY(k_copy_f32(c->att_src[l], d->att_src[l], (int64_t)c->heads * c->head_dim, s));
+                NRT_TRY(k_copy_f32(c->att_dst[l], d->att_dst[l], (int64_t)c->heads * c->head_dim, s));
+            }
             if (c->kind == NRT_GIN) {
                 NRT_TRY(k_transpose(d->W[l][1], c->Wt[l][1], c->dims[l + 1], c->dims[l + 1], s));
                 if (d->b[l][1]) NRT_TRY(k_copy_f32(c->bias[l][1], d->b[l][1], c->dims[l + 1], s));
@@ -476,6 +564,10 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         NRT_TRY(k_dst_records(nullptr, n, g->in, c->recs, c->hubs, &c->lc[1], true, s));
         NRT_TRY(k_fill_u64(&c->lc[1].count, 1, (uint64_t)n, s));
         for (int l = 1; l <= c->L; ++l) {
+            if (c->kind == NRT_GAT) {
+                NRT_TRY(run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, 0, nullptr, 0, s));
+                continue;
+            }
             if (l > 1) HIP_TRY(hipMemcpyAsync(&c->lc[l], &c->lc[1], sizeof(LayerCtrs), hipMemcpyDeviceToDevice, s));
             NRT_TRY(run_gather(c, l, false, 0, s));
             NRT_TRY(run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, s));
@@ -566,8 +658,8 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
     if (gcn) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
 
-    // ---- structural terms on the old caches, all layers in one launch
-    {
+    // ---- structural terms on the old caches, all layers in one launch (GAT recomputes those destinations in full)
+    if (c->kind != NRT_GAT) {
         FoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
@@ -617,6 +709,14 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
         NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
                           g->scan_tmp_len, &c->lc[l].count, s));
+        if (c->kind == NRT_GAT) {
+            NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
+            NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
+                                  prev, l == c->L ? affected_rows : nullptr, capacity, s));
+            NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
+            prev = cur;
+            continue;
+        }
         NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, s));
         NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
         NRT_TRY(run_gather(c, l, true, prev, s));

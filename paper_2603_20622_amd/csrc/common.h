@@ -187,9 +187,37 @@ struct GemmArgs {
     float* DP;                      // [M][N] delta payload for the next layer or null
     const int32_t* indeg_old;       // GCN payload scale for DP (with indeg as new), else null
     int dp_scale_gcn;
+    int dp_store_old;               // DP receives the overwritten row of H instead of a payload delta (GAT: old z)
 };
 nrt_status k_gemm(const GemmArgs& a, hipStream_t s);
 nrt_status k_transpose(const float* W, float* Wt, int K, int N, hipStream_t s);   // Wt[n][k] = W[k][n]
+
+// ---------------------------------------------------------------- gat.hip
+struct GatArgs {
+    const int32_t* rows;            // listed vertices (null: all n)
+    const uint64_t* n_rows_dev;     // their number on the device (with rows)
+    int64_t rows_bound;             // launch bound for the listed rows
+    int64_t n;
+    int heads, head_dim;
+    float slope;
+    const float* att_src; const float* att_dst;   // [heads][head_dim]
+    float* Z;                       // [N][D] current z = x W
+    float* AS; float* AD;           // [N][heads] attention scalars
+    float* AS_old;                  // [rows][heads] compact: scalars before this batch (k_gat_scalars writes, gather reads)
+    const float* Z_old;             // [rows][D] compact: z before this batch
+    // gather only
+    Adj in;
+    const uint32_t* src_bitmap;     // vertices whose z changed (null: full forward for every row)
+    const int32_t* src_slot;        // their slots in Z_old / AS_old
+    const uint32_t* ddst_bitmap;    // destinations of updated edges
+    float* M; float* DEN;           // [N][heads]
+    float* S;                       // [N][D]
+    float* Hout;                    // [N][D] layer output
+    const float* bias; int act;
+    float* out_rows; int64_t out_cap;
+};
+nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s);
+nrt_status k_gat_gather(const GatArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------- graph.hip
 nrt_status graph_layout(Bump& b, nrt_graph* g);

@@ -1,0 +1,250 @@
+// GAT on the incremental path (Eq. 3-4; Algorithms 2 and 3).
+//
+// Cached per layer and vertex: z = x W, the two attention scalars per head as = a_src . z, ad = a_dst . z (they
+// replace the per-edge cached attention of Algorithm 3 line 3: an old logit is recomputed from old scalars), a
+// running bound m of the largest logit, the attention sum den = sum exp(e - m) (Algorithm 3's at_sum, shifted by
+// m so that exp cannot overflow) and the context-free aggregate S = sum exp(e - m) z_u (Algorithm 3's a-hat).
+//
+// For an affected destination v:
+//   * if its own z changed (its layer input changed) or it gained/lost an in-edge, every logit of v may have
+//     changed: v is recomputed over its full new in-neighbourhood plus itself (Algorithm 2; the constrained-model
+//     rule of Section III-D / Algorithm 4 lines 5-7);
+//   * otherwise only the in-neighbours whose z changed contribute (Algorithm 3 lines 2-7):
+//       den += sum (at_new - at_old),  S += sum (at_new z_new - at_old z_old),
+//     after raising m if a new logit exceeds it (den and S are rescaled by exp(m_old - m_new)).  When the update
+//     removes most of the old attention mass (den shrinks below 1/64 of its old value) the subtraction has
+//     cancelled the leading digits, and v is recomputed in full instead.
+// One wave per destination; lane = 4 consecutive columns of the row, a head = head_dim/4 neighbouring lanes.
+#include "common.h"
+
+namespace {
+
+__device__ inline float leaky(float x, float slope) { return x > 0.f ? x : slope * x; }
+
+// ------------------------------------------------------------------ attention scalars of the listed rows
+__global__ void gat_scalars_kernel(GatArgs a) {
+    const int64_t m = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    const int64_t count = a.rows ? (int64_t)*a.n_rows_dev : a.n;
+    if (m >= count) return;
+    const int64_t v = a.rows ? (int64_t)a.rows[m] : m;
+    const int D = a.heads * a.head_dim;
+    for (int k = 0; k < a.heads; ++k) {
+        float ps = 0.f, pd = 0.f;
+        for (int c = lane; c < a.head_dim; c += 64) {
+            const float z = a.Z[v * D + k * a.head_dim + c];
+            ps += a.att_src[k * a.head_dim + c] * z;
+            pd += a.att_dst[k * a.head_dim + c] * z;
+        }
+#pragma unroll
+        for (int s = 32; s >= 1; s >>= 1) { ps += __shfl_xor(ps, s, 64); pd += __shfl_xor(pd, s, 64); }
+        if (lane == 0) {
+            if (a.AS_old) a.AS_old[m * a.heads + k] = a.AS[v * a.heads + k];
+            a.AS[v * a.heads + k] = ps;
+            a.AD[v * a.heads + k] = pd;
+        }
+    }
+}
+
+// ------------------------------------------------------------------ gather
+template <int NV>
+__global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    const int64_t count = a.rows ? (int64_t)*a.n_rows_dev : a.n;
+    const int H = a.heads, hd = a.head_dim, D = H * hd;
+    const float slope = a.slope;
+    int col[NV], head[NV];
+    bool live[NV];
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        col[q] = lane * 4 + q * 256;
+        live[q] = col[q] < D;
+        head[q] = live[q] ? col[q] / hd : 0;
+    }
+    for (int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; s < count; s += waves) {
+        const int32_t v = a.rows ? a.rows[s] : (int32_t)s;
+        const int64_t off = a.in.off[v];
+        const int32_t deg = a.in.deg[v];
+        bool full = true;
+        if (a.src_bitmap) {
+            const bool own = (a.src_bitmap[v >> 5] >> (v & 31)) & 1u;
+            const bool edge = (a.ddst_bitmap[v >> 5] >> (v & 31)) & 1u;
+            full = own || edge;
+        }
+        float adv[NV], mcur[NV], den[NV];
+        float4 acc[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)v * H + head[q]] : 0.f;
+
+        if (!full) {
+            // ---- Algorithm 3: only the in-neighbours whose z changed
+            float mold[NV];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) { mold[q] = live[q] ? a.M[(int64_t)v * H + head[q]] : 0.f; mcur[q] = mold[q]; }
+            // pass 1: raise the bound to the largest new logit
+            for (int32_t j0 = 0; j0 < deg; j0 += 64) {
+                const int32_t jj = j0 + lane;
+                int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                bool ok = u >= 0 && ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u);
+                unsigned long long mask = __ballot(ok);
+                while (mask) {
+                    const int bit = __ffsll((long long)mask) - 1;
+                    mask &= mask - 1;
+                    const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+#pragma unroll
+                    for (int q = 0; q < NV; ++q)
+                        if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+                }
+            }
+            bool redo = false;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const float f = __expf(mold[q] - mcur[q]);
+                den[q] = live[q] ? a.DEN[(int64_t)v * H + head[q]] * f : 1.f;
+                acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (live[q]) {
+                    const float4 so = *reinterpret_cast<const float4*>(a.S + (int64_t)v * D + col[q]);
+                    acc[q] = make_float4(so.x * f, so.y * f, so.z * f, so.w * f);
+                }
+            }
+            float den0[NV];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) den0[q] = den[q];
+            // pass 2: exchange old terms for new ones
+            for (int32_t j0 = 0; j0 < deg; j0 += 64) {
+                const int32_t jj = j0 + lane;
+                int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                bool ok = u >= 0 && ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u);
+                int32_t sl = ok ? a.src_slot[u] : -1;
+                unsigned long long mask = __ballot(ok);
+                while (mask) {
+                    const int bit = __ffsll((long long)mask) - 1;
+                    mask &= mask - 1;
+                    const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+                    const int32_t ss = __builtin_amdgcn_readlane(sl, bit);
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) {
+                        if (!live[q]) continue;
+                        const float en = leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope);
+                        const float eo = leaky(adv[q] + a.AS_old[(int64_t)ss * H + head[q]], slope);
+                        const float cn = __expf(en - mcur[q]), co = __expf(eo - mcur[q]);
+                        const float4 zn = *reinterpret_cast<const float4*>(a.Z + (int64_t)uu * D + col[q]);
+                        const float4 zo = *reinterpret_cast<const float4*>(a.Z_old + (int64_t)ss * D + col[q]);
+                        den[q] += cn - co;
+                        acc[q].x += cn * zn.x - co * zo.x; acc[q].y += cn * zn.y - co * zo.y;
+                        acc[q].z += cn * zn.z - co * zo.z; acc[q].w += cn * zn.w - co * zo.w;
+                    }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                if (live[q] && !(den[q] > den0[q] * (1.0f / 64.0f))) redo = true;
+            full = __ballot(redo) != 0ULL;        // cancellation: recompute this destination over all its neighbours
+        }
+        if (full) {
+            // ---- Algorithm 2: every in-neighbour of the new graph plus the self-loop
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                mcur[q] = live[q] ? leaky(adv[q] + a.AS[(int64_t)v * H + head[q]], slope) : 0.f;
+            for (int32_t j0 = 0; j0 < deg; j0 += 64) {
+                const int32_t jj = j0 + lane;
+                const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                unsigned long long mask = __ballot(u >= 0);
+                while (mask) {
+                    const int bit = __ffsll((long long)mask) - 1;
+                    mask &= mask - 1;
+                    const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+#pragma unroll
+                    for (int q = 0; q < NV; ++q)
+                        if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                den[q] = 0.f;
+                acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (live[q]) {
+                    const float c = __expf(leaky(adv[q] + a.AS[(int64_t)v * H + head[q]], slope) - mcur[q]);
+                    const float4 z = *reinterpret_cast<const float4*>(a.Z + (int64_t)v * D + col[q]);
+                    den[q] = c;
+                    acc[q] = make_float4(c * z.x, c * z.y, c * z.z, c * z.w);
+                }
+            }
+            for (int32_t j0 = 0; j0 < deg; j0 += 64) {
+                const int32_t jj = j0 + lane;
+                const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                unsigned long long mask = __ballot(u >= 0);
+                while (mask) {
+                    const int b0 = __ffsll((long long)mask) - 1;
+                    mask &= mask - 1;
+                    const int32_t u0 = __builtin_amdgcn_readlane(u, b0);
+                    int32_t u1 = -1;
+                    if (mask) {
+                        const int b1 = __ffsll((long long)mask) - 1;
+                        mask &= mask - 1;
+                        u1 = __builtin_amdgcn_readlane(u, b1);
+                    }
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) {
+                        if (!live[q]) continue;
+                        const float c0 = __expf(leaky(adv[q] + a.AS[(int64_t)u0 * H + head[q]], slope) - mcur[q]);
+                        const float4 z0 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u0 * D + col[q]);
+                        float c1 = 0.f;
+                        float4 z1 = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (u1 >= 0) {
+                            c1 = __expf(leaky(adv[q] + a.AS[(int64_t)u1 * H + head[q]], slope) - mcur[q]);
+                            z1 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u1 * D + col[q]);
+                        }
+                        den[q] += c0 + c1;
+                        acc[q].x += c0 * z0.x + c1 * z1.x; acc[q].y += c0 * z0.y + c1 * z1.y;
+                        acc[q].z += c0 * z0.z + c1 * z1.z; acc[q].w += c0 * z0.w + c1 * z1.w;
+                    }
+                }
+            }
+        }
+        // ---- store the context, the aggregate and the layer output  h = act(S / den + b)
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            if (!live[q]) continue;
+            if ((col[q] % hd) == 0) {
+                a.M[(int64_t)v * H + head[q]] = mcur[q];
+                a.DEN[(int64_t)v * H + head[q]] = den[q];
+            }
+            *reinterpret_cast<float4*>(a.S + (int64_t)v * D + col[q]) = acc[q];
+            const float inv = 1.0f / den[q];
+            float y[4] = {acc[q].x * inv, acc[q].y * inv, acc[q].z * inv, acc[q].w * inv};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (a.bias) y[t] += a.bias[col[q] + t];
+                if (a.act == 2) y[t] = y[t] > 0.f ? y[t] : expm1f(y[t]);
+            }
+            const float4 yo = make_float4(y[0], y[1], y[2], y[3]);
+            *reinterpret_cast<float4*>(a.Hout + (int64_t)v * D + col[q]) = yo;
+            if (a.out_rows && s < a.out_cap) *reinterpret_cast<float4*>(a.out_rows + s * D + col[q]) = yo;
+        }
+    }
+}
+
+}  // namespace
+
+nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s) {
+    const int64_t bound = a.rows ? a.rows_bound : a.n;
+    if (bound <= 0) return NRT_OK;
+    gat_scalars_kernel<<<(unsigned)cdiv(bound * 64, 256), 256, 0, s>>>(a);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_gat_gather(const GatArgs& a, hipStream_t s) {
+    const int D = a.heads * a.head_dim;
+    const int64_t bound = a.rows ? a.rows_bound : a.n;
+    if (bound <= 0) return NRT_OK;
+    int64_t g = cdiv(bound, 4);
+    if (g > 16384) g = 16384;
+    if (D <= 256) gat_gather_kernel<1><<<(int)g, 256, 0, s>>>(a);
+    else if (D <= 512) gat_gather_kernel<2><<<(int)g, 256, 0, s>>>(a);
+    else gat_gather_kernel<4><<<(int)g, 256, 0, s>>>(a);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}

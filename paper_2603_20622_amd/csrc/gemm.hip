@@ -187,7 +187,7 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
                     else if (g.act == 2) y = y > 0.f ? y : expm1f(y);
                     if (g.out_compact && mrow[rr] < g.out_cap) g.out_compact[mrow[rr] * g.N + n] = y;
                     if (g.H) {
-                        if (g.DP) g.DP[mrow[rr] * g.N + n] = y * cn[rr] - oldv[rr][j] * co[rr];
+                        if (g.DP) g.DP[mrow[rr] * g.N + n] = g.dp_store_old ? oldv[rr][j] : y * cn[rr] - oldv[rr][j] * co[rr];
                         g.H[vrow[rr] * g.N + n] = y;
                     }
                 }

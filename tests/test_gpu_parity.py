@@ -64,7 +64,7 @@ def small_case(kind, seed=0, n=3000, e=40000, dims=None, bias=False, L=2):
     return n, src, dst, w, x, spec, params, stream
 
 
-KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN]
+KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT]
 
 
 @pytest.mark.parametrize("kind", KINDS)
