@@ -59,6 +59,8 @@ struct nrt_cache {
     float *AS[NRT_MAX_LAYERS + 1], *AD[NRT_MAX_LAYERS + 1], *M[NRT_MAX_LAYERS + 1], *DEN[NRT_MAX_LAYERS + 1];
     float *att_src[NRT_MAX_LAYERS], *att_dst[NRT_MAX_LAYERS];
     float* AS_old;
+    float *part_m, *part_den;
+    bool is_gat;
     DstRec* recs;
     HubWork hubs;
     BatchScratch sc;
@@ -261,6 +263,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         }
     }
     c->AS_old = gat ? b.take<float>(n * c->heads) : nullptr;
+    c->is_gat = gat;
     for (int l = 0; l < c->L; ++l) {
         const int kin = (c->kind == NRT_SAGE_MEAN ? 2 : 1) * c->dims[l];
         c->Wt[l][0] = b.take<float>((size_t)kin * c->dims[l + 1]);
@@ -293,6 +296,8 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->hubs.item_hub = b.take<int32_t>(c->hubs.item_cap);
     c->hubs.item_chunk = b.take<int32_t>(c->hubs.item_cap);
     c->hubs.partial = b.take<float>(c->hubs.item_cap * maxd);
+    c->part_m = c->is_gat ? b.take<float>(c->hubs.item_cap * c->heads) : nullptr;
+    c->part_den = c->is_gat ? b.take<float>(c->hubs.item_cap * c->heads) : nullptr;
     c->xhub_cap = g->e_capacity / 512 + 64;                    // sources with more than 512 live out-edges
     c->xhub_list = b.take<int32_t>(c->xhub_cap);
     c->flags = b.take<uint8_t>(n + 64);
@@ -492,6 +497,11 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
     a.rows = dst_rows;
     a.n_rows_dev = n_dst_dev;
     a.rows_bound = dst_bound;
+    a.recs = c->recs;
+    a.hubs = c->hubs;
+    a.lc = &c->lc[l];
+    a.part_m = c->part_m;
+    a.part_den = c->part_den;
     a.Z_old = c->DP[0];
     a.in = g->in;
     if (incremental) {
@@ -564,11 +574,11 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         NRT_TRY(k_dst_records(nullptr, n, g->in, c->recs, c->hubs, &c->lc[1], true, s));
         NRT_TRY(k_fill_u64(&c->lc[1].count, 1, (uint64_t)n, s));
         for (int l = 1; l <= c->L; ++l) {
+            if (l > 1) HIP_TRY(hipMemcpyAsync(&c->lc[l], &c->lc[1], sizeof(LayerCtrs), hipMemcpyDeviceToDevice, s));
             if (c->kind == NRT_GAT) {
                 NRT_TRY(run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, 0, nullptr, 0, s));
                 continue;
             }
-            if (l > 1) HIP_TRY(hipMemcpyAsync(&c->lc[l], &c->lc[1], sizeof(LayerCtrs), hipMemcpyDeviceToDevice, s));
             NRT_TRY(run_gather(c, l, false, 0, s));
             NRT_TRY(run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, s));
         }
@@ -710,6 +720,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
                           g->scan_tmp_len, &c->lc[l].count, s));
         if (c->kind == NRT_GAT) {
+            NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, s));
             NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
             NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
                                   prev, l == c->L ? affected_rows : nullptr, capacity, s));

@@ -205,7 +205,11 @@ struct GatArgs {
     float* AS; float* AD;           // [N][heads] attention scalars
     float* AS_old;                  // [rows][heads] compact: scalars before this batch (k_gat_scalars writes, gather reads)
     const float* Z_old;             // [rows][D] compact: z before this batch
-    // gather only
+    // gather only: destination records, hub items and counters of the destination layer
+    const DstRec* recs;
+    HubWork hubs;
+    const LayerCtrs* lc;
+    float* part_m; float* part_den; // [item_cap][heads] partial max / sum of hub items
     Adj in;
     const uint32_t* src_bitmap;     // vertices whose z changed (null: full forward for every row)
     const int32_t* src_slot;        // their slots in Z_old / AS_old

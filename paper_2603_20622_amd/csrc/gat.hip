@@ -47,11 +47,111 @@ __global__ void gat_scalars_kernel(GatArgs a) {
 }
 
 // ------------------------------------------------------------------ gather
+// Softmax aggregate over `cnt` in-list entries starting at pool position `base`, optionally with the self-loop
+// of v, all with current values (Algorithm 2).  Two passes: largest logit, then the shifted sums.
+template <int NV>
+__device__ inline void gat_full_pass(const GatArgs& a, int32_t v, int64_t base, int32_t cnt, bool with_self, int lane,
+                                     const int (&col)[NV], const int (&head)[NV], const bool (&live)[NV],
+                                     const float (&adv)[NV], float (&mcur)[NV], float (&den)[NV], float4 (&acc)[NV]) {
+    const int H = a.heads, D = a.heads * a.head_dim;
+    const float slope = a.slope;
+#pragma unroll
+    for (int q = 0; q < NV; ++q)
+        mcur[q] = (live[q] && with_self) ? leaky(adv[q] + a.AS[(int64_t)v * H + head[q]], slope) : -3.0e38f;
+    for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
+        const int32_t jj = j0 + lane;
+        const int32_t u = jj < cnt ? a.in.idx[base + jj] : -1;
+        unsigned long long mask = __ballot(u >= 0);
+        while (mask) {
+            const int bit = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        den[q] = 0.f;
+        acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (live[q] && with_self) {
+            const float c = __expf(leaky(adv[q] + a.AS[(int64_t)v * H + head[q]], slope) - mcur[q]);
+            const float4 z = *reinterpret_cast<const float4*>(a.Z + (int64_t)v * D + col[q]);
+            den[q] = c;
+            acc[q] = make_float4(c * z.x, c * z.y, c * z.z, c * z.w);
+        }
+    }
+    for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
+        const int32_t jj = j0 + lane;
+        const int32_t u = jj < cnt ? a.in.idx[base + jj] : -1;
+        unsigned long long mask = __ballot(u >= 0);
+        while (mask) {
+            const int b0 = __ffsll((long long)mask) - 1;
+            mask &= mask - 1;
+            const int32_t u0 = __builtin_amdgcn_readlane(u, b0);
+            int32_t u1 = -1;
+            if (mask) {
+                const int b1 = __ffsll((long long)mask) - 1;
+                mask &= mask - 1;
+                u1 = __builtin_amdgcn_readlane(u, b1);
+            }
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                if (!live[q]) continue;
+                const float c0 = __expf(leaky(adv[q] + a.AS[(int64_t)u0 * H + head[q]], slope) - mcur[q]);
+                const float4 z0 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u0 * D + col[q]);
+                float c1 = 0.f;
+                float4 z1 = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (u1 >= 0) {
+                    c1 = __expf(leaky(adv[q] + a.AS[(int64_t)u1 * H + head[q]], slope) - mcur[q]);
+                    z1 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u1 * D + col[q]);
+                }
+                den[q] += c0 + c1;
+                acc[q].x += c0 * z0.x + c1 * z1.x; acc[q].y += c0 * z0.y + c1 * z1.y;
+                acc[q].z += c0 * z0.z + c1 * z1.z; acc[q].w += c0 * z0.w + c1 * z1.w;
+            }
+        }
+    }
+}
+
+// store context, aggregate and layer output h = act(S / den + b) of vertex v (list position s)
+template <int NV>
+__device__ inline void gat_store(const GatArgs& a, int32_t v, int64_t s, const int (&col)[NV], const int (&head)[NV],
+                                 const bool (&live)[NV], const float (&mcur)[NV], const float (&den)[NV],
+                                 const float4 (&acc)[NV]) {
+    const int H = a.heads, hd = a.head_dim, D = H * hd;
+#pragma unroll
+    for (int q = 0; q < NV; ++q) {
+        if (!live[q]) continue;
+        if ((col[q] % hd) == 0) {
+            a.M[(int64_t)v * H + head[q]] = mcur[q];
+            a.DEN[(int64_t)v * H + head[q]] = den[q];
+        }
+        *reinterpret_cast<float4*>(a.S + (int64_t)v * D + col[q]) = acc[q];
+        const float inv = 1.0f / den[q];
+        float y[4] = {acc[q].x * inv, acc[q].y * inv, acc[q].z * inv, acc[q].w * inv};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (a.bias) y[t] += a.bias[col[q] + t];
+            if (a.act == 2) y[t] = y[t] > 0.f ? y[t] : expm1f(y[t]);
+        }
+        const float4 yo = make_float4(y[0], y[1], y[2], y[3]);
+        *reinterpret_cast<float4*>(a.Hout + (int64_t)v * D + col[q]) = yo;
+        if (a.out_rows && s < a.out_cap) *reinterpret_cast<float4*>(a.out_rows + s * D + col[q]) = yo;
+    }
+}
+
+// Units [0, n_items): hub items (NRT_CHUNK in-list entries of a destination with a long in-list; such a
+// destination is always recomputed in full, its items write partial (max, sum, row) triples).  Units
+// [n_items, n_items + n_dst): the destinations themselves, hubs skipped.
 template <int NV>
 __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
     const int lane = threadIdx.x & 63;
     const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
-    const int64_t count = a.rows ? (int64_t)*a.n_rows_dev : a.n;
+    const int64_t n_dst = (int64_t)a.lc->count;
+    int64_t n_items = (int64_t)a.lc->n_items;
+    if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
     const int H = a.heads, hd = a.head_dim, D = H * hd;
     const float slope = a.slope;
     int col[NV], head[NV];
@@ -62,18 +162,39 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
         live[q] = col[q] < D;
         head[q] = live[q] ? col[q] / hd : 0;
     }
-    for (int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; s < count; s += waves) {
-        const int32_t v = a.rows ? a.rows[s] : (int32_t)s;
-        const int64_t off = a.in.off[v];
-        const int32_t deg = a.in.deg[v];
+    for (int64_t unit = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; unit < n_items + n_dst; unit += waves) {
+        float adv[NV], mcur[NV], den[NV];
+        float4 acc[NV];
+        if (unit < n_items) {
+            const int32_t chunk = a.hubs.item_chunk[unit];
+            const DstRec rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[unit]]];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)rec.v * H + head[q]] : 0.f;
+            gat_full_pass<NV>(a, rec.v, rec.off + (int64_t)chunk * NRT_CHUNK, min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK),
+                              false, lane, col, head, live, adv, mcur, den, acc);
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                if (!live[q]) continue;
+                if ((col[q] % hd) == 0) {
+                    a.part_m[unit * H + head[q]] = mcur[q];
+                    a.part_den[unit * H + head[q]] = den[q];
+                }
+                *reinterpret_cast<float4*>(a.hubs.partial + unit * D + col[q]) = acc[q];
+            }
+            continue;
+        }
+        const int64_t s = unit - n_items;
+        const DstRec rec = a.recs[s];
+        if (rec.deg > NRT_CHUNK) continue;
+        const int32_t v = rec.v;
+        const int64_t off = rec.off;
+        const int32_t deg = rec.deg;
         bool full = true;
         if (a.src_bitmap) {
             const bool own = (a.src_bitmap[v >> 5] >> (v & 31)) & 1u;
             const bool edge = (a.ddst_bitmap[v >> 5] >> (v & 31)) & 1u;
             full = own || edge;
         }
-        float adv[NV], mcur[NV], den[NV];
-        float4 acc[NV];
 #pragma unroll
         for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)v * H + head[q]] : 0.f;
 
@@ -98,19 +219,18 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 }
             }
             bool redo = false;
+            float den0[NV];
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
                 const float f = __expf(mold[q] - mcur[q]);
                 den[q] = live[q] ? a.DEN[(int64_t)v * H + head[q]] * f : 1.f;
+                den0[q] = den[q];
                 acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (live[q]) {
                     const float4 so = *reinterpret_cast<const float4*>(a.S + (int64_t)v * D + col[q]);
                     acc[q] = make_float4(so.x * f, so.y * f, so.z * f, so.w * f);
                 }
             }
-            float den0[NV];
-#pragma unroll
-            for (int q = 0; q < NV; ++q) den0[q] = den[q];
             // pass 2: exchange old terms for new ones
             for (int32_t j0 = 0; j0 < deg; j0 += 64) {
                 const int32_t jj = j0 + lane;
@@ -142,87 +262,65 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 if (live[q] && !(den[q] > den0[q] * (1.0f / 64.0f))) redo = true;
             full = __ballot(redo) != 0ULL;        // cancellation: recompute this destination over all its neighbours
         }
-        if (full) {
-            // ---- Algorithm 2: every in-neighbour of the new graph plus the self-loop
+        if (full) gat_full_pass<NV>(a, v, off, deg, true, lane, col, head, live, adv, mcur, den, acc);
+        gat_store<NV>(a, v, s, col, head, live, mcur, den, acc);
+    }
+}
+
+// one wave per hub: merge the partial triples of its items and its self-loop
+template <int NV>
+__global__ void __launch_bounds__(256) gat_combine_kernel(GatArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    int64_t nh = (int64_t)a.lc->n_hubs;
+    if (nh > a.hubs.hub_cap) nh = a.hubs.hub_cap;
+    const int H = a.heads, hd = a.head_dim, D = H * hd;
+    int col[NV], head[NV];
+    bool live[NV];
 #pragma unroll
-            for (int q = 0; q < NV; ++q)
-                mcur[q] = live[q] ? leaky(adv[q] + a.AS[(int64_t)v * H + head[q]], slope) : 0.f;
-            for (int32_t j0 = 0; j0 < deg; j0 += 64) {
-                const int32_t jj = j0 + lane;
-                const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
-                unsigned long long mask = __ballot(u >= 0);
-                while (mask) {
-                    const int bit = __ffsll((long long)mask) - 1;
-                    mask &= mask - 1;
-                    const int32_t uu = __builtin_amdgcn_readlane(u, bit);
-#pragma unroll
-                    for (int q = 0; q < NV; ++q)
-                        if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < NV; ++q) {
-                den[q] = 0.f;
-                acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (live[q]) {
-                    const float c = __expf(leaky(adv[q] + a.AS[(int64_t)v * H + head[q]], slope) - mcur[q]);
-                    const float4 z = *reinterpret_cast<const float4*>(a.Z + (int64_t)v * D + col[q]);
-                    den[q] = c;
-                    acc[q] = make_float4(c * z.x, c * z.y, c * z.z, c * z.w);
-                }
-            }
-            for (int32_t j0 = 0; j0 < deg; j0 += 64) {
-                const int32_t jj = j0 + lane;
-                const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
-                unsigned long long mask = __ballot(u >= 0);
-                while (mask) {
-                    const int b0 = __ffsll((long long)mask) - 1;
-                    mask &= mask - 1;
-                    const int32_t u0 = __builtin_amdgcn_readlane(u, b0);
-                    int32_t u1 = -1;
-                    if (mask) {
-                        const int b1 = __ffsll((long long)mask) - 1;
-                        mask &= mask - 1;
-                        u1 = __builtin_amdgcn_readlane(u, b1);
-                    }
-#pragma unroll
-                    for (int q = 0; q < NV; ++q) {
-                        if (!live[q]) continue;
-                        const float c0 = __expf(leaky(adv[q] + a.AS[(int64_t)u0 * H + head[q]], slope) - mcur[q]);
-                        const float4 z0 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u0 * D + col[q]);
-                        float c1 = 0.f;
-                        float4 z1 = make_float4(0.f, 0.f, 0.f, 0.f);
-                        if (u1 >= 0) {
-                            c1 = __expf(leaky(adv[q] + a.AS[(int64_t)u1 * H + head[q]], slope) - mcur[q]);
-                            z1 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u1 * D + col[q]);
-                        }
-                        den[q] += c0 + c1;
-                        acc[q].x += c0 * z0.x + c1 * z1.x; acc[q].y += c0 * z0.y + c1 * z1.y;
-                        acc[q].z += c0 * z0.z + c1 * z1.z; acc[q].w += c0 * z0.w + c1 * z1.w;
-                    }
-                }
-            }
-        }
-        // ---- store the context, the aggregate and the layer output  h = act(S / den + b)
+    for (int q = 0; q < NV; ++q) {
+        col[q] = lane * 4 + q * 256;
+        live[q] = col[q] < D;
+        head[q] = live[q] ? col[q] / hd : 0;
+    }
+    for (int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; h < nh; h += waves) {
+        const int64_t s = a.hubs.hub_slot[h];
+        const DstRec rec = a.recs[s];
+        const int32_t nch = (rec.deg + NRT_CHUNK - 1) / NRT_CHUNK;
+        const int64_t first = (int64_t)a.hubs.hub_first[h];
+        float mcur[NV], den[NV], eself[NV];
+        float4 acc[NV];
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
-            if (!live[q]) continue;
-            if ((col[q] % hd) == 0) {
-                a.M[(int64_t)v * H + head[q]] = mcur[q];
-                a.DEN[(int64_t)v * H + head[q]] = den[q];
-            }
-            *reinterpret_cast<float4*>(a.S + (int64_t)v * D + col[q]) = acc[q];
-            const float inv = 1.0f / den[q];
-            float y[4] = {acc[q].x * inv, acc[q].y * inv, acc[q].z * inv, acc[q].w * inv};
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                if (a.bias) y[t] += a.bias[col[q] + t];
-                if (a.act == 2) y[t] = y[t] > 0.f ? y[t] : expm1f(y[t]);
-            }
-            const float4 yo = make_float4(y[0], y[1], y[2], y[3]);
-            *reinterpret_cast<float4*>(a.Hout + (int64_t)v * D + col[q]) = yo;
-            if (a.out_rows && s < a.out_cap) *reinterpret_cast<float4*>(a.out_rows + s * D + col[q]) = yo;
+            eself[q] = live[q] ? leaky(a.AD[(int64_t)rec.v * H + head[q]] + a.AS[(int64_t)rec.v * H + head[q]], a.slope) : 0.f;
+            mcur[q] = eself[q];
         }
+        for (int32_t c = 0; c < nch; ++c)
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                if (live[q]) mcur[q] = fmaxf(mcur[q], a.part_m[(first + c) * H + head[q]]);
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            den[q] = 0.f;
+            acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (live[q]) {
+                const float cs = __expf(eself[q] - mcur[q]);
+                const float4 z = *reinterpret_cast<const float4*>(a.Z + (int64_t)rec.v * D + col[q]);
+                den[q] = cs;
+                acc[q] = make_float4(cs * z.x, cs * z.y, cs * z.z, cs * z.w);
+            }
+        }
+        for (int32_t c = 0; c < nch; ++c) {
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                if (!live[q]) continue;
+                const float f = __expf(a.part_m[(first + c) * H + head[q]] - mcur[q]);
+                const float4 p = *reinterpret_cast<const float4*>(a.hubs.partial + (first + c) * D + col[q]);
+                den[q] += f * a.part_den[(first + c) * H + head[q]];
+                acc[q].x += f * p.x; acc[q].y += f * p.y; acc[q].z += f * p.z; acc[q].w += f * p.w;
+            }
+        }
+        gat_store<NV>(a, rec.v, s, col, head, live, mcur, den, acc);
     }
 }
 
@@ -238,13 +336,10 @@ nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s) {
 
 nrt_status k_gat_gather(const GatArgs& a, hipStream_t s) {
     const int D = a.heads * a.head_dim;
-    const int64_t bound = a.rows ? a.rows_bound : a.n;
-    if (bound <= 0) return NRT_OK;
-    int64_t g = cdiv(bound, 4);
-    if (g > 16384) g = 16384;
-    if (D <= 256) gat_gather_kernel<1><<<(int)g, 256, 0, s>>>(a);
-    else if (D <= 512) gat_gather_kernel<2><<<(int)g, 256, 0, s>>>(a);
-    else gat_gather_kernel<4><<<(int)g, 256, 0, s>>>(a);
+    const int g = 8192;                     // fixed grid: sizes are read on the device
+    if (D <= 256) { gat_gather_kernel<1><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<1><<<2048, 256, 0, s>>>(a); }
+    else if (D <= 512) { gat_gather_kernel<2><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<2><<<2048, 256, 0, s>>>(a); }
+    else { gat_gather_kernel<4><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<4><<<2048, 256, 0, s>>>(a); }
     LAUNCH_CHECK();
     return NRT_OK;
 }
