@@ -19,6 +19,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
+INFINITY_CACHE_BYTES = 256 * 1024 * 1024
 
 
 def main():
@@ -89,9 +90,12 @@ def main():
         for l in range(L):
             ls = st.layer[l]
             d_in = dims[l]
-            # algorithmic bytes of the gather launch: per delta message its in-list id and slot-map entry (8 B),
-            # every changed source row once (4*d), every affected aggregate row read and written (8*d)
-            gbytes = ls.n_pairs * 8.0 + ls.n_src * 4.0 * d_in + ls.n_affected * 8.0 * d_in if ls.n_src else 0.0
+            # algorithmic bytes of the gather launch: per delta message its in-list id and slot-map entry (8 B);
+            # the delta rows: every changed source row once (4*d) while the delta buffer fits the 256 MB Infinity
+            # Cache, else one row per delta message; every affected aggregate row read and written (8*d)
+            d_agg = dims[l + 1] if cfg.spec.kind == wl.GAT else d_in
+            row_fetches = ls.n_src if ls.n_src * 4.0 * d_agg <= INFINITY_CACHE_BYTES else ls.n_pairs
+            gbytes = ls.n_pairs * 8.0 + row_fetches * 4.0 * d_agg + ls.n_affected * 8.0 * d_agg if ls.n_src else 0.0
             kin = (2 if cfg.spec.kind == wl.SAGE_MEAN else 1) * d_in
             flop = 2.0 * ls.n_affected * kin * dims[l + 1]
             if cfg.spec.kind == wl.GIN:

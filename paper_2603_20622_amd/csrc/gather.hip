@@ -162,6 +162,7 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
     if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
     const int64_t total = n_dst + n_items;
     int upw = (int)(total / 16384);                        // units per wave: keep ~16k waves when there is enough work
+                                                           // (more units per wave = fewer pipeline fill/drain bubbles)
     upw = upw < 1 ? 1 : (upw > MAX_UPW ? MAX_UPW : upw);
     const int64_t n_chunks = (total + upw - 1) / upw;
     const int64_t n_waves = (int64_t)gridDim.x * WAVES_PER_BLOCK;

@@ -25,33 +25,29 @@ constexpr int BM = 128;
 
 __device__ inline float gcn_scale(int32_t indeg) { return 1.0f / sqrtf((float)(indeg + 1)); }
 
-// Branch-free on purpose: the address is clamped into the row and the value masked afterwards, so that the
-// loads of one slice are issued back to back instead of each waiting behind its own bounds branch.
+// Branch-free on purpose: the address is clamped into the row, the raw value stays in registers and the mask /
+// scale `mul` is applied only when the slice is written to LDS one iteration later, so that the loads of a slice
+// are issued back to back and nothing waits for them before the MFMAs of the current slice have been issued.
 template <int AMODE>
-__device__ inline float4 load_a(const GemmArgs& g, int64_t v, float sc, int k, bool ok) {
+__device__ inline void load_a(const GemmArgs& g, int64_t v, float sc, int k, bool ok, float4& raw, float4& raw2, float& mul) {
     const bool live = ok && k < g.K;
     const int kc = k < g.K ? k : g.K - 4;
-    float4 r;
     float m = 1.0f;
     if (AMODE == A_PLAIN) {
-        r = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
+        raw = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
     } else if (AMODE == A_SCALE_GCN) {
-        r = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
+        raw = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
         m = sc;
     } else if (AMODE == A_CONCAT_MEAN) {
         const bool self = kc < g.ldp;
         const float* p = (self ? g.P0 : g.P1) + v * g.ldp + (self ? kc : kc - g.ldp);
-        r = *reinterpret_cast<const float4*>(p);
+        raw = *reinterpret_cast<const float4*>(p);
         m = self ? 1.0f : sc;
     } else {
-        const float4 p = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
-        const float4 q = *reinterpret_cast<const float4*>(g.P1 + v * g.ldp + kc);
-        r.x = fmaf(g.axpy_c, p.x, q.x); r.y = fmaf(g.axpy_c, p.y, q.y);
-        r.z = fmaf(g.axpy_c, p.z, q.z); r.w = fmaf(g.axpy_c, p.w, q.w);
+        raw = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
+        raw2 = *reinterpret_cast<const float4*>(g.P1 + v * g.ldp + kc);
     }
-    m = live ? m : 0.0f;
-    r.x *= m; r.y *= m; r.z *= m; r.w *= m;
-    return r;
+    mul = live ? m : 0.0f;
 }
 
 template <int BN, int WM, int WN, int AMODE, int KT>
@@ -97,19 +93,18 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    float4 ra[A_LOADS], rb[B_LOADS];
+    float4 ra[A_LOADS], ra2[AMODE == A_AXPY ? A_LOADS : 1], rb[B_LOADS];
+    float am[A_LOADS], bmul[B_LOADS];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int p = 0; p < A_LOADS; ++p) ra[p] = load_a<AMODE>(g, av[p], asc[p], k0 + lk, aok[p]);
+        for (int p = 0; p < A_LOADS; ++p) load_a<AMODE>(g, av[p], asc[p], k0 + lk, aok[p], ra[p], ra2[AMODE == A_AXPY ? p : 0], am[p]);
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
             const int n = col_base + lr + RPP * p;
             const int k = k0 + lk;
             const int nc = n < g.N ? n : g.N - 1, kc = k < g.K ? k : g.K - 4;
-            float4 t = *reinterpret_cast<const float4*>(g.Wt + (int64_t)nc * g.K + kc);
-            const float m = (n < g.N && k < g.K) ? 1.0f : 0.0f;
-            t.x *= m; t.y *= m; t.z *= m; t.w *= m;
-            rb[p] = t;
+            rb[p] = *reinterpret_cast<const float4*>(g.Wt + (int64_t)nc * g.K + kc);
+            bmul[p] = (n < g.N && k < g.K) ? 1.0f : 0.0f;
         }
     };
 
@@ -117,11 +112,22 @@ __global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
     const int half = lane >> 5, l32 = lane & 31;
     for (int k0 = 0; k0 < g.K; k0 += KT) {
 #pragma unroll
-        for (int p = 0; p < A_LOADS; ++p)
-            *reinterpret_cast<float4*>(&As[(lr + RPP * p) * LDS_STRIDE + lk]) = ra[p];
+        for (int p = 0; p < A_LOADS; ++p) {
+            float4 t = ra[p];
+            if (AMODE == A_AXPY) {
+                const float4 q = ra2[p];
+                t.x = fmaf(g.axpy_c, t.x, q.x); t.y = fmaf(g.axpy_c, t.y, q.y);
+                t.z = fmaf(g.axpy_c, t.z, q.z); t.w = fmaf(g.axpy_c, t.w, q.w);
+            }
+            t.x *= am[p]; t.y *= am[p]; t.z *= am[p]; t.w *= am[p];
+            *reinterpret_cast<float4*>(&As[(lr + RPP * p) * LDS_STRIDE + lk]) = t;
+        }
 #pragma unroll
-        for (int p = 0; p < B_LOADS; ++p)
-            *reinterpret_cast<float4*>(&Bs[(lr + RPP * p) * LDS_STRIDE + lk]) = rb[p];
+        for (int p = 0; p < B_LOADS; ++p) {
+            float4 t = rb[p];
+            t.x *= bmul[p]; t.y *= bmul[p]; t.z *= bmul[p]; t.w *= bmul[p];
+            *reinterpret_cast<float4*>(&Bs[(lr + RPP * p) * LDS_STRIDE + lk]) = t;
+        }
         __syncthreads();
         if (k0 + KT < g.K) fetch(k0 + KT);
 #pragma unroll
