@@ -150,6 +150,7 @@ def main():
         "roofline": roofline,
         "update_gemm": {"bound": "mfma", "achieved": round(upd_tflops, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(upd_tflops / FP32_MFMA_PEAK_TFLOPS, 4)},
+        "gpu_full_forward_ms": round(ses.cache.init_ms, 3),   # nrt_cache_init: full-neighbour L-layer forward on the GPU
         "phase_ms_per_step": {k[:-3]: round(v / K, 4) for k, v in agg.items() if k.endswith("_ms")},
         "per_layer_avg": [{"layer": l + 1, "n_src": pl["n_src"] / K, "n_affected": pl["n_aff"] / K,
                            "delta_messages": pl["n_pairs"] / K, "in_edges_scanned": pl["n_in"] / K,

@@ -9,6 +9,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import time
 from typing import List, Optional
 
 import torch
@@ -216,9 +217,13 @@ def nrt_cache_init(g: Graph, desc: nrt_model_desc, features: torch.Tensor, max_b
                    max_batch_feats: int) -> Cache:
     ws = _workspace(nrt_cache_workspace_bytes(g, desc, max_batch_edges, max_batch_feats))
     h = ctypes.c_void_p()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
     _check(lib().nrt_cache_init(g.handle, ctypes.byref(desc), _ptr(features), max_batch_edges, max_batch_feats,
                                 ctypes.c_void_p(ws.data_ptr()), ws.numel(), _stream(), ctypes.byref(h)))
-    return Cache(h, ws, g, desc)
+    c = Cache(h, ws, g, desc)
+    c.init_ms = (time.perf_counter() - t0) * 1e3      # the call synchronises the stream before it returns
+    return c
 
 
 def make_batch(ins_src=None, ins_dst=None, ins_w=None, del_src=None, del_dst=None, feat_ids=None,

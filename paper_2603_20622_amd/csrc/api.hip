@@ -61,6 +61,8 @@ struct nrt_cache {
     float* AS_old;
     float *part_m, *part_den;
     bool is_gat;
+    float* SD[NRT_MAX_LAYERS + 1];      // structural-delta rows of a batch, [max_edges][dagg[l]]
+    int32_t *list_dd, *slot_dd;         // destinations of updated edges: sorted ids, vertex -> row of SD
     DstRec* recs;
     HubWork hubs;
     BatchScratch sc;
@@ -262,6 +264,9 @@ static void cache_layout(Bump& b, nrt_cache* c) {
             c->att_dst[l - 1] = b.take<float>((size_t)c->heads * c->head_dim);
         }
     }
+    for (int l = 1; l <= c->L; ++l) c->SD[l] = gat ? nullptr : b.take<float>((size_t)(c->max_edges + 1) * c->dagg[l]);
+    c->list_dd = b.take<int32_t>(c->max_edges + 64);
+    c->slot_dd = b.take<int32_t>(n);
     c->AS_old = gat ? b.take<float>(n * c->heads) : nullptr;
     c->is_gat = gat;
     for (int l = 0; l < c->L; ++l) {
@@ -373,6 +378,12 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hi
         a.n_src_dev = &c->lc[l - 1].count;
         a.src_scale_gcn = 0;
         a.accumulate = 1;
+        a.sd = c->SD[l];
+        a.dd_bitmap = c->bm_ddst;
+        a.dd_slot = c->slot_dd;
+        a.guard = c->kind == NRT_GIN;            // un-normalised sums: a fold can cancel most of a row's magnitude
+        a.Pfull = c->H[l - 1];
+        a.full_scale_gcn = c->kind == NRT_GCN;
         if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     } else {
         a.P = c->H[l - 1];
@@ -667,6 +678,13 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     if (c->profiling) NRT_TRY(k_fill_u64((uint64_t*)c->pair_ctr, 1024 * NRT_MAX_LAYERS, 0, s));
     NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
     if (gcn) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
+    if (c->kind != NRT_GAT && b->n_ins + b->n_del > 0) {
+        // destinations of updated edges -> compact rows that collect their structural terms (bm[1] is scratch here)
+        NRT_TRY(k_compact(nullptr, c->bm_ddst, nullptr, c->bm[1], n, c->list_dd, c->slot_dd, g->scan_tmp, g->scan_tmp_len,
+                          (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
+        for (int l = 1; l <= c->L; ++l)
+            NRT_TRY(k_fill_u32((uint32_t*)c->SD[l], (b->n_ins + b->n_del) * (int64_t)c->dagg[l], 0, s));
+    }
 
     // ---- structural terms on the old caches, all layers in one launch (GAT recomputes those destinations in full)
     if (c->kind != NRT_GAT) {
@@ -677,9 +695,10 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         if (c->kind == NRT_GIN && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
         f.indeg_old = gcn ? g->in.deg : nullptr;
         f.n_layers = c->L;
+        f.dd_slot = c->slot_dd;
         for (int l = 1; l <= c->L; ++l) {
             f.Hprev[l - 1] = c->H[l - 1];
-            f.S[l - 1] = c->S[l];
+            f.SD[l - 1] = c->SD[l];
             f.D[l - 1] = c->dagg[l];
         }
         NRT_TRY(k_structural_fold(f, s));

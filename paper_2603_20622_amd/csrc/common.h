@@ -139,6 +139,16 @@ struct GatherArgs {
     int accumulate;            // 1: S[v] += sum, 0: S[v] = sum
     float* S;                  // [N][D]
     unsigned long long* pair_ctr; // null or 1024 counters
+    // structural terms of the batch (inserted / deleted in-edges), one compact row per destination of an updated
+    // edge, added by the wave that owns the destination (null: none)
+    const float* sd;
+    const uint32_t* dd_bitmap; // destinations of updated edges
+    const int32_t* dd_slot;    // their rows in sd
+    // cancellation guard: when a fold removes most of a row's magnitude the row is rebuilt from the full
+    // in-neighbourhood, rows read from Pfull (the current h^{l-1})
+    int guard;
+    const float* Pfull;
+    int full_scale_gcn;
 };
 // destination records of list[0 .. *count) (list null: all n vertices), hub list and hub items; fills lc
 nrt_status k_dst_records(const int32_t* list, int64_t bound, const Adj& in, DstRec* recs, const HubWork& hubs,
@@ -152,7 +162,8 @@ struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update 
     const float *ins_w, *del_w;  // null when unweighted
     int n_layers;                // blockIdx.y walks the layers
     const float* Hprev[NRT_MAX_LAYERS];   // h^{l-1} (old)
-    float* S[NRT_MAX_LAYERS];
+    float* SD[NRT_MAX_LAYERS];            // compact structural-delta rows, one per destination of an updated edge
+    const int32_t* dd_slot;               // vertex -> row of SD
     int D[NRT_MAX_LAYERS];
     const int32_t* indeg_old;    // for the GCN payload scale, else null
 };

@@ -145,6 +145,68 @@ dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, Hub
 //      with a lane read, so the row address is wave-uniform and the row load is one coalesced instruction
 //      (rows narrower than 256 floats put RPI = 2 or 4 survivors into one load, one per LPR-lane sub-group);
 //      on the last step of a unit reduce the sub-groups and write the row.
+// Rebuild the aggregate row of v from its whole in-neighbourhood with current values (the full-neighbour
+// definition, Eq. 1): the fallback when an incremental fold has cancelled the leading digits of a row.
+template <int LPR, int NV>
+__device__ inline void full_row(const GatherArgs& a, int32_t v, int64_t off, int32_t deg, int lane, float4 (&acc)[NV]) {
+    constexpr int RPI = 64 / LPR;
+    const int sub = lane / LPR, gl = lane % LPR, D = a.D;
+    const float* Pl = a.Pfull + gl * 4;
+#pragma unroll
+    for (int q = 0; q < NV; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int32_t j0 = 0; j0 < deg; j0 += 64) {
+        const int32_t jj = j0 + lane;
+        const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+        float c = 1.0f;
+        if (u >= 0 && a.use_weights) c = a.in.wts[off + jj];
+        if (u >= 0 && a.full_scale_gcn) c *= gcn_scale(a.in.deg[u]);
+        unsigned long long m = __ballot(u >= 0);
+        while (m) {
+            int32_t rr = -1;
+            float cc = 0.f;
+#pragma unroll
+            for (int t = 0; t < RPI; ++t) {
+                if (m) {
+                    const int bit = __ffsll((long long)m) - 1;
+                    m &= m - 1;
+                    const int32_t rs = __builtin_amdgcn_readlane(u, bit);
+                    const float cs = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, c), bit));
+                    if (sub == t) { rr = rs; cc = cs; }
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                if (rr >= 0 && gl * 4 + q * LPR * 4 < D)
+                    acc[q] = f4_fma(cc, *reinterpret_cast<const float4*>(Pl + (int64_t)rr * D + q * LPR * 4), acc[q]);
+        }
+    }
+    if (a.self_pair && sub == 0) {
+        const float cs = a.full_scale_gcn ? gcn_scale(deg) : 1.0f;
+#pragma unroll
+        for (int q = 0; q < NV; ++q)
+            if (gl * 4 + q * LPR * 4 < D)
+                acc[q] = f4_fma(cs, *reinterpret_cast<const float4*>(Pl + (int64_t)v * D + q * LPR * 4), acc[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < NV; ++q)
+#pragma unroll
+        for (int mm = LPR; mm < 64; mm <<= 1) acc[q] = f4_add(acc[q], f4_shfl_xor(acc[q], mm));
+}
+
+// largest |component| over the lanes of a wave (lanes outside `use` contribute 0)
+template <int NV>
+__device__ inline float wave_absmax(const float4 (&x)[NV], bool use) {
+    float m = 0.f;
+    if (use) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) m = fmaxf(m, fmaxf(fmaxf(fabsf(x[q].x), fabsf(x[q].y)), fmaxf(fabsf(x[q].z), fabsf(x[q].w))));
+    }
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) m = fmaxf(m, __shfl_xor(m, s, 64));
+    return m;
+}
+constexpr float GUARD_RATIO = 16.0f;     // rebuild a row when the fold is 16x larger than what it leaves behind
+
 // Step flags kept in the per-wave step table.
 enum { SF_FIRST = 1, SF_LAST = 2, SF_PART = 4, SF_SELF = 8 };
 
@@ -156,7 +218,7 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int sub = lane / LPR, gl = lane % LPR;
     const int D = a.D;
-    if (a.n_src_dev && *a.n_src_dev == 0) return;          // nothing changed upstream of this layer
+    if (a.n_src_dev && *a.n_src_dev == 0 && !a.sd) return;   // nothing changed upstream of this layer
     const int64_t n_dst = (int64_t)a.lc->count;
     int64_t n_items = (int64_t)a.lc->n_items;
     if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
@@ -348,19 +410,42 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
                         pairs += 1;
                     }
                 }
+                if ((f & SF_SELF) && a.sd) {                 // structural terms of the batch for this destination
+                    const int32_t v = __builtin_amdgcn_readlane(t_v, i - 3);
+                    if ((a.dd_bitmap[v >> 5] >> (v & 31)) & 1u) {
+                        const float* sp = a.sd + (int64_t)a.dd_slot[v] * D + gl * 4;
+#pragma unroll
+                        for (int q = 0; q < NV; ++q)
+                            if (sub == 0 && gl * 4 + q * LPR * 4 < D)
+                                acc[q] = f4_add(acc[q], *reinterpret_cast<const float4*>(sp + q * LPR * 4));
+                    }
+                }
                 if (f & SF_LAST) {
                     const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane(t_out_lo, i - 3);
                     const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane(t_out_hi, i - 3);
                     float* op = ((f & SF_PART) ? a.hubs.partial : a.S) + (int64_t)(((uint64_t)hi << 32) | lo) + gl * 4;
+                    const bool fold = !(f & SF_PART) && a.accumulate;
 #pragma unroll
-                    for (int q = 0; q < NV; ++q) {
+                    for (int q = 0; q < NV; ++q)
 #pragma unroll
                         for (int mm = LPR; mm < 64; mm <<= 1) acc[q] = f4_add(acc[q], f4_shfl_xor(acc[q], mm));
-                        if (sub == 0 && gl * 4 + q * LPR * 4 < D) {
-                            float4 y = acc[q];
-                            if (!(f & SF_PART) && a.accumulate) y = f4_add(y, oldD[q]);
-                            *reinterpret_cast<float4*>(op + q * LPR * 4) = y;
+                    float4 y[NV];
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) y[q] = fold ? f4_add(acc[q], oldD[q]) : acc[q];
+                    if (fold && a.guard) {
+                        const float big = wave_absmax<NV>(acc, sub == 0), left = wave_absmax<NV>(y, sub == 0);
+                        if (big > GUARD_RATIO * left) {          // the fold cancelled the row: rebuild it in full
+                            const int32_t v = __builtin_amdgcn_readlane(t_v, i - 3);
+                            const int32_t dg = __builtin_amdgcn_readlane(t_deg, i - 3);
+                            const uint32_t blo = (uint32_t)__builtin_amdgcn_readlane(t_base_lo, i - 3);
+                            const uint32_t bhi = (uint32_t)__builtin_amdgcn_readlane(t_base_hi, i - 3);
+                            const int64_t off = (int64_t)(((uint64_t)bhi << 32) | blo) - __builtin_amdgcn_readlane(t_j, i - 3);
+                            full_row<LPR, NV>(a, v, off, dg, lane, y);
                         }
+                    }
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) {
+                        if (sub == 0 && gl * 4 + q * LPR * 4 < D) *reinterpret_cast<float4*>(op + q * LPR * 4) = y[q];
                         acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
                     }
                 }
@@ -378,7 +463,7 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
 
 // one wave per hub (strided): sum its partial rows in item order into the cached aggregate
 __global__ void combine_kernel(GatherArgs a) {
-    if (a.n_src_dev && *a.n_src_dev == 0) return;
+    if (a.n_src_dev && *a.n_src_dev == 0 && !a.sd) return;
     const int lane = threadIdx.x & 63;
     int64_t nh = (int64_t)a.lc->n_hubs;
     if (nh > a.hubs.hub_cap) nh = a.hubs.hub_cap;
@@ -388,6 +473,7 @@ __global__ void combine_kernel(GatherArgs a) {
         const DstRec rec = a.recs[a.hubs.hub_slot[h]];
         const int32_t nch = (rec.deg + NRT_CHUNK - 1) / NRT_CHUNK;
         const int64_t first = (int64_t)a.hubs.hub_first[h];
+        float big = 0.f, left = 0.f;
         for (int col = lane * 4; col < D; col += 256) {
             const float* p = a.hubs.partial + first * D + col;
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -401,14 +487,37 @@ __global__ void combine_kernel(GatherArgs a) {
             }
             for (; c < nch; ++c) acc = f4_add(acc, *reinterpret_cast<const float4*>(p + (int64_t)c * D));
             float4* dst = reinterpret_cast<float4*>(a.S + (int64_t)rec.v * D + col);
-            if (a.accumulate) acc = f4_add(acc, *dst);
-            *dst = acc;
+            float4 y = acc;
+            if (a.accumulate) y = f4_add(acc, *dst);
+            *dst = y;
+            if (a.accumulate && a.guard) {
+                big = fmaxf(big, fmaxf(fmaxf(fabsf(acc.x), fabsf(acc.y)), fmaxf(fabsf(acc.z), fabsf(acc.w))));
+                left = fmaxf(left, fmaxf(fmaxf(fabsf(y.x), fabsf(y.y)), fmaxf(fabsf(y.z), fabsf(y.w))));
+            }
+        }
+        if (a.accumulate && a.guard) {
+#pragma unroll
+            for (int s = 32; s >= 1; s >>= 1) { big = fmaxf(big, __shfl_xor(big, s, 64)); left = fmaxf(left, __shfl_xor(left, s, 64)); }
+            if (big > GUARD_RATIO * left) {                  // cancelled: rebuild the hub's row in full
+                if (D <= 256) {
+                    float4 full[1];
+                    full_row<64, 1>(a, rec.v, rec.off, rec.deg, lane, full);
+                    if (lane * 4 < D) *reinterpret_cast<float4*>(a.S + (int64_t)rec.v * D + lane * 4) = full[0];
+                } else {
+                    float4 full[4];
+                    full_row<64, 4>(a, rec.v, rec.off, rec.deg, lane, full);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        if (lane * 4 + q * 256 < D) *reinterpret_cast<float4*>(a.S + (int64_t)rec.v * D + lane * 4 + q * 256) = full[q];
+                }
+            }
         }
     }
 }
 
 // ------------------------------------------------------------------ structural fold
-// one wave per (updated edge, layer): S^l[dst] += sign * c * p^{l-1}_src(old)
+// one wave per (updated edge, layer): SD^l[slot(dst)] += sign * c * p^{l-1}_src(old); the gather wave that owns
+// dst adds the row to the cached aggregate, so the aggregate itself is never touched by atomics
 __global__ void structural_fold_kernel(FoldArgs a) {
     const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
@@ -424,7 +533,7 @@ __global__ void structural_fold_kernel(FoldArgs a) {
     if (a.indeg_old) c *= gcn_scale(a.indeg_old[u]);
     const int D = a.D[l];
     const float* src = a.Hprev[l] + (int64_t)u * D;
-    float* dst = a.S[l] + (int64_t)v * D;
+    float* dst = a.SD[l] + (int64_t)a.dd_slot[v] * D;
     for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, c * src[k]);
 }
 
