@@ -10,7 +10,7 @@
 // change of the source payload dp = y_new*cn - y_old*co (cn = co = 1 except for GCN, where the payload is
 // y / sqrt(d_v) and the degree may have changed), so no separate pass re-reads the rows.
 //
-// Tiling: 256 threads = 4 waves; block tile 128 x BN; K is consumed in slices of 32 staged through LDS
+// Tiling: 4 waves (8 for the 256-wide tile); block tile 128 x BN; K is consumed in slices of 32 staged through LDS
 // (rows padded to 36 floats so that the 16-byte operand reads of 8 neighbouring lanes cover all banks).
 // Each wave owns (TM x TN) 32x32 accumulator tiles fed by v_mfma_f32_32x32x2_f32: lane = (i mod 32, half),
 // the two halves supply two different k, so one 16-byte LDS read per operand feeds four MFMAs.
@@ -51,13 +51,14 @@ __device__ inline void load_a(const GemmArgs& g, int64_t v, float sc, int k, boo
 }
 
 template <int BN, int WM, int WN, int AMODE, int KT>
-__global__ void __launch_bounds__(256) gemm_kernel(GemmArgs g) {
+__global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
+    constexpr int NT = WM * WN * 64;       // threads of the workgroup
     constexpr int LDS_STRIDE = KT + 4;
     constexpr int TPR = KT / 4;            // threads that stage one row of a slice
-    constexpr int RPP = 256 / TPR;         // rows staged per pass
+    constexpr int RPP = NT / TPR;          // rows staged per pass
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-    constexpr int A_LOADS = BM * KT / 4 / 256;   // float4 per thread per slice
-    constexpr int B_LOADS = BN * KT / 4 / 256;
+    constexpr int A_LOADS = BM * KT / 4 / NT;    // float4 per thread per slice
+    constexpr int B_LOADS = BN * KT / 4 / NT;
     __shared__ __attribute__((aligned(16))) float As[BM * LDS_STRIDE];
     __shared__ __attribute__((aligned(16))) float Bs[BN * LDS_STRIDE];
 
@@ -218,7 +219,7 @@ static void launch_gemm(const GemmArgs& g, hipStream_t s) {
     int64_t tiles = cdiv(g.M, BM);
     if (g.M_dev && tiles > 2048) tiles = 2048;               // device-sized problem: a fixed grid strides over the tiles
     const unsigned gx = (unsigned)tiles;
-    if (g.N > 128) gemm_kernel<256, 2, 2, AMODE, 32><<<dim3(gx, (unsigned)cdiv(g.N, 256)), 256, 0, s>>>(g);
+    if (g.N > 128) gemm_kernel<256, 4, 2, AMODE, 32><<<dim3(gx, (unsigned)cdiv(g.N, 256)), 512, 0, s>>>(g);
     else if (g.N > 64) gemm_kernel<128, 2, 2, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
     else if (g.N > 32) gemm_kernel<64, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
     else gemm_kernel<32, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);

@@ -243,3 +243,93 @@ def test_gin_cancellation_is_guarded(S, oracle):
     after = oracle.forward(spec, params, n, *cur)
     for l in range(1, 4):
         assert row_err(ses.layer(l).cpu().numpy(), after[l - 1]) <= TOL, l
+
+
+@pytest.mark.parametrize("kind,dims,heads,head_dim", [
+    (wl.GCN, [16, 8, 4], 1, 0),                 # rows narrower than one 64-lane load (16 lanes per row, masked)
+    (wl.SAGE_MEAN, [512, 40, 12], 1, 0),        # 512-wide aggregate: two 16-byte loads per lane; K = 1024 update
+    (wl.GIN, [260, 132, 20], 1, 0),             # widths that are multiples of 4 only
+    (wl.GAT, [24, 512, 512], 8, 64),            # 512-wide attention rows, 8 heads
+    (wl.GAT, [12, 8, 8], 2, 4),                 # smallest head width
+])
+def test_unusual_widths(S, oracle, kind, dims, heads, head_dim):
+    n, e = 1500, 20000
+    src, dst, sampler = wl.rmat_graph(n, e, 31)
+    weighted = kind == wl.GIN
+    w = wl.edge_weights(e, 31) if weighted else None
+    spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=head_dim, weighted=weighted)
+    params = wl.make_params(spec, 31, bias=True)
+    x = wl.features(n, dims[0], 31)
+    stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], 31)
+    ses = S.Session(spec, params, n, src, dst, w, x)
+    ref = oracle.forward(spec, params, n, src, dst, w, x)
+    for l in range(1, 3):
+        assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], ("init", kind, l))
+    cur = (src, dst, w, x)
+    for k in range(3):
+        b = stream.next_batch(25, 25, 6)
+        na = ses.apply(b)
+        cur = oracle.apply_batch(n, *cur, b)
+        ref = oracle.forward(spec, params, n, *cur)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1])
+        for l in range(1, 3):
+            assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, k, l))
+
+
+def test_single_layer_and_four_layers(S, oracle):
+    for L, dims in ((1, [32, 8]), (4, [16, 32, 32, 16, 8])):
+        n, e = 1200, 9000
+        src, dst, sampler = wl.rmat_graph(n, e, 41)
+        spec = wl.ModelSpec(wl.GCN, dims)
+        params = wl.make_params(spec, 41)
+        x = wl.features(n, dims[0], 41)
+        stream = wl.BatchStream(n, src, dst, None, sampler, dims[0], 41)
+        ses = S.Session(spec, params, n, src, dst, None, x)
+        b = stream.next_batch(20, 20, 5)
+        na = ses.apply(b)
+        cur = oracle.apply_batch(n, src, dst, None, x, b)
+        ref = oracle.forward(spec, params, n, *cur)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1])
+        assert rel_err(ses.layer(L).cpu().numpy(), ref[-1]) <= TOL
+
+
+def test_edgeless_graph_and_feature_only_batches(S, oracle):
+    """No edges at all, then only feature replacements, then inserts into the empty graph."""
+    n = 300
+    spec = wl.ModelSpec(wl.SAGE_MEAN, [8, 8, 4])
+    params = wl.make_params(spec, 51)
+    x = wl.features(n, 8, 51)
+    e0 = np.empty(0, np.int32)
+    ses = S.Session(spec, params, n, e0, e0.copy(), None, x, e_capacity=4096)
+    ref = oracle.forward(spec, params, n, e0, e0, None, x)
+    assert rel_err(ses.layer(2).cpu().numpy(), ref[-1]) <= TOL
+    b = wl.empty_batch(8)
+    b.feat_ids = np.array([5, 17], np.int32)
+    b.feat_rows = np.ones((2, 8), np.float32)
+    assert ses.apply(b) == 2
+    cur = oracle.apply_batch(n, e0, e0, None, x, b)
+    b2 = wl.empty_batch(8)
+    b2.ins_src = np.array([5, 17, 9], np.int32)
+    b2.ins_dst = np.array([17, 9, 5], np.int32)
+    na = ses.apply(b2)
+    cur = oracle.apply_batch(n, *cur, b2)
+    sets = oracle.affected_sets(spec, n, cur[0], cur[1], b2)
+    assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1])
+    assert rel_err(ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1]) <= TOL
+
+
+def test_capacity_too_small_still_updates_caches(S, oracle):
+    import torch
+    from paper_2603_20622_amd import binding as nb
+    n, src, dst, w, x, spec, params, stream = small_case(wl.GCN, seed=61, n=600, e=5000)
+    ses = S.Session(spec, params, n, src, dst, w, x)
+    b = stream.next_batch(10, 10, 2)
+    small_ids = torch.empty(3, dtype=torch.int32, device="cuda")
+    db = S.DeviceBatch(b)
+    with pytest.raises(nb.NrtError) as ei:
+        nb.nrt_apply_batch(ses.cache, db.struct, small_ids, None)
+    assert ei.value.status == nb.NRT_ERR_INVALID_ARG
+    cur = oracle.apply_batch(n, src, dst, w, x, b)
+    assert rel_err(ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1]) <= TOL
