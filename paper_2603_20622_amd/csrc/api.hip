@@ -67,6 +67,8 @@ struct nrt_cache {
     HubWork hubs;
     BatchScratch sc;
     unsigned long long* pair_ctr;
+    uint32_t* coarse;          // coarse changed-source filter of the current layer
+    int coarse_shift, coarse_words;
     // profiling
     int profiling;
     hipEvent_t ev[MAX_EVENTS];
@@ -319,6 +321,10 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->sc.feat_stamp = b.take<int32_t>(n);
     c->sc.err = g->dev_ctrs ? (int32_t*)(g->dev_ctrs + CTR_ERR) : nullptr;
     c->pair_ctr = b.take<unsigned long long>(1024 * NRT_MAX_LAYERS);
+    c->coarse = b.take<uint32_t>(NRT_COARSE_WORDS);
+    c->coarse_shift = 0;
+    while ((((n + ((int64_t)1 << c->coarse_shift) - 1) >> c->coarse_shift) + 31) / 32 > NRT_COARSE_WORDS) ++c->coarse_shift;
+    c->coarse_words = (int)((((n + ((int64_t)1 << c->coarse_shift) - 1) >> c->coarse_shift) + 31) / 32);
 }
 
 static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_desc* d, int64_t max_edges,
@@ -384,6 +390,12 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hi
         a.guard = c->kind == NRT_GIN;            // un-normalised sums: a fold can cancel most of a row's magnitude
         a.Pfull = c->H[l - 1];
         a.full_scale_gcn = c->kind == NRT_GCN;
+        a.sparse_ok = 1;
+        a.n_vertices = g->n;
+        a.coarse = c->coarse;
+        a.coarse_shift = c->coarse_shift;
+        a.coarse_words = c->coarse_words;
+        NRT_TRY(k_coarse_bitmap(c->bm[prev], g->n, c->coarse_shift, c->coarse, c->coarse_words, s));
         if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     } else {
         a.P = c->H[l - 1];

@@ -9,6 +9,7 @@
 // layout of the device counter block (int64 cells) mirrored to pinned host memory in one copy
 enum { CTR_GROW = 0 /*2*/, CTR_HEAD_OUT = 8, CTR_HEAD_IN = 9, CTR_ERR = 16 /*8 x int32*/, CTR_COUNT = 24,
        CTR_ITEMS = 25 /* low 32 items, high 32 partial rows */, CTR_MULTI = 26, CTR_INEDGES = 27, NRT_NCTRS = 64 };
+#define NRT_COARSE_WORDS 6144  // 24 KiB of LDS for the coarse changed-source filter of the sparse gather
 #define NRT_CHUNK 256          // in-list entries per gather work item (one wave each)
 
 // ---------------------------------------------------------------- error plumbing (api.hip)
@@ -149,11 +150,18 @@ struct GatherArgs {
     int guard;
     const float* Pfull;
     int full_scale_gcn;
+    // layers whose changed sources are few may be served by the short-instruction variant of the gather
+    int sparse_ok;
+    int64_t n_vertices;
+    const uint32_t* coarse;    // coarse copy of src_bitmap: bit i covers vertices [i << coarse_shift, (i+1) << coarse_shift)
+    int coarse_shift;
+    int coarse_words;          // at most NRT_COARSE_WORDS
 };
 // destination records of list[0 .. *count) (list null: all n vertices), hub list and hub items; fills lc
 nrt_status k_dst_records(const int32_t* list, int64_t bound, const Adj& in, DstRec* recs, const HubWork& hubs,
                          LayerCtrs* lc, bool all_vertices, hipStream_t s);
 nrt_status k_gather(const GatherArgs& a, hipStream_t s);
+nrt_status k_coarse_bitmap(const uint32_t* fine, int64_t n, int shift, uint32_t* coarse, int64_t n_words, hipStream_t s);
 nrt_status k_combine_partials(const GatherArgs& a, hipStream_t s);
 
 struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update caches

@@ -11,12 +11,12 @@
 // aggregation of Eq. 1 used by nrt_cache_init.
 //
 // Mapping to the machine: destinations are walked through their in-lists (no atomics, no sort: each
-// destination row is owned by one wave).  An in-list is cut into items of NRT_CHUNK entries; a wave stages the
-// ids of one item, filters them against the bitmap of changed sources with a ballot/prefix-count, keeps the
-// surviving (row, coefficient) pairs in LDS and then streams the rows: one 16-byte load per lane, so a
-// 256-float row is one fully coalesced 1 KiB wave load (narrower rows put 2 or 4 neighbours in one load).
-// Destinations with more than one item write partial rows that a second small kernel sums in item order,
-// which keeps a 100k-degree hub from serialising on one wave and keeps the result order-deterministic.
+// destination row is owned by one wave).  An in-list of more than NRT_CHUNK entries is cut into items of
+// NRT_CHUNK entries that write partial rows; a second small kernel sums them in item order, which keeps a
+// 100k-degree hub from serialising on one wave and keeps the result order-deterministic.  Two kernels serve the
+// layers: gather_kernel (software pipeline over 64-entry steps, built for layers where most in-list entries
+// contribute and the row traffic dominates) and gather_sparse_kernel (short per-entry path with an LDS filter,
+// for layers where few sources changed); the device counters decide which of the two runs.
 #include "common.h"
 
 namespace {
@@ -207,6 +207,12 @@ __device__ inline float wave_absmax(const float4 (&x)[NV], bool use) {
 }
 constexpr float GUARD_RATIO = 16.0f;     // rebuild a row when the fold is 16x larger than what it leaves behind
 
+// The host cannot know how many sources changed without a synchronisation, so both gather kernels are launched
+// and each asks the device counters whether the layer is its to serve.
+__device__ inline bool layer_is_sparse(const GatherArgs& a) {
+    return a.sparse_ok && a.n_src_dev && (int64_t)(*a.n_src_dev) * 16 <= a.n_vertices;
+}
+
 // Step flags kept in the per-wave step table.
 enum { SF_FIRST = 1, SF_LAST = 2, SF_PART = 4, SF_SELF = 8 };
 
@@ -219,6 +225,7 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
     const int sub = lane / LPR, gl = lane % LPR;
     const int D = a.D;
     if (a.n_src_dev && *a.n_src_dev == 0 && !a.sd) return;   // nothing changed upstream of this layer
+    if (FILTER && NV == 1 && layer_is_sparse(a)) return;     // served by gather_sparse_kernel
     const int64_t n_dst = (int64_t)a.lc->count;
     int64_t n_items = (int64_t)a.lc->n_items;
     if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
@@ -461,6 +468,254 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
     if (a.pair_ctr && lane == 0 && pairs) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)pairs);
 }
 
+// ------------------------------------------------------------------ gather over sparsely changed sources
+// When only a small part of the vertices changed, most in-list entries fail the bitmap test and the cost of a
+// destination is the instructions spent per scanned entry, not the bytes of the few delta rows.  This variant
+// keeps the per-entry work short: a wave takes four consecutive units at a time, one per 16-lane group, and
+//   scan   every lane reads four in-list entries of its group's unit (64 entries per unit and trip), then the
+//          bitmap words, then the slots of the survivors: three batches of independent loads;
+//   pack   the survivors of each group are written, in in-list order, to the group's queue in LDS;
+//   rows   the queues are drained four slots per LDS read; each LPR-lane sub-group streams the rows of one
+//          unit (RPI = 64 / LPR units at a time), so row addresses come from LDS, not from lane reads;
+//   fold   the old aggregate rows (requested before the scan when they fit the registers) are added and stored.
+// The order of additions is fixed by the in-lists, so the result does not depend on the schedule.
+constexpr int SQ_CAP = 72;      // queue entries per group: 64 scanned entries + the self term, padded to 16 bytes
+constexpr int SP_WAVES = 8;     // waves per workgroup: they share one copy of the coarse filter in LDS
+constexpr int SP_BLOCKS = 768;  // persistent grid: three workgroups per compute unit
+
+// A random probe of the changed-source bitmap from HBM/L2 pulls a whole cache line per in-list entry; with a
+// bitmap far larger than the vector L1 that line traffic, not arithmetic, bounds the scan.  Each workgroup
+// therefore keeps a coarse copy in LDS (one bit per 2^shift vertices, at most COARSE_WORDS words) and only the
+// entries that pass it go on to the exact bitmap.  coarse_bitmap_kernel builds the copy once per layer.
+__global__ void coarse_bitmap_kernel(const uint32_t* fine, int64_t n, int shift, uint32_t* coarse, int64_t n_words) {
+    const int64_t cw = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (cw >= n_words) return;
+    const int64_t fine_words = (n + 31) >> 5;
+    uint32_t out = 0;
+    for (int i = 0; i < 32; ++i) {
+        const int64_t v0 = (cw * 32 + i) << shift;            // first vertex of the bit's group
+        if (v0 >= n) break;
+        uint32_t any = 0;
+        if (shift <= 5) {
+            const uint32_t word = fine[v0 >> 5];
+            const uint32_t mask = shift == 5 ? 0xffffffffu : (((1u << (1 << shift)) - 1u) << (v0 & 31));
+            any = word & mask;
+        } else {
+            const int64_t w0 = v0 >> 5, nw = (int64_t)1 << (shift - 5);
+            for (int64_t k = 0; k < nw && w0 + k < fine_words; ++k) any |= fine[w0 + k];
+        }
+        if (any) out |= 1u << i;
+    }
+    coarse[cw] = out;
+}
+
+template <int LPR, bool COEF>
+__global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs a) {
+    constexpr int RPI = 64 / LPR;          // units served by one row load
+    constexpr int NPASS = 4 / RPI;         // row passes over the four units of a round
+    constexpr bool PREFETCH = NPASS <= 2;  // old aggregate rows requested before the scan
+    __shared__ __attribute__((aligned(16))) int32_t s_slot[SP_WAVES][4][SQ_CAP];
+    __shared__ __attribute__((aligned(16))) float s_coef[SP_WAVES][4][COEF ? SQ_CAP : 4];
+    __shared__ uint32_t s_coarse[NRT_COARSE_WORDS];
+    if (!layer_is_sparse(a)) return;
+    if (*a.n_src_dev == 0 && !a.sd) return;
+    for (int i = threadIdx.x; i < a.coarse_words; i += SP_WAVES * 64) s_coarse[i] = a.coarse[i];
+    __syncthreads();
+    const int csh = a.coarse_shift;
+    const int lane = threadIdx.x & 63;
+    const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int g = lane >> 4, l16 = lane & 15;          // scan role
+    const int sub = lane / LPR, gl = lane % LPR;       // row role
+    const int D = a.D;
+    const bool live = gl * 4 < D;
+    const int64_t n_dst = (int64_t)a.lc->count;
+    int64_t n_items = (int64_t)a.lc->n_items;
+    if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
+    const int64_t total = n_dst + n_items;
+    const int64_t n_rounds = (total + 3) >> 2;
+    const int64_t n_waves = (int64_t)gridDim.x * SP_WAVES;
+    const float* Pl = a.P + gl * 4;
+    int32_t* q_mine = &s_slot[w][g][0];
+    float* c_mine = &s_coef[w][g][0];
+    const uint32_t below = (1u << l16) - 1u;
+    long long pairs = 0;
+
+    for (int64_t r = (int64_t)blockIdx.x * SP_WAVES + w; r < n_rounds; r += n_waves) {
+        // ---- scan role: the unit of this lane's group
+        const int64_t unit = r * 4 + g;
+        int64_t u_base = 0, u_out = 0;
+        int32_t u_cnt = 0, u_v = 0, u_deg = 0, u_flags = 0;     // flags == 0: nothing to serve, nothing to write
+        if (unit < total) {
+            DstRec rec;
+            int32_t chunk = 0;
+            if (unit >= n_items) {
+                rec = a.recs[unit - n_items];
+                if (rec.deg <= NRT_CHUNK) { u_cnt = rec.deg; u_flags = SF_SELF | SF_LAST; }   // hubs are served through their items
+                u_out = (int64_t)rec.v * D;
+            } else {
+                chunk = a.hubs.item_chunk[unit];
+                rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[unit]]];
+                u_cnt = min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK);
+                u_out = unit * D;
+                u_flags = SF_PART | SF_LAST | (chunk == 0 ? SF_SELF : 0);
+            }
+            u_base = rec.off + (int64_t)chunk * NRT_CHUNK;
+            u_v = rec.v;
+            u_deg = rec.deg;
+        }
+        // ---- row role: accumulators, and the old rows while the scan runs
+        float4 acc[NPASS], old[NPASS];
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            acc[ps] = make_float4(0.f, 0.f, 0.f, 0.f);
+            old[ps] = acc[ps];
+            if (PREFETCH) {
+                const int from = (ps * RPI + sub) << 4;
+                const int32_t fl = __shfl(u_flags, from, 64);
+                const int32_t vr = __shfl(u_v, from, 64);
+                if ((fl & (SF_LAST | SF_PART)) == SF_LAST && live)
+                    old[ps] = *reinterpret_cast<const float4*>(a.S + (int64_t)vr * D + gl * 4);
+            }
+        }
+        int32_t maxcnt = max(max(__builtin_amdgcn_readlane(u_cnt, 0), __builtin_amdgcn_readlane(u_cnt, 16)),
+                             max(__builtin_amdgcn_readlane(u_cnt, 32), __builtin_amdgcn_readlane(u_cnt, 48)));
+        int32_t hits = 0;                                        // per group, over the whole unit
+        int32_t j = 0;
+        do {
+            // ---- scan: entries, bitmap words, slots
+            int32_t e[5];
+            float wv[5];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int32_t jj = j + k * 16 + l16;
+                e[k] = -1;
+                wv[k] = 1.0f;
+                if (jj < u_cnt) {
+                    e[k] = a.in.idx[u_base + jj];
+                    if (COEF) wv[k] = a.in.wts[u_base + jj];
+                }
+            }
+            e[4] = (j == 0 && l16 == 0 && a.self_pair && (u_flags & SF_SELF)) ? u_v : -1;
+            wv[4] = 1.0f;
+            uint32_t bw[5];
+#pragma unroll
+            for (int k = 0; k < 5; ++k) {                       // coarse filter in LDS
+                bw[k] = 0u;
+                if (e[k] >= 0) {
+                    const uint32_t cbit = (uint32_t)e[k] >> csh;
+                    bw[k] = (s_coarse[cbit >> 5] >> (cbit & 31)) & 1u;
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 5; ++k) bw[k] = bw[k] ? a.src_bitmap[(uint32_t)e[k] >> 5] : 0u;
+            int32_t sl[5];
+#pragma unroll
+            for (int k = 0; k < 5; ++k) sl[k] = ((bw[k] >> (e[k] & 31)) & 1u) ? a.src_slot[(uint32_t)e[k]] : -1;
+            // ---- pack the survivors of each group, in in-list order
+            int32_t nq = 0;
+#pragma unroll
+            for (int k = 0; k < 5; ++k) {
+                const bool hit = sl[k] >= 0;
+                const unsigned long long b = __ballot(hit);
+                pairs += __popcll(b);
+                const uint32_t gb = (uint32_t)(b >> (g << 4)) & 0xffffu;
+                if (hit) {
+                    const int pos = nq + __popc(gb & below);
+                    q_mine[pos] = sl[k];
+                    if (COEF) c_mine[pos] = wv[k];
+                }
+                nq += __popc(gb);
+            }
+            hits += nq;
+            __builtin_amdgcn_wave_barrier();
+            // ---- rows: RPI units per pass, four queue entries per trip
+#pragma unroll
+            for (int ps = 0; ps < NPASS; ++ps) {
+                const int uu = ps * RPI + sub;
+                const int32_t n_u = __shfl(nq, uu << 4, 64);
+                int32_t n_max = 0;
+#pragma unroll
+                for (int t = 0; t < RPI; ++t) n_max = max(n_max, __builtin_amdgcn_readlane(nq, (ps * RPI + t) << 4));
+                const int32_t* qu = &s_slot[w][uu][0];
+                const float* cu = &s_coef[w][COEF ? uu : 0][0];
+                for (int32_t t = 0; t < n_max; t += 4) {
+                    const int4 s4 = *reinterpret_cast<const int4*>(qu + t);
+                    float4 c4 = make_float4(1.f, 1.f, 1.f, 1.f);
+                    if (COEF) {                                  // entries past the queue's end are stale: keep them finite
+                        c4 = *reinterpret_cast<const float4*>(cu + t);
+                        if (t + 0 >= n_u) c4.x = 0.f;
+                        if (t + 1 >= n_u) c4.y = 0.f;
+                        if (t + 2 >= n_u) c4.z = 0.f;
+                        if (t + 3 >= n_u) c4.w = 0.f;
+                    }
+                    float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0, x2 = x0, x3 = x0;
+                    if (t + 0 < n_u && live) x0 = *reinterpret_cast<const float4*>(Pl + (int64_t)s4.x * D);
+                    if (t + 1 < n_u && live) x1 = *reinterpret_cast<const float4*>(Pl + (int64_t)s4.y * D);
+                    if (t + 2 < n_u && live) x2 = *reinterpret_cast<const float4*>(Pl + (int64_t)s4.z * D);
+                    if (t + 3 < n_u && live) x3 = *reinterpret_cast<const float4*>(Pl + (int64_t)s4.w * D);
+                    acc[ps] = COEF ? f4_fma(c4.x, x0, acc[ps]) : f4_add(acc[ps], x0);
+                    acc[ps] = COEF ? f4_fma(c4.y, x1, acc[ps]) : f4_add(acc[ps], x1);
+                    acc[ps] = COEF ? f4_fma(c4.z, x2, acc[ps]) : f4_add(acc[ps], x2);
+                    acc[ps] = COEF ? f4_fma(c4.w, x3, acc[ps]) : f4_add(acc[ps], x3);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            j += 64;
+        } while (j < maxcnt);
+
+        // ---- fold and store
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int from = (ps * RPI + sub) << 4;
+            const int32_t fl = __shfl(u_flags, from, 64);
+            const int32_t vr = __shfl(u_v, from, 64);
+            const int32_t nh = __shfl(hits, from, 64);
+            const int64_t out = (int64_t)(((uint64_t)(uint32_t)__shfl((int32_t)(u_out >> 32), from, 64) << 32) |
+                                          (uint32_t)__shfl((int32_t)(u_out & 0xffffffff), from, 64));
+            float4 y = acc[ps];
+            bool touched = nh > 0;
+            if (a.sd && (fl & SF_SELF)) {
+                if ((a.dd_bitmap[vr >> 5] >> (vr & 31)) & 1u) {
+                    touched = true;
+                    if (live) y = f4_add(y, *reinterpret_cast<const float4*>(a.sd + (int64_t)a.dd_slot[vr] * D + gl * 4));
+                }
+            }
+            const bool part = fl & SF_PART;
+            if (part && live) *reinterpret_cast<float4*>(a.hubs.partial + out + gl * 4) = y;
+            const bool fold = !part && (fl & SF_LAST) && touched && live;      // no early exit: the votes below need every lane
+            if (!PREFETCH && fold) old[ps] = *reinterpret_cast<const float4*>(a.S + out + gl * 4);
+            float4 z = f4_add(y, old[ps]);
+            if (a.guard) {
+                float big = 0.f, left = 0.f;
+                if (fold) {
+                    big = fmaxf(fmaxf(fabsf(y.x), fabsf(y.y)), fmaxf(fabsf(y.z), fabsf(y.w)));
+                    left = fmaxf(fmaxf(fabsf(z.x), fabsf(z.y)), fmaxf(fabsf(z.z), fabsf(z.w)));
+                }
+#pragma unroll
+                for (int sft = 1; sft < LPR; sft <<= 1) {
+                    big = fmaxf(big, __shfl_xor(big, sft, 64));
+                    left = fmaxf(left, __shfl_xor(left, sft, 64));
+                }
+                unsigned long long trig = __ballot(gl == 0 && big > GUARD_RATIO * left);
+                while (trig) {                                   // rebuild the cancelled rows, one unit at a time
+                    const int bit = __ffsll((long long)trig) - 1;
+                    trig &= trig - 1;
+                    const int src = (ps * RPI + bit / LPR) << 4;
+                    const int32_t fv = __builtin_amdgcn_readlane(u_v, src);
+                    const int32_t fd = __builtin_amdgcn_readlane(u_deg, src);
+                    const uint32_t blo = (uint32_t)__builtin_amdgcn_readlane((int32_t)(u_base & 0xffffffff), src);
+                    const uint32_t bhi = (uint32_t)__builtin_amdgcn_readlane((int32_t)(u_base >> 32), src);
+                    float4 full[1];
+                    full_row<LPR, 1>(a, fv, (int64_t)(((uint64_t)bhi << 32) | blo), fd, lane, full);
+                    if (sub == bit / LPR) z = full[0];
+                }
+            }
+            if (fold) *reinterpret_cast<float4*>(a.S + out + gl * 4) = z;
+        }
+    }
+    if (a.pair_ctr && lane == 0 && pairs) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)pairs);
+}
+
 // one wave per hub (strided): sum its partial rows in item order into the cached aggregate
 __global__ void combine_kernel(GatherArgs a) {
     if (a.n_src_dev && *a.n_src_dev == 0 && !a.sd) return;
@@ -582,6 +837,10 @@ static void launch_gather(const GatherArgs& a, hipStream_t s) {
     else if (filter) gather_kernel<LPR, NV, true, false><<<nb, threads, 0, s>>>(a);
     else if (coef) gather_kernel<LPR, NV, false, true><<<nb, threads, 0, s>>>(a);
     else gather_kernel<LPR, NV, false, false><<<nb, threads, 0, s>>>(a);
+    if (NV == 1 && a.sparse_ok) {
+        if (coef) gather_sparse_kernel<LPR, true><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
+        else gather_sparse_kernel<LPR, false><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
+    }
 }
 
 nrt_status k_gather(const GatherArgs& a, hipStream_t s) {
@@ -590,6 +849,13 @@ nrt_status k_gather(const GatherArgs& a, hipStream_t s) {
     else if (a.D <= 256) launch_gather<64, 1>(a, s);
     else if (a.D <= 512) launch_gather<64, 2>(a, s);
     else launch_gather<64, 4>(a, s);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_coarse_bitmap(const uint32_t* fine, int64_t n, int shift, uint32_t* coarse, int64_t n_words, hipStream_t s) {
+    if (n_words <= 0) return NRT_OK;
+    coarse_bitmap_kernel<<<(int)cdiv(n_words, 256), 256, 0, s>>>(fine, n, shift, coarse, n_words);
     LAUNCH_CHECK();
     return NRT_OK;
 }
