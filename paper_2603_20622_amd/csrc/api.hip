@@ -46,7 +46,8 @@ struct nrt_cache {
     int64_t nw_pad;
     uint8_t* flags;                     // one byte per vertex: the set an expansion hop is building
     LayerCtrs* lc;                      // device, [NRT_MAX_LAYERS + 1]
-    LayerCtrs* lc_host;                 // pinned mirror
+    LayerCtrs* lc_host;                 // pinned mirror, followed by the mirror of pair_ctr (profiling)
+    unsigned long long* pair_host;
     int32_t* xhub_list;
     int64_t xhub_cap;
     int32_t* list[NRT_MAX_LAYERS + 1];
@@ -567,11 +568,14 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     cache_fill(c, g, d, max_batch_edges, max_batch_feats);
     Bump b{static_cast<char*>(workspace), 0};
     cache_layout(b, c);
-    if (hipHostMalloc((void**)&c->lc_host, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs), hipHostMallocDefault) != hipSuccess) {
+    const size_t lc_bytes = ((NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs) + 255) & ~size_t(255);
+    if (hipHostMalloc((void**)&c->lc_host, lc_bytes + 1024 * NRT_MAX_LAYERS * sizeof(unsigned long long),
+                      hipHostMallocDefault) != hipSuccess) {
         delete c;
         nrt_set_error("pinned host allocation failed");
         return NRT_ERR_OOM;
     }
+    c->pair_host = reinterpret_cast<unsigned long long*>(reinterpret_cast<char*>(c->lc_host) + lc_bytes);
     const int64_t n = g->n;
     auto run = [&]() -> nrt_status {
         NRT_TRY(k_copy_f32(c->H[0], features, n * c->dims[0], s));
@@ -653,7 +657,18 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     NRT_TRY(prof_mark(c, TAG_START, 0, s));
 
     // ---- validate (no state change yet); the one synchronisation before the end of the batch
-    NRT_TRY(graph_validate_batch(g, b, c->sc, s));
+    {
+        // per-batch scratch of the cache is cleared in the validation's fill launch: set bitmaps, layer counters,
+        // the rows that collect structural terms (none of it is state, so a rejected batch loses nothing)
+        FillJobs f;
+        memset(&f, 0, sizeof(f));
+        f.add(c->bm_ddst, 2 * c->nw_pad);                     // bm_ddst and bm_feat are adjacent
+        f.add(c->lc, (int64_t)((NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs) / 4));
+        if (c->profiling) f.add(c->pair_ctr, 2 * 1024 * NRT_MAX_LAYERS);
+        if (c->kind != NRT_GAT)
+            for (int l = 1; l <= c->L; ++l) f.add(c->SD[l], (b->n_ins + b->n_del) * (int64_t)c->dagg[l]);
+        NRT_TRY(graph_validate_batch(g, b, c->sc, &f, s));
+    }
     NRT_TRY(read_ctrs(g, s));
     {
         const int32_t* err = (const int32_t*)(g->host_pinned + CTR_ERR);
@@ -685,17 +700,12 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
 
     // ---- sets of the batch, per-layer counters
     const bool gcn = c->kind == NRT_GCN;
-    NRT_TRY(k_fill_u32(c->bm_ddst, 2 * c->nw_pad, 0, s));     // bm_ddst and bm_feat are adjacent
-    NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs) / 8, 0, s));
-    if (c->profiling) NRT_TRY(k_fill_u64((uint64_t*)c->pair_ctr, 1024 * NRT_MAX_LAYERS, 0, s));
     NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
     if (gcn) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     if (c->kind != NRT_GAT && b->n_ins + b->n_del > 0) {
         // destinations of updated edges -> compact rows that collect their structural terms (bm[1] is scratch here)
         NRT_TRY(k_compact(nullptr, c->bm_ddst, nullptr, c->bm[1], n, c->list_dd, c->slot_dd, g->scan_tmp, g->scan_tmp_len,
                           (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
-        for (int l = 1; l <= c->L; ++l)
-            NRT_TRY(k_fill_u32((uint32_t*)c->SD[l], (b->n_ins + b->n_del) * (int64_t)c->dagg[l], 0, s));
     }
 
     // ---- structural terms on the old caches, all layers in one launch (GAT recomputes those destinations in full)
@@ -769,6 +779,9 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     }
     NRT_TRY(k_copy_counted_i32(affected_ids, c->list[c->L], &c->lc[c->L].count, capacity, n, s));
     HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
+    if (c->profiling)
+        HIP_TRY(hipMemcpyAsync(c->pair_host, c->pair_ctr, 1024 * NRT_MAX_LAYERS * sizeof(unsigned long long),
+                               hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     for (int l = 0; l <= c->L; ++l) c->n_list[l] = (int64_t)c->lc_host[l].count;
     for (int l = 1; l <= c->L; ++l) {
@@ -785,12 +798,9 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     }
     NRT_TRY(prof_collect(c));
     if (c->profiling) {
-        static thread_local unsigned long long host_ctr[1024];
         for (int l = 1; l <= c->L; ++l) {
-            if (c->n_list[l - 1] == 0) continue;
-            HIP_TRY(hipMemcpy(host_ctr, c->pair_ctr + (size_t)(l - 1) * 1024, sizeof(host_ctr), hipMemcpyDeviceToHost));
             unsigned long long tot = 0;
-            for (int i = 0; i < 1024; ++i) tot += host_ctr[i];
+            for (int i = 0; i < 1024; ++i) tot += c->pair_host[(size_t)(l - 1) * 1024 + i];
             c->stats.layer[l - 1].n_pairs = (int64_t)tot;
         }
     }

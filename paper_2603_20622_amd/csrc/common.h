@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <stddef.h>
+#include <string.h>
 #include "nrt.h"
 
 #define NRT_WAVE 64
@@ -86,6 +87,14 @@ struct LayerCtrs {
 
 // ---------------------------------------------------------------- prims.hip
 nrt_status k_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
+// several fills in one launch (a batch clears a dozen small scratch areas; separate launches would cost more than the stores)
+struct FillJob { uint32_t* p; int64_t n; uint32_t v; };      // n 32-bit words
+struct FillJobs {
+    FillJob j[12];
+    int count;
+    void add(void* p, int64_t n_words, uint32_t v = 0) { if (n_words > 0 && count < 12) { j[count].p = (uint32_t*)p; j[count].n = n_words; j[count].v = v; ++count; } }
+};
+nrt_status k_multi_fill(const FillJobs& f, hipStream_t s);
 nrt_status k_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
 nrt_status k_or_words(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t nwords, hipStream_t s);
 nrt_status k_copy_i32(int32_t* dst, const int32_t* src, int64_t n, hipStream_t s);
@@ -256,6 +265,7 @@ struct BatchScratch {
     int32_t* feat_stamp;                        // [N] epoch stamps that detect repeated feature ids
 };
 // validate (no state change); err flags and growth need are read back by the caller
-nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipStream_t s);
+// `clears`: scratch areas of the caller to zero in the same launch as the validation's own (may be null)
+nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, const FillJobs* clears, hipStream_t s);
 nrt_status graph_cancel_batch(nrt_graph* g, const nrt_batch* b, hipStream_t s);   // undo counters after a failed validation
 nrt_status graph_mutate(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipStream_t s);

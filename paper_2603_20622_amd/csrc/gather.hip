@@ -103,20 +103,31 @@ dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, Hub
             s_ibase = atomicAdd((unsigned long long*)&lc->n_items, (unsigned long long)(tot & 0xffffffffu));
         }
         __syncthreads();
+        // every wave walks its lanes that hold a hub; all 64 lanes then write that hub's items (a hub of a
+        // hundred thousand in-edges has hundreds of items: one thread writing them alone would set the kernel's time)
+        const int lane = threadIdx.x & 63;
 #pragma unroll
         for (int e = 0; e < REC_EPT; ++e) {
-            if (!nch[e]) continue;
             const int64_t i = i0 + (int64_t)e * REC_THREADS + threadIdx.x;
             const int64_t h = (int64_t)(s_hbase + (ex >> 32));
             const int64_t first = (int64_t)(s_ibase + (ex & 0xffffffffu));
-            ex += (1ULL << 32) | nch[e];
-            if (h < hubs.hub_cap) {
+            const bool is_hub = nch[e] != 0 && h < hubs.hub_cap;
+            if (nch[e]) ex += (1ULL << 32) | nch[e];
+            if (is_hub) {
                 hubs.hub_slot[h] = (int32_t)i;
                 hubs.hub_first[h] = (uint64_t)first;
-                for (int64_t c = 0; c < (int64_t)nch[e]; ++c) {
-                    if (first + c < hubs.item_cap) {
-                        hubs.item_hub[first + c] = (int32_t)h;
-                        hubs.item_chunk[first + c] = (int32_t)c;
+            }
+            unsigned long long m = __ballot(is_hub);
+            while (m) {
+                const int from = __ffsll((long long)m) - 1;
+                m &= m - 1;
+                const int32_t hh = (int32_t)__shfl((long long)h, from, 64);
+                const int64_t ff = (int64_t)__shfl((long long)first, from, 64);
+                const int32_t nn = (int32_t)__shfl((long long)nch[e], from, 64);
+                for (int32_t c = lane; c < nn; c += 64) {
+                    if (ff + c < hubs.item_cap) {
+                        hubs.item_hub[ff + c] = hh;
+                        hubs.item_chunk[ff + c] = c;
                     }
                 }
             }
@@ -724,30 +735,39 @@ __global__ void combine_kernel(GatherArgs a) {
     if (nh > a.hubs.hub_cap) nh = a.hubs.hub_cap;
     const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     const int D = a.D;
+    // rows narrower than 256 floats leave lanes free: LW lanes cover a row, the 64 / LW sub-groups take every
+    // (64 / LW)-th partial row, eight loads in flight each, and are reduced with lane exchanges at the end
+    const int LW = D <= 64 ? 16 : (D <= 128 ? 32 : 64);
+    const int G = 64 / LW, sub = lane / LW, gl = lane % LW;
     for (int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; h < nh; h += waves) {
         const DstRec rec = a.recs[a.hubs.hub_slot[h]];
         const int32_t nch = (rec.deg + NRT_CHUNK - 1) / NRT_CHUNK;
         const int64_t first = (int64_t)a.hubs.hub_first[h];
         float big = 0.f, left = 0.f;
-        for (int col = lane * 4; col < D; col += 256) {
+        for (int col = gl * 4; col < D; col += 256) {
             const float* p = a.hubs.partial + first * D + col;
             float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            int32_t c = 0;
-            for (; c + 3 < nch; c += 4) {
-                const float4 x0 = *reinterpret_cast<const float4*>(p + (int64_t)c * D);
-                const float4 x1 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 1) * D);
-                const float4 x2 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 2) * D);
-                const float4 x3 = *reinterpret_cast<const float4*>(p + (int64_t)(c + 3) * D);
-                acc = f4_add(acc, x0); acc = f4_add(acc, x1); acc = f4_add(acc, x2); acc = f4_add(acc, x3);
+            for (int32_t c0 = sub; c0 < nch; c0 += 8 * G) {
+                float4 x[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    const int32_t c = c0 + k * G;
+                    x[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (c < nch) x[k] = *reinterpret_cast<const float4*>(p + (int64_t)c * D);
+                }
+#pragma unroll
+                for (int k = 0; k < 8; ++k) acc = f4_add(acc, x[k]);
             }
-            for (; c < nch; ++c) acc = f4_add(acc, *reinterpret_cast<const float4*>(p + (int64_t)c * D));
+            for (int mm = LW; mm < 64; mm <<= 1) acc = f4_add(acc, f4_shfl_xor(acc, mm));
             float4* dst = reinterpret_cast<float4*>(a.S + (int64_t)rec.v * D + col);
             float4 y = acc;
-            if (a.accumulate) y = f4_add(acc, *dst);
-            *dst = y;
-            if (a.accumulate && a.guard) {
-                big = fmaxf(big, fmaxf(fmaxf(fabsf(acc.x), fabsf(acc.y)), fmaxf(fabsf(acc.z), fabsf(acc.w))));
-                left = fmaxf(left, fmaxf(fmaxf(fabsf(y.x), fabsf(y.y)), fmaxf(fabsf(y.z), fabsf(y.w))));
+            if (sub == 0) {
+                if (a.accumulate) y = f4_add(acc, *dst);
+                *dst = y;
+                if (a.accumulate && a.guard) {
+                    big = fmaxf(big, fmaxf(fmaxf(fabsf(acc.x), fabsf(acc.y)), fmaxf(fabsf(acc.z), fabsf(acc.w))));
+                    left = fmaxf(left, fmaxf(fmaxf(fabsf(y.x), fabsf(y.y)), fmaxf(fabsf(y.z), fabsf(y.w))));
+                }
             }
         }
         if (a.accumulate && a.guard) {

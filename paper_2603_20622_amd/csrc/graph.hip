@@ -394,17 +394,21 @@ nrt_status graph_build(nrt_graph* g, const int64_t* csr_indptr, const int32_t* c
     return NRT_OK;
 }
 
-nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipStream_t s) {
+nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, const FillJobs* clears, hipStream_t s) {
     const int64_t nops = b->n_ins + b->n_del;
-    NRT_TRY(k_fill_u64((uint64_t*)(g->dev_ctrs + CTR_ERR), 4, 0, s));      // 8 int32 flags
-    NRT_TRY(k_fill_u64((uint64_t*)(g->dev_ctrs + CTR_GROW), 2, 0, s));
+    FillJobs f;
+    memset(&f, 0, sizeof(f));
+    if (clears) f = *clears;
+    f.add(g->dev_ctrs + CTR_ERR, 8);        // 8 int32 flags
+    f.add(g->dev_ctrs + CTR_GROW, 4);
+    if (nops > 0) f.add(sc.hash_keys, 2 * sc.hash_cap);
+    NRT_TRY(k_multi_fill(f, s));
     if (b->n_feat > 0) {
         validate_feats_kernel<<<(int)cdiv(b->n_feat, 256), 256, 0, s>>>(g->n, b->n_feat, b->feat_ids, sc.feat_index,
                                                                        sc.feat_stamp, g->epoch, sc.err);
         LAUNCH_CHECK();
     }
     if (nops == 0) return NRT_OK;
-    NRT_TRY(k_fill_u64(sc.hash_keys, sc.hash_cap, 0, s));
     validate_edges_kernel<<<(unsigned)nops, VAL_THREADS, 0, s>>>(
         g->out, g->in, g->n, b->n_ins, b->n_del, b->ins_src, b->ins_dst, b->del_src, b->del_dst, sc.hash_keys,
         sc.hash_cap, sc.pos_out, sc.pos_in, sc.del_w, sc.err, g->inscnt[0], g->inscnt[1], g->delcnt[0], g->delcnt[1]);

@@ -46,6 +46,12 @@ __global__ void fill_u64_kernel(uint64_t* p, int64_t n, uint64_t v) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) p[i] = v;
 }
+__global__ void multi_fill_kernel(FillJobs f) {
+    const FillJob j = f.j[blockIdx.y];
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < j.n; i += stride) j.p[i] = j.v;
+}
 __global__ void or_words_kernel(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -204,6 +210,16 @@ nrt_status k_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s) {
 nrt_status k_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s) {
     if (n <= 0) return NRT_OK;
     fill_u64_kernel<<<grid_for(n, 256), 256, 0, s>>>(p, n, v);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_multi_fill(const FillJobs& f, hipStream_t s) {
+    if (f.count <= 0) return NRT_OK;
+    int64_t longest = 0;
+    for (int i = 0; i < f.count; ++i) longest = f.j[i].n > longest ? f.j[i].n : longest;
+    if (longest <= 0) return NRT_OK;
+    dim3 grid((unsigned)grid_for(longest, 256), (unsigned)f.count, 1);
+    multi_fill_kernel<<<grid, 256, 0, s>>>(f);
     LAUNCH_CHECK();
     return NRT_OK;
 }
