@@ -103,8 +103,8 @@ dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, Hub
             s_ibase = atomicAdd((unsigned long long*)&lc->n_items, (unsigned long long)(tot & 0xffffffffu));
         }
         __syncthreads();
-        // every wave walks its lanes that hold a hub; all 64 lanes then write that hub's items (a hub of a
-        // hundred thousand in-edges has hundreds of items: one thread writing them alone would set the kernel's time)
+        // items of a hub: a hub of a hundred thousand in-edges has hundreds of them, and one thread writing them
+        // alone would set the kernel's time, so the wave writes those together
         const int lane = threadIdx.x & 63;
 #pragma unroll
         for (int e = 0; e < REC_EPT; ++e) {
@@ -117,7 +117,15 @@ dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, Hub
                 hubs.hub_slot[h] = (int32_t)i;
                 hubs.hub_first[h] = (uint64_t)first;
             }
-            unsigned long long m = __ballot(is_hub);
+            if (is_hub && nch[e] <= 8) {                          // the many small hubs: their own lane writes the few items
+                for (int32_t c = 0; c < (int32_t)nch[e]; ++c) {
+                    if (first + c < hubs.item_cap) {
+                        hubs.item_hub[first + c] = (int32_t)h;
+                        hubs.item_chunk[first + c] = c;
+                    }
+                }
+            }
+            unsigned long long m = __ballot(is_hub && nch[e] > 8);  // the few long ones: the whole wave writes
             while (m) {
                 const int from = __ffsll((long long)m) - 1;
                 m &= m - 1;

@@ -11,7 +11,9 @@ namespace {
 
 constexpr int RB_THREADS = 1024;   // threads of a list-rebuild workgroup
 constexpr int RB_EPT = 4;
+constexpr int RB_FEW = 256;        // up to this many deletions a list is patched instead of squeezed
 constexpr int VAL_THREADS = 1024; // threads of an edge-validation workgroup
+constexpr int VAL_UNROLL = 4;     // independent list loads per thread and trip
 
 __device__ inline int32_t new_cap_for(int32_t need) { return need + need / 2 + 4; }
 __device__ inline int32_t initial_cap_for(int32_t deg) { return deg + deg / 8 + 2; }
@@ -82,15 +84,15 @@ __device__ inline int64_t find_in_list(const Adj& a, int32_t k, int32_t target, 
     const int32_t d = a.deg[k];
     if (threadIdx.x == 0) *s_pos = -1;
     __syncthreads();
-    for (int32_t j = threadIdx.x; j < d; j += 4 * VAL_THREADS) {
-        int32_t e[4];
+    for (int32_t j = threadIdx.x; j < d; j += VAL_UNROLL * VAL_THREADS) {
+        int32_t e[VAL_UNROLL];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < VAL_UNROLL; ++t) {
             const int32_t jj = j + t * VAL_THREADS;
             e[t] = jj < d ? a.idx[o + jj] : -2;
         }
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
+        for (int t = 0; t < VAL_UNROLL; ++t)
             if (e[t] == target) *s_pos = o + j + t * VAL_THREADS;
     }
     __syncthreads();
@@ -108,7 +110,8 @@ validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins, int64_t n_del,
                       const int32_t* del_dst, uint64_t* hash, int64_t hash_cap, int64_t* pos_out,
                       int64_t* pos_in, float* del_w, int32_t* err, int32_t* inscnt0,
                       int32_t* inscnt1, int32_t* delcnt0, int32_t* delcnt1) {
-    __shared__ int64_t s_pos;
+    __shared__ int64_t s_pos1;
+    int64_t* const s_pos = &s_pos1;
     const int64_t op = blockIdx.x;
     const bool lead = threadIdx.x == 0;
     const bool is_del = op >= n_ins;
@@ -128,8 +131,8 @@ validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins, int64_t n_del,
         }
     }
     if (is_del) {
-        const int64_t po = find_in_list(out, u, v, &s_pos);
-        const int64_t pi = find_in_list(in, v, u, &s_pos);
+        const int64_t po = find_in_list(out, u, v, s_pos);
+        const int64_t pi = find_in_list(in, v, u, s_pos);
         if (po < 0 || pi < 0) { if (lead) err[3] = 1; return; }
         if (lead) {
             pos_out[i] = po;
@@ -140,7 +143,7 @@ validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins, int64_t n_del,
         }
     } else {
         const bool use_out = out.deg[u] <= in.deg[v];
-        const int64_t p = use_out ? find_in_list(out, u, v, &s_pos) : find_in_list(in, v, u, &s_pos);
+        const int64_t p = use_out ? find_in_list(out, u, v, s_pos) : find_in_list(in, v, u, s_pos);
         if (p >= 0) { if (lead) err[2] = 1; return; }
         if (lead) {
             atomicAdd(&inscnt0[u], 1);
@@ -232,6 +235,8 @@ rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_
     __shared__ uint32_t wsum[RB_THREADS / 64];
     __shared__ int32_t s_owner;
     __shared__ int64_t s_newoff;
+    __shared__ int s_nh;
+    __shared__ int32_t s_hole[RB_FEW];
     const int dir = blockIdx.y;
     const int64_t op = blockIdx.x;
     const bool is_del = op >= n_ins;
@@ -248,7 +253,48 @@ rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_
     const int32_t deg0 = a.deg[k];
     const int32_t dc = delcnt[k], ic = inscnt[k];
     int32_t live = deg0;
-    if (dc > 0) {
+    if (dc > 0 && dc <= RB_FEW) {
+        // A few tombstones in a possibly very long list: find them with a read-only pass, then move the live entries
+        // of the last dc positions into the holes in front of them.  Holes and fillers are matched in ascending
+        // position order, so the resulting list order does not depend on thread scheduling.
+        if (threadIdx.x == 0) s_nh = 0;
+        __syncthreads();
+        for (int32_t p0 = threadIdx.x; p0 < deg0; p0 += RB_THREADS * 8) {      // eight independent loads, then the tests
+            int32_t e8[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int32_t p = p0 + j * RB_THREADS;
+                e8[j] = p < deg0 ? a.idx[base + p] : 0;
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (e8[j] < 0) { const int at = atomicAdd(&s_nh, 1); if (at < RB_FEW) s_hole[at] = p0 + j * RB_THREADS; }
+        }
+        __syncthreads();
+        const int nh = min(s_nh, RB_FEW);            // equals dc for a validated batch
+        const int32_t keep = deg0 - nh;
+        int32_t my_hole = -1, my_rank = 0;
+        if ((int)threadIdx.x < nh) {
+            my_hole = s_hole[threadIdx.x];
+            for (int j = 0; j < nh; ++j) my_rank += s_hole[j] < my_hole;
+        }
+        __syncthreads();
+        if (my_hole >= 0) s_hole[my_rank] = my_hole;                // ascending
+        __syncthreads();
+        // thread t looks at tail position keep + t; a live entry there is the r-th filler, r = t - holes before it
+        if ((int)threadIdx.x < nh) {
+            const int32_t p = keep + (int32_t)threadIdx.x;
+            const int32_t e = a.idx[base + p];
+            if (e >= 0) {
+                int r = threadIdx.x;
+                for (int j = 0; j < nh; ++j) r -= (s_hole[j] >= keep && s_hole[j] < p);
+                const int32_t h = s_hole[r];                        // r-th hole overall; all of these lie below keep
+                a.idx[base + h] = e;
+                if (a.wts) a.wts[base + h] = a.wts[base + p];
+            }
+        }
+        live = keep;
+    } else if (dc > 0) {
         uint32_t outpos = 0;
         for (int32_t start = 0; start < deg0; start += RB_THREADS * RB_EPT) {
             int32_t e[RB_EPT];
