@@ -56,7 +56,8 @@ def main():
         cfg.n_del = args.batch_edges - cfg.n_ins
     t0 = time.time()
     src, dst, w, x, params, stream = wl.build(cfg, args.seed)
-    n_total = 2 * args.steps + args.warmup
+    k_modes = min(args.steps, 10)                       # steps per non-incremental mode (comparison legs)
+    n_total = 2 * args.steps + args.warmup + 2 * k_modes
     batches = [stream.next_batch(cfg.n_ins, cfg.n_del, cfg.n_feat) for _ in range(n_total)]
     final_edges = stream.edges()
     t_gen = time.time() - t0
@@ -100,7 +101,7 @@ def main():
            "ingest_ms": 0.0, "expand_ms": 0.0, "compact_ms": 0.0, "items_ms": 0.0, "combine_ms": 0.0}
     per_layer = [dict(n_src=0, n_aff=0, n_pairs=0, n_in=0, gather_ms=0.0, update_ms=0.0, bytes=0.0) for _ in range(L)]
     t_start2 = time.perf_counter()
-    for b in dev_batches[args.warmup + K:]:
+    for b in dev_batches[args.warmup + K:args.warmup + 2 * K]:
         ses.apply(b)
         st = ses.stats()
         agg["ingest_ms"] += st.ms_ingest
@@ -136,6 +137,23 @@ def main():
     torch.cuda.synchronize()
     ms_per_step_events = (time.perf_counter() - t_start2) * 1e3 / K
 
+    # ---- comparison legs (Section II-C): the same chained stream continued with every affected vertex recomputed over
+    # its whole in-neighbourhood ("unaffected embedding reuse"), then with the whole graph recomputed per batch
+    ses.profiling(False)
+    mode_ms = {}
+    at = args.warmup + 2 * K
+    for name, mode in (("recompute_affected", 1), ("full_graph", 2)):
+        ses.mode(mode)
+        ses.apply(dev_batches[at])                       # one untimed step in the new mode
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        for b in dev_batches[at + 1:at + k_modes]:
+            ses.apply(b)
+        torch.cuda.synchronize()
+        mode_ms[name] = (time.perf_counter() - t3) * 1e3 / max(1, k_modes - 1)
+        at += k_modes
+    ses.mode(0)
+
     # HBM bytes per launch measured with rocprofv3 counters on this workload (committed summary), if present
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "gather_kernel_%s_hbm_traffic.txt" % cfg.name)
@@ -169,6 +187,12 @@ def main():
                                 "phase_ms_per_step and per_layer_avg come from it"},
         "update_gemm": {"bound": "mfma", "achieved": round(upd_tflops, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(upd_tflops / FP32_MFMA_PEAK_TFLOPS, 4)},
+        "modes_ms_per_step": {"incremental": round(ms_per_step, 4),
+                              "recompute_affected": round(mode_ms["recompute_affected"], 4),
+                              "full_graph": round(mode_ms["full_graph"], 4), "steps_each": k_modes - 1},
+        "edges_processed_per_step": {"incremental_delta_messages": round(sum(pl["n_pairs"] for pl in per_layer) / K),
+                                     "recompute_affected_in_edges": round(sum(pl["n_in"] for pl in per_layer) / K),
+                                     "full_graph": L * cfg.e},
         "gpu_full_forward_ms": round(ses.cache.init_ms, 3),   # nrt_cache_init: full-neighbour L-layer forward on the GPU
         "phase_ms_per_step": {k[:-3]: round(v / K, 4) for k, v in agg.items() if k.endswith("_ms")},
         "per_layer_avg": [{"layer": l + 1, "n_src": pl["n_src"] / K, "n_affected": pl["n_aff"] / K,

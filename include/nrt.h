@@ -178,6 +178,17 @@ nrt_status nrt_get_aggregate(const nrt_cache*, int32_t layer, const float** rows
 /* Per-layer affected list A_l (l = 1..L) of the last batch: borrowed device int32 array, ascending. */
 nrt_status nrt_get_layer_affected(const nrt_cache*, int32_t layer, const int32_t** ids, int64_t* n);
 
+/* How nrt_apply_batch brings the caches up to date (Section II-C, the non-incremental ways of running RTEC
+ * that the paper compares against, on the same kernels and the same caches; results are equal up to fp32
+ * rounding in every mode, and a cache may switch mode between batches):
+ *   NRT_MODE_INCREMENTAL  delta messages over the affected subgraph only (Algorithms 1, 3, 4); the default.
+ *   NRT_MODE_RECOMPUTE    "unaffected embedding reuse": the same affected sets, but every affected vertex
+ *                         re-aggregates its whole in-neighbourhood from the current h^{l-1}.
+ *   NRT_MODE_FULL         every vertex of every layer is recomputed on the updated graph; the affected list
+ *                         is still produced by the frontier expansion.
+ * Errors: NRT_ERR_INVALID_ARG (null cache, unknown mode). */
+typedef enum { NRT_MODE_INCREMENTAL = 0, NRT_MODE_RECOMPUTE = 1, NRT_MODE_FULL = 2 } nrt_mode;
+nrt_status nrt_set_mode(nrt_cache*, int32_t mode);
 nrt_status nrt_set_profiling(nrt_cache*, int32_t on);
 nrt_status nrt_get_stats(const nrt_cache*, nrt_stats* out /*host*/);
 

@@ -61,7 +61,7 @@ class NrtError(RuntimeError):
 EXPORTS = ["nrt_graph_workspace_bytes", "nrt_graph_create", "nrt_graph_destroy", "nrt_graph_num_edges",
            "nrt_graph_export_csc", "nrt_cache_workspace_bytes", "nrt_cache_init", "nrt_cache_destroy",
            "nrt_apply_batch", "nrt_get_layer", "nrt_get_aggregate", "nrt_get_layer_affected", "nrt_set_profiling",
-           "nrt_get_stats", "nrt_last_error", "nrt_version"]
+           "nrt_set_mode", "nrt_get_stats", "nrt_last_error", "nrt_version"]
 
 _lib = None
 
@@ -89,6 +89,7 @@ def lib() -> ctypes.CDLL:
         L.nrt_get_aggregate.argtypes = [c_fp, i32, P(c_fp), P(i64), P(i64)]
         L.nrt_get_layer_affected.argtypes = [c_fp, i32, P(c_fp), P(i64)]
         L.nrt_set_profiling.argtypes = [c_fp, i32]
+        L.nrt_set_mode.argtypes = [c_fp, i32]
         L.nrt_get_stats.argtypes = [c_fp, P(nrt_stats)]
         L.nrt_last_error.restype = ctypes.c_char_p
         L.nrt_version.restype = ctypes.c_char_p
@@ -264,6 +265,13 @@ def nrt_get_layer_affected(c: Cache, layer: int) -> torch.Tensor:
     if n.value == 0:
         return torch.empty(0, dtype=torch.int32, device="cuda")
     return _view(p.value, (n.value,), torch.int32, c.ws)
+
+
+NRT_MODE_INCREMENTAL, NRT_MODE_RECOMPUTE, NRT_MODE_FULL = 0, 1, 2
+
+
+def nrt_set_mode(c: Cache, mode: int) -> None:
+    _check(lib().nrt_set_mode(c.handle, int(mode)))
 
 
 def nrt_set_profiling(c: Cache, on: bool) -> None:

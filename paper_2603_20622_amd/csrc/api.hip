@@ -45,7 +45,9 @@ struct nrt_cache {
     uint32_t *bm_ddst, *bm_feat, *bm[2];
     int64_t nw_pad;
     uint8_t* flags;                     // one byte per vertex: the set an expansion hop is building
-    LayerCtrs* lc;                      // device, [NRT_MAX_LAYERS + 1]
+    LayerCtrs* lc;                      // device, [NRT_MAX_LAYERS + 2]; the last one serves whole-graph passes of a batch
+    LayerCtrs* lc_use;                  // counters the layer steps read instead of lc[l] (null: lc[l])
+    int mode;                           // nrt_mode
     LayerCtrs* lc_host;                 // pinned mirror, followed by the mirror of pair_ctr (profiling)
     unsigned long long* pair_host;
     int32_t* xhub_list;
@@ -309,7 +311,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->xhub_cap = g->e_capacity / 512 + 64;                    // sources with more than 512 live out-edges
     c->xhub_list = b.take<int32_t>(c->xhub_cap);
     c->flags = b.take<uint8_t>(n + 64);
-    c->lc = b.take<LayerCtrs>(NRT_MAX_LAYERS + 1);
+    c->lc = b.take<LayerCtrs>(NRT_MAX_LAYERS + 2);
     c->sc.max_edges = c->max_edges;
     int64_t hc = 16;
     while (hc < 2 * (c->max_edges + 1)) hc <<= 1;
@@ -372,7 +374,7 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hi
     memset(&a, 0, sizeof(a));
     a.recs = c->recs;
     a.hubs = c->hubs;
-    a.lc = &c->lc[l];
+    a.lc = c->lc_use ? c->lc_use : &c->lc[l];
     a.in = g->in;
     a.D = c->dagg[l];
     a.use_weights = (c->kind == NRT_GIN && g->weighted) ? 1 : 0;
@@ -397,12 +399,12 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hi
         a.coarse_shift = c->coarse_shift;
         a.coarse_words = c->coarse_words;
         NRT_TRY(k_coarse_bitmap(c->bm[prev], g->n, c->coarse_shift, c->coarse, c->coarse_words, s));
-        if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     } else {
         a.P = c->H[l - 1];
         a.src_scale_gcn = c->kind == NRT_GCN;
         a.accumulate = 0;
     }
+    if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
     NRT_TRY(k_gather(a, s));
     NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
@@ -482,14 +484,16 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
 }
 
 // GAT layer l: z = x W on the listed rows (null: all), attention scalars, then the attention gather + output
+// `listed`: only the rows of src_rows / dst_rows are touched; `incremental`: Algorithm 3 on top of that (old z and
+// attention scalars kept, terms exchanged), else every listed destination is recomputed over its whole in-list
 static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
-                                const int32_t* dst_rows, const uint64_t* n_dst_dev, int64_t dst_bound, bool incremental,
-                                int prev, float* out_rows, int64_t out_cap, hipStream_t s) {
+                                const int32_t* dst_rows, const uint64_t* n_dst_dev, int64_t dst_bound, bool listed,
+                                bool incremental, int prev, float* out_rows, int64_t out_cap, hipStream_t s) {
     nrt_graph* g = c->g;
     const bool last = l == c->L;
     GemmArgs z;
     memset(&z, 0, sizeof(z));
-    z.M = incremental ? src_bound : g->n;
+    z.M = listed ? src_bound : g->n;
     z.M_dev = n_src_dev;
     z.rows = src_rows;
     z.a_mode = A_PLAIN;
@@ -523,7 +527,7 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
     a.rows_bound = dst_bound;
     a.recs = c->recs;
     a.hubs = c->hubs;
-    a.lc = &c->lc[l];
+    a.lc = c->lc_use ? c->lc_use : &c->lc[l];
     a.part_m = c->part_m;
     a.part_den = c->part_den;
     a.Z_old = c->DP[0];
@@ -544,6 +548,29 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
     NRT_TRY(k_gat_gather(a, s));
     NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
     return NRT_OK;
+}
+
+// Full-neighbour forward over every vertex of every layer (Eq. 1) from the current h^0 and graph; fills all caches.
+// Every vertex is a destination: records and hub items are built once, with their counters in the spare
+// LayerCtrs slot (zero on entry), and serve all layers.
+static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
+    nrt_graph* g = c->g;
+    const int64_t n = g->n;
+    LayerCtrs* all = &c->lc[NRT_MAX_LAYERS + 1];
+    NRT_TRY(k_dst_records(nullptr, n, g->in, c->recs, c->hubs, all, true, s));
+    NRT_TRY(k_fill_u64(&all->count, 1, (uint64_t)n, s));
+    c->lc_use = all;
+    nrt_status st = NRT_OK;
+    for (int l = 1; l <= c->L && st == NRT_OK; ++l) {
+        if (c->kind == NRT_GAT) {
+            st = run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, false, 0, nullptr, 0, s);
+            continue;
+        }
+        st = run_gather(c, l, false, 0, s);
+        if (st == NRT_OK) st = run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, s);
+    }
+    c->lc_use = nullptr;
+    return st;
 }
 
 // ------------------------------------------------------------------ cache init
@@ -568,7 +595,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     cache_fill(c, g, d, max_batch_edges, max_batch_feats);
     Bump b{static_cast<char*>(workspace), 0};
     cache_layout(b, c);
-    const size_t lc_bytes = ((NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs) + 255) & ~size_t(255);
+    const size_t lc_bytes = ((NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) + 255) & ~size_t(255);
     if (hipHostMalloc((void**)&c->lc_host, lc_bytes + 1024 * NRT_MAX_LAYERS * sizeof(unsigned long long),
                       hipHostMallocDefault) != hipSuccess) {
         delete c;
@@ -581,7 +608,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         NRT_TRY(k_copy_f32(c->H[0], features, n * c->dims[0], s));
         NRT_TRY(k_fill_u32((uint32_t*)c->sc.feat_stamp, n, 0, s));
         NRT_TRY(k_fill_u32((uint32_t*)c->flags, (n + 64) / 4, 0, s));
-        NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs) / 8, 0, s));
+        NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
         for (int l = 0; l < c->L; ++l) {
             const int kin = (c->kind == NRT_SAGE_MEAN ? 2 : 1) * c->dims[l];
             NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
@@ -597,18 +624,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
                 else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][1], c->dims[l + 1], 0, s));
             }
         }
-        // every vertex is a destination: records and hub items once (kept in lc[1]), then layer by layer
-        NRT_TRY(k_dst_records(nullptr, n, g->in, c->recs, c->hubs, &c->lc[1], true, s));
-        NRT_TRY(k_fill_u64(&c->lc[1].count, 1, (uint64_t)n, s));
-        for (int l = 1; l <= c->L; ++l) {
-            if (l > 1) HIP_TRY(hipMemcpyAsync(&c->lc[l], &c->lc[1], sizeof(LayerCtrs), hipMemcpyDeviceToDevice, s));
-            if (c->kind == NRT_GAT) {
-                NRT_TRY(run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, 0, nullptr, 0, s));
-                continue;
-            }
-            NRT_TRY(run_gather(c, l, false, 0, s));
-            NRT_TRY(run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, s));
-        }
+        NRT_TRY(full_forward(c, s));
         HIP_TRY(hipStreamSynchronize(s));
         return NRT_OK;
     };
@@ -663,7 +679,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         FillJobs f;
         memset(&f, 0, sizeof(f));
         f.add(c->bm_ddst, 2 * c->nw_pad);                     // bm_ddst and bm_feat are adjacent
-        f.add(c->lc, (int64_t)((NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs) / 4));
+        f.add(c->lc, (int64_t)((NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 4));
         if (c->profiling) f.add(c->pair_ctr, 2 * 1024 * NRT_MAX_LAYERS);
         if (c->kind != NRT_GAT)
             for (int l = 1; l <= c->L; ++l) f.add(c->SD[l], (b->n_ins + b->n_del) * (int64_t)c->dagg[l]);
@@ -700,16 +716,17 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
 
     // ---- sets of the batch, per-layer counters
     const bool gcn = c->kind == NRT_GCN;
+    const bool inc = c->mode == NRT_MODE_INCREMENTAL;
     NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
-    if (gcn) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
-    if (c->kind != NRT_GAT && b->n_ins + b->n_del > 0) {
+    if (gcn && inc) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
+    if (inc && c->kind != NRT_GAT && b->n_ins + b->n_del > 0) {
         // destinations of updated edges -> compact rows that collect their structural terms (bm[1] is scratch here)
         NRT_TRY(k_compact(nullptr, c->bm_ddst, nullptr, c->bm[1], n, c->list_dd, c->slot_dd, g->scan_tmp, g->scan_tmp_len,
                           (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
     }
 
     // ---- structural terms on the old caches, all layers in one launch (GAT recomputes those destinations in full)
-    if (c->kind != NRT_GAT) {
+    if (inc && c->kind != NRT_GAT) {
         FoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
@@ -745,7 +762,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         da.H0 = c->H[0];
         da.DP = c->DP[0];
         da.D = c->dims[0];
-        if (gcn) { da.indeg_new = g->in.deg; da.indeg_old = c->indeg_old; }
+        if (gcn && inc) { da.indeg_new = g->in.deg; da.indeg_old = c->indeg_old; }
         NRT_TRY(k_layer0_delta(da, s));
     }
     NRT_TRY(prof_mark(c, TAG_INGEST, 0, s));
@@ -760,25 +777,32 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
         NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
                           g->scan_tmp_len, &c->lc[l].count, s));
-        if (c->kind == NRT_GAT) {
-            NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, s));
+        if (c->mode == NRT_MODE_FULL) {                    // only the affected lists are needed layer by layer
             NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
-            NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
-                                  prev, l == c->L ? affected_rows : nullptr, capacity, s));
-            NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
             prev = cur;
             continue;
         }
         NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, s));
         NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
-        NRT_TRY(run_gather(c, l, true, prev, s));
-        NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, true, cur, l == c->L ? affected_rows : nullptr,
-                           capacity, s));
+        if (c->kind == NRT_GAT) {
+            NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
+                                  inc, prev, l == c->L ? affected_rows : nullptr, capacity, s));
+        } else {
+            NRT_TRY(run_gather(c, l, inc, prev, s));
+            NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, inc, cur, l == c->L ? affected_rows : nullptr,
+                               capacity, s));
+        }
         NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
         prev = cur;
     }
+    if (c->mode == NRT_MODE_FULL) {
+        NRT_TRY(full_forward(c, s));
+        if (affected_rows)
+            NRT_TRY(k_gather_rows(affected_rows, c->H[c->L], c->list[c->L], &c->lc[c->L].count, capacity, n, c->dims[c->L], s));
+        NRT_TRY(prof_mark(c, TAG_UPDATE, c->L, s));
+    }
     NRT_TRY(k_copy_counted_i32(affected_ids, c->list[c->L], &c->lc[c->L].count, capacity, n, s));
-    HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, (NRT_MAX_LAYERS + 1) * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
     if (c->profiling)
         HIP_TRY(hipMemcpyAsync(c->pair_host, c->pair_ctr, 1024 * NRT_MAX_LAYERS * sizeof(unsigned long long),
                                hipMemcpyDeviceToHost, s));
@@ -792,6 +816,13 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         for (int q = 0; q < 16; ++q) ls->n_in_edges += (int64_t)c->lc_host[l].in_edges[q];
         if ((int64_t)c->lc_host[l].n_hubs > c->hubs.hub_cap || (int64_t)c->lc_host[l].n_items > c->hubs.item_cap ||
             (int64_t)c->lc_host[l - 1].n_xhubs > c->xhub_cap) {
+            nrt_set_error("internal: hub buffers too small");
+            return NRT_ERR_STATE;
+        }
+    }
+    if (c->mode == NRT_MODE_FULL) {
+        const LayerCtrs& all = c->lc_host[NRT_MAX_LAYERS + 1];
+        if ((int64_t)all.n_hubs > c->hubs.hub_cap || (int64_t)all.n_items > c->hubs.item_cap) {
             nrt_set_error("internal: hub buffers too small");
             return NRT_ERR_STATE;
         }
@@ -836,6 +867,12 @@ extern "C" nrt_status nrt_get_layer_affected(const nrt_cache* c, int32_t layer, 
     REQUIRE(layer >= 1 && layer <= c->L, "layer out of range");
     *ids = c->list[layer];
     *n = c->n_list[layer];
+    return NRT_OK;
+}
+extern "C" nrt_status nrt_set_mode(nrt_cache* c, int32_t mode) {
+    REQUIRE(c, "null argument");
+    REQUIRE(mode == NRT_MODE_INCREMENTAL || mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL, "unknown mode");
+    c->mode = mode;
     return NRT_OK;
 }
 extern "C" nrt_status nrt_set_profiling(nrt_cache* c, int32_t on) {

@@ -95,6 +95,9 @@ struct FillJobs {
     void add(void* p, int64_t n_words, uint32_t v = 0) { if (n_words > 0 && count < 12) { j[count].p = (uint32_t*)p; j[count].n = n_words; j[count].v = v; ++count; } }
 };
 nrt_status k_multi_fill(const FillJobs& f, hipStream_t s);
+// dst[i][:] = src[list[i]][:] for i < min(*count, cap); rows of D floats, D a multiple of 4
+nrt_status k_gather_rows(float* dst, const float* src, const int32_t* list, const uint64_t* count, int64_t cap, int64_t bound,
+                         int D, hipStream_t s);
 nrt_status k_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
 nrt_status k_or_words(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t nwords, hipStream_t s);
 nrt_status k_copy_i32(int32_t* dst, const int32_t* src, int64_t n, hipStream_t s);

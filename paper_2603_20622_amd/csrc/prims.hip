@@ -52,6 +52,18 @@ __global__ void multi_fill_kernel(FillJobs f) {
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < j.n; i += stride) j.p[i] = j.v;
 }
+// dst[i][:] = src[list[i]][:] for i < min(*count, cap); one wave per row, 16 bytes per lane and trip
+__global__ void gather_rows_kernel(float* dst, const float* src, const int32_t* list, const uint64_t* count, int64_t cap, int D) {
+    int64_t n = (int64_t)*count;
+    if (n > cap) n = cap;
+    const int lane = threadIdx.x & 63;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; i < n; i += waves) {
+        const float* p = src + (int64_t)list[i] * D;
+        for (int k = lane * 4; k < D; k += 256)
+            *reinterpret_cast<float4*>(dst + i * D + k) = *reinterpret_cast<const float4*>(p + k);
+    }
+}
 __global__ void or_words_kernel(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -220,6 +232,15 @@ nrt_status k_multi_fill(const FillJobs& f, hipStream_t s) {
     if (longest <= 0) return NRT_OK;
     dim3 grid((unsigned)grid_for(longest, 256), (unsigned)f.count, 1);
     multi_fill_kernel<<<grid, 256, 0, s>>>(f);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_gather_rows(float* dst, const float* src, const int32_t* list, const uint64_t* count, int64_t cap, int64_t bound,
+                         int D, hipStream_t s) {
+    if (bound <= 0 || cap <= 0) return NRT_OK;
+    int64_t g = cdiv(bound < cap ? bound : cap, 4);
+    if (g > 4096) g = 4096;
+    gather_rows_kernel<<<(int)g, 256, 0, s>>>(dst, src, list, count, cap, D);
     LAUNCH_CHECK();
     return NRT_OK;
 }

@@ -77,6 +77,9 @@ class Session:
     def stats(self):
         return nb.nrt_get_stats(self.cache)
 
+    def mode(self, mode: int):
+        nb.nrt_set_mode(self.cache, mode)
+
     def profiling(self, on: bool):
         nb.nrt_set_profiling(self.cache, on)
 

@@ -333,3 +333,26 @@ def test_capacity_too_small_still_updates_caches(S, oracle):
     assert ei.value.status == nb.NRT_ERR_INVALID_ARG
     cur = oracle.apply_batch(n, src, dst, w, x, b)
     assert rel_err(ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1]) <= TOL
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("mode", [1, 2])
+def test_recompute_modes_match_oracle(S, oracle, kind, mode):
+    """Section II-C baselines on the same caches: affected-vertex recomputation (1) and whole-graph recomputation
+    (2) return the same affected lists and embeddings; switching back to incremental afterwards keeps working."""
+    n, src, dst, w, x, spec, params, stream = small_case(kind, seed=71)
+    ses = S.Session(spec, params, n, src, dst, w, x)
+    cur = (src, dst, w, x)
+    L = spec.n_layers
+    for k, m in enumerate([mode, mode, 0, mode, 0]):
+        ses.mode(m)
+        b = stream.next_batch(30, 30, 8)
+        na = ses.apply(b)
+        cur = oracle.apply_batch(n, *cur, b)
+        ref = oracle.forward(spec, params, n, *cur)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        ids = ses.ids[:na].cpu().numpy()
+        assert np.array_equal(ids, sets[-1]), (kind, mode, k)
+        for l in range(1, L + 1):
+            assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, mode, k, l))
+        assert_parity(kind, ses.rows[:na].cpu().numpy(), ref[-1][ids], (kind, mode, k, "rows"))
