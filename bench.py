@@ -156,7 +156,7 @@ def main():
 
     # HBM bytes per launch measured with rocprofv3 counters on this workload (committed summary), if present
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "gather_kernel_%s_hbm_traffic.txt" % cfg.name)
+    tpath = os.path.join(ROOT, "profiles", "gather_sparse_kernel_%s_hbm_traffic.txt" % cfg.name)
     if args.scale == 1.0 and not args.batch_edges and os.path.exists(tpath):
         for line in open(tpath):
             if line.startswith("traffic_bytes_per_launch:"):
@@ -165,7 +165,8 @@ def main():
     g_avg_ms = agg["gather_ms"] / nl
     g_avg_bytes = agg["gather_bytes"] / nl
     achieved = (g_avg_bytes / 1e9) / (g_avg_ms / 1e3) if g_avg_ms > 0 else 0.0
-    roofline = {"kernel": "gather_kernel (delta-message gather + fold)", "bound": "hbm",
+    roofline = {"kernel": "delta-message gather + fold (gather_sparse_kernel on layers with few changed sources, "
+                          "gather_kernel otherwise)", "bound": "hbm",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_launch_ms": round(g_avg_ms, 4), "avg_launch_bytes": round(g_avg_bytes),
