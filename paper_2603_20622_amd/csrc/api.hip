@@ -65,6 +65,8 @@ struct nrt_cache {
     float *part_m, *part_den;
     bool is_gat;
     float* SD[NRT_MAX_LAYERS + 1];      // structural-delta rows of a batch, [max_edges][dagg[l]]
+    float* SDden[NRT_MAX_LAYERS + 1];   // GAT: their attention-sum part, [max_edges][heads]
+    int32_t* ins_cnt;                   // GAT: inserted in-edges per destination of an updated edge, [max_edges]
     int32_t *list_dd, *slot_dd;         // destinations of updated edges: sorted ids, vertex -> row of SD
     DstRec* recs;
     HubWork hubs;
@@ -269,7 +271,11 @@ static void cache_layout(Bump& b, nrt_cache* c) {
             c->att_dst[l - 1] = b.take<float>((size_t)c->heads * c->head_dim);
         }
     }
-    for (int l = 1; l <= c->L; ++l) c->SD[l] = gat ? nullptr : b.take<float>((size_t)(c->max_edges + 1) * c->dagg[l]);
+    for (int l = 1; l <= c->L; ++l) {
+        c->SD[l] = b.take<float>((size_t)(c->max_edges + 1) * c->dagg[l]);
+        c->SDden[l] = gat ? b.take<float>((size_t)(c->max_edges + 1) * c->heads) : nullptr;
+    }
+    c->ins_cnt = gat ? b.take<int32_t>(c->max_edges + 1) : nullptr;
     c->list_dd = b.take<int32_t>(c->max_edges + 64);
     c->slot_dd = b.take<int32_t>(n);
     c->AS_old = gat ? b.take<float>(n * c->heads) : nullptr;
@@ -536,6 +542,11 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
         a.src_bitmap = c->bm[prev];
         a.src_slot = c->slot[prev];
         a.ddst_bitmap = c->bm_ddst;
+        a.dd_slot = c->slot_dd;
+        a.sd_s = c->SD[l];
+        a.sd_den = c->SDden[l];
+        a.ins_cnt = c->ins_cnt;
+        a.n_src_dev = n_src_dev;
     }
     a.M = c->M[l];
     a.DEN = c->DEN[l];
@@ -557,7 +568,7 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
     nrt_graph* g = c->g;
     const int64_t n = g->n;
     LayerCtrs* all = &c->lc[NRT_MAX_LAYERS + 1];
-    NRT_TRY(k_dst_records(nullptr, n, g->in, c->recs, c->hubs, all, true, s));
+    NRT_TRY(k_dst_records(nullptr, n, g->in, c->recs, c->hubs, all, true, nullptr, s));
     NRT_TRY(k_fill_u64(&all->count, 1, (uint64_t)n, s));
     c->lc_use = all;
     nrt_status st = NRT_OK;
@@ -681,8 +692,11 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         f.add(c->bm_ddst, 2 * c->nw_pad);                     // bm_ddst and bm_feat are adjacent
         f.add(c->lc, (int64_t)((NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 4));
         if (c->profiling) f.add(c->pair_ctr, 2 * 1024 * NRT_MAX_LAYERS);
-        if (c->kind != NRT_GAT)
-            for (int l = 1; l <= c->L; ++l) f.add(c->SD[l], (b->n_ins + b->n_del) * (int64_t)c->dagg[l]);
+        for (int l = 1; l <= c->L; ++l) {
+            f.add(c->SD[l], (b->n_ins + b->n_del) * (int64_t)c->dagg[l]);
+            if (c->kind == NRT_GAT) f.add(c->SDden[l], (b->n_ins + b->n_del) * (int64_t)c->heads);
+        }
+        if (c->kind == NRT_GAT) f.add(c->ins_cnt, b->n_ins + b->n_del);
         NRT_TRY(graph_validate_batch(g, b, c->sc, &f, s));
     }
     NRT_TRY(read_ctrs(g, s));
@@ -719,13 +733,27 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     const bool inc = c->mode == NRT_MODE_INCREMENTAL;
     NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
     if (gcn && inc) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
-    if (inc && c->kind != NRT_GAT && b->n_ins + b->n_del > 0) {
+    if (inc && b->n_ins + b->n_del > 0) {
         // destinations of updated edges -> compact rows that collect their structural terms (bm[1] is scratch here)
         NRT_TRY(k_compact(nullptr, c->bm_ddst, nullptr, c->bm[1], n, c->list_dd, c->slot_dd, g->scan_tmp, g->scan_tmp_len,
                           (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
     }
 
-    // ---- structural terms on the old caches, all layers in one launch (GAT recomputes those destinations in full)
+    // ---- structural terms on the old caches, all layers in one launch
+    if (inc && c->kind == NRT_GAT) {
+        GatFoldArgs f;
+        memset(&f, 0, sizeof(f));
+        f.n_ins = b->n_ins; f.n_del = b->n_del;
+        f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
+        f.dd_slot = c->slot_dd;
+        f.ins_cnt = c->ins_cnt;
+        f.n_layers = c->L; f.heads = c->heads; f.head_dim = c->head_dim; f.slope = c->leaky_slope;
+        for (int l = 1; l <= c->L; ++l) {
+            f.Z[l - 1] = c->Z[l]; f.AS[l - 1] = c->AS[l]; f.AD[l - 1] = c->AD[l]; f.M[l - 1] = c->M[l];
+            f.SDS[l - 1] = c->SD[l]; f.SDDEN[l - 1] = c->SDden[l];
+        }
+        NRT_TRY(k_gat_structural_fold(f, s));
+    }
     if (inc && c->kind != NRT_GAT) {
         FoldArgs f;
         memset(&f, 0, sizeof(f));
@@ -782,7 +810,10 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             prev = cur;
             continue;
         }
-        NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, s));
+        // GAT with only edge updates in the layer (no z changed): every destination takes the O(#updates) path of
+        // Algorithm 3, also those with long in-lists, so no items are cut
+        NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false,
+                              (c->kind == NRT_GAT && inc) ? &c->lc[l - 1].count : nullptr, s));
         NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
         if (c->kind == NRT_GAT) {
             NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,

@@ -90,9 +90,9 @@ nrt_status k_fill_u32(uint32_t* p, int64_t n, uint32_t v, hipStream_t s);
 // several fills in one launch (a batch clears a dozen small scratch areas; separate launches would cost more than the stores)
 struct FillJob { uint32_t* p; int64_t n; uint32_t v; };      // n 32-bit words
 struct FillJobs {
-    FillJob j[12];
+    FillJob j[16];
     int count;
-    void add(void* p, int64_t n_words, uint32_t v = 0) { if (n_words > 0 && count < 12) { j[count].p = (uint32_t*)p; j[count].n = n_words; j[count].v = v; ++count; } }
+    void add(void* p, int64_t n_words, uint32_t v = 0) { if (n_words > 0 && count < 16) { j[count].p = (uint32_t*)p; j[count].n = n_words; j[count].v = v; ++count; } }
 };
 nrt_status k_multi_fill(const FillJobs& f, hipStream_t s);
 // dst[i][:] = src[list[i]][:] for i < min(*count, cap); rows of D floats, D a multiple of 4
@@ -170,8 +170,9 @@ struct GatherArgs {
     int coarse_words;          // at most NRT_COARSE_WORDS
 };
 // destination records of list[0 .. *count) (list null: all n vertices), hub list and hub items; fills lc
+// `plain_if_zero` (may be null): when the device counter it points to is 0, long in-lists are not cut into items
 nrt_status k_dst_records(const int32_t* list, int64_t bound, const Adj& in, DstRec* recs, const HubWork& hubs,
-                         LayerCtrs* lc, bool all_vertices, hipStream_t s);
+                         LayerCtrs* lc, bool all_vertices, const uint64_t* plain_if_zero, hipStream_t s);
 nrt_status k_gather(const GatherArgs& a, hipStream_t s);
 nrt_status k_coarse_bitmap(const uint32_t* fine, int64_t n, int shift, uint32_t* coarse, int64_t n_words, hipStream_t s);
 nrt_status k_combine_partials(const GatherArgs& a, hipStream_t s);
@@ -245,6 +246,14 @@ struct GatArgs {
     const uint32_t* src_bitmap;     // vertices whose z changed (null: full forward for every row)
     const int32_t* src_slot;        // their slots in Z_old / AS_old
     const uint32_t* ddst_bitmap;    // destinations of updated edges
+    // structural terms of the batch for those destinations (Algorithm 3 applied to edge updates): compact rows,
+    // one per destination of an updated edge, holding minus the old attention terms of its deleted in-edges
+    // relative to the destination's cached bound m; its inserted in-edges are the last ins_cnt entries of its in-list
+    const int32_t* dd_slot;         // vertex -> row of sd_s / sd_den / ins_cnt
+    const float* sd_s;              // [rows][D]
+    const float* sd_den;            // [rows][heads]
+    const int32_t* ins_cnt;         // [rows]
+    const uint64_t* n_src_dev;      // number of vertices whose z changed in this layer (gather, incremental)
     float* M; float* DEN;           // [N][heads]
     float* S;                       // [N][D]
     float* Hout;                    // [N][D] layer output
@@ -252,6 +261,18 @@ struct GatArgs {
     float* out_rows; int64_t out_cap;
 };
 nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s);
+struct GatFoldArgs {   // structural terms of a batch for GAT, evaluated on the pre-update caches, all layers in one launch
+    int64_t n_ins, n_del;
+    const int32_t *ins_dst, *del_src, *del_dst;
+    const int32_t* dd_slot;
+    int32_t* ins_cnt;
+    int n_layers, heads, head_dim;
+    float slope;
+    const float* Z[NRT_MAX_LAYERS]; const float* AS[NRT_MAX_LAYERS]; const float* AD[NRT_MAX_LAYERS];
+    const float* M[NRT_MAX_LAYERS];
+    float* SDS[NRT_MAX_LAYERS]; float* SDDEN[NRT_MAX_LAYERS];
+};
+nrt_status k_gat_structural_fold(const GatFoldArgs& a, hipStream_t s);
 nrt_status k_gat_gather(const GatArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------- graph.hip

@@ -6,14 +6,19 @@
 // m so that exp cannot overflow) and the context-free aggregate S = sum exp(e - m) z_u (Algorithm 3's a-hat).
 //
 // For an affected destination v:
-//   * if its own z changed (its layer input changed) or it gained/lost an in-edge, every logit of v may have
-//     changed: v is recomputed over its full new in-neighbourhood plus itself (Algorithm 2; the constrained-model
-//     rule of Section III-D / Algorithm 4 lines 5-7);
-//   * otherwise only the in-neighbours whose z changed contribute (Algorithm 3 lines 2-7):
-//       den += sum (at_new - at_old),  S += sum (at_new z_new - at_old z_old),
-//     after raising m if a new logit exceeds it (den and S are rescaled by exp(m_old - m_new)).  When the update
-//     removes most of the old attention mass (den shrinks below 1/64 of its old value) the subtraction has
-//     cancelled the leading digits, and v is recomputed in full instead.
+//   * if its own z changed (its layer input changed), every logit of v has changed: v is recomputed over its full
+//     new in-neighbourhood plus itself (Algorithm 2; the constrained-model rule of Section III-D / Algorithm 4
+//     lines 5-7);
+//   * otherwise Algorithm 3 (lines 2-7) touches only what changed:
+//       den += sum (at_new - at_old),  S += sum (at_new z_new - at_old z_old)
+//     over the in-neighbours whose z changed, plus the edge updates of the batch: a deleted in-edge contributes
+//     (-at_old, -at_old z_old), folded on the old caches into a compact row per destination before the graph
+//     changes (gat_structural_fold_kernel); an inserted in-edge contributes (+at_new, +at_new z_new) and is found
+//     at the end of the in-list, where the graph appends.  m is raised first if a new logit exceeds it (den and S
+//     are rescaled by exp(m_old - m_new)).  When the update removes most of the old attention mass (den shrinks
+//     below 1/64 of its old value) the subtraction has cancelled the leading digits, and v is recomputed in full.
+//   A destination with more than NRT_CHUNK in-edges is recomputed in full through its items whenever some z
+//   changed in the layer; when none did (edge updates only) it takes the same O(#updates) path as the others.
 // One wave per destination; lane = 4 consecutive columns of the row, a head = head_dim/4 neighbouring lanes.
 #include "common.h"
 
@@ -43,6 +48,34 @@ __global__ void gat_scalars_kernel(GatArgs a) {
             a.AS[v * a.heads + k] = ps;
             a.AD[v * a.heads + k] = pd;
         }
+    }
+}
+
+// ------------------------------------------------------------------ structural terms (Algorithm 3 on edge updates)
+// One wave per (updated edge, layer), before the graph and the caches change.  Deleted edge u->v: minus its old
+// attention term, relative to v's cached bound m, into the compact row of v.  Inserted edge: layer 0 counts it for
+// its destination (the gather finds that many new entries at the end of the in-list).
+__global__ void gat_structural_fold_kernel(GatFoldArgs a) {
+    const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    const int l = blockIdx.y;
+    if (op >= a.n_ins + a.n_del) return;
+    if (op < a.n_ins) {
+        if (l == 0 && lane == 0) atomicAdd(&a.ins_cnt[a.dd_slot[a.ins_dst[op]]], 1);
+        return;
+    }
+    const int64_t i = op - a.n_ins;
+    const int32_t u = a.del_src[i], v = a.del_dst[i];
+    const int64_t row = a.dd_slot[v];
+    const int H = a.heads, hd = a.head_dim, D = H * hd;
+    for (int col = lane * 4; col < D; col += 256) {
+        const int k = col / hd;
+        const float e = leaky(a.AD[l][(int64_t)v * H + k] + a.AS[l][(int64_t)u * H + k], a.slope);
+        const float w = __expf(e - a.M[l][(int64_t)v * H + k]);        // at most 1: m bounds every cached logit of v
+        const float4 z = *reinterpret_cast<const float4*>(a.Z[l] + (int64_t)u * D + col);
+        float* dst = a.SDS[l] + row * D + col;
+        atomicAdd(dst + 0, -w * z.x); atomicAdd(dst + 1, -w * z.y); atomicAdd(dst + 2, -w * z.z); atomicAdd(dst + 3, -w * z.w);
+        if (col % hd == 0) atomicAdd(a.SDDEN[l] + row * H + k, -w);
     }
 }
 
@@ -162,6 +195,7 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
         live[q] = col[q] < D;
         head[q] = live[q] ? col[q] / hd : 0;
     }
+    const bool any_src = !(a.src_bitmap && a.n_src_dev && *a.n_src_dev == 0);   // false: only edge updates in this layer
     for (int64_t unit = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; unit < n_items + n_dst; unit += waves) {
         float adv[NV], mcur[NV], den[NV];
         float4 acc[NV];
@@ -185,28 +219,47 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
         }
         const int64_t s = unit - n_items;
         const DstRec rec = a.recs[s];
-        if (rec.deg > NRT_CHUNK) continue;
+        if (rec.deg > NRT_CHUNK && any_src) continue;         // served through its items
         const int32_t v = rec.v;
         const int64_t off = rec.off;
         const int32_t deg = rec.deg;
         bool full = true;
+        int32_t n_new = 0;          // inserted in-edges of v: the last n_new entries of its in-list
+        int64_t sd_row = -1;        // row of v's structural terms
         if (a.src_bitmap) {
             const bool own = (a.src_bitmap[v >> 5] >> (v & 31)) & 1u;
             const bool edge = (a.ddst_bitmap[v >> 5] >> (v & 31)) & 1u;
-            full = own || edge;
+            full = own;
+            if (edge && !own) { sd_row = a.dd_slot[v]; n_new = a.ins_cnt[sd_row]; }
         }
 #pragma unroll
         for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)v * H + head[q]] : 0.f;
 
         if (!full) {
-            // ---- Algorithm 3: only the in-neighbours whose z changed
+            // ---- Algorithm 3: the in-neighbours whose z changed (entries before the inserted ones, skipped when no z
+            // changed in this layer) and the inserted entries
+            const int32_t n_kept = deg - n_new;
+            const int32_t scan_end = any_src ? n_kept : 0;
             float mold[NV];
 #pragma unroll
             for (int q = 0; q < NV; ++q) { mold[q] = live[q] ? a.M[(int64_t)v * H + head[q]] : 0.f; mcur[q] = mold[q]; }
             // pass 1: raise the bound to the largest new logit
-            for (int32_t j0 = 0; j0 < deg; j0 += 64) {
+            for (int32_t j0 = n_kept; j0 < deg; j0 += 64) {
                 const int32_t jj = j0 + lane;
-                int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                unsigned long long mask = __ballot(u >= 0);
+                while (mask) {
+                    const int bit = __ffsll((long long)mask) - 1;
+                    mask &= mask - 1;
+                    const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+#pragma unroll
+                    for (int q = 0; q < NV; ++q)
+                        if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+                }
+            }
+            for (int32_t j0 = 0; j0 < scan_end; j0 += 64) {
+                const int32_t jj = j0 + lane;
+                int32_t u = jj < scan_end ? a.in.idx[off + jj] : -1;
                 bool ok = u >= 0 && ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u);
                 unsigned long long mask = __ballot(ok);
                 while (mask) {
@@ -229,12 +282,36 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 if (live[q]) {
                     const float4 so = *reinterpret_cast<const float4*>(a.S + (int64_t)v * D + col[q]);
                     acc[q] = make_float4(so.x * f, so.y * f, so.z * f, so.w * f);
+                    if (sd_row >= 0) {                            // deleted in-edges: terms relative to mold
+                        const float4 sd = *reinterpret_cast<const float4*>(a.sd_s + sd_row * D + col[q]);
+                        den[q] += a.sd_den[sd_row * H + head[q]] * f;
+                        acc[q].x += sd.x * f; acc[q].y += sd.y * f; acc[q].z += sd.z * f; acc[q].w += sd.w * f;
+                    }
                 }
             }
-            // pass 2: exchange old terms for new ones
-            for (int32_t j0 = 0; j0 < deg; j0 += 64) {
+            // pass 2: the inserted in-edges bring new terms ...
+            for (int32_t j0 = n_kept; j0 < deg; j0 += 64) {
                 const int32_t jj = j0 + lane;
-                int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                unsigned long long mask = __ballot(u >= 0);
+                while (mask) {
+                    const int bit = __ffsll((long long)mask) - 1;
+                    mask &= mask - 1;
+                    const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+#pragma unroll
+                    for (int q = 0; q < NV; ++q) {
+                        if (!live[q]) continue;
+                        const float cn = __expf(leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope) - mcur[q]);
+                        const float4 zn = *reinterpret_cast<const float4*>(a.Z + (int64_t)uu * D + col[q]);
+                        den[q] += cn;
+                        acc[q].x += cn * zn.x; acc[q].y += cn * zn.y; acc[q].z += cn * zn.z; acc[q].w += cn * zn.w;
+                    }
+                }
+            }
+            // ... and the kept in-edges whose source changed exchange their old term for the new one
+            for (int32_t j0 = 0; j0 < scan_end; j0 += 64) {
+                const int32_t jj = j0 + lane;
+                int32_t u = jj < scan_end ? a.in.idx[off + jj] : -1;
                 bool ok = u >= 0 && ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u);
                 int32_t sl = ok ? a.src_slot[u] : -1;
                 unsigned long long mask = __ballot(ok);
@@ -330,6 +407,15 @@ nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s) {
     const int64_t bound = a.rows ? a.rows_bound : a.n;
     if (bound <= 0) return NRT_OK;
     gat_scalars_kernel<<<(unsigned)cdiv(bound * 64, 256), 256, 0, s>>>(a);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_gat_structural_fold(const GatFoldArgs& a, hipStream_t s) {
+    const int64_t nops = a.n_ins + a.n_del;
+    if (nops <= 0) return NRT_OK;
+    dim3 grid((unsigned)cdiv(nops * 64, 256), (unsigned)a.n_layers, 1);
+    gat_structural_fold_kernel<<<grid, 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }

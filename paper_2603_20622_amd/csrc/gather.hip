@@ -63,10 +63,12 @@ __device__ inline uint64_t rec_block_scan(uint64_t v, uint64_t* total, uint64_t*
 }
 
 __global__ void __launch_bounds__(REC_THREADS)
-dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, HubWork hubs, LayerCtrs* lc) {
+dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, HubWork hubs, LayerCtrs* lc,
+                   const uint64_t* plain_if_zero) {
     __shared__ uint64_t wsum[REC_THREADS / 64];
     __shared__ unsigned long long s_hbase, s_ibase;
     const int64_t count = list ? (int64_t)lc->count : n_all;
+    const bool no_items = plain_if_zero && *plain_if_zero == 0;
     const int64_t per_round = (int64_t)REC_THREADS * REC_EPT;
     const int64_t stride = (int64_t)gridDim.x * per_round;
     uint64_t degsum = 0;
@@ -92,7 +94,7 @@ dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, Hub
             if (i < count) {
                 recs[i] = r[e];
                 degsum += (uint64_t)r[e].deg;
-                if (r[e].deg > NRT_CHUNK) nch[e] = (uint64_t)((r[e].deg + NRT_CHUNK - 1) / NRT_CHUNK);
+                if (r[e].deg > NRT_CHUNK && !no_items) nch[e] = (uint64_t)((r[e].deg + NRT_CHUNK - 1) / NRT_CHUNK);
                 mine += nch[e] ? ((1ULL << 32) | nch[e]) : 0ULL;     // high 32 bits: hubs, low 32 bits: items
             }
         }
@@ -846,11 +848,11 @@ __global__ void layer0_delta_kernel(DeltaArgs a) {
 }  // namespace
 
 nrt_status k_dst_records(const int32_t* list, int64_t bound, const Adj& in, DstRec* recs, const HubWork& hubs,
-                         LayerCtrs* lc, bool all_vertices, hipStream_t s) {
+                         LayerCtrs* lc, bool all_vertices, const uint64_t* plain_if_zero, hipStream_t s) {
     if (bound <= 0) return NRT_OK;
     int64_t g = cdiv(bound, (int64_t)REC_THREADS * REC_EPT);
     if (g > 1024) g = 1024;
-    dst_records_kernel<<<(int)g, REC_THREADS, 0, s>>>(all_vertices ? nullptr : list, bound, in, recs, hubs, lc);
+    dst_records_kernel<<<(int)g, REC_THREADS, 0, s>>>(all_vertices ? nullptr : list, bound, in, recs, hubs, lc, plain_if_zero);
     LAUNCH_CHECK();
     return NRT_OK;
 }

@@ -356,3 +356,26 @@ def test_recompute_modes_match_oracle(S, oracle, kind, mode):
         for l in range(1, L + 1):
             assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, mode, k, l))
         assert_parity(kind, ses.rows[:na].cpu().numpy(), ref[-1][ids], (kind, mode, k, "rows"))
+
+
+def test_gat_edge_updates_only_with_long_in_lists(S, oracle):
+    """No feature changes: no z changes at layer 1, so every affected destination there, also those with more than
+    256 in-edges, is updated from its inserted / deleted in-edges alone (Algorithm 3 applied to edge updates)."""
+    n, e = 1200, 60000
+    src, dst, sampler = wl.rmat_graph(n, e, 81)
+    assert np.bincount(dst, minlength=n).max() > 600
+    spec = wl.ModelSpec(wl.GAT, [16, 32, 32], heads=4, head_dim=8)
+    params = wl.make_params(spec, 81, bias=True)
+    x = wl.features(n, 16, 81)
+    stream = wl.BatchStream(n, src, dst, None, sampler, 16, 81)
+    ses = S.Session(spec, params, n, src, dst, None, x)
+    cur = (src, dst, None, x)
+    for k, (ni, nd) in enumerate([(40, 40), (0, 60), (60, 0), (1, 0), (0, 1), (200, 200)]):
+        b = stream.next_batch(ni, nd, 0)
+        na = ses.apply(b)
+        cur = oracle.apply_batch(n, *cur, b)
+        ref = oracle.forward(spec, params, n, *cur)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1]), k
+        for l in (1, 2):
+            assert_parity(wl.GAT, ses.layer(l).cpu().numpy(), ref[l - 1], ("gat-struct", k, l))
