@@ -156,11 +156,12 @@ def main():
 
     # HBM bytes per launch measured with rocprofv3 counters on this workload (committed summary), if present
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "gather_sparse_kernel_%s_hbm_traffic.txt" % cfg.name)
-    if args.scale == 1.0 and not args.batch_edges and os.path.exists(tpath):
-        for line in open(tpath):
-            if line.startswith("traffic_bytes_per_launch:"):
-                traffic = int(line.split(":")[1])
+    import glob
+    if args.scale == 1.0 and not args.batch_edges:
+        for tpath in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_%s_*.txt" % cfg.name))):
+            for line in open(tpath):
+                if line.startswith("traffic_bytes_per_launch:"):
+                    traffic = int(line.split(":")[1].split()[0])
     nl = max(1, agg["gather_launches"])
     g_avg_ms = agg["gather_ms"] / nl
     g_avg_bytes = agg["gather_bytes"] / nl

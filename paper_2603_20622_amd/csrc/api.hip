@@ -72,6 +72,7 @@ struct nrt_cache {
     HubWork hubs;
     BatchScratch sc;
     unsigned long long* pair_ctr;
+    int32_t* pull_list;        // [n] second-pass queue of the pull-direction expansion
     uint32_t* coarse;          // coarse changed-source filter of the current layer
     int coarse_shift, coarse_words;
     // profiling
@@ -330,6 +331,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->sc.feat_stamp = b.take<int32_t>(n);
     c->sc.err = g->dev_ctrs ? (int32_t*)(g->dev_ctrs + CTR_ERR) : nullptr;
     c->pair_ctr = b.take<unsigned long long>(1024 * NRT_MAX_LAYERS);
+    c->pull_list = b.take<int32_t>(n);
     c->coarse = b.take<uint32_t>(NRT_COARSE_WORDS);
     c->coarse_shift = 0;
     while ((((n + ((int64_t)1 << c->coarse_shift) - 1) >> c->coarse_shift) + 31) / 32 > NRT_COARSE_WORDS) ++c->coarse_shift;
@@ -680,7 +682,8 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     memset(&c->stats, 0, sizeof(c->stats));
     c->stats.n_layers = c->L;
     c->n_ev = 0;
-    for (int l = 0; l <= c->L; ++l) c->n_list[l] = 0;
+    int64_t prev_n_list[NRT_MAX_LAYERS + 1];            // sizes of the previous batch's sets: hints for this one
+    for (int l = 0; l <= c->L; ++l) { prev_n_list[l] = c->n_list[l]; c->n_list[l] = 0; }
     NRT_TRY(prof_mark(c, TAG_START, 0, s));
 
     // ---- validate (no state change yet); the one synchronisation before the end of the batch
@@ -800,8 +803,16 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     for (int l = 1; l <= c->L; ++l) {
         const int cur = 1 - prev;
         const int64_t src_bound = l == 1 ? n0_bound : n;
+        PullArgs pull;
+        memset(&pull, 0, sizeof(pull));
+        pull.allowed = prev_n_list[l - 1] * 16 > n;      // hint from the previous batch; the device decides (8x)
+        pull.n = n;
+        pull.src_bitmap = c->bm[prev];
+        pull.long_list = c->pull_list;
+        pull.long_cap = n;
+        pull.long_count = (unsigned long long*)&c->lc[l - 1].n_pull_long;
         NRT_TRY(k_expand_frontier(g->out, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->flags, &c->lc[l - 1],
-                                  c->xhub_list, c->xhub_cap, s));
+                                  c->xhub_list, c->xhub_cap, g->in, pull, s));
         NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
         NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
                           g->scan_tmp_len, &c->lc[l].count, s));

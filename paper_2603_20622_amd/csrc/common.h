@@ -82,7 +82,8 @@ struct LayerCtrs {
     uint64_t n_items;      // their items of NRT_CHUNK in-list entries
     uint64_t n_xhubs;      // sources with a long out-list queued by the expansion
     uint64_t in_edges[16]; // in-edges of the affected vertices (a statistic, spread over cells)
-    uint64_t pad[4];
+    uint64_t n_pull_long;  // vertices queued by the pull-direction expansion for its second pass
+    uint64_t pad[3];
 };
 
 // ---------------------------------------------------------------- prims.hip
@@ -116,9 +117,19 @@ nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b,
                      int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s);
 
 // ---------------------------------------------------------------- frontier.hip
-// flags[v] = 1 for every out-neighbour v of the sources src_list[0 .. *ns_dev)
+// flags[v] = 1 for every out-neighbour v of the sources src_list[0 .. *ns_dev) that is not itself a source
+// (sources may or may not get their flag: the caller ORs the source set in afterwards).
+struct PullArgs {              // pull direction of the hop, used when the source set is a large part of the graph
+    int allowed;               // host hint: the previous batch had a large source set at this hop
+    int64_t n;                 // vertices
+    const uint32_t* src_bitmap;   // the source set as a bitmap
+    int32_t* long_list;        // [long_cap] vertices handed from the first to the second pull pass
+    int64_t long_cap;
+    unsigned long long* long_count;   // device counter, zero on entry
+};
 nrt_status k_expand_frontier(const Adj& out, const int32_t* src_list, const uint64_t* ns_dev, int64_t ns_bound,
-                             uint8_t* flags, LayerCtrs* lc, int32_t* xhub_list, int64_t xhub_cap, hipStream_t s);
+                             uint8_t* flags, LayerCtrs* lc, int32_t* xhub_list, int64_t xhub_cap, const Adj& in,
+                             const PullArgs& pull, hipStream_t s);
 
 // ---------------------------------------------------------------- gather.hip
 // What a gather wave needs to know about destination slot s, in one 16-byte load.

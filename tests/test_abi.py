@@ -48,3 +48,22 @@ def test_struct_sizes_match_header():
     assert ctypes.sizeof(nb.nrt_model_desc) == 48 + 8 * (8 + 8 + 4 + 4)
     assert ctypes.sizeof(nb.nrt_batch) == 10 * 8
     assert ctypes.sizeof(nb.nrt_layer_stats) == 5 * 8 + 6 * 4
+
+
+def test_mode_and_profiling_reject_null_handles():
+    from paper_2603_20622_amd import binding as nb
+    L = nb.lib()
+    assert L.nrt_set_mode(None, nb.NRT_MODE_RECOMPUTE) == nb.NRT_ERR_INVALID_ARG
+    assert L.nrt_set_profiling(None, 1) == nb.NRT_ERR_INVALID_ARG
+    assert (nb.NRT_MODE_INCREMENTAL, nb.NRT_MODE_RECOMPUTE, nb.NRT_MODE_FULL) == (0, 1, 2)
+    text = open(os.path.join(ROOT, "include", "nrt.h")).read()
+    assert re.search(r"NRT_MODE_INCREMENTAL\s*=\s*0,\s*NRT_MODE_RECOMPUTE\s*=\s*1,\s*NRT_MODE_FULL\s*=\s*2", text)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
+    assert r.stdout.strip() == ""
