@@ -118,13 +118,18 @@ def main():
             flop = 2.0 * ls.n_affected * kin * dims[l + 1]
             if cfg.spec.kind == wl.GIN:
                 flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]
+            upd_ms = ls.ms_update
             if cfg.spec.kind == wl.GAT:
-                flop = 2.0 * ls.n_src * d_in * dims[l + 1]       # z = x W on the rows whose input changed
-            if ls.n_src:
+                flop = 2.0 * ls.n_src * d_in * dims[l + 1]       # z = x W on the rows whose input changed,
+                upd_ms = ls.ms_items                             # timed (with the attention scalars) before the gather
+                # GAT gather: every fetched z row (full recomputation of constrained destinations, old and new
+                # rows of exchanged terms) with its id and attention scalars; aggregate rows read and written
+                gbytes = ls.n_pairs * (4.0 * d_agg + 8.0 + 4.0 * cfg.spec.heads) + ls.n_affected * 12.0 * d_agg
+            if ls.n_src or (cfg.spec.kind == wl.GAT and ls.n_affected):
                 agg["gather_ms"] += ls.ms_gather
                 agg["gather_bytes"] += gbytes
                 agg["gather_launches"] += 1
-            agg["update_ms"] += ls.ms_update
+            agg["update_ms"] += upd_ms
             agg["update_flop"] += flop
             agg["expand_ms"] += ls.ms_expand
             agg["compact_ms"] += ls.ms_compact
@@ -132,7 +137,7 @@ def main():
             agg["combine_ms"] += ls.ms_combine
             pl = per_layer[l]
             pl["n_src"] += ls.n_src; pl["n_aff"] += ls.n_affected; pl["n_pairs"] += ls.n_pairs
-            pl["n_in"] += ls.n_in_edges; pl["gather_ms"] += ls.ms_gather; pl["update_ms"] += ls.ms_update
+            pl["n_in"] += ls.n_in_edges; pl["gather_ms"] += ls.ms_gather; pl["update_ms"] += upd_ms
             pl["bytes"] += gbytes
     torch.cuda.synchronize()
     ms_per_step_events = (time.perf_counter() - t_start2) * 1e3 / K
@@ -166,8 +171,10 @@ def main():
     g_avg_ms = agg["gather_ms"] / nl
     g_avg_bytes = agg["gather_bytes"] / nl
     achieved = (g_avg_bytes / 1e9) / (g_avg_ms / 1e3) if g_avg_ms > 0 else 0.0
-    roofline = {"kernel": "delta-message gather + fold (gather_sparse_kernel on layers with few changed sources, "
-                          "gather_kernel otherwise)", "bound": "hbm",
+    kname = ("gat_gather_kernel (attention gather: Algorithm 3 exchange / constrained full recomputation)"
+             if cfg.spec.kind == wl.GAT else
+             "delta-message gather + fold (gather_sparse_kernel on layers with few changed sources, gather_kernel otherwise)")
+    roofline = {"kernel": kname, "bound": "hbm",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
                 "avg_launch_ms": round(g_avg_ms, 4), "avg_launch_bytes": round(g_avg_bytes),

@@ -103,8 +103,9 @@ typedef struct {
     int64_t n_affected;   /* |A_l|                                                         */
     int64_t n_items;      /* work items (destination, in-list chunk) of the gather         */
     int64_t n_in_edges;   /* in-edges of A_l scanned by the gather                         */
-    int64_t n_pairs;      /* (source, destination) delta messages folded (profiling only)  */
-    float ms_expand, ms_compact, ms_items, ms_gather /* the gather kernel alone */, ms_combine, ms_update;
+    int64_t n_pairs;      /* source rows fetched: delta messages folded (GAT: z rows read) (profiling only) */
+    float ms_expand, ms_compact, ms_items /* GAT: the z product and attention scalars */,
+          ms_gather /* the gather kernels alone */, ms_combine, ms_update;
 } nrt_layer_stats;
 
 typedef struct {

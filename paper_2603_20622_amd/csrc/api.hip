@@ -558,6 +558,7 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
     a.act = last ? 0 : 2;
     a.out_rows = last ? out_rows : nullptr;
     a.out_cap = out_cap;
+    if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     NRT_TRY(k_gat_gather(a, s));
     NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
     return NRT_OK;

@@ -265,6 +265,7 @@ struct GatArgs {
     const float* sd_den;            // [rows][heads]
     const int32_t* ins_cnt;         // [rows]
     const uint64_t* n_src_dev;      // number of vertices whose z changed in this layer (gather, incremental)
+    unsigned long long* pair_ctr;   // null or 1024 counters: z rows fetched by the gather (a statistic)
     float* M; float* DEN;           // [N][heads]
     float* S;                       // [N][D]
     float* Hout;                    // [N][D] layer output

@@ -196,6 +196,7 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
         head[q] = live[q] ? col[q] / hd : 0;
     }
     const bool any_src = !(a.src_bitmap && a.n_src_dev && *a.n_src_dev == 0);   // false: only edge updates in this layer
+    long long rows_read = 0;
     for (int64_t unit = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; unit < n_items + n_dst; unit += waves) {
         float adv[NV], mcur[NV], den[NV];
         float4 acc[NV];
@@ -206,6 +207,7 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
             for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)rec.v * H + head[q]] : 0.f;
             gat_full_pass<NV>(a, rec.v, rec.off + (int64_t)chunk * NRT_CHUNK, min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK),
                               false, lane, col, head, live, adv, mcur, den, acc);
+            rows_read += min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK);
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
                 if (!live[q]) continue;
@@ -294,6 +296,7 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 const int32_t jj = j0 + lane;
                 const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
                 unsigned long long mask = __ballot(u >= 0);
+                rows_read += __popcll(mask);
                 while (mask) {
                     const int bit = __ffsll((long long)mask) - 1;
                     mask &= mask - 1;
@@ -315,6 +318,7 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 bool ok = u >= 0 && ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u);
                 int32_t sl = ok ? a.src_slot[u] : -1;
                 unsigned long long mask = __ballot(ok);
+                rows_read += 2 * __popcll(mask);
                 while (mask) {
                     const int bit = __ffsll((long long)mask) - 1;
                     mask &= mask - 1;
@@ -339,9 +343,13 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 if (live[q] && !(den[q] > den0[q] * (1.0f / 64.0f))) redo = true;
             full = __ballot(redo) != 0ULL;        // cancellation: recompute this destination over all its neighbours
         }
-        if (full) gat_full_pass<NV>(a, v, off, deg, true, lane, col, head, live, adv, mcur, den, acc);
+        if (full) {
+            gat_full_pass<NV>(a, v, off, deg, true, lane, col, head, live, adv, mcur, den, acc);
+            rows_read += deg + 1;
+        }
         gat_store<NV>(a, v, s, col, head, live, mcur, den, acc);
     }
+    if (a.pair_ctr && lane == 0 && rows_read) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)rows_read);
 }
 
 // one wave per hub: merge the partial triples of its items and its self-loop
