@@ -379,3 +379,83 @@ def test_gat_edge_updates_only_with_long_in_lists(S, oracle):
         assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1]), k
         for l in (1, 2):
             assert_parity(wl.GAT, ses.layer(l).cpu().numpy(), ref[l - 1], ("gat-struct", k, l))
+
+
+def _export_edges(ses, n):
+    from paper_2603_20622_amd import binding as nb
+    indptr, indices, ww = nb.nrt_graph_export_csc(ses.graph)
+    indptr, indices = indptr.cpu().numpy(), indices.cpu().numpy()
+    got_dst = np.repeat(np.arange(n), np.diff(indptr))
+    key = indices.astype(np.int64) * n + got_dst
+    order = np.argsort(key)
+    return key[order], None if ww is None else ww.cpu().numpy()[order]
+
+
+def test_heavy_churn_on_one_vertex(S, oracle):
+    """A star: one vertex with 3000 in-edges and 3000 out-edges.  Batches delete a few of its edges (patched list),
+    many of them (squeezed list), and insert more than its slack holds (relocated list); the exported graph and the
+    embeddings follow the oracle after each batch."""
+    n, hub = 4000, 7
+    others = np.array([v for v in range(n) if v != hub], np.int32)
+    rng = np.random.default_rng(5)
+    ins_pool = rng.permutation(others)
+    src = np.concatenate([ins_pool[:3000], np.full(3000, hub, np.int32)]).astype(np.int32)
+    dst = np.concatenate([np.full(3000, hub, np.int32), ins_pool[500:3500]]).astype(np.int32)
+    w = rng.random(len(src)).astype(np.float32)
+    spec = wl.ModelSpec(wl.GIN, [8, 8, 4], weighted=True)
+    params = wl.make_params(spec, 5)
+    x = wl.features(n, 8, 5)
+    ses = S.Session(spec, params, n, src, dst, w, x, e_capacity=12000, max_batch_edges=4096)
+    cur = (src, dst, w, x)
+
+    def batch(del_idx, new_src, new_dst):
+        b = wl.empty_batch(8, weighted=True)
+        b.del_src, b.del_dst = cur[0][del_idx].copy(), cur[1][del_idx].copy()
+        b.ins_src, b.ins_dst = np.asarray(new_src, np.int32), np.asarray(new_dst, np.int32)
+        b.ins_w = rng.random(len(b.ins_src)).astype(np.float32)
+        return b
+
+    in_hub = lambda: np.nonzero(cur[1] == hub)[0]
+    out_hub = lambda: np.nonzero(cur[0] == hub)[0]
+    present_in = lambda: set(cur[0][in_hub()].tolist())
+    steps = [
+        lambda: batch(np.concatenate([in_hub()[:5], out_hub()[-3:]]), [], []),                       # few deletions
+        lambda: batch(in_hub()[::2][:1200], [], []),                                                  # many deletions
+        lambda: (lambda new: batch(in_hub()[:1], new, [hub] * len(new)))(
+            [v for v in others if v not in present_in()][:2000]),                                    # outgrows its slack
+        lambda: (lambda new: batch(np.concatenate([in_hub()[-200:], out_hub()[:200]]), [hub] * len(new), new))(
+            [v for v in others if v not in set(cur[1][out_hub()].tolist())][:300]),
+    ]
+    for k, make in enumerate(steps):
+        b = make()
+        na = ses.apply(b)
+        cur = oracle.apply_batch(n, *cur, b)
+        key, ww = _export_edges(ses, n)
+        want = cur[0].astype(np.int64) * n + cur[1]
+        order = np.argsort(want)
+        assert np.array_equal(key, want[order]), k
+        assert np.array_equal(ww, cur[2][order]), k
+        ref = oracle.forward(spec, params, n, *cur)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1]), k
+        assert_parity(wl.GIN, ses.layer(2).cpu().numpy(), ref[-1], ("churn", k))
+
+
+def test_widest_rows(S, oracle):
+    """1024-wide aggregates (four 16-byte loads per lane in the gather, K = 1024 in the update)."""
+    n, e = 800, 6000
+    src, dst, sampler = wl.rmat_graph(n, e, 91)
+    spec = wl.ModelSpec(wl.GCN, [1024, 1024, 8])
+    params = wl.make_params(spec, 91)
+    x = wl.features(n, 1024, 91)
+    stream = wl.BatchStream(n, src, dst, None, sampler, 1024, 91)
+    ses = S.Session(spec, params, n, src, dst, None, x)
+    cur = (src, dst, None, x)
+    for k in range(2):
+        b = stream.next_batch(15, 15, 3)
+        na = ses.apply(b)
+        cur = oracle.apply_batch(n, *cur, b)
+        ref = oracle.forward(spec, params, n, *cur)
+        assert np.array_equal(ses.ids[:na].cpu().numpy(), oracle.affected_sets(spec, n, cur[0], cur[1], b)[-1])
+        for l in (1, 2):
+            assert rel_err(ses.layer(l).cpu().numpy(), ref[l - 1]) <= TOL
