@@ -182,13 +182,17 @@ nrt_status nrt_get_layer_affected(const nrt_cache*, int32_t layer, const int32_t
 /* How nrt_apply_batch brings the caches up to date (Section II-C, the non-incremental ways of running RTEC
  * that the paper compares against, on the same kernels and the same caches; results are equal up to fp32
  * rounding in every mode, and a cache may switch mode between batches):
- *   NRT_MODE_INCREMENTAL  delta messages over the affected subgraph only (Algorithms 1, 3, 4); the default.
+ *   NRT_MODE_INCREMENTAL  delta messages over the affected subgraph only (Algorithms 1, 3, 4) at every layer.
  *   NRT_MODE_RECOMPUTE    "unaffected embedding reuse": the same affected sets, but every affected vertex
  *                         re-aggregates its whole in-neighbourhood from the current h^{l-1}.
  *   NRT_MODE_FULL         every vertex of every layer is recomputed on the updated graph; the affected list
  *                         is still produced by the frontier expansion.
+ *   NRT_MODE_AUTO         the default: incremental, except that a layer whose changed sources exceed a quarter
+ *                         of the vertices (nearly every in-edge of its affected vertices then carries a delta)
+ *                         is served as in NRT_MODE_RECOMPUTE; decided per layer on the device.  GAT layers are
+ *                         always incremental.
  * Errors: NRT_ERR_INVALID_ARG (null cache, unknown mode). */
-typedef enum { NRT_MODE_INCREMENTAL = 0, NRT_MODE_RECOMPUTE = 1, NRT_MODE_FULL = 2 } nrt_mode;
+typedef enum { NRT_MODE_INCREMENTAL = 0, NRT_MODE_RECOMPUTE = 1, NRT_MODE_FULL = 2, NRT_MODE_AUTO = 3 } nrt_mode;
 nrt_status nrt_set_mode(nrt_cache*, int32_t mode);
 nrt_status nrt_set_profiling(nrt_cache*, int32_t on);
 nrt_status nrt_get_stats(const nrt_cache*, nrt_stats* out /*host*/);

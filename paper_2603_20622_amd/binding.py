@@ -267,7 +267,7 @@ def nrt_get_layer_affected(c: Cache, layer: int) -> torch.Tensor:
     return _view(p.value, (n.value,), torch.int32, c.ws)
 
 
-NRT_MODE_INCREMENTAL, NRT_MODE_RECOMPUTE, NRT_MODE_FULL = 0, 1, 2
+NRT_MODE_INCREMENTAL, NRT_MODE_RECOMPUTE, NRT_MODE_FULL, NRT_MODE_AUTO = 0, 1, 2, 3
 
 
 def nrt_set_mode(c: Cache, mode: int) -> None:

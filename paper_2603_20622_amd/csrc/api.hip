@@ -376,7 +376,7 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
 
 // gather + fold of layer l over the destinations described by c->recs and the hub items built from them;
 // all sizes are read on the device from c->lc[l]
-static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hipStream_t s) {
+static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bool may_recompute, hipStream_t s) {
     nrt_graph* g = c->g;
     GatherArgs a;
     memset(&a, 0, sizeof(a));
@@ -388,6 +388,12 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hi
     a.use_weights = (c->kind == NRT_GIN && g->weighted) ? 1 : 0;
     a.self_pair = c->kind == NRT_GCN;
     a.S = c->S[l];
+    a.n_vertices = g->n;
+    if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
+    GatherArgs full = a;                         // full-neighbour aggregation from h^{l-1} (Eq. 1)
+    full.P = c->H[l - 1];
+    full.src_scale_gcn = c->kind == NRT_GCN;
+    full.accumulate = 0;
     if (incremental) {
         a.P = c->DP[prev];
         a.src_bitmap = c->bm[prev];
@@ -402,19 +408,22 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hi
         a.Pfull = c->H[l - 1];
         a.full_scale_gcn = c->kind == NRT_GCN;
         a.sparse_ok = 1;
-        a.n_vertices = g->n;
         a.coarse = c->coarse;
         a.coarse_shift = c->coarse_shift;
         a.coarse_words = c->coarse_words;
         NRT_TRY(k_coarse_bitmap(c->bm[prev], g->n, c->coarse_shift, c->coarse, c->coarse_words, s));
+        if (may_recompute) {                     // the device counters pick one of the two (GatherArgs::auto_role)
+            a.auto_role = 1;
+            a.auto_src_dev = &c->lc[l - 1].count;
+            full.auto_role = 2;
+            full.auto_src_dev = &c->lc[l - 1].count;
+        }
     } else {
-        a.P = c->H[l - 1];
-        a.src_scale_gcn = c->kind == NRT_GCN;
-        a.accumulate = 0;
+        a = full;
     }
-    if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
     NRT_TRY(k_gather(a, s));
+    if (incremental && may_recompute) NRT_TRY(k_gather(full, s));
     NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
     NRT_TRY(k_combine_partials(a, s));
     NRT_TRY(prof_mark(c, TAG_COMBINE, l, s));
@@ -423,7 +432,8 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, hi
 
 // dense update of layer l on the rows listed in `rows` (null: all n rows); M_dev: their number on the device
 static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M, const uint64_t* M_dev,
-                             bool incremental, int cur, float* out_rows, int64_t out_cap, hipStream_t s) {
+                             bool incremental, int cur, float* out_rows, int64_t out_cap, bool next_may_recompute,
+                             hipStream_t s) {
     nrt_graph* g = c->g;
     const bool last = l == c->L;
     GemmArgs a;
@@ -452,6 +462,8 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.act = last ? 0 : 1;
         a.H = c->H[l];
         a.DP = dp;
+        a.dp_skip_large = next_may_recompute;
+        a.n_vertices = g->n;
         a.dp_scale_gcn = c->kind == NRT_GCN;
         a.out_compact = last ? out_rows : nullptr;
         a.out_cap = out_cap;
@@ -484,6 +496,8 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         b2.act = last ? 0 : 1;
         b2.H = c->H[l];
         b2.DP = dp;
+        b2.dp_skip_large = next_may_recompute;
+        b2.n_vertices = g->n;
         b2.out_compact = last ? out_rows : nullptr;
         b2.out_cap = out_cap;
         NRT_TRY(k_gemm(b2, s));
@@ -580,8 +594,8 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
             st = run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, false, 0, nullptr, 0, s);
             continue;
         }
-        st = run_gather(c, l, false, 0, s);
-        if (st == NRT_OK) st = run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, s);
+        st = run_gather(c, l, false, 0, false, s);
+        if (st == NRT_OK) st = run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, false, s);
     }
     c->lc_use = nullptr;
     return st;
@@ -644,6 +658,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     };
     nrt_status st = run();
     if (st != NRT_OK) { (void)hipHostFree(c->lc_host); delete c; return st; }
+    c->mode = NRT_MODE_AUTO;
     g->has_cache = true;
     *out = c;
     return NRT_OK;
@@ -734,7 +749,12 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
 
     // ---- sets of the batch, per-layer counters
     const bool gcn = c->kind == NRT_GCN;
-    const bool inc = c->mode == NRT_MODE_INCREMENTAL;
+    const bool inc = c->mode == NRT_MODE_INCREMENTAL || c->mode == NRT_MODE_AUTO;
+    // layers that may switch to recomputation on the device: only where the previous batch had a large source set
+    // (no extra launches for small frontiers); the device counters of this batch take the decision
+    bool may_rec[NRT_MAX_LAYERS + 2];
+    for (int l = 0; l <= c->L + 1; ++l)
+        may_rec[l] = c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
     if (gcn && inc) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     if (inc && b->n_ins + b->n_del > 0) {
@@ -831,9 +851,9 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
                                   inc, prev, l == c->L ? affected_rows : nullptr, capacity, s));
         } else {
-            NRT_TRY(run_gather(c, l, inc, prev, s));
+            NRT_TRY(run_gather(c, l, inc, prev, may_rec[l], s));
             NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, inc, cur, l == c->L ? affected_rows : nullptr,
-                               capacity, s));
+                               capacity, may_rec[l + 1], s));
         }
         NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
         prev = cur;
@@ -914,7 +934,8 @@ extern "C" nrt_status nrt_get_layer_affected(const nrt_cache* c, int32_t layer, 
 }
 extern "C" nrt_status nrt_set_mode(nrt_cache* c, int32_t mode) {
     REQUIRE(c, "null argument");
-    REQUIRE(mode == NRT_MODE_INCREMENTAL || mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL, "unknown mode");
+    REQUIRE(mode == NRT_MODE_INCREMENTAL || mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL || mode == NRT_MODE_AUTO,
+            "unknown mode");
     c->mode = mode;
     return NRT_OK;
 }

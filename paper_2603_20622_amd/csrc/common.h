@@ -176,6 +176,13 @@ struct GatherArgs {
     // layers whose changed sources are few may be served by the short-instruction variant of the gather
     int sparse_ok;
     int64_t n_vertices;
+    // Automatic choice per layer between folding deltas and recomputing the affected aggregates from h^{l-1}: when
+    // the changed sources are a large part of the graph nearly every in-edge carries a delta, so recomputation reads
+    // the same rows without slot lookups, without reading the old aggregate, and spares the previous layer's
+    // write-back its payload deltas.  auto_role 1: this launch folds deltas and yields when 4 * changed > n_vertices;
+    // auto_role 2: this launch recomputes and runs only then; 0: no test.  auto_src_dev: the changed-source count.
+    int auto_role;
+    const uint64_t* auto_src_dev;
     const uint32_t* coarse;    // coarse copy of src_bitmap: bit i covers vertices [i << coarse_shift, (i+1) << coarse_shift)
     int coarse_shift;
     int coarse_words;          // at most NRT_COARSE_WORDS
@@ -231,6 +238,8 @@ struct GemmArgs {
     const int32_t* indeg_old;       // GCN payload scale for DP (with indeg as new), else null
     int dp_scale_gcn;
     int dp_store_old;               // DP receives the overwritten row of H instead of a payload delta (GAT: old z)
+    int dp_skip_large;              // leave DP (and the read of the old rows) out when 4 * rows > n_vertices
+    int64_t n_vertices;
 };
 nrt_status k_gemm(const GemmArgs& a, hipStream_t s);
 nrt_status k_transpose(const float* W, float* Wt, int K, int N, hipStream_t s);   // Wt[n][k] = W[k][n]

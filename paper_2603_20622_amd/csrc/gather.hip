@@ -234,6 +234,13 @@ __device__ inline bool layer_is_sparse(const GatherArgs& a) {
     return a.sparse_ok && a.n_src_dev && (int64_t)(*a.n_src_dev) * 16 <= a.n_vertices;
 }
 
+// true when this launch is not the one that serves the layer (see GatherArgs::auto_role)
+__device__ inline bool layer_goes_to_other_role(const GatherArgs& a) {
+    if (!a.auto_role) return false;
+    const bool recompute = 4 * (int64_t)(*a.auto_src_dev) > a.n_vertices;
+    return a.auto_role == 1 ? recompute : !recompute;
+}
+
 // Step flags kept in the per-wave step table.
 enum { SF_FIRST = 1, SF_LAST = 2, SF_PART = 4, SF_SELF = 8 };
 
@@ -245,6 +252,7 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
     const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int sub = lane / LPR, gl = lane % LPR;
     const int D = a.D;
+    if (layer_goes_to_other_role(a)) return;
     if (a.n_src_dev && *a.n_src_dev == 0 && !a.sd) return;   // nothing changed upstream of this layer
     if (FILTER && NV == 1 && layer_is_sparse(a)) return;     // served by gather_sparse_kernel
     const int64_t n_dst = (int64_t)a.lc->count;
@@ -538,7 +546,7 @@ __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs
     __shared__ __attribute__((aligned(16))) int32_t s_slot[SP_WAVES][4][SQ_CAP];
     __shared__ __attribute__((aligned(16))) float s_coef[SP_WAVES][4][COEF ? SQ_CAP : 4];
     __shared__ uint32_t s_coarse[NRT_COARSE_WORDS];
-    if (!layer_is_sparse(a)) return;
+    if (layer_goes_to_other_role(a) || !layer_is_sparse(a)) return;
     if (*a.n_src_dev == 0 && !a.sd) return;
     for (int i = threadIdx.x; i < a.coarse_words; i += SP_WAVES * 64) s_coarse[i] = a.coarse[i];
     __syncthreads();
@@ -740,6 +748,10 @@ __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs
 // one wave per hub (strided): sum its partial rows in item order into the cached aggregate
 __global__ void combine_kernel(GatherArgs a) {
     if (a.n_src_dev && *a.n_src_dev == 0 && !a.sd) return;
+    if (a.auto_role == 1 && layer_goes_to_other_role(a)) {   // the layer was recomputed: partial rows are whole sums
+        a.accumulate = 0;
+        a.guard = 0;
+    }
     const int lane = threadIdx.x & 63;
     int64_t nh = (int64_t)a.lc->n_hubs;
     if (nh > a.hubs.hub_cap) nh = a.hubs.hub_cap;

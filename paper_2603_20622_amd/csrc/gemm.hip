@@ -66,6 +66,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
     const int wm = wave / WN, wn = wave % WN;
     const int col_base = blockIdx.y * BN;
     const int64_t M = g.M_dev ? (int64_t)*g.M_dev : g.M;      // rows known only on the device: stride over the tiles
+    // the next layer recomputes its aggregates from h when these rows are a large part of the graph: no payload deltas then
+    float* const DPout = (g.dp_skip_large && 4 * M > g.n_vertices) ? nullptr : g.DP;
   for (int64_t row_base = (int64_t)blockIdx.x * BM; row_base < M; row_base += (int64_t)gridDim.x * BM) {
 
     // rows this thread stages
@@ -174,12 +176,12 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
                 const bool ok = mrow[rr] < M;
                 vrow[rr] = ok ? (g.rows ? (int64_t)g.rows[mrow[rr]] : mrow[rr]) : 0;
                 cn[rr] = 1.0f; co[rr] = 1.0f;
-                if (ok && g.DP && g.dp_scale_gcn) { cn[rr] = gcn_scale(g.indeg[vrow[rr]]); co[rr] = gcn_scale(g.indeg_old[vrow[rr]]); }
+                if (ok && DPout && g.dp_scale_gcn) { cn[rr] = gcn_scale(g.indeg[vrow[rr]]); co[rr] = gcn_scale(g.indeg_old[vrow[rr]]); }
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int n = col_base + (wn * TN + j) * 32 + l32;
                     const int nc = n < g.N ? n : g.N - 1;
-                    oldv[rr][j] = g.DP ? g.H[vrow[rr] * g.N + nc] : 0.f;   // vrow is 0 for rows past M: always in range
+                    oldv[rr][j] = DPout ? g.H[vrow[rr] * g.N + nc] : 0.f;   // vrow is 0 for rows past M: always in range
                 }
             }
 #pragma unroll
@@ -194,7 +196,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
                     else if (g.act == 2) y = y > 0.f ? y : expm1f(y);
                     if (g.out_compact && mrow[rr] < g.out_cap) g.out_compact[mrow[rr] * g.N + n] = y;
                     if (g.H) {
-                        if (g.DP) g.DP[mrow[rr] * g.N + n] = g.dp_store_old ? oldv[rr][j] : y * cn[rr] - oldv[rr][j] * co[rr];
+                        if (DPout) DPout[mrow[rr] * g.N + n] = g.dp_store_old ? oldv[rr][j] : y * cn[rr] - oldv[rr][j] * co[rr];
                         g.H[vrow[rr] * g.N + n] = y;
                     }
                 }

@@ -55,9 +55,9 @@ def test_mode_and_profiling_reject_null_handles():
     L = nb.lib()
     assert L.nrt_set_mode(None, nb.NRT_MODE_RECOMPUTE) == nb.NRT_ERR_INVALID_ARG
     assert L.nrt_set_profiling(None, 1) == nb.NRT_ERR_INVALID_ARG
-    assert (nb.NRT_MODE_INCREMENTAL, nb.NRT_MODE_RECOMPUTE, nb.NRT_MODE_FULL) == (0, 1, 2)
+    assert (nb.NRT_MODE_INCREMENTAL, nb.NRT_MODE_RECOMPUTE, nb.NRT_MODE_FULL, nb.NRT_MODE_AUTO) == (0, 1, 2, 3)
     text = open(os.path.join(ROOT, "include", "nrt.h")).read()
-    assert re.search(r"NRT_MODE_INCREMENTAL\s*=\s*0,\s*NRT_MODE_RECOMPUTE\s*=\s*1,\s*NRT_MODE_FULL\s*=\s*2", text)
+    assert re.search(r"NRT_MODE_INCREMENTAL\s*=\s*0,\s*NRT_MODE_RECOMPUTE\s*=\s*1,\s*NRT_MODE_FULL\s*=\s*2,\s*NRT_MODE_AUTO\s*=\s*3", text)
 
 
 def test_bench_refuses_more_than_one_gpu():

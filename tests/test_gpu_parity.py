@@ -336,7 +336,7 @@ def test_capacity_too_small_still_updates_caches(S, oracle):
 
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("mode", [0, 1, 2, 3])
 def test_recompute_modes_match_oracle(S, oracle, kind, mode):
     """Section II-C baselines on the same caches: affected-vertex recomputation (1) and whole-graph recomputation
     (2) return the same affected lists and embeddings; switching back to incremental afterwards keeps working."""
@@ -344,7 +344,7 @@ def test_recompute_modes_match_oracle(S, oracle, kind, mode):
     ses = S.Session(spec, params, n, src, dst, w, x)
     cur = (src, dst, w, x)
     L = spec.n_layers
-    for k, m in enumerate([mode, mode, 0, mode, 0]):
+    for k, m in enumerate([mode, mode, 0, mode, 3, 3, 0, mode]):
         ses.mode(m)
         b = stream.next_batch(30, 30, 8)
         na = ses.apply(b)
