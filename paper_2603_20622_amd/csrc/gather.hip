@@ -242,7 +242,7 @@ __device__ inline bool layer_goes_to_other_role(const GatherArgs& a) {
 }
 
 // Step flags kept in the per-wave step table.
-enum { SF_FIRST = 1, SF_LAST = 2, SF_PART = 4, SF_SELF = 8 };
+enum { SF_FIRST = 1, SF_LAST = 2, SF_PART = 4, SF_SELF = 8, SF_DD = 16 };
 
 template <int LPR, int NV, bool FILTER, bool COEF>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs a) {
@@ -591,6 +591,9 @@ __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs
             u_base = rec.off + (int64_t)chunk * NRT_CHUNK;
             u_v = rec.v;
             u_deg = rec.deg;
+            // destination of an updated edge: its structural terms join the fold (tested here, with the record, so
+            // that the fold itself waits for no load in the common case)
+            if (a.sd && (u_flags & SF_SELF) && ((a.dd_bitmap[rec.v >> 5] >> (rec.v & 31)) & 1u)) u_flags |= SF_DD;
         }
         // ---- row role: accumulators, and the old rows while the scan runs
         float4 acc[NPASS], old[NPASS];
@@ -703,11 +706,9 @@ __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs
                                           (uint32_t)__shfl((int32_t)(u_out & 0xffffffff), from, 64));
             float4 y = acc[ps];
             bool touched = nh > 0;
-            if (a.sd && (fl & SF_SELF)) {
-                if ((a.dd_bitmap[vr >> 5] >> (vr & 31)) & 1u) {
-                    touched = true;
-                    if (live) y = f4_add(y, *reinterpret_cast<const float4*>(a.sd + (int64_t)a.dd_slot[vr] * D + gl * 4));
-                }
+            if (fl & SF_DD) {
+                touched = true;
+                if (live) y = f4_add(y, *reinterpret_cast<const float4*>(a.sd + (int64_t)a.dd_slot[vr] * D + gl * 4));
             }
             const bool part = fl & SF_PART;
             if (part && live) *reinterpret_cast<float4*>(a.hubs.partial + out + gl * 4) = y;
