@@ -81,6 +81,8 @@ struct nrt_cache {
     int ev_tag[MAX_EVENTS];
     int n_ev;
     bool events_made;
+    hipEvent_t ev_validated;            // recorded after the read-back of the validation result
+    bool ev_validated_made;
     nrt_stats stats;
 };
 
@@ -659,6 +661,13 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     nrt_status st = run();
     if (st != NRT_OK) { (void)hipHostFree(c->lc_host); delete c; return st; }
     c->mode = NRT_MODE_AUTO;
+    if (hipEventCreateWithFlags(&c->ev_validated, hipEventDisableTiming) != hipSuccess) {
+        (void)hipHostFree(c->lc_host);
+        delete c;
+        nrt_set_error("hipEventCreate failed");
+        return NRT_ERR_DEVICE;
+    }
+    c->ev_validated_made = true;
     g->has_cache = true;
     *out = c;
     return NRT_OK;
@@ -668,6 +677,7 @@ extern "C" void nrt_cache_destroy(nrt_cache* c) {
     if (!c) return;
     if (c->events_made)
         for (int i = 0; i < MAX_EVENTS; ++i) (void)hipEventDestroy(c->ev[i]);
+    if (c->ev_validated_made) (void)hipEventDestroy(c->ev_validated);
     if (c->lc_host) (void)hipHostFree(c->lc_host);
     if (c->g) c->g->has_cache = false;
     delete c;
@@ -702,7 +712,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     for (int l = 0; l <= c->L; ++l) { prev_n_list[l] = c->n_list[l]; c->n_list[l] = 0; }
     NRT_TRY(prof_mark(c, TAG_START, 0, s));
 
-    // ---- validate (no state change yet); the one synchronisation before the end of the batch
+    // ---- validate (no state change yet)
     {
         // per-batch scratch of the cache is cleared in the validation's fill launch: set bitmaps, layer counters,
         // the rows that collect structural terms (none of it is state, so a rejected batch loses nothing)
@@ -718,7 +728,63 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         if (c->kind == NRT_GAT) f.add(c->ins_cnt, b->n_ins + b->n_del);
         NRT_TRY(graph_validate_batch(g, b, c->sc, &f, s));
     }
-    NRT_TRY(read_ctrs(g, s));
+    // The verdict travels to the host while the device goes on with work that touches only per-batch scratch and
+    // tolerates a bad batch (ids are range-checked there, caches are only read): the host waits for the event, not
+    // for the stream, so the queue never runs dry between validation and mutation.
+    HIP_TRY(hipMemcpyAsync(g->host_pinned, g->dev_ctrs, NRT_NCTRS * sizeof(int64_t), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipEventRecord(c->ev_validated, s));
+    const bool empty_batch = b->n_ins + b->n_del + b->n_feat == 0;
+    // ---- sets of the batch, structural terms on the old caches (scratch only)
+    const bool gcn = c->kind == NRT_GCN;
+    const bool inc = c->mode == NRT_MODE_INCREMENTAL || c->mode == NRT_MODE_AUTO;
+    // layers that may switch to recomputation on the device: only where the previous batch had a large source set
+    // (no extra launches for small frontiers); the device counters of this batch take the decision
+    bool may_rec[NRT_MAX_LAYERS + 2];
+    for (int l = 0; l <= c->L + 1; ++l)
+        may_rec[l] = c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
+    if (!empty_batch) NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, n, s));
+    if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
+    if (inc && b->n_ins + b->n_del > 0) {
+        // destinations of updated edges -> compact rows that collect their structural terms (bm[1] is scratch here)
+        NRT_TRY(k_compact(nullptr, c->bm_ddst, nullptr, c->bm[1], n, c->list_dd, c->slot_dd, g->scan_tmp, g->scan_tmp_len,
+                          (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
+    }
+
+    // ---- structural terms on the old caches, all layers in one launch
+    if (inc && c->kind == NRT_GAT) {
+        GatFoldArgs f;
+        memset(&f, 0, sizeof(f));
+        f.n_ins = b->n_ins; f.n_del = b->n_del;
+        f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
+        f.dd_slot = c->slot_dd;
+        f.ins_cnt = c->ins_cnt;
+        f.n = n;
+        f.n_layers = c->L; f.heads = c->heads; f.head_dim = c->head_dim; f.slope = c->leaky_slope;
+        for (int l = 1; l <= c->L; ++l) {
+            f.Z[l - 1] = c->Z[l]; f.AS[l - 1] = c->AS[l]; f.AD[l - 1] = c->AD[l]; f.M[l - 1] = c->M[l];
+            f.SDS[l - 1] = c->SD[l]; f.SDDEN[l - 1] = c->SDden[l];
+        }
+        NRT_TRY(k_gat_structural_fold(f, s));
+    }
+    if (inc && c->kind != NRT_GAT) {
+        FoldArgs f;
+        memset(&f, 0, sizeof(f));
+        f.n_ins = b->n_ins; f.n_del = b->n_del;
+        f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
+        if (c->kind == NRT_GIN && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
+        f.indeg_old = gcn ? g->in.deg : nullptr;
+        f.n_layers = c->L;
+        f.n = n;
+        f.dd_slot = c->slot_dd;
+        for (int l = 1; l <= c->L; ++l) {
+            f.Hprev[l - 1] = c->H[l - 1];
+            f.SD[l - 1] = c->SD[l];
+            f.D[l - 1] = c->dagg[l];
+        }
+        NRT_TRY(k_structural_fold(f, s));
+    }
+
+    HIP_TRY(hipEventSynchronize(c->ev_validated));
     {
         const int32_t* err = (const int32_t*)(g->host_pinned + CTR_ERR);
         const char* msg = nullptr;
@@ -745,54 +811,6 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(graph_mutate(g, b, c->sc, s));
         *n_affected = 0;
         return NRT_OK;
-    }
-
-    // ---- sets of the batch, per-layer counters
-    const bool gcn = c->kind == NRT_GCN;
-    const bool inc = c->mode == NRT_MODE_INCREMENTAL || c->mode == NRT_MODE_AUTO;
-    // layers that may switch to recomputation on the device: only where the previous batch had a large source set
-    // (no extra launches for small frontiers); the device counters of this batch take the decision
-    bool may_rec[NRT_MAX_LAYERS + 2];
-    for (int l = 0; l <= c->L + 1; ++l)
-        may_rec[l] = c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
-    NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, s));
-    if (gcn && inc) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
-    if (inc && b->n_ins + b->n_del > 0) {
-        // destinations of updated edges -> compact rows that collect their structural terms (bm[1] is scratch here)
-        NRT_TRY(k_compact(nullptr, c->bm_ddst, nullptr, c->bm[1], n, c->list_dd, c->slot_dd, g->scan_tmp, g->scan_tmp_len,
-                          (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
-    }
-
-    // ---- structural terms on the old caches, all layers in one launch
-    if (inc && c->kind == NRT_GAT) {
-        GatFoldArgs f;
-        memset(&f, 0, sizeof(f));
-        f.n_ins = b->n_ins; f.n_del = b->n_del;
-        f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
-        f.dd_slot = c->slot_dd;
-        f.ins_cnt = c->ins_cnt;
-        f.n_layers = c->L; f.heads = c->heads; f.head_dim = c->head_dim; f.slope = c->leaky_slope;
-        for (int l = 1; l <= c->L; ++l) {
-            f.Z[l - 1] = c->Z[l]; f.AS[l - 1] = c->AS[l]; f.AD[l - 1] = c->AD[l]; f.M[l - 1] = c->M[l];
-            f.SDS[l - 1] = c->SD[l]; f.SDDEN[l - 1] = c->SDden[l];
-        }
-        NRT_TRY(k_gat_structural_fold(f, s));
-    }
-    if (inc && c->kind != NRT_GAT) {
-        FoldArgs f;
-        memset(&f, 0, sizeof(f));
-        f.n_ins = b->n_ins; f.n_del = b->n_del;
-        f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
-        if (c->kind == NRT_GIN && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
-        f.indeg_old = gcn ? g->in.deg : nullptr;
-        f.n_layers = c->L;
-        f.dd_slot = c->slot_dd;
-        for (int l = 1; l <= c->L; ++l) {
-            f.Hprev[l - 1] = c->H[l - 1];
-            f.SD[l - 1] = c->SD[l];
-            f.D[l - 1] = c->dagg[l];
-        }
-        NRT_TRY(k_structural_fold(f, s));
     }
 
     // ---- graph mutation

@@ -107,9 +107,9 @@ nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
 nrt_status k_copy_counted_i32(int32_t* dst, const int32_t* src, const uint64_t* count, int64_t cap, int64_t bound, hipStream_t s);
 // exclusive scan of n uint64 values in place; writes the total to *total (device)
 nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_t tmp_len, uint64_t* total, hipStream_t s);
-// bm_a |= ids of a0 and a1, bm_b |= ids of b0, one launch
+// bm_a |= ids of a0 and a1, bm_b |= ids of b0, one launch; ids outside [0, n) are skipped
 nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
-                        const int32_t* b0, int64_t nb0, hipStream_t s);
+                        const int32_t* b0, int64_t nb0, int64_t n, hipStream_t s);
 // Compaction of a vertex set into a sorted id list.  The set is the union of the byte flags (one byte per vertex,
 // may be null; they are cleared on the way), and up to two bitmaps or_a, or_b (may be null).  Writes the set as
 // bitmap `out_bm`, its sorted ids to `list`, slot[id] = position, *count = size.
@@ -195,8 +195,8 @@ nrt_status k_gather(const GatherArgs& a, hipStream_t s);
 nrt_status k_coarse_bitmap(const uint32_t* fine, int64_t n, int shift, uint32_t* coarse, int64_t n_words, hipStream_t s);
 nrt_status k_combine_partials(const GatherArgs& a, hipStream_t s);
 
-struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update caches
-    int64_t n_ins, n_del;
+struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update caches; edges with an id outside [0, n) are skipped
+    int64_t n_ins, n_del, n;
     const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
     const float *ins_w, *del_w;  // null when unweighted
     int n_layers;                // blockIdx.y walks the layers
@@ -283,7 +283,7 @@ struct GatArgs {
 };
 nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s);
 struct GatFoldArgs {   // structural terms of a batch for GAT, evaluated on the pre-update caches, all layers in one launch
-    int64_t n_ins, n_del;
+    int64_t n_ins, n_del, n;    // edges with an id outside [0, n) are skipped
     const int32_t *ins_dst, *del_src, *del_dst;
     const int32_t* dd_slot;
     int32_t* ins_cnt;

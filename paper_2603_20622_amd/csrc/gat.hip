@@ -61,11 +61,13 @@ __global__ void gat_structural_fold_kernel(GatFoldArgs a) {
     const int l = blockIdx.y;
     if (op >= a.n_ins + a.n_del) return;
     if (op < a.n_ins) {
-        if (l == 0 && lane == 0) atomicAdd(&a.ins_cnt[a.dd_slot[a.ins_dst[op]]], 1);
+        const int32_t vd = a.ins_dst[op];
+        if (l == 0 && lane == 0 && vd >= 0 && vd < a.n) atomicAdd(&a.ins_cnt[a.dd_slot[vd]], 1);
         return;
     }
     const int64_t i = op - a.n_ins;
     const int32_t u = a.del_src[i], v = a.del_dst[i];
+    if (u < 0 || u >= a.n || v < 0 || v >= a.n) return;     // the batch's verdict is not known yet: it will be rejected
     const int64_t row = a.dd_slot[v];
     const int H = a.heads, hd = a.head_dim, D = H * hd;
     for (int col = lane * 4; col < D; col += 256) {

@@ -825,6 +825,7 @@ __global__ void structural_fold_kernel(FoldArgs a) {
     const int64_t i = is_del ? op - a.n_ins : op;
     const int32_t u = is_del ? a.del_src[i] : a.ins_src[i];
     const int32_t v = is_del ? a.del_dst[i] : a.ins_dst[i];
+    if (u < 0 || u >= a.n || v < 0 || v >= a.n) return;     // the batch's verdict is not known yet: it will be rejected
     float c = is_del ? -1.0f : 1.0f;
     if (is_del && a.del_w) c *= a.del_w[i];
     if (!is_del && a.ins_w) c *= a.ins_w[i];

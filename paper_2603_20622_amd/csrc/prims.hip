@@ -76,7 +76,7 @@ __global__ void copy_u32_kernel(uint32_t* dst, const uint32_t* src, int64_t n) {
 }
 
 __global__ void mark_batch_kernel(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1,
-                                  uint32_t* bm_b, const int32_t* b0, int64_t nb0) {
+                                  uint32_t* bm_b, const int32_t* b0, int64_t nb0, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint32_t* bm = bm_a;
     int32_t v;
@@ -84,6 +84,7 @@ __global__ void mark_batch_kernel(uint32_t* bm_a, const int32_t* a0, int64_t na0
     else if ((i -= na0) < na1) v = a1[i];
     else if ((i -= na1) < nb0) { v = b0[i]; bm = bm_b; }
     else return;
+    if (v < 0 || v >= n) return;          // runs before the batch's verdict is known: a bad id must not be dereferenced
     atomicOr(&bm[v >> 5], 1u << (v & 31));
 }
 
@@ -264,10 +265,10 @@ nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s) {
 }
 
 nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
-                        const int32_t* b0, int64_t nb0, hipStream_t s) {
+                        const int32_t* b0, int64_t nb0, int64_t nv, hipStream_t s) {
     const int64_t n = na0 + na1 + nb0;
     if (n <= 0) return NRT_OK;
-    mark_batch_kernel<<<(int)cdiv(n, 256), 256, 0, s>>>(bm_a, a0, na0, a1, na1, bm_b, b0, nb0);
+    mark_batch_kernel<<<(int)cdiv(n, 256), 256, 0, s>>>(bm_a, a0, na0, a1, na1, bm_b, b0, nb0, nv);
     LAUNCH_CHECK();
     return NRT_OK;
 }
