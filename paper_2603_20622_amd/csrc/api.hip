@@ -48,6 +48,7 @@ struct nrt_cache {
     LayerCtrs* lc;                      // device, [NRT_MAX_LAYERS + 2]; the last one serves whole-graph passes of a batch
     LayerCtrs* lc_use;                  // counters the layer steps read instead of lc[l] (null: lc[l])
     int mode;                           // nrt_mode
+    bool have_history;                  // n_list holds the set sizes of a previous batch (hints for kernel choice)
     LayerCtrs* lc_host;                 // pinned mirror, followed by the mirror of pair_ctr (profiling)
     unsigned long long* pair_host;
     int32_t* xhub_list;
@@ -378,7 +379,8 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
 
 // gather + fold of layer l over the destinations described by c->recs and the hub items built from them;
 // all sizes are read on the device from c->lc[l]
-static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bool may_recompute, hipStream_t s) {
+static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bool may_recompute, int sparse_hint,
+                             hipStream_t s) {
     nrt_graph* g = c->g;
     GatherArgs a;
     memset(&a, 0, sizeof(a));
@@ -409,7 +411,7 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
         a.guard = c->kind == NRT_GIN;            // un-normalised sums: a fold can cancel most of a row's magnitude
         a.Pfull = c->H[l - 1];
         a.full_scale_gcn = c->kind == NRT_GCN;
-        a.sparse_ok = 1;
+        a.sparse_ok = (sparse_hint == 2 && a.D > 256) ? 1 : sparse_hint;    // rows wider than 256 floats: pipelined kernel only
         a.coarse = c->coarse;
         a.coarse_shift = c->coarse_shift;
         a.coarse_words = c->coarse_words;
@@ -596,7 +598,7 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
             st = run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, false, 0, nullptr, 0, s);
             continue;
         }
-        st = run_gather(c, l, false, 0, false, s);
+        st = run_gather(c, l, false, 0, false, 0, s);
         if (st == NRT_OK) st = run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, false, s);
     }
     c->lc_use = nullptr;
@@ -710,6 +712,8 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     c->n_ev = 0;
     int64_t prev_n_list[NRT_MAX_LAYERS + 1];            // sizes of the previous batch's sets: hints for this one
     for (int l = 0; l <= c->L; ++l) { prev_n_list[l] = c->n_list[l]; c->n_list[l] = 0; }
+    const bool had_history = c->have_history;
+    c->have_history = false;
     NRT_TRY(prof_mark(c, TAG_START, 0, s));
 
     // ---- validate (no state change yet)
@@ -869,7 +873,11 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
                                   inc, prev, l == c->L ? affected_rows : nullptr, capacity, s));
         } else {
-            NRT_TRY(run_gather(c, l, inc, prev, may_rec[l], s));
+            // which gather kernel: the previous batch's source count at this layer is the hint; a clearly sparse or
+            // clearly dense layer launches one kernel, in between both are launched and the device counter decides
+            const int64_t pn = prev_n_list[l - 1];
+            const int sparse_hint = !had_history ? 1 : (pn * 64 <= n ? 2 : (pn * 4 > n ? 0 : 1));
+            NRT_TRY(run_gather(c, l, inc, prev, may_rec[l], sparse_hint, s));
             NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, inc, cur, l == c->L ? affected_rows : nullptr,
                                capacity, may_rec[l + 1], s));
         }
@@ -889,6 +897,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
                                hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     for (int l = 0; l <= c->L; ++l) c->n_list[l] = (int64_t)c->lc_host[l].count;
+    c->have_history = true;
     for (int l = 1; l <= c->L; ++l) {
         nrt_layer_stats* ls = &c->stats.layer[l - 1];
         ls->n_src = c->n_list[l - 1];

@@ -173,7 +173,8 @@ struct GatherArgs {
     int guard;
     const float* Pfull;
     int full_scale_gcn;
-    // layers whose changed sources are few may be served by the short-instruction variant of the gather
+    // layers whose changed sources are few are served by the short-instruction variant of the gather:
+    // 0 never, 1 the device counters decide (both kernels are launched), 2 always (only that kernel is launched)
     int sparse_ok;
     int64_t n_vertices;
     // Automatic choice per layer between folding deltas and recomputing the affected aggregates from h^{l-1}: when

@@ -231,6 +231,7 @@ constexpr float GUARD_RATIO = 16.0f;     // rebuild a row when the fold is 16x l
 // The host cannot know how many sources changed without a synchronisation, so both gather kernels are launched
 // and each asks the device counters whether the layer is its to serve.
 __device__ inline bool layer_is_sparse(const GatherArgs& a) {
+    if (a.sparse_ok == 2) return true;          // the host launched only the sparse kernel (it is correct at any density)
     return a.sparse_ok && a.n_src_dev && (int64_t)(*a.n_src_dev) * 16 <= a.n_vertices;
 }
 
@@ -877,6 +878,11 @@ static void launch_gather(const GatherArgs& a, hipStream_t s) {
     const int threads = WAVES_PER_BLOCK * 64;
     const bool filter = a.src_bitmap != nullptr;
     const bool coef = a.use_weights || a.src_scale_gcn;
+    if (NV == 1 && a.sparse_ok == 2) {
+        if (coef) gather_sparse_kernel<LPR, true><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
+        else gather_sparse_kernel<LPR, false><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
+        return;
+    }
     if (filter && coef) gather_kernel<LPR, NV, true, true><<<nb, threads, 0, s>>>(a);
     else if (filter) gather_kernel<LPR, NV, true, false><<<nb, threads, 0, s>>>(a);
     else if (coef) gather_kernel<LPR, NV, false, true><<<nb, threads, 0, s>>>(a);
