@@ -10,7 +10,9 @@
 // change of the source payload dp = y_new*cn - y_old*co (cn = co = 1 except for GCN, where the payload is
 // y / sqrt(d_v) and the degree may have changed), so no separate pass re-reads the rows.
 //
-// Tiling: 4 waves (8 for the 256-wide tile); block tile 128 x BN; K is consumed in slices of 32 staged through LDS
+// Tiling: block tile 128 x BN with 4 waves, 64 x 256 with 8 waves for wide outputs (its 126 registers let two
+// workgroups share a compute unit, so one's row-index prologue and write-back epilogue overlap the other's MFMAs);
+// K is consumed in slices of 32 staged through LDS
 // (rows padded to 36 floats so that the 16-byte operand reads of 8 neighbouring lanes cover all banks).
 // Each wave owns (TM x TN) 32x32 accumulator tiles fed by v_mfma_f32_32x32x2_f32: lane = (i mod 32, half),
 // the two halves supply two different k, so one 16-byte LDS read per operand feeds four MFMAs.
@@ -21,7 +23,6 @@ namespace {
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128;
 
 __device__ inline float gcn_scale(int32_t indeg) { return 1.0f / sqrtf((float)(indeg + 1)); }
 
@@ -50,7 +51,7 @@ __device__ inline void load_a(const GemmArgs& g, int64_t v, float sc, int k, boo
     mul = live ? m : 0.0f;
 }
 
-template <int BN, int WM, int WN, int AMODE, int KT>
+template <int BM, int BN, int WM, int WN, int AMODE, int KT>
 __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
     constexpr int NT = WM * WN * 64;       // threads of the workgroup
     constexpr int LDS_STRIDE = KT + 4;
@@ -218,13 +219,14 @@ __global__ void transpose_kernel(const float* W, float* Wt, int K, int N) {
 
 template <int AMODE>
 static void launch_gemm(const GemmArgs& g, hipStream_t s) {
+    const int BM = g.N > 128 ? 64 : 128;
     int64_t tiles = cdiv(g.M, BM);
-    if (g.M_dev && tiles > 2048) tiles = 2048;               // device-sized problem: a fixed grid strides over the tiles
+    if (g.M_dev && tiles > 4096) tiles = 4096;               // device-sized problem: a fixed grid strides over the tiles
     const unsigned gx = (unsigned)tiles;
-    if (g.N > 128) gemm_kernel<256, 4, 2, AMODE, 32><<<dim3(gx, (unsigned)cdiv(g.N, 256)), 512, 0, s>>>(g);
-    else if (g.N > 64) gemm_kernel<128, 2, 2, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
-    else if (g.N > 32) gemm_kernel<64, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
-    else gemm_kernel<32, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
+    if (g.N > 128) gemm_kernel<64, 256, 2, 4, AMODE, 32><<<dim3(gx, (unsigned)cdiv(g.N, 256)), 512, 0, s>>>(g);
+    else if (g.N > 64) gemm_kernel<128, 128, 2, 2, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
+    else if (g.N > 32) gemm_kernel<128, 64, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
+    else gemm_kernel<128, 32, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
 }
 
 nrt_status k_gemm(const GemmArgs& g, hipStream_t s) {
