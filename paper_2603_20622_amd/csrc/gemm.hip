@@ -10,8 +10,9 @@
 // change of the source payload dp = y_new*cn - y_old*co (cn = co = 1 except for GCN, where the payload is
 // y / sqrt(d_v) and the degree may have changed), so no separate pass re-reads the rows.
 //
-// Tiling: block tile 128 x BN with 4 waves, 64 x 256 with 8 waves for wide outputs (its 126 registers let two
-// workgroups share a compute unit, so one's row-index prologue and write-back epilogue overlap the other's MFMAs);
+// Tiling: block tile 64 x {64, 128} with 4 waves, 64 x 256 with 8 waves (128 x 32 for the narrowest outputs).  Short
+// tiles keep the register count low enough for several workgroups per compute unit, so one's row-index prologue
+// and write-back epilogue overlap the others' MFMAs, and give small affected sets more tiles than compute units;
 // K is consumed in slices of 32 staged through LDS
 // (rows padded to 36 floats so that the 16-byte operand reads of 8 neighbouring lanes cover all banks).
 // Each wave owns (TM x TN) 32x32 accumulator tiles fed by v_mfma_f32_32x32x2_f32: lane = (i mod 32, half),
@@ -219,13 +220,13 @@ __global__ void transpose_kernel(const float* W, float* Wt, int K, int N) {
 
 template <int AMODE>
 static void launch_gemm(const GemmArgs& g, hipStream_t s) {
-    const int BM = g.N > 128 ? 64 : 128;
+    const int BM = g.N > 32 ? 64 : 128;
     int64_t tiles = cdiv(g.M, BM);
     if (g.M_dev && tiles > 4096) tiles = 4096;               // device-sized problem: a fixed grid strides over the tiles
     const unsigned gx = (unsigned)tiles;
     if (g.N > 128) gemm_kernel<64, 256, 2, 4, AMODE, 32><<<dim3(gx, (unsigned)cdiv(g.N, 256)), 512, 0, s>>>(g);
-    else if (g.N > 64) gemm_kernel<128, 128, 2, 2, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
-    else if (g.N > 32) gemm_kernel<128, 64, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
+    else if (g.N > 64) gemm_kernel<64, 128, 2, 2, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
+    else if (g.N > 32) gemm_kernel<64, 64, 2, 2, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
     else gemm_kernel<128, 32, 4, 1, AMODE, 32><<<dim3(gx, 1), 256, 0, s>>>(g);
 }
 
