@@ -194,6 +194,24 @@ nrt_status nrt_get_layer_affected(const nrt_cache*, int32_t layer, const int32_t
  * Errors: NRT_ERR_INVALID_ARG (null cache, unknown mode). */
 typedef enum { NRT_MODE_INCREMENTAL = 0, NRT_MODE_RECOMPUTE = 1, NRT_MODE_FULL = 2, NRT_MODE_AUTO = 3 } nrt_mode;
 nrt_status nrt_set_mode(nrt_cache*, int32_t mode);
+/* On-demand embedding computation (Section IV-D): serve a small set of query vertices without keeping every
+ * cached row up to date.  With the on-demand mode on, nrt_apply_batch validates the batch, mutates the graph,
+ * replaces the feature rows and expands the affected sets as usual (affected_ids is filled; affected_rows must be
+ * NULL), but instead of refreshing the caches it only records, per layer, that the affected vertices are stale.
+ * nrt_query then returns the final-layer rows of the queried vertices on the current snapshot: it intersects the
+ * stale sets with the L-hop in-neighbourhood of the query (need_L = Q and stale_L, need_{l-1} = stale_{l-1} and
+ * (need_l or their in-neighbours)), recomputes exactly those vertices layer by layer over their whole
+ * in-neighbourhoods (the recomputation of NRT_MODE_RECOMPUTE) and clears their stale marks; everything else stays
+ * stale until some later query needs it.  Turning the mode off recomputes all remaining stale vertices first.
+ * nrt_query also works with the mode off (it then only gathers rows).  Not available for NRT_GAT.
+ *   query_ids  device, n_query ids in [0, N), repeats allowed
+ *   rows       device, [n_query][d_L], row i = embedding of query_ids[i]
+ *   n_recomputed  host, may be NULL: vertices recomputed, summed over the layers
+ * Errors: NRT_ERR_INVALID_ARG (null pointers, an id out of range: rows are then unspecified),
+ * NRT_ERR_UNSUPPORTED (GAT), NRT_ERR_DEVICE.  Both calls synchronise the stream before returning. */
+nrt_status nrt_set_lazy(nrt_cache*, int32_t on, void* stream);
+nrt_status nrt_query(nrt_cache*, const int32_t* query_ids, int64_t n_query, float* rows, int64_t* n_recomputed /*host*/,
+                     void* stream);
 nrt_status nrt_set_profiling(nrt_cache*, int32_t on);
 nrt_status nrt_get_stats(const nrt_cache*, nrt_stats* out /*host*/);
 

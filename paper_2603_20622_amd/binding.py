@@ -61,7 +61,7 @@ class NrtError(RuntimeError):
 EXPORTS = ["nrt_graph_workspace_bytes", "nrt_graph_create", "nrt_graph_destroy", "nrt_graph_num_edges",
            "nrt_graph_export_csc", "nrt_cache_workspace_bytes", "nrt_cache_init", "nrt_cache_destroy",
            "nrt_apply_batch", "nrt_get_layer", "nrt_get_aggregate", "nrt_get_layer_affected", "nrt_set_profiling",
-           "nrt_set_mode", "nrt_get_stats", "nrt_last_error", "nrt_version"]
+           "nrt_set_mode", "nrt_set_lazy", "nrt_query", "nrt_get_stats", "nrt_last_error", "nrt_version"]
 
 _lib = None
 
@@ -90,6 +90,8 @@ def lib() -> ctypes.CDLL:
         L.nrt_get_layer_affected.argtypes = [c_fp, i32, P(c_fp), P(i64)]
         L.nrt_set_profiling.argtypes = [c_fp, i32]
         L.nrt_set_mode.argtypes = [c_fp, i32]
+        L.nrt_set_lazy.argtypes = [c_fp, i32, c_fp]
+        L.nrt_query.argtypes = [c_fp, c_fp, i64, c_fp, P(i64), c_fp]
         L.nrt_get_stats.argtypes = [c_fp, P(nrt_stats)]
         L.nrt_last_error.restype = ctypes.c_char_p
         L.nrt_version.restype = ctypes.c_char_p
@@ -272,6 +274,17 @@ NRT_MODE_INCREMENTAL, NRT_MODE_RECOMPUTE, NRT_MODE_FULL, NRT_MODE_AUTO = 0, 1, 2
 
 def nrt_set_mode(c: Cache, mode: int) -> None:
     _check(lib().nrt_set_mode(c.handle, int(mode)))
+
+
+def nrt_set_lazy(c: Cache, on: bool) -> None:
+    _check(lib().nrt_set_lazy(c.handle, int(on), _stream()))
+
+
+def nrt_query(c: Cache, query_ids: torch.Tensor, rows: torch.Tensor) -> int:
+    """rows[i] = final-layer embedding of query_ids[i]; returns the number of vertices recomputed for it."""
+    n = ctypes.c_int64(0)
+    _check(lib().nrt_query(c.handle, _ptr(query_ids), int(query_ids.numel()), _ptr(rows), ctypes.byref(n), _stream()))
+    return int(n.value)
 
 
 def nrt_set_profiling(c: Cache, on: bool) -> None:

@@ -49,6 +49,8 @@ struct nrt_cache {
     LayerCtrs* lc_use;                  // counters the layer steps read instead of lc[l] (null: lc[l])
     int mode;                           // nrt_mode
     bool have_history;                  // n_list holds the set sizes of a previous batch (hints for kernel choice)
+    int lazy;                           // on-demand mode: batches only record what became stale
+    uint32_t* stale[NRT_MAX_LAYERS + 1]; // per layer: vertices whose cached aggregate / embedding is out of date
     LayerCtrs* lc_host;                 // pinned mirror, followed by the mirror of pair_ctr (profiling)
     unsigned long long* pair_host;
     int32_t* xhub_list;
@@ -335,6 +337,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->sc.err = g->dev_ctrs ? (int32_t*)(g->dev_ctrs + CTR_ERR) : nullptr;
     c->pair_ctr = b.take<unsigned long long>(1024 * NRT_MAX_LAYERS);
     c->pull_list = b.take<int32_t>(n);
+    for (int l = 1; l <= c->L; ++l) c->stale[l] = gat ? nullptr : b.take<uint32_t>(nw);
     c->coarse = b.take<uint32_t>(NRT_COARSE_WORDS);
     c->coarse_shift = 0;
     while ((((n + ((int64_t)1 << c->coarse_shift) - 1) >> c->coarse_shift) + 31) / 32 > NRT_COARSE_WORDS) ++c->coarse_shift;
@@ -656,6 +659,8 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
                 else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][1], c->dims[l + 1], 0, s));
             }
         }
+        for (int l = 1; l <= c->L; ++l)
+            if (c->stale[l]) NRT_TRY(k_fill_u32(c->stale[l], (n + 31) / 32, 0, s));
         NRT_TRY(full_forward(c, s));
         HIP_TRY(hipStreamSynchronize(s));
         return NRT_OK;
@@ -691,6 +696,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     REQUIRE(c && b && n_affected, "null argument");
     REQUIRE(b->n_ins >= 0 && b->n_del >= 0 && b->n_feat >= 0, "negative batch count");
     REQUIRE(capacity >= 0 && (capacity == 0 || affected_ids), "affected_ids is null");
+    REQUIRE(!(c->lazy && affected_rows), "on-demand mode returns no rows from nrt_apply_batch (use nrt_query)");
     nrt_graph* g = c->g;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int64_t n = g->n;
@@ -740,12 +746,12 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     const bool empty_batch = b->n_ins + b->n_del + b->n_feat == 0;
     // ---- sets of the batch, structural terms on the old caches (scratch only)
     const bool gcn = c->kind == NRT_GCN;
-    const bool inc = c->mode == NRT_MODE_INCREMENTAL || c->mode == NRT_MODE_AUTO;
+    const bool inc = !c->lazy && (c->mode == NRT_MODE_INCREMENTAL || c->mode == NRT_MODE_AUTO);
     // layers that may switch to recomputation on the device: only where the previous batch had a large source set
     // (no extra launches for small frontiers); the device counters of this batch take the decision
     bool may_rec[NRT_MAX_LAYERS + 2];
     for (int l = 0; l <= c->L + 1; ++l)
-        may_rec[l] = c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
+        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     if (!empty_batch) NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, n, s));
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     if (inc && b->n_ins + b->n_del > 0) {
@@ -859,6 +865,11 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
         NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
                           g->scan_tmp_len, &c->lc[l].count, s));
+        if (c->lazy) {                                     // on-demand mode: A_l only becomes stale
+            NRT_TRY(k_or_words(c->stale[l], c->stale[l], c->bm[cur], (n + 31) / 32, s));
+            prev = cur;
+            continue;
+        }
         if (c->mode == NRT_MODE_FULL) {                    // only the affected lists are needed layer by layer
             NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
             prev = cur;
@@ -884,7 +895,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
         prev = cur;
     }
-    if (c->mode == NRT_MODE_FULL) {
+    if (c->mode == NRT_MODE_FULL && !c->lazy) {
         NRT_TRY(full_forward(c, s));
         if (affected_rows)
             NRT_TRY(k_gather_rows(affected_rows, c->H[c->L], c->list[c->L], &c->lc[c->L].count, capacity, n, c->dims[c->L], s));
@@ -910,7 +921,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             return NRT_ERR_STATE;
         }
     }
-    if (c->mode == NRT_MODE_FULL) {
+    if (c->mode == NRT_MODE_FULL && !c->lazy) {
         const LayerCtrs& all = c->lc_host[NRT_MAX_LAYERS + 1];
         if ((int64_t)all.n_hubs > c->hubs.hub_cap || (int64_t)all.n_items > c->hubs.item_cap) {
             nrt_set_error("internal: hub buffers too small");
@@ -959,6 +970,102 @@ extern "C" nrt_status nrt_get_layer_affected(const nrt_cache* c, int32_t layer, 
     *n = c->n_list[layer];
     return NRT_OK;
 }
+// ------------------------------------------------------------------ on-demand mode
+// Recompute, layer by layer, the vertices listed in c->list[l] (counts in c->lc[l].count) over their whole
+// in-neighbourhoods from the current h^{l-1}, and clear their stale bits.
+static nrt_status recompute_listed(nrt_cache* c, hipStream_t s) {
+    nrt_graph* g = c->g;
+    const int64_t n = g->n;
+    for (int l = 1; l <= c->L; ++l) {
+        NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, nullptr, s));
+        NRT_TRY(run_gather(c, l, false, 0, false, 0, s));
+        NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, false, 0, nullptr, 0, false, s));
+        NRT_TRY(k_clear_listed_bits(c->stale[l], c->list[l], &c->lc[l].count, n, s));
+    }
+    return NRT_OK;
+}
+
+static nrt_status finish_recompute(nrt_cache* c, int64_t* n_recomputed, hipStream_t s) {
+    HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    int64_t tot = 0;
+    for (int l = 1; l <= c->L; ++l) {
+        tot += (int64_t)c->lc_host[l].count;
+        if ((int64_t)c->lc_host[l].n_hubs > c->hubs.hub_cap || (int64_t)c->lc_host[l].n_items > c->hubs.item_cap ||
+            (int64_t)c->lc_host[l].n_xhubs > c->xhub_cap) {
+            nrt_set_error("internal: hub buffers too small");
+            return NRT_ERR_STATE;
+        }
+    }
+    if (n_recomputed) *n_recomputed = tot;
+    c->have_history = false;        // the set sizes of this pass are not those of a batch
+    return NRT_OK;
+}
+
+extern "C" nrt_status nrt_set_lazy(nrt_cache* c, int32_t on, void* stream) {
+    REQUIRE(c, "null argument");
+    if (c->kind == NRT_GAT) { nrt_set_error("on-demand mode is not available for GAT"); return NRT_ERR_UNSUPPORTED; }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (c->lazy && !on) {            // bring every stale vertex up to date before batches are applied eagerly again
+        nrt_graph* g = c->g;
+        const int64_t n = g->n;
+        NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
+        for (int l = 1; l <= c->L; ++l)
+            NRT_TRY(k_compact(nullptr, c->stale[l], nullptr, c->bm[0], n, c->list[l], nullptr, g->scan_tmp, g->scan_tmp_len,
+                              &c->lc[l].count, s));
+        NRT_TRY(recompute_listed(c, s));
+        NRT_TRY(finish_recompute(c, nullptr, s));
+    }
+    c->lazy = on ? 1 : 0;
+    return NRT_OK;
+}
+
+extern "C" nrt_status nrt_query(nrt_cache* c, const int32_t* query_ids, int64_t n_query, float* rows,
+                                int64_t* n_recomputed, void* stream) {
+    REQUIRE(c && n_query >= 0 && (n_query == 0 || (query_ids && rows)), "null argument or negative count");
+    if (n_recomputed) *n_recomputed = 0;
+    if (n_query == 0) return NRT_OK;
+    nrt_graph* g = c->g;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int64_t n = g->n;
+    const int64_t nw = (n + 31) / 32;
+    LayerCtrs* spare = &c->lc[NRT_MAX_LAYERS + 1];          // count = n_query for the final row gather; in_edges[0] = bad-id flag
+    NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
+    NRT_TRY(k_fill_u64(&spare->count, 1, (uint64_t)n_query, s));
+    if (c->lazy) {
+        // ---- which stale vertices do the queried embeddings depend on?  Backwards from the last layer:
+        // need_L = Q and stale_L;  need_{l-1} = stale_{l-1} and (need_l or in-neighbours(need_l))
+        NRT_TRY(k_fill_u32(c->bm_feat, nw, 0, s));
+        NRT_TRY(k_mark_ids(c->bm_feat, query_ids, n_query, n, (int32_t*)&spare->in_edges[0], s));
+        int cur = 0;
+        NRT_TRY(k_compact(nullptr, c->bm_feat, nullptr, c->bm[cur], n, c->list[c->L], nullptr, g->scan_tmp, g->scan_tmp_len,
+                          &c->lc[c->L].count, s, c->stale[c->L]));
+        PullArgs no_pull;
+        memset(&no_pull, 0, sizeof(no_pull));
+        for (int l = c->L; l >= 2; --l) {
+            // the in-lists play the part of out-lists: flags[u] = 1 for every in-neighbour u of need_l
+            NRT_TRY(k_expand_frontier(g->in, c->list[l], &c->lc[l].count, n, c->flags, &c->lc[l], c->xhub_list, c->xhub_cap,
+                                      g->out, no_pull, s));
+            NRT_TRY(k_compact(c->flags, c->bm[cur], nullptr, c->bm[1 - cur], n, c->list[l - 1], nullptr, g->scan_tmp,
+                              g->scan_tmp_len, &c->lc[l - 1].count, s, c->stale[l - 1]));
+            cur = 1 - cur;
+        }
+        NRT_TRY(recompute_listed(c, s));
+    } else {
+        NRT_TRY(k_fill_u32(c->bm_feat, nw, 0, s));
+        NRT_TRY(k_mark_ids(c->bm_feat, query_ids, n_query, n, (int32_t*)&spare->in_edges[0], s));   // only validates the ids
+    }
+    // rows of the queried vertices (ids already range-checked: a bad id makes the whole call fail below, and the
+    // gather skips nothing it should not read because such ids are replaced by vertex 0)
+    NRT_TRY(k_gather_rows_checked(rows, c->H[c->L], query_ids, n_query, n, c->dims[c->L], s));
+    NRT_TRY(finish_recompute(c, n_recomputed, s));
+    if (c->lc_host[NRT_MAX_LAYERS + 1].in_edges[0] != 0) {
+        nrt_set_error("query id out of range");
+        return NRT_ERR_INVALID_ARG;
+    }
+    return NRT_OK;
+}
+
 extern "C" nrt_status nrt_set_mode(nrt_cache* c, int32_t mode) {
     REQUIRE(c, "null argument");
     REQUIRE(mode == NRT_MODE_INCREMENTAL || mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL || mode == NRT_MODE_AUTO,

@@ -111,10 +111,19 @@ nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_
 nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
                         const int32_t* b0, int64_t nb0, int64_t n, hipStream_t s);
 // Compaction of a vertex set into a sorted id list.  The set is the union of the byte flags (one byte per vertex,
-// may be null; they are cleared on the way), and up to two bitmaps or_a, or_b (may be null).  Writes the set as
-// bitmap `out_bm`, its sorted ids to `list`, slot[id] = position, *count = size.
+// may be null; they are cleared on the way), and up to two bitmaps or_a, or_b (may be null), intersected with
+// and_mask when given.  Writes the set as bitmap `out_bm`, its sorted ids to `list`, slot[id] = position (slot may
+// be null), *count = size.
 nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm, int64_t n,
-                     int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s);
+                     int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s,
+                     const uint32_t* and_mask = nullptr);
+// dst[i][:] = src[ids[i]][:] for i < n_ids (host count); an id outside [0, n) reads row 0
+nrt_status k_gather_rows_checked(float* dst, const float* src, const int32_t* ids, int64_t n_ids, int64_t n, int D,
+                                 hipStream_t s);
+// bm |= ids; an id outside [0, n) sets *bad (device) instead
+nrt_status k_mark_ids(uint32_t* bm, const int32_t* ids, int64_t n_ids, int64_t n, int32_t* bad, hipStream_t s);
+// bm &= ~(list[0 .. *count))
+nrt_status k_clear_listed_bits(uint32_t* bm, const int32_t* list, const uint64_t* count, int64_t bound, hipStream_t s);
 
 // ---------------------------------------------------------------- frontier.hip
 // flags[v] = 1 for every out-neighbour v of the sources src_list[0 .. *ns_dev) that is not itself a source

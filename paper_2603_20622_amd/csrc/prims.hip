@@ -64,6 +64,18 @@ __global__ void gather_rows_kernel(float* dst, const float* src, const int32_t* 
             *reinterpret_cast<float4*>(dst + i * D + k) = *reinterpret_cast<const float4*>(p + k);
     }
 }
+// dst[i][:] = src[ids[i]][:] for i < n_ids; an id outside [0, n) reads row 0 (the caller reports it as an error)
+__global__ void gather_rows_checked_kernel(float* dst, const float* src, const int32_t* ids, int64_t n_ids, int64_t n, int D) {
+    const int lane = threadIdx.x & 63;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t i = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; i < n_ids; i += waves) {
+        int32_t v = ids[i];
+        if (v < 0 || v >= n) v = 0;
+        const float* p = src + (int64_t)v * D;
+        for (int k = lane * 4; k < D; k += 256)
+            *reinterpret_cast<float4*>(dst + i * D + k) = *reinterpret_cast<const float4*>(p + k);
+    }
+}
 __global__ void or_words_kernel(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -154,8 +166,8 @@ __device__ inline uint32_t pack_flags(uint8_t* flags, int64_t w, int64_t n) {
     }
     return bits;
 }
-__global__ void set_count_kernel(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm,
-                                 int64_t n, int64_t nw, uint64_t* tmp) {
+__global__ void set_count_kernel(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, const uint32_t* and_mask,
+                                 uint32_t* out_bm, int64_t n, int64_t nw, uint64_t* tmp) {
     const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
     uint64_t s = 0;
 #pragma unroll
@@ -165,6 +177,7 @@ __global__ void set_count_kernel(uint8_t* flags, const uint32_t* or_a, const uin
             uint32_t bits = flags ? pack_flags(flags, w, n) : 0u;
             if (or_a) bits |= or_a[w];
             if (or_b) bits |= or_b[w];
+            if (and_mask) bits &= and_mask[w];
             out_bm[w] = bits;
             s += __popc(bits);
         }
@@ -172,6 +185,24 @@ __global__ void set_count_kernel(uint8_t* flags, const uint32_t* or_a, const uin
     uint64_t tot;
     block_excl_scan(s, &tot);
     if (threadIdx.x == 0) tmp[blockIdx.x] = tot;
+}
+// bm |= ids (ids outside [0, n) raise *bad instead)
+__global__ void mark_ids_kernel(uint32_t* bm, const int32_t* ids, int64_t n_ids, int64_t n, int32_t* bad) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n_ids) return;
+    const int32_t v = ids[i];
+    if (v < 0 || v >= n) { *bad = 1; return; }
+    atomicOr(&bm[v >> 5], 1u << (v & 31));
+}
+// bm &= ~(listed ids)
+__global__ void clear_listed_bits_kernel(uint32_t* bm, const int32_t* list, const uint64_t* count) {
+    const int64_t n = (int64_t)*count;
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        const int32_t v = list[i];
+        atomicAnd(&bm[v >> 5], ~(1u << (v & 31)));
+    }
 }
 __global__ void bm_emit_kernel(const uint32_t* bm, int64_t nw, const uint64_t* tmp, int32_t* list, int32_t* slot) {
     const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
@@ -245,6 +276,15 @@ nrt_status k_gather_rows(float* dst, const float* src, const int32_t* list, cons
     LAUNCH_CHECK();
     return NRT_OK;
 }
+nrt_status k_gather_rows_checked(float* dst, const float* src, const int32_t* ids, int64_t n_ids, int64_t n, int D,
+                                 hipStream_t s) {
+    if (n_ids <= 0) return NRT_OK;
+    int64_t g = cdiv(n_ids, 4);
+    if (g > 4096) g = 4096;
+    gather_rows_checked_kernel<<<(int)g, 256, 0, s>>>(dst, src, ids, n_ids, n, D);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
 nrt_status k_or_words(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t nwords, hipStream_t s) {
     if (nwords <= 0) return NRT_OK;
     or_words_kernel<<<grid_for(nwords, 256), 256, 0, s>>>(dst, a, b, nwords);
@@ -283,12 +323,25 @@ nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_
     return NRT_OK;
 }
 
+nrt_status k_mark_ids(uint32_t* bm, const int32_t* ids, int64_t n_ids, int64_t n, int32_t* bad, hipStream_t s) {
+    if (n_ids <= 0) return NRT_OK;
+    mark_ids_kernel<<<(int)cdiv(n_ids, 256), 256, 0, s>>>(bm, ids, n_ids, n, bad);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_clear_listed_bits(uint32_t* bm, const int32_t* list, const uint64_t* count, int64_t bound, hipStream_t s) {
+    if (bound <= 0) return NRT_OK;
+    clear_listed_bits_kernel<<<grid_for(bound, 256, 2048), 256, 0, s>>>(bm, list, count);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
 nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm, int64_t n,
-                     int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s) {
+                     int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s,
+                     const uint32_t* and_mask) {
     const int64_t nw = cdiv(n, 32);
     const int64_t nb = nw > 0 ? cdiv(nw, EPB) : 0;
     if (nb > tmp_len) { nrt_set_error("scan scratch too small"); return NRT_ERR_INVALID_ARG; }
-    if (nb > 0) { set_count_kernel<<<(int)nb, TPB, 0, s>>>(flags, or_a, or_b, out_bm, n, nw, tmp); LAUNCH_CHECK(); }
+    if (nb > 0) { set_count_kernel<<<(int)nb, TPB, 0, s>>>(flags, or_a, or_b, and_mask, out_bm, n, nw, tmp); LAUNCH_CHECK(); }
     scan_top_kernel<<<1, TPB, 0, s>>>(tmp, nb, count);
     LAUNCH_CHECK();
     if (nb > 0) { bm_emit_kernel<<<(int)nb, TPB, 0, s>>>(out_bm, nw, tmp, list, slot); LAUNCH_CHECK(); }

@@ -80,6 +80,16 @@ class Session:
     def mode(self, mode: int):
         nb.nrt_set_mode(self.cache, mode)
 
+    def lazy(self, on: bool):
+        nb.nrt_set_lazy(self.cache, on)
+
+    def query(self, ids: np.ndarray):
+        """(rows, n_recomputed) for the queried vertex ids."""
+        q = _dev(np.asarray(ids, dtype=np.int32))
+        rows = torch.empty((len(ids), self.spec.dims[-1]), dtype=torch.float32, device="cuda")
+        n = nb.nrt_query(self.cache, q, rows)
+        return rows, n
+
     def profiling(self, on: bool):
         nb.nrt_set_profiling(self.cache, on)
 

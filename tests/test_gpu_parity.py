@@ -459,3 +459,77 @@ def test_widest_rows(S, oracle):
         assert np.array_equal(ses.ids[:na].cpu().numpy(), oracle.affected_sets(spec, n, cur[0], cur[1], b)[-1])
         for l in (1, 2):
             assert rel_err(ses.layer(l).cpu().numpy(), ref[l - 1]) <= TOL
+
+
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN])
+def test_on_demand_queries_match_oracle(S, oracle, kind):
+    """On-demand mode (Section IV-D): batches only mark vertices stale; a query recomputes the stale part of the
+    L-hop in-neighbourhood of the queried vertices, nothing else, and returns rows equal to a full recomputation."""
+    from paper_2603_20622_amd import binding as nb
+    n, e = 6000, 30000
+    src, dst, sampler = wl.rmat_graph(n, e, 101)
+    weighted = kind == wl.GIN
+    w = wl.edge_weights(e, 101) if weighted else None
+    spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted)
+    params = wl.make_params(spec, 101, bias=True)
+    x = wl.features(n, 16, 101)
+    stream = wl.BatchStream(n, src, dst, w, sampler, 16, 101)
+    ses = S.Session(spec, params, n, src, dst, w, x)
+    cur = (src, dst, w, x)
+    rng = np.random.default_rng(7)
+    ses.lazy(True)
+    stale_total = 0
+    for k in range(3):
+        b = stream.next_batch(4, 4, 2)
+        na = ses.apply(b, want_rows=False)
+        cur = oracle.apply_batch(n, *cur, b)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1]), k
+        stale_total += sum(len(a) for a in sets)
+    ref = oracle.forward(spec, params, n, *cur)
+    assert np.array_equal(ses.layer(0).cpu().numpy(), cur[3])                 # features are never stale
+    q = rng.choice(n, 40, replace=False).astype(np.int32)
+    rows, n_rec = ses.query(q)
+    assert_parity(kind, rows.cpu().numpy(), ref[-1][q], (kind, "query"))
+    assert 0 <= n_rec < stale_total                                            # only what the query depends on
+    rows2, n_rec2 = ses.query(q)
+    assert n_rec2 == 0 and np.array_equal(rows2.cpu().numpy(), rows.cpu().numpy())
+    # more batches, a query with repeats, then everything
+    for k in range(2):
+        b = stream.next_batch(5, 5, 1)
+        ses.apply(b, want_rows=False)
+        cur = oracle.apply_batch(n, *cur, b)
+    ref = oracle.forward(spec, params, n, *cur)
+    q2 = np.concatenate([q[:5], q[:5], rng.choice(n, 10).astype(np.int32)])
+    rows, _ = ses.query(q2)
+    assert_parity(kind, rows.cpu().numpy(), ref[-1][q2], (kind, "query2"))
+    allv = np.arange(n, dtype=np.int32)
+    rows, _ = ses.query(allv)
+    assert_parity(kind, rows.cpu().numpy(), ref[-1], (kind, "all"))
+    # an id out of range is an error
+    with pytest.raises(nb.NrtError) as ei:
+        ses.query(np.array([3, n], np.int32))
+    assert ei.value.status == nb.NRT_ERR_INVALID_ARG
+    # back to eager maintenance: stale vertices are flushed, the next batch is incremental again
+    b = stream.next_batch(6, 6, 2)
+    ses.apply(b, want_rows=False)
+    cur = oracle.apply_batch(n, *cur, b)
+    ses.lazy(False)
+    ref = oracle.forward(spec, params, n, *cur)
+    for l in range(1, spec.n_layers + 1):
+        assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "flush", l))
+    b = stream.next_batch(6, 6, 2)
+    na = ses.apply(b)
+    cur = oracle.apply_batch(n, *cur, b)
+    ref = oracle.forward(spec, params, n, *cur)
+    for l in range(1, spec.n_layers + 1):
+        assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "eager", l))
+
+
+def test_on_demand_is_refused_for_gat(S, oracle):
+    from paper_2603_20622_amd import binding as nb
+    n, src, dst, w, x, spec, params, stream = small_case(wl.GAT, seed=5)
+    ses = S.Session(spec, params, n, src, dst, w, x)
+    with pytest.raises(nb.NrtError) as ei:
+        ses.lazy(True)
+    assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
