@@ -8,8 +8,8 @@
  * then applies a batch of edge insertions, edge deletions and feature replacements by
  *   (1) expanding the affected vertex set hop by hop (Algorithm 4),
  *   (2) gathering delta messages over the affected edges only and folding them into the cached
- *       aggregates (Algorithm 1 lines 1-6, Algorithm 3 lines 1-8 for GAT),
- *   (3) re-running the dense update on the affected rows only (Algorithm 1 line 7),
+ *       aggregates (the message and aggregation steps of Algorithm 1, Algorithm 3 for GAT),
+ *   (3) re-running the dense update on the affected rows only (the update step of Algorithm 1),
  *   (4) writing the refreshed rows back into the caches,
  * and returns the refreshed final-layer rows with the sorted list of affected vertex ids.
  * By Theorem 1 the result equals a full recomputation on the post-update snapshot.

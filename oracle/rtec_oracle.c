@@ -10,7 +10,7 @@
  *                  per-source payload p_u and per-edge coefficient are chosen by the caller)
  *
  *  orc_gat_attend  o_v = sum_u softmax_u(LeakyReLU(ad_v + as_u)) * z_u over u in N(v) U {v}
- *                  (GAT attention Eq. 3 and aggregation Eq. 4; Algorithm 2 lines 1-6),
+ *                  (GAT attention Eq. 3 and aggregation Eq. 4; Algorithm 2),
  *                  evaluated with the usual max-subtracted softmax, which is the same
  *                  function as the raw exp / sum form the paper prints.
  *

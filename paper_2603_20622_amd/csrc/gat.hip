@@ -1,15 +1,15 @@
 // GAT on the incremental path (Eq. 3-4; Algorithms 2 and 3).
 //
 // Cached per layer and vertex: z = x W, the two attention scalars per head as = a_src . z, ad = a_dst . z (they
-// replace the per-edge cached attention of Algorithm 3 line 3: an old logit is recomputed from old scalars), a
+// replace the per-edge cached attention that Algorithm 3 keeps: an old logit is recomputed from old scalars), a
 // running bound m of the largest logit, the attention sum den = sum exp(e - m) (Algorithm 3's at_sum, shifted by
 // m so that exp cannot overflow) and the context-free aggregate S = sum exp(e - m) z_u (Algorithm 3's a-hat).
 //
 // For an affected destination v:
 //   * if its own z changed (its layer input changed), every logit of v has changed: v is recomputed over its full
-//     new in-neighbourhood plus itself (Algorithm 2; the constrained-model rule of Section III-D / Algorithm 4
-//     lines 5-7);
-//   * otherwise Algorithm 3 (lines 2-7) touches only what changed:
+//     new in-neighbourhood plus itself (Algorithm 2; the constrained-model rule of Section III-D, the
+//     destination-affected case of Algorithm 4);
+//   * otherwise Algorithm 3 touches only what changed:
 //       den += sum (at_new - at_old),  S += sum (at_new z_new - at_old z_old)
 //     over the in-neighbours whose z changed, plus the edge updates of the batch: a deleted in-edge contributes
 //     (-at_old, -at_old z_old), folded on the old caches into a compact row per destination before the graph

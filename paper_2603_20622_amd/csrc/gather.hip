@@ -1,4 +1,4 @@
-// Delta-message gather and fold (Algorithm 1 lines 1-6 with the aggregate cached in context-free form).
+// Delta-message gather and fold (the message and aggregation steps of Algorithm 1, with the aggregate cached in context-free form).
 //
 // For every affected destination v the cached sum S[v] = sum_u c_uv p_u receives the changes of its
 // affected in-neighbours: S[v] += sum_{u in N_new(v), u changed} c_uv * dp_u, where dp_u is the change of

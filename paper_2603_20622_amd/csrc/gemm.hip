@@ -1,4 +1,4 @@
-// Affected-row dense update (Algorithm 1 line 7; "update" column of Table II) as an fp32 MFMA GEMM.
+// Affected-row dense update (the update step of Algorithm 1; "update" column of Table II) as an fp32 MFMA GEMM.
 //
 //   Y[m][:] = act( A[m][:] . W + bias ),  m over the affected rows only,
 // where row m of A is formed on the fly from the cached rows of vertex rows[m]:
