@@ -27,6 +27,8 @@ __device__ inline float4 f4_fma(float c, float4 x, float4 a) {
     a.x = fmaf(c, x.x, a.x); a.y = fmaf(c, x.y, a.y); a.z = fmaf(c, x.z, a.z); a.w = fmaf(c, x.w, a.w);
     return a;
 }
+// Element offset of a row: row ids are non-negative, so the product is one unsigned 32x32->64 multiply.
+__device__ inline int64_t row_off(int32_t row, int D) { return (int64_t)((uint64_t)(uint32_t)row * (uint32_t)D); }
 __device__ inline float4 f4_add(float4 a, float4 b) { return make_float4(a.x + b.x, a.y + b.y, a.z + b.z, a.w + b.w); }
 __device__ inline float4 f4_shfl_xor(float4 a, int m) {
     return make_float4(__shfl_xor(a.x, m, 64), __shfl_xor(a.y, m, 64), __shfl_xor(a.z, m, 64), __shfl_xor(a.w, m, 64));
@@ -198,7 +200,7 @@ __device__ inline void full_row(const GatherArgs& a, int32_t v, int64_t off, int
 #pragma unroll
             for (int q = 0; q < NV; ++q)
                 if (rr >= 0 && gl * 4 + q * LPR * 4 < D)
-                    acc[q] = f4_fma(cc, *reinterpret_cast<const float4*>(Pl + (int64_t)rr * D + q * LPR * 4), acc[q]);
+                    acc[q] = f4_fma(cc, *reinterpret_cast<const float4*>(Pl + row_off(rr, D) + q * LPR * 4), acc[q]);
         }
     }
     if (a.self_pair && sub == 0) {
@@ -352,10 +354,10 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
             for (int q = 0; q < NV; ++q) {
                 const bool live = gl * 4 + q * LPR * 4 < D;
                 float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0, x2 = x0, x3 = x0;
-                if (p0.x >= 0 && live) x0 = *reinterpret_cast<const float4*>(Pl + (int64_t)p0.x * D + q * LPR * 4);
-                if (p1.x >= 0 && live) x1 = *reinterpret_cast<const float4*>(Pl + (int64_t)p1.x * D + q * LPR * 4);
-                if (p2.x >= 0 && live) x2 = *reinterpret_cast<const float4*>(Pl + (int64_t)p2.x * D + q * LPR * 4);
-                if (p3.x >= 0 && live) x3 = *reinterpret_cast<const float4*>(Pl + (int64_t)p3.x * D + q * LPR * 4);
+                if (p0.x >= 0 && live) x0 = *reinterpret_cast<const float4*>(Pl + row_off(p0.x, D) + q * LPR * 4);
+                if (p1.x >= 0 && live) x1 = *reinterpret_cast<const float4*>(Pl + row_off(p1.x, D) + q * LPR * 4);
+                if (p2.x >= 0 && live) x2 = *reinterpret_cast<const float4*>(Pl + row_off(p2.x, D) + q * LPR * 4);
+                if (p3.x >= 0 && live) x3 = *reinterpret_cast<const float4*>(Pl + row_off(p3.x, D) + q * LPR * 4);
                 acc[q] = COEF ? f4_fma(c0, x0, acc[q]) : f4_add(acc[q], x0);
                 acc[q] = COEF ? f4_fma(c1, x1, acc[q]) : f4_add(acc[q], x1);
                 acc[q] = COEF ? f4_fma(c2, x2, acc[q]) : f4_add(acc[q], x2);
@@ -369,8 +371,8 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
             for (int q = 0; q < NV; ++q) {
                 const bool live = gl * 4 + q * LPR * 4 < D;
                 float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0;
-                if (p0.x >= 0 && live) x0 = *reinterpret_cast<const float4*>(Pl + (int64_t)p0.x * D + q * LPR * 4);
-                if (p1.x >= 0 && live) x1 = *reinterpret_cast<const float4*>(Pl + (int64_t)p1.x * D + q * LPR * 4);
+                if (p0.x >= 0 && live) x0 = *reinterpret_cast<const float4*>(Pl + row_off(p0.x, D) + q * LPR * 4);
+                if (p1.x >= 0 && live) x1 = *reinterpret_cast<const float4*>(Pl + row_off(p1.x, D) + q * LPR * 4);
                 acc[q] = COEF ? f4_fma(c0, x0, acc[q]) : f4_add(acc[q], x0);
                 acc[q] = COEF ? f4_fma(c1, x1, acc[q]) : f4_add(acc[q], x1);
             }
@@ -607,7 +609,7 @@ __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs
                 const int32_t fl = __shfl(u_flags, from, 64);
                 const int32_t vr = __shfl(u_v, from, 64);
                 if ((fl & (SF_LAST | SF_PART)) == SF_LAST && live)
-                    old[ps] = *reinterpret_cast<const float4*>(a.S + (int64_t)vr * D + gl * 4);
+                    old[ps] = *reinterpret_cast<const float4*>(a.S + row_off(vr, D) + gl * 4);
             }
         }
         int32_t maxcnt = max(max(__builtin_amdgcn_readlane(u_cnt, 0), __builtin_amdgcn_readlane(u_cnt, 16)),
@@ -682,10 +684,10 @@ __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs
                         if (t + 3 >= n_u) c4.w = 0.f;
                     }
                     float4 x0 = make_float4(0.f, 0.f, 0.f, 0.f), x1 = x0, x2 = x0, x3 = x0;
-                    if (t + 0 < n_u && live) x0 = *reinterpret_cast<const float4*>(Pl + (int64_t)s4.x * D);
-                    if (t + 1 < n_u && live) x1 = *reinterpret_cast<const float4*>(Pl + (int64_t)s4.y * D);
-                    if (t + 2 < n_u && live) x2 = *reinterpret_cast<const float4*>(Pl + (int64_t)s4.z * D);
-                    if (t + 3 < n_u && live) x3 = *reinterpret_cast<const float4*>(Pl + (int64_t)s4.w * D);
+                    if (t + 0 < n_u && live) x0 = *reinterpret_cast<const float4*>(Pl + row_off(s4.x, D));
+                    if (t + 1 < n_u && live) x1 = *reinterpret_cast<const float4*>(Pl + row_off(s4.y, D));
+                    if (t + 2 < n_u && live) x2 = *reinterpret_cast<const float4*>(Pl + row_off(s4.z, D));
+                    if (t + 3 < n_u && live) x3 = *reinterpret_cast<const float4*>(Pl + row_off(s4.w, D));
                     acc[ps] = COEF ? f4_fma(c4.x, x0, acc[ps]) : f4_add(acc[ps], x0);
                     acc[ps] = COEF ? f4_fma(c4.y, x1, acc[ps]) : f4_add(acc[ps], x1);
                     acc[ps] = COEF ? f4_fma(c4.z, x2, acc[ps]) : f4_add(acc[ps], x2);

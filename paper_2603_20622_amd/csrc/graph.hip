@@ -14,6 +14,8 @@ constexpr int RB_EPT = 4;
 constexpr int RB_FEW = 256;        // up to this many deletions a list is patched instead of squeezed
 constexpr int VAL_THREADS = 1024; // threads of an edge-validation workgroup
 constexpr int VAL_UNROLL = 4;     // independent list loads per thread and trip
+constexpr int WAVE_LIST_MAX = 1024;        // longest list one wave searches or squeezes by itself
+constexpr int64_t PACKED_MIN_OPS = 4096;   // batches with more edge updates than this pack 16 updates into a workgroup
 
 __device__ inline int32_t new_cap_for(int32_t need) { return need + need / 2 + 4; }
 __device__ inline int32_t initial_cap_for(int32_t deg) { return deg + deg / 8 + 2; }
@@ -101,55 +103,141 @@ __device__ inline int64_t find_in_list(const Adj& a, int32_t k, int32_t target, 
     return r;
 }
 
-// One workgroup per updated edge.
 // err: [0] id out of range  [1] self-loop  [2] inserted edge present  [3] deleted edge absent
 //      [4] repeated entry   [5] repeated feature id
-__global__ void __launch_bounds__(VAL_THREADS)
-validate_edges_kernel(Adj out, Adj in, int64_t n, int64_t n_ins, int64_t n_del,
-                      const int32_t* ins_src, const int32_t* ins_dst, const int32_t* del_src,
-                      const int32_t* del_dst, uint64_t* hash, int64_t hash_cap, int64_t* pos_out,
-                      int64_t* pos_in, float* del_w, int32_t* err, int32_t* inscnt0,
-                      int32_t* inscnt1, int32_t* delcnt0, int32_t* delcnt1) {
-    __shared__ int64_t s_pos1;
-    int64_t* const s_pos = &s_pos1;
-    const int64_t op = blockIdx.x;
+struct ValArgs {
+    Adj out, in;
+    int64_t n, n_ins, n_del;
+    const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
+    uint64_t* hash; int64_t hash_cap;
+    int64_t *pos_out, *pos_in;
+    float* del_w;
+    int32_t* err;
+    int32_t *inscnt0, *inscnt1, *delcnt0, *delcnt1;
+};
+
+// records the update in the batch's set of (src, dst) keys; a key met twice is a repeated entry
+__device__ inline void note_key(const ValArgs& A, int32_t u, int32_t v) {
+    const uint64_t key = (((uint64_t)(uint32_t)u) << 32 | (uint32_t)v) + 1;   // 0 marks an empty cell
+    uint64_t h = mix64(key) & (uint64_t)(A.hash_cap - 1);
+    for (int64_t probe = 0; probe < A.hash_cap; ++probe) {
+        unsigned long long prev = atomicCAS((unsigned long long*)&A.hash[h], 0ULL, (unsigned long long)key);
+        if (prev == 0ULL) break;
+        if (prev == key) { A.err[4] = 1; break; }
+        h = (h + 1) & (uint64_t)(A.hash_cap - 1);
+    }
+}
+
+// what a validated update leaves behind: positions and weight of a deleted edge, the per-vertex counts
+__device__ inline void note_delete(const ValArgs& A, int64_t i, int32_t u, int32_t v, int64_t po, int64_t pi) {
+    A.pos_out[i] = po;
+    A.pos_in[i] = pi;
+    if (A.del_w) A.del_w[i] = A.out.wts ? A.out.wts[po] : 1.0f;
+    atomicAdd(&A.delcnt0[u], 1);
+    atomicAdd(&A.delcnt1[v], 1);
+}
+__device__ inline void note_insert(const ValArgs& A, int32_t u, int32_t v) {
+    atomicAdd(&A.inscnt0[u], 1);
+    atomicAdd(&A.inscnt1[v], 1);
+}
+
+// One update checked by the whole workgroup (every condition below is uniform over the workgroup).
+__device__ inline void validate_by_workgroup(const ValArgs& A, int64_t op, bool with_key, int64_t* s_pos) {
     const bool lead = threadIdx.x == 0;
-    const bool is_del = op >= n_ins;
-    const int64_t i = is_del ? op - n_ins : op;
-    const int32_t u = is_del ? del_src[i] : ins_src[i];
-    const int32_t v = is_del ? del_dst[i] : ins_dst[i];
-    if (u < 0 || u >= n || v < 0 || v >= n) { if (lead) err[0] = 1; return; }
-    if (u == v) { if (lead) err[1] = 1; return; }
-    if (lead) {
-        const uint64_t key = (((uint64_t)(uint32_t)u) << 32 | (uint32_t)v) + 1;   // 0 marks an empty cell
-        uint64_t h = mix64(key) & (uint64_t)(hash_cap - 1);
-        for (int64_t probe = 0; probe < hash_cap; ++probe) {
-            unsigned long long prev = atomicCAS((unsigned long long*)&hash[h], 0ULL, (unsigned long long)key);
-            if (prev == 0ULL) break;
-            if (prev == key) { err[4] = 1; break; }
-            h = (h + 1) & (uint64_t)(hash_cap - 1);
-        }
-    }
+    const bool is_del = op >= A.n_ins;
+    const int64_t i = is_del ? op - A.n_ins : op;
+    const int32_t u = is_del ? A.del_src[i] : A.ins_src[i];
+    const int32_t v = is_del ? A.del_dst[i] : A.ins_dst[i];
+    if (u < 0 || u >= A.n || v < 0 || v >= A.n) { if (lead) A.err[0] = 1; return; }
+    if (u == v) { if (lead) A.err[1] = 1; return; }
+    if (lead && with_key) note_key(A, u, v);
     if (is_del) {
-        const int64_t po = find_in_list(out, u, v, s_pos);
-        const int64_t pi = find_in_list(in, v, u, s_pos);
-        if (po < 0 || pi < 0) { if (lead) err[3] = 1; return; }
-        if (lead) {
-            pos_out[i] = po;
-            pos_in[i] = pi;
-            if (del_w) del_w[i] = out.wts ? out.wts[po] : 1.0f;
-            atomicAdd(&delcnt0[u], 1);
-            atomicAdd(&delcnt1[v], 1);
-        }
+        const int64_t po = find_in_list(A.out, u, v, s_pos);
+        const int64_t pi = find_in_list(A.in, v, u, s_pos);
+        if (po < 0 || pi < 0) { if (lead) A.err[3] = 1; return; }
+        if (lead) note_delete(A, i, u, v, po, pi);
     } else {
-        const bool use_out = out.deg[u] <= in.deg[v];
-        const int64_t p = use_out ? find_in_list(out, u, v, s_pos) : find_in_list(in, v, u, s_pos);
-        if (p >= 0) { if (lead) err[2] = 1; return; }
-        if (lead) {
-            atomicAdd(&inscnt0[u], 1);
-            atomicAdd(&inscnt1[v], 1);
+        const bool use_out = A.out.deg[u] <= A.in.deg[v];
+        const int64_t p = use_out ? find_in_list(A.out, u, v, s_pos) : find_in_list(A.in, v, u, s_pos);
+        if (p >= 0) { if (lead) A.err[2] = 1; return; }
+        if (lead) note_insert(A, u, v);
+    }
+}
+
+// One workgroup per updated edge: the latency of a batch of a few thousand updates is that of its longest lists.
+__global__ void __launch_bounds__(VAL_THREADS) validate_edges_kernel(ValArgs A) {
+    __shared__ int64_t s_pos;
+    validate_by_workgroup(A, blockIdx.x, true, &s_pos);
+}
+
+// search by one wave; every lane gets the pool position or -1 (edges are unique, so at most one hit)
+__device__ inline int64_t wave_find_in_list(const Adj& a, int32_t k, int32_t target, int lane) {
+    const int64_t o = a.off[k];
+    const int32_t d = a.deg[k];
+    int32_t found = -1;
+    for (int32_t j0 = 0; j0 < d; j0 += VAL_UNROLL * 64) {
+        int32_t e[VAL_UNROLL];
+#pragma unroll
+        for (int t = 0; t < VAL_UNROLL; ++t) {
+            const int32_t jj = j0 + t * 64 + lane;
+            e[t] = jj < d ? a.idx[o + jj] : -2;
+        }
+#pragma unroll
+        for (int t = 0; t < VAL_UNROLL; ++t)
+            if (e[t] == target) found = j0 + t * 64 + lane;
+    }
+#pragma unroll
+    for (int sft = 1; sft < 64; sft <<= 1) found = max(found, __shfl_xor(found, sft, 64));
+    return found < 0 ? -1 : o + found;
+}
+
+// Large batches: a workgroup takes 16 updates, one per wave.  Most lists are short and a wave checks its update
+// alone; updates that need a list longer than WAVE_LIST_MAX are then checked one after the other by the whole
+// workgroup.  No queue and no second launch: the many short updates no longer pay for a workgroup each.
+__global__ void __launch_bounds__(VAL_THREADS) validate_edges_packed_kernel(ValArgs A) {
+    __shared__ int64_t s_pos;
+    __shared__ int32_t s_long[VAL_THREADS / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t nops = A.n_ins + A.n_del;
+    const int64_t op0 = (int64_t)blockIdx.x * (VAL_THREADS / 64);
+    const int64_t op = op0 + w;
+    int32_t is_long = 0;
+    if (op < nops) {
+        const bool is_del = op >= A.n_ins;
+        const int64_t i = is_del ? op - A.n_ins : op;
+        const int32_t u = is_del ? A.del_src[i] : A.ins_src[i];
+        const int32_t v = is_del ? A.del_dst[i] : A.ins_dst[i];
+        if (u < 0 || u >= A.n || v < 0 || v >= A.n) {
+            if (lane == 0) A.err[0] = 1;
+        } else if (u == v) {
+            if (lane == 0) A.err[1] = 1;
+        } else {
+            if (lane == 0) note_key(A, u, v);
+            const int32_t du = A.out.deg[u], dv = A.in.deg[v];
+            if (is_del) {
+                if (du > WAVE_LIST_MAX || dv > WAVE_LIST_MAX) {
+                    is_long = 1;
+                } else {
+                    const int64_t po = wave_find_in_list(A.out, u, v, lane);
+                    const int64_t pi = wave_find_in_list(A.in, v, u, lane);
+                    if (po < 0 || pi < 0) { if (lane == 0) A.err[3] = 1; }
+                    else if (lane == 0) note_delete(A, i, u, v, po, pi);
+                }
+            } else {
+                if (min(du, dv) > WAVE_LIST_MAX) {
+                    is_long = 1;
+                } else {
+                    const int64_t p = du <= dv ? wave_find_in_list(A.out, u, v, lane) : wave_find_in_list(A.in, v, u, lane);
+                    if (p >= 0) { if (lane == 0) A.err[2] = 1; }
+                    else if (lane == 0) note_insert(A, u, v);
+                }
+            }
         }
     }
+    if (lane == 0) s_long[w] = is_long;
+    __syncthreads();
+    for (int t = 0; t < VAL_THREADS / 64; ++t)
+        if (s_long[t]) validate_by_workgroup(A, op0 + t, false, &s_pos);     // uniform over the workgroup
 }
 
 __global__ void validate_feats_kernel(int64_t n, int64_t n_feat, const int32_t* ids, int32_t* feat_index,
@@ -227,28 +315,32 @@ __device__ inline uint32_t block_excl_scan_u32(uint32_t v, uint32_t* total, uint
     return base + inc - v;
 }
 
-// One workgroup per (op, direction); only the first to stamp the key vertex works on its list.
-__global__ void __launch_bounds__(RB_THREADS)
-rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_t* ins_src, const int32_t* ins_dst,
-                     const int32_t* del_src, const int32_t* del_dst, int32_t* stamp0, int32_t* stamp1,
-                     int32_t epoch, int32_t* inscnt0, int32_t* inscnt1, int32_t* delcnt0, int32_t* delcnt1) {
-    __shared__ uint32_t wsum[RB_THREADS / 64];
-    __shared__ int32_t s_owner;
-    __shared__ int64_t s_newoff;
-    __shared__ int s_nh;
-    __shared__ int32_t s_hole[RB_FEW];
-    const int dir = blockIdx.y;
-    const int64_t op = blockIdx.x;
-    const bool is_del = op >= n_ins;
-    const int64_t i = is_del ? op - n_ins : op;
-    const int32_t k = dir == 0 ? (is_del ? del_src[i] : ins_src[i]) : (is_del ? del_dst[i] : ins_dst[i]);
-    int32_t* stamp = dir ? stamp1 : stamp0;
-    if (threadIdx.x == 0) s_owner = atomicMax(&stamp[k], epoch) < epoch;
-    __syncthreads();
-    if (!s_owner) return;
-    Adj a = dir ? in : out;
-    int32_t* inscnt = dir ? inscnt1 : inscnt0;
-    int32_t* delcnt = dir ? delcnt1 : delcnt0;
+struct RebuildArgs {
+    Adj out, in;
+    int64_t n_ins, n_del;
+    const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
+    int32_t *stamp0, *stamp1;
+    int32_t epoch;
+    int32_t *inscnt0, *inscnt1, *delcnt0, *delcnt1;
+};
+struct RebuildShared {
+    uint32_t wsum[RB_THREADS / 64];
+    int64_t newoff;
+    int nh;
+    int32_t hole[RB_FEW];
+};
+
+__device__ inline int32_t rebuild_key(const RebuildArgs& A, int64_t op, int dir) {
+    const bool is_del = op >= A.n_ins;
+    const int64_t i = is_del ? op - A.n_ins : op;
+    return dir == 0 ? (is_del ? A.del_src[i] : A.ins_src[i]) : (is_del ? A.del_dst[i] : A.ins_dst[i]);
+}
+
+// The whole workgroup drops the tombstones of vertex k's list in direction dir and makes room for its inserts.
+__device__ inline void rebuild_by_workgroup(const RebuildArgs& A, int32_t k, int dir, RebuildShared& sh) {
+    Adj a = dir ? A.in : A.out;
+    int32_t* inscnt = dir ? A.inscnt1 : A.inscnt0;
+    int32_t* delcnt = dir ? A.delcnt1 : A.delcnt0;
     const int64_t base = a.off[k];
     const int32_t deg0 = a.deg[k];
     const int32_t dc = delcnt[k], ic = inscnt[k];
@@ -257,7 +349,7 @@ rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_
         // A few tombstones in a possibly very long list: find them with a read-only pass, then move the live entries
         // of the last dc positions into the holes in front of them.  Holes and fillers are matched in ascending
         // position order, so the resulting list order does not depend on thread scheduling.
-        if (threadIdx.x == 0) s_nh = 0;
+        if (threadIdx.x == 0) sh.nh = 0;
         __syncthreads();
         for (int32_t p0 = threadIdx.x; p0 < deg0; p0 += RB_THREADS * 8) {      // eight independent loads, then the tests
             int32_t e8[8];
@@ -268,18 +360,18 @@ rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_
             }
 #pragma unroll
             for (int j = 0; j < 8; ++j)
-                if (e8[j] < 0) { const int at = atomicAdd(&s_nh, 1); if (at < RB_FEW) s_hole[at] = p0 + j * RB_THREADS; }
+                if (e8[j] < 0) { const int at = atomicAdd(&sh.nh, 1); if (at < RB_FEW) sh.hole[at] = p0 + j * RB_THREADS; }
         }
         __syncthreads();
-        const int nh = min(s_nh, RB_FEW);            // equals dc for a validated batch
+        const int nh = min(sh.nh, RB_FEW);            // equals dc for a validated batch
         const int32_t keep = deg0 - nh;
         int32_t my_hole = -1, my_rank = 0;
         if ((int)threadIdx.x < nh) {
-            my_hole = s_hole[threadIdx.x];
-            for (int j = 0; j < nh; ++j) my_rank += s_hole[j] < my_hole;
+            my_hole = sh.hole[threadIdx.x];
+            for (int j = 0; j < nh; ++j) my_rank += sh.hole[j] < my_hole;
         }
         __syncthreads();
-        if (my_hole >= 0) s_hole[my_rank] = my_hole;                // ascending
+        if (my_hole >= 0) sh.hole[my_rank] = my_hole;                // ascending
         __syncthreads();
         // thread t looks at tail position keep + t; a live entry there is the r-th filler, r = t - holes before it
         if ((int)threadIdx.x < nh) {
@@ -287,8 +379,8 @@ rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_
             const int32_t e = a.idx[base + p];
             if (e >= 0) {
                 int r = threadIdx.x;
-                for (int j = 0; j < nh; ++j) r -= (s_hole[j] >= keep && s_hole[j] < p);
-                const int32_t h = s_hole[r];                        // r-th hole overall; all of these lie below keep
+                for (int j = 0; j < nh; ++j) r -= (sh.hole[j] >= keep && sh.hole[j] < p);
+                const int32_t h = sh.hole[r];                        // r-th hole overall; all of these lie below keep
                 a.idx[base + h] = e;
                 if (a.wts) a.wts[base + h] = a.wts[base + p];
             }
@@ -308,7 +400,7 @@ rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_
                 cnt += e[j] >= 0;
             }
             uint32_t tot;
-            uint32_t ex = block_excl_scan_u32(cnt, &tot, wsum);   // barriers inside: all reads precede all writes
+            uint32_t ex = block_excl_scan_u32(cnt, &tot, sh.wsum);   // barriers inside: all reads precede all writes
             uint32_t q = outpos + ex;
 #pragma unroll
             for (int j = 0; j < RB_EPT; ++j) {
@@ -326,9 +418,9 @@ rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_
     if (need > a.cap[k]) {
         const int32_t nc = new_cap_for(need);
         __syncthreads();
-        if (threadIdx.x == 0) s_newoff = (int64_t)atomicAdd((unsigned long long*)a.head, (unsigned long long)nc);
+        if (threadIdx.x == 0) sh.newoff = (int64_t)atomicAdd((unsigned long long*)a.head, (unsigned long long)nc);
         __syncthreads();
-        const int64_t no = s_newoff;
+        const int64_t no = sh.newoff;
         for (int32_t p = threadIdx.x; p < live; p += RB_THREADS) {
             a.idx[no + p] = a.idx[base + p];
             if (a.wts) a.wts[no + p] = a.wts[base + p];
@@ -336,6 +428,92 @@ rebuild_lists_kernel(Adj out, Adj in, int64_t n_ins, int64_t n_del, const int32_
         if (threadIdx.x == 0) { a.off[k] = no; a.cap[k] = nc; }
     }
     if (threadIdx.x == 0) { a.deg[k] = live; inscnt[k] = 0; delcnt[k] = 0; }
+    __syncthreads();                                   // the shared scratch may be reused for the next list
+}
+
+// One workgroup per (op, direction); only the first to stamp the key vertex works on its list.
+__global__ void __launch_bounds__(RB_THREADS) rebuild_lists_kernel(RebuildArgs A) {
+    __shared__ RebuildShared sh;
+    __shared__ int32_t s_owner;
+    const int dir = blockIdx.y;
+    const int32_t k = rebuild_key(A, blockIdx.x, dir);
+    int32_t* stamp = dir ? A.stamp1 : A.stamp0;
+    if (threadIdx.x == 0) s_owner = atomicMax(&stamp[k], A.epoch) < A.epoch;
+    __syncthreads();
+    if (!s_owner) return;
+    rebuild_by_workgroup(A, k, dir, sh);
+}
+
+// Large batches: a workgroup takes 16 (op, direction) items, one per wave.  The wave that stamps a key vertex first
+// owns its list; a list of up to WAVE_LIST_MAX entries is squeezed (in list order) and, if needed, moved by that wave
+// alone, the longer ones are then rebuilt one after the other by the whole workgroup.
+__global__ void __launch_bounds__(RB_THREADS) rebuild_lists_packed_kernel(RebuildArgs A) {
+    __shared__ RebuildShared sh;
+    __shared__ int32_t s_long[RB_THREADS / 64];       // key vertex + 1, negative for the in-direction; 0: nothing left
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t nops = A.n_ins + A.n_del;
+    const int64_t item = (int64_t)blockIdx.x * (RB_THREADS / 64) + w;
+    int32_t left = 0;
+    if (item < 2 * nops) {
+        const int dir = item >= nops;
+        const int32_t k = rebuild_key(A, dir ? item - nops : item, dir);
+        int32_t* stamp = dir ? A.stamp1 : A.stamp0;
+        int32_t owner = 0;
+        if (lane == 0) owner = atomicMax(&stamp[k], A.epoch) < A.epoch;
+        owner = __shfl(owner, 0, 64);
+        if (owner) {
+            Adj a = dir ? A.in : A.out;
+            const int32_t deg0 = a.deg[k];
+            if (deg0 > WAVE_LIST_MAX) {
+                left = dir ? -(k + 1) : k + 1;
+            } else {
+                int32_t* inscnt = dir ? A.inscnt1 : A.inscnt0;
+                int32_t* delcnt = dir ? A.delcnt1 : A.delcnt0;
+                const int64_t base = a.off[k];
+                const int32_t dc = delcnt[k], ic = inscnt[k];
+                int32_t live = deg0;
+                if (dc > 0) {
+                    // in-place squeeze: the entries of a trip are all read before any of them is written, and they
+                    // are written at or below the positions just read
+                    const unsigned long long below = (1ULL << lane) - 1ULL;
+                    int32_t outpos = 0;
+                    for (int32_t start = 0; start < deg0; start += 64) {
+                        const int32_t p = start + lane;
+                        const int32_t e = p < deg0 ? a.idx[base + p] : -1;
+                        const float wt = (p < deg0 && a.wts) ? a.wts[base + p] : 0.f;
+                        const unsigned long long m = __ballot(e >= 0);
+                        if (e >= 0) {
+                            const int32_t q = outpos + __popcll(m & below);
+                            a.idx[base + q] = e;
+                            if (a.wts) a.wts[base + q] = wt;
+                        }
+                        outpos += __popcll(m);
+                    }
+                    live = outpos;
+                }
+                const int32_t need = live + ic;
+                if (need > a.cap[k]) {
+                    const int32_t nc = new_cap_for(need);
+                    long long no = 0;
+                    if (lane == 0) no = (long long)atomicAdd((unsigned long long*)a.head, (unsigned long long)nc);
+                    no = __shfl(no, 0, 64);
+                    for (int32_t p = lane; p < live; p += 64) {
+                        a.idx[no + p] = a.idx[base + p];
+                        if (a.wts) a.wts[no + p] = a.wts[base + p];
+                    }
+                    if (lane == 0) { a.off[k] = no; a.cap[k] = nc; }
+                }
+                if (lane == 0) { a.deg[k] = live; inscnt[k] = 0; delcnt[k] = 0; }
+            }
+        }
+    }
+    if (lane == 0) s_long[w] = left;
+    __syncthreads();
+    for (int t = 0; t < RB_THREADS / 64; ++t) {
+        const int32_t code = s_long[t];                               // uniform over the workgroup
+        if (code > 0) rebuild_by_workgroup(A, code - 1, 0, sh);
+        else if (code < 0) rebuild_by_workgroup(A, -code - 1, 1, sh);
+    }
 }
 
 __global__ void append_kernel(Adj out, Adj in, int64_t n_ins, const int32_t* ins_src, const int32_t* ins_dst,
@@ -455,9 +633,15 @@ nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& 
         LAUNCH_CHECK();
     }
     if (nops == 0) return NRT_OK;
-    validate_edges_kernel<<<(unsigned)nops, VAL_THREADS, 0, s>>>(
-        g->out, g->in, g->n, b->n_ins, b->n_del, b->ins_src, b->ins_dst, b->del_src, b->del_dst, sc.hash_keys,
-        sc.hash_cap, sc.pos_out, sc.pos_in, sc.del_w, sc.err, g->inscnt[0], g->inscnt[1], g->delcnt[0], g->delcnt[1]);
+    ValArgs va;
+    va.out = g->out; va.in = g->in;
+    va.n = g->n; va.n_ins = b->n_ins; va.n_del = b->n_del;
+    va.ins_src = b->ins_src; va.ins_dst = b->ins_dst; va.del_src = b->del_src; va.del_dst = b->del_dst;
+    va.hash = sc.hash_keys; va.hash_cap = sc.hash_cap;
+    va.pos_out = sc.pos_out; va.pos_in = sc.pos_in; va.del_w = sc.del_w; va.err = sc.err;
+    va.inscnt0 = g->inscnt[0]; va.inscnt1 = g->inscnt[1]; va.delcnt0 = g->delcnt[0]; va.delcnt1 = g->delcnt[1];
+    if (nops > PACKED_MIN_OPS) validate_edges_packed_kernel<<<(unsigned)cdiv(nops, VAL_THREADS / 64), VAL_THREADS, 0, s>>>(va);
+    else validate_edges_kernel<<<(unsigned)nops, VAL_THREADS, 0, s>>>(va);
     LAUNCH_CHECK();
     plan_growth_kernel<<<(int)cdiv(2 * nops, 256), 256, 0, s>>>(
         g->out, g->in, g->n, b->n_ins, b->n_del, b->ins_src, b->ins_dst, b->del_src, b->del_dst, g->stamp[0],
@@ -485,10 +669,18 @@ nrt_status graph_mutate(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipS
         tombstone_kernel<<<(int)cdiv(b->n_del, 256), 256, 0, s>>>(g->out, g->in, b->n_del, sc.pos_out, sc.pos_in);
         LAUNCH_CHECK();
     }
-    dim3 grid((unsigned)nops, 2, 1);
-    rebuild_lists_kernel<<<grid, RB_THREADS, 0, s>>>(g->out, g->in, b->n_ins, b->n_del, b->ins_src, b->ins_dst,
-                                                     b->del_src, b->del_dst, g->stamp[0], g->stamp[1], g->epoch + 1,
-                                                     g->inscnt[0], g->inscnt[1], g->delcnt[0], g->delcnt[1]);
+    RebuildArgs ra;
+    ra.out = g->out; ra.in = g->in;
+    ra.n_ins = b->n_ins; ra.n_del = b->n_del;
+    ra.ins_src = b->ins_src; ra.ins_dst = b->ins_dst; ra.del_src = b->del_src; ra.del_dst = b->del_dst;
+    ra.stamp0 = g->stamp[0]; ra.stamp1 = g->stamp[1]; ra.epoch = g->epoch + 1;
+    ra.inscnt0 = g->inscnt[0]; ra.inscnt1 = g->inscnt[1]; ra.delcnt0 = g->delcnt[0]; ra.delcnt1 = g->delcnt[1];
+    if (nops > PACKED_MIN_OPS) {
+        rebuild_lists_packed_kernel<<<(unsigned)cdiv(2 * nops, RB_THREADS / 64), RB_THREADS, 0, s>>>(ra);
+    } else {
+        dim3 grid((unsigned)nops, 2, 1);
+        rebuild_lists_kernel<<<grid, RB_THREADS, 0, s>>>(ra);
+    }
     LAUNCH_CHECK();
     if (b->n_ins > 0) {
         append_kernel<<<(int)cdiv(b->n_ins, 256), 256, 0, s>>>(g->out, g->in, b->n_ins, b->ins_src, b->ins_dst, b->ins_w);

@@ -441,6 +441,70 @@ def test_heavy_churn_on_one_vertex(S, oracle):
         assert_parity(wl.GIN, ses.layer(2).cpu().numpy(), ref[-1], ("churn", k))
 
 
+@pytest.mark.parametrize("kind", [wl.GCN, wl.GIN])
+def test_large_batches_pack_updates_per_wave(S, oracle, kind):
+    """Batches of more than 4096 edge updates are validated and applied 16 updates per workgroup: short lists by one
+    wave each, lists of more than 1024 entries by the whole workgroup.  The exported graph (with weights), the
+    affected sets and the embeddings follow the oracle; a bad update hidden in such a batch is still refused."""
+    from paper_2603_20622_amd import binding as nb
+    n, src, dst, w, x, spec, params, stream = small_case(kind, seed=21, n=20000, e=300000, dims=[16, 32, 8])
+    assert np.bincount(dst, minlength=n).max() > 2048 and np.bincount(src, minlength=n).max() > 2048
+    ses = S.Session(spec, params, n, src, dst, w, x, e_capacity=330000, max_batch_edges=8192)
+    cur = (src, dst, w, x)
+    for k, (n_ins, n_del) in enumerate([(3000, 3000), (6000, 500), (200, 5000)]):   # the second outgrows list slack
+        b = stream.next_batch(n_ins, n_del, 20)
+        na = ses.apply(b)
+        cur = oracle.apply_batch(n, *cur, b)
+        key, ww = _export_edges(ses, n)
+        want = cur[0].astype(np.int64) * n + cur[1]
+        order = np.argsort(want)
+        assert np.array_equal(key, want[order]), k
+        if ww is not None:
+            assert np.array_equal(ww, cur[2][order]), k
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1]), k
+        ref = oracle.forward(spec, params, n, *cur)
+        fresh = S.Session(spec, params, n, *cur) if kind == wl.GIN else None
+        assert_parity(kind, ses.layer(2).cpu().numpy(), ref[-1], ("packed", k),
+                      None if fresh is None else fresh.layer(2).cpu().numpy())
+    # one bad update among thousands: an absent edge deleted, a present edge inserted, a repeated entry; the same on
+    # lists that only the whole workgroup searches
+    import copy
+    base = ses.layer(2).cpu().numpy().copy()
+    hub_in = int(np.argmax(np.bincount(cur[1], minlength=n)))
+    by_out = np.argsort(np.bincount(cur[0], minlength=n))
+    hub_out = int(by_out[-1] if by_out[-1] != hub_in else by_out[-2])
+    assert np.count_nonzero(cur[0] == hub_out) > 1024 and np.count_nonzero(cur[1] == hub_in) > 1024
+    on_hub = np.nonzero(cur[1] == hub_in)[0]
+    nbrs = set(cur[0][on_hub].tolist())
+    not_nbr = next(v for v in range(n) if v != hub_in and v not in nbrs)
+    good = stream.next_batch(2500, 2500, 0)
+    for what in ("absent", "present", "repeat", "absent_on_hub", "hub_pair"):
+        b = copy.deepcopy(good)
+        if what == "absent":
+            b.del_src[1234], b.del_dst[1234] = b.ins_src[0], b.ins_dst[0]       # not in the graph yet
+        elif what == "present":
+            b.ins_src[77], b.ins_dst[77] = cur[0][5], cur[1][5]
+        elif what == "repeat":
+            b.ins_src[2000], b.ins_dst[2000] = b.ins_src[10], b.ins_dst[10]
+        elif what == "absent_on_hub":
+            b.del_src[9], b.del_dst[9] = not_nbr, hub_in
+        elif hub_out in nbrs:
+            b.ins_src[9], b.ins_dst[9] = hub_out, hub_in                        # present, both lists long
+        else:
+            b.del_src[9], b.del_dst[9] = hub_out, hub_in                        # absent, both lists long
+        with pytest.raises(nb.NrtError) as ei:
+            ses.apply(b)
+        assert ei.value.status == nb.NRT_ERR_BAD_BATCH, what
+        assert np.array_equal(ses.layer(2).cpu().numpy(), base), what
+        key2, _ = _export_edges(ses, n)
+        assert np.array_equal(key2, key), what
+    ses.apply(good)                                                             # and the handle still works
+    cur = oracle.apply_batch(n, *cur, good)
+    key3, _ = _export_edges(ses, n)
+    assert np.array_equal(key3, np.sort(cur[0].astype(np.int64) * n + cur[1]))
+
+
 def test_widest_rows(S, oracle):
     """1024-wide aggregates (four 16-byte loads per lane in the gather, K = 1024 in the update)."""
     n, e = 800, 6000
