@@ -114,7 +114,7 @@ def main():
             d_agg = dims[l + 1] if cfg.spec.kind == wl.GAT else d_in
             row_fetches = ls.n_src if ls.n_src * 4.0 * d_agg <= INFINITY_CACHE_BYTES else ls.n_pairs
             gbytes = ls.n_pairs * 8.0 + row_fetches * 4.0 * d_agg + ls.n_affected * 8.0 * d_agg if ls.n_src else 0.0
-            kin = (2 if cfg.spec.kind == wl.SAGE_MEAN else 1) * d_in
+            kin = (2 if cfg.spec.kind in (wl.SAGE_MEAN, wl.COMMNET) else 1) * d_in
             flop = 2.0 * ls.n_affected * kin * dims[l + 1]
             if cfg.spec.kind == wl.GIN:
                 flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]

@@ -230,9 +230,12 @@ extern "C" nrt_status nrt_graph_export_csc(const nrt_graph* g, int64_t* indptr, 
 }
 
 // ------------------------------------------------------------------ cache layout
+// models whose update runs on the concatenation [h_v || aggregate] (Table II rows PinSAGE and CommNet)
+static inline bool concat_self(int kind) { return kind == NRT_SAGE_MEAN || kind == NRT_COMMNET; }
+
 static nrt_status check_desc(const nrt_model_desc* d) {
     REQUIRE(d, "model desc is null");
-    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_GAT, "unknown model kind");
+    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_COMMNET, "unknown model kind");
     REQUIRE(d->n_layers >= 1 && d->n_layers <= NRT_MAX_LAYERS, "n_layers out of range");
     for (int l = 0; l <= d->n_layers; ++l) {
         if (d->dims[l] <= 0 || d->dims[l] % 4 || d->dims[l] > 1024) {
@@ -287,7 +290,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->AS_old = gat ? b.take<float>(n * c->heads) : nullptr;
     c->is_gat = gat;
     for (int l = 0; l < c->L; ++l) {
-        const int kin = (c->kind == NRT_SAGE_MEAN ? 2 : 1) * c->dims[l];
+        const int kin = (concat_self(c->kind) ? 2 : 1) * c->dims[l];
         c->Wt[l][0] = b.take<float>((size_t)kin * c->dims[l + 1]);
         c->bias[l][0] = b.take<float>(c->dims[l + 1]);
         if (c->kind == NRT_GIN) {
@@ -411,7 +414,7 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
         a.sd = c->SD[l];
         a.dd_bitmap = c->bm_ddst;
         a.dd_slot = c->slot_dd;
-        a.guard = c->kind == NRT_GIN;            // un-normalised sums: a fold can cancel most of a row's magnitude
+        a.guard = c->kind == NRT_GIN || c->kind == NRT_COMMNET;   // un-normalised sums: a fold can cancel most of a row's magnitude
         a.Pfull = c->H[l - 1];
         a.full_scale_gcn = c->kind == NRT_GCN;
         a.sparse_ok = (sparse_hint == 2 && a.D > 256) ? 1 : sparse_hint;    // rows wider than 256 floats: pipelined kernel only
@@ -453,7 +456,7 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
     a.ldp = c->dims[l - 1];
     a.N = c->dims[l];
     float* dp = (incremental && !last) ? c->DP[cur] : nullptr;
-    if (c->kind == NRT_GCN || c->kind == NRT_SAGE_MEAN) {
+    if (c->kind == NRT_GCN || concat_self(c->kind)) {
         if (c->kind == NRT_GCN) {
             a.a_mode = A_SCALE_GCN;
             a.P0 = c->S[l];
@@ -463,6 +466,7 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
             a.P0 = c->H[l - 1];
             a.P1 = c->S[l];
             a.K = 2 * c->dims[l - 1];
+            if (c->kind == NRT_COMMNET) a.indeg = nullptr;      // the sum itself, not the mean
         }
         a.Wt = c->Wt[l - 1][0];
         a.bias = c->bias[l - 1][0];
@@ -645,7 +649,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         NRT_TRY(k_fill_u32((uint32_t*)c->flags, (n + 64) / 4, 0, s));
         NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
         for (int l = 0; l < c->L; ++l) {
-            const int kin = (c->kind == NRT_SAGE_MEAN ? 2 : 1) * c->dims[l];
+            const int kin = (concat_self(c->kind) ? 2 : 1) * c->dims[l];
             NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
             if (d->b[l][0]) NRT_TRY(k_copy_f32(c->bias[l][0], d->b[l][0], c->dims[l + 1], s));
             else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][0], c->dims[l + 1], 0, s));

@@ -4,7 +4,8 @@
 // where row m of A is formed on the fly from the cached rows of vertex rows[m]:
 //   A_PLAIN        P0[v]
 //   A_SCALE_GCN    P0[v] / sqrt(indeg(v)+1)                (msg_cbn of the GCN row applied to the cached sum)
-//   A_CONCAT_MEAN  [ P0[v] || P1[v] / indeg(v) ]           (GraphSAGE: self row, mean = cached sum / count)
+//   A_CONCAT_MEAN  [ P0[v] || P1[v] / indeg(v) ]           (GraphSAGE: self row, mean = cached sum / count;
+//                                                           CommNet: indeg == nullptr, the cached sum itself)
 //   A_AXPY         c * P0[v] + P1[v]                       (GIN: (1+eps) x_v + cached weighted sum)
 // The epilogue is the cache write-back: it stores the new row into h^l[v] and, for the next layer, the
 // change of the source payload dp = y_new*cn - y_old*co (cn = co = 1 except for GCN, where the payload is
@@ -84,7 +85,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
         av[p] = aok[p] ? ((g.rows && !g.a_is_compact) ? (int64_t)g.rows[m] : m) : 0;
         asc[p] = 1.0f;
         if (aok[p] && AMODE == A_SCALE_GCN) asc[p] = gcn_scale(g.indeg[av[p]]);
-        if (aok[p] && AMODE == A_CONCAT_MEAN) {
+        if (aok[p] && AMODE == A_CONCAT_MEAN && g.indeg) {          // no degree vector: the sum is used as it is
             const int32_t d = g.indeg[av[p]];
             asc[p] = d > 0 ? 1.0f / (float)d : 0.0f;
         }

@@ -3,8 +3,8 @@
 // The paper keeps a packed-memory-array CSR in host memory (Section IV "Packed-memory-array-based CSR
 // structure"); here both directions live in HBM.  Each vertex owns a segment [off, off+cap) of a pool, the
 // first deg entries are live.  A batch (a) turns deleted entries into tombstones, (b) lets one workgroup per
-// touched vertex squeeze its list and, if the pending inserts do not fit, move the list to a fresh, larger
-// segment at the pool head, (c) appends the inserted entries.
+// touched vertex (one wave for the short lists of a large batch) squeeze its list and, if the pending inserts do
+// not fit, move the list to a fresh, larger segment at the pool head, (c) appends the inserted entries.
 #include "common.h"
 
 namespace {

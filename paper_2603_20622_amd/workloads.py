@@ -18,8 +18,8 @@ from typing import Dict, List, Optional
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT = 1, 2, 3, 4
-KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat"}
+GCN, SAGE_MEAN, GIN, GAT, COMMNET = 1, 2, 3, 4, 5
+KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet"}
 
 
 @dataclass
@@ -136,7 +136,7 @@ def make_params(spec: ModelSpec, seed: int = 0, bias: bool = False) -> Params:
     p = Params()
     for l in range(1, spec.n_layers + 1):
         din, dout = spec.dims[l - 1], spec.dims[l]
-        kin = 2 * din if spec.kind == SAGE_MEAN else din
+        kin = 2 * din if spec.kind in (SAGE_MEAN, COMMNET) else din
         Ws = [_glorot(rng, kin, dout, (kin, dout))]
         if spec.kind == GIN:
             Ws.append(_glorot(rng, dout, dout, (dout, dout)))

@@ -1,7 +1,7 @@
 """Pins for the CPU oracle: things other than the oracle itself that fix its values.
 
   * brute force: a per-vertex recursive evaluation of the message-aggregate-update layer (Eq. 1)
-    from hand-written adjacency lists, in Python floats, for all four models;
+    from hand-written adjacency lists, in Python floats, for all five models;
   * the dense-matrix closed forms the models reduce to (normalised adjacency products);
   * closed forms on special graphs / parameters (cycle, constant features, zero attention,
     two-term softmax, star hub);
@@ -55,6 +55,13 @@ def brute_embedding(spec, params, in_nbrs, x, v, l):
             for k in range(d):
                 m[k] += hu[u][k] / len(in_nbrs[v])
         y = _lin(hv + m, W[0], b[0])
+        act = "relu"
+    elif spec.kind == wl.COMMNET:
+        tot = [0.0] * d
+        for u, _ in in_nbrs[v]:
+            for k in range(d):
+                tot[k] += hu[u][k]
+        y = _lin(hv + tot, W[0], b[0])
         act = "relu"
     elif spec.kind == wl.GIN:
         t = [(1.0 + spec.gin_eps) * hv[k] for k in range(d)]
@@ -120,7 +127,7 @@ def _in_lists(n, src, dst, w):
     return lists
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET])
 @pytest.mark.parametrize("L", [1, 2, 3])
 def test_forward_matches_brute_force(oracle, kind, L):
     n, src, dst, w, x, spec, params = _tiny(kind, L, seed=3 + L)
@@ -189,6 +196,60 @@ def test_gin_is_weighted_adjacency_product(oracle):
             h = np.maximum(h, 0)
     outs = oracle.forward(spec, params, n, src, dst, w, x)
     np.testing.assert_allclose(outs[1], h, rtol=1e-11, atol=1e-12)
+
+
+def test_commnet_is_adjacency_product(oracle):
+    """Table II CommNet row as matrices: H' = act(H W_1 + A H W_2) with the plain 0/1 adjacency."""
+    n, e = 45, 280
+    src, dst, _ = wl.rmat_graph(n, e, seed=12)
+    spec = wl.ModelSpec(wl.COMMNET, [4, 5, 3])
+    params = wl.make_params(spec, 8, bias=True)
+    x = wl.features(n, 4, 9).astype(np.float64)
+    A = _dense_adj(n, src, dst)
+    f = lambda a: a.astype(np.float64)
+    W0, W1 = f(params.W[0][0]), f(params.W[1][0])
+    h1 = np.maximum(x @ W0[:4] + A @ x @ W0[4:] + f(params.b[0][0]), 0)
+    h2 = h1 @ W1[:5] + A @ h1 @ W1[5:] + f(params.b[1][0])
+    outs = oracle.forward(spec, params, n, src, dst, None, x)
+    np.testing.assert_allclose(outs[0], h1, rtol=1e-11, atol=1e-12)
+    np.testing.assert_allclose(outs[1], h2, rtol=1e-11, atol=1e-12)
+
+
+def test_commnet_reduces_to_sage_and_gin_on_special_cases(oracle):
+    """In-regular graph of degree k: the sum is k times the mean, so CommNet with [W_1; W_2] equals GraphSAGE-mean
+    with [W_1; k W_2].  With W_1 = W_2 = W a layer is (x_v + sum_u x_u) W: the first product of a GIN layer with
+    eps = 0 and unit edge weights."""
+    n, k = 12, 4                                     # a power of two: scaling the fp32 weights by k is exact
+    src = np.array([(v + j + 1) % n for v in range(n) for j in range(k)], np.int32)     # v hears v+1..v+k
+    dst = np.array([v for v in range(n) for _ in range(k)], np.int32)
+    x = wl.features(n, 4, 13)
+    com = wl.ModelSpec(wl.COMMNET, [4, 6, 2])
+    params = wl.make_params(com, 14, bias=True)
+    sage = wl.ModelSpec(wl.SAGE_MEAN, [4, 6, 2])
+    scaled = wl.make_params(sage, 14, bias=True)
+    for l, d in enumerate([4, 6]):
+        scaled.W[l][0] = params.W[l][0].copy()
+        scaled.W[l][0][d:] *= k
+        scaled.b[l][0] = params.b[l][0].copy()
+    got = oracle.forward(com, params, n, src, dst, None, x)
+    want = oracle.forward(sage, scaled, n, src, dst, None, x)
+    np.testing.assert_allclose(got[1], want[1], rtol=1e-12, atol=1e-13)
+
+    one = wl.ModelSpec(wl.COMMNET, [4, 3])
+    p1 = wl.make_params(one, 15)
+    p1.W[0][0][4:] = p1.W[0][0][:4]
+    out = oracle.forward(one, p1, n, src, dst, None, x)[0]
+    t = x.astype(np.float64) + _dense_adj(n, src, dst) @ x.astype(np.float64)
+    np.testing.assert_allclose(out, t @ p1.W[0][0][:4].astype(np.float64), rtol=1e-12, atol=1e-13)
+
+
+def test_commnet_single_edge_by_hand(oracle):
+    """Edge 0 -> 1, scalar feature, W_1 = 2, W_2 = -3:  h_0 = 2 x_0,  h_1 = 2 x_1 - 3 x_0."""
+    spec = wl.ModelSpec(wl.COMMNET, [1, 1])
+    params = wl.Params(W=[[np.array([[2.0], [-3.0]], np.float32)]], b=[[None]], att_src=[None], att_dst=[None])
+    x = np.array([[3.0], [5.0]], np.float32)
+    out = oracle.forward(spec, params, 2, np.array([0], np.int32), np.array([1], np.int32), None, x)[0]
+    np.testing.assert_allclose(out[:, 0], [6.0, 10.0 - 9.0], rtol=1e-14)
 
 
 # ------------------------------------------------------------------ closed forms on special inputs
@@ -351,7 +412,7 @@ def test_affected_sets_hand_enumerated(oracle):
         assert [a.tolist() for a in got] == [[3, 4], [3, 4]]
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET])
 def test_affected_sets_match_reachability_powers(oracle, kind):
     n, e = 70, 260
     src, dst, sampler = wl.rmat_graph(n, e, seed=12)
@@ -375,7 +436,7 @@ def test_affected_sets_match_reachability_powers(oracle, kind):
 
 
 # ------------------------------------------------------------------ invariants
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET])
 def test_batch_invariants(oracle, kind):
     n, e = 200, 1500
     src, dst, sampler = wl.rmat_graph(n, e, seed=13)
