@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
+    ap.add_argument("--model", choices=["commnet", "pinsage"], default=None,
+                    help="run another Table II model on the chosen config's graph, widths and batches (not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -50,6 +52,10 @@ def main():
         sys.exit(3)
 
     cfg = wl.config(args.config, args.scale)
+    if args.model:
+        kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE}[args.model]
+        cfg.spec = wl.ModelSpec(kind, list(cfg.spec.dims[:1]) + list(cfg.spec.dims[1:]), weighted=kind == wl.PINSAGE)
+        cfg.name = cfg.name + "_as_" + args.model
     if args.batch_edges:
         frac = cfg.n_ins / max(1, cfg.n_ins + cfg.n_del)
         cfg.n_ins = int(round(args.batch_edges * frac))
@@ -118,6 +124,8 @@ def main():
             flop = 2.0 * ls.n_affected * kin * dims[l + 1]
             if cfg.spec.kind == wl.GIN:
                 flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]
+            if cfg.spec.kind == wl.PINSAGE:                      # message transform of the changed rows (timed under "items")
+                flop += 2.0 * ls.n_src * d_in * d_in
             upd_ms = ls.ms_update
             if cfg.spec.kind == wl.GAT:
                 flop = 2.0 * ls.n_src * d_in * dims[l + 1]       # z = x W on the rows whose input changed,

@@ -51,7 +51,7 @@ typedef enum {
     NRT_ERR_UNSUPPORTED = 6  /* model shape outside what the kernels cover                            */
 } nrt_status;
 
-typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5 } nrt_model_kind;
+typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6 } nrt_model_kind;
 
 typedef struct nrt_graph nrt_graph;
 typedef struct nrt_cache nrt_cache;
@@ -70,6 +70,9 @@ typedef struct nrt_cache nrt_cache;
  *                 N(v) U {v}, h_v = act( sum_u alpha_uv z_u + b[l][0] )
  *   NRT_COMMNET   (Table II row CommNet)  a_v = sum_{u in N(v)} x_u (no normalisation);
  *                 h_v = act( [x_v || a_v] W[l][0] + b[l][0] ),  W is [2 d_{l-1}][d_l]: rows W_1 (self), then W_2
+ *   NRT_PINSAGE   (Table II row PinSAGE)  m_u = ReLU(x_u W[l][1] + b[l][1]),  W[l][1] is [d_{l-1}][d_{l-1}];
+ *                 a_v = (sum_{u in N(v)} w_uv m_u) / |N(v)|  (w_uv = 1 on an unweighted graph, a_v = 0 if N(v) is empty);
+ *                 h_v = act( [x_v || a_v] W[l][0] + b[l][0] ),  W[l][0] is [2 d_{l-1}][d_l]
  * W, b, att_* are device pointers, row-major [in][out] / [heads][head_dim]; b entries may be NULL (zero).
  * They are copied at nrt_cache_init.
  */

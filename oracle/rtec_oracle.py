@@ -25,13 +25,16 @@ Readings taken where the paper is silent or garbled (the GPU path takes the same
     neighbor", Section III-C related work), so every destination of an updated edge is a
     source of change at every layer.
   * Every configured model has a self term (GCN/GAT self-loop, SAGE concat-self, GIN
-    (1+eps) x_v, CommNet W_1 h_v), so a vertex affected at layer l-1 is affected at layer l.
+    (1+eps) x_v, CommNet W_1 h_v, PinSAGE concat-self), so a vertex affected at layer l-1 is affected at layer l.
   * Hidden layers are activated (Table II "update" column), the last layer is linear.
   * GraphSAGE-mean: y_v = [x_v || mean_{u in N(v)} x_u] W, the mean of an empty neighbourhood is 0.
   * GIN: t_v = (1+eps) x_v + sum_u w_uv x_u;  y_v = ReLU(t_v Wa + ba) Wb + bb.
   * CommNet: y_v = x_v W_1 + (sum_{u in N(v)} x_u) W_2 as in its Table II row; hidden layers are activated
     like those of the other models (the row prints no activation; without one the layers would collapse
     into a single linear map).
+  * PinSAGE: the importance alpha_uv of its Table II row is the edge weight (1 on an unweighted graph), sigma is
+    ReLU, Q is square (the message keeps the width of h), and the mean divides by the neighbour count as the
+    row's count context says (not by the sum of the weights).
   * GAT: z = x W viewed [heads][head_dim]; e_uv = LeakyReLU(a_dst . z_v + a_src . z_u)
     (destination first, as in Eq. 3); softmax over N(v) U {v}; heads concatenated; ELU on
     hidden layers.
@@ -46,7 +49,7 @@ from typing import List, Optional, Sequence
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET = 1, 2, 3, 4, 5
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE = 1, 2, 3, 4, 5, 6
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librtec_oracle.so")
@@ -185,6 +188,15 @@ def layer(spec, params, l: int, n: int, src, dst, w, x: np.ndarray) -> np.ndarra
         # Table II CommNet row: message 1 * h_u, plain sum, update W_1 h_v + W_2 a_v (W[0] holds W_1 above W_2).
         s = in_sum(n, src, dst, None, x)
         y = x @ W[0][: x.shape[1]] + s @ W[0][x.shape[1]:]
+        if b[0] is not None:
+            y = y + b[0]
+    elif spec.kind == PINSAGE:
+        # Table II PinSAGE row: message alpha_uv * sigma(Q h_u + q), count context, mean, update on [x_v || a_v].
+        m = _act_relu(x @ W[1] + (0.0 if b[1] is None else b[1]))
+        cnt = np.bincount(dst, minlength=n).astype(np.float64)
+        s = in_sum(n, src, dst, _f64(w), m)
+        mean = np.where(cnt[:, None] > 0, s / np.maximum(cnt, 1.0)[:, None], 0.0)
+        y = np.concatenate([x, mean], axis=1) @ W[0]
         if b[0] is not None:
             y = y + b[0]
     elif spec.kind == GIN:

@@ -39,6 +39,7 @@ struct nrt_cache {
     int maxd;
     float* H[NRT_MAX_LAYERS + 1];
     float* S[NRT_MAX_LAYERS + 1];
+    float* MP[NRT_MAX_LAYERS + 1];      // PinSAGE: message payload of layer l's rows, ReLU(h^l Q + q) (null otherwise)
     float* Wt[NRT_MAX_LAYERS][2];
     float* bias[NRT_MAX_LAYERS][2];
     int32_t* indeg_old;
@@ -231,11 +232,14 @@ extern "C" nrt_status nrt_graph_export_csc(const nrt_graph* g, int64_t* indptr, 
 
 // ------------------------------------------------------------------ cache layout
 // models whose update runs on the concatenation [h_v || aggregate] (Table II rows PinSAGE and CommNet)
-static inline bool concat_self(int kind) { return kind == NRT_SAGE_MEAN || kind == NRT_COMMNET; }
+static inline bool concat_self(int kind) { return kind == NRT_SAGE_MEAN || kind == NRT_COMMNET || kind == NRT_PINSAGE; }
+
+// models whose messages carry the edge weight
+static inline bool weighted_messages(int kind) { return kind == NRT_GIN || kind == NRT_PINSAGE; }
 
 static nrt_status check_desc(const nrt_model_desc* d) {
     REQUIRE(d, "model desc is null");
-    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_COMMNET, "unknown model kind");
+    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_PINSAGE, "unknown model kind");
     REQUIRE(d->n_layers >= 1 && d->n_layers <= NRT_MAX_LAYERS, "n_layers out of range");
     for (int l = 0; l <= d->n_layers; ++l) {
         if (d->dims[l] <= 0 || d->dims[l] % 4 || d->dims[l] > 1024) {
@@ -265,6 +269,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     for (int l = 0; l <= c->L; ++l) maxd = c->dims[l] > maxd ? c->dims[l] : maxd;
     c->maxd = maxd;
     for (int l = 0; l <= c->L; ++l) c->H[l] = b.take<float>(n * c->dims[l]);
+    for (int l = 0; l <= c->L; ++l) c->MP[l] = (c->kind == NRT_PINSAGE && l < c->L) ? b.take<float>(n * c->dims[l]) : nullptr;
     c->S[0] = nullptr;
     const bool gat = c->kind == NRT_GAT;
     for (int l = 1; l <= c->L; ++l) {
@@ -296,6 +301,9 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         if (c->kind == NRT_GIN) {
             c->Wt[l][1] = b.take<float>((size_t)c->dims[l + 1] * c->dims[l + 1]);
             c->bias[l][1] = b.take<float>(c->dims[l + 1]);
+        } else if (c->kind == NRT_PINSAGE) {
+            c->Wt[l][1] = b.take<float>((size_t)c->dims[l] * c->dims[l]);
+            c->bias[l][1] = b.take<float>(c->dims[l]);
         } else {
             c->Wt[l][1] = nullptr;
             c->bias[l][1] = nullptr;
@@ -383,6 +391,33 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
     return NRT_OK;
 }
 
+// what the in-neighbours of layer l+1 aggregate: h^l itself, or its transform for PinSAGE
+static inline const float* payload_rows(const nrt_cache* c, int l) { return c->kind == NRT_PINSAGE ? c->MP[l] : c->H[l]; }
+
+// PinSAGE (Table II): the message of a vertex, ReLU(h^l Q + q), on the listed rows (null: all n rows); with `dp` the
+// compact rows new - old that the gather of layer l+1 folds
+static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_t M, const uint64_t* M_dev, float* dp,
+                                bool skip_dp_when_large, hipStream_t s) {
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = M;
+    a.M_dev = M_dev;
+    a.rows = rows;
+    a.a_mode = A_PLAIN;
+    a.P0 = c->H[l];
+    a.ldp = c->dims[l];
+    a.K = c->dims[l];
+    a.N = c->dims[l];
+    a.Wt = c->Wt[l][1];
+    a.bias = c->bias[l][1];
+    a.act = 1;
+    a.H = c->MP[l];
+    a.DP = dp;
+    a.dp_skip_large = skip_dp_when_large;
+    a.n_vertices = c->g->n;
+    return k_gemm(a, s);
+}
+
 // gather + fold of layer l over the destinations described by c->recs and the hub items built from them;
 // all sizes are read on the device from c->lc[l]
 static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bool may_recompute, int sparse_hint,
@@ -395,13 +430,13 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
     a.lc = c->lc_use ? c->lc_use : &c->lc[l];
     a.in = g->in;
     a.D = c->dagg[l];
-    a.use_weights = (c->kind == NRT_GIN && g->weighted) ? 1 : 0;
+    a.use_weights = (weighted_messages(c->kind) && g->weighted) ? 1 : 0;
     a.self_pair = c->kind == NRT_GCN;
     a.S = c->S[l];
     a.n_vertices = g->n;
     if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     GatherArgs full = a;                         // full-neighbour aggregation from h^{l-1} (Eq. 1)
-    full.P = c->H[l - 1];
+    full.P = payload_rows(c, l - 1);
     full.src_scale_gcn = c->kind == NRT_GCN;
     full.accumulate = 0;
     if (incremental) {
@@ -415,7 +450,7 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
         a.dd_bitmap = c->bm_ddst;
         a.dd_slot = c->slot_dd;
         a.guard = c->kind == NRT_GIN || c->kind == NRT_COMMNET;   // un-normalised sums: a fold can cancel most of a row's magnitude
-        a.Pfull = c->H[l - 1];
+        a.Pfull = payload_rows(c, l - 1);
         a.full_scale_gcn = c->kind == NRT_GCN;
         a.sparse_ok = (sparse_hint == 2 && a.D > 256) ? 1 : sparse_hint;    // rows wider than 256 floats: pipelined kernel only
         a.coarse = c->coarse;
@@ -455,7 +490,8 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
     a.indeg_old = c->indeg_old;
     a.ldp = c->dims[l - 1];
     a.N = c->dims[l];
-    float* dp = (incremental && !last) ? c->DP[cur] : nullptr;
+    // PinSAGE: the next layer's payload deltas come from the transform of the changed rows, not from here
+    float* dp = (incremental && !last && c->kind != NRT_PINSAGE) ? c->DP[cur] : nullptr;
     if (c->kind == NRT_GCN || concat_self(c->kind)) {
         if (c->kind == NRT_GCN) {
             a.a_mode = A_SCALE_GCN;
@@ -605,7 +641,8 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
             st = run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, false, 0, nullptr, 0, s);
             continue;
         }
-        st = run_gather(c, l, false, 0, false, 0, s);
+        if (c->kind == NRT_PINSAGE) st = run_transform(c, l - 1, nullptr, n, nullptr, nullptr, false, s);
+        if (st == NRT_OK) st = run_gather(c, l, false, 0, false, 0, s);
         if (st == NRT_OK) st = run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, false, s);
     }
     c->lc_use = nullptr;
@@ -626,6 +663,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     for (int l = 0; l < d->n_layers; ++l) {
         REQUIRE(d->W[l][0], "W[l][0] is null");
         if (d->kind == NRT_GIN) REQUIRE(d->W[l][1], "GIN needs W[l][1]");
+        if (d->kind == NRT_PINSAGE) REQUIRE(d->W[l][1], "PinSAGE needs W[l][1]");
         if (d->kind == NRT_GAT) REQUIRE(d->att_src[l] && d->att_dst[l], "GAT needs att_src[l] and att_dst[l]");
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -657,10 +695,11 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
                 NRT_TRY(k_copy_f32(c->att_src[l], d->att_src[l], (int64_t)c->heads * c->head_dim, s));
                 NRT_TRY(k_copy_f32(c->att_dst[l], d->att_dst[l], (int64_t)c->heads * c->head_dim, s));
             }
-            if (c->kind == NRT_GIN) {
-                NRT_TRY(k_transpose(d->W[l][1], c->Wt[l][1], c->dims[l + 1], c->dims[l + 1], s));
-                if (d->b[l][1]) NRT_TRY(k_copy_f32(c->bias[l][1], d->b[l][1], c->dims[l + 1], s));
-                else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][1], c->dims[l + 1], 0, s));
+            if (c->kind == NRT_GIN || c->kind == NRT_PINSAGE) {
+                const int dq = c->kind == NRT_GIN ? c->dims[l + 1] : c->dims[l];
+                NRT_TRY(k_transpose(d->W[l][1], c->Wt[l][1], dq, dq, s));
+                if (d->b[l][1]) NRT_TRY(k_copy_f32(c->bias[l][1], d->b[l][1], dq, s));
+                else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][1], dq, 0, s));
             }
         }
         for (int l = 1; l <= c->L; ++l)
@@ -785,13 +824,13 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
         f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
-        if (c->kind == NRT_GIN && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
+        if (weighted_messages(c->kind) && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
         f.indeg_old = gcn ? g->in.deg : nullptr;
         f.n_layers = c->L;
         f.n = n;
         f.dd_slot = c->slot_dd;
         for (int l = 1; l <= c->L; ++l) {
-            f.Hprev[l - 1] = c->H[l - 1];
+            f.Hprev[l - 1] = payload_rows(c, l - 1);
             f.SD[l - 1] = c->SD[l];
             f.D[l - 1] = c->dagg[l];
         }
@@ -870,6 +909,8 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
                           g->scan_tmp_len, &c->lc[l].count, s));
         if (c->lazy) {                                     // on-demand mode: A_l only becomes stale
+            if (c->kind == NRT_PINSAGE && l == 1)          // h^0 is never stale, so neither may its message rows be
+                NRT_TRY(run_transform(c, 0, c->list[0], src_bound, &c->lc[0].count, nullptr, false, s));
             NRT_TRY(k_or_words(c->stale[l], c->stale[l], c->bm[cur], (n + 31) / 32, s));
             prev = cur;
             continue;
@@ -892,6 +933,9 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             // clearly dense layer launches one kernel, in between both are launched and the device counter decides
             const int64_t pn = prev_n_list[l - 1];
             const int sparse_hint = !had_history ? 1 : (pn * 64 <= n ? 2 : (pn * 4 > n ? 0 : 1));
+            if (c->kind == NRT_PINSAGE)
+                NRT_TRY(run_transform(c, l - 1, c->list[l - 1], src_bound, &c->lc[l - 1].count, inc ? c->DP[prev] : nullptr,
+                                      may_rec[l], s));
             NRT_TRY(run_gather(c, l, inc, prev, may_rec[l], sparse_hint, s));
             NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, inc, cur, l == c->L ? affected_rows : nullptr,
                                capacity, may_rec[l + 1], s));
@@ -984,6 +1028,8 @@ static nrt_status recompute_listed(nrt_cache* c, hipStream_t s) {
         NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, nullptr, s));
         NRT_TRY(run_gather(c, l, false, 0, false, 0, s));
         NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, false, 0, nullptr, 0, false, s));
+        if (c->kind == NRT_PINSAGE && l < c->L)            // message rows follow every h row that is brought up to date
+            NRT_TRY(run_transform(c, l, c->list[l], n, &c->lc[l].count, nullptr, false, s));
         NRT_TRY(k_clear_listed_bits(c->stale[l], c->list[l], &c->lc[l].count, n, s));
     }
     return NRT_OK;

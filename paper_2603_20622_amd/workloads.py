@@ -18,8 +18,8 @@ from typing import Dict, List, Optional
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET = 1, 2, 3, 4, 5
-KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet"}
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE = 1, 2, 3, 4, 5, 6
+KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage"}
 
 
 @dataclass
@@ -136,10 +136,12 @@ def make_params(spec: ModelSpec, seed: int = 0, bias: bool = False) -> Params:
     p = Params()
     for l in range(1, spec.n_layers + 1):
         din, dout = spec.dims[l - 1], spec.dims[l]
-        kin = 2 * din if spec.kind in (SAGE_MEAN, COMMNET) else din
+        kin = 2 * din if spec.kind in (SAGE_MEAN, COMMNET, PINSAGE) else din
         Ws = [_glorot(rng, kin, dout, (kin, dout))]
         if spec.kind == GIN:
             Ws.append(_glorot(rng, dout, dout, (dout, dout)))
+        if spec.kind == PINSAGE:
+            Ws.append(_glorot(rng, din, din, (din, din)))
         bs: List[Optional[np.ndarray]] = []
         for W in Ws:
             bs.append(rng.uniform(-0.1, 0.1, size=W.shape[1]).astype(np.float32) if bias else None)

@@ -51,7 +51,7 @@ def S():
 
 def small_case(kind, seed=0, n=3000, e=40000, dims=None, bias=False, L=2):
     src, dst, sampler = wl.rmat_graph(n, e, seed)
-    weighted = kind == wl.GIN
+    weighted = kind in WEIGHTED
     w = wl.edge_weights(e, seed) if weighted else None
     if dims is None:
         dims = [64, 128, 32] if L == 2 else [32, 64, 64, 16]
@@ -65,7 +65,8 @@ def small_case(kind, seed=0, n=3000, e=40000, dims=None, bias=False, L=2):
     return n, src, dst, w, x, spec, params, stream
 
 
-KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET]
+KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE]
+WEIGHTED = (wl.GIN, wl.PINSAGE)           # models whose messages carry the edge weight
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -251,13 +252,14 @@ def test_gin_cancellation_is_guarded(S, oracle):
     (wl.SAGE_MEAN, [512, 40, 12], 1, 0),        # 512-wide aggregate: two 16-byte loads per lane; K = 1024 update
     (wl.GIN, [260, 132, 20], 1, 0),             # widths that are multiples of 4 only
     (wl.COMMNET, [36, 260, 8], 1, 0),           # concatenated K = 72 and 520
+    (wl.PINSAGE, [20, 132, 12], 1, 0),          # message transforms 20x20 and 132x132
     (wl.GAT, [24, 512, 512], 8, 64),            # 512-wide attention rows, 8 heads
     (wl.GAT, [12, 8, 8], 2, 4),                 # smallest head width
 ])
 def test_unusual_widths(S, oracle, kind, dims, heads, head_dim):
     n, e = 1500, 20000
     src, dst, sampler = wl.rmat_graph(n, e, 31)
-    weighted = kind == wl.GIN
+    weighted = kind in WEIGHTED
     w = wl.edge_weights(e, 31) if weighted else None
     spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=head_dim, weighted=weighted)
     params = wl.make_params(spec, 31, bias=True)
@@ -527,14 +529,14 @@ def test_widest_rows(S, oracle):
             assert rel_err(ses.layer(l).cpu().numpy(), ref[l - 1]) <= TOL
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.COMMNET])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.COMMNET, wl.PINSAGE])
 def test_on_demand_queries_match_oracle(S, oracle, kind):
     """On-demand mode (Section IV-D): batches only mark vertices stale; a query recomputes the stale part of the
     L-hop in-neighbourhood of the queried vertices, nothing else, and returns rows equal to a full recomputation."""
     from paper_2603_20622_amd import binding as nb
     n, e = 6000, 30000
     src, dst, sampler = wl.rmat_graph(n, e, 101)
-    weighted = kind == wl.GIN
+    weighted = kind in WEIGHTED
     w = wl.edge_weights(e, 101) if weighted else None
     spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted)
     params = wl.make_params(spec, 101, bias=True)

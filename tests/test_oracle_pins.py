@@ -1,7 +1,7 @@
 """Pins for the CPU oracle: things other than the oracle itself that fix its values.
 
   * brute force: a per-vertex recursive evaluation of the message-aggregate-update layer (Eq. 1)
-    from hand-written adjacency lists, in Python floats, for all five models;
+    from hand-written adjacency lists, in Python floats, for all six models;
   * the dense-matrix closed forms the models reduce to (normalised adjacency products);
   * closed forms on special graphs / parameters (cycle, constant features, zero attention,
     two-term softmax, star hub);
@@ -56,6 +56,14 @@ def brute_embedding(spec, params, in_nbrs, x, v, l):
                 m[k] += hu[u][k] / len(in_nbrs[v])
         y = _lin(hv + m, W[0], b[0])
         act = "relu"
+    elif spec.kind == wl.PINSAGE:
+        m = [0.0] * d
+        for u, w in in_nbrs[v]:
+            mu = [max(q, 0.0) for q in _lin(hu[u], W[1], b[1])]
+            for k in range(d):
+                m[k] += float(w) * mu[k] / len(in_nbrs[v])
+        y = _lin(hv + m, W[0], b[0])
+        act = "relu"
     elif spec.kind == wl.COMMNET:
         tot = [0.0] * d
         for u, _ in in_nbrs[v]:
@@ -108,13 +116,13 @@ def _tiny(kind, L, seed, bias=True):
     src = np.array([e[0] for e in TINY_EDGES], dtype=np.int32)
     dst = np.array([e[1] for e in TINY_EDGES], dtype=np.int32)
     rng = np.random.default_rng(seed)
-    w = rng.random(src.size, dtype=np.float32) if kind == wl.GIN else None
+    w = rng.random(src.size, dtype=np.float32) if kind in (wl.GIN, wl.PINSAGE) else None
     if kind == wl.GAT:
         dims = [3] + [4] * L
         spec = wl.ModelSpec(kind, dims, heads=2, head_dim=2)
     else:
         dims = [3, 5, 4, 2][: L + 1]
-        spec = wl.ModelSpec(kind, dims, weighted=(kind == wl.GIN))
+        spec = wl.ModelSpec(kind, dims, weighted=(kind in (wl.GIN, wl.PINSAGE)))
     params = wl.make_params(spec, seed, bias=bias)
     x = rng.standard_normal((n, dims[0])).astype(np.float32)
     return n, src, dst, w, x, spec, params
@@ -127,7 +135,7 @@ def _in_lists(n, src, dst, w):
     return lists
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE])
 @pytest.mark.parametrize("L", [1, 2, 3])
 def test_forward_matches_brute_force(oracle, kind, L):
     n, src, dst, w, x, spec, params = _tiny(kind, L, seed=3 + L)
@@ -241,6 +249,61 @@ def test_commnet_reduces_to_sage_and_gin_on_special_cases(oracle):
     out = oracle.forward(one, p1, n, src, dst, None, x)[0]
     t = x.astype(np.float64) + _dense_adj(n, src, dst) @ x.astype(np.float64)
     np.testing.assert_allclose(out, t @ p1.W[0][0][:4].astype(np.float64), rtol=1e-12, atol=1e-13)
+
+
+def test_pinsage_is_weighted_row_normalised_product(oracle):
+    """Table II PinSAGE row as matrices: M = ReLU(H Q + q); A_w = weighted adjacency; a = (A_w M) / count;
+    H' = act([H || a] W + b)."""
+    n, e = 40, 260
+    src, dst, _ = wl.rmat_graph(n, e, seed=16)
+    w = wl.edge_weights(e, 16)
+    spec = wl.ModelSpec(wl.PINSAGE, [4, 6, 3], weighted=True)
+    params = wl.make_params(spec, 17, bias=True)
+    x = wl.features(n, 4, 18).astype(np.float64)
+    f = lambda a: a.astype(np.float64)
+    Aw = _dense_adj(n, src, dst, w)
+    cnt = _dense_adj(n, src, dst).sum(axis=1)
+    assert (cnt == 0).any()
+    h = x
+    for l in range(2):
+        m = np.maximum(h @ f(params.W[l][1]) + f(params.b[l][1]), 0)
+        a = np.where(cnt[:, None] > 0, (Aw @ m) / np.maximum(cnt, 1)[:, None], 0.0)
+        h = np.hstack([h, a]) @ f(params.W[l][0]) + f(params.b[l][0])
+        if l == 0:
+            h = np.maximum(h, 0)
+    outs = oracle.forward(spec, params, n, src, dst, w, x)
+    np.testing.assert_allclose(outs[1], h, rtol=1e-11, atol=1e-12)
+
+
+def test_pinsage_with_identity_transform_is_graphsage(oracle):
+    """Q = I, q = 0, unit importances, non-negative inputs: the message is h_u itself (ReLU of a non-negative row;
+    hidden layers are non-negative after their own ReLU), so the model is GraphSAGE-mean with the same W."""
+    n, e = 35, 200
+    src, dst, _ = wl.rmat_graph(n, e, seed=19)
+    x = np.abs(wl.features(n, 4, 19))
+    sage = wl.ModelSpec(wl.SAGE_MEAN, [4, 5, 5, 2])
+    ps = wl.make_params(sage, 20, bias=True)
+    pin = wl.ModelSpec(wl.PINSAGE, [4, 5, 5, 2])
+    pp = wl.make_params(pin, 21, bias=True)
+    for l, d in enumerate([4, 5, 5]):
+        pp.W[l][0], pp.b[l][0] = ps.W[l][0], ps.b[l][0]
+        pp.W[l][1], pp.b[l][1] = np.eye(d, dtype=np.float32), None
+    got = oracle.forward(pin, pp, n, src, dst, None, x)
+    want = oracle.forward(sage, ps, n, src, dst, None, x)
+    for l in range(3):
+        np.testing.assert_allclose(got[l], want[l], rtol=1e-12, atol=1e-13)
+
+
+def test_pinsage_two_edges_by_hand(oracle):
+    """Edges 0 -> 2 (weight 0.5) and 1 -> 2 (weight 2), scalar feature, Q = -1, q = 1, W = [3; 4]:
+    m_0 = ReLU(1 - 2) = 0, m_1 = ReLU(1 + 3) = 4, a_2 = (0.5*0 + 2*4)/2 = 4, h_2 = 3*5 + 4*4 = 31; h_0 = 3*2."""
+    spec = wl.ModelSpec(wl.PINSAGE, [1, 1], weighted=True)
+    params = wl.Params(W=[[np.array([[3.0], [4.0]], np.float32), np.array([[-1.0]], np.float32)]],
+                       b=[[None, np.array([1.0], np.float32)]], att_src=[None], att_dst=[None])
+    x = np.array([[2.0], [-3.0], [5.0]], np.float32)
+    out = oracle.forward(spec, params, 3, np.array([0, 1], np.int32), np.array([2, 2], np.int32),
+                         np.array([0.5, 2.0], np.float32), x)[0]
+    np.testing.assert_allclose(out[:, 0], [6.0, -9.0, 31.0], rtol=1e-14)
 
 
 def test_commnet_single_edge_by_hand(oracle):
@@ -412,7 +475,7 @@ def test_affected_sets_hand_enumerated(oracle):
         assert [a.tolist() for a in got] == [[3, 4], [3, 4]]
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE])
 def test_affected_sets_match_reachability_powers(oracle, kind):
     n, e = 70, 260
     src, dst, sampler = wl.rmat_graph(n, e, seed=12)
@@ -436,11 +499,11 @@ def test_affected_sets_match_reachability_powers(oracle, kind):
 
 
 # ------------------------------------------------------------------ invariants
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE])
 def test_batch_invariants(oracle, kind):
     n, e = 200, 1500
     src, dst, sampler = wl.rmat_graph(n, e, seed=13)
-    weighted = kind == wl.GIN
+    weighted = kind in (wl.GIN, wl.PINSAGE)
     w = wl.edge_weights(e, 13) if weighted else None
     spec = wl.ModelSpec(kind, [6, 8, 4], heads=2, head_dim=4 if kind == wl.GAT else 0, weighted=weighted)
     if kind == wl.GAT:
