@@ -185,6 +185,10 @@ class BatchStream:
             np.empty(0, dtype=np.int64)
         del_keys = self.keys[del_pos]
         ins_keys = np.empty(0, dtype=np.int64)
+        # rejection sampling only ends while enough absent pairs are left; refuse what would spin for ever or nearly so
+        free = self.n * (self.n - 1) - self.keys.size
+        if n_ins > free // 2:
+            raise ValueError("cannot draw %d new edges: only %d absent pairs are left" % (n_ins, free))
         while ins_keys.size < n_ins:
             s, d = self.sampler.draw(rng, int((n_ins - ins_keys.size) * 1.5) + 64)
             cand = s * self.n + d

@@ -36,6 +36,17 @@ def test_batch_stream_keeps_a_consistent_edge_set():
         assert set((s2.astype(np.int64) * n + d2).tolist()) == keys and w2.size == len(keys)
 
 
+def test_batch_stream_refuses_inserts_a_nearly_complete_graph_cannot_hold():
+    import pytest
+    n = 12
+    src, dst, sampler = wl.rmat_graph(n, 100, seed=2)       # 100 of the 132 possible edges
+    st = wl.BatchStream(n, src, dst, None, sampler, 4, seed=2)
+    with pytest.raises(ValueError):
+        st.next_batch(40, 0, 0)
+    b = st.next_batch(5, 5, 0)                              # a request that fits is still served
+    assert b.ins_src.size == 5 and b.del_src.size == 5
+
+
 def test_configs_have_the_benchmark_shapes():
     shapes = [(wl.GCN, [64, 64, 16], 10_000, 100_000), (wl.SAGE_MEAN, [128, 128, 64], 1_000_000, 20_000_000),
               (wl.GCN, [128, 256, 256, 64], 4_000_000, 100_000_000), (wl.GIN, [128, 256, 256, 128], 10_000_000, 200_000_000),
