@@ -51,7 +51,7 @@ typedef enum {
     NRT_ERR_UNSUPPORTED = 6  /* model shape outside what the kernels cover                            */
 } nrt_status;
 
-typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6 } nrt_model_kind;
+typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7 } nrt_model_kind;
 
 typedef struct nrt_graph nrt_graph;
 typedef struct nrt_cache nrt_cache;
@@ -73,6 +73,9 @@ typedef struct nrt_cache nrt_cache;
  *   NRT_PINSAGE   (Table II row PinSAGE)  m_u = ReLU(x_u W[l][1] + b[l][1]),  W[l][1] is [d_{l-1}][d_{l-1}];
  *                 a_v = (sum_{u in N(v)} w_uv m_u) / |N(v)|  (w_uv = 1 on an unweighted graph, a_v = 0 if N(v) is empty);
  *                 h_v = act( [x_v || a_v] W[l][0] + b[l][0] ),  W[l][0] is [2 d_{l-1}][d_l]
+ *   NRT_AGNN      (Table II row A-GNN)  a_v = sum_{u in N(v)} agnn_beta[l] * cos(x_v, x_u) * x_u, the cosine of a
+ *                 zero row taken as 0;  h_v = act( a_v W[l][0] + b[l][0] ).  The message reads the destination's own
+ *                 row: a "constrained" model (Section III-D), recomputed in full where that row changed
  * W, b, att_* are device pointers, row-major [in][out] / [heads][head_dim]; b entries may be NULL (zero).
  * They are copied at nrt_cache_init.
  */
@@ -87,6 +90,7 @@ typedef struct {
     const float* b[NRT_MAX_LAYERS][2];  /* device or NULL */
     const float* att_src[NRT_MAX_LAYERS]; /* device, GAT only */
     const float* att_dst[NRT_MAX_LAYERS]; /* device, GAT only */
+    float agnn_beta[NRT_MAX_LAYERS];    /* A-GNN only: the scalar of layer l+1 (host values) */
 } nrt_model_desc;
 
 /*

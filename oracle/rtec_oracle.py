@@ -35,6 +35,9 @@ Readings taken where the paper is silent or garbled (the GPU path takes the same
   * PinSAGE: the importance alpha_uv of its Table II row is the edge weight (1 on an unweighted graph), sigma is
     ReLU, Q is square (the message keeps the width of h), and the mean divides by the neighbour count as the
     row's count context says (not by the sum of the weights).
+  * A-GNN: a_v = sum_{u in N(v)} w cos(h_v, h_u) h_u exactly as its Table II row prints it (no softmax, no
+    self-loop); the cosine with a zero row is 0; a vertex affected at layer l-1 is affected at layer l because
+    its own row enters every one of its messages.
   * GAT: z = x W viewed [heads][head_dim]; e_uv = LeakyReLU(a_dst . z_v + a_src . z_u)
     (destination first, as in Eq. 3); softmax over N(v) U {v}; heads concatenated; ELU on
     hidden layers.
@@ -49,7 +52,7 @@ from typing import List, Optional, Sequence
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE = 1, 2, 3, 4, 5, 6
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN = 1, 2, 3, 4, 5, 6, 7
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librtec_oracle.so")
@@ -197,6 +200,15 @@ def layer(spec, params, l: int, n: int, src, dst, w, x: np.ndarray) -> np.ndarra
         s = in_sum(n, src, dst, _f64(w), m)
         mean = np.where(cnt[:, None] > 0, s / np.maximum(cnt, 1.0)[:, None], 0.0)
         y = np.concatenate([x, mean], axis=1) @ W[0]
+        if b[0] is not None:
+            y = y + b[0]
+    elif spec.kind == AGNN:
+        # Table II A-GNN row: message w * cos(h_v, h_u) * h_u, plain sum, update sigma(W a_v).
+        nrm = np.sqrt((x * x).sum(axis=1))
+        unit = np.where(nrm[:, None] > 0, x / np.where(nrm > 0, nrm, 1.0)[:, None], 0.0)
+        cos = (unit[dst] * unit[src]).sum(axis=1)
+        a = in_sum(n, src, dst, float(spec.agnn_beta) * cos, x)
+        y = a @ W[0]
         if b[0] is not None:
             y = y + b[0]
     elif spec.kind == GIN:

@@ -31,7 +31,8 @@ class nrt_model_desc(ctypes.Structure):
                 ("heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("gin_eps", ctypes.c_float), ("leaky_slope", ctypes.c_float),
                 ("W", (c_fp * 2) * NRT_MAX_LAYERS), ("b", (c_fp * 2) * NRT_MAX_LAYERS),
-                ("att_src", c_fp * NRT_MAX_LAYERS), ("att_dst", c_fp * NRT_MAX_LAYERS)]
+                ("att_src", c_fp * NRT_MAX_LAYERS), ("att_dst", c_fp * NRT_MAX_LAYERS),
+                ("agnn_beta", ctypes.c_float * NRT_MAX_LAYERS)]
 
 
 class nrt_batch(ctypes.Structure):
@@ -186,6 +187,8 @@ def make_desc(spec, dev_params) -> nrt_model_desc:
         d.dims[i] = v
     d.heads, d.head_dim = spec.heads, spec.head_dim
     d.gin_eps, d.leaky_slope = spec.gin_eps, spec.leaky_slope
+    for l in range(d.n_layers):
+        d.agnn_beta[l] = float(getattr(spec, "agnn_beta", 1.0))
     for l in range(d.n_layers):
         for j, W in enumerate(dev_params["W"][l]):
             d.W[l][j] = W.data_ptr()

@@ -1,0 +1,281 @@
+// A-GNN (Table II): the message of an edge <u,v> is w * cos(h_v, h_u) * h_u, summed over the in-neighbours.
+//
+// The coefficient reads the destination's own embedding, so the model is one of the paper's constrained ones
+// (Section III-D): a destination whose own h^{l-1} changed is summed again over its whole in-neighbourhood; every
+// other affected destination only exchanges the terms of its changed in-neighbours, c_new h_new - c_old h_old, where
+// the old term is recomputed from the old row and the old norm kept compact for the changed vertices (the role the
+// cached per-edge attention plays in Algorithm 3).  Deleted and inserted in-edges contribute their terms on the old
+// caches, folded into one compact row per destination before the graph changes, exactly as for the other models.
+//
+// Cached per layer: h^{l-1} (the layer input), the inverse norm of each of its rows (0 for a zero row, whose cosine
+// is taken as 0), and the aggregate a_v.  Destinations with long in-lists are always summed in full through their
+// items (partial rows, added up by the common combine kernel).
+#include "common.h"
+
+namespace {
+
+constexpr int AG_WAVES = 4;        // waves per workgroup
+constexpr int AG_BLOCKS = 4096;    // fixed grid: sizes are read on the device
+constexpr int AG_TERMS = 4;        // rows in flight per wave
+constexpr float AG_GUARD_RATIO = 16.0f;   // an exchange larger than this many times what it leaves is redone in full
+
+__device__ inline float wave_sum(float x) {
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1) x += __shfl_xor(x, s, 64);
+    return x;
+}
+
+__device__ inline bool in_set(const uint32_t* bm, int32_t v) { return (bm[(uint32_t)v >> 5] >> (v & 31)) & 1u; }
+
+// acc += sum_t c[t] * (hv . row_t) * row_t for t < nt (uniform over the wave); the rows are loaded together
+template <int NV>
+__device__ inline void add_terms(const float* (&row)[AG_TERMS], const float (&c)[AG_TERMS], int nt, const float4 (&hv)[NV],
+                                 float4 (&acc)[NV], const bool (&live)[NV], int lane) {
+    float4 x[AG_TERMS][NV];
+    float d[AG_TERMS];
+#pragma unroll
+    for (int t = 0; t < AG_TERMS; ++t) {
+        d[t] = 0.f;
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            x[t][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (t < nt && live[q]) x[t][q] = *reinterpret_cast<const float4*>(row[t] + lane * 4 + q * 256);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < AG_TERMS; ++t)
+#pragma unroll
+        for (int q = 0; q < NV; ++q)
+            d[t] += hv[q].x * x[t][q].x + hv[q].y * x[t][q].y + hv[q].z * x[t][q].z + hv[q].w * x[t][q].w;
+#pragma unroll
+    for (int s = 32; s >= 1; s >>= 1)
+#pragma unroll
+        for (int t = 0; t < AG_TERMS; ++t) d[t] += __shfl_xor(d[t], s, 64);
+#pragma unroll
+    for (int t = 0; t < AG_TERMS; ++t) {
+        const float k = c[t] * d[t];                         // zero rows and c = 0 beyond nt: nothing is added
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            acc[q].x += k * x[t][q].x; acc[q].y += k * x[t][q].y;
+            acc[q].z += k * x[t][q].z; acc[q].w += k * x[t][q].w;
+        }
+    }
+}
+
+// R[v] = 1 / |h_v| for the listed rows (list null: rows 0 .. n_all); r_old[m] keeps the value it replaces
+__global__ void agnn_norms_kernel(const int32_t* list, const uint64_t* count_dev, int64_t bound, const float* H, int D,
+                                  float* R, float* r_old) {
+    const int lane = threadIdx.x & 63;
+    int64_t count = list ? (int64_t)*count_dev : bound;
+    if (count > bound) count = bound;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t m = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; m < count; m += waves) {
+        const int64_t v = list ? (int64_t)list[m] : m;
+        const float* row = H + v * D;
+        float s = 0.f;
+        for (int k = lane * 4; k < D; k += 256) {
+            const float4 x = *reinterpret_cast<const float4*>(row + k);
+            s += x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w;
+        }
+        s = wave_sum(s);
+        if (lane == 0) {
+            if (r_old) r_old[m] = R[v];
+            R[v] = s > 0.f ? 1.0f / sqrtf(s) : 0.f;
+        }
+    }
+}
+
+// One wave per unit (a destination with a short in-list, or one item of a long one).  NV: 16-byte pieces of a row
+// per lane (rows of up to 256 * NV floats).
+template <int NV>
+__global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int D = a.D;
+    const int64_t n_dst = (int64_t)a.lc->count;
+    int64_t n_items = (int64_t)a.lc->n_items;
+    if (n_items > a.hubs.item_cap) n_items = a.hubs.item_cap;
+    const int64_t total = n_dst + n_items;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    bool live[NV];
+#pragma unroll
+    for (int q = 0; q < NV; ++q) live[q] = lane * 4 + q * 256 < D;
+    long long pairs = 0;
+
+    for (int64_t unit = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; unit < total; unit += waves) {
+        DstRec rec;
+        int32_t cnt;
+        int64_t base;
+        bool part;
+        if (unit >= n_items) {
+            rec = a.recs[unit - n_items];
+            if (rec.deg > NRT_CHUNK) continue;               // served through its items
+            cnt = rec.deg; base = rec.off; part = false;
+        } else {
+            const int32_t chunk = a.hubs.item_chunk[unit];
+            rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[unit]]];
+            cnt = min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK);
+            base = rec.off + (int64_t)chunk * NRT_CHUNK;
+            part = true;
+        }
+        const int32_t v = rec.v;
+        bool full = part || !a.incremental || in_set(a.src_bitmap, v);   // uniform over the wave
+        float4 hv[NV], acc[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            hv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (live[q]) hv[q] = *reinterpret_cast<const float4*>(a.H + (int64_t)v * D + lane * 4 + q * 256);
+        }
+        const float cv = a.beta * a.R[v];
+
+      // at most two passes: an exchange that cancels most of the row is redone as a full sum (see below)
+      for (;;) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
+            const int32_t j = j0 + lane;
+            const int32_t u = j < cnt ? a.in.idx[base + j] : -1;
+            bool take = u >= 0;
+            int32_t slot = 0;
+            if (!full) {
+                take = take && in_set(a.src_bitmap, u);
+                if (take) slot = a.src_slot[u];
+            }
+            const float ru = take ? a.R[u] : 0.f;
+            const float ro = (take && !full) ? a.old_r[slot] : 0.f;
+            unsigned long long m = __ballot(take);
+            pairs += __popcll(m);
+            // in in-list order, AG_TERMS rows at a time: the sum does not depend on the schedule
+            while (m) {
+                const float* row[AG_TERMS];
+                float c[AG_TERMS];
+                int nt = 0;
+                if (full) {
+#pragma unroll
+                    for (int t = 0; t < AG_TERMS; ++t) {
+                        row[t] = a.H; c[t] = 0.f;
+                        if (m) {
+                            const int b = __ffsll((long long)m) - 1;
+                            m &= m - 1;
+                            row[t] = a.H + (int64_t)__shfl(u, b, 64) * D;
+                            c[t] = cv * __shfl(ru, b, 64);
+                            nt = t + 1;
+                        }
+                    }
+                } else {                                      // the new term of a changed in-neighbour minus its old one
+#pragma unroll
+                    for (int t = 0; t < AG_TERMS; t += 2) {
+                        row[t] = a.H; c[t] = 0.f; row[t + 1] = a.H; c[t + 1] = 0.f;
+                        if (m) {
+                            const int b = __ffsll((long long)m) - 1;
+                            m &= m - 1;
+                            row[t] = a.H + (int64_t)__shfl(u, b, 64) * D;
+                            c[t] = cv * __shfl(ru, b, 64);
+                            row[t + 1] = a.old_rows + (int64_t)__shfl(slot, b, 64) * D;
+                            c[t + 1] = -cv * __shfl(ro, b, 64);
+                            nt = t + 2;
+                        }
+                    }
+                }
+                add_terms<NV>(row, c, nt, hv, acc, live, lane);
+            }
+        }
+
+        if (part) {
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                if (live[q]) *reinterpret_cast<float4*>(a.hubs.partial + unit * D + lane * 4 + q * 256) = acc[q];
+            break;
+        }
+        float* out = a.S + (int64_t)v * D;
+        if (full) {
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                if (live[q]) *reinterpret_cast<float4*>(out + lane * 4 + q * 256) = acc[q];
+            break;
+        }
+        const bool dd = a.sd && in_set(a.dd_bitmap, v);
+        const float* sdrow = dd ? a.sd + (int64_t)a.dd_slot[v] * D : nullptr;
+        float4 y[NV];
+        float big = 0.f, left = 0.f;
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            y[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (!live[q]) continue;
+            float4 d = acc[q];
+            if (dd) {
+                const float4 e = *reinterpret_cast<const float4*>(sdrow + lane * 4 + q * 256);
+                d.x += e.x; d.y += e.y; d.z += e.z; d.w += e.w;
+            }
+            const float4 o = *reinterpret_cast<const float4*>(out + lane * 4 + q * 256);
+            y[q] = make_float4(o.x + d.x, o.y + d.y, o.z + d.z, o.w + d.w);
+            big = fmaxf(big, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+            left = fmaxf(left, fmaxf(fmaxf(fabsf(y[q].x), fabsf(y[q].y)), fmaxf(fabsf(y[q].z), fabsf(y[q].w))));
+        }
+#pragma unroll
+        for (int sft = 32; sft >= 1; sft >>= 1) {
+            big = fmaxf(big, __shfl_xor(big, sft, 64));
+            left = fmaxf(left, __shfl_xor(left, sft, 64));
+        }
+        // Cancellation guard.  What an exchange leaves of a row that it mostly removes is rounding residue of the
+        // removed terms; the next layer normalises this row (cosine), which would turn a residue of 1e-11 into a
+        // direction.  Such a row is summed again over the whole in-list (an exact zero stays an exact zero).
+        if (big > AG_GUARD_RATIO * left) { full = true; continue; }
+#pragma unroll
+        for (int q = 0; q < NV; ++q)
+            if (live[q]) *reinterpret_cast<float4*>(out + lane * 4 + q * 256) = y[q];
+        break;
+      }
+    }
+    if (a.pair_ctr && lane == 0 && pairs) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)pairs);
+}
+
+// one wave per (updated edge, layer): SD^l[slot(dst)] += sign * w * cos(h_dst, h_src) * h_src on the old caches
+__global__ void agnn_structural_fold_kernel(AgnnFoldArgs a) {
+    const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    const int l = blockIdx.y;
+    if (op >= a.n_ins + a.n_del) return;
+    const bool is_del = op >= a.n_ins;
+    const int64_t i = is_del ? op - a.n_ins : op;
+    const int32_t u = is_del ? a.del_src[i] : a.ins_src[i];
+    const int32_t v = is_del ? a.del_dst[i] : a.ins_dst[i];
+    if (u < 0 || u >= a.n || v < 0 || v >= a.n) return;     // the batch's verdict is not known yet: it will be rejected
+    const int D = a.D[l];
+    const float* hu = a.H[l] + (int64_t)u * D;
+    const float* hv = a.H[l] + (int64_t)v * D;
+    float d = 0.f;
+    for (int k = lane; k < D; k += 64) d += hu[k] * hv[k];
+    d = wave_sum(d);
+    const float c = (is_del ? -1.0f : 1.0f) * a.beta[l] * a.R[l][u] * a.R[l][v] * d;
+    float* dst = a.SD[l] + (int64_t)a.dd_slot[v] * D;
+    for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, c * hu[k]);
+}
+
+}  // namespace
+
+nrt_status k_agnn_norms(const int32_t* list, const uint64_t* count_dev, int64_t bound, const float* H, int D, float* R,
+                        float* r_old, hipStream_t s) {
+    if (bound <= 0) return NRT_OK;
+    int64_t g = cdiv(bound, 4);
+    if (g > 4096) g = 4096;
+    agnn_norms_kernel<<<(int)g, 256, 0, s>>>(list, count_dev, bound, H, D, R, r_old);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_agnn_gather(const AgnnArgs& a, hipStream_t s) {
+    if (a.D % 4 || a.D > 1024) { nrt_set_error("agnn: row width must be a multiple of 4, at most 1024"); return NRT_ERR_UNSUPPORTED; }
+    if (a.D <= 256) agnn_gather_kernel<1><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+    else if (a.D <= 512) agnn_gather_kernel<2><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+    else agnn_gather_kernel<4><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_agnn_structural_fold(const AgnnFoldArgs& a, hipStream_t s) {
+    const int64_t nops = a.n_ins + a.n_del;
+    if (nops <= 0 || a.n_layers <= 0) return NRT_OK;
+    agnn_structural_fold_kernel<<<dim3((unsigned)cdiv(nops * 64, 256), (unsigned)a.n_layers, 1), 256, 0, s>>>(a);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}

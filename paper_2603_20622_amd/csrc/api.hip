@@ -39,6 +39,9 @@ struct nrt_cache {
     int maxd;
     float* H[NRT_MAX_LAYERS + 1];
     float* S[NRT_MAX_LAYERS + 1];
+    float* R[NRT_MAX_LAYERS + 1];       // A-GNN: inverse norms of the rows of h^l (null otherwise)
+    float* r_old;                       // A-GNN: [N] compact, inverse norms of the changed rows before the batch
+    float agnn_beta[NRT_MAX_LAYERS];
     float* MP[NRT_MAX_LAYERS + 1];      // PinSAGE: message payload of layer l's rows, ReLU(h^l Q + q) (null otherwise)
     float* Wt[NRT_MAX_LAYERS][2];
     float* bias[NRT_MAX_LAYERS][2];
@@ -239,7 +242,7 @@ static inline bool weighted_messages(int kind) { return kind == NRT_GIN || kind 
 
 static nrt_status check_desc(const nrt_model_desc* d) {
     REQUIRE(d, "model desc is null");
-    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_PINSAGE, "unknown model kind");
+    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_AGNN, "unknown model kind");
     REQUIRE(d->n_layers >= 1 && d->n_layers <= NRT_MAX_LAYERS, "n_layers out of range");
     for (int l = 0; l <= d->n_layers; ++l) {
         if (d->dims[l] <= 0 || d->dims[l] % 4 || d->dims[l] > 1024) {
@@ -270,6 +273,8 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->maxd = maxd;
     for (int l = 0; l <= c->L; ++l) c->H[l] = b.take<float>(n * c->dims[l]);
     for (int l = 0; l <= c->L; ++l) c->MP[l] = (c->kind == NRT_PINSAGE && l < c->L) ? b.take<float>(n * c->dims[l]) : nullptr;
+    for (int l = 0; l <= c->L; ++l) c->R[l] = (c->kind == NRT_AGNN && l < c->L) ? b.take<float>(n) : nullptr;
+    c->r_old = c->kind == NRT_AGNN ? b.take<float>(n) : nullptr;
     c->S[0] = nullptr;
     const bool gat = c->kind == NRT_GAT;
     for (int l = 1; l <= c->L; ++l) {
@@ -366,6 +371,7 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     c->head_dim = d->head_dim;
     c->gin_eps = d->gin_eps;
     c->leaky_slope = d->leaky_slope;
+    for (int l = 0; l < c->L; ++l) c->agnn_beta[l] = d->agnn_beta[l];
     c->max_edges = max_edges;
     c->max_feats = max_feats;
     return NRT_OK;
@@ -625,6 +631,74 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
     return NRT_OK;
 }
 
+// One A-GNN layer: norms of the changed rows of h^{l-1} (src_rows null: all rows), the cosine-weighted gather over the
+// destinations described by c->recs (listed in `rows`, null: all n), the sums of long in-lists, the dense update.
+static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
+                                 const int32_t* rows, const uint64_t* M_dev, int64_t M, bool incremental, int prev, int cur,
+                                 float* out_rows, int64_t out_cap, hipStream_t s) {
+    nrt_graph* g = c->g;
+    const bool last = l == c->L;
+    const int D = c->dims[l - 1];
+    NRT_TRY(k_agnn_norms(src_rows, n_src_dev, src_rows ? src_bound : g->n, c->H[l - 1], D, c->R[l - 1],
+                         (incremental && src_rows) ? c->r_old : nullptr, s));
+    NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
+    AgnnArgs a;
+    memset(&a, 0, sizeof(a));
+    a.recs = c->recs;
+    a.hubs = c->hubs;
+    a.lc = c->lc_use ? c->lc_use : &c->lc[l];
+    a.in = g->in;
+    a.H = c->H[l - 1];
+    a.R = c->R[l - 1];
+    a.D = D;
+    a.beta = c->agnn_beta[l - 1];
+    a.S = c->S[l];
+    if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
+    if (incremental) {
+        a.incremental = 1;
+        a.src_bitmap = c->bm[prev];
+        a.src_slot = c->slot[prev];
+        a.old_rows = c->DP[prev];
+        a.old_r = c->r_old;
+        a.sd = c->SD[l];
+        a.dd_bitmap = c->bm_ddst;
+        a.dd_slot = c->slot_dd;
+    }
+    NRT_TRY(k_agnn_gather(a, s));
+    NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
+    GatherArgs cmb;                               // long in-lists: their items hold whole partial sums
+    memset(&cmb, 0, sizeof(cmb));
+    cmb.recs = c->recs;
+    cmb.hubs = c->hubs;
+    cmb.lc = a.lc;
+    cmb.in = g->in;
+    cmb.D = D;
+    cmb.S = c->S[l];
+    cmb.n_vertices = g->n;
+    NRT_TRY(k_combine_partials(cmb, s));
+    NRT_TRY(prof_mark(c, TAG_COMBINE, l, s));
+    GemmArgs u;
+    memset(&u, 0, sizeof(u));
+    u.M = M;
+    u.M_dev = M_dev;
+    u.rows = rows;
+    u.a_mode = A_PLAIN;
+    u.P0 = c->S[l];
+    u.ldp = D;
+    u.K = D;
+    u.N = c->dims[l];
+    u.Wt = c->Wt[l - 1][0];
+    u.bias = c->bias[l - 1][0];
+    u.act = last ? 0 : 1;
+    u.H = c->H[l];
+    u.DP = (incremental && !last) ? c->DP[cur] : nullptr;      // the rows this update replaces: the next layer's old terms
+    u.dp_store_old = 1;
+    u.n_vertices = g->n;
+    u.out_compact = last ? out_rows : nullptr;
+    u.out_cap = out_cap;
+    return k_gemm(u, s);
+}
+
 // Full-neighbour forward over every vertex of every layer (Eq. 1) from the current h^0 and graph; fills all caches.
 // Every vertex is a destination: records and hub items are built once, with their counters in the spare
 // LayerCtrs slot (zero on entry), and serve all layers.
@@ -639,6 +713,10 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
     for (int l = 1; l <= c->L && st == NRT_OK; ++l) {
         if (c->kind == NRT_GAT) {
             st = run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, false, 0, nullptr, 0, s);
+            continue;
+        }
+        if (c->kind == NRT_AGNN) {
+            st = run_agnn_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, 0, 0, nullptr, 0, s);
             continue;
         }
         if (c->kind == NRT_PINSAGE) st = run_transform(c, l - 1, nullptr, n, nullptr, nullptr, false, s);
@@ -794,7 +872,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     // (no extra launches for small frontiers); the device counters of this batch take the decision
     bool may_rec[NRT_MAX_LAYERS + 2];
     for (int l = 0; l <= c->L + 1; ++l)
-        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
+        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && c->kind != NRT_AGNN && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     if (!empty_batch) NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, n, s));
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     if (inc && b->n_ins + b->n_del > 0) {
@@ -819,7 +897,20 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         }
         NRT_TRY(k_gat_structural_fold(f, s));
     }
-    if (inc && c->kind != NRT_GAT) {
+    if (inc && c->kind == NRT_AGNN) {
+        AgnnFoldArgs f;
+        memset(&f, 0, sizeof(f));
+        f.n_ins = b->n_ins; f.n_del = b->n_del; f.n = n;
+        f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
+        f.dd_slot = c->slot_dd;
+        f.n_layers = c->L;
+        for (int l = 1; l <= c->L; ++l) {
+            f.H[l - 1] = c->H[l - 1]; f.R[l - 1] = c->R[l - 1]; f.SD[l - 1] = c->SD[l];
+            f.D[l - 1] = c->dagg[l]; f.beta[l - 1] = c->agnn_beta[l - 1];
+        }
+        NRT_TRY(k_agnn_structural_fold(f, s));
+    }
+    if (inc && c->kind != NRT_GAT && c->kind != NRT_AGNN) {
         FoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
@@ -886,6 +977,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         da.DP = c->DP[0];
         da.D = c->dims[0];
         if (gcn && inc) { da.indeg_new = g->in.deg; da.indeg_old = c->indeg_old; }
+        da.store_old = c->kind == NRT_AGNN;
         NRT_TRY(k_layer0_delta(da, s));
     }
     NRT_TRY(prof_mark(c, TAG_INGEST, 0, s));
@@ -928,6 +1020,9 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         if (c->kind == NRT_GAT) {
             NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
                                   inc, prev, l == c->L ? affected_rows : nullptr, capacity, s));
+        } else if (c->kind == NRT_AGNN) {
+            NRT_TRY(run_agnn_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, inc,
+                                   prev, cur, l == c->L ? affected_rows : nullptr, capacity, s));
         } else {
             // which gather kernel: the previous batch's source count at this layer is the hint; a clearly sparse or
             // clearly dense layer launches one kernel, in between both are launched and the device counter decides
@@ -1054,7 +1149,10 @@ static nrt_status finish_recompute(nrt_cache* c, int64_t* n_recomputed, hipStrea
 
 extern "C" nrt_status nrt_set_lazy(nrt_cache* c, int32_t on, void* stream) {
     REQUIRE(c, "null argument");
-    if (c->kind == NRT_GAT) { nrt_set_error("on-demand mode is not available for GAT"); return NRT_ERR_UNSUPPORTED; }
+    if (c->kind == NRT_GAT || c->kind == NRT_AGNN) {
+        nrt_set_error("on-demand mode is not available for GAT and A-GNN");
+        return NRT_ERR_UNSUPPORTED;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (c->lazy && !on) {            // bring every stale vertex up to date before batches are applied eagerly again
         nrt_graph* g = c->g;

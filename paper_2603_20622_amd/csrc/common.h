@@ -223,6 +223,7 @@ struct DeltaArgs {  // layer-0 delta payloads and feature scatter
     const uint32_t* feat_bitmap; const int32_t* feat_index; const float* feat_rows;
     float* H0; float* DP; int D;
     const int32_t* indeg_new; const int32_t* indeg_old;   // GCN payload scale, else null
+    int store_old;                  // DP receives the replaced row itself instead of new - old (A-GNN: old h^0)
 };
 nrt_status k_layer0_delta(const DeltaArgs& a, hipStream_t s);
 
@@ -305,6 +306,44 @@ struct GatFoldArgs {   // structural terms of a batch for GAT, evaluated on the 
 };
 nrt_status k_gat_structural_fold(const GatFoldArgs& a, hipStream_t s);
 nrt_status k_gat_gather(const GatArgs& a, hipStream_t s);
+
+// ---------------------------------------------------------------- agnn.hip
+struct AgnnArgs {
+    const DstRec* recs;             // destination records, hub items and counters of the destination layer
+    HubWork hubs;
+    const LayerCtrs* lc;
+    Adj in;
+    const float* H;                 // [N][D] h^{l-1}, current
+    const float* R;                 // [N] inverse norms of its rows (0 for a zero row)
+    int D;
+    float beta;                     // the layer's scalar w
+    int incremental;                // 0: every destination is summed over its whole in-list
+    const uint32_t* src_bitmap;     // vertices whose h^{l-1} changed (incremental)
+    const int32_t* src_slot;        // their rows in old_rows / old_r
+    const float* old_rows;          // [changed][D] compact: h^{l-1} before this batch
+    const float* old_r;             // [changed] compact: inverse norms before this batch
+    const float* sd;                // structural terms, one compact row per destination of an updated edge (or null)
+    const uint32_t* dd_bitmap;
+    const int32_t* dd_slot;
+    float* S;                       // [N][D] cached aggregate
+    unsigned long long* pair_ctr;   // null or 1024 counters: rows of h fetched (a statistic)
+};
+struct AgnnFoldArgs {   // structural terms of a batch, evaluated on the pre-update caches, all layers in one launch
+    int64_t n_ins, n_del, n;        // edges with an id outside [0, n) are skipped
+    const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
+    const int32_t* dd_slot;
+    int n_layers;
+    const float* H[NRT_MAX_LAYERS];   // h^{l-1} (old)
+    const float* R[NRT_MAX_LAYERS];   // its inverse norms (old)
+    float* SD[NRT_MAX_LAYERS];
+    int D[NRT_MAX_LAYERS];
+    float beta[NRT_MAX_LAYERS];
+};
+// R[v] = 1/|H[v]| for v in list[0 .. *count_dev) (list null: rows 0 .. bound); r_old[m] (may be null) keeps the old value
+nrt_status k_agnn_norms(const int32_t* list, const uint64_t* count_dev, int64_t bound, const float* H, int D, float* R,
+                        float* r_old, hipStream_t s);
+nrt_status k_agnn_gather(const AgnnArgs& a, hipStream_t s);
+nrt_status k_agnn_structural_fold(const AgnnFoldArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------- graph.hip
 nrt_status graph_layout(Bump& b, nrt_graph* g);

@@ -857,7 +857,7 @@ __global__ void layer0_delta_kernel(DeltaArgs a) {
         const float4 xn = isfeat ? *reinterpret_cast<const float4*>(fresh + k) : xo;
         float4 d;
         d.x = xn.x * cn - xo.x * co; d.y = xn.y * cn - xo.y * co; d.z = xn.z * cn - xo.z * co; d.w = xn.w * cn - xo.w * co;
-        *reinterpret_cast<float4*>(dp + k) = d;
+        *reinterpret_cast<float4*>(dp + k) = a.store_old ? xo : d;
         if (isfeat) *reinterpret_cast<float4*>(h + k) = xn;
     }
 }

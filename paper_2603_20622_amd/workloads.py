@@ -18,8 +18,8 @@ from typing import Dict, List, Optional
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE = 1, 2, 3, 4, 5, 6
-KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage"}
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN = 1, 2, 3, 4, 5, 6, 7
+KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage", AGNN: "agnn"}
 
 
 @dataclass
@@ -32,6 +32,7 @@ class ModelSpec:
     gin_eps: float = 0.1
     leaky_slope: float = 0.2
     weighted: bool = False
+    agnn_beta: float = 1.0          # A-GNN: the scalar in front of the cosine (the same at every layer)
 
     @property
     def n_layers(self) -> int:

@@ -1,7 +1,7 @@
 """Pins for the CPU oracle: things other than the oracle itself that fix its values.
 
   * brute force: a per-vertex recursive evaluation of the message-aggregate-update layer (Eq. 1)
-    from hand-written adjacency lists, in Python floats, for all six models;
+    from hand-written adjacency lists, in Python floats, for all seven models;
   * the dense-matrix closed forms the models reduce to (normalised adjacency products);
   * closed forms on special graphs / parameters (cycle, constant features, zero attention,
     two-term softmax, star hub);
@@ -64,6 +64,16 @@ def brute_embedding(spec, params, in_nbrs, x, v, l):
                 m[k] += float(w) * mu[k] / len(in_nbrs[v])
         y = _lin(hv + m, W[0], b[0])
         act = "relu"
+    elif spec.kind == wl.AGNN:
+        a = [0.0] * d
+        nv = math.sqrt(sum(q * q for q in hv))
+        for u, _ in in_nbrs[v]:
+            nu = math.sqrt(sum(q * q for q in hu[u]))
+            cos = 0.0 if nv == 0 or nu == 0 else sum(hv[k] * hu[u][k] for k in range(d)) / (nv * nu)
+            for k in range(d):
+                a[k] += spec.agnn_beta * cos * hu[u][k]
+        y = _lin(a, W[0], b[0])
+        act = "relu"
     elif spec.kind == wl.COMMNET:
         tot = [0.0] * d
         for u, _ in in_nbrs[v]:
@@ -122,7 +132,7 @@ def _tiny(kind, L, seed, bias=True):
         spec = wl.ModelSpec(kind, dims, heads=2, head_dim=2)
     else:
         dims = [3, 5, 4, 2][: L + 1]
-        spec = wl.ModelSpec(kind, dims, weighted=(kind in (wl.GIN, wl.PINSAGE)))
+        spec = wl.ModelSpec(kind, dims, weighted=(kind in (wl.GIN, wl.PINSAGE)), agnn_beta=0.7)
     params = wl.make_params(spec, seed, bias=bias)
     x = rng.standard_normal((n, dims[0])).astype(np.float32)
     return n, src, dst, w, x, spec, params
@@ -135,7 +145,7 @@ def _in_lists(n, src, dst, w):
     return lists
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN])
 @pytest.mark.parametrize("L", [1, 2, 3])
 def test_forward_matches_brute_force(oracle, kind, L):
     n, src, dst, w, x, spec, params = _tiny(kind, L, seed=3 + L)
@@ -304,6 +314,47 @@ def test_pinsage_two_edges_by_hand(oracle):
     out = oracle.forward(spec, params, 3, np.array([0, 1], np.int32), np.array([2, 2], np.int32),
                          np.array([0.5, 2.0], np.float32), x)[0]
     np.testing.assert_allclose(out[:, 0], [6.0, -9.0, 31.0], rtol=1e-14)
+
+
+def test_agnn_is_cosine_masked_adjacency_product(oracle):
+    """Table II A-GNN row as matrices: C = w * (X_hat X_hat^T) masked by the adjacency, a = C X, H' = act(a W + b);
+    rows of zeros (they appear after a ReLU) have cosine 0 with everything."""
+    n, e = 40, 260
+    src, dst, _ = wl.rmat_graph(n, e, seed=22)
+    spec = wl.ModelSpec(wl.AGNN, [5, 6, 3], agnn_beta=1.3)
+    params = wl.make_params(spec, 23, bias=True)
+    x = wl.features(n, 5, 24).astype(np.float64)
+    x[3] = 0.0
+    f = lambda a: a.astype(np.float64)
+    A = _dense_adj(n, src, dst)
+    h = x
+    for l in range(2):
+        nrm = np.linalg.norm(h, axis=1)
+        hat = np.divide(h, nrm[:, None], out=np.zeros_like(h), where=nrm[:, None] > 0)
+        a = (1.3 * (hat @ hat.T) * A) @ h
+        h = a @ f(params.W[l][0]) + f(params.b[l][0])
+        if l == 0:
+            h = np.maximum(h, 0)
+    outs = oracle.forward(spec, params, n, src, dst, None, x.astype(np.float32))
+    np.testing.assert_allclose(outs[1], h, rtol=1e-10, atol=1e-12)
+
+
+def test_agnn_special_directions_by_hand(oracle):
+    """Hub 0 with x_0 = (3, 4) hears: 1 with 2*x_0 (cos 1), 2 with (-4, 3) (orthogonal, cos 0), 3 with -x_0 (cos -1),
+    4 with (5, 0) (cos 3/5).  w = 2, W = identity:
+    a_0 = 2 * [ (6, 8) + 0 - (-3, -4) + 0.6 * (5, 0) ] = 2 * (12, 12) = (24, 24).
+    Scaling x_0 by a positive factor leaves a_0 unchanged; vertices without in-neighbours get 0."""
+    src = np.array([1, 2, 3, 4], np.int32)
+    dst = np.zeros(4, np.int32)
+    spec = wl.ModelSpec(wl.AGNN, [2, 2], agnn_beta=2.0)
+    params = wl.Params(W=[[np.eye(2, dtype=np.float32)]], b=[[None]], att_src=[None], att_dst=[None])
+    x = np.array([[3, 4], [6, 8], [-4, 3], [-3, -4], [5, 0]], np.float32)
+    out = oracle.forward(spec, params, 5, src, dst, None, x)[0]
+    np.testing.assert_allclose(out[0], [24.0, 24.0], rtol=1e-14)
+    np.testing.assert_allclose(out[1:], 0.0, atol=0)
+    x2 = x.copy()
+    x2[0] *= 8
+    np.testing.assert_allclose(oracle.forward(spec, params, 5, src, dst, None, x2)[0][0], [24.0, 24.0], rtol=1e-14)
 
 
 def test_commnet_single_edge_by_hand(oracle):
@@ -475,7 +526,7 @@ def test_affected_sets_hand_enumerated(oracle):
         assert [a.tolist() for a in got] == [[3, 4], [3, 4]]
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN])
 def test_affected_sets_match_reachability_powers(oracle, kind):
     n, e = 70, 260
     src, dst, sampler = wl.rmat_graph(n, e, seed=12)
@@ -499,7 +550,7 @@ def test_affected_sets_match_reachability_powers(oracle, kind):
 
 
 # ------------------------------------------------------------------ invariants
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN])
 def test_batch_invariants(oracle, kind):
     n, e = 200, 1500
     src, dst, sampler = wl.rmat_graph(n, e, seed=13)
