@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
     ap.add_argument("--model", choices=["commnet", "pinsage", "agnn"], default=None,
                     help="run another Table II model on the chosen config's graph, widths and batches (not the headline)")
+    ap.add_argument("--agg-only", action="store_true",
+                    help="GCN configs: keep only the aggregates of hidden layers (storage option; not the headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -56,6 +58,9 @@ def main():
         kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE, "agnn": wl.AGNN}[args.model]
         cfg.spec = wl.ModelSpec(kind, list(cfg.spec.dims[:1]) + list(cfg.spec.dims[1:]), weighted=kind == wl.PINSAGE)
         cfg.name = cfg.name + "_as_" + args.model
+    if args.agg_only:
+        cfg.spec.agg_only = True
+        cfg.name = cfg.name + "_agg_only"
     if args.batch_edges:
         frac = cfg.n_ins / max(1, cfg.n_ins + cfg.n_del)
         cfg.n_ins = int(round(args.batch_edges * frac))
@@ -158,6 +163,9 @@ def main():
     mode_ms = {}
     at = args.warmup + 2 * K
     for name, mode in (("incremental_every_layer", 0), ("recompute_affected", 1), ("full_graph", 2)):
+        if args.agg_only and mode != 0:                  # recomputation reads hidden rows, which this cache does not keep
+            mode_ms[name] = None
+            continue
         ses.mode(mode)
         ses.apply(dev_batches[at])                       # one untimed step in the new mode
         torch.cuda.synchronize()
@@ -172,7 +180,7 @@ def main():
     # ---- on-demand leg (Section IV-D): batches only mark vertices stale, each is followed by a query for the
     # final-layer rows of 1000 random vertices, which recomputes the stale part of their L-hop in-neighbourhood
     on_demand = None
-    if cfg.spec.kind not in (wl.GAT, wl.AGNN):
+    if cfg.spec.kind not in (wl.GAT, wl.AGNN) and not args.agg_only:
         rng = np.random.default_rng(args.seed + 77)
         ses.lazy(True)
         t_apply = t_query = 0.0
@@ -235,13 +243,14 @@ def main():
         "update_gemm": {"bound": "mfma", "achieved": round(upd_tflops, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(upd_tflops / FP32_MFMA_PEAK_TFLOPS, 4)},
         "modes_ms_per_step": {"default_incremental_with_auto_recompute_of_saturated_layers": round(ms_per_step, 4),
-                              "incremental_every_layer": round(mode_ms["incremental_every_layer"], 4),
-                              "recompute_affected": round(mode_ms["recompute_affected"], 4),
-                              "full_graph": round(mode_ms["full_graph"], 4), "steps_each": k_modes - 1},
+                              "incremental_every_layer": None if mode_ms["incremental_every_layer"] is None else round(mode_ms["incremental_every_layer"], 4),
+                              "recompute_affected": None if mode_ms["recompute_affected"] is None else round(mode_ms["recompute_affected"], 4),
+                              "full_graph": None if mode_ms["full_graph"] is None else round(mode_ms["full_graph"], 4), "steps_each": k_modes - 1},
         "edges_processed_per_step": {"default_mode_source_rows_fetched": round(sum(pl["n_pairs"] for pl in per_layer) / K),
                                      "recompute_affected_in_edges": round(sum(pl["n_in"] for pl in per_layer) / K),
                                      "full_graph": L * cfg.e},
         "on_demand": on_demand,
+        "cache_workspace_GB": round(ses.cache.ws.numel() * ses.cache.ws.element_size() / 1e9, 3),
         "gpu_full_forward_ms": round(ses.cache.init_ms, 3),   # nrt_cache_init: full-neighbour L-layer forward on the GPU
         "phase_ms_per_step": {k[:-3]: round(v / K, 4) for k, v in agg.items() if k.endswith("_ms")},
         "per_layer_avg": [{"layer": l + 1, "n_src": pl["n_src"] / K, "n_affected": pl["n_aff"] / K,

@@ -91,6 +91,12 @@ typedef struct {
     const float* att_src[NRT_MAX_LAYERS]; /* device, GAT only */
     const float* att_dst[NRT_MAX_LAYERS]; /* device, GAT only */
     float agnn_beta[NRT_MAX_LAYERS];    /* A-GNN only: the scalar of layer l+1 (host values) */
+    int32_t agg_only;                   /* 1: keep only the aggregates of the hidden layers and recompute their rows when
+                                           a batch needs them (Section IV, "Recomputation-based embedding storage
+                                           optimization").  GCN only.  Saves N * (d_1 + ... + d_{L-1}) floats of the
+                                           workspace; such a cache refuses nrt_get_layer for hidden layers,
+                                           NRT_MODE_RECOMPUTE, NRT_MODE_FULL and the on-demand mode, whose kernels
+                                           read those rows.                                                        */
 } nrt_model_desc;
 
 /*

@@ -32,7 +32,7 @@ class nrt_model_desc(ctypes.Structure):
                 ("gin_eps", ctypes.c_float), ("leaky_slope", ctypes.c_float),
                 ("W", (c_fp * 2) * NRT_MAX_LAYERS), ("b", (c_fp * 2) * NRT_MAX_LAYERS),
                 ("att_src", c_fp * NRT_MAX_LAYERS), ("att_dst", c_fp * NRT_MAX_LAYERS),
-                ("agnn_beta", ctypes.c_float * NRT_MAX_LAYERS)]
+                ("agnn_beta", ctypes.c_float * NRT_MAX_LAYERS), ("agg_only", ctypes.c_int32)]
 
 
 class nrt_batch(ctypes.Structure):
@@ -189,6 +189,7 @@ def make_desc(spec, dev_params) -> nrt_model_desc:
     d.gin_eps, d.leaky_slope = spec.gin_eps, spec.leaky_slope
     for l in range(d.n_layers):
         d.agnn_beta[l] = float(getattr(spec, "agnn_beta", 1.0))
+    d.agg_only = int(bool(getattr(spec, "agg_only", False)))
     for l in range(d.n_layers):
         for j, W in enumerate(dev_params["W"][l]):
             d.W[l][j] = W.data_ptr()

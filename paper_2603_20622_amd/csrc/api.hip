@@ -39,6 +39,9 @@ struct nrt_cache {
     int maxd;
     float* H[NRT_MAX_LAYERS + 1];
     float* S[NRT_MAX_LAYERS + 1];
+    int agg_only;                       // hidden-layer rows h^l are not kept, only the aggregates (GCN)
+    float* ES[NRT_MAX_LAYERS + 1];      // agg_only: h^l of the sources of the batch's updated edges, one row per update
+    int32_t* es_rows;                   // agg_only: those sources, inserts first
     float* R[NRT_MAX_LAYERS + 1];       // A-GNN: inverse norms of the rows of h^l (null otherwise)
     float* r_old;                       // A-GNN: [N] compact, inverse norms of the changed rows before the batch
     float agnn_beta[NRT_MAX_LAYERS];
@@ -250,6 +253,10 @@ static nrt_status check_desc(const nrt_model_desc* d) {
             return NRT_ERR_UNSUPPORTED;
         }
     }
+    if (d->agg_only && d->kind != NRT_GCN) {
+        nrt_set_error("aggregate-only storage is available for GCN");
+        return NRT_ERR_UNSUPPORTED;
+    }
     if (d->kind == NRT_GAT) {
         if (d->heads < 1 || d->head_dim < 4 || d->head_dim % 4) {
             nrt_set_error("GAT needs heads >= 1 and head_dim a multiple of 4");
@@ -271,7 +278,12 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     int maxd = 0;
     for (int l = 0; l <= c->L; ++l) maxd = c->dims[l] > maxd ? c->dims[l] : maxd;
     c->maxd = maxd;
-    for (int l = 0; l <= c->L; ++l) c->H[l] = b.take<float>(n * c->dims[l]);
+    for (int l = 0; l <= c->L; ++l) {
+        const bool hidden = l >= 1 && l < c->L;
+        c->H[l] = (c->agg_only && hidden) ? nullptr : b.take<float>(n * c->dims[l]);
+        c->ES[l] = (c->agg_only && hidden) ? b.take<float>((size_t)(c->max_edges + 1) * c->dims[l]) : nullptr;
+    }
+    c->es_rows = c->agg_only ? b.take<int32_t>(c->max_edges + 1) : nullptr;
     for (int l = 0; l <= c->L; ++l) c->MP[l] = (c->kind == NRT_PINSAGE && l < c->L) ? b.take<float>(n * c->dims[l]) : nullptr;
     for (int l = 0; l <= c->L; ++l) c->R[l] = (c->kind == NRT_AGNN && l < c->L) ? b.take<float>(n) : nullptr;
     c->r_old = c->kind == NRT_AGNN ? b.take<float>(n) : nullptr;
@@ -372,6 +384,7 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     c->gin_eps = d->gin_eps;
     c->leaky_slope = d->leaky_slope;
     for (int l = 0; l < c->L; ++l) c->agnn_beta[l] = d->agnn_beta[l];
+    c->agg_only = d->agg_only ? 1 : 0;
     c->max_edges = max_edges;
     c->max_feats = max_feats;
     return NRT_OK;
@@ -631,6 +644,36 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
     return NRT_OK;
 }
 
+// Aggregate-only storage (GCN, hidden layer l): h^l of the listed rows from the cached aggregate and the given degree
+// vector, not stored by vertex.  out_compact: the rows themselves; dp with dp_no_h 1: minus their payload (old degrees),
+// 2: plus their payload added to what dp holds.
+static nrt_status run_update_unkept(nrt_cache* c, int l, const int32_t* rows, int64_t M, const uint64_t* M_dev,
+                                    const int32_t* indeg, float* out_compact, int64_t out_cap, float* dp, int dp_no_h,
+                                    hipStream_t s) {
+    GemmArgs a;
+    memset(&a, 0, sizeof(a));
+    a.M = M;
+    a.M_dev = M_dev;
+    a.rows = rows;
+    a.indeg = indeg;
+    a.indeg_old = c->indeg_old;
+    a.ldp = c->dims[l - 1];
+    a.K = c->dims[l - 1];
+    a.N = c->dims[l];
+    a.a_mode = A_SCALE_GCN;
+    a.P0 = c->S[l];
+    a.Wt = c->Wt[l - 1][0];
+    a.bias = c->bias[l - 1][0];
+    a.act = 1;
+    a.DP = dp;
+    a.dp_no_h = dp_no_h;
+    a.dp_scale_gcn = 1;
+    a.n_vertices = c->g->n;
+    a.out_compact = out_compact;
+    a.out_cap = out_cap;
+    return k_gemm(a, s);
+}
+
 // One A-GNN layer: norms of the changed rows of h^{l-1} (src_rows null: all rows), the cosine-weighted gather over the
 // destinations described by c->recs (listed in `rows`, null: all n), the sums of long in-lists, the dense update.
 static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
@@ -710,6 +753,8 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
     NRT_TRY(k_fill_u64(&all->count, 1, (uint64_t)n, s));
     c->lc_use = all;
     nrt_status st = NRT_OK;
+    if (c->agg_only)                       // hidden rows live in the two delta buffers while the aggregates are built
+        for (int l = 1; l < c->L; ++l) c->H[l] = c->DP[l & 1];
     for (int l = 1; l <= c->L && st == NRT_OK; ++l) {
         if (c->kind == NRT_GAT) {
             st = run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, false, 0, nullptr, 0, s);
@@ -724,6 +769,8 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
         if (st == NRT_OK) st = run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, false, s);
     }
     c->lc_use = nullptr;
+    if (c->agg_only)
+        for (int l = 1; l < c->L; ++l) c->H[l] = nullptr;
     return st;
 }
 
@@ -872,7 +919,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     // (no extra launches for small frontiers); the device counters of this batch take the decision
     bool may_rec[NRT_MAX_LAYERS + 2];
     for (int l = 0; l <= c->L + 1; ++l)
-        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && c->kind != NRT_AGNN && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
+        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && c->kind != NRT_AGNN && !c->agg_only && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     if (!empty_batch) NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, n, s));
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     if (inc && b->n_ins + b->n_del > 0) {
@@ -916,12 +963,20 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         f.n_ins = b->n_ins; f.n_del = b->n_del;
         f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
         if (weighted_messages(c->kind) && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
+        if (c->agg_only && c->L > 1 && b->n_ins + b->n_del > 0) {
+            // the hidden rows of the updated edges' sources are not kept: recompute them from the (old) aggregates
+            const int64_t nops = b->n_ins + b->n_del;
+            NRT_TRY(k_concat_ids(c->es_rows, b->ins_src, b->n_ins, b->del_src, b->n_del, n, s));
+            for (int l = 1; l < c->L; ++l)
+                NRT_TRY(run_update_unkept(c, l, c->es_rows, nops, nullptr, g->in.deg, c->ES[l], nops, nullptr, 0, s));
+        }
         f.indeg_old = gcn ? g->in.deg : nullptr;
         f.n_layers = c->L;
         f.n = n;
         f.dd_slot = c->slot_dd;
         for (int l = 1; l <= c->L; ++l) {
             f.Hprev[l - 1] = payload_rows(c, l - 1);
+            if (c->agg_only && l - 1 >= 1) { f.Hprev[l - 1] = c->ES[l - 1]; f.compact_src[l - 1] = 1; }
             f.SD[l - 1] = c->SD[l];
             f.D[l - 1] = c->dagg[l];
         }
@@ -1031,9 +1086,17 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             if (c->kind == NRT_PINSAGE)
                 NRT_TRY(run_transform(c, l - 1, c->list[l - 1], src_bound, &c->lc[l - 1].count, inc ? c->DP[prev] : nullptr,
                                       may_rec[l], s));
-            NRT_TRY(run_gather(c, l, inc, prev, may_rec[l], sparse_hint, s));
-            NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, inc, cur, l == c->L ? affected_rows : nullptr,
-                               capacity, may_rec[l + 1], s));
+            if (c->agg_only && l < c->L) {
+                // the layer's rows are not kept: the payload deltas of its affected rows are minus the old payload,
+                // computed from the aggregate before the fold, plus the new one, computed after it
+                NRT_TRY(run_update_unkept(c, l, c->list[l], n, &c->lc[l].count, c->indeg_old, nullptr, 0, c->DP[cur], 1, s));
+                NRT_TRY(run_gather(c, l, inc, prev, false, sparse_hint, s));
+                NRT_TRY(run_update_unkept(c, l, c->list[l], n, &c->lc[l].count, g->in.deg, nullptr, 0, c->DP[cur], 2, s));
+            } else {
+                NRT_TRY(run_gather(c, l, inc, prev, may_rec[l], sparse_hint, s));
+                NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, inc, cur, l == c->L ? affected_rows : nullptr,
+                                   capacity, may_rec[l + 1], s));
+            }
         }
         NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
         prev = cur;
@@ -1092,6 +1155,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
 extern "C" nrt_status nrt_get_layer(const nrt_cache* c, int32_t layer, const float** rows, int64_t* n_rows, int64_t* ld) {
     REQUIRE(c && rows && n_rows && ld, "null argument");
     REQUIRE(layer >= 0 && layer <= c->L, "layer out of range");
+    if (!c->H[layer]) { nrt_set_error("the rows of hidden layers are not kept with aggregate-only storage"); return NRT_ERR_UNSUPPORTED; }
     *rows = c->H[layer];
     *n_rows = c->g->n;
     *ld = c->dims[layer];
@@ -1149,8 +1213,8 @@ static nrt_status finish_recompute(nrt_cache* c, int64_t* n_recomputed, hipStrea
 
 extern "C" nrt_status nrt_set_lazy(nrt_cache* c, int32_t on, void* stream) {
     REQUIRE(c, "null argument");
-    if (c->kind == NRT_GAT || c->kind == NRT_AGNN) {
-        nrt_set_error("on-demand mode is not available for GAT and A-GNN");
+    if (c->kind == NRT_GAT || c->kind == NRT_AGNN || c->agg_only) {
+        nrt_set_error("on-demand mode is not available for GAT, A-GNN and aggregate-only storage");
         return NRT_ERR_UNSUPPORTED;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1218,6 +1282,10 @@ extern "C" nrt_status nrt_set_mode(nrt_cache* c, int32_t mode) {
     REQUIRE(c, "null argument");
     REQUIRE(mode == NRT_MODE_INCREMENTAL || mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL || mode == NRT_MODE_AUTO,
             "unknown mode");
+    if (c->agg_only && (mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL)) {
+        nrt_set_error("with aggregate-only storage the hidden rows that recomputation reads are not kept");
+        return NRT_ERR_UNSUPPORTED;
+    }
     c->mode = mode;
     return NRT_OK;
 }

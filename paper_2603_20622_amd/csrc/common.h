@@ -102,6 +102,8 @@ nrt_status k_gather_rows(float* dst, const float* src, const int32_t* list, cons
 nrt_status k_fill_u64(uint64_t* p, int64_t n, uint64_t v, hipStream_t s);
 nrt_status k_or_words(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t nwords, hipStream_t s);
 nrt_status k_copy_i32(int32_t* dst, const int32_t* src, int64_t n, hipStream_t s);
+// dst = [a | b] with every id outside [0, n) replaced by 0
+nrt_status k_concat_ids(int32_t* dst, const int32_t* a, int64_t na, const int32_t* b, int64_t nb, int64_t n, hipStream_t s);
 nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
 // dst[0 .. min(*count, cap)) = src[...]
 nrt_status k_copy_counted_i32(int32_t* dst, const int32_t* src, const uint64_t* count, int64_t cap, int64_t bound, hipStream_t s);
@@ -215,6 +217,7 @@ struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update 
     const int32_t* dd_slot;               // vertex -> row of SD
     int D[NRT_MAX_LAYERS];
     const int32_t* indeg_old;    // for the GCN payload scale, else null
+    int compact_src[NRT_MAX_LAYERS];      // Hprev[l] holds one row per updated edge (inserts first) instead of one per vertex
 };
 nrt_status k_structural_fold(const FoldArgs& a, hipStream_t s);
 
@@ -249,6 +252,8 @@ struct GemmArgs {
     const int32_t* indeg_old;       // GCN payload scale for DP (with indeg as new), else null
     int dp_scale_gcn;
     int dp_store_old;               // DP receives the overwritten row of H instead of a payload delta (GAT: old z)
+    int dp_no_h;                    // H null (rows of the layer are not kept): 1: DP = -(old payload), computed from the
+                                    // aggregate before the fold; 2: DP += new payload, computed after it
     int dp_skip_large;              // leave DP (and the read of the old rows) out when 4 * rows > n_vertices
     int64_t n_vertices;
 };

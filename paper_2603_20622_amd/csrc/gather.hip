@@ -834,7 +834,7 @@ __global__ void structural_fold_kernel(FoldArgs a) {
     if (!is_del && a.ins_w) c *= a.ins_w[i];
     if (a.indeg_old) c *= gcn_scale(a.indeg_old[u]);
     const int D = a.D[l];
-    const float* src = a.Hprev[l] + (int64_t)u * D;
+    const float* src = a.Hprev[l] + (a.compact_src[l] ? op : (int64_t)u) * D;
     float* dst = a.SD[l] + (int64_t)a.dd_slot[v] * D;
     for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, c * src[k]);
 }

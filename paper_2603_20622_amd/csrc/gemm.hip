@@ -184,7 +184,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
                 for (int j = 0; j < TN; ++j) {
                     const int n = col_base + (wn * TN + j) * 32 + l32;
                     const int nc = n < g.N ? n : g.N - 1;
-                    oldv[rr][j] = DPout ? g.H[vrow[rr] * g.N + nc] : 0.f;   // vrow is 0 for rows past M: always in range
+                    if (g.H) oldv[rr][j] = DPout ? g.H[vrow[rr] * g.N + nc] : 0.f;   // vrow is 0 for rows past M: always in range
+                    else oldv[rr][j] = (DPout && g.dp_no_h == 2) ? DPout[(ok ? mrow[rr] : 0) * g.N + nc] : 0.f;
                 }
             }
 #pragma unroll
@@ -201,6 +202,9 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
                     if (g.H) {
                         if (DPout) DPout[mrow[rr] * g.N + n] = g.dp_store_old ? oldv[rr][j] : y * cn[rr] - oldv[rr][j] * co[rr];
                         g.H[vrow[rr] * g.N + n] = y;
+                    } else if (DPout) {       // the layer's rows are not kept: the payload delta is built by two launches
+                        if (g.dp_no_h == 1) DPout[mrow[rr] * g.N + n] = -y * co[rr];
+                        else if (g.dp_no_h == 2) DPout[mrow[rr] * g.N + n] = oldv[rr][j] + y * cn[rr];
                     }
                 }
             }

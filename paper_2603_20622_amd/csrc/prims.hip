@@ -81,6 +81,14 @@ __global__ void or_words_kernel(uint32_t* dst, const uint32_t* a, const uint32_t
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (; i < n; i += stride) dst[i] = a[i] | (b ? b[i] : 0u);
 }
+__global__ void concat_ids_kernel(int32_t* dst, const int32_t* a, int64_t na, const int32_t* b, int64_t nb, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (; i < na + nb; i += stride) {
+        const int32_t v = i < na ? a[i] : b[i - na];
+        dst[i] = (v >= 0 && v < n) ? v : 0;
+    }
+}
 __global__ void copy_u32_kernel(uint32_t* dst, const uint32_t* src, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -288,6 +296,12 @@ nrt_status k_gather_rows_checked(float* dst, const float* src, const int32_t* id
 nrt_status k_or_words(uint32_t* dst, const uint32_t* a, const uint32_t* b, int64_t nwords, hipStream_t s) {
     if (nwords <= 0) return NRT_OK;
     or_words_kernel<<<grid_for(nwords, 256), 256, 0, s>>>(dst, a, b, nwords);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_concat_ids(int32_t* dst, const int32_t* a, int64_t na, const int32_t* b, int64_t nb, int64_t n, hipStream_t s) {
+    if (na + nb <= 0) return NRT_OK;
+    concat_ids_kernel<<<grid_for(na + nb, 256), 256, 0, s>>>(dst, a, na, b, nb, n);
     LAUNCH_CHECK();
     return NRT_OK;
 }

@@ -33,6 +33,7 @@ class ModelSpec:
     leaky_slope: float = 0.2
     weighted: bool = False
     agnn_beta: float = 1.0          # A-GNN: the scalar in front of the cosine (the same at every layer)
+    agg_only: bool = False          # GCN: keep only the aggregates of hidden layers (storage option of the cache)
 
     @property
     def n_layers(self) -> int:

@@ -510,6 +510,59 @@ def test_large_batches_pack_updates_per_wave(S, oracle, kind):
     assert np.array_equal(key3, np.sort(cur[0].astype(np.int64) * n + cur[1]))
 
 
+def test_gcn_aggregate_only_storage(S, oracle):
+    """The storage option of Section IV ("recomputation-based embedding storage optimization"): a GCN cache that
+    keeps the aggregates of its hidden layers but not their rows, and recomputes the rows a batch needs (old and new
+    rows of the affected vertices, rows of the sources of updated edges).  Same affected sets, same final layer,
+    same aggregates as the oracle; a smaller workspace; and the calls that would read hidden rows are refused."""
+    import dataclasses
+    from paper_2603_20622_amd import binding as nb
+    n, src, dst, w, x, spec, params, stream = small_case(wl.GCN, seed=9, L=3)
+    lean_spec = dataclasses.replace(spec, agg_only=True)
+    ses = S.Session(lean_spec, params, n, src, dst, w, x)
+    kept = nb.nrt_cache_workspace_bytes(ses.graph, nb.make_desc(spec, ses.dev_params), 1 << 16, 1 << 12)
+    lean = nb.nrt_cache_workspace_bytes(ses.graph, ses.desc, 1 << 16, 1 << 12)
+    hidden_bytes = 4 * n * (spec.dims[1] + spec.dims[2])
+    edge_rows_bytes = 4 * ((1 << 16) + 1) * (spec.dims[1] + spec.dims[2] + 1)
+    assert lean <= kept - hidden_bytes + edge_rows_bytes + 4096
+    cur = (src, dst, w, x)
+    ref = oracle.forward(spec, params, n, *cur)
+    assert rel_err(ses.layer(3).cpu().numpy(), ref[-1]) <= TOL
+    for k in range(6):
+        batch = stream.next_batch(40, 40, 12 if k % 2 == 0 else 0)
+        na = ses.apply(batch)
+        cur = oracle.apply_batch(n, *cur, batch)
+        ref = oracle.forward(spec, params, n, *cur)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], batch)
+        ids = ses.ids[:na].cpu().numpy()
+        assert np.array_equal(ids, sets[-1])
+        for l in range(1, 4):
+            assert np.array_equal(ses.affected(l), sets[l - 1])
+        assert rel_err(ses.layer(3).cpu().numpy(), ref[-1]) <= TOL, k
+        assert np.array_equal(ses.rows[:na].cpu().numpy(), ses.layer(3).cpu().numpy()[ids])
+        # the cached aggregates are the sums over N(v) U {v} of h^{l-1}/sqrt(d): check them against the oracle's layers
+        deg = np.bincount(cur[1], minlength=n).astype(np.float64) + 1.0
+        hs = [cur[3].astype(np.float64)] + ref
+        for l in range(1, 4):
+            p = hs[l - 1] / np.sqrt(deg)[:, None]
+            want = oracle.in_sum(n, cur[0], cur[1], None, p) + p
+            assert rel_err(ses.aggregate(l).cpu().numpy(), want) <= TOL, (k, l)
+    for l in (1, 2):
+        with pytest.raises(nb.NrtError) as ei:
+            ses.layer(l)
+        assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
+    for call in (lambda: ses.mode(nb.NRT_MODE_RECOMPUTE), lambda: ses.mode(nb.NRT_MODE_FULL), lambda: ses.lazy(True)):
+        with pytest.raises(nb.NrtError) as ei:
+            call()
+        assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
+    ses.mode(nb.NRT_MODE_INCREMENTAL)
+    # only GCN has the option
+    n2, s2, d2, w2, x2, spec2, params2, _ = small_case(wl.SAGE_MEAN, seed=9)
+    with pytest.raises(nb.NrtError) as ei:
+        S.Session(dataclasses.replace(spec2, agg_only=True), params2, n2, s2, d2, w2, x2)
+    assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
+
+
 def test_widest_rows(S, oracle):
     """1024-wide aggregates (four 16-byte loads per lane in the gather, K = 1024 in the update)."""
     n, e = 800, 6000
