@@ -8,8 +8,8 @@
 // caches, folded into one compact row per destination before the graph changes, exactly as for the other models.
 //
 // Cached per layer: h^{l-1} (the layer input), the inverse norm of each of its rows (0 for a zero row, whose cosine
-// is taken as 0), and the aggregate a_v.  Destinations with long in-lists are always summed in full through their
-// items (partial rows, added up by the common combine kernel).
+// is taken as 0), and the aggregate a_v.  Destinations with long in-lists are served through their items (partial
+// rows of the sum or of the exchange), added up by the combine kernel below.
 #include "common.h"
 
 namespace {
@@ -62,6 +62,64 @@ __device__ inline void add_terms(const float* (&row)[AG_TERMS], const float (&c)
     }
 }
 
+// acc += the terms of in-list entries [base, base + cnt) for destination row hv (cv = w / |h_v|): every entry when
+// `full`, else the exchange new - old of the entries whose source changed.  Returns the number of rows' sources used.
+template <int NV>
+__device__ inline int sum_terms(const AgnnArgs& a, int64_t base, int32_t cnt, bool full, const float4 (&hv)[NV], float cv,
+                                float4 (&acc)[NV], const bool (&live)[NV], int lane) {
+    const int D = a.D;
+    int pairs = 0;
+    for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
+        const int32_t j = j0 + lane;
+        const int32_t u = j < cnt ? a.in.idx[base + j] : -1;
+        bool take = u >= 0;
+        int32_t slot = 0;
+        if (!full) {
+            take = take && in_set(a.src_bitmap, u);
+            if (take) slot = a.src_slot[u];
+        }
+        const float ru = take ? a.R[u] : 0.f;
+        const float ro = (take && !full) ? a.old_r[slot] : 0.f;
+        unsigned long long m = __ballot(take);
+        pairs += __popcll(m);
+        // in in-list order, AG_TERMS rows at a time: the sum does not depend on the schedule
+        while (m) {
+            const float* row[AG_TERMS];
+            float c[AG_TERMS];
+            int nt = 0;
+            if (full) {
+#pragma unroll
+                for (int t = 0; t < AG_TERMS; ++t) {
+                    row[t] = a.H; c[t] = 0.f;
+                    if (m) {
+                        const int b = __ffsll((long long)m) - 1;
+                        m &= m - 1;
+                        row[t] = a.H + (int64_t)__shfl(u, b, 64) * D;
+                        c[t] = cv * __shfl(ru, b, 64);
+                        nt = t + 1;
+                    }
+                }
+            } else {                                      // the new term of a changed in-neighbour minus its old one
+#pragma unroll
+                for (int t = 0; t < AG_TERMS; t += 2) {
+                    row[t] = a.H; c[t] = 0.f; row[t + 1] = a.H; c[t + 1] = 0.f;
+                    if (m) {
+                        const int b = __ffsll((long long)m) - 1;
+                        m &= m - 1;
+                        row[t] = a.H + (int64_t)__shfl(u, b, 64) * D;
+                        c[t] = cv * __shfl(ru, b, 64);
+                        row[t + 1] = a.old_rows + (int64_t)__shfl(slot, b, 64) * D;
+                        c[t + 1] = -cv * __shfl(ro, b, 64);
+                        nt = t + 2;
+                    }
+                }
+            }
+            add_terms<NV>(row, c, nt, hv, acc, live, lane);
+        }
+    }
+    return pairs;
+}
+
 // R[v] = 1 / |h_v| for the listed rows (list null: rows 0 .. n_all); r_old[m] keeps the value it replaces
 __global__ void agnn_norms_kernel(const int32_t* list, const uint64_t* count_dev, int64_t bound, const float* H, int D,
                                   float* R, float* r_old) {
@@ -106,19 +164,20 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
         int32_t cnt;
         int64_t base;
         bool part;
+        int32_t chunk = 0;
         if (unit >= n_items) {
             rec = a.recs[unit - n_items];
             if (rec.deg > NRT_CHUNK) continue;               // served through its items
             cnt = rec.deg; base = rec.off; part = false;
         } else {
-            const int32_t chunk = a.hubs.item_chunk[unit];
+            chunk = a.hubs.item_chunk[unit];
             rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[unit]]];
             cnt = min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK);
             base = rec.off + (int64_t)chunk * NRT_CHUNK;
             part = true;
         }
         const int32_t v = rec.v;
-        bool full = part || !a.incremental || in_set(a.src_bitmap, v);   // uniform over the wave
+        bool full = !a.incremental || in_set(a.src_bitmap, v);   // uniform over the wave
         float4 hv[NV], acc[NV];
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
@@ -131,59 +190,23 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
       for (;;) {
 #pragma unroll
         for (int q = 0; q < NV; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
-            const int32_t j = j0 + lane;
-            const int32_t u = j < cnt ? a.in.idx[base + j] : -1;
-            bool take = u >= 0;
-            int32_t slot = 0;
-            if (!full) {
-                take = take && in_set(a.src_bitmap, u);
-                if (take) slot = a.src_slot[u];
-            }
-            const float ru = take ? a.R[u] : 0.f;
-            const float ro = (take && !full) ? a.old_r[slot] : 0.f;
-            unsigned long long m = __ballot(take);
-            pairs += __popcll(m);
-            // in in-list order, AG_TERMS rows at a time: the sum does not depend on the schedule
-            while (m) {
-                const float* row[AG_TERMS];
-                float c[AG_TERMS];
-                int nt = 0;
-                if (full) {
-#pragma unroll
-                    for (int t = 0; t < AG_TERMS; ++t) {
-                        row[t] = a.H; c[t] = 0.f;
-                        if (m) {
-                            const int b = __ffsll((long long)m) - 1;
-                            m &= m - 1;
-                            row[t] = a.H + (int64_t)__shfl(u, b, 64) * D;
-                            c[t] = cv * __shfl(ru, b, 64);
-                            nt = t + 1;
-                        }
-                    }
-                } else {                                      // the new term of a changed in-neighbour minus its old one
-#pragma unroll
-                    for (int t = 0; t < AG_TERMS; t += 2) {
-                        row[t] = a.H; c[t] = 0.f; row[t + 1] = a.H; c[t + 1] = 0.f;
-                        if (m) {
-                            const int b = __ffsll((long long)m) - 1;
-                            m &= m - 1;
-                            row[t] = a.H + (int64_t)__shfl(u, b, 64) * D;
-                            c[t] = cv * __shfl(ru, b, 64);
-                            row[t + 1] = a.old_rows + (int64_t)__shfl(slot, b, 64) * D;
-                            c[t + 1] = -cv * __shfl(ro, b, 64);
-                            nt = t + 2;
-                        }
-                    }
-                }
-                add_terms<NV>(row, c, nt, hv, acc, live, lane);
-            }
-        }
+        pairs += sum_terms<NV>(a, base, cnt, full, hv, cv, acc, live, lane);
 
         if (part) {
+            // an item holds its share of the whole sum, or of the exchange (the first item also takes the structural
+            // terms); the combine kernel adds the items up and, for an exchange, applies the guard
+            const bool dd0 = !full && chunk == 0 && a.sd && in_set(a.dd_bitmap, v);
+            const float* sd0 = dd0 ? a.sd + (int64_t)a.dd_slot[v] * D : nullptr;
 #pragma unroll
-            for (int q = 0; q < NV; ++q)
-                if (live[q]) *reinterpret_cast<float4*>(a.hubs.partial + unit * D + lane * 4 + q * 256) = acc[q];
+            for (int q = 0; q < NV; ++q) {
+                if (!live[q]) continue;
+                float4 d = acc[q];
+                if (dd0) {
+                    const float4 e = *reinterpret_cast<const float4*>(sd0 + lane * 4 + q * 256);
+                    d.x += e.x; d.y += e.y; d.z += e.z; d.w += e.w;
+                }
+                *reinterpret_cast<float4*>(a.hubs.partial + unit * D + lane * 4 + q * 256) = d;
+            }
             break;
         }
         float* out = a.S + (int64_t)v * D;
@@ -229,6 +252,72 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
     if (a.pair_ctr && lane == 0 && pairs) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)pairs);
 }
 
+// One wave per destination with a long in-list: its items' rows are added up in item order.  They are the whole sum when
+// the destination's own row changed (or nothing is incremental), else an exchange that is added to the cached
+// aggregate under the same guard as above; a guarded destination is summed again over its whole in-list by this wave.
+template <int NV>
+__global__ void __launch_bounds__(AG_WAVES * 64) agnn_combine_kernel(AgnnArgs a) {
+    const int lane = threadIdx.x & 63;
+    const int D = a.D;
+    int64_t nh = (int64_t)a.lc->n_hubs;
+    if (nh > a.hubs.hub_cap) nh = a.hubs.hub_cap;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    bool live[NV];
+#pragma unroll
+    for (int q = 0; q < NV; ++q) live[q] = lane * 4 + q * 256 < D;
+    for (int64_t h = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; h < nh; h += waves) {
+        const DstRec rec = a.recs[a.hubs.hub_slot[h]];
+        const int32_t nch = (rec.deg + NRT_CHUNK - 1) / NRT_CHUNK;
+        const int64_t first = (int64_t)a.hubs.hub_first[h];
+        const int32_t v = rec.v;
+        const bool full = !a.incremental || in_set(a.src_bitmap, v);
+        float4 tot[NV];
+#pragma unroll
+        for (int q = 0; q < NV; ++q) tot[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int32_t c = 0; c < nch; ++c) {
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                if (!live[q]) continue;
+                const float4 x = *reinterpret_cast<const float4*>(a.hubs.partial + (first + c) * D + lane * 4 + q * 256);
+                tot[q].x += x.x; tot[q].y += x.y; tot[q].z += x.z; tot[q].w += x.w;
+            }
+        }
+        float* out = a.S + (int64_t)v * D;
+        bool redo = false;
+        if (!full) {
+            float big = 0.f, left = 0.f;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                if (!live[q]) continue;
+                const float4 o = *reinterpret_cast<const float4*>(out + lane * 4 + q * 256);
+                const float4 d = tot[q];
+                tot[q] = make_float4(o.x + d.x, o.y + d.y, o.z + d.z, o.w + d.w);
+                big = fmaxf(big, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
+                left = fmaxf(left, fmaxf(fmaxf(fabsf(tot[q].x), fabsf(tot[q].y)), fmaxf(fabsf(tot[q].z), fabsf(tot[q].w))));
+            }
+#pragma unroll
+            for (int sft = 32; sft >= 1; sft >>= 1) {
+                big = fmaxf(big, __shfl_xor(big, sft, 64));
+                left = fmaxf(left, __shfl_xor(left, sft, 64));
+            }
+            redo = big > AG_GUARD_RATIO * left;
+        }
+        if (redo) {
+            float4 hv[NV];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                hv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                tot[q] = hv[q];
+                if (live[q]) hv[q] = *reinterpret_cast<const float4*>(a.H + (int64_t)v * D + lane * 4 + q * 256);
+            }
+            sum_terms<NV>(a, rec.off, rec.deg, true, hv, a.beta * a.R[v], tot, live, lane);
+        }
+#pragma unroll
+        for (int q = 0; q < NV; ++q)
+            if (live[q]) *reinterpret_cast<float4*>(out + lane * 4 + q * 256) = tot[q];
+    }
+}
+
 // one wave per (updated edge, layer): SD^l[slot(dst)] += sign * w * cos(h_dst, h_src) * h_src on the old caches
 __global__ void agnn_structural_fold_kernel(AgnnFoldArgs a) {
     const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
@@ -268,6 +357,14 @@ nrt_status k_agnn_gather(const AgnnArgs& a, hipStream_t s) {
     if (a.D <= 256) agnn_gather_kernel<1><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
     else if (a.D <= 512) agnn_gather_kernel<2><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
     else agnn_gather_kernel<4><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_agnn_combine(const AgnnArgs& a, hipStream_t s) {
+    if (a.D <= 256) agnn_combine_kernel<1><<<1024, AG_WAVES * 64, 0, s>>>(a);
+    else if (a.D <= 512) agnn_combine_kernel<2><<<1024, AG_WAVES * 64, 0, s>>>(a);
+    else agnn_combine_kernel<4><<<1024, AG_WAVES * 64, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }

@@ -709,16 +709,7 @@ static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, c
     }
     NRT_TRY(k_agnn_gather(a, s));
     NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
-    GatherArgs cmb;                               // long in-lists: their items hold whole partial sums
-    memset(&cmb, 0, sizeof(cmb));
-    cmb.recs = c->recs;
-    cmb.hubs = c->hubs;
-    cmb.lc = a.lc;
-    cmb.in = g->in;
-    cmb.D = D;
-    cmb.S = c->S[l];
-    cmb.n_vertices = g->n;
-    NRT_TRY(k_combine_partials(cmb, s));
+    NRT_TRY(k_agnn_combine(a, s));
     NRT_TRY(prof_mark(c, TAG_COMBINE, l, s));
     GemmArgs u;
     memset(&u, 0, sizeof(u));

@@ -348,6 +348,7 @@ struct AgnnFoldArgs {   // structural terms of a batch, evaluated on the pre-upd
 nrt_status k_agnn_norms(const int32_t* list, const uint64_t* count_dev, int64_t bound, const float* H, int D, float* R,
                         float* r_old, hipStream_t s);
 nrt_status k_agnn_gather(const AgnnArgs& a, hipStream_t s);
+nrt_status k_agnn_combine(const AgnnArgs& a, hipStream_t s);   // after the gather, same arguments: destinations with long in-lists
 nrt_status k_agnn_structural_fold(const AgnnFoldArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------- graph.hip
