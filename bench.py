@@ -34,7 +34,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
-    ap.add_argument("--model", choices=["commnet", "pinsage", "agnn"], default=None,
+    ap.add_argument("--model", choices=["commnet", "pinsage", "agnn", "monet"], default=None,
                     help="run another Table II model on the chosen config's graph, widths and batches (not the headline)")
     ap.add_argument("--agg-only", action="store_true",
                     help="GCN configs: keep only the aggregates of hidden layers (storage option; not the headline)")
@@ -55,8 +55,9 @@ def main():
 
     cfg = wl.config(args.config, args.scale)
     if args.model:
-        kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE, "agnn": wl.AGNN}[args.model]
-        cfg.spec = wl.ModelSpec(kind, list(cfg.spec.dims[:1]) + list(cfg.spec.dims[1:]), weighted=kind == wl.PINSAGE)
+        kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE, "agnn": wl.AGNN, "monet": wl.MONET}[args.model]
+        cfg.spec = wl.ModelSpec(kind, list(cfg.spec.dims[:1]) + list(cfg.spec.dims[1:]), weighted=kind == wl.PINSAGE,
+                                monet_kernels=64)
         cfg.name = cfg.name + "_as_" + args.model
     if args.agg_only:
         cfg.spec.agg_only = True
@@ -122,10 +123,12 @@ def main():
             # algorithmic bytes of the gather launch: per delta message its in-list id and slot-map entry (8 B);
             # the delta rows: every changed source row once (4*d) while the delta buffer fits the 256 MB Infinity
             # Cache, else one row per delta message; every affected aggregate row read and written (8*d)
-            d_agg = dims[l + 1] if cfg.spec.kind == wl.GAT else d_in
+            d_agg = dims[l + 1] if cfg.spec.kind == wl.GAT else (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)
             row_fetches = ls.n_src if ls.n_src * 4.0 * d_agg <= INFINITY_CACHE_BYTES else ls.n_pairs
             gbytes = ls.n_pairs * 8.0 + row_fetches * 4.0 * d_agg + ls.n_affected * 8.0 * d_agg if ls.n_src else 0.0
-            kin = (2 if cfg.spec.kind in (wl.SAGE_MEAN, wl.COMMNET) else 1) * d_in
+            kin = (2 if cfg.spec.kind in (wl.SAGE_MEAN, wl.COMMNET, wl.PINSAGE) else 1) * d_in
+            if cfg.spec.kind == wl.MONET:
+                kin = d_agg
             flop = 2.0 * ls.n_affected * kin * dims[l + 1]
             if cfg.spec.kind == wl.GIN:
                 flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]

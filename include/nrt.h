@@ -51,7 +51,7 @@ typedef enum {
     NRT_ERR_UNSUPPORTED = 6  /* model shape outside what the kernels cover                            */
 } nrt_status;
 
-typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7 } nrt_model_kind;
+typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7, NRT_MONET = 8 } nrt_model_kind;
 
 typedef struct nrt_graph nrt_graph;
 typedef struct nrt_cache nrt_cache;
@@ -76,6 +76,10 @@ typedef struct nrt_cache nrt_cache;
  *   NRT_AGNN      (Table II row A-GNN)  a_v = sum_{u in N(v)} agnn_beta[l] * cos(x_v, x_u) * x_u, the cosine of a
  *                 zero row taken as 0;  h_v = act( a_v W[l][0] + b[l][0] ).  The message reads the destination's own
  *                 row: a "constrained" model (Section III-D), recomputed in full where that row changed
+ *   NRT_MONET     (Table II row MoNet)  J = monet_kernels Gaussian kernels per layer with means monet_mu[l] and diagonal
+ *                 precisions monet_prec[l] (both [J][d_{l-1}], precisions >= 0):
+ *                 g_j(x) = exp( -1/2 sum_k monet_prec[l][j][k] (x_k - monet_mu[l][j][k])^2 );
+ *                 a_v = sum_{u in N(v)} g(x_u)  (a J-vector);  h_v = act( a_v W[l][0] + b[l][0] ),  W[l][0] is [J][d_l]
  * W, b, att_* are device pointers, row-major [in][out] / [heads][head_dim]; b entries may be NULL (zero).
  * They are copied at nrt_cache_init.
  */
@@ -91,6 +95,9 @@ typedef struct {
     const float* att_src[NRT_MAX_LAYERS]; /* device, GAT only */
     const float* att_dst[NRT_MAX_LAYERS]; /* device, GAT only */
     float agnn_beta[NRT_MAX_LAYERS];    /* A-GNN only: the scalar of layer l+1 (host values) */
+    int32_t monet_kernels;              /* MoNet only: J, a multiple of 4 in [4, 1024] */
+    const float* monet_mu[NRT_MAX_LAYERS];   /* device, MoNet only */
+    const float* monet_prec[NRT_MAX_LAYERS]; /* device, MoNet only */
     int32_t agg_only;                   /* 1: keep only the aggregates of the hidden layers and recompute their rows when
                                            a batch needs them (Section IV, "Recomputation-based embedding storage
                                            optimization").  GCN only.  Saves N * (d_1 + ... + d_{L-1}) floats of the

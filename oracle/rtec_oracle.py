@@ -38,6 +38,12 @@ Readings taken where the paper is silent or garbled (the GPU path takes the same
   * A-GNN: a_v = sum_{u in N(v)} w cos(h_v, h_u) h_u exactly as its Table II row prints it (no softmax, no
     self-loop); the cosine with a zero row is 0; a vertex affected at layer l-1 is affected at layer l because
     its own row enters every one of its messages.
+  * MoNet: its Table II row prints exp(1/2 (h_u - w_u)^t W_j (h_u - w_u)) with f_nn = 1 and update ReLU(W a_v).
+    Read as the Gaussian mixture kernels of MoNet evaluated on the source row: J kernels per layer with mean mu_j
+    and a diagonal precision, g_j(h_u) = exp(-1/2 sum_k prec_jk (h_uk - mu_jk)^2) (the sign of the exponent is lost
+    in the printed row), the aggregate is the J-vector of summed responses and W maps J to the layer width.  No
+    self term in the row; a vertex affected at layer l-1 stays affected at layer l (the structural rule of all
+    models here), its row then simply does not change unless an in-neighbour did.
   * GAT: z = x W viewed [heads][head_dim]; e_uv = LeakyReLU(a_dst . z_v + a_src . z_u)
     (destination first, as in Eq. 3); softmax over N(v) U {v}; heads concatenated; ELU on
     hidden layers.
@@ -52,7 +58,7 @@ from typing import List, Optional, Sequence
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN = 1, 2, 3, 4, 5, 6, 7
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET = 1, 2, 3, 4, 5, 6, 7, 8
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librtec_oracle.so")
@@ -208,6 +214,15 @@ def layer(spec, params, l: int, n: int, src, dst, w, x: np.ndarray) -> np.ndarra
         unit = np.where(nrm[:, None] > 0, x / np.where(nrm > 0, nrm, 1.0)[:, None], 0.0)
         cos = (unit[dst] * unit[src]).sum(axis=1)
         a = in_sum(n, src, dst, float(spec.agnn_beta) * cos, x)
+        y = a @ W[0]
+        if b[0] is not None:
+            y = y + b[0]
+    elif spec.kind == MONET:
+        # Table II MoNet row: message = the Gaussian kernel responses of the source row, f_nn = 1, plain sum.
+        mu, prec = _f64(params.monet_mu[l - 1]), _f64(params.monet_prec[l - 1])
+        diff = x[:, None, :] - mu[None, :, :]
+        g = np.exp(-0.5 * (prec[None, :, :] * diff * diff).sum(axis=2))
+        a = in_sum(n, src, dst, None, g)
         y = a @ W[0]
         if b[0] is not None:
             y = y + b[0]

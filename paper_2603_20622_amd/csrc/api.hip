@@ -45,7 +45,11 @@ struct nrt_cache {
     float* R[NRT_MAX_LAYERS + 1];       // A-GNN: inverse norms of the rows of h^l (null otherwise)
     float* r_old;                       // A-GNN: [N] compact, inverse norms of the changed rows before the batch
     float agnn_beta[NRT_MAX_LAYERS];
-    float* MP[NRT_MAX_LAYERS + 1];      // PinSAGE: message payload of layer l's rows, ReLU(h^l Q + q) (null otherwise)
+    float* MP[NRT_MAX_LAYERS + 1];      // PinSAGE, MoNet: message payload of layer l's rows (ReLU(h^l Q + q); the Gaussian
+                                        // kernel responses of h^l), null otherwise
+    int monet_J;                        // MoNet: kernels per layer = width of its payload and aggregate
+    float* muT[NRT_MAX_LAYERS];         // MoNet: [d_l][J] transposed means / precisions of layer l+1
+    float* precT[NRT_MAX_LAYERS];
     float* Wt[NRT_MAX_LAYERS][2];
     float* bias[NRT_MAX_LAYERS][2];
     int32_t* indeg_old;
@@ -240,18 +244,24 @@ extern "C" nrt_status nrt_graph_export_csc(const nrt_graph* g, int64_t* indptr, 
 // models whose update runs on the concatenation [h_v || aggregate] (Table II rows PinSAGE and CommNet)
 static inline bool concat_self(int kind) { return kind == NRT_SAGE_MEAN || kind == NRT_COMMNET || kind == NRT_PINSAGE; }
 
+// models that aggregate a per-vertex transform of h instead of h itself, cached by vertex
+static inline bool has_message_cache(int kind) { return kind == NRT_PINSAGE || kind == NRT_MONET; }
 // models whose messages carry the edge weight
 static inline bool weighted_messages(int kind) { return kind == NRT_GIN || kind == NRT_PINSAGE; }
 
 static nrt_status check_desc(const nrt_model_desc* d) {
     REQUIRE(d, "model desc is null");
-    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_AGNN, "unknown model kind");
+    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_MONET, "unknown model kind");
     REQUIRE(d->n_layers >= 1 && d->n_layers <= NRT_MAX_LAYERS, "n_layers out of range");
     for (int l = 0; l <= d->n_layers; ++l) {
         if (d->dims[l] <= 0 || d->dims[l] % 4 || d->dims[l] > 1024) {
             nrt_set_error("layer widths must be multiples of 4 in [4, 1024]");
             return NRT_ERR_UNSUPPORTED;
         }
+    }
+    if (d->kind == NRT_MONET && (d->monet_kernels < 4 || d->monet_kernels % 4 || d->monet_kernels > 1024)) {
+        nrt_set_error("MoNet needs monet_kernels a multiple of 4 in [4, 1024]");
+        return NRT_ERR_UNSUPPORTED;
     }
     if (d->agg_only && d->kind != NRT_GCN) {
         nrt_set_error("aggregate-only storage is available for GCN");
@@ -277,6 +287,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     const int64_t nw = cdiv(n, 32);
     int maxd = 0;
     for (int l = 0; l <= c->L; ++l) maxd = c->dims[l] > maxd ? c->dims[l] : maxd;
+    if (c->kind == NRT_MONET && c->monet_J > maxd) maxd = c->monet_J;
     c->maxd = maxd;
     for (int l = 0; l <= c->L; ++l) {
         const bool hidden = l >= 1 && l < c->L;
@@ -284,13 +295,21 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         c->ES[l] = (c->agg_only && hidden) ? b.take<float>((size_t)(c->max_edges + 1) * c->dims[l]) : nullptr;
     }
     c->es_rows = c->agg_only ? b.take<int32_t>(c->max_edges + 1) : nullptr;
-    for (int l = 0; l <= c->L; ++l) c->MP[l] = (c->kind == NRT_PINSAGE && l < c->L) ? b.take<float>(n * c->dims[l]) : nullptr;
+    for (int l = 0; l <= c->L; ++l) {
+        c->MP[l] = nullptr;
+        if (c->kind == NRT_PINSAGE && l < c->L) c->MP[l] = b.take<float>(n * c->dims[l]);
+        if (c->kind == NRT_MONET && l < c->L) {
+            c->MP[l] = b.take<float>(n * c->monet_J);
+            c->muT[l] = b.take<float>((size_t)c->dims[l] * c->monet_J);
+            c->precT[l] = b.take<float>((size_t)c->dims[l] * c->monet_J);
+        }
+    }
     for (int l = 0; l <= c->L; ++l) c->R[l] = (c->kind == NRT_AGNN && l < c->L) ? b.take<float>(n) : nullptr;
     c->r_old = c->kind == NRT_AGNN ? b.take<float>(n) : nullptr;
     c->S[0] = nullptr;
     const bool gat = c->kind == NRT_GAT;
     for (int l = 1; l <= c->L; ++l) {
-        c->dagg[l] = gat ? c->dims[l] : c->dims[l - 1];
+        c->dagg[l] = gat ? c->dims[l] : (c->kind == NRT_MONET ? c->monet_J : c->dims[l - 1]);
         c->S[l] = b.take<float>(n * c->dagg[l]);
         if (gat) {
             c->Z[l] = b.take<float>(n * c->dims[l]);
@@ -312,7 +331,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->AS_old = gat ? b.take<float>(n * c->heads) : nullptr;
     c->is_gat = gat;
     for (int l = 0; l < c->L; ++l) {
-        const int kin = (concat_self(c->kind) ? 2 : 1) * c->dims[l];
+        const int kin = c->kind == NRT_MONET ? c->monet_J : (concat_self(c->kind) ? 2 : 1) * c->dims[l];
         c->Wt[l][0] = b.take<float>((size_t)kin * c->dims[l + 1]);
         c->bias[l][0] = b.take<float>(c->dims[l + 1]);
         if (c->kind == NRT_GIN) {
@@ -385,6 +404,7 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     c->leaky_slope = d->leaky_slope;
     for (int l = 0; l < c->L; ++l) c->agnn_beta[l] = d->agnn_beta[l];
     c->agg_only = d->agg_only ? 1 : 0;
+    c->monet_J = d->kind == NRT_MONET ? d->monet_kernels : 0;
     c->max_edges = max_edges;
     c->max_feats = max_feats;
     return NRT_OK;
@@ -411,12 +431,27 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
 }
 
 // what the in-neighbours of layer l+1 aggregate: h^l itself, or its transform for PinSAGE
-static inline const float* payload_rows(const nrt_cache* c, int l) { return c->kind == NRT_PINSAGE ? c->MP[l] : c->H[l]; }
+static inline const float* payload_rows(const nrt_cache* c, int l) { return has_message_cache(c->kind) ? c->MP[l] : c->H[l]; }
 
-// PinSAGE (Table II): the message of a vertex, ReLU(h^l Q + q), on the listed rows (null: all n rows); with `dp` the
-// compact rows new - old that the gather of layer l+1 folds
+// PinSAGE, MoNet (Table II): the message of a vertex (ReLU(h^l Q + q); Gaussian kernel responses of h^l) on the listed rows
+// (null: all n rows); with `dp` the compact rows new - old that the gather of layer l+1 folds
 static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_t M, const uint64_t* M_dev, float* dp,
                                 bool skip_dp_when_large, hipStream_t s) {
+    if (c->kind == NRT_MONET) {            // the Gaussian kernel responses of the rows
+        MonetArgs m;
+        memset(&m, 0, sizeof(m));
+        m.rows = rows;
+        m.count_dev = M_dev;
+        m.bound = M;
+        m.H = c->H[l];
+        m.d = c->dims[l];
+        m.muT = c->muT[l];
+        m.precT = c->precT[l];
+        m.J = c->monet_J;
+        m.G = c->MP[l];
+        m.DP = dp;
+        return k_monet_transform(m, s);
+    }
     GemmArgs a;
     memset(&a, 0, sizeof(a));
     a.M = M;
@@ -468,7 +503,7 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
         a.sd = c->SD[l];
         a.dd_bitmap = c->bm_ddst;
         a.dd_slot = c->slot_dd;
-        a.guard = c->kind == NRT_GIN || c->kind == NRT_COMMNET;   // un-normalised sums: a fold can cancel most of a row's magnitude
+        a.guard = c->kind == NRT_GIN || c->kind == NRT_COMMNET || c->kind == NRT_MONET;   // un-normalised sums: a fold can cancel most of a row's magnitude
         a.Pfull = payload_rows(c, l - 1);
         a.full_scale_gcn = c->kind == NRT_GCN;
         a.sparse_ok = (sparse_hint == 2 && a.D > 256) ? 1 : sparse_hint;    // rows wider than 256 floats: pipelined kernel only
@@ -510,8 +545,21 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
     a.ldp = c->dims[l - 1];
     a.N = c->dims[l];
     // PinSAGE: the next layer's payload deltas come from the transform of the changed rows, not from here
-    float* dp = (incremental && !last && c->kind != NRT_PINSAGE) ? c->DP[cur] : nullptr;
-    if (c->kind == NRT_GCN || concat_self(c->kind)) {
+    float* dp = (incremental && !last && !has_message_cache(c->kind)) ? c->DP[cur] : nullptr;
+    if (c->kind == NRT_MONET) {
+        a.a_mode = A_PLAIN;
+        a.P0 = c->S[l];
+        a.ldp = c->monet_J;
+        a.K = c->monet_J;
+        a.Wt = c->Wt[l - 1][0];
+        a.bias = c->bias[l - 1][0];
+        a.act = last ? 0 : 1;
+        a.H = c->H[l];
+        a.n_vertices = g->n;
+        a.out_compact = last ? out_rows : nullptr;
+        a.out_cap = out_cap;
+        NRT_TRY(k_gemm(a, s));
+    } else if (c->kind == NRT_GCN || concat_self(c->kind)) {
         if (c->kind == NRT_GCN) {
             a.a_mode = A_SCALE_GCN;
             a.P0 = c->S[l];
@@ -755,7 +803,7 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
             st = run_agnn_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, 0, 0, nullptr, 0, s);
             continue;
         }
-        if (c->kind == NRT_PINSAGE) st = run_transform(c, l - 1, nullptr, n, nullptr, nullptr, false, s);
+        if (has_message_cache(c->kind)) st = run_transform(c, l - 1, nullptr, n, nullptr, nullptr, false, s);
         if (st == NRT_OK) st = run_gather(c, l, false, 0, false, 0, s);
         if (st == NRT_OK) st = run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, false, s);
     }
@@ -780,6 +828,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         REQUIRE(d->W[l][0], "W[l][0] is null");
         if (d->kind == NRT_GIN) REQUIRE(d->W[l][1], "GIN needs W[l][1]");
         if (d->kind == NRT_PINSAGE) REQUIRE(d->W[l][1], "PinSAGE needs W[l][1]");
+        if (d->kind == NRT_MONET) REQUIRE(d->monet_mu[l] && d->monet_prec[l], "MoNet needs monet_mu[l] and monet_prec[l]");
         if (d->kind == NRT_GAT) REQUIRE(d->att_src[l] && d->att_dst[l], "GAT needs att_src[l] and att_dst[l]");
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -803,10 +852,14 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         NRT_TRY(k_fill_u32((uint32_t*)c->flags, (n + 64) / 4, 0, s));
         NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
         for (int l = 0; l < c->L; ++l) {
-            const int kin = (concat_self(c->kind) ? 2 : 1) * c->dims[l];
+            const int kin = c->kind == NRT_MONET ? c->monet_J : (concat_self(c->kind) ? 2 : 1) * c->dims[l];
             NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
             if (d->b[l][0]) NRT_TRY(k_copy_f32(c->bias[l][0], d->b[l][0], c->dims[l + 1], s));
             else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][0], c->dims[l + 1], 0, s));
+            if (c->kind == NRT_MONET) {
+                NRT_TRY(k_transpose(d->monet_mu[l], c->muT[l], c->monet_J, c->dims[l], s));
+                NRT_TRY(k_transpose(d->monet_prec[l], c->precT[l], c->monet_J, c->dims[l], s));
+            }
             if (c->kind == NRT_GAT) {
                 NRT_TRY(k_copy_f32(c->att_src[l], d->att_src[l], (int64_t)c->heads * c->head_dim, s));
                 NRT_TRY(k_copy_f32(c->att_dst[l], d->att_dst[l], (int64_t)c->heads * c->head_dim, s));
@@ -1047,7 +1100,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
                           g->scan_tmp_len, &c->lc[l].count, s));
         if (c->lazy) {                                     // on-demand mode: A_l only becomes stale
-            if (c->kind == NRT_PINSAGE && l == 1)          // h^0 is never stale, so neither may its message rows be
+            if (has_message_cache(c->kind) && l == 1)      // h^0 is never stale, so neither may its message rows be
                 NRT_TRY(run_transform(c, 0, c->list[0], src_bound, &c->lc[0].count, nullptr, false, s));
             NRT_TRY(k_or_words(c->stale[l], c->stale[l], c->bm[cur], (n + 31) / 32, s));
             prev = cur;
@@ -1074,7 +1127,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             // clearly dense layer launches one kernel, in between both are launched and the device counter decides
             const int64_t pn = prev_n_list[l - 1];
             const int sparse_hint = !had_history ? 1 : (pn * 64 <= n ? 2 : (pn * 4 > n ? 0 : 1));
-            if (c->kind == NRT_PINSAGE)
+            if (has_message_cache(c->kind))
                 NRT_TRY(run_transform(c, l - 1, c->list[l - 1], src_bound, &c->lc[l - 1].count, inc ? c->DP[prev] : nullptr,
                                       may_rec[l], s));
             if (c->agg_only && l < c->L) {
@@ -1178,7 +1231,7 @@ static nrt_status recompute_listed(nrt_cache* c, hipStream_t s) {
         NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, nullptr, s));
         NRT_TRY(run_gather(c, l, false, 0, false, 0, s));
         NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, false, 0, nullptr, 0, false, s));
-        if (c->kind == NRT_PINSAGE && l < c->L)            // message rows follow every h row that is brought up to date
+        if (has_message_cache(c->kind) && l < c->L)        // message rows follow every h row that is brought up to date
             NRT_TRY(run_transform(c, l, c->list[l], n, &c->lc[l].count, nullptr, false, s));
         NRT_TRY(k_clear_listed_bits(c->stale[l], c->list[l], &c->lc[l].count, n, s));
     }

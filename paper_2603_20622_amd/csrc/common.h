@@ -351,6 +351,19 @@ nrt_status k_agnn_gather(const AgnnArgs& a, hipStream_t s);
 nrt_status k_agnn_combine(const AgnnArgs& a, hipStream_t s);   // after the gather, same arguments: destinations with long in-lists
 nrt_status k_agnn_structural_fold(const AgnnFoldArgs& a, hipStream_t s);
 
+// ---------------------------------------------------------------- monet.hip
+struct MonetArgs {
+    const int32_t* rows;            // listed vertices (null: rows 0 .. bound)
+    const uint64_t* count_dev;      // their number on the device (with rows)
+    int64_t bound;
+    const float* H; int d;          // [N][d] layer input
+    const float* muT; const float* precT;   // [d][J] transposed means and diagonal precisions
+    int J;
+    float* G;                       // [N][J] kernel responses, by vertex
+    float* DP;                      // [listed][J] compact: new - old (or null)
+};
+nrt_status k_monet_transform(const MonetArgs& a, hipStream_t s);
+
 // ---------------------------------------------------------------- graph.hip
 nrt_status graph_layout(Bump& b, nrt_graph* g);
 nrt_status graph_build(nrt_graph* g, const int64_t* csr_indptr, const int32_t* csr_indices, const float* csr_w,

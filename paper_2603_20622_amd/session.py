@@ -53,6 +53,8 @@ class Session:
             "b": [[_dev(b) for b in bs] for bs in params.b],
             "att_src": [_dev(a) for a in params.att_src],
             "att_dst": [_dev(a) for a in params.att_dst],
+            "monet_mu": [_dev(a) for a in getattr(params, "monet_mu", [])],
+            "monet_prec": [_dev(a) for a in getattr(params, "monet_prec", [])],
         }
         self.desc = nb.make_desc(spec, self.dev_params)
         xd = _dev(x, torch.float32)

@@ -18,8 +18,8 @@ from typing import Dict, List, Optional
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN = 1, 2, 3, 4, 5, 6, 7
-KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage", AGNN: "agnn"}
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET = 1, 2, 3, 4, 5, 6, 7, 8
+KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage", AGNN: "agnn", MONET: "monet"}
 
 
 @dataclass
@@ -33,6 +33,7 @@ class ModelSpec:
     leaky_slope: float = 0.2
     weighted: bool = False
     agnn_beta: float = 1.0          # A-GNN: the scalar in front of the cosine (the same at every layer)
+    monet_kernels: int = 0          # MoNet: Gaussian kernels per layer (the width of its aggregate)
     agg_only: bool = False          # GCN: keep only the aggregates of hidden layers (storage option of the cache)
 
     @property
@@ -47,6 +48,8 @@ class Params:
     b: List[List[Optional[np.ndarray]]] = field(default_factory=list)
     att_src: List[Optional[np.ndarray]] = field(default_factory=list)   # GAT [heads][head_dim]
     att_dst: List[Optional[np.ndarray]] = field(default_factory=list)
+    monet_mu: List[Optional[np.ndarray]] = field(default_factory=list)     # MoNet [kernels][d_in] means
+    monet_prec: List[Optional[np.ndarray]] = field(default_factory=list)   # MoNet [kernels][d_in] diagonal precisions
 
 
 @dataclass
@@ -139,6 +142,8 @@ def make_params(spec: ModelSpec, seed: int = 0, bias: bool = False) -> Params:
     for l in range(1, spec.n_layers + 1):
         din, dout = spec.dims[l - 1], spec.dims[l]
         kin = 2 * din if spec.kind in (SAGE_MEAN, COMMNET, PINSAGE) else din
+        if spec.kind == MONET:
+            kin = spec.monet_kernels
         Ws = [_glorot(rng, kin, dout, (kin, dout))]
         if spec.kind == GIN:
             Ws.append(_glorot(rng, dout, dout, (dout, dout)))
@@ -149,6 +154,13 @@ def make_params(spec: ModelSpec, seed: int = 0, bias: bool = False) -> Params:
             bs.append(rng.uniform(-0.1, 0.1, size=W.shape[1]).astype(np.float32) if bias else None)
         p.W.append(Ws)
         p.b.append(bs)
+        if spec.kind == MONET:
+            # means spread like the inputs, precisions small enough that a kernel answers to more than one point
+            p.monet_mu.append(rng.standard_normal((spec.monet_kernels, din)).astype(np.float32))
+            p.monet_prec.append((rng.uniform(0.2, 2.0, size=(spec.monet_kernels, din)) / din).astype(np.float32))
+        else:
+            p.monet_mu.append(None)
+            p.monet_prec.append(None)
         if spec.kind == GAT:
             p.att_src.append(_glorot(rng, 2 * spec.head_dim, 1, (spec.heads, spec.head_dim)))
             p.att_dst.append(_glorot(rng, 2 * spec.head_dim, 1, (spec.heads, spec.head_dim)))

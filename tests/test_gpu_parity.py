@@ -11,7 +11,7 @@ from paper_2603_20622_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
-UNNORMALISED = (wl.GIN, wl.COMMNET, wl.AGNN)      # plain sums: magnitudes grow with degree and depth
+UNNORMALISED = (wl.GIN, wl.COMMNET, wl.AGNN, wl.MONET)      # plain sums: magnitudes grow with degree and depth
 
 
 def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
@@ -58,14 +58,14 @@ def small_case(kind, seed=0, n=3000, e=40000, dims=None, bias=False, L=2):
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [dims[0]] + [64] * L, heads=4, head_dim=16)
     else:
-        spec = wl.ModelSpec(kind, dims, weighted=weighted)
+        spec = wl.ModelSpec(kind, dims, weighted=weighted, monet_kernels=24)
     params = wl.make_params(spec, seed, bias=bias)
     x = wl.features(n, dims[0], seed)
     stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], seed)
     return n, src, dst, w, x, spec, params, stream
 
 
-KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN]
+KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET]
 WEIGHTED = (wl.GIN, wl.PINSAGE)           # models whose messages carry the edge weight
 
 
@@ -254,6 +254,7 @@ def test_gin_cancellation_is_guarded(S, oracle):
     (wl.COMMNET, [36, 260, 8], 1, 0),           # concatenated K = 72 and 520
     (wl.PINSAGE, [20, 132, 12], 1, 0),          # message transforms 20x20 and 132x132
     (wl.AGNN, [300, 520, 8], 1, 0),             # cosine rows of two and of four 16-byte pieces per lane
+    (wl.MONET, [36, 132, 8], 1, 0),             # 260 kernels: wider than every layer
     (wl.GAT, [24, 512, 512], 8, 64),            # 512-wide attention rows, 8 heads
     (wl.GAT, [12, 8, 8], 2, 4),                 # smallest head width
 ])
@@ -262,7 +263,7 @@ def test_unusual_widths(S, oracle, kind, dims, heads, head_dim):
     src, dst, sampler = wl.rmat_graph(n, e, 31)
     weighted = kind in WEIGHTED
     w = wl.edge_weights(e, 31) if weighted else None
-    spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=head_dim, weighted=weighted)
+    spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=head_dim, weighted=weighted, monet_kernels=260)
     params = wl.make_params(spec, 31, bias=True)
     x = wl.features(n, dims[0], 31)
     stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], 31)
@@ -583,7 +584,7 @@ def test_widest_rows(S, oracle):
             assert rel_err(ses.layer(l).cpu().numpy(), ref[l - 1]) <= TOL
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.COMMNET, wl.PINSAGE])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.COMMNET, wl.PINSAGE, wl.MONET])
 def test_on_demand_queries_match_oracle(S, oracle, kind):
     """On-demand mode (Section IV-D): batches only mark vertices stale; a query recomputes the stale part of the
     L-hop in-neighbourhood of the queried vertices, nothing else, and returns rows equal to a full recomputation."""
@@ -592,7 +593,7 @@ def test_on_demand_queries_match_oracle(S, oracle, kind):
     src, dst, sampler = wl.rmat_graph(n, e, 101)
     weighted = kind in WEIGHTED
     w = wl.edge_weights(e, 101) if weighted else None
-    spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted)
+    spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted, monet_kernels=20)
     params = wl.make_params(spec, 101, bias=True)
     x = wl.features(n, 16, 101)
     stream = wl.BatchStream(n, src, dst, w, sampler, 16, 101)

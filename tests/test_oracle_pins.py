@@ -1,7 +1,7 @@
 """Pins for the CPU oracle: things other than the oracle itself that fix its values.
 
   * brute force: a per-vertex recursive evaluation of the message-aggregate-update layer (Eq. 1)
-    from hand-written adjacency lists, in Python floats, for all seven models;
+    from hand-written adjacency lists, in Python floats, for all eight models;
   * the dense-matrix closed forms the models reduce to (normalised adjacency products);
   * closed forms on special graphs / parameters (cycle, constant features, zero attention,
     two-term softmax, star hub);
@@ -63,6 +63,15 @@ def brute_embedding(spec, params, in_nbrs, x, v, l):
             for k in range(d):
                 m[k] += float(w) * mu[k] / len(in_nbrs[v])
         y = _lin(hv + m, W[0], b[0])
+        act = "relu"
+    elif spec.kind == wl.MONET:
+        mu, prec = params.monet_mu[l - 1], params.monet_prec[l - 1]
+        a = [0.0] * spec.monet_kernels
+        for u, _ in in_nbrs[v]:
+            for j in range(spec.monet_kernels):
+                q = sum(float(prec[j][k]) * (hu[u][k] - float(mu[j][k])) ** 2 for k in range(d))
+                a[j] += math.exp(-0.5 * q)
+        y = _lin(a, W[0], b[0])
         act = "relu"
     elif spec.kind == wl.AGNN:
         a = [0.0] * d
@@ -132,7 +141,7 @@ def _tiny(kind, L, seed, bias=True):
         spec = wl.ModelSpec(kind, dims, heads=2, head_dim=2)
     else:
         dims = [3, 5, 4, 2][: L + 1]
-        spec = wl.ModelSpec(kind, dims, weighted=(kind in (wl.GIN, wl.PINSAGE)), agnn_beta=0.7)
+        spec = wl.ModelSpec(kind, dims, weighted=(kind in (wl.GIN, wl.PINSAGE)), agnn_beta=0.7, monet_kernels=4)
     params = wl.make_params(spec, seed, bias=bias)
     x = rng.standard_normal((n, dims[0])).astype(np.float32)
     return n, src, dst, w, x, spec, params
@@ -145,7 +154,7 @@ def _in_lists(n, src, dst, w):
     return lists
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET])
 @pytest.mark.parametrize("L", [1, 2, 3])
 def test_forward_matches_brute_force(oracle, kind, L):
     n, src, dst, w, x, spec, params = _tiny(kind, L, seed=3 + L)
@@ -357,6 +366,50 @@ def test_agnn_special_directions_by_hand(oracle):
     np.testing.assert_allclose(oracle.forward(spec, params, 5, src, dst, None, x2)[0][0], [24.0, 24.0], rtol=1e-14)
 
 
+def test_monet_is_adjacency_product_of_kernel_responses(oracle):
+    """Table II MoNet row as matrices: G = exp(-1/2 sum_k prec (h - mu)^2) per vertex and kernel, a = A G, H' = act(a W + b)."""
+    n, e = 40, 240
+    src, dst, _ = wl.rmat_graph(n, e, seed=25)
+    spec = wl.ModelSpec(wl.MONET, [5, 6, 3], monet_kernels=8)
+    params = wl.make_params(spec, 26, bias=True)
+    x = wl.features(n, 5, 27).astype(np.float64)
+    f = lambda a: a.astype(np.float64)
+    A = _dense_adj(n, src, dst)
+    h = x
+    for l in range(2):
+        mu, prec = f(params.monet_mu[l]), f(params.monet_prec[l])
+        G = np.stack([np.exp(-0.5 * (prec[j] * (h - mu[j]) ** 2).sum(axis=1)) for j in range(8)], axis=1)
+        h = A @ G @ f(params.W[l][0]) + f(params.b[l][0])
+        if l == 0:
+            h = np.maximum(h, 0)
+    outs = oracle.forward(spec, params, n, src, dst, None, x.astype(np.float32))
+    np.testing.assert_allclose(outs[1], h, rtol=1e-10, atol=1e-12)
+
+
+def test_monet_special_kernels_by_hand(oracle):
+    """Zero precision: every response is 1, the aggregate is the in-degree in every kernel, h_v = indeg(v) * colsum(W).
+    One kernel by hand: mu = (1, 2), prec = (2, 0.5); sources (1, 2) -> 1, (2, 2) -> exp(-1), (1, 4) -> exp(-1),
+    (3, 0) -> exp(-5);  W = [[10]]."""
+    n, e = 30, 150
+    src, dst, _ = wl.rmat_graph(n, e, seed=28)
+    spec = wl.ModelSpec(wl.MONET, [3, 4], monet_kernels=4)
+    params = wl.make_params(spec, 29)
+    params.monet_prec[0][:] = 0
+    x = wl.features(n, 3, 30)
+    out = oracle.forward(spec, params, n, src, dst, None, x)[0]
+    indeg = np.bincount(dst, minlength=n).astype(np.float64)
+    np.testing.assert_allclose(out, indeg[:, None] * params.W[0][0].astype(np.float64).sum(axis=0)[None, :], rtol=1e-12)
+
+    one = wl.ModelSpec(wl.MONET, [2, 1], monet_kernels=1)
+    p1 = wl.Params(W=[[np.array([[10.0]], np.float32)]], b=[[None]], att_src=[None], att_dst=[None],
+                   monet_mu=[np.array([[1.0, 2.0]], np.float32)], monet_prec=[np.array([[2.0, 0.5]], np.float32)])
+    x1 = np.array([[0, 0], [1, 2], [2, 2], [1, 4], [3, 0]], np.float32)
+    s1, d1 = np.array([1, 2, 3, 4], np.int32), np.zeros(4, np.int32)
+    got = oracle.forward(one, p1, 5, s1, d1, None, x1)[0]
+    np.testing.assert_allclose(got[0, 0], 10 * (1 + 2 * math.exp(-1) + math.exp(-5)), rtol=1e-14)
+    np.testing.assert_allclose(got[1:, 0], 0.0, atol=0)
+
+
 def test_commnet_single_edge_by_hand(oracle):
     """Edge 0 -> 1, scalar feature, W_1 = 2, W_2 = -3:  h_0 = 2 x_0,  h_1 = 2 x_1 - 3 x_0."""
     spec = wl.ModelSpec(wl.COMMNET, [1, 1])
@@ -526,14 +579,14 @@ def test_affected_sets_hand_enumerated(oracle):
         assert [a.tolist() for a in got] == [[3, 4], [3, 4]]
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET])
 def test_affected_sets_match_reachability_powers(oracle, kind):
     n, e = 70, 260
     src, dst, sampler = wl.rmat_graph(n, e, seed=12)
     stream = wl.BatchStream(n, src, dst, None, sampler, 3, seed=1)
     batch = stream.next_batch(4, 4, 2)
     ns, nd, _ = stream.edges()
-    spec = wl.ModelSpec(kind, [3, 4, 4, 4], heads=2, head_dim=2)
+    spec = wl.ModelSpec(kind, [3, 4, 4, 4], heads=2, head_dim=2, monet_kernels=4)
     got = oracle.affected_sets(spec, n, ns, nd, batch)
     Out = np.zeros((n, n), dtype=np.int64)               # Out[u, v] = 1 for edge u -> v
     Out[ns, nd] = 1
@@ -550,13 +603,13 @@ def test_affected_sets_match_reachability_powers(oracle, kind):
 
 
 # ------------------------------------------------------------------ invariants
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET])
 def test_batch_invariants(oracle, kind):
     n, e = 200, 1500
     src, dst, sampler = wl.rmat_graph(n, e, seed=13)
     weighted = kind in (wl.GIN, wl.PINSAGE)
     w = wl.edge_weights(e, 13) if weighted else None
-    spec = wl.ModelSpec(kind, [6, 8, 4], heads=2, head_dim=4 if kind == wl.GAT else 0, weighted=weighted)
+    spec = wl.ModelSpec(kind, [6, 8, 4], heads=2, head_dim=4 if kind == wl.GAT else 0, weighted=weighted, monet_kernels=8)
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [6, 8, 8], heads=2, head_dim=4)
     params = wl.make_params(spec, 9)
