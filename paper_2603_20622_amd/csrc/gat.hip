@@ -17,8 +17,10 @@
 //     at the end of the in-list, where the graph appends.  m is raised first if a new logit exceeds it (den and S
 //     are rescaled by exp(m_old - m_new)).  When the update removes most of the old attention mass (den shrinks
 //     below 1/64 of its old value) the subtraction has cancelled the leading digits, and v is recomputed in full.
-//   A destination with more than NRT_CHUNK in-edges is recomputed in full through its items whenever some z
-//   changed in the layer; when none did (edge updates only) it takes the same O(#updates) path as the others.
+//   A destination with more than NRT_CHUNK in-edges is cut into items whenever some z changed in the layer: each item
+//   holds its share of the full sums (own z changed) or of Algorithm 3's exchange relative to a bound of its own,
+//   and the combine kernel merges them; when no z changed (edge updates only) such a destination takes the same
+//   O(#updates) path as the others.
 // One wave per destination; lane = 4 consecutive columns of the row, a head = head_dim/4 neighbouring lanes.
 #include "common.h"
 
@@ -177,8 +179,8 @@ __device__ inline void gat_store(const GatArgs& a, int32_t v, int64_t s, const i
     }
 }
 
-// Units [0, n_items): hub items (NRT_CHUNK in-list entries of a destination with a long in-list; such a
-// destination is always recomputed in full, its items write partial (max, sum, row) triples).  Units
+// Units [0, n_items): hub items (NRT_CHUNK in-list entries of a destination with a long in-list; they write partial
+// (bound, sum, row) triples of the full sums or of the exchange).  Units
 // [n_items, n_items + n_dst): the destinations themselves, hubs skipped.
 template <int NV>
 __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
@@ -205,11 +207,69 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
         if (unit < n_items) {
             const int32_t chunk = a.hubs.item_chunk[unit];
             const DstRec rec = a.recs[a.hubs.hub_slot[a.hubs.item_hub[unit]]];
+            const int32_t v = rec.v;
+            const int32_t cnt = min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK);
+            const int64_t base = rec.off + (int64_t)chunk * NRT_CHUNK;
 #pragma unroll
-            for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)rec.v * H + head[q]] : 0.f;
-            gat_full_pass<NV>(a, rec.v, rec.off + (int64_t)chunk * NRT_CHUNK, min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK),
-                              false, lane, col, head, live, adv, mcur, den, acc);
-            rows_read += min(NRT_CHUNK, rec.deg - chunk * NRT_CHUNK);
+            for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)v * H + head[q]] : 0.f;
+            const bool own = a.src_bitmap ? ((a.src_bitmap[v >> 5] >> (v & 31)) & 1u) != 0 : true;
+            if (own) {                                        // every logit of v changed: its share of the full sums
+                gat_full_pass<NV>(a, v, base, cnt, false, lane, col, head, live, adv, mcur, den, acc);
+                rows_read += cnt;
+            } else {
+                // Algorithm 3 on this part of the in-list, relative to a bound of its own (the cached bound of v raised
+                // by the new logits met here); the combine kernel brings the parts to one bound
+                const bool edge = (a.ddst_bitmap[v >> 5] >> (v & 31)) & 1u;
+                const int32_t n_new = edge ? a.ins_cnt[a.dd_slot[v]] : 0;
+                const int32_t first_new = rec.deg - n_new - chunk * NRT_CHUNK;   // entries from here on were inserted
+#pragma unroll
+                for (int q = 0; q < NV; ++q) mcur[q] = live[q] ? a.M[(int64_t)v * H + head[q]] : 0.f;
+                for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
+                    const int32_t jj = j0 + lane;
+                    const int32_t u = jj < cnt ? a.in.idx[base + jj] : -1;
+                    const bool ok = u >= 0 && (jj >= first_new || ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u));
+                    unsigned long long mask = __ballot(ok);
+                    while (mask) {
+                        const int bit = __ffsll((long long)mask) - 1;
+                        mask &= mask - 1;
+                        const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+#pragma unroll
+                        for (int q = 0; q < NV; ++q)
+                            if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < NV; ++q) { den[q] = 0.f; acc[q] = make_float4(0.f, 0.f, 0.f, 0.f); }
+                for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
+                    const int32_t jj = j0 + lane;
+                    const int32_t u = jj < cnt ? a.in.idx[base + jj] : -1;
+                    const bool fresh = jj >= first_new;
+                    const bool ok = u >= 0 && (fresh || ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u));
+                    const int32_t sl = (ok && !fresh) ? a.src_slot[u] : -1;
+                    unsigned long long mask = __ballot(ok);
+                    while (mask) {
+                        const int bit = __ffsll((long long)mask) - 1;
+                        mask &= mask - 1;
+                        const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+                        const int32_t ss = __builtin_amdgcn_readlane(sl, bit);     // -1: an inserted in-edge, new term only
+                        rows_read += ss >= 0 ? 2 : 1;
+#pragma unroll
+                        for (int q = 0; q < NV; ++q) {
+                            if (!live[q]) continue;
+                            const float cn = __expf(leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope) - mcur[q]);
+                            const float4 zn = *reinterpret_cast<const float4*>(a.Z + (int64_t)uu * D + col[q]);
+                            den[q] += cn;
+                            acc[q].x += cn * zn.x; acc[q].y += cn * zn.y; acc[q].z += cn * zn.z; acc[q].w += cn * zn.w;
+                            if (ss >= 0) {
+                                const float co = __expf(leaky(adv[q] + a.AS_old[(int64_t)ss * H + head[q]], slope) - mcur[q]);
+                                const float4 zo = *reinterpret_cast<const float4*>(a.Z_old + (int64_t)ss * D + col[q]);
+                                den[q] -= co;
+                                acc[q].x -= co * zo.x; acc[q].y -= co * zo.y; acc[q].z -= co * zo.z; acc[q].w -= co * zo.w;
+                            }
+                        }
+                    }
+                }
+            }
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
                 if (!live[q]) continue;
@@ -377,6 +437,59 @@ __global__ void __launch_bounds__(256) gat_combine_kernel(GatArgs a) {
         const int64_t first = (int64_t)a.hubs.hub_first[h];
         float mcur[NV], den[NV], eself[NV];
         float4 acc[NV];
+        const int32_t v = rec.v;
+        const bool own = a.src_bitmap ? ((a.src_bitmap[v >> 5] >> (v & 31)) & 1u) != 0 : true;
+        if (!own) {
+            // the items hold Algorithm 3's exchanged terms, each relative to its own bound: bring the cached sums, the
+            // structural terms and the items to the largest bound and add them up
+            float mold[NV], den0[NV];
+#pragma unroll
+            for (int q = 0; q < NV; ++q) { mold[q] = live[q] ? a.M[(int64_t)v * H + head[q]] : 0.f; mcur[q] = mold[q]; }
+            for (int32_t c = 0; c < nch; ++c)
+#pragma unroll
+                for (int q = 0; q < NV; ++q)
+                    if (live[q]) mcur[q] = fmaxf(mcur[q], a.part_m[(first + c) * H + head[q]]);
+            const bool edge = (a.ddst_bitmap[v >> 5] >> (v & 31)) & 1u;
+            const int64_t sd_row = edge ? (int64_t)a.dd_slot[v] : -1;
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                const float f = __expf(mold[q] - mcur[q]);
+                den[q] = live[q] ? a.DEN[(int64_t)v * H + head[q]] * f : 1.f;
+                den0[q] = den[q];
+                acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (live[q]) {
+                    const float4 so = *reinterpret_cast<const float4*>(a.S + (int64_t)v * D + col[q]);
+                    acc[q] = make_float4(so.x * f, so.y * f, so.z * f, so.w * f);
+                    if (sd_row >= 0) {
+                        const float4 sd = *reinterpret_cast<const float4*>(a.sd_s + sd_row * D + col[q]);
+                        den[q] += a.sd_den[sd_row * H + head[q]] * f;
+                        acc[q].x += sd.x * f; acc[q].y += sd.y * f; acc[q].z += sd.z * f; acc[q].w += sd.w * f;
+                    }
+                }
+            }
+            for (int32_t c = 0; c < nch; ++c) {
+#pragma unroll
+                for (int q = 0; q < NV; ++q) {
+                    if (!live[q]) continue;
+                    const float f = __expf(a.part_m[(first + c) * H + head[q]] - mcur[q]);
+                    const float4 p = *reinterpret_cast<const float4*>(a.hubs.partial + (first + c) * D + col[q]);
+                    den[q] += f * a.part_den[(first + c) * H + head[q]];
+                    acc[q].x += f * p.x; acc[q].y += f * p.y; acc[q].z += f * p.z; acc[q].w += f * p.w;
+                }
+            }
+            bool redo = false;
+#pragma unroll
+            for (int q = 0; q < NV; ++q)
+                if (live[q] && !(den[q] > den0[q] * (1.0f / 64.0f))) redo = true;
+            if (__ballot(redo) != 0ULL) {     // cancellation: this wave recomputes the destination over all its neighbours
+                float adv[NV];
+#pragma unroll
+                for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)v * H + head[q]] : 0.f;
+                gat_full_pass<NV>(a, v, rec.off, rec.deg, true, lane, col, head, live, adv, mcur, den, acc);
+            }
+            gat_store<NV>(a, v, s, col, head, live, mcur, den, acc);
+            continue;
+        }
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
             eself[q] = live[q] ? leaky(a.AD[(int64_t)rec.v * H + head[q]] + a.AS[(int64_t)rec.v * H + head[q]], a.slope) : 0.f;
