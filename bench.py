@@ -34,7 +34,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
-    ap.add_argument("--model", choices=["commnet", "pinsage", "agnn", "monet"], default=None,
+    ap.add_argument("--model", choices=["commnet", "pinsage", "agnn", "monet", "ggcn"], default=None,
                     help="run another Table II model on the chosen config's graph, widths and batches (not the headline)")
     ap.add_argument("--agg-only", action="store_true",
                     help="GCN configs: keep only the aggregates of hidden layers (storage option; not the headline)")
@@ -55,7 +55,7 @@ def main():
 
     cfg = wl.config(args.config, args.scale)
     if args.model:
-        kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE, "agnn": wl.AGNN, "monet": wl.MONET}[args.model]
+        kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE, "agnn": wl.AGNN, "monet": wl.MONET, "ggcn": wl.GGCN}[args.model]
         cfg.spec = wl.ModelSpec(kind, list(cfg.spec.dims[:1]) + list(cfg.spec.dims[1:]), weighted=kind == wl.PINSAGE,
                                 monet_kernels=64)
         cfg.name = cfg.name + "_as_" + args.model
@@ -183,7 +183,7 @@ def main():
     # ---- on-demand leg (Section IV-D): batches only mark vertices stale, each is followed by a query for the
     # final-layer rows of 1000 random vertices, which recomputes the stale part of their L-hop in-neighbourhood
     on_demand = None
-    if cfg.spec.kind not in (wl.GAT, wl.AGNN) and not args.agg_only:
+    if cfg.spec.kind not in (wl.GAT, wl.AGNN, wl.GGCN) and not args.agg_only:
         rng = np.random.default_rng(args.seed + 77)
         ses.lazy(True)
         t_apply = t_query = 0.0

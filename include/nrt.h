@@ -51,7 +51,7 @@ typedef enum {
     NRT_ERR_UNSUPPORTED = 6  /* model shape outside what the kernels cover                            */
 } nrt_status;
 
-typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7, NRT_MONET = 8 } nrt_model_kind;
+typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7, NRT_MONET = 8, NRT_GGCN = 9 } nrt_model_kind;
 
 typedef struct nrt_graph nrt_graph;
 typedef struct nrt_cache nrt_cache;
@@ -80,6 +80,9 @@ typedef struct nrt_cache nrt_cache;
  *                 precisions monet_prec[l] (both [J][d_{l-1}], precisions >= 0):
  *                 g_j(x) = exp( -1/2 sum_k monet_prec[l][j][k] (x_k - monet_mu[l][j][k])^2 );
  *                 a_v = sum_{u in N(v)} g(x_u)  (a J-vector);  h_v = act( a_v W[l][0] + b[l][0] ),  W[l][0] is [J][d_l]
+ *   NRT_GGCN      (Table II row G-GCN)  a_v = sum_{u in N(v)} sigmoid(x_u W_1 + x_v W_2) * x_u element by element, with
+ *                 W[l][1] = [W_1; W_2] of shape [2 d_{l-1}][d_{l-1}];  h_v = act( a_v W[l][0] + b[l][0] ).  Constrained
+ *                 like NRT_AGNN (the gate reads the destination's own row)
  * W, b, att_* are device pointers, row-major [in][out] / [heads][head_dim]; b entries may be NULL (zero).
  * They are copied at nrt_cache_init.
  */

@@ -44,6 +44,9 @@ Readings taken where the paper is silent or garbled (the GPU path takes the same
     in the printed row), the aggregate is the J-vector of summed responses and W maps J to the layer width.  No
     self term in the row; a vertex affected at layer l-1 stays affected at layer l (the structural rule of all
     models here), its row then simply does not change unless an in-neighbour did.
+  * G-GCN: the sigma of its message is the logistic function (a gate in (0, 1), as in gated graph ConvNets), applied
+    element by element to W_1 h_u + W_2 h_v, both matrices square; the sigma of its update is the ReLU of the
+    other models; no self term in the row.
   * GAT: z = x W viewed [heads][head_dim]; e_uv = LeakyReLU(a_dst . z_v + a_src . z_u)
     (destination first, as in Eq. 3); softmax over N(v) U {v}; heads concatenated; ELU on
     hidden layers.
@@ -57,8 +60,9 @@ import subprocess
 from typing import List, Optional, Sequence
 
 import numpy as np
+from scipy.special import expit
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET = 1, 2, 3, 4, 5, 6, 7, 8
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET, GGCN = 1, 2, 3, 4, 5, 6, 7, 8, 9
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librtec_oracle.so")
@@ -223,6 +227,16 @@ def layer(spec, params, l: int, n: int, src, dst, w, x: np.ndarray) -> np.ndarra
         diff = x[:, None, :] - mu[None, :, :]
         g = np.exp(-0.5 * (prec[None, :, :] * diff * diff).sum(axis=2))
         a = in_sum(n, src, dst, None, g)
+        y = a @ W[0]
+        if b[0] is not None:
+            y = y + b[0]
+    elif spec.kind == GGCN:
+        # Table II G-GCN row: message sigma(W_1 h_u + W_2 h_v) * h_u element by element, plain sum, update sigma(W a_v).
+        d = x.shape[1]
+        p1, p2 = x @ W[1][:d], x @ W[1][d:]
+        gate = expit(p1[src] + p2[dst])
+        a = np.zeros((n, d))
+        np.add.at(a, dst, gate * x[src])
         y = a @ W[0]
         if b[0] is not None:
             y = y + b[0]

@@ -1,4 +1,7 @@
 // A-GNN (Table II): the message of an edge <u,v> is w * cos(h_v, h_u) * h_u, summed over the in-neighbours.
+// G-GCN (Table II) shares every kernel of this file (template flag GATE): its message is sigmoid(W_1 h_u + W_2 h_v) * h_u
+// element by element, with the two projections cached per vertex (and the old W_1 h_u of the changed vertices kept
+// compact next to their old rows).
 //
 // The coefficient reads the destination's own embedding, so the model is one of the paper's constrained ones
 // (Section III-D): a destination whose own h^{l-1} changed is summed again over its whole in-neighbourhood; every
@@ -27,11 +30,39 @@ __device__ inline float wave_sum(float x) {
 
 __device__ inline bool in_set(const uint32_t* bm, int32_t v) { return (bm[(uint32_t)v >> 5] >> (v & 31)) & 1u; }
 
-// acc += sum_t c[t] * (hv . row_t) * row_t for t < nt (uniform over the wave); the rows are loaded together
-template <int NV>
-__device__ inline void add_terms(const float* (&row)[AG_TERMS], const float (&c)[AG_TERMS], int nt, const float4 (&hv)[NV],
-                                 float4 (&acc)[NV], const bool (&live)[NV], int lane) {
+__device__ inline float sigmoidf(float x) { return 1.0f / (1.0f + expf(-x)); }
+
+// A-GNN: acc += sum_t c[t] * (hv . row_t) * row_t for t < nt (uniform over the wave); the rows are loaded together.
+// G-GCN (GATE): acc += sum_t c[t] * sigmoid(aux_t + hv) * row_t element by element (hv = the destination's W_2 h_v,
+// aux_t = the source's W_1 h_u), c[t] = +-1.
+template <int NV, bool GATE>
+__device__ inline void add_terms(const float* (&row)[AG_TERMS], const float* (&aux)[AG_TERMS], const float (&c)[AG_TERMS],
+                                 int nt, const float4 (&hv)[NV], float4 (&acc)[NV], const bool (&live)[NV], int lane) {
     float4 x[AG_TERMS][NV];
+    if (GATE) {
+        float4 g[AG_TERMS][NV];
+#pragma unroll
+        for (int t = 0; t < AG_TERMS; ++t)
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                x[t][q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                g[t][q] = x[t][q];
+                if (t < nt && live[q]) {
+                    x[t][q] = *reinterpret_cast<const float4*>(row[t] + lane * 4 + q * 256);
+                    g[t][q] = *reinterpret_cast<const float4*>(aux[t] + lane * 4 + q * 256);
+                }
+            }
+#pragma unroll
+        for (int t = 0; t < AG_TERMS; ++t)
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                acc[q].x += c[t] * sigmoidf(g[t][q].x + hv[q].x) * x[t][q].x;
+                acc[q].y += c[t] * sigmoidf(g[t][q].y + hv[q].y) * x[t][q].y;
+                acc[q].z += c[t] * sigmoidf(g[t][q].z + hv[q].z) * x[t][q].z;
+                acc[q].w += c[t] * sigmoidf(g[t][q].w + hv[q].w) * x[t][q].w;
+            }
+        return;
+    }
     float d[AG_TERMS];
 #pragma unroll
     for (int t = 0; t < AG_TERMS; ++t) {
@@ -64,7 +95,7 @@ __device__ inline void add_terms(const float* (&row)[AG_TERMS], const float (&c)
 
 // acc += the terms of in-list entries [base, base + cnt) for destination row hv (cv = w / |h_v|): every entry when
 // `full`, else the exchange new - old of the entries whose source changed.  Returns the number of rows' sources used.
-template <int NV>
+template <int NV, bool GATE>
 __device__ inline int sum_terms(const AgnnArgs& a, int64_t base, int32_t cnt, bool full, const float4 (&hv)[NV], float cv,
                                 float4 (&acc)[NV], const bool (&live)[NV], int lane) {
     const int D = a.D;
@@ -78,23 +109,26 @@ __device__ inline int sum_terms(const AgnnArgs& a, int64_t base, int32_t cnt, bo
             take = take && in_set(a.src_bitmap, u);
             if (take) slot = a.src_slot[u];
         }
-        const float ru = take ? a.R[u] : 0.f;
-        const float ro = (take && !full) ? a.old_r[slot] : 0.f;
+        const float ru = GATE ? 1.0f : (take ? a.R[u] : 0.f);
+        const float ro = GATE ? 1.0f : ((take && !full) ? a.old_r[slot] : 0.f);
         unsigned long long m = __ballot(take);
         pairs += __popcll(m);
         // in in-list order, AG_TERMS rows at a time: the sum does not depend on the schedule
         while (m) {
             const float* row[AG_TERMS];
+            const float* aux[AG_TERMS];
             float c[AG_TERMS];
             int nt = 0;
             if (full) {
 #pragma unroll
                 for (int t = 0; t < AG_TERMS; ++t) {
-                    row[t] = a.H; c[t] = 0.f;
+                    row[t] = a.H; aux[t] = a.H; c[t] = 0.f;
                     if (m) {
                         const int b = __ffsll((long long)m) - 1;
                         m &= m - 1;
-                        row[t] = a.H + (int64_t)__shfl(u, b, 64) * D;
+                        const int64_t uu = __shfl(u, b, 64);
+                        row[t] = a.H + uu * D;
+                        if (GATE) aux[t] = a.P1 + uu * D;
                         c[t] = cv * __shfl(ru, b, 64);
                         nt = t + 1;
                     }
@@ -102,19 +136,21 @@ __device__ inline int sum_terms(const AgnnArgs& a, int64_t base, int32_t cnt, bo
             } else {                                      // the new term of a changed in-neighbour minus its old one
 #pragma unroll
                 for (int t = 0; t < AG_TERMS; t += 2) {
-                    row[t] = a.H; c[t] = 0.f; row[t + 1] = a.H; c[t + 1] = 0.f;
+                    row[t] = a.H; aux[t] = a.H; c[t] = 0.f; row[t + 1] = a.H; aux[t + 1] = a.H; c[t + 1] = 0.f;
                     if (m) {
                         const int b = __ffsll((long long)m) - 1;
                         m &= m - 1;
-                        row[t] = a.H + (int64_t)__shfl(u, b, 64) * D;
+                        const int64_t uu = __shfl(u, b, 64), ss = __shfl(slot, b, 64);
+                        row[t] = a.H + uu * D;
                         c[t] = cv * __shfl(ru, b, 64);
-                        row[t + 1] = a.old_rows + (int64_t)__shfl(slot, b, 64) * D;
+                        row[t + 1] = a.old_rows + ss * D;
                         c[t + 1] = -cv * __shfl(ro, b, 64);
+                        if (GATE) { aux[t] = a.P1 + uu * D; aux[t + 1] = a.old_p1 + ss * D; }
                         nt = t + 2;
                     }
                 }
             }
-            add_terms<NV>(row, c, nt, hv, acc, live, lane);
+            add_terms<NV, GATE>(row, aux, c, nt, hv, acc, live, lane);
         }
     }
     return pairs;
@@ -145,7 +181,7 @@ __global__ void agnn_norms_kernel(const int32_t* list, const uint64_t* count_dev
 
 // One wave per unit (a destination with a short in-list, or one item of a long one).  NV: 16-byte pieces of a row
 // per lane (rows of up to 256 * NV floats).
-template <int NV>
+template <int NV, bool GATE>
 __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) {
     const int lane = threadIdx.x & 63;
     const int D = a.D;
@@ -182,15 +218,15 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
             hv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (live[q]) hv[q] = *reinterpret_cast<const float4*>(a.H + (int64_t)v * D + lane * 4 + q * 256);
+            if (live[q]) hv[q] = *reinterpret_cast<const float4*>((GATE ? a.P2 : a.H) + (int64_t)v * D + lane * 4 + q * 256);
         }
-        const float cv = a.beta * a.R[v];
+        const float cv = GATE ? 1.0f : a.beta * a.R[v];
 
       // at most two passes: an exchange that cancels most of the row is redone as a full sum (see below)
       for (;;) {
 #pragma unroll
         for (int q = 0; q < NV; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        pairs += sum_terms<NV>(a, base, cnt, full, hv, cv, acc, live, lane);
+        pairs += sum_terms<NV, GATE>(a, base, cnt, full, hv, cv, acc, live, lane);
 
         if (part) {
             // an item holds its share of the whole sum, or of the exchange (the first item also takes the structural
@@ -255,7 +291,7 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
 // One wave per destination with a long in-list: its items' rows are added up in item order.  They are the whole sum when
 // the destination's own row changed (or nothing is incremental), else an exchange that is added to the cached
 // aggregate under the same guard as above; a guarded destination is summed again over its whole in-list by this wave.
-template <int NV>
+template <int NV, bool GATE>
 __global__ void __launch_bounds__(AG_WAVES * 64) agnn_combine_kernel(AgnnArgs a) {
     const int lane = threadIdx.x & 63;
     const int D = a.D;
@@ -308,9 +344,9 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_combine_kernel(AgnnArgs a)
             for (int q = 0; q < NV; ++q) {
                 hv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
                 tot[q] = hv[q];
-                if (live[q]) hv[q] = *reinterpret_cast<const float4*>(a.H + (int64_t)v * D + lane * 4 + q * 256);
+                if (live[q]) hv[q] = *reinterpret_cast<const float4*>((GATE ? a.P2 : a.H) + (int64_t)v * D + lane * 4 + q * 256);
             }
-            sum_terms<NV>(a, rec.off, rec.deg, true, hv, a.beta * a.R[v], tot, live, lane);
+            sum_terms<NV, GATE>(a, rec.off, rec.deg, true, hv, GATE ? 1.0f : a.beta * a.R[v], tot, live, lane);
         }
 #pragma unroll
         for (int q = 0; q < NV; ++q)
@@ -332,11 +368,18 @@ __global__ void agnn_structural_fold_kernel(AgnnFoldArgs a) {
     const int D = a.D[l];
     const float* hu = a.H[l] + (int64_t)u * D;
     const float* hv = a.H[l] + (int64_t)v * D;
+    float* dst = a.SD[l] + (int64_t)a.dd_slot[v] * D;
+    if (a.gate) {                   // G-GCN: sign * sigmoid(W_1 h_src + W_2 h_dst) * h_src, element by element
+        const float sign = is_del ? -1.0f : 1.0f;
+        const float* p1 = a.P1[l] + (int64_t)u * D;
+        const float* p2 = a.P2[l] + (int64_t)v * D;
+        for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, sign * sigmoidf(p1[k] + p2[k]) * hu[k]);
+        return;
+    }
     float d = 0.f;
     for (int k = lane; k < D; k += 64) d += hu[k] * hv[k];
     d = wave_sum(d);
     const float c = (is_del ? -1.0f : 1.0f) * a.beta[l] * a.R[l][u] * a.R[l][v] * d;
-    float* dst = a.SD[l] + (int64_t)a.dd_slot[v] * D;
     for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, c * hu[k]);
 }
 
@@ -354,17 +397,29 @@ nrt_status k_agnn_norms(const int32_t* list, const uint64_t* count_dev, int64_t 
 
 nrt_status k_agnn_gather(const AgnnArgs& a, hipStream_t s) {
     if (a.D % 4 || a.D > 1024) { nrt_set_error("agnn: row width must be a multiple of 4, at most 1024"); return NRT_ERR_UNSUPPORTED; }
-    if (a.D <= 256) agnn_gather_kernel<1><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
-    else if (a.D <= 512) agnn_gather_kernel<2><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
-    else agnn_gather_kernel<4><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+    if (a.gate) {
+        if (a.D <= 256) agnn_gather_kernel<1, true><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else if (a.D <= 512) agnn_gather_kernel<2, true><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else agnn_gather_kernel<4, true><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+    } else {
+        if (a.D <= 256) agnn_gather_kernel<1, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else if (a.D <= 512) agnn_gather_kernel<2, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else agnn_gather_kernel<4, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+    }
     LAUNCH_CHECK();
     return NRT_OK;
 }
 
 nrt_status k_agnn_combine(const AgnnArgs& a, hipStream_t s) {
-    if (a.D <= 256) agnn_combine_kernel<1><<<1024, AG_WAVES * 64, 0, s>>>(a);
-    else if (a.D <= 512) agnn_combine_kernel<2><<<1024, AG_WAVES * 64, 0, s>>>(a);
-    else agnn_combine_kernel<4><<<1024, AG_WAVES * 64, 0, s>>>(a);
+    if (a.gate) {
+        if (a.D <= 256) agnn_combine_kernel<1, true><<<1024, AG_WAVES * 64, 0, s>>>(a);
+        else if (a.D <= 512) agnn_combine_kernel<2, true><<<1024, AG_WAVES * 64, 0, s>>>(a);
+        else agnn_combine_kernel<4, true><<<1024, AG_WAVES * 64, 0, s>>>(a);
+    } else {
+        if (a.D <= 256) agnn_combine_kernel<1, false><<<1024, AG_WAVES * 64, 0, s>>>(a);
+        else if (a.D <= 512) agnn_combine_kernel<2, false><<<1024, AG_WAVES * 64, 0, s>>>(a);
+        else agnn_combine_kernel<4, false><<<1024, AG_WAVES * 64, 0, s>>>(a);
+    }
     LAUNCH_CHECK();
     return NRT_OK;
 }

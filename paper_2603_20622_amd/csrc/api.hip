@@ -43,6 +43,10 @@ struct nrt_cache {
     float* ES[NRT_MAX_LAYERS + 1];      // agg_only: h^l of the sources of the batch's updated edges, one row per update
     int32_t* es_rows;                   // agg_only: those sources, inserts first
     float* R[NRT_MAX_LAYERS + 1];       // A-GNN: inverse norms of the rows of h^l (null otherwise)
+    float* P1[NRT_MAX_LAYERS + 1];      // G-GCN: W_1 h^l and W_2 h^l by vertex (null otherwise)
+    float* P2[NRT_MAX_LAYERS + 1];
+    float* old_p1;                      // G-GCN: [N][max d] compact, W_1 h of the changed rows before the batch
+    float* W2t[NRT_MAX_LAYERS];         // G-GCN: transposed W_2 (W_1 sits in Wt[l][1])
     float* r_old;                       // A-GNN: [N] compact, inverse norms of the changed rows before the batch
     float agnn_beta[NRT_MAX_LAYERS];
     float* MP[NRT_MAX_LAYERS + 1];      // PinSAGE, MoNet: message payload of layer l's rows (ReLU(h^l Q + q); the Gaussian
@@ -246,12 +250,14 @@ static inline bool concat_self(int kind) { return kind == NRT_SAGE_MEAN || kind 
 
 // models that aggregate a per-vertex transform of h instead of h itself, cached by vertex
 static inline bool has_message_cache(int kind) { return kind == NRT_PINSAGE || kind == NRT_MONET; }
+// constrained models served by the kernels of agnn.hip
+static inline bool agnn_family(int kind) { return kind == NRT_AGNN || kind == NRT_GGCN; }
 // models whose messages carry the edge weight
 static inline bool weighted_messages(int kind) { return kind == NRT_GIN || kind == NRT_PINSAGE; }
 
 static nrt_status check_desc(const nrt_model_desc* d) {
     REQUIRE(d, "model desc is null");
-    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_MONET, "unknown model kind");
+    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_GGCN, "unknown model kind");
     REQUIRE(d->n_layers >= 1 && d->n_layers <= NRT_MAX_LAYERS, "n_layers out of range");
     for (int l = 0; l <= d->n_layers; ++l) {
         if (d->dims[l] <= 0 || d->dims[l] % 4 || d->dims[l] > 1024) {
@@ -306,6 +312,13 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     }
     for (int l = 0; l <= c->L; ++l) c->R[l] = (c->kind == NRT_AGNN && l < c->L) ? b.take<float>(n) : nullptr;
     c->r_old = c->kind == NRT_AGNN ? b.take<float>(n) : nullptr;
+    for (int l = 0; l <= c->L; ++l) {
+        const bool on = c->kind == NRT_GGCN && l < c->L;
+        c->P1[l] = on ? b.take<float>(n * c->dims[l]) : nullptr;
+        c->P2[l] = on ? b.take<float>(n * c->dims[l]) : nullptr;
+        if (l < c->L) c->W2t[l] = on ? b.take<float>((size_t)c->dims[l] * c->dims[l]) : nullptr;
+    }
+    c->old_p1 = c->kind == NRT_GGCN ? b.take<float>(n * maxd) : nullptr;
     c->S[0] = nullptr;
     const bool gat = c->kind == NRT_GAT;
     for (int l = 1; l <= c->L; ++l) {
@@ -337,7 +350,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         if (c->kind == NRT_GIN) {
             c->Wt[l][1] = b.take<float>((size_t)c->dims[l + 1] * c->dims[l + 1]);
             c->bias[l][1] = b.take<float>(c->dims[l + 1]);
-        } else if (c->kind == NRT_PINSAGE) {
+        } else if (c->kind == NRT_PINSAGE || c->kind == NRT_GGCN) {
             c->Wt[l][1] = b.take<float>((size_t)c->dims[l] * c->dims[l]);
             c->bias[l][1] = b.take<float>(c->dims[l]);
         } else {
@@ -722,7 +735,7 @@ static nrt_status run_update_unkept(nrt_cache* c, int l, const int32_t* rows, in
     return k_gemm(a, s);
 }
 
-// One A-GNN layer: norms of the changed rows of h^{l-1} (src_rows null: all rows), the cosine-weighted gather over the
+// One A-GNN or G-GCN layer: norms (G-GCN: the two projections) of the changed rows of h^{l-1} (src_rows null: all rows), the gather over the
 // destinations described by c->recs (listed in `rows`, null: all n), the sums of long in-lists, the dense update.
 static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
                                  const int32_t* rows, const uint64_t* M_dev, int64_t M, bool incremental, int prev, int cur,
@@ -730,8 +743,32 @@ static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, c
     nrt_graph* g = c->g;
     const bool last = l == c->L;
     const int D = c->dims[l - 1];
-    NRT_TRY(k_agnn_norms(src_rows, n_src_dev, src_rows ? src_bound : g->n, c->H[l - 1], D, c->R[l - 1],
-                         (incremental && src_rows) ? c->r_old : nullptr, s));
+    const bool gate = c->kind == NRT_GGCN;
+    if (gate) {                                   // the two projections of the rows of h^{l-1} that changed
+        GemmArgs p;
+        memset(&p, 0, sizeof(p));
+        p.M = src_rows ? src_bound : g->n;
+        p.M_dev = n_src_dev;
+        p.rows = src_rows;
+        p.a_mode = A_PLAIN;
+        p.P0 = c->H[l - 1];
+        p.ldp = D;
+        p.K = D;
+        p.N = D;
+        p.n_vertices = g->n;
+        p.Wt = c->Wt[l - 1][1];
+        p.H = c->P1[l - 1];
+        p.DP = (incremental && src_rows) ? c->old_p1 : nullptr;    // the W_1 rows this launch replaces
+        p.dp_store_old = 1;
+        NRT_TRY(k_gemm(p, s));
+        p.Wt = c->W2t[l - 1];
+        p.H = c->P2[l - 1];
+        p.DP = nullptr;
+        NRT_TRY(k_gemm(p, s));
+    } else {
+        NRT_TRY(k_agnn_norms(src_rows, n_src_dev, src_rows ? src_bound : g->n, c->H[l - 1], D, c->R[l - 1],
+                             (incremental && src_rows) ? c->r_old : nullptr, s));
+    }
     NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
     AgnnArgs a;
     memset(&a, 0, sizeof(a));
@@ -743,6 +780,10 @@ static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, c
     a.R = c->R[l - 1];
     a.D = D;
     a.beta = c->agnn_beta[l - 1];
+    a.gate = gate ? 1 : 0;
+    a.P1 = c->P1[l - 1];
+    a.P2 = c->P2[l - 1];
+    a.old_p1 = c->old_p1;
     a.S = c->S[l];
     if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     if (incremental) {
@@ -799,7 +840,7 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
             st = run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, false, 0, nullptr, 0, s);
             continue;
         }
-        if (c->kind == NRT_AGNN) {
+        if (agnn_family(c->kind)) {
             st = run_agnn_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, 0, 0, nullptr, 0, s);
             continue;
         }
@@ -828,6 +869,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         REQUIRE(d->W[l][0], "W[l][0] is null");
         if (d->kind == NRT_GIN) REQUIRE(d->W[l][1], "GIN needs W[l][1]");
         if (d->kind == NRT_PINSAGE) REQUIRE(d->W[l][1], "PinSAGE needs W[l][1]");
+        if (d->kind == NRT_GGCN) REQUIRE(d->W[l][1], "G-GCN needs W[l][1] = [W_1; W_2]");
         if (d->kind == NRT_MONET) REQUIRE(d->monet_mu[l] && d->monet_prec[l], "MoNet needs monet_mu[l] and monet_prec[l]");
         if (d->kind == NRT_GAT) REQUIRE(d->att_src[l] && d->att_dst[l], "GAT needs att_src[l] and att_dst[l]");
     }
@@ -856,6 +898,11 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
             NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
             if (d->b[l][0]) NRT_TRY(k_copy_f32(c->bias[l][0], d->b[l][0], c->dims[l + 1], s));
             else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][0], c->dims[l + 1], 0, s));
+            if (c->kind == NRT_GGCN) {                     // W[l][1] is [2 d][d]: W_1 on top of W_2
+                const int dq = c->dims[l];
+                NRT_TRY(k_transpose(d->W[l][1], c->Wt[l][1], dq, dq, s));
+                NRT_TRY(k_transpose(d->W[l][1] + (size_t)dq * dq, c->W2t[l], dq, dq, s));
+            }
             if (c->kind == NRT_MONET) {
                 NRT_TRY(k_transpose(d->monet_mu[l], c->muT[l], c->monet_J, c->dims[l], s));
                 NRT_TRY(k_transpose(d->monet_prec[l], c->precT[l], c->monet_J, c->dims[l], s));
@@ -963,7 +1010,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     // (no extra launches for small frontiers); the device counters of this batch take the decision
     bool may_rec[NRT_MAX_LAYERS + 2];
     for (int l = 0; l <= c->L + 1; ++l)
-        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && c->kind != NRT_AGNN && !c->agg_only && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
+        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && !agnn_family(c->kind) && !c->agg_only && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     if (!empty_batch) NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, n, s));
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     if (inc && b->n_ins + b->n_del > 0) {
@@ -988,7 +1035,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         }
         NRT_TRY(k_gat_structural_fold(f, s));
     }
-    if (inc && c->kind == NRT_AGNN) {
+    if (inc && agnn_family(c->kind)) {
         AgnnFoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del; f.n = n;
@@ -998,10 +1045,12 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         for (int l = 1; l <= c->L; ++l) {
             f.H[l - 1] = c->H[l - 1]; f.R[l - 1] = c->R[l - 1]; f.SD[l - 1] = c->SD[l];
             f.D[l - 1] = c->dagg[l]; f.beta[l - 1] = c->agnn_beta[l - 1];
+            f.P1[l - 1] = c->P1[l - 1]; f.P2[l - 1] = c->P2[l - 1];
         }
+        f.gate = c->kind == NRT_GGCN;
         NRT_TRY(k_agnn_structural_fold(f, s));
     }
-    if (inc && c->kind != NRT_GAT && c->kind != NRT_AGNN) {
+    if (inc && c->kind != NRT_GAT && !agnn_family(c->kind)) {
         FoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
@@ -1076,7 +1125,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         da.DP = c->DP[0];
         da.D = c->dims[0];
         if (gcn && inc) { da.indeg_new = g->in.deg; da.indeg_old = c->indeg_old; }
-        da.store_old = c->kind == NRT_AGNN;
+        da.store_old = agnn_family(c->kind);
         NRT_TRY(k_layer0_delta(da, s));
     }
     NRT_TRY(prof_mark(c, TAG_INGEST, 0, s));
@@ -1119,7 +1168,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         if (c->kind == NRT_GAT) {
             NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
                                   inc, prev, l == c->L ? affected_rows : nullptr, capacity, s));
-        } else if (c->kind == NRT_AGNN) {
+        } else if (agnn_family(c->kind)) {
             NRT_TRY(run_agnn_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, inc,
                                    prev, cur, l == c->L ? affected_rows : nullptr, capacity, s));
         } else {
@@ -1257,8 +1306,8 @@ static nrt_status finish_recompute(nrt_cache* c, int64_t* n_recomputed, hipStrea
 
 extern "C" nrt_status nrt_set_lazy(nrt_cache* c, int32_t on, void* stream) {
     REQUIRE(c, "null argument");
-    if (c->kind == NRT_GAT || c->kind == NRT_AGNN || c->agg_only) {
-        nrt_set_error("on-demand mode is not available for GAT, A-GNN and aggregate-only storage");
+    if (c->kind == NRT_GAT || agnn_family(c->kind) || c->agg_only) {
+        nrt_set_error("on-demand mode is not available for GAT, A-GNN, G-GCN and aggregate-only storage");
         return NRT_ERR_UNSUPPORTED;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);

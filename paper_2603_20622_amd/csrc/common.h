@@ -332,6 +332,9 @@ struct AgnnArgs {
     const int32_t* dd_slot;
     float* S;                       // [N][D] cached aggregate
     unsigned long long* pair_ctr;   // null or 1024 counters: rows of h fetched (a statistic)
+    int gate;                       // G-GCN: element-wise gate sigmoid(P1[u] + P2[v]) instead of the cosine
+    const float* P1; const float* P2;   // [N][D] W_1 h and W_2 h, current
+    const float* old_p1;            // [changed][D] compact: W_1 h before this batch
 };
 struct AgnnFoldArgs {   // structural terms of a batch, evaluated on the pre-update caches, all layers in one launch
     int64_t n_ins, n_del, n;        // edges with an id outside [0, n) are skipped
@@ -343,6 +346,8 @@ struct AgnnFoldArgs {   // structural terms of a batch, evaluated on the pre-upd
     float* SD[NRT_MAX_LAYERS];
     int D[NRT_MAX_LAYERS];
     float beta[NRT_MAX_LAYERS];
+    int gate;                         // G-GCN
+    const float* P1[NRT_MAX_LAYERS]; const float* P2[NRT_MAX_LAYERS];
 };
 // R[v] = 1/|H[v]| for v in list[0 .. *count_dev) (list null: rows 0 .. bound); r_old[m] (may be null) keeps the old value
 nrt_status k_agnn_norms(const int32_t* list, const uint64_t* count_dev, int64_t bound, const float* H, int D, float* R,

@@ -18,8 +18,8 @@ from typing import Dict, List, Optional
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET = 1, 2, 3, 4, 5, 6, 7, 8
-KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage", AGNN: "agnn", MONET: "monet"}
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET, GGCN = 1, 2, 3, 4, 5, 6, 7, 8, 9
+KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage", AGNN: "agnn", MONET: "monet", GGCN: "ggcn"}
 
 
 @dataclass
@@ -149,6 +149,8 @@ def make_params(spec: ModelSpec, seed: int = 0, bias: bool = False) -> Params:
             Ws.append(_glorot(rng, dout, dout, (dout, dout)))
         if spec.kind == PINSAGE:
             Ws.append(_glorot(rng, din, din, (din, din)))
+        if spec.kind == GGCN:                                   # [W_1; W_2], the gate's two projections
+            Ws.append(_glorot(rng, 2 * din, din, (2 * din, din)))
         bs: List[Optional[np.ndarray]] = []
         for W in Ws:
             bs.append(rng.uniform(-0.1, 0.1, size=W.shape[1]).astype(np.float32) if bias else None)

@@ -11,7 +11,7 @@ from paper_2603_20622_amd import workloads as wl
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-4
-UNNORMALISED = (wl.GIN, wl.COMMNET, wl.AGNN, wl.MONET)      # plain sums: magnitudes grow with degree and depth
+UNNORMALISED = (wl.GIN, wl.COMMNET, wl.AGNN, wl.MONET, wl.GGCN)      # plain sums: magnitudes grow with degree and depth
 
 
 def rel_err(gpu: np.ndarray, ref: np.ndarray) -> float:
@@ -65,7 +65,7 @@ def small_case(kind, seed=0, n=3000, e=40000, dims=None, bias=False, L=2):
     return n, src, dst, w, x, spec, params, stream
 
 
-KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET]
+KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN]
 WEIGHTED = (wl.GIN, wl.PINSAGE)           # models whose messages carry the edge weight
 
 
@@ -255,6 +255,7 @@ def test_gin_cancellation_is_guarded(S, oracle):
     (wl.PINSAGE, [20, 132, 12], 1, 0),          # message transforms 20x20 and 132x132
     (wl.AGNN, [300, 520, 8], 1, 0),             # cosine rows of two and of four 16-byte pieces per lane
     (wl.MONET, [36, 132, 8], 1, 0),             # 260 kernels: wider than every layer
+    (wl.GGCN, [260, 36, 8], 1, 0),              # gate rows of two 16-byte pieces per lane
     (wl.GAT, [24, 512, 512], 8, 64),            # 512-wide attention rows, 8 heads
     (wl.GAT, [12, 8, 8], 2, 4),                 # smallest head width
 ])
@@ -649,7 +650,7 @@ def test_on_demand_queries_match_oracle(S, oracle, kind):
         assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "eager", l))
 
 
-@pytest.mark.parametrize("kind", [wl.GAT, wl.AGNN])
+@pytest.mark.parametrize("kind", [wl.GAT, wl.AGNN, wl.GGCN])
 def test_on_demand_is_refused_for_constrained_models(S, oracle, kind):
     from paper_2603_20622_amd import binding as nb
     n, src, dst, w, x, spec, params, stream = small_case(kind, seed=5)

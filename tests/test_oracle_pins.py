@@ -1,7 +1,7 @@
 """Pins for the CPU oracle: things other than the oracle itself that fix its values.
 
   * brute force: a per-vertex recursive evaluation of the message-aggregate-update layer (Eq. 1)
-    from hand-written adjacency lists, in Python floats, for all eight models;
+    from hand-written adjacency lists, in Python floats, for all nine models;
   * the dense-matrix closed forms the models reduce to (normalised adjacency products);
   * closed forms on special graphs / parameters (cycle, constant features, zero attention,
     two-term softmax, star hub);
@@ -63,6 +63,15 @@ def brute_embedding(spec, params, in_nbrs, x, v, l):
             for k in range(d):
                 m[k] += float(w) * mu[k] / len(in_nbrs[v])
         y = _lin(hv + m, W[0], b[0])
+        act = "relu"
+    elif spec.kind == wl.GGCN:
+        a = [0.0] * d
+        for u, _ in in_nbrs[v]:
+            g1 = _lin(hu[u], W[1][:d])
+            g2 = _lin(hv, W[1][d:])
+            for k in range(d):
+                a[k] += hu[u][k] / (1.0 + math.exp(-(g1[k] + g2[k])))
+        y = _lin(a, W[0], b[0])
         act = "relu"
     elif spec.kind == wl.MONET:
         mu, prec = params.monet_mu[l - 1], params.monet_prec[l - 1]
@@ -154,7 +163,7 @@ def _in_lists(n, src, dst, w):
     return lists
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN])
 @pytest.mark.parametrize("L", [1, 2, 3])
 def test_forward_matches_brute_force(oracle, kind, L):
     n, src, dst, w, x, spec, params = _tiny(kind, L, seed=3 + L)
@@ -410,6 +419,49 @@ def test_monet_special_kernels_by_hand(oracle):
     np.testing.assert_allclose(got[1:, 0], 0.0, atol=0)
 
 
+def test_ggcn_is_gated_sum_in_matrix_form(oracle):
+    """Table II G-GCN row with dense tensors: gate[v, u, :] = sigmoid(h_u W_1 + h_v W_2) on the edges, a_v = sum_u
+    gate[v, u] * h_u, H' = act(a W + b)."""
+    n, e = 30, 170
+    src, dst, _ = wl.rmat_graph(n, e, seed=31)
+    spec = wl.ModelSpec(wl.GGCN, [4, 5, 3])
+    params = wl.make_params(spec, 32, bias=True)
+    x = wl.features(n, 4, 33).astype(np.float64)
+    f = lambda a: a.astype(np.float64)
+    A = _dense_adj(n, src, dst)
+    h = x
+    for l, d in enumerate([4, 5]):
+        W12 = f(params.W[l][1])
+        gate = 1.0 / (1.0 + np.exp(-((h @ W12[:d])[None, :, :] + (h @ W12[d:])[:, None, :])))     # [v, u, k]
+        a = np.einsum("vu,vuk,uk->vk", A, gate, h)
+        h = a @ f(params.W[l][0]) + f(params.b[l][0])
+        if l == 0:
+            h = np.maximum(h, 0)
+    outs = oracle.forward(spec, params, n, src, dst, None, x.astype(np.float32))
+    np.testing.assert_allclose(outs[1], h, rtol=1e-10, atol=1e-12)
+
+
+def test_ggcn_zero_gate_weights_halve_commnet_sum(oracle):
+    """W_1 = W_2 = 0: every gate is sigmoid(0) = 1/2, so a_v is half the plain neighbour sum.  One edge by hand:
+    0 -> 1, x_0 = 2, x_1 = -1, W_1 = 1, W_2 = 3: gate = sigmoid(2 - 3), a_1 = gate * 2, W = 5."""
+    n, e = 25, 120
+    src, dst, _ = wl.rmat_graph(n, e, seed=34)
+    spec = wl.ModelSpec(wl.GGCN, [3, 2])
+    params = wl.make_params(spec, 35)
+    params.W[0][1][:] = 0
+    x = wl.features(n, 3, 36)
+    out = oracle.forward(spec, params, n, src, dst, None, x)[0]
+    half = 0.5 * (_dense_adj(n, src, dst) @ x.astype(np.float64))
+    np.testing.assert_allclose(out, half @ params.W[0][0].astype(np.float64), rtol=1e-12, atol=1e-14)
+
+    one = wl.ModelSpec(wl.GGCN, [1, 1])
+    p1 = wl.Params(W=[[np.array([[5.0]], np.float32), np.array([[1.0], [3.0]], np.float32)]], b=[[None, None]],
+                   att_src=[None], att_dst=[None])
+    got = oracle.forward(one, p1, 2, np.array([0], np.int32), np.array([1], np.int32), None,
+                         np.array([[2.0], [-1.0]], np.float32))[0]
+    np.testing.assert_allclose(got[:, 0], [0.0, 5 * 2 / (1 + math.exp(1.0))], rtol=1e-14)
+
+
 def test_commnet_single_edge_by_hand(oracle):
     """Edge 0 -> 1, scalar feature, W_1 = 2, W_2 = -3:  h_0 = 2 x_0,  h_1 = 2 x_1 - 3 x_0."""
     spec = wl.ModelSpec(wl.COMMNET, [1, 1])
@@ -579,7 +631,7 @@ def test_affected_sets_hand_enumerated(oracle):
         assert [a.tolist() for a in got] == [[3, 4], [3, 4]]
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN])
 def test_affected_sets_match_reachability_powers(oracle, kind):
     n, e = 70, 260
     src, dst, sampler = wl.rmat_graph(n, e, seed=12)
@@ -603,7 +655,7 @@ def test_affected_sets_match_reachability_powers(oracle, kind):
 
 
 # ------------------------------------------------------------------ invariants
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN])
 def test_batch_invariants(oracle, kind):
     n, e = 200, 1500
     src, dst, sampler = wl.rmat_graph(n, e, seed=13)
