@@ -19,7 +19,8 @@ namespace {
 
 constexpr int AG_WAVES = 4;        // waves per workgroup
 constexpr int AG_BLOCKS = 4096;    // fixed grid: sizes are read on the device
-constexpr int AG_TERMS = 4;        // rows in flight per wave
+constexpr int AG_TERMS = 4;        // row slots loaded together by a wave
+constexpr int AG_LIST = 2 * AG_TERMS;     // terms handed over at a time (two per slot for rows of up to 128 floats)
 constexpr float AG_GUARD_RATIO = 16.0f;   // an exchange larger than this many times what it leaves is redone in full
 
 __device__ inline float wave_sum(float x) {
@@ -35,9 +36,30 @@ __device__ inline float sigmoidf(float x) { return 1.0f / (1.0f + expf(-x)); }
 // A-GNN: acc += sum_t c[t] * (hv . row_t) * row_t for t < nt (uniform over the wave); the rows are loaded together.
 // G-GCN (GATE): acc += sum_t c[t] * sigmoid(aux_t + hv) * row_t element by element (hv = the destination's W_2 h_v,
 // aux_t = the source's W_1 h_u), c[t] = +-1.
-template <int NV, bool GATE>
-__device__ inline void add_terms(const float* (&row)[AG_TERMS], const float* (&aux)[AG_TERMS], const float (&c)[AG_TERMS],
-                                 int nt, const float4 (&hv)[NV], float4 (&acc)[NV], const bool (&live)[NV], int lane) {
+// HALF (rows of up to 128 floats): a row takes 32 lanes, so the two halves of the wave take terms 2s and 2s+1 of row
+// slot s; each half accumulates its own partial row, the caller adds the halves.  A slot beyond nt points at row 0
+// with c = 0.
+template <int NV, bool GATE, bool HALF>
+__device__ inline void add_terms(const float* (&row)[AG_LIST], const float* (&aux)[AG_LIST], const float (&c)[AG_LIST],
+                                 int nt, const float4 (&hv)[NV], float4 (&acc)[NV], const bool (&live)[NV], int lane,
+                                 int col0) {
+    const bool hi = HALF && lane >= 32;
+    const float* r[AG_TERMS];
+    const float* g1[AG_TERMS];
+    float cc[AG_TERMS];
+    bool on[AG_TERMS];
+#pragma unroll
+    for (int t = 0; t < AG_TERMS; ++t) {
+        if (HALF) {
+            r[t] = hi ? row[2 * t + 1] : row[2 * t];
+            g1[t] = hi ? aux[2 * t + 1] : aux[2 * t];
+            cc[t] = hi ? c[2 * t + 1] : c[2 * t];
+            on[t] = 2 * t < nt;
+        } else {
+            r[t] = row[t]; g1[t] = aux[t]; cc[t] = c[t];
+            on[t] = t < nt;
+        }
+    }
     float4 x[AG_TERMS][NV];
     if (GATE) {
         float4 g[AG_TERMS][NV];
@@ -47,19 +69,19 @@ __device__ inline void add_terms(const float* (&row)[AG_TERMS], const float* (&a
             for (int q = 0; q < NV; ++q) {
                 x[t][q] = make_float4(0.f, 0.f, 0.f, 0.f);
                 g[t][q] = x[t][q];
-                if (t < nt && live[q]) {
-                    x[t][q] = *reinterpret_cast<const float4*>(row[t] + lane * 4 + q * 256);
-                    g[t][q] = *reinterpret_cast<const float4*>(aux[t] + lane * 4 + q * 256);
+                if (on[t] && live[q]) {
+                    x[t][q] = *reinterpret_cast<const float4*>(r[t] + col0 + q * 256);
+                    g[t][q] = *reinterpret_cast<const float4*>(g1[t] + col0 + q * 256);
                 }
             }
 #pragma unroll
         for (int t = 0; t < AG_TERMS; ++t)
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
-                acc[q].x += c[t] * sigmoidf(g[t][q].x + hv[q].x) * x[t][q].x;
-                acc[q].y += c[t] * sigmoidf(g[t][q].y + hv[q].y) * x[t][q].y;
-                acc[q].z += c[t] * sigmoidf(g[t][q].z + hv[q].z) * x[t][q].z;
-                acc[q].w += c[t] * sigmoidf(g[t][q].w + hv[q].w) * x[t][q].w;
+                acc[q].x += cc[t] * sigmoidf(g[t][q].x + hv[q].x) * x[t][q].x;
+                acc[q].y += cc[t] * sigmoidf(g[t][q].y + hv[q].y) * x[t][q].y;
+                acc[q].z += cc[t] * sigmoidf(g[t][q].z + hv[q].z) * x[t][q].z;
+                acc[q].w += cc[t] * sigmoidf(g[t][q].w + hv[q].w) * x[t][q].w;
             }
         return;
     }
@@ -70,7 +92,7 @@ __device__ inline void add_terms(const float* (&row)[AG_TERMS], const float* (&a
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
             x[t][q] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (t < nt && live[q]) x[t][q] = *reinterpret_cast<const float4*>(row[t] + lane * 4 + q * 256);
+            if (on[t] && live[q]) x[t][q] = *reinterpret_cast<const float4*>(r[t] + col0 + q * 256);
         }
     }
 #pragma unroll
@@ -79,12 +101,12 @@ __device__ inline void add_terms(const float* (&row)[AG_TERMS], const float* (&a
         for (int q = 0; q < NV; ++q)
             d[t] += hv[q].x * x[t][q].x + hv[q].y * x[t][q].y + hv[q].z * x[t][q].z + hv[q].w * x[t][q].w;
 #pragma unroll
-    for (int s = 32; s >= 1; s >>= 1)
+    for (int s = HALF ? 16 : 32; s >= 1; s >>= 1)         // HALF: the sums stay inside each half of the wave
 #pragma unroll
         for (int t = 0; t < AG_TERMS; ++t) d[t] += __shfl_xor(d[t], s, 64);
 #pragma unroll
     for (int t = 0; t < AG_TERMS; ++t) {
-        const float k = c[t] * d[t];                         // zero rows and c = 0 beyond nt: nothing is added
+        const float k = cc[t] * d[t];                        // zero rows and c = 0 beyond nt: nothing is added
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
             acc[q].x += k * x[t][q].x; acc[q].y += k * x[t][q].y;
@@ -95,9 +117,10 @@ __device__ inline void add_terms(const float* (&row)[AG_TERMS], const float* (&a
 
 // acc += the terms of in-list entries [base, base + cnt) for destination row hv (cv = w / |h_v|): every entry when
 // `full`, else the exchange new - old of the entries whose source changed.  Returns the number of rows' sources used.
-template <int NV, bool GATE>
+template <int NV, bool GATE, bool HALF>
 __device__ inline int sum_terms(const AgnnArgs& a, int64_t base, int32_t cnt, bool full, const float4 (&hv)[NV], float cv,
-                                float4 (&acc)[NV], const bool (&live)[NV], int lane) {
+                                float4 (&acc)[NV], const bool (&live)[NV], int lane, int col0) {
+    constexpr int NT = HALF ? AG_LIST : AG_TERMS;          // terms per hand-over
     const int D = a.D;
     int pairs = 0;
     for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
@@ -113,16 +136,17 @@ __device__ inline int sum_terms(const AgnnArgs& a, int64_t base, int32_t cnt, bo
         const float ro = GATE ? 1.0f : ((take && !full) ? a.old_r[slot] : 0.f);
         unsigned long long m = __ballot(take);
         pairs += __popcll(m);
-        // in in-list order, AG_TERMS rows at a time: the sum does not depend on the schedule
+        // in in-list order, a few rows at a time: the sum does not depend on the schedule
         while (m) {
-            const float* row[AG_TERMS];
-            const float* aux[AG_TERMS];
-            float c[AG_TERMS];
+            const float* row[AG_LIST];
+            const float* aux[AG_LIST];
+            float c[AG_LIST];
+#pragma unroll
+            for (int t = 0; t < AG_LIST; ++t) { row[t] = a.H; aux[t] = a.H; c[t] = 0.f; }
             int nt = 0;
             if (full) {
 #pragma unroll
-                for (int t = 0; t < AG_TERMS; ++t) {
-                    row[t] = a.H; aux[t] = a.H; c[t] = 0.f;
+                for (int t = 0; t < NT; ++t) {
                     if (m) {
                         const int b = __ffsll((long long)m) - 1;
                         m &= m - 1;
@@ -133,10 +157,30 @@ __device__ inline int sum_terms(const AgnnArgs& a, int64_t base, int32_t cnt, bo
                         nt = t + 1;
                     }
                 }
+            } else if (HALF) {
+                // two changed in-neighbours per pair of row slots, one per half of the wave: slot 2p holds their new
+                // terms, slot 2p + 1 their old ones, so that each half adds a neighbour's new term and takes its old
+                // one away back to back (the running sum stays as small as the exchange itself)
+#pragma unroll
+                for (int p = 0; p < AG_LIST / 4; ++p) {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        if (m) {
+                            const int b = __ffsll((long long)m) - 1;
+                            m &= m - 1;
+                            const int64_t uu = __shfl(u, b, 64), ss = __shfl(slot, b, 64);
+                            row[4 * p + h] = a.H + uu * D;
+                            c[4 * p + h] = cv * __shfl(ru, b, 64);
+                            row[4 * p + 2 + h] = a.old_rows + ss * D;
+                            c[4 * p + 2 + h] = -cv * __shfl(ro, b, 64);
+                            if (GATE) { aux[4 * p + h] = a.P1 + uu * D; aux[4 * p + 2 + h] = a.old_p1 + ss * D; }
+                            nt = 4 * p + 4;
+                        }
+                    }
+                }
             } else {                                      // the new term of a changed in-neighbour minus its old one
 #pragma unroll
-                for (int t = 0; t < AG_TERMS; t += 2) {
-                    row[t] = a.H; aux[t] = a.H; c[t] = 0.f; row[t + 1] = a.H; aux[t + 1] = a.H; c[t + 1] = 0.f;
+                for (int t = 0; t < NT; t += 2) {
                     if (m) {
                         const int b = __ffsll((long long)m) - 1;
                         m &= m - 1;
@@ -150,7 +194,7 @@ __device__ inline int sum_terms(const AgnnArgs& a, int64_t base, int32_t cnt, bo
                     }
                 }
             }
-            add_terms<NV, GATE>(row, aux, c, nt, hv, acc, live, lane);
+            add_terms<NV, GATE, HALF>(row, aux, c, nt, hv, acc, live, lane, col0);
         }
     }
     return pairs;
@@ -181,9 +225,11 @@ __global__ void agnn_norms_kernel(const int32_t* list, const uint64_t* count_dev
 
 // One wave per unit (a destination with a short in-list, or one item of a long one).  NV: 16-byte pieces of a row
 // per lane (rows of up to 256 * NV floats).
-template <int NV, bool GATE>
+template <int NV, bool GATE, bool HALF>
 __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) {
     const int lane = threadIdx.x & 63;
+    const int col0 = HALF ? (lane & 31) * 4 : lane * 4;    // HALF: both halves of the wave cover the same columns
+    const bool writer = !HALF || lane < 32;
     const int D = a.D;
     const int64_t n_dst = (int64_t)a.lc->count;
     int64_t n_items = (int64_t)a.lc->n_items;
@@ -192,7 +238,7 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
     const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     bool live[NV];
 #pragma unroll
-    for (int q = 0; q < NV; ++q) live[q] = lane * 4 + q * 256 < D;
+    for (int q = 0; q < NV; ++q) live[q] = col0 + q * 256 < D;
     long long pairs = 0;
 
     for (int64_t unit = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; unit < total; unit += waves) {
@@ -218,7 +264,7 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
 #pragma unroll
         for (int q = 0; q < NV; ++q) {
             hv[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (live[q]) hv[q] = *reinterpret_cast<const float4*>((GATE ? a.P2 : a.H) + (int64_t)v * D + lane * 4 + q * 256);
+            if (live[q]) hv[q] = *reinterpret_cast<const float4*>((GATE ? a.P2 : a.H) + (int64_t)v * D + col0 + q * 256);
         }
         const float cv = GATE ? 1.0f : a.beta * a.R[v];
 
@@ -226,7 +272,14 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
       for (;;) {
 #pragma unroll
         for (int q = 0; q < NV; ++q) acc[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        pairs += sum_terms<NV, GATE>(a, base, cnt, full, hv, cv, acc, live, lane);
+        pairs += sum_terms<NV, GATE, HALF>(a, base, cnt, full, hv, cv, acc, live, lane, col0);
+        if (HALF) {                                           // the two halves summed different terms
+#pragma unroll
+            for (int q = 0; q < NV; ++q) {
+                acc[q].x += __shfl_xor(acc[q].x, 32, 64); acc[q].y += __shfl_xor(acc[q].y, 32, 64);
+                acc[q].z += __shfl_xor(acc[q].z, 32, 64); acc[q].w += __shfl_xor(acc[q].w, 32, 64);
+            }
+        }
 
         if (part) {
             // an item holds its share of the whole sum, or of the exchange (the first item also takes the structural
@@ -235,13 +288,13 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
             const float* sd0 = dd0 ? a.sd + (int64_t)a.dd_slot[v] * D : nullptr;
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
-                if (!live[q]) continue;
+                if (!live[q] || !writer) continue;
                 float4 d = acc[q];
                 if (dd0) {
-                    const float4 e = *reinterpret_cast<const float4*>(sd0 + lane * 4 + q * 256);
+                    const float4 e = *reinterpret_cast<const float4*>(sd0 + col0 + q * 256);
                     d.x += e.x; d.y += e.y; d.z += e.z; d.w += e.w;
                 }
-                *reinterpret_cast<float4*>(a.hubs.partial + unit * D + lane * 4 + q * 256) = d;
+                *reinterpret_cast<float4*>(a.hubs.partial + unit * D + col0 + q * 256) = d;
             }
             break;
         }
@@ -249,7 +302,7 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
         if (full) {
 #pragma unroll
             for (int q = 0; q < NV; ++q)
-                if (live[q]) *reinterpret_cast<float4*>(out + lane * 4 + q * 256) = acc[q];
+                if (live[q] && writer) *reinterpret_cast<float4*>(out + col0 + q * 256) = acc[q];
             break;
         }
         const bool dd = a.sd && in_set(a.dd_bitmap, v);
@@ -262,10 +315,10 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
             if (!live[q]) continue;
             float4 d = acc[q];
             if (dd) {
-                const float4 e = *reinterpret_cast<const float4*>(sdrow + lane * 4 + q * 256);
+                const float4 e = *reinterpret_cast<const float4*>(sdrow + col0 + q * 256);
                 d.x += e.x; d.y += e.y; d.z += e.z; d.w += e.w;
             }
-            const float4 o = *reinterpret_cast<const float4*>(out + lane * 4 + q * 256);
+            const float4 o = *reinterpret_cast<const float4*>(out + col0 + q * 256);
             y[q] = make_float4(o.x + d.x, o.y + d.y, o.z + d.z, o.w + d.w);
             big = fmaxf(big, fmaxf(fmaxf(fabsf(d.x), fabsf(d.y)), fmaxf(fabsf(d.z), fabsf(d.w))));
             left = fmaxf(left, fmaxf(fmaxf(fabsf(y[q].x), fabsf(y[q].y)), fmaxf(fabsf(y[q].z), fabsf(y[q].w))));
@@ -281,7 +334,7 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_gather_kernel(AgnnArgs a) 
         if (big > AG_GUARD_RATIO * left) { full = true; continue; }
 #pragma unroll
         for (int q = 0; q < NV; ++q)
-            if (live[q]) *reinterpret_cast<float4*>(out + lane * 4 + q * 256) = y[q];
+            if (live[q] && writer) *reinterpret_cast<float4*>(out + col0 + q * 256) = y[q];
         break;
       }
     }
@@ -346,7 +399,7 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_combine_kernel(AgnnArgs a)
                 tot[q] = hv[q];
                 if (live[q]) hv[q] = *reinterpret_cast<const float4*>((GATE ? a.P2 : a.H) + (int64_t)v * D + lane * 4 + q * 256);
             }
-            sum_terms<NV, GATE>(a, rec.off, rec.deg, true, hv, GATE ? 1.0f : a.beta * a.R[v], tot, live, lane);
+            sum_terms<NV, GATE, false>(a, rec.off, rec.deg, true, hv, GATE ? 1.0f : a.beta * a.R[v], tot, live, lane, lane * 4);
         }
 #pragma unroll
         for (int q = 0; q < NV; ++q)
@@ -398,13 +451,15 @@ nrt_status k_agnn_norms(const int32_t* list, const uint64_t* count_dev, int64_t 
 nrt_status k_agnn_gather(const AgnnArgs& a, hipStream_t s) {
     if (a.D % 4 || a.D > 1024) { nrt_set_error("agnn: row width must be a multiple of 4, at most 1024"); return NRT_ERR_UNSUPPORTED; }
     if (a.gate) {
-        if (a.D <= 256) agnn_gather_kernel<1, true><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
-        else if (a.D <= 512) agnn_gather_kernel<2, true><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
-        else agnn_gather_kernel<4, true><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        if (a.D <= 128) agnn_gather_kernel<1, true, true><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else if (a.D <= 256) agnn_gather_kernel<1, true, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else if (a.D <= 512) agnn_gather_kernel<2, true, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else agnn_gather_kernel<4, true, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
     } else {
-        if (a.D <= 256) agnn_gather_kernel<1, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
-        else if (a.D <= 512) agnn_gather_kernel<2, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
-        else agnn_gather_kernel<4, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        if (a.D <= 128) agnn_gather_kernel<1, false, true><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else if (a.D <= 256) agnn_gather_kernel<1, false, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else if (a.D <= 512) agnn_gather_kernel<2, false, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
+        else agnn_gather_kernel<4, false, false><<<AG_BLOCKS, AG_WAVES * 64, 0, s>>>(a);
     }
     LAUNCH_CHECK();
     return NRT_OK;
