@@ -1,0 +1,100 @@
+"""Randomised parity: seeded random models, graphs, batch mixes and modes through the C ABI against the fp64 oracle.
+
+Every case draws a model kind (all nine), a graph size and density, 1-3 layers with random widths, and a short
+chain of batches with random sizes (including none of a kind, and batches large enough for the packed ingest path),
+random modes and, where the model allows it, the on-demand mode with queries.  Bar as in test_gpu_parity: affected
+lists bit-exact; embeddings element-wise 1e-4 for the normalised models, row-normalised 1e-4 for the plain-sum
+models (their element-wise error is additionally compared with a from-scratch fp32 forward when it exceeds 1e-4)."""
+import numpy as np
+import pytest
+
+from paper_2603_20622_amd import workloads as wl
+from tests.test_gpu_parity import TOL, UNNORMALISED, rel_err, row_err
+
+pytestmark = pytest.mark.gpu
+
+KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN]
+CONSTRAINED = (wl.GAT, wl.AGNN, wl.GGCN)
+
+
+@pytest.fixture(scope="module")
+def S():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2603_20622_amd import session
+    return session
+
+
+def _check_layers(S, oracle, ses, spec, params, n, cur, L, what):
+    ref = oracle.forward(spec, params, n, *cur)
+    fresh = None
+    for l in range(1, L + 1):
+        got = ses.layer(l).cpu().numpy()
+        if spec.kind not in UNNORMALISED:
+            assert rel_err(got, ref[l - 1]) <= TOL, (what, l)
+            continue
+        assert row_err(got, ref[l - 1]) <= TOL, (what, l)
+        if rel_err(got, ref[l - 1]) > TOL:                       # noise floor of the plain-sum models
+            if fresh is None:
+                fresh = S.Session(spec, params, n, *cur, max_batch_edges=64, max_batch_feats=64)
+            floor = rel_err(fresh.layer(l).cpu().numpy(), ref[l - 1])
+            assert rel_err(got, ref[l - 1]) <= max(TOL, 10.0 * floor), (what, l)
+    return ref
+
+
+@pytest.mark.parametrize("seed", range(90))
+def test_random_case(S, oracle, seed):
+    rng = np.random.default_rng([seed, 2603])
+    kind = KINDS[seed % len(KINDS)]
+    n = int(rng.choice([60, 300, 2000, 6000]))
+    e = int(min(n * (n - 1) // 4, n * int(rng.choice([1, 5, 15, 30]))))
+    L = int(rng.integers(1, 4))
+    heads, hd = 1, 0
+    if kind == wl.GAT:
+        heads, hd = int(rng.choice([1, 2, 4])), int(rng.choice([4, 8, 16]))
+        dims = [int(rng.choice([4, 8, 20]))] + [heads * hd] * L
+    else:
+        dims = [int(rng.choice([4, 8, 12, 32, 68, 128])) for _ in range(L + 1)]
+    weighted = kind in (wl.GIN, wl.PINSAGE) and bool(rng.integers(0, 2))
+    src, dst, sampler = wl.rmat_graph(n, e, seed)
+    w = wl.edge_weights(e, seed) if weighted else None
+    spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=hd, weighted=weighted, agnn_beta=0.8,
+                        monet_kernels=int(rng.choice([4, 12, 40])))
+    params = wl.make_params(spec, seed, bias=bool(rng.integers(0, 2)))
+    x = wl.features(n, dims[0], seed)
+    stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], seed)
+    ses = S.Session(spec, params, n, src, dst, w, x, max_batch_edges=16384, max_batch_feats=512)
+    cur = (src, dst, w, x)
+    _check_layers(S, oracle, ses, spec, params, n, cur, L, ("init", seed))
+    lazy = False
+    for k in range(int(rng.integers(2, 5))):
+        ses.mode(int(rng.choice([0, 1, 2, 3, 3])))
+        if kind not in CONSTRAINED and rng.random() < 0.3:
+            lazy = not lazy
+            ses.lazy(lazy)                                       # switching it off brings every stale vertex up to date
+        big = n >= 2000 and e >= 30000 and rng.random() < 0.3
+        n_ins = int(rng.choice([2500, 5000])) if big else int(rng.choice([0, 1, 7, 60, 300]))
+        n_del = int(rng.choice([2000, 4000])) if big else int(rng.choice([0, 1, 7, 60, 300]))
+        n_del = min(n_del, len(stream.edges()[0]) // 2)
+        n_feat = int(rng.choice([0, 0, 3, 30]))
+        if n_ins > (n * (n - 1) - len(stream.edges()[0])) // 2:
+            n_ins = 0
+        b = stream.next_batch(n_ins, n_del, min(n_feat, n))
+        na = ses.apply(b, want_rows=not lazy)
+        cur = oracle.apply_batch(n, *cur, b)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        ids = ses.ids[:na].cpu().numpy()
+        assert np.array_equal(ids, sets[-1]), (seed, k)
+        if lazy:
+            q = rng.choice(n, min(n, 25), replace=False).astype(np.int32)
+            rows, _ = ses.query(q)
+            ref = oracle.forward(spec, params, n, *cur)[-1]
+            got = rows.cpu().numpy()
+            err = row_err(got, ref[q]) if kind in UNNORMALISED else rel_err(got, ref[q])
+            assert err <= TOL, (seed, k, "query")
+        else:
+            _check_layers(S, oracle, ses, spec, params, n, cur, L, (seed, k))
+            assert np.array_equal(ses.rows[:na].cpu().numpy(), ses.layer(L).cpu().numpy()[ids]), (seed, k)
+    if lazy:
+        ses.lazy(False)
+        _check_layers(S, oracle, ses, spec, params, n, cur, L, (seed, "flush"))
