@@ -569,6 +569,79 @@ def test_gcn_aggregate_only_storage(S, oracle):
     assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
 
 
+@pytest.mark.parametrize("kind", [wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.AGNN, wl.GGCN, wl.MONET])
+def test_in_degrees_at_the_item_boundaries(S, oracle, kind):
+    """Destinations whose in-degree sits exactly at, just below and just above the sizes the kernels cut work at (64
+    entries per scan step, 256 entries per item): initial forward, a feature batch that changes a few in-neighbours
+    of each (the exchange path), an edge batch that moves every one of them across its boundary upwards, and one
+    that moves them back down."""
+    degs = [1, 15, 16, 17, 63, 64, 65, 255, 256, 257, 511, 512, 513, 1025]
+    n = 1400
+    rng = np.random.default_rng(77)
+    src_l, dst_l = [], []
+    for i, d in enumerate(degs):                       # destination i hears d distinct sources among 100 .. n-1
+        nb = rng.choice(np.arange(100, n), size=d, replace=False)
+        src_l.append(nb); dst_l.append(np.full(d, i))
+    extra_s = rng.integers(100, n, 3000); extra_d = rng.integers(100, n, 3000)       # a sparse background
+    keep = extra_s != extra_d
+    src = np.concatenate(src_l + [extra_s[keep]]).astype(np.int32)
+    dst = np.concatenate(dst_l + [extra_d[keep]]).astype(np.int32)
+    _, first = np.unique(src.astype(np.int64) * n + dst, return_index=True)
+    src, dst = src[np.sort(first)], dst[np.sort(first)]
+    weighted = kind in WEIGHTED
+    w = rng.random(len(src)).astype(np.float32) if weighted else None
+    if kind == wl.GAT:
+        spec = wl.ModelSpec(kind, [12, 32, 32], heads=2, head_dim=16)
+    else:
+        spec = wl.ModelSpec(kind, [12, 32, 8], weighted=weighted, monet_kernels=16)
+    params = wl.make_params(spec, 78, bias=True)
+    x = wl.features(n, 12, 78)
+    ses = S.Session(spec, params, n, src, dst, w, x, max_batch_edges=4096)
+    cur = (src, dst, w, x)
+
+    def check(what):
+        ref = oracle.forward(spec, params, n, *cur)
+        fresh = S.Session(spec, params, n, *cur) if kind in UNNORMALISED else None
+        for l in (1, 2):
+            assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (what, l),
+                          None if fresh is None else fresh.layer(l).cpu().numpy())
+
+    check("init")
+    have = set(zip(cur[0].tolist(), cur[1].tolist()))
+    # 1. features of three in-neighbours of every boundary destination (and of vertex 0's own row)
+    b = wl.empty_batch(12, weighted)
+    ids = np.unique(np.concatenate([nb[:3] for nb in src_l] + [np.array([0])])).astype(np.int32)
+    b.feat_ids, b.feat_rows = ids, rng.standard_normal((len(ids), 12)).astype(np.float32)
+    na = ses.apply(b)
+    cur = oracle.apply_batch(n, *cur, b)
+    assert np.array_equal(ses.ids[:na].cpu().numpy(), oracle.affected_sets(spec, n, cur[0], cur[1], b)[-1])
+    check("features")
+    # 2. two more in-edges for every boundary destination, 3. three deleted again
+    for what in ("up", "down"):
+        b = wl.empty_batch(12, weighted)
+        if what == "up":
+            new = [(int(u), i) for i in range(len(degs)) for u in rng.permutation(np.arange(100, n)) [:40]
+                   if (int(u), i) not in have][: 2 * len(degs) * 20]
+            per = {}
+            new = [p for p in new if per.setdefault(p[1], 0) < 2 and not per.update({p[1]: per[p[1]] + 1})]
+            b.ins_src = np.array([p[0] for p in new], np.int32); b.ins_dst = np.array([p[1] for p in new], np.int32)
+            if weighted:
+                b.ins_w = rng.random(len(new)).astype(np.float32)
+            have |= set(new)
+        else:
+            gone = []
+            for i in range(len(degs)):
+                mine = np.nonzero(cur[1] == i)[0][:3]
+                gone += [(int(cur[0][j]), i) for j in mine]
+            b.del_src = np.array([p[0] for p in gone], np.int32); b.del_dst = np.array([p[1] for p in gone], np.int32)
+        na = ses.apply(b)
+        cur = oracle.apply_batch(n, *cur, b)
+        assert np.array_equal(ses.ids[:na].cpu().numpy(), oracle.affected_sets(spec, n, cur[0], cur[1], b)[-1]), what
+        got_deg = np.bincount(cur[1], minlength=n)[: len(degs)]
+        assert np.array_equal(got_deg, np.array(degs) + (2 if what == "up" else -1)), what
+        check(what)
+
+
 def test_widest_rows(S, oracle):
     """1024-wide aggregates (four 16-byte loads per lane in the gather, K = 1024 in the update)."""
     n, e = 800, 6000
