@@ -642,6 +642,36 @@ def test_in_degrees_at_the_item_boundaries(S, oracle, kind):
         check(what)
 
 
+def test_batches_at_and_beyond_the_declared_bounds(S, oracle):
+    """A batch of exactly max_batch_edges updates and max_batch_feats rows is applied; one more of either, or an edge
+    count beyond e_capacity, is refused with the documented status and changes nothing."""
+    from paper_2603_20622_amd import binding as nb
+    n, src, dst, w, x, spec, params, stream = small_case(wl.GIN, seed=13, n=1500, e=12000)
+    ses = S.Session(spec, params, n, src, dst, w, x, e_capacity=12000 + 40, max_batch_edges=300, max_batch_feats=50)
+    b = stream.next_batch(170, 130, 50)                          # exactly at both bounds; the graph grows by 40: full
+    na = ses.apply(b)
+    cur = oracle.apply_batch(n, src, dst, w, x, b)
+    assert np.array_equal(ses.ids[:na].cpu().numpy(), oracle.affected_sets(spec, n, cur[0], cur[1], b)[-1])
+    ref = oracle.forward(spec, params, n, *cur)
+    fresh = S.Session(spec, params, n, *cur)
+    assert_parity(wl.GIN, ses.layer(2).cpu().numpy(), ref[-1], "at the bounds", fresh.layer(2).cpu().numpy())
+    base = ses.layer(2).cpu().numpy().copy()
+    for what, (ni, nd, nf), status in (("edges", (151, 150, 0), nb.NRT_ERR_BAD_BATCH),
+                                       ("rows", (0, 0, 51), nb.NRT_ERR_BAD_BATCH),
+                                       ("capacity", (1, 0, 0), nb.NRT_ERR_OOM)):
+        import copy
+        st2 = copy.deepcopy(stream)
+        bad = st2.next_batch(ni, nd, nf)
+        with pytest.raises(nb.NrtError) as ei:
+            ses.apply(bad)
+        assert ei.value.status == status, what
+        assert np.array_equal(ses.layer(2).cpu().numpy(), base), what
+    ok = stream.next_batch(0, 60, 5)                             # deleting makes room again
+    ses.apply(ok)
+    cur = oracle.apply_batch(n, *cur, ok)
+    assert row_err(ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1]) <= TOL
+
+
 def test_widest_rows(S, oracle):
     """1024-wide aggregates (four 16-byte loads per lane in the gather, K = 1024 in the update)."""
     n, e = 800, 6000
