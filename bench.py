@@ -4,12 +4,19 @@
 A step = one nrt_apply_batch (validate + ingest, frontier expansion, delta gather/fold, affected-row update
 with write-back, all layers) over one synthetic update batch; batches are chained (each step sees the graph
 and caches the previous step left).  Inputs (graph, caches, every batch) are resident in HBM before the timed
-region.  Two timed passes of K steps each: the first, with the library's per-phase HIP events off, gives the
-headline (value, ms_per_step, latency); the second, over the next K chained batches with the events on (they
+region.  Per configuration two timed passes of K steps each: the first, with the library's per-phase HIP events
+off, gives value, ms_per_step and latency; the second, over the next K chained batches with the events on (they
 cost a few percent), gives the per-kernel durations behind `roofline`, `update_gemm` and the phase breakdown.
-Prints ONE JSON line.
+
+The headline (top level of the one JSON line) is the largest configuration, config 4 of the benchmark spec (3-layer
+GIN, 10M vertices / 200M weighted edges); `other_configs` carries the same record for the other four
+configurations, each timed the same way in the same run with its own CPU-oracle baseline.  `--only` runs the
+chosen configuration alone.  `stream_ceilings` are a plain read kernel and a plain copy kernel of the same
+library timed in the same process.
 """
 import argparse
+import gc
+import glob
 import json
 import os
 import sys
@@ -23,41 +30,39 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 FP32_MFMA_PEAK_TFLOPS = 157.3
 INFINITY_CACHE_BYTES = 256 * 1024 * 1024
+HEADLINE = 3                       # index into benchmark configs: config 4, the largest single-GPU configuration
+# steps / warmup / steps per comparison mode of the configurations that are not the headline
+NESTED_STEPS = {0: (40, 5, 10), 1: (40, 5, 10), 2: (6, 2, 4), 3: (10, 3, 4), 4: (8, 2, 4)}
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=1, help="index into BASELINE.json configs (default: configs[1])")
-    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
-    ap.add_argument("--seed", type=int, default=0)
-    ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
-    ap.add_argument("--model", choices=["commnet", "pinsage", "agnn", "monet", "ggcn"], default=None,
-                    help="run another Table II model on the chosen config's graph, widths and batches (not the headline)")
-    ap.add_argument("--agg-only", action="store_true",
-                    help="GCN configs: keep only the aggregates of hidden layers (storage option; not the headline)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU only (caches resident in one MI355X's HBM, no collectives); "
-              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
-        sys.exit(2)
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
 
+
+def stream_ceilings(torch, nb):
+    """What a plain streaming kernel reaches on this GPU: read-only and copy, 2 GiB buffers (far beyond every cache)."""
+    n = 512 * 1024 * 1024
+    a = torch.empty(n, dtype=torch.float32, device="cuda").fill_(1.0)
+    b = torch.empty(n, dtype=torch.float32, device="cuda")
+    torch.cuda.synchronize()
+    ms_read = nb.nrt_measure_stream(1, b, a, 10)
+    ms_copy = nb.nrt_measure_stream(0, b, a, 10)
+    del a, b
+    torch.cuda.empty_cache()
+    return {"read_GBps": round(4.0 * n / 1e9 / (ms_read / 1e3), 1), "copy_GBps_read_plus_write": round(8.0 * n / 1e9 / (ms_copy / 1e3), 1),
+            "buffer_GB": round(4.0 * n / 1e9, 2), "passes": 10,
+            "note": "stream_read_kernel / stream_copy_kernel of libnrt (16 B per lane and access), HIP events around 10 passes"}
+
+
+def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
     import torch
     from paper_2603_20622_amd import workloads as wl
     from paper_2603_20622_amd import session as S
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(3)
-
-    cfg = wl.config(args.config, args.scale)
+    cfg = wl.config(index, args.scale)
     if args.model:
         kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE, "agnn": wl.AGNN, "monet": wl.MONET, "ggcn": wl.GGCN}[args.model]
-        cfg.spec = wl.ModelSpec(kind, list(cfg.spec.dims[:1]) + list(cfg.spec.dims[1:]), weighted=kind == wl.PINSAGE,
-                                monet_kernels=64)
+        cfg.spec = wl.ModelSpec(kind, list(cfg.spec.dims), weighted=kind == wl.PINSAGE, monet_kernels=64)
         cfg.name = cfg.name + "_as_" + args.model
     if args.agg_only:
         cfg.spec.agg_only = True
@@ -68,36 +73,34 @@ def main():
         cfg.n_del = args.batch_edges - cfg.n_ins
     t0 = time.time()
     src, dst, w, x, params, stream = wl.build(cfg, args.seed)
-    k_modes = min(args.steps, 10)                       # steps per non-incremental mode (comparison legs)
-    n_total = 2 * args.steps + args.warmup + 4 * k_modes
+    n_total = 2 * K + W + 3 * k_modes + (k_modes if with_on_demand else 0)
     batches = [stream.next_batch(cfg.n_ins, cfg.n_del, cfg.n_feat) for _ in range(n_total)]
     final_edges = stream.edges()
-    t_gen = time.time() - t0
-    print("[bench] %s: generated graph %d/%d and %d batches in %.1fs" % (cfg.name, cfg.n, cfg.e, n_total, t_gen),
-          file=sys.stderr, flush=True)
+    del stream
+    log("%s: generated graph %d/%d and %d batches in %.1fs" % (cfg.name, cfg.n, cfg.e, n_total, time.time() - t0))
 
     ses = S.Session(cfg.spec, params, cfg.n, src, dst, w, x,
                     max_batch_edges=max(1024, 2 * (cfg.n_ins + cfg.n_del)), max_batch_feats=max(64, 2 * cfg.n_feat))
+    del src, dst, w
     dev_batches = [S.DeviceBatch(b) for b in batches]
     ses.profiling(False)
     torch.cuda.synchronize()
-    print("[bench] caches initialised, running %d warmup + 2 x %d timed steps" % (args.warmup, args.steps),
-          file=sys.stderr, flush=True)
+    log("%s: caches initialised, running %d warmup + 2 x %d timed steps" % (cfg.name, W, K))
 
-    for b in dev_batches[:args.warmup]:
+    for b in dev_batches[:W]:
         ses.apply(b)
     torch.cuda.synchronize()
 
     L = cfg.spec.n_layers
-    K = args.steps
     dims = cfg.spec.dims
 
-    # ---- pass 1: the headline
+    # ---- pass 1: value, ms_per_step, latency
     lat = []
     edge_updates = 0
+    launches = 0
     torch.cuda.synchronize()
     t_start = time.perf_counter()
-    for b in dev_batches[args.warmup:args.warmup + K]:
+    for b in dev_batches[W:W + K]:
         t1 = time.perf_counter()
         ses.apply(b)
         lat.append((time.perf_counter() - t1) * 1e3)
@@ -111,11 +114,12 @@ def main():
     ses.profiling(True)
     agg = {"gather_ms": 0.0, "gather_bytes": 0.0, "gather_launches": 0, "update_ms": 0.0, "update_flop": 0.0,
            "ingest_ms": 0.0, "expand_ms": 0.0, "compact_ms": 0.0, "items_ms": 0.0, "combine_ms": 0.0}
-    per_layer = [dict(n_src=0, n_aff=0, n_pairs=0, n_in=0, gather_ms=0.0, update_ms=0.0, bytes=0.0) for _ in range(L)]
+    per_layer = [dict(n_src=0, n_aff=0, n_pairs=0, n_in=0, gather_ms=0.0, update_ms=0.0, bytes=0.0, flop=0.0) for _ in range(L)]
     t_start2 = time.perf_counter()
-    for b in dev_batches[args.warmup + K:args.warmup + 2 * K]:
+    for b in dev_batches[W + K:W + 2 * K]:
         ses.apply(b)
         st = ses.stats()
+        launches += st.n_launches
         agg["ingest_ms"] += st.ms_ingest
         for l in range(L):
             ls = st.layer[l]
@@ -154,7 +158,7 @@ def main():
             pl = per_layer[l]
             pl["n_src"] += ls.n_src; pl["n_aff"] += ls.n_affected; pl["n_pairs"] += ls.n_pairs
             pl["n_in"] += ls.n_in_edges; pl["gather_ms"] += ls.ms_gather; pl["update_ms"] += upd_ms
-            pl["bytes"] += gbytes
+            pl["bytes"] += gbytes; pl["flop"] += flop
     torch.cuda.synchronize()
     ms_per_step_events = (time.perf_counter() - t_start2) * 1e3 / K
 
@@ -164,7 +168,7 @@ def main():
     # graph recomputed per batch
     ses.profiling(False)
     mode_ms = {}
-    at = args.warmup + 2 * K
+    at = W + 2 * K
     for name, mode in (("incremental_every_layer", 0), ("recompute_affected", 1), ("full_graph", 2)):
         if args.agg_only and mode != 0:                  # recomputation reads hidden rows, which this cache does not keep
             mode_ms[name] = None
@@ -181,9 +185,9 @@ def main():
     ses.mode(3)
 
     # ---- on-demand leg (Section IV-D): batches only mark vertices stale, each is followed by a query for the
-    # final-layer rows of 1000 random vertices, which recomputes the stale part of their L-hop in-neighbourhood
+    # final-layer rows of 1000 random vertices, which brings the stale part of their L-hop in-neighbourhood up to date
     on_demand = None
-    if cfg.spec.kind not in (wl.GAT, wl.AGNN, wl.GGCN) and not args.agg_only:
+    if with_on_demand and cfg.spec.kind not in (wl.GAT, wl.AGNN, wl.GGCN) and not args.agg_only:
         rng = np.random.default_rng(args.seed + 77)
         ses.lazy(True)
         t_apply = t_query = 0.0
@@ -200,7 +204,7 @@ def main():
             t_query += t6 - t5
             n_rec += nr
         t7 = time.perf_counter()
-        ses.lazy(False)                                  # recompute everything still stale
+        ses.lazy(False)                                  # bring everything still stale up to date
         t_flush = time.perf_counter() - t7
         on_demand = {"batches": k_modes, "query_vertices": min(1000, cfg.n),
                      "apply_ms_per_batch": round(t_apply * 1e3 / k_modes, 4),
@@ -208,14 +212,15 @@ def main():
                      "final_flush_ms": round(t_flush * 1e3, 3),
                      "note": "query time includes the upload of the 1000 ids and the allocation of the result"}
 
-    # HBM bytes per launch measured with rocprofv3 counters on this workload (committed summary), if present
-    traffic = None
-    import glob
-    if args.scale == 1.0 and not args.batch_edges:
+    # HBM bytes per launch measured with rocprofv3 counters on this workload: bench.py cannot run the profiler on
+    # itself, so the figure is read from the committed summary of the same command (profiles/), which is named
+    traffic, traffic_source = None, None
+    if args.scale == 1.0 and not args.batch_edges and not args.model and not args.agg_only:
         for tpath in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_%s_*.txt" % cfg.name))):
             for line in open(tpath):
                 if line.startswith("traffic_bytes_per_launch:"):
                     traffic = int(line.split(":")[1].split()[0])
+                    traffic_source = os.path.relpath(tpath, ROOT)
     nl = max(1, agg["gather_launches"])
     g_avg_ms = agg["gather_ms"] / nl
     g_avg_bytes = agg["gather_bytes"] / nl
@@ -225,18 +230,19 @@ def main():
              "delta-message gather + fold (gather_sparse_kernel on layers with few changed sources, gather_kernel otherwise)")
     roofline = {"kernel": kname, "bound": "hbm",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic, "traffic_source": traffic_source,
+                "frac_of_stream_read_ceiling": round(achieved / ceilings["read_GBps"], 4) if ceilings else None,
                 "avg_launch_ms": round(g_avg_ms, 4), "avg_launch_bytes": round(g_avg_bytes),
                 "launches_per_step": agg["gather_launches"] / K}
     upd_tflops = (agg["update_flop"] / 1e12) / (agg["update_ms"] / 1e3) if agg["update_ms"] > 0 else 0.0
 
     out = {
         "metric": "edge_updates_per_s", "value": round(value, 1), "unit": "edge updates/s", "n_gpus": 1,
-        "steps": K, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": cfg.name, "model": wl.KIND_NAMES[cfg.spec.kind], "dims": dims, "vertices": cfg.n,
-                   "edges": cfg.e, "batch_inserts": cfg.n_ins, "batch_deletes": cfg.n_del,
-                   "batch_feature_rows": cfg.n_feat, "chained_batches": n_total, "seed": args.seed, "scale": args.scale},
+        "config": {"workload": cfg.name, "vertices": cfg.n, "edges": cfg.e, "batch_inserts": cfg.n_ins,
+                   "batch_deletes": cfg.n_del, "batch_feature_rows": cfg.n_feat, "chained_batches": n_total,
+                   "seed": args.seed, "scale": args.scale},
         "latency_ms": {"median": round(float(np.median(lat)), 4), "mean": round(float(np.mean(lat)), 4),
                        "p95": round(float(np.percentile(lat, 95)), 4), "min": round(float(np.min(lat)), 4)},
         "roofline": roofline,
@@ -245,6 +251,7 @@ def main():
                                 "phase_ms_per_step and per_layer_avg come from it"},
         "update_gemm": {"bound": "mfma", "achieved": round(upd_tflops, 2), "peak": FP32_MFMA_PEAK_TFLOPS,
                         "unit": "TFLOP/s", "frac": round(upd_tflops / FP32_MFMA_PEAK_TFLOPS, 4)},
+        "kernel_launches_per_step": round(launches / K, 1),
         "modes_ms_per_step": {"default_incremental_with_auto_recompute_of_saturated_layers": round(ms_per_step, 4),
                               "incremental_every_layer": None if mode_ms["incremental_every_layer"] is None else round(mode_ms["incremental_every_layer"], 4),
                               "recompute_affected": None if mode_ms["recompute_affected"] is None else round(mode_ms["recompute_affected"], 4),
@@ -259,34 +266,97 @@ def main():
         "per_layer_avg": [{"layer": l + 1, "n_src": pl["n_src"] / K, "n_affected": pl["n_aff"] / K,
                            "delta_messages": pl["n_pairs"] / K, "in_edges_scanned": pl["n_in"] / K,
                            "gather_ms": round(pl["gather_ms"] / K, 4), "update_ms": round(pl["update_ms"] / K, 4),
-                           "gather_GBps": round((pl["bytes"] / 1e9) / (pl["gather_ms"] / 1e3), 1) if pl["gather_ms"] > 0 else 0.0}
+                           "gather_GBps": round((pl["bytes"] / 1e9) / (pl["gather_ms"] / 1e3), 1) if pl["gather_ms"] > 0 else 0.0,
+                           "update_TFLOPs": round((pl["flop"] / 1e12) / (pl["update_ms"] / 1e3), 2) if pl["update_ms"] > 0 else 0.0}
                           for l, pl in enumerate(per_layer)],
     }
 
-    if not args.no_cpu_baseline:
+    got = ses.layer(L).cpu().numpy() if with_cpu else None
+    ses.close()
+    del ses, dev_batches
+    gc.collect()
+    torch.cuda.empty_cache()
+
+    if with_cpu:
         from oracle import rtec_oracle as orc
         fs, fd, fw = final_edges
         xf = np.array(x, copy=True)
         for b in batches:
             if len(b.feat_ids):
                 xf[b.feat_ids] = b.feat_rows
-        # bounded sample: whole recomputations of the final snapshot until about 10 s of CPU work (at most 5)
+        # bounded sample: whole recomputations of the final snapshot until about 10 s of CPU work (at most 5; the
+        # large configurations take one, 20-45 s)
         t_cpu_total, n_rec = 0.0, 0
         while n_rec < 5 and (n_rec == 0 or t_cpu_total < 10.0):
             t2 = time.perf_counter()
-            ref = orc.forward(cfg.spec, params, cfg.n, fs, fd, fw, xf)
+            ref = orc.forward(cfg.spec, params, cfg.n, fs, fd, fw, xf)[-1]
             t_cpu_total += time.perf_counter() - t2
             n_rec += 1
         t_cpu = t_cpu_total / n_rec
         per_batch = cfg.n_ins + cfg.n_del
         out["cpu_baseline"] = {"value": round(per_batch / t_cpu, 2), "unit": "edge updates/s",
                                "cores": orc.num_threads(), "kind": "oracle",
-                               "sample": "%d fp64 full-neighbour %d-layer recomputations of the final snapshot "
+                               "sample": "%d fp64 full-neighbour %d-layer recomputation(s) of the final snapshot "
                                          "(%.2f s each), i.e. the cost per batch without any cache" % (n_rec, L, t_cpu),
                                "seconds_per_recompute": round(t_cpu, 3)}
-        got = ses.layer(L).cpu().numpy()
-        err = float(np.max(np.abs(got.astype(np.float64) - ref[-1]) / np.maximum(np.abs(ref[-1]), 1.0)))
-        out["parity_after_chain"] = {"max_rel_err_elementwise": err, "batches_applied": n_total}
+        d = np.abs(got.astype(np.float64) - ref)
+        err = float(np.max(d / np.maximum(np.abs(ref), 1.0)))
+        rown = float(np.max(d / np.maximum(np.abs(ref).max(axis=1, keepdims=True), 1.0)))
+        out["parity_after_chain"] = {"max_rel_err_elementwise": err, "max_rel_err_row_normalised": rown,
+                                     "batches_applied": n_total}
+        del ref, d, got, xf
+    log("%s: %.3f ms per step, gather %.0f GB/s (%.2f of peak), update %.1f TFLOP/s, done at %.0fs"
+        % (cfg.name, ms_per_step, achieved, achieved / HBM_PEAK_GBS, upd_tflops, time.time() - t0))
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="timed steps of the headline configuration (default 10)")
+    ap.add_argument("--warmup", type=int, default=-1, help="untimed steps of the headline configuration (default 3)")
+    ap.add_argument("--config", type=int, default=HEADLINE, help="index into BASELINE.json configs of the top-level record "
+                    "(default 3: config 4, the largest)")
+    ap.add_argument("--only", action="store_true", help="run the chosen configuration alone (no other_configs)")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
+    ap.add_argument("--model", choices=["commnet", "pinsage", "agnn", "monet", "ggcn"], default=None,
+                    help="run another Table II model on the chosen config's graph, widths and batches (implies --only)")
+    ap.add_argument("--agg-only", action="store_true",
+                    help="GCN configs: keep only the aggregates of hidden layers (storage option; implies --only)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (caches resident in one MI355X's HBM, no collectives); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_20622_amd import binding as nb
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    only = args.only or args.model is not None or args.agg_only or args.batch_edges > 0 or args.scale != 1.0
+    t_all = time.time()
+    ceilings = stream_ceilings(torch, nb)
+    log("stream ceilings: read %.0f GB/s, copy %.0f GB/s" % (ceilings["read_GBps"], ceilings["copy_GBps_read_plus_write"]))
+    dK, dW, dM = NESTED_STEPS[args.config]
+    K = args.steps if args.steps > 0 else dK
+    W = args.warmup if args.warmup >= 0 else dW
+    out = run_config(args, args.config, K, W, min(K, dM) if K > 1 else 2, ceilings, not args.no_cpu_baseline, True)
+    out["stream_ceilings"] = ceilings
+    if not only:
+        others = {}
+        for index in range(5):
+            if index == args.config:
+                continue
+            k, w, m = NESTED_STEPS[index]
+            rec = run_config(args, index, k, w, m, ceilings, not args.no_cpu_baseline, index <= 1)
+            others[rec["config"]["workload"]] = rec
+        out["other_configs"] = others
+    out["bench_wall_s"] = round(time.time() - t_all, 1)
     print(json.dumps(out), flush=True)
 
 

@@ -138,6 +138,7 @@ typedef struct {
     nrt_layer_stats layer[NRT_MAX_LAYERS];
     float ms_ingest;      /* validate + structural fold + graph mutation + layer-0 deltas */
     float ms_total;       /* first to last event of the call                              */
+    int64_t n_launches;   /* kernel launches the call issued                              */
 } nrt_stats;
 
 /* ---- graph -------------------------------------------------------------------------------- */
@@ -239,6 +240,17 @@ nrt_status nrt_query(nrt_cache*, const int32_t* query_ids, int64_t n_query, floa
                      void* stream);
 nrt_status nrt_set_profiling(nrt_cache*, int32_t on);
 nrt_status nrt_get_stats(const nrt_cache*, nrt_stats* out /*host*/);
+
+/*
+ * Bandwidth ceilings of the device, for the report that sets the gathers' achieved HBM rate beside what a plain
+ * streaming kernel reaches on the same GPU (Section V reports response time and throughput; the roofline view is
+ * this build's).  kind 0: copy a -> b (n_floats read and n_floats written per pass); kind 1: read a (b receives at most
+ * one float).  a, b: device, 16-byte aligned, n_floats each, distinct.  One untimed pass, then `reps` passes timed with
+ * HIP events on `stream`; *ms_per_pass (host) is their average.  Synchronises the stream.
+ * Errors: NRT_ERR_INVALID_ARG, NRT_ERR_DEVICE.
+ */
+nrt_status nrt_measure_stream(int32_t kind, float* b, const float* a, int64_t n_floats, int32_t reps, void* stream,
+                              float* ms_per_pass /*host*/);
 
 const char* nrt_last_error(void);
 const char* nrt_version(void);

@@ -51,7 +51,7 @@ class nrt_layer_stats(ctypes.Structure):
 
 class nrt_stats(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("layer", nrt_layer_stats * NRT_MAX_LAYERS),
-                ("ms_ingest", ctypes.c_float), ("ms_total", ctypes.c_float)]
+                ("ms_ingest", ctypes.c_float), ("ms_total", ctypes.c_float), ("n_launches", ctypes.c_int64)]
 
 
 class NrtError(RuntimeError):
@@ -63,7 +63,7 @@ class NrtError(RuntimeError):
 EXPORTS = ["nrt_graph_workspace_bytes", "nrt_graph_create", "nrt_graph_destroy", "nrt_graph_num_edges",
            "nrt_graph_export_csc", "nrt_cache_workspace_bytes", "nrt_cache_init", "nrt_cache_destroy",
            "nrt_apply_batch", "nrt_get_layer", "nrt_get_aggregate", "nrt_get_layer_affected", "nrt_set_profiling",
-           "nrt_set_mode", "nrt_set_lazy", "nrt_query", "nrt_get_stats", "nrt_last_error", "nrt_version"]
+           "nrt_set_mode", "nrt_set_lazy", "nrt_query", "nrt_get_stats", "nrt_measure_stream", "nrt_last_error", "nrt_version"]
 
 _lib = None
 
@@ -95,6 +95,7 @@ def lib() -> ctypes.CDLL:
         L.nrt_set_lazy.argtypes = [c_fp, i32, c_fp]
         L.nrt_query.argtypes = [c_fp, c_fp, i64, c_fp, P(i64), c_fp]
         L.nrt_get_stats.argtypes = [c_fp, P(nrt_stats)]
+        L.nrt_measure_stream.argtypes = [i32, c_fp, c_fp, i64, i32, c_fp, P(ctypes.c_float)]
         L.nrt_last_error.restype = ctypes.c_char_p
         L.nrt_version.restype = ctypes.c_char_p
         _lib = L
@@ -304,3 +305,10 @@ def nrt_get_stats(c: Cache) -> nrt_stats:
     s = nrt_stats()
     _check(lib().nrt_get_stats(c.handle, ctypes.byref(s)))
     return s
+
+
+def nrt_measure_stream(kind: int, b: torch.Tensor, a: torch.Tensor, reps: int = 10) -> float:
+    """Average milliseconds of one streaming pass over a (kind 0: copy into b, kind 1: read only)."""
+    ms = ctypes.c_float(0.0)
+    _check(lib().nrt_measure_stream(int(kind), _ptr(b), _ptr(a), int(a.numel()), int(reps), _stream(), ctypes.byref(ms)))
+    return float(ms.value)

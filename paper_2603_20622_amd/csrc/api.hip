@@ -14,6 +14,7 @@ void nrt_set_error(const char* fmt, ...) {
     vsnprintf(g_err, sizeof(g_err), fmt, ap);
     va_end(ap);
 }
+thread_local int64_t nrt_launch_count = 0;
 extern "C" const char* nrt_last_error(void) { return g_err; }
 extern "C" const char* nrt_version(void) { return "nrt 0.1 (gfx950)"; }
 
@@ -975,6 +976,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     memset(&c->stats, 0, sizeof(c->stats));
     c->stats.n_layers = c->L;
     c->n_ev = 0;
+    nrt_launch_count = 0;
     int64_t prev_n_list[NRT_MAX_LAYERS + 1];            // sizes of the previous batch's sets: hints for this one
     for (int l = 0; l <= c->L; ++l) { prev_n_list[l] = c->n_list[l]; c->n_list[l] = 0; }
     const bool had_history = c->have_history;
@@ -1227,6 +1229,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             return NRT_ERR_STATE;
         }
     }
+    c->stats.n_launches = nrt_launch_count;
     NRT_TRY(prof_collect(c));
     if (c->profiling) {
         for (int l = 1; l <= c->L; ++l) {
@@ -1382,6 +1385,33 @@ extern "C" nrt_status nrt_set_mode(nrt_cache* c, int32_t mode) {
     c->mode = mode;
     return NRT_OK;
 }
+extern "C" nrt_status nrt_measure_stream(int32_t kind, float* b, const float* a, int64_t n_floats, int32_t reps, void* stream,
+                                         float* ms_per_pass) {
+    REQUIRE(a && b && ms_per_pass, "null argument");
+    REQUIRE(kind == 0 || kind == 1, "kind must be 0 (copy) or 1 (read)");
+    REQUIRE(n_floats >= 4 && reps >= 1, "need n_floats >= 4 and reps >= 1");
+    REQUIRE(((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b)) & 15) == 0, "buffers must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); nrt_set_error("hipEventCreate failed"); return NRT_ERR_DEVICE; }
+    auto run = [&]() -> nrt_status {
+        NRT_TRY(kind == 0 ? k_stream_copy(b, a, n_floats, s) : k_stream_read(b, a, n_floats, s));     // untimed first pass
+        HIP_TRY(hipEventRecord(e0, s));
+        for (int r = 0; r < reps; ++r) NRT_TRY(kind == 0 ? k_stream_copy(b, a, n_floats, s) : k_stream_read(b, a, n_floats, s));
+        HIP_TRY(hipEventRecord(e1, s));
+        HIP_TRY(hipEventSynchronize(e1));
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+        *ms_per_pass = ms / (float)reps;
+        return NRT_OK;
+    };
+    const nrt_status st = run();
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return st;
+}
+
 extern "C" nrt_status nrt_set_profiling(nrt_cache* c, int32_t on) {
     REQUIRE(c, "null argument");
     if (on && !c->events_made) {

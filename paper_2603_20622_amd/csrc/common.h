@@ -28,7 +28,9 @@ void nrt_set_error(const char* fmt, ...);
         nrt_status _s = (expr);           \
         if (_s != NRT_OK) return _s;      \
     } while (0)
-#define LAUNCH_CHECK() HIP_TRY(hipGetLastError())
+// kernel launches issued by the calling thread since the counter was last cleared (a statistic of nrt_get_stats)
+extern thread_local int64_t nrt_launch_count;
+#define LAUNCH_CHECK() do { ++nrt_launch_count; HIP_TRY(hipGetLastError()); } while (0)
 
 static inline int64_t cdiv(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
@@ -126,6 +128,10 @@ nrt_status k_gather_rows_checked(float* dst, const float* src, const int32_t* id
 nrt_status k_mark_ids(uint32_t* bm, const int32_t* ids, int64_t n_ids, int64_t n, int32_t* bad, hipStream_t s);
 // bm &= ~(list[0 .. *count))
 nrt_status k_clear_listed_bits(uint32_t* bm, const int32_t* list, const uint64_t* count, int64_t bound, hipStream_t s);
+
+// streaming kernels for the bandwidth ceilings reported beside the gathers: copy a -> b, or read a (b receives nothing)
+nrt_status k_stream_copy(float* b, const float* a, int64_t n_floats, hipStream_t s);
+nrt_status k_stream_read(float* b, const float* a, int64_t n_floats, hipStream_t s);
 
 // ---------------------------------------------------------------- frontier.hip
 // flags[v] = 1 for every out-neighbour v of the sources src_list[0 .. *ns_dev) that is not itself a source

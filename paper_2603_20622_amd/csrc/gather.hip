@@ -890,6 +890,7 @@ static void launch_gather(const GatherArgs& a, hipStream_t s) {
     else if (coef) gather_kernel<LPR, NV, false, true><<<nb, threads, 0, s>>>(a);
     else gather_kernel<LPR, NV, false, false><<<nb, threads, 0, s>>>(a);
     if (NV == 1 && a.sparse_ok) {
+        ++nrt_launch_count;                     // the second launch of this call
         if (coef) gather_sparse_kernel<LPR, true><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
         else gather_sparse_kernel<LPR, false><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
     }

@@ -244,6 +244,32 @@ __global__ void copy_counted_kernel(uint32_t* dst, const uint32_t* src, const ui
     for (; i < n; i += stride) dst[i] = src[i];
 }
 
+// ---- streaming kernels (bandwidth ceilings): 16 bytes per lane and access, four independent accesses per trip
+__global__ void __launch_bounds__(256) stream_copy_kernel(float4* b, const float4* a, int64_t n4) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        const float4 x0 = a[i], x1 = a[i + stride], x2 = a[i + 2 * stride], x3 = a[i + 3 * stride];
+        b[i] = x0; b[i + stride] = x1; b[i + 2 * stride] = x2; b[i + 3 * stride] = x3;
+    }
+    for (; i < n4; i += stride) b[i] = a[i];
+}
+__global__ void __launch_bounds__(256) stream_read_kernel(float* out, const float4* a, int64_t n4) {
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0, s2 = s0, s3 = s0;
+    for (; i + 3 * stride < n4; i += 4 * stride) {
+        const float4 x0 = a[i], x1 = a[i + stride], x2 = a[i + 2 * stride], x3 = a[i + 3 * stride];
+        s0.x += x0.x; s0.y += x0.y; s0.z += x0.z; s0.w += x0.w;
+        s1.x += x1.x; s1.y += x1.y; s1.z += x1.z; s1.w += x1.w;
+        s2.x += x2.x; s2.y += x2.y; s2.z += x2.z; s2.w += x2.w;
+        s3.x += x3.x; s3.y += x3.y; s3.z += x3.z; s3.w += x3.w;
+    }
+    for (; i < n4; i += stride) { const float4 x = a[i]; s0.x += x.x; s0.y += x.y; s0.z += x.z; s0.w += x.w; }
+    const float t = (s0.x + s0.y + s0.z + s0.w) + (s1.x + s1.y + s1.z + s1.w) + (s2.x + s2.y + s2.z + s2.w) + (s3.x + s3.y + s3.z + s3.w);
+    if (t == -1.2345e30f) out[0] = t;        // keeps the loads alive; practically never taken
+}
+
 inline int grid_for(int64_t n, int tpb, int64_t cap = 65536) {
     int64_t g = cdiv(n, tpb);
     if (g < 1) g = 1;
@@ -314,6 +340,19 @@ nrt_status k_copy_i32(int32_t* dst, const int32_t* src, int64_t n, hipStream_t s
 nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s) {
     if (n <= 0) return NRT_OK;
     copy_u32_kernel<<<grid_for(n, 256), 256, 0, s>>>((uint32_t*)dst, (const uint32_t*)src, n);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_stream_copy(float* b, const float* a, int64_t n_floats, hipStream_t s) {
+    if (n_floats < 4) return NRT_OK;
+    stream_copy_kernel<<<grid_for(n_floats / 16, 256, 8192), 256, 0, s>>>((float4*)b, (const float4*)a, n_floats / 4);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_stream_read(float* b, const float* a, int64_t n_floats, hipStream_t s) {
+    if (n_floats < 4) return NRT_OK;
+    stream_read_kernel<<<grid_for(n_floats / 16, 256, 8192), 256, 0, s>>>(b, (const float4*)a, n_floats / 4);
     LAUNCH_CHECK();
     return NRT_OK;
 }

