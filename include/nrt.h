@@ -169,6 +169,18 @@ nrt_status nrt_graph_num_edges(const nrt_graph*, int64_t* n_edges /*host*/);
 nrt_status nrt_graph_export_csc(const nrt_graph*, int64_t* indptr, int32_t* indices, float* weights,
                                 int64_t cap, void* stream);
 
+/*
+ * nrt_graph_export_csc for callers that cannot allocate device memory and hand the library no scratch of their own
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same result, but the
+ * block sums of the offset scan live in a device array inside the library (1 MiB per GPU, held until the process
+ * ends) instead of the graph's workspace, and the call allocates nothing.  Graphs of more than 134 184 959 vertices
+ * do not fit that array: NRT_ERR_INVALID_ARG with a message, nothing written.  All calls on one GPU share the
+ * array (it keeps the last call's contents; nothing in it needs to start at zero): calls that overlap on one GPU race.
+ * Other arguments, errors and the final stream synchronisation as nrt_graph_export_csc.
+ */
+nrt_status nrt_graph_export_csc_static(const nrt_graph*, int64_t* indptr, int32_t* indices, float* weights,
+                                       int64_t cap, void* stream);
+
 /* ---- caches ------------------------------------------------------------------------------- */
 
 nrt_status nrt_cache_workspace_bytes(const nrt_graph*, const nrt_model_desc*, int64_t max_batch_edges,

@@ -61,7 +61,7 @@ class NrtError(RuntimeError):
 
 
 EXPORTS = ["nrt_graph_workspace_bytes", "nrt_graph_create", "nrt_graph_destroy", "nrt_graph_num_edges",
-           "nrt_graph_export_csc", "nrt_cache_workspace_bytes", "nrt_cache_init", "nrt_cache_destroy",
+           "nrt_graph_export_csc", "nrt_graph_export_csc_static", "nrt_cache_workspace_bytes", "nrt_cache_init", "nrt_cache_destroy",
            "nrt_apply_batch", "nrt_get_layer", "nrt_get_aggregate", "nrt_get_layer_affected", "nrt_set_profiling",
            "nrt_set_mode", "nrt_set_lazy", "nrt_query", "nrt_get_stats", "nrt_measure_stream", "nrt_last_error", "nrt_version"]
 
@@ -82,6 +82,7 @@ def lib() -> ctypes.CDLL:
         L.nrt_graph_destroy.restype = None
         L.nrt_graph_num_edges.argtypes = [c_fp, P(i64)]
         L.nrt_graph_export_csc.argtypes = [c_fp, c_fp, c_fp, c_fp, i64, c_fp]
+        L.nrt_graph_export_csc_static.argtypes = [c_fp, c_fp, c_fp, c_fp, i64, c_fp]
         L.nrt_cache_workspace_bytes.argtypes = [c_fp, P(nrt_model_desc), i64, i64, P(sz)]
         L.nrt_cache_init.argtypes = [c_fp, P(nrt_model_desc), c_fp, i64, i64, c_fp, sz, c_fp, P(c_fp)]
         L.nrt_cache_destroy.argtypes = [c_fp]
@@ -178,6 +179,11 @@ def nrt_graph_export_csc(g: Graph):
     w = torch.empty(max(e, 1), dtype=torch.float32, device="cuda") if g.weighted else None
     _check(lib().nrt_graph_export_csc(g.handle, _ptr(indptr), _ptr(indices), _ptr(w), max(e, 1), _stream()))
     return indptr, indices[:e], None if w is None else w[:e]
+
+
+def nrt_graph_export_csc_static(g: Graph, indptr: torch.Tensor, indices: torch.Tensor, weights: Optional[torch.Tensor]) -> None:
+    """The export into buffers the caller already holds; the call itself allocates nothing."""
+    _check(lib().nrt_graph_export_csc_static(g.handle, _ptr(indptr), _ptr(indices), _ptr(weights), indices.numel(), _stream()))
 
 
 def make_desc(spec, dev_params) -> nrt_model_desc:

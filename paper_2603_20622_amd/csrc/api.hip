@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 // ------------------------------------------------------------------ errors
@@ -239,6 +240,57 @@ extern "C" nrt_status nrt_graph_export_csc(const nrt_graph* g, int64_t* indptr, 
     LAUNCH_CHECK();
     NRT_TRY(k_exclusive_scan_u64((uint64_t*)indptr, n + 1, g->scan_tmp, g->scan_tmp_len,
                                  (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
+    export_lists_kernel<<<(int)cdiv(n * 64, 256), 256, 0, s>>>(g->in, n, indptr, indices, weights);
+    LAUNCH_CHECK();
+    HIP_TRY(hipStreamSynchronize(s));
+    return NRT_OK;
+}
+
+// ---- the same export for callers that cannot allocate or bring a workspace of their own for it: the block sums
+// of the offset scan live in a file-scope device array instead of the graph's workspace.  Every GPU holds its own
+// copy of the array at its own address; the address is looked up once per device and only that pointer is ever
+// handed to kernels.
+constexpr size_t NRT_STATIC_SCRATCH_BYTES = size_t(1) << 20;
+constexpr int NRT_STATIC_MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[NRT_STATIC_SCRATCH_BYTES];
+static void* g_scratch_ptr[NRT_STATIC_MAX_DEVICES];
+static std::mutex g_scratch_mutex;
+
+static nrt_status static_scratch(void** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= NRT_STATIC_MAX_DEVICES) { nrt_set_error("device index %d out of range", dev); return NRT_ERR_DEVICE; }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { nrt_set_error("hipGetSymbolAddress returned a null address"); return NRT_ERR_DEVICE; }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return NRT_OK;
+}
+
+extern "C" nrt_status nrt_graph_export_csc_static(const nrt_graph* g, int64_t* indptr, int32_t* indices, float* weights,
+                                                  int64_t cap, void* stream) {
+    REQUIRE(g && indptr && (indices || g->e == 0), "null argument");
+    REQUIRE(cap >= g->e, "export capacity too small");
+    const int64_t n = g->n;
+    // layout of the static array: [0, 256) the scan's total, then one uint64 block sum per 1024 offsets
+    const int64_t tmp_len = (int64_t)((NRT_STATIC_SCRATCH_BYTES - 256) / sizeof(uint64_t));
+    if (cdiv(n + 1, 1024) > tmp_len) {
+        nrt_set_error("graph of %lld vertices exceeds the static scratch (%lld vertices at most); use nrt_graph_export_csc",
+                      (long long)n, (long long)(tmp_len * 1024 - 1));
+        return NRT_ERR_INVALID_ARG;
+    }
+    void* base = nullptr;
+    NRT_TRY(static_scratch(&base));
+    uint64_t* total = reinterpret_cast<uint64_t*>(base);
+    uint64_t* tmp = reinterpret_cast<uint64_t*>(static_cast<unsigned char*>(base) + 256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    export_deg_kernel<<<(int)cdiv(n + 1, 256), 256, 0, s>>>(g->in.deg, n, (uint64_t*)indptr);
+    LAUNCH_CHECK();
+    NRT_TRY(k_exclusive_scan_u64((uint64_t*)indptr, n + 1, tmp, tmp_len, total, s));
     export_lists_kernel<<<(int)cdiv(n * 64, 256), 256, 0, s>>>(g->in, n, indptr, indices, weights);
     LAUNCH_CHECK();
     HIP_TRY(hipStreamSynchronize(s));
