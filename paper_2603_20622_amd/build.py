@@ -10,9 +10,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnrt.so")
-SOURCES = ["prims.hip", "graph.hip", "frontier.hip", "gather.hip", "gemm.hip", "gat.hip", "agnn.hip", "monet.hip", "api.hip"]
+SOURCES = ["prims.hip", "graph.hip", "plan.hip", "frontier.hip", "gather.hip", "gemm.hip", "gat.hip", "agnn.hip", "monet.hip", "api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
-         "-packed-fp32-ops", "-munsafe-fp-atomics", "-Wall", "-Wno-unused-function",
+         "-packed-fp32-ops", "-Wall", "-Wno-unused-function",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
 
 

@@ -407,33 +407,40 @@ __global__ void __launch_bounds__(AG_WAVES * 64) agnn_combine_kernel(AgnnArgs a)
     }
 }
 
-// one wave per (updated edge, layer): SD^l[slot(dst)] += sign * w * cos(h_dst, h_src) * h_src on the old caches
+// one wave per (destination of an updated edge, layer): SD^l[slot] = sum over the destination's updates, in the order of
+// the batch plan, of sign * w * cos(h_dst, h_src) * h_src on the old caches (G-GCN: sign * gate * h_src); the wave owns
+// the row, so nothing is accumulated with atomics
 __global__ void agnn_structural_fold_kernel(AgnnFoldArgs a) {
-    const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
     const int l = blockIdx.y;
-    if (op >= a.n_ins + a.n_del) return;
-    const bool is_del = op >= a.n_ins;
-    const int64_t i = is_del ? op - a.n_ins : op;
-    const int32_t u = is_del ? a.del_src[i] : a.ins_src[i];
-    const int32_t v = is_del ? a.del_dst[i] : a.ins_dst[i];
-    if (u < 0 || u >= a.n || v < 0 || v >= a.n) return;     // the batch's verdict is not known yet: it will be rejected
+    const int64_t nd = (int64_t)*a.n_slots;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     const int D = a.D[l];
-    const float* hu = a.H[l] + (int64_t)u * D;
-    const float* hv = a.H[l] + (int64_t)v * D;
-    float* dst = a.SD[l] + (int64_t)a.dd_slot[v] * D;
-    if (a.gate) {                   // G-GCN: sign * sigmoid(W_1 h_src + W_2 h_dst) * h_src, element by element
-        const float sign = is_del ? -1.0f : 1.0f;
-        const float* p1 = a.P1[l] + (int64_t)u * D;
-        const float* p2 = a.P2[l] + (int64_t)v * D;
-        for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, sign * sigmoidf(p1[k] + p2[k]) * hu[k]);
-        return;
+    for (int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; s < nd; s += waves) {
+        const int32_t b = a.off[s], e = a.off[s + 1];
+        const int32_t v = a.list[s];
+        const float* hv = a.H[l] + (int64_t)v * D;
+        float* dst = a.SD[l] + s * D;
+        for (int k = lane; k < D; k += 64) dst[k] = 0.f;           // the row is this wave's alone
+        for (int32_t j = b; j < e; ++j) {
+            const int32_t op = a.ord[j];
+            const bool is_del = op >= a.n_ins;
+            const int32_t u = is_del ? a.del_src[op - a.n_ins] : a.ins_src[op];
+            const float* hu = a.H[l] + (int64_t)u * D;
+            const float sign = is_del ? -1.0f : 1.0f;
+            if (a.gate) {               // G-GCN: sign * sigmoid(W_1 h_src + W_2 h_dst) * h_src, element by element
+                const float* p1 = a.P1[l] + (int64_t)u * D;
+                const float* p2 = a.P2[l] + (int64_t)v * D;
+                for (int k = lane; k < D; k += 64) dst[k] += sign * sigmoidf(p1[k] + p2[k]) * hu[k];
+                continue;
+            }
+            float d = 0.f;
+            for (int k = lane; k < D; k += 64) d += hu[k] * hv[k];
+            d = wave_sum(d);
+            const float c = sign * a.beta[l] * a.R[l][u] * a.R[l][v] * d;
+            for (int k = lane; k < D; k += 64) dst[k] += c * hu[k];
+        }
     }
-    float d = 0.f;
-    for (int k = lane; k < D; k += 64) d += hu[k] * hv[k];
-    d = wave_sum(d);
-    const float c = (is_del ? -1.0f : 1.0f) * a.beta[l] * a.R[l][u] * a.R[l][v] * d;
-    for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, c * hu[k]);
 }
 
 }  // namespace
@@ -482,7 +489,9 @@ nrt_status k_agnn_combine(const AgnnArgs& a, hipStream_t s) {
 nrt_status k_agnn_structural_fold(const AgnnFoldArgs& a, hipStream_t s) {
     const int64_t nops = a.n_ins + a.n_del;
     if (nops <= 0 || a.n_layers <= 0) return NRT_OK;
-    agnn_structural_fold_kernel<<<dim3((unsigned)cdiv(nops * 64, 256), (unsigned)a.n_layers, 1), 256, 0, s>>>(a);
+    int64_t g = cdiv(nops, 4);
+    if (g > 2048) g = 2048;
+    agnn_structural_fold_kernel<<<dim3((unsigned)g, (unsigned)a.n_layers, 1), 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }

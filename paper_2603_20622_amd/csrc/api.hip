@@ -86,8 +86,12 @@ struct nrt_cache {
     bool is_gat;
     float* SD[NRT_MAX_LAYERS + 1];      // structural-delta rows of a batch, [max_edges][dagg[l]]
     float* SDden[NRT_MAX_LAYERS + 1];   // GAT: their attention-sum part, [max_edges][heads]
-    int32_t* ins_cnt;                   // GAT: inserted in-edges per destination of an updated edge, [max_edges]
-    int32_t *list_dd, *slot_dd;         // destinations of updated edges: sorted ids, vertex -> row of SD
+    int32_t* ins_cnt;                   // inserted in-edges per destination of an updated edge, [max_edges]
+    int32_t *list_dd, *slot_dd;         // destinations of updated edges: sorted ids, vertex -> row of SD (the batch plan's slots)
+    int32_t *plan_off, *plan_ord, *ins_rank;   // the batch plan: runs of updates per destination, rank of each insert
+    uint64_t* plan_off64;               // its scratch for batches of more than 2048 updates
+    int32_t *plan_cursor, *plan_tmp;
+    uint64_t* plan_scan; int64_t plan_scan_len;   // block sums of its scans
     DstRec* recs;
     HubWork hubs;
     BatchScratch sc;
@@ -391,7 +395,15 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         c->SD[l] = b.take<float>((size_t)(c->max_edges + 1) * c->dagg[l]);
         c->SDden[l] = gat ? b.take<float>((size_t)(c->max_edges + 1) * c->heads) : nullptr;
     }
-    c->ins_cnt = gat ? b.take<int32_t>(c->max_edges + 1) : nullptr;
+    c->ins_cnt = b.take<int32_t>(c->max_edges + 1);
+    c->plan_off = b.take<int32_t>(c->max_edges + 2);
+    c->plan_ord = b.take<int32_t>(c->max_edges + 1);
+    c->ins_rank = b.take<int32_t>(c->max_edges + 1);
+    c->plan_off64 = b.take<uint64_t>(c->max_edges + 2);
+    c->plan_cursor = b.take<int32_t>(c->max_edges + 1);
+    c->plan_tmp = b.take<int32_t>(c->max_edges + 1);
+    c->plan_scan_len = cdiv(c->max_edges + 2 > nw ? c->max_edges + 2 : nw, 1024) + 64;
+    c->plan_scan = b.take<uint64_t>(c->plan_scan_len);
     c->list_dd = b.take<int32_t>(c->max_edges + 64);
     c->slot_dd = b.take<int32_t>(n);
     c->AS_old = gat ? b.take<float>(n * c->heads) : nullptr;
@@ -1044,11 +1056,10 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         f.add(c->bm_ddst, 2 * c->nw_pad);                     // bm_ddst and bm_feat are adjacent
         f.add(c->lc, (int64_t)((NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 4));
         if (c->profiling) f.add(c->pair_ctr, 2 * 1024 * NRT_MAX_LAYERS);
-        for (int l = 1; l <= c->L; ++l) {
-            f.add(c->SD[l], (b->n_ins + b->n_del) * (int64_t)c->dagg[l]);
-            if (c->kind == NRT_GAT) f.add(c->SDden[l], (b->n_ins + b->n_del) * (int64_t)c->heads);
+        if (b->n_ins + b->n_del > 2048) {                     // scratch of the batch plan's counting form
+            f.add(c->plan_off64, 2 * (b->n_ins + b->n_del + 1));
+            f.add(c->plan_cursor, b->n_ins + b->n_del);
         }
-        if (c->kind == NRT_GAT) f.add(c->ins_cnt, b->n_ins + b->n_del);
         NRT_TRY(graph_validate_batch(g, b, c->sc, &f, s));
     }
     // The verdict travels to the host while the device goes on with work that touches only per-batch scratch and
@@ -1067,20 +1078,34 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && !agnn_family(c->kind) && !c->agg_only && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     if (!empty_batch) NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, n, s));
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
-    if (inc && b->n_ins + b->n_del > 0) {
-        // destinations of updated edges -> compact rows that collect their structural terms (bm[1] is scratch here)
-        NRT_TRY(k_compact(nullptr, c->bm_ddst, nullptr, c->bm[1], n, c->list_dd, c->slot_dd, g->scan_tmp, g->scan_tmp_len,
-                          (uint64_t*)(g->dev_ctrs + CTR_COUNT), s));
+    uint64_t* n_slots_dev = (uint64_t*)(g->dev_ctrs + CTR_COUNT);
+    if (b->n_ins + b->n_del > 0) {
+        // the batch plan: updates grouped by destination in a fixed order.  Its slots are the compact rows that collect
+        // the structural terms; its ranks place the inserted in-edges (bm[1] is scratch here)
+        PlanArgs p;
+        memset(&p, 0, sizeof(p));
+        p.n_ins = b->n_ins; p.n_del = b->n_del; p.n = n;
+        p.ins_src = b->ins_src; p.ins_dst = b->ins_dst; p.del_src = b->del_src; p.del_dst = b->del_dst;
+        p.dst_bitmap = c->bm_ddst;
+        p.scratch_bm = c->bm[1];
+        p.list = c->list_dd; p.slot_of = c->slot_dd;
+        p.off = c->plan_off; p.ord = c->plan_ord; p.ins_cnt = c->ins_cnt; p.ins_rank = c->ins_rank;
+        p.count = n_slots_dev;
+        p.off64 = c->plan_off64; p.cursor = c->plan_cursor; p.tmp = c->plan_tmp;
+        p.total = (uint64_t*)(g->dev_ctrs + CTR_PLAN_TOTAL);
+        NRT_TRY(k_batch_plan(p, c->plan_scan, c->plan_scan_len, s));
     }
+    c->sc.plan_slot_of = c->slot_dd;
+    c->sc.plan_ins_cnt = c->ins_cnt;
+    c->sc.plan_ins_rank = c->ins_rank;
 
     // ---- structural terms on the old caches, all layers in one launch
     if (inc && c->kind == NRT_GAT) {
         GatFoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
-        f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
-        f.dd_slot = c->slot_dd;
-        f.ins_cnt = c->ins_cnt;
+        f.del_src = b->del_src; f.del_dst = b->del_dst;
+        f.n_slots = n_slots_dev; f.off = c->plan_off; f.ord = c->plan_ord; f.list = c->list_dd;
         f.n = n;
         f.n_layers = c->L; f.heads = c->heads; f.head_dim = c->head_dim; f.slope = c->leaky_slope;
         for (int l = 1; l <= c->L; ++l) {
@@ -1093,8 +1118,8 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         AgnnFoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del; f.n = n;
-        f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
-        f.dd_slot = c->slot_dd;
+        f.ins_src = b->ins_src; f.del_src = b->del_src;
+        f.n_slots = n_slots_dev; f.off = c->plan_off; f.ord = c->plan_ord; f.list = c->list_dd;
         f.n_layers = c->L;
         for (int l = 1; l <= c->L; ++l) {
             f.H[l - 1] = c->H[l - 1]; f.R[l - 1] = c->R[l - 1]; f.SD[l - 1] = c->SD[l];
@@ -1120,7 +1145,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         f.indeg_old = gcn ? g->in.deg : nullptr;
         f.n_layers = c->L;
         f.n = n;
-        f.dd_slot = c->slot_dd;
+        f.n_slots = n_slots_dev; f.off = c->plan_off; f.ord = c->plan_ord;
         for (int l = 1; l <= c->L; ++l) {
             f.Hprev[l - 1] = payload_rows(c, l - 1);
             if (c->agg_only && l - 1 >= 1) { f.Hprev[l - 1] = c->ES[l - 1]; f.compact_src[l - 1] = 1; }

@@ -9,7 +9,7 @@
 #define NRT_WAVE 64
 // layout of the device counter block (int64 cells) mirrored to pinned host memory in one copy
 enum { CTR_GROW = 0 /*2*/, CTR_HEAD_OUT = 8, CTR_HEAD_IN = 9, CTR_ERR = 16 /*8 x int32*/, CTR_COUNT = 24,
-       CTR_ITEMS = 25 /* low 32 items, high 32 partial rows */, CTR_MULTI = 26, CTR_INEDGES = 27, NRT_NCTRS = 64 };
+       CTR_PLAN_TOTAL = 25 /* updates that entered the batch plan */, NRT_NCTRS = 64 };
 #define NRT_COARSE_WORDS 6144  // 24 KiB of LDS for the coarse changed-source filter of the sparse gather
 #define NRT_CHUNK 256          // in-list entries per gather work item (one wave each)
 
@@ -213,14 +213,37 @@ nrt_status k_gather(const GatherArgs& a, hipStream_t s);
 nrt_status k_coarse_bitmap(const uint32_t* fine, int64_t n, int shift, uint32_t* coarse, int64_t n_words, hipStream_t s);
 nrt_status k_combine_partials(const GatherArgs& a, hipStream_t s);
 
-struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update caches; edges with an id outside [0, n) are skipped
+// ---------------------------------------------------------------- plan.hip
+struct PlanArgs {   // the batch's edge updates grouped by destination in a fixed order (see plan.hip)
     int64_t n_ins, n_del, n;
+    const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
+    const uint32_t* dst_bitmap;    // destinations of the updates (more than 2048 updates: the slots come from it)
+    uint32_t* scratch_bm;          // [n / 32] scratch of the compaction
+    int32_t* list;                 // [updates] destination of a slot, ascending
+    int32_t* slot_of;              // [n] vertex -> slot (only entries of this batch's destinations are current)
+    int32_t* off;                  // [updates + 1] first position of a slot's run in ord
+    int32_t* ord;                  // [updates] update numbers, run by run
+    int32_t* ins_cnt;              // [updates] inserts in a slot's run
+    int32_t* ins_rank;             // [n_ins] rank of an insert among the inserts of its destination
+    uint64_t* count;               // device: number of slots
+    // scratch of the form for more than 2048 updates (zero on entry: off64, cursor)
+    uint64_t* off64;               // [updates + 1]
+    int32_t* cursor;               // [updates]
+    int32_t* tmp;                  // [updates]
+    uint64_t* total;               // device: updates that entered the plan
+};
+nrt_status k_batch_plan(const PlanArgs& a, uint64_t* scan_tmp, int64_t scan_tmp_len, hipStream_t s);
+
+struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update caches, one owner wave per destination
+    int64_t n_ins, n_del, n;
+    const uint64_t* n_slots;      // the batch plan: number of destinations, their runs of updates
+    const int32_t* off;
+    const int32_t* ord;
     const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
     const float *ins_w, *del_w;  // null when unweighted
     int n_layers;                // blockIdx.y walks the layers
     const float* Hprev[NRT_MAX_LAYERS];   // h^{l-1} (old)
-    float* SD[NRT_MAX_LAYERS];            // compact structural-delta rows, one per destination of an updated edge
-    const int32_t* dd_slot;               // vertex -> row of SD
+    float* SD[NRT_MAX_LAYERS];            // compact structural-delta rows, one per destination of an updated edge (plan slot)
     int D[NRT_MAX_LAYERS];
     const int32_t* indeg_old;    // for the GCN payload scale, else null
     int compact_src[NRT_MAX_LAYERS];      // Hprev[l] holds one row per updated edge (inserts first) instead of one per vertex
@@ -305,10 +328,12 @@ struct GatArgs {
 };
 nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s);
 struct GatFoldArgs {   // structural terms of a batch for GAT, evaluated on the pre-update caches, all layers in one launch
-    int64_t n_ins, n_del, n;    // edges with an id outside [0, n) are skipped
-    const int32_t *ins_dst, *del_src, *del_dst;
-    const int32_t* dd_slot;
-    int32_t* ins_cnt;
+    int64_t n_ins, n_del, n;
+    const int32_t *del_src, *del_dst;
+    const uint64_t* n_slots;    // the batch plan: destinations, their runs of updates (inserts first)
+    const int32_t* off;
+    const int32_t* ord;
+    const int32_t* list;        // destination vertex of a slot
     int n_layers, heads, head_dim;
     float slope;
     const float* Z[NRT_MAX_LAYERS]; const float* AS[NRT_MAX_LAYERS]; const float* AD[NRT_MAX_LAYERS];
@@ -343,9 +368,12 @@ struct AgnnArgs {
     const float* old_p1;            // [changed][D] compact: W_1 h before this batch
 };
 struct AgnnFoldArgs {   // structural terms of a batch, evaluated on the pre-update caches, all layers in one launch
-    int64_t n_ins, n_del, n;        // edges with an id outside [0, n) are skipped
-    const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
-    const int32_t* dd_slot;
+    int64_t n_ins, n_del, n;
+    const int32_t *ins_src, *del_src;
+    const uint64_t* n_slots;        // the batch plan: destinations, their runs of updates
+    const int32_t* off;
+    const int32_t* ord;
+    const int32_t* list;            // destination vertex of a slot
     int n_layers;
     const float* H[NRT_MAX_LAYERS];   // h^{l-1} (old)
     const float* R[NRT_MAX_LAYERS];   // its inverse norms (old)
@@ -387,6 +415,10 @@ struct BatchScratch {
     int32_t* err;                               // device error flags [8] (inside the counter block)
     int32_t* feat_index;                        // [N] position of a vertex in the batch's feature list
     int32_t* feat_stamp;                        // [N] epoch stamps that detect repeated feature ids
+    // from the batch plan: where an inserted in-edge goes in its destination's list (reproducible list order)
+    const int32_t* plan_slot_of;                // [N] vertex -> plan slot
+    const int32_t* plan_ins_cnt;                // [slots] inserts per destination
+    const int32_t* plan_ins_rank;               // [n_ins] rank of an insert among those of its destination
 };
 // validate (no state change); err flags and growth need are read back by the caller
 // `clears`: scratch areas of the caller to zero in the same launch as the validation's own (may be null)

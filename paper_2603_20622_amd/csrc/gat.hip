@@ -54,32 +54,36 @@ __global__ void gat_scalars_kernel(GatArgs a) {
 }
 
 // ------------------------------------------------------------------ structural terms (Algorithm 3 on edge updates)
-// One wave per (updated edge, layer), before the graph and the caches change.  Deleted edge u->v: minus its old
-// attention term, relative to v's cached bound m, into the compact row of v.  Inserted edge: layer 0 counts it for
-// its destination (the gather finds that many new entries at the end of the in-list).
+// One wave per (destination of an updated edge, layer), before the graph and the caches change: the destination's
+// deleted in-edges u->v, in the order of the batch plan, each contribute minus their old attention term relative to
+// v's cached bound m, summed in registers into the compact row of v (no atomics: the wave owns the row).  Its
+// inserted in-edges are only counted (by the plan): the gather finds them at the end of the in-list.
 __global__ void gat_structural_fold_kernel(GatFoldArgs a) {
-    const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int lane = threadIdx.x & 63;
     const int l = blockIdx.y;
-    if (op >= a.n_ins + a.n_del) return;
-    if (op < a.n_ins) {
-        const int32_t vd = a.ins_dst[op];
-        if (l == 0 && lane == 0 && vd >= 0 && vd < a.n) atomicAdd(&a.ins_cnt[a.dd_slot[vd]], 1);
-        return;
-    }
-    const int64_t i = op - a.n_ins;
-    const int32_t u = a.del_src[i], v = a.del_dst[i];
-    if (u < 0 || u >= a.n || v < 0 || v >= a.n) return;     // the batch's verdict is not known yet: it will be rejected
-    const int64_t row = a.dd_slot[v];
+    const int64_t nd = (int64_t)*a.n_slots;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     const int H = a.heads, hd = a.head_dim, D = H * hd;
-    for (int col = lane * 4; col < D; col += 256) {
-        const int k = col / hd;
-        const float e = leaky(a.AD[l][(int64_t)v * H + k] + a.AS[l][(int64_t)u * H + k], a.slope);
-        const float w = __expf(e - a.M[l][(int64_t)v * H + k]);        // at most 1: m bounds every cached logit of v
-        const float4 z = *reinterpret_cast<const float4*>(a.Z[l] + (int64_t)u * D + col);
-        float* dst = a.SDS[l] + row * D + col;
-        atomicAdd(dst + 0, -w * z.x); atomicAdd(dst + 1, -w * z.y); atomicAdd(dst + 2, -w * z.z); atomicAdd(dst + 3, -w * z.w);
-        if (col % hd == 0) atomicAdd(a.SDDEN[l] + row * H + k, -w);
+    for (int64_t s = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; s < nd; s += waves) {
+        const int32_t b = a.off[s], e = a.off[s + 1];
+        const int32_t v = a.list[s];
+        for (int col = lane * 4; col < D; col += 256) {
+            const int k = col / hd;
+            const float adv = a.AD[l][(int64_t)v * H + k], mv = a.M[l][(int64_t)v * H + k];
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            float den = 0.f;
+            for (int32_t j = b; j < e; ++j) {
+                const int32_t op = a.ord[j];
+                if (op < a.n_ins) continue;                            // inserts come first in the run
+                const int32_t u = a.del_src[op - a.n_ins];
+                const float w = __expf(leaky(adv + a.AS[l][(int64_t)u * H + k], a.slope) - mv);   // at most 1: m bounds every cached logit of v
+                const float4 z = *reinterpret_cast<const float4*>(a.Z[l] + (int64_t)u * D + col);
+                acc.x -= w * z.x; acc.y -= w * z.y; acc.z -= w * z.z; acc.w -= w * z.w;
+                den -= w;
+            }
+            *reinterpret_cast<float4*>(a.SDS[l] + s * D + col) = acc;
+            if (col % hd == 0) a.SDDEN[l][s * H + k] = den;
+        }
     }
 }
 
@@ -536,9 +540,10 @@ nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s) {
 
 nrt_status k_gat_structural_fold(const GatFoldArgs& a, hipStream_t s) {
     const int64_t nops = a.n_ins + a.n_del;
-    if (nops <= 0) return NRT_OK;
-    dim3 grid((unsigned)cdiv(nops * 64, 256), (unsigned)a.n_layers, 1);
-    gat_structural_fold_kernel<<<grid, 256, 0, s>>>(a);
+    if (nops <= 0 || a.n_layers <= 0) return NRT_OK;
+    int64_t g = cdiv(nops, 4);
+    if (g > 2048) g = 2048;
+    gat_structural_fold_kernel<<<dim3((unsigned)g, (unsigned)a.n_layers, 1), 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }

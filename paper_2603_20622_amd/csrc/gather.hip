@@ -3,7 +3,7 @@
 // For every affected destination v the cached sum S[v] = sum_u c_uv p_u receives the changes of its
 // affected in-neighbours: S[v] += sum_{u in N_new(v), u changed} c_uv * dp_u, where dp_u is the change of
 // the source payload (already formed by the previous layer's write-back).  The terms of inserted and
-// deleted edges are folded beforehand on the old caches (k_structural_fold): +c p_u(old) for an inserted
+// deleted edges are folded beforehand on the old caches (k_structural_fold, plan.hip): +c p_u(old) for an inserted
 // edge, -c p_u(old) for a deleted one, so that an inserted edge whose source also changed sums to
 // c p_u(new) (Section IV-B: insert = positive message, delete = negative, update = both).
 //
@@ -816,29 +816,6 @@ __global__ void combine_kernel(GatherArgs a) {
     }
 }
 
-// ------------------------------------------------------------------ structural fold
-// one wave per (updated edge, layer): SD^l[slot(dst)] += sign * c * p^{l-1}_src(old); the gather wave that owns
-// dst adds the row to the cached aggregate, so the aggregate itself is never touched by atomics
-__global__ void structural_fold_kernel(FoldArgs a) {
-    const int64_t op = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-    const int lane = threadIdx.x & 63;
-    const int l = blockIdx.y;
-    if (op >= a.n_ins + a.n_del) return;
-    const bool is_del = op >= a.n_ins;
-    const int64_t i = is_del ? op - a.n_ins : op;
-    const int32_t u = is_del ? a.del_src[i] : a.ins_src[i];
-    const int32_t v = is_del ? a.del_dst[i] : a.ins_dst[i];
-    if (u < 0 || u >= a.n || v < 0 || v >= a.n) return;     // the batch's verdict is not known yet: it will be rejected
-    float c = is_del ? -1.0f : 1.0f;
-    if (is_del && a.del_w) c *= a.del_w[i];
-    if (!is_del && a.ins_w) c *= a.ins_w[i];
-    if (a.indeg_old) c *= gcn_scale(a.indeg_old[u]);
-    const int D = a.D[l];
-    const float* src = a.Hprev[l] + (a.compact_src[l] ? op : (int64_t)u) * D;
-    float* dst = a.SD[l] + (int64_t)a.dd_slot[v] * D;
-    for (int k = lane; k < D; k += 64) unsafeAtomicAdd(dst + k, c * src[k]);
-}
-
 // ------------------------------------------------------------------ layer-0 delta payloads
 // one wave per source of change at layer 1: replaced features and (GCN) re-normalised payloads
 __global__ void layer0_delta_kernel(DeltaArgs a) {
@@ -915,14 +892,6 @@ nrt_status k_coarse_bitmap(const uint32_t* fine, int64_t n, int shift, uint32_t*
 
 nrt_status k_combine_partials(const GatherArgs& a, hipStream_t s) {
     combine_kernel<<<2048, 256, 0, s>>>(a);
-    LAUNCH_CHECK();
-    return NRT_OK;
-}
-
-nrt_status k_structural_fold(const FoldArgs& a, hipStream_t s) {
-    const int64_t nops = a.n_ins + a.n_del;
-    if (nops <= 0) return NRT_OK;
-    structural_fold_kernel<<<dim3((unsigned)cdiv(nops * 64, 256), (unsigned)a.n_layers, 1), 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }

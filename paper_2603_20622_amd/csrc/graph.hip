@@ -57,7 +57,8 @@ __global__ void copy_lists_kernel(const int64_t* indptr, const int32_t* indices,
         if (a.wts) a.wts[o + (j - b)] = w[j];
     }
 }
-// one wave per key vertex of the given direction: scatter into the other direction with cursors
+// one wave per key vertex of the given direction: scatter into the other direction with cursors (sort_lists_kernel
+// then fixes the order inside each list)
 __global__ void transpose_fill_kernel(const int64_t* indptr, const int32_t* indices, const float* w, int64_t n,
                                       Adj other, int32_t* cursor) {
     const int64_t k = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
@@ -70,6 +71,97 @@ __global__ void transpose_fill_kernel(const int64_t* indptr, const int32_t* indi
         int32_t p = atomicAdd(&cursor[t], 1);
         other.idx[other.off[t] + p] = (int32_t)k;
         if (other.wts) other.wts[other.off[t] + p] = w[j];
+    }
+}
+
+// The cursors above hand out positions in whatever order the waves arrive.  The gathers sum a destination's messages
+// in the order of its in-list, so a derived direction is brought into a fixed order afterwards: every list sorted by
+// neighbour id (ids are distinct inside a list), weights moved along.  A wave sorts a list of up to 64 entries in
+// its registers (rank by counting); longer lists are left to the whole workgroup, which sorts them with a bitonic
+// network (ascending compare-exchanges only, so positions past the end act as +infinity and any length works), in
+// LDS up to SORT_LDS entries and in place in global memory beyond.
+constexpr int SORT_THREADS = 1024;
+constexpr int SORT_LDS = 4096;
+
+__device__ inline void sort_cex(int32_t* ki, float* kw, int lo, int hi) {
+    const int32_t x = ki[lo], y = ki[hi];
+    if (x > y) {
+        ki[lo] = y; ki[hi] = x;
+        if (kw) { const float t = kw[lo]; kw[lo] = kw[hi]; kw[hi] = t; }
+    }
+}
+// all threads of the workgroup; ki/kw point to LDS or global memory holding len entries
+__device__ inline void sort_network(int32_t* ki, float* kw, int len) {
+    int P = 2;
+    while (P < len) P <<= 1;
+    for (int k = 2; k <= P; k <<= 1) {
+        const int half = k >> 1;
+        for (int t = threadIdx.x; t < (P >> 1); t += SORT_THREADS) {         // first step of a merge: mirror pairs
+            const int blk = t / half, o = t - blk * half;
+            const int lo = blk * k + o, hi = blk * k + k - 1 - o;
+            if (hi < len) sort_cex(ki, kw, lo, hi);
+        }
+        __syncthreads();
+        for (int j = half >> 1; j > 0; j >>= 1) {
+            for (int t = threadIdx.x; t < (P >> 1); t += SORT_THREADS) {
+                const int lo = ((t & ~(j - 1)) << 1) | (t & (j - 1)), hi = lo | j;
+                if (hi < len) sort_cex(ki, kw, lo, hi);
+            }
+            __syncthreads();
+        }
+    }
+}
+
+__global__ void __launch_bounds__(SORT_THREADS) sort_lists_kernel(Adj a, int64_t n) {
+    __shared__ int32_t s_idx[SORT_LDS];
+    __shared__ float s_wts[SORT_LDS];
+    __shared__ int32_t s_long[SORT_THREADS / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t per_round = SORT_THREADS / 64;
+    const int64_t rounds = (n + (int64_t)gridDim.x * per_round - 1) / ((int64_t)gridDim.x * per_round);   // uniform trip count
+    for (int64_t r = 0; r < rounds; ++r) {
+        const int64_t v = (r * gridDim.x + blockIdx.x) * per_round + w;
+        int32_t is_long = -1;
+        if (v < n) {
+            const int32_t d = a.deg[v];
+            const int64_t o = a.off[v];
+            if (d > 64) {
+                is_long = (int32_t)v;
+            } else if (d > 1) {
+                const int32_t mine = lane < d ? a.idx[o + lane] : 0x7fffffff;
+                const float mw = (a.wts && lane < d) ? a.wts[o + lane] : 0.f;
+                int rank = 0;
+                for (int j = 0; j < d; ++j) rank += __builtin_amdgcn_readlane(mine, j) < mine;   // d is wave-uniform
+                if (lane < d) {
+                    a.idx[o + rank] = mine;
+                    if (a.wts) a.wts[o + rank] = mw;
+                }
+            }
+        }
+        if (lane == 0) s_long[w] = is_long;
+        __syncthreads();
+        for (int t = 0; t < SORT_THREADS / 64; ++t) {
+            const int32_t lv = s_long[t];                           // uniform over the workgroup
+            if (lv < 0) continue;
+            const int32_t d = a.deg[lv];
+            const int64_t o = a.off[lv];
+            if (d <= SORT_LDS) {
+                for (int i = threadIdx.x; i < d; i += SORT_THREADS) {
+                    s_idx[i] = a.idx[o + i];
+                    if (a.wts) s_wts[i] = a.wts[o + i];
+                }
+                __syncthreads();
+                sort_network(s_idx, a.wts ? s_wts : nullptr, d);
+                for (int i = threadIdx.x; i < d; i += SORT_THREADS) {
+                    a.idx[o + i] = s_idx[i];
+                    if (a.wts) a.wts[o + i] = s_wts[i];
+                }
+                __syncthreads();
+            } else {
+                sort_network(a.idx + o, a.wts ? a.wts + o : nullptr, d);
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -427,7 +519,9 @@ __device__ inline void rebuild_by_workgroup(const RebuildArgs& A, int32_t k, int
         }
         if (threadIdx.x == 0) { a.off[k] = no; a.cap[k] = nc; }
     }
-    if (threadIdx.x == 0) { a.deg[k] = live; inscnt[k] = 0; delcnt[k] = 0; }
+    // an in-list already counts its pending inserts: each is then written at its planned position behind the live
+    // entries (append_kernel), so the order of an in-list does not depend on thread scheduling
+    if (threadIdx.x == 0) { a.deg[k] = live + (dir ? ic : 0); inscnt[k] = 0; delcnt[k] = 0; }
     __syncthreads();                                   // the shared scratch may be reused for the next list
 }
 
@@ -503,7 +597,7 @@ __global__ void __launch_bounds__(RB_THREADS) rebuild_lists_packed_kernel(Rebuil
                     }
                     if (lane == 0) { a.off[k] = no; a.cap[k] = nc; }
                 }
-                if (lane == 0) { a.deg[k] = live; inscnt[k] = 0; delcnt[k] = 0; }
+                if (lane == 0) { a.deg[k] = live + (dir ? ic : 0); inscnt[k] = 0; delcnt[k] = 0; }
             }
         }
     }
@@ -516,8 +610,11 @@ __global__ void __launch_bounds__(RB_THREADS) rebuild_lists_packed_kernel(Rebuil
     }
 }
 
+// Out-lists take their inserts through a cursor (their order matters to no result: they only serve set expansion and
+// lookups).  In-lists fix the order in which the gathers sum, so an inserted in-edge goes to the position the batch
+// plan gave it: behind the live entries of its destination (whose degree already counts the inserts), by rank.
 __global__ void append_kernel(Adj out, Adj in, int64_t n_ins, const int32_t* ins_src, const int32_t* ins_dst,
-                              const float* ins_w) {
+                              const float* ins_w, const int32_t* slot_of, const int32_t* ins_cnt, const int32_t* ins_rank) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_ins) return;
     const int32_t u = ins_src[i], v = ins_dst[i];
@@ -525,7 +622,7 @@ __global__ void append_kernel(Adj out, Adj in, int64_t n_ins, const int32_t* ins
     int32_t p = atomicAdd(&out.deg[u], 1);
     out.idx[out.off[u] + p] = v;
     if (out.wts) out.wts[out.off[u] + p] = w;
-    int32_t q = atomicAdd(&in.deg[v], 1);
+    const int32_t q = in.deg[v] - ins_cnt[slot_of[v]] + ins_rank[i];
     in.idx[in.off[v] + q] = u;
     if (in.wts) in.wts[in.off[v] + q] = w;
 }
@@ -592,6 +689,10 @@ static nrt_status derive_direction(nrt_graph* g, Adj& other, const int64_t* indp
     transpose_fill_kernel<<<(int)cdiv(n * 64, 256), 256, 0, s>>>(indptr, indices, w, n, other, cursor);
     LAUNCH_CHECK();
     NRT_TRY(k_fill_u32((uint32_t*)cursor, n, 0, s));
+    int64_t grid = cdiv(n, SORT_THREADS / 64);
+    if (grid > 4096) grid = 4096;
+    sort_lists_kernel<<<(int)grid, SORT_THREADS, 0, s>>>(other, n);
+    LAUNCH_CHECK();
     return NRT_OK;
 }
 
@@ -665,6 +766,10 @@ nrt_status graph_cancel_batch(nrt_graph* g, const nrt_batch* b, hipStream_t s) {
 nrt_status graph_mutate(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipStream_t s) {
     const int64_t nops = b->n_ins + b->n_del;
     if (nops == 0) { g->epoch += 2; return NRT_OK; }
+    if (b->n_ins > 0 && (!sc.plan_slot_of || !sc.plan_ins_cnt || !sc.plan_ins_rank)) {      // before anything changes
+        nrt_set_error("internal: batch plan missing");
+        return NRT_ERR_STATE;
+    }
     if (b->n_del > 0) {
         tombstone_kernel<<<(int)cdiv(b->n_del, 256), 256, 0, s>>>(g->out, g->in, b->n_del, sc.pos_out, sc.pos_in);
         LAUNCH_CHECK();
@@ -683,7 +788,8 @@ nrt_status graph_mutate(nrt_graph* g, const nrt_batch* b, BatchScratch& sc, hipS
     }
     LAUNCH_CHECK();
     if (b->n_ins > 0) {
-        append_kernel<<<(int)cdiv(b->n_ins, 256), 256, 0, s>>>(g->out, g->in, b->n_ins, b->ins_src, b->ins_dst, b->ins_w);
+        append_kernel<<<(int)cdiv(b->n_ins, 256), 256, 0, s>>>(g->out, g->in, b->n_ins, b->ins_src, b->ins_dst, b->ins_w,
+                                                               sc.plan_slot_of, sc.plan_ins_cnt, sc.plan_ins_rank);
         LAUNCH_CHECK();
     }
     g->epoch += 2;

@@ -403,6 +403,11 @@ def test_gat_edge_updates_only_with_long_in_lists(S, oracle):
             assert_parity(wl.GAT, ses.layer(l).cpu().numpy(), ref[l - 1], ("gat-struct", k, l))
 
 
+def _export_edges_raw(ses):
+    from paper_2603_20622_amd import binding as nb
+    return nb.nrt_graph_export_csc(ses.graph)
+
+
 def _export_edges(ses, n):
     from paper_2603_20622_amd import binding as nb
     indptr, indices, ww = nb.nrt_graph_export_csc(ses.graph)
@@ -766,6 +771,90 @@ def test_on_demand_queries_match_oracle(S, oracle, kind):
     ref = oracle.forward(spec, params, n, *cur)
     for l in range(1, spec.n_layers + 1):
         assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "eager", l))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_two_runs_of_a_chain_give_identical_bits(S, oracle, kind):
+    """Nothing on the batch path may depend on how the GPU schedules threads: the same chain applied to two fresh
+    sessions must leave bit-identical caches and in-lists.  The batches put many updates on few destinations (runs of
+    several terms per structural row, several inserts per in-list), one of them large enough for the counting form of
+    the batch plan; the last comparison is against the oracle, so both runs are also right."""
+    import torch
+    n, src, dst, w, x, spec, params, _ = small_case(kind, seed=31, n=1500, e=30000, L=3)
+    sizes = [(300, 300, 20), (40, 900, 0), (1500, 1200, 50), (700, 0, 5)]
+    outs = []
+    for run in range(2):
+        _, _, sampler = wl.rmat_graph(n, 30000, 31)
+        stream = wl.BatchStream(n, src, dst, w, sampler, spec.dims[0], seed=31)
+        ses = S.Session(spec, params, n, src, dst, w, x, max_batch_edges=4096, max_batch_feats=128)
+        cur = (src, dst, w, x)
+        for n_ins, n_del, n_feat in sizes:
+            b = stream.next_batch(n_ins, n_del, n_feat)
+            ses.apply(b, want_rows=False)
+            if run == 0:
+                cur = oracle.apply_batch(n, *cur, b)
+        layers = [ses.layer(l).clone() for l in range(1, spec.n_layers + 1)]
+        aggs = [ses.aggregate(l).clone() for l in range(1, spec.n_layers + 1)]
+        indptr, indices, weights = _export_edges_raw(ses)
+        outs.append((layers, aggs, indptr, indices, weights))
+        if run == 0:
+            ref = oracle.forward(spec, params, n, *cur)
+            assert_parity(kind, layers[-1].cpu().numpy(), ref[-1], (kind, "run 0"))
+    a, b2 = outs
+    for l in range(spec.n_layers):
+        assert torch.equal(a[0][l], b2[0][l]), (kind, "layer", l + 1)
+        assert torch.equal(a[1][l], b2[1][l]), (kind, "aggregate", l + 1)
+    assert torch.equal(a[2], b2[2]) and torch.equal(a[3], b2[3]), (kind, "in-lists")
+    if a[4] is not None:
+        assert torch.equal(a[4], b2[4]), (kind, "in-list weights")
+
+
+@pytest.mark.parametrize("give", ["csr", "csc"])
+def test_derived_direction_has_a_fixed_order(S, oracle, give):
+    """When only one adjacency direction is given the other is derived on the device; its lists must come out in a
+    fixed order (ascending neighbour id), whatever the thread schedule: lists of 1, of up to 64, of up to 4096 and of
+    more than 4096 entries (a star of 6000 spokes in both directions), with the weights moved along."""
+    import torch
+    from paper_2603_20622_amd import binding as nb
+    n = 6001
+    rng = np.random.default_rng(77)
+    spokes = np.arange(1, n, dtype=np.int64)
+    extra_s = rng.integers(1, n, size=60000)
+    extra_d = rng.integers(1, n, size=60000)
+    keep = extra_s != extra_d
+    keys = np.unique(np.concatenate([spokes * n + 0, 0 * n + spokes, extra_s[keep] * n + extra_d[keep]]))
+    src, dst = (keys // n).astype(np.int32), (keys % n).astype(np.int32)
+    w = rng.random(keys.size, dtype=np.float32)
+    spec = wl.ModelSpec(wl.GIN, [8, 8, 8], weighted=True)
+    params = wl.make_params(spec, 3)
+    x = wl.features(n, 8, 3)
+    ses = S.Session(spec, params, n, src, dst, w, x, give=give)
+    # the in-lists as stored
+    indptr, indices, ww = (t.cpu().numpy() for t in nb.nrt_graph_export_csc(ses.graph))
+    order = np.lexsort((src, dst))                               # by destination, then ascending source
+    want_ptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(np.bincount(dst, minlength=n), out=want_ptr[1:])
+    assert np.array_equal(indptr, want_ptr)
+    if give == "csr":                                            # the in-direction was derived: ascending sources
+        assert np.array_equal(indices, src[order])
+        assert np.array_equal(ww, w[order])
+    else:                                                        # the in-direction was given: kept as given
+        ip, ix, wx = wl.to_csr(n, dst, src, w)
+        assert np.array_equal(indices, ix) and np.array_equal(ww, wx)
+    ref = oracle.forward(spec, params, n, src, dst, w, x)
+    fresh = S.Session(spec, params, n, src, dst, w, x)
+    assert_parity(wl.GIN, ses.layer(2).cpu().numpy(), ref[-1], ("derived", give), fresh.layer(2).cpu().numpy())
+    # a batch on the derived lists (the out-direction, derived for give == "csc", serves validation and expansion)
+    sampler = wl.EdgeSampler(n, None, uniform=True)
+    stream = wl.BatchStream(n, src, dst, w, sampler, 8, seed=3)
+    b = stream.next_batch(200, 200, 10)
+    na = ses.apply(b)
+    cur = oracle.apply_batch(n, src, dst, w, x, b)
+    sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+    assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1])
+    fresh2 = S.Session(spec, params, n, *cur)
+    assert_parity(wl.GIN, ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1], ("derived batch", give),
+                  fresh2.layer(2).cpu().numpy())
 
 
 @pytest.mark.parametrize("kind", [wl.GAT, wl.AGNN, wl.GGCN])
