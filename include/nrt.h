@@ -241,12 +241,15 @@ nrt_status nrt_set_mode(nrt_cache*, int32_t mode);
  * (need_l or their in-neighbours)), recomputes exactly those vertices layer by layer over their whole
  * in-neighbourhoods (the recomputation of NRT_MODE_RECOMPUTE) and clears their stale marks; everything else stays
  * stale until some later query needs it.  Turning the mode off recomputes all remaining stale vertices first.
- * nrt_query also works with the mode off (it then only gathers rows).  Not available for NRT_GAT.
+ * nrt_query also works with the mode off (it then only gathers rows).  Every model kind is served; for the
+ * constrained models (GAT, A-GNN, G-GCN; Section III-D) what a layer caches per source vertex (z and the attention
+ * scalars, inverse norms, gate projections) is re-derived for exactly the rows a query brings up to date one layer
+ * below, and for the rows of h^0 every batch replaces.  Not available with aggregate-only storage.
  *   query_ids  device, n_query ids in [0, N), repeats allowed
  *   rows       device, [n_query][d_L], row i = embedding of query_ids[i]
  *   n_recomputed  host, may be NULL: vertices recomputed, summed over the layers
  * Errors: NRT_ERR_INVALID_ARG (null pointers, an id out of range: rows are then unspecified),
- * NRT_ERR_UNSUPPORTED (GAT), NRT_ERR_DEVICE.  Both calls synchronise the stream before returning. */
+ * NRT_ERR_UNSUPPORTED (aggregate-only storage), NRT_ERR_DEVICE.  Both calls synchronise the stream before returning. */
 nrt_status nrt_set_lazy(nrt_cache*, int32_t on, void* stream);
 nrt_status nrt_query(nrt_cache*, const int32_t* query_ids, int64_t n_query, float* rows, int64_t* n_recomputed /*host*/,
                      void* stream);

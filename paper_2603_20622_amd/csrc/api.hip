@@ -462,7 +462,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->sc.err = g->dev_ctrs ? (int32_t*)(g->dev_ctrs + CTR_ERR) : nullptr;
     c->pair_ctr = b.take<unsigned long long>(1024 * NRT_MAX_LAYERS);
     c->pull_list = b.take<int32_t>(n);
-    for (int l = 1; l <= c->L; ++l) c->stale[l] = gat ? nullptr : b.take<uint32_t>(nw);
+    for (int l = 1; l <= c->L; ++l) c->stale[l] = b.take<uint32_t>(nw);
     c->coarse = b.take<uint32_t>(NRT_COARSE_WORDS);
     c->coarse_shift = 0;
     while ((((n + ((int64_t)1 << c->coarse_shift) - 1) >> c->coarse_shift) + 31) / 32 > NRT_COARSE_WORDS) ++c->coarse_shift;
@@ -700,11 +700,11 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
 // GAT layer l: z = x W on the listed rows (null: all), attention scalars, then the attention gather + output
 // `listed`: only the rows of src_rows / dst_rows are touched; `incremental`: Algorithm 3 on top of that (old z and
 // attention scalars kept, terms exchanged), else every listed destination is recomputed over its whole in-list
-static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
-                                const int32_t* dst_rows, const uint64_t* n_dst_dev, int64_t dst_bound, bool listed,
-                                bool incremental, int prev, float* out_rows, int64_t out_cap, hipStream_t s) {
+// GAT, layer l: z = h^{l-1} W and the attention scalars of the listed rows (null: all rows); with `incremental` the
+// rows they replace are kept compact (old z in DP[0], old scalars in AS_old) for Algorithm 3's exchange
+static nrt_status run_gat_project(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
+                                  bool listed, bool incremental, GatArgs* out_args, hipStream_t s) {
     nrt_graph* g = c->g;
-    const bool last = l == c->L;
     GemmArgs z;
     memset(&z, 0, sizeof(z));
     z.M = listed ? src_bound : g->n;
@@ -735,6 +735,17 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
     a.rows_bound = src_bound;
     a.AS_old = incremental ? c->AS_old : nullptr;
     NRT_TRY(k_gat_scalars(a, s));
+    if (out_args) *out_args = a;
+    return NRT_OK;
+}
+
+static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
+                                const int32_t* dst_rows, const uint64_t* n_dst_dev, int64_t dst_bound, bool listed,
+                                bool incremental, int prev, float* out_rows, int64_t out_cap, hipStream_t s) {
+    nrt_graph* g = c->g;
+    const bool last = l == c->L;
+    GatArgs a;
+    NRT_TRY(run_gat_project(c, l, src_rows, n_src_dev, src_bound, listed, incremental, &a, s));
     NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
     a.rows = dst_rows;
     a.n_rows_dev = n_dst_dev;
@@ -800,16 +811,13 @@ static nrt_status run_update_unkept(nrt_cache* c, int l, const int32_t* rows, in
     return k_gemm(a, s);
 }
 
-// One A-GNN or G-GCN layer: norms (G-GCN: the two projections) of the changed rows of h^{l-1} (src_rows null: all rows), the gather over the
-// destinations described by c->recs (listed in `rows`, null: all n), the sums of long in-lists, the dense update.
-static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
-                                 const int32_t* rows, const uint64_t* M_dev, int64_t M, bool incremental, int prev, int cur,
-                                 float* out_rows, int64_t out_cap, hipStream_t s) {
+// A-GNN / G-GCN, layer l: what the messages need of the rows of h^{l-1} that changed (src_rows null: all rows): their
+// inverse norms, or for G-GCN the two projections W_1 h and W_2 h; with `incremental` the replaced values are kept compact
+static nrt_status run_agnn_project(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
+                                   bool incremental, hipStream_t s) {
     nrt_graph* g = c->g;
-    const bool last = l == c->L;
     const int D = c->dims[l - 1];
-    const bool gate = c->kind == NRT_GGCN;
-    if (gate) {                                   // the two projections of the rows of h^{l-1} that changed
+    if (c->kind == NRT_GGCN) {
         GemmArgs p;
         memset(&p, 0, sizeof(p));
         p.M = src_rows ? src_bound : g->n;
@@ -829,11 +837,22 @@ static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, c
         p.Wt = c->W2t[l - 1];
         p.H = c->P2[l - 1];
         p.DP = nullptr;
-        NRT_TRY(k_gemm(p, s));
-    } else {
-        NRT_TRY(k_agnn_norms(src_rows, n_src_dev, src_rows ? src_bound : g->n, c->H[l - 1], D, c->R[l - 1],
-                             (incremental && src_rows) ? c->r_old : nullptr, s));
+        return k_gemm(p, s);
     }
+    return k_agnn_norms(src_rows, n_src_dev, src_rows ? src_bound : g->n, c->H[l - 1], D, c->R[l - 1],
+                        (incremental && src_rows) ? c->r_old : nullptr, s);
+}
+
+// One A-GNN or G-GCN layer: norms (G-GCN: the two projections) of the changed rows of h^{l-1} (src_rows null: all rows), the gather over the
+// destinations described by c->recs (listed in `rows`, null: all n), the sums of long in-lists, the dense update.
+static nrt_status run_agnn_layer(nrt_cache* c, int l, const int32_t* src_rows, const uint64_t* n_src_dev, int64_t src_bound,
+                                 const int32_t* rows, const uint64_t* M_dev, int64_t M, bool incremental, int prev, int cur,
+                                 float* out_rows, int64_t out_cap, hipStream_t s) {
+    nrt_graph* g = c->g;
+    const bool last = l == c->L;
+    const int D = c->dims[l - 1];
+    const bool gate = c->kind == NRT_GGCN;
+    NRT_TRY(run_agnn_project(c, l, src_rows, n_src_dev, src_bound, incremental, s));
     NRT_TRY(prof_mark(c, TAG_ITEMS, l, s));
     AgnnArgs a;
     memset(&a, 0, sizeof(a));
@@ -1228,8 +1247,14 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
                           g->scan_tmp_len, &c->lc[l].count, s));
         if (c->lazy) {                                     // on-demand mode: A_l only becomes stale
-            if (has_message_cache(c->kind) && l == 1)      // h^0 is never stale, so neither may its message rows be
+            // h^0 is never stale, so neither may be what layer 1 caches of it by vertex: message rows, z and the
+            // attention scalars, inverse norms, gate projections
+            if (has_message_cache(c->kind) && l == 1)
                 NRT_TRY(run_transform(c, 0, c->list[0], src_bound, &c->lc[0].count, nullptr, false, s));
+            if (c->kind == NRT_GAT && l == 1)
+                NRT_TRY(run_gat_project(c, 1, c->list[0], &c->lc[0].count, src_bound, true, false, nullptr, s));
+            if (agnn_family(c->kind) && l == 1)
+                NRT_TRY(run_agnn_project(c, 1, c->list[0], &c->lc[0].count, src_bound, false, s));
             NRT_TRY(k_or_words(c->stale[l], c->stale[l], c->bm[cur], (n + 31) / 32, s));
             prev = cur;
             continue;
@@ -1358,6 +1383,20 @@ static nrt_status recompute_listed(nrt_cache* c, hipStream_t s) {
     const int64_t n = g->n;
     for (int l = 1; l <= c->L; ++l) {
         NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, nullptr, s));
+        if (c->kind == NRT_GAT || agnn_family(c->kind)) {
+            // constrained models (Section III-D): the rows of h^{l-1} brought up to date one layer below are re-projected
+            // (layer 1 reads h^0, whose projections every batch keeps current), then the listed destinations are summed
+            // over their whole in-neighbourhoods
+            const int64_t sb = l == 1 ? 0 : n;
+            if (c->kind == NRT_GAT)
+                NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, sb, c->list[l], &c->lc[l].count, n, true, false,
+                                      0, nullptr, 0, s));
+            else
+                NRT_TRY(run_agnn_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, sb, c->list[l], &c->lc[l].count, n, false, 0, 0,
+                                       nullptr, 0, s));
+            NRT_TRY(k_clear_listed_bits(c->stale[l], c->list[l], &c->lc[l].count, n, s));
+            continue;
+        }
         NRT_TRY(run_gather(c, l, false, 0, false, 0, s));
         NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, false, 0, nullptr, 0, false, s));
         if (has_message_cache(c->kind) && l < c->L)        // message rows follow every h row that is brought up to date
@@ -1386,8 +1425,8 @@ static nrt_status finish_recompute(nrt_cache* c, int64_t* n_recomputed, hipStrea
 
 extern "C" nrt_status nrt_set_lazy(nrt_cache* c, int32_t on, void* stream) {
     REQUIRE(c, "null argument");
-    if (c->kind == NRT_GAT || agnn_family(c->kind) || c->agg_only) {
-        nrt_set_error("on-demand mode is not available for GAT, A-GNN, G-GCN and aggregate-only storage");
+    if (c->agg_only) {
+        nrt_set_error("on-demand mode is not available with aggregate-only storage");
         return NRT_ERR_UNSUPPORTED;
     }
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -71,7 +71,7 @@ def test_random_case(S, oracle, seed):
     lazy = False
     for k in range(int(rng.integers(2, 5))):
         ses.mode(int(rng.choice([0, 1, 2, 3, 3])))
-        if kind not in CONSTRAINED and rng.random() < 0.3:
+        if rng.random() < 0.3:
             lazy = not lazy
             ses.lazy(lazy)                                       # switching it off brings every stale vertex up to date
         big = n >= 2000 and e >= 30000 and rng.random() < 0.3
