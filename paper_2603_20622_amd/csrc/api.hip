@@ -97,8 +97,10 @@ struct nrt_cache {
     BatchScratch sc;
     unsigned long long* pair_ctr;
     int32_t* pull_list;        // [n] second-pass queue of the pull-direction expansion
-    uint32_t* coarse;          // coarse changed-source filter of the current layer
+    uint32_t* coarse[2];       // coarse copies of the sets bm[0], bm[1] (the sparse gather's LDS filter), written by the compaction
     int coarse_shift, coarse_words;
+    uint64_t* cmp_state;       // look-back cells of the single-pass compaction
+    int64_t cmp_state_len;
     // profiling
     int profiling;
     hipEvent_t ev[MAX_EVENTS];
@@ -463,7 +465,10 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->pair_ctr = b.take<unsigned long long>(1024 * NRT_MAX_LAYERS);
     c->pull_list = b.take<int32_t>(n);
     for (int l = 1; l <= c->L; ++l) c->stale[l] = b.take<uint32_t>(nw);
-    c->coarse = b.take<uint32_t>(NRT_COARSE_WORDS);
+    c->coarse[0] = b.take<uint32_t>(NRT_COARSE_WORDS);
+    c->coarse[1] = b.take<uint32_t>(NRT_COARSE_WORDS);
+    c->cmp_state_len = cdiv(nw, 1024) + 8;
+    c->cmp_state = b.take<uint64_t>(c->cmp_state_len);
     c->coarse_shift = 0;
     while ((((n + ((int64_t)1 << c->coarse_shift) - 1) >> c->coarse_shift) + 31) / 32 > NRT_COARSE_WORDS) ++c->coarse_shift;
     c->coarse_words = (int)((((n + ((int64_t)1 << c->coarse_shift) - 1) >> c->coarse_shift) + 31) / 32);
@@ -585,10 +590,11 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
         a.Pfull = payload_rows(c, l - 1);
         a.full_scale_gcn = c->kind == NRT_GCN;
         a.sparse_ok = (sparse_hint == 2 && a.D > 256) ? 1 : sparse_hint;    // rows wider than 256 floats: pipelined kernel only
-        a.coarse = c->coarse;
+        a.coarse = c->coarse[prev];                  // written by the compaction that produced bm[prev]
         a.coarse_shift = c->coarse_shift;
         a.coarse_words = c->coarse_words;
-        NRT_TRY(k_coarse_bitmap(c->bm[prev], g->n, c->coarse_shift, c->coarse, c->coarse_words, s));
+        if (c->coarse_shift > 10)                    // beyond 200M vertices a coarse word spans several compaction workgroups
+            NRT_TRY(k_coarse_bitmap(c->bm[prev], g->n, c->coarse_shift, c->coarse[prev], c->coarse_words, s));
         if (may_recompute) {                     // the device counters pick one of the two (GatherArgs::auto_role)
             a.auto_role = 1;
             a.auto_src_dev = &c->lc[l - 1].count;
@@ -977,6 +983,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         NRT_TRY(k_fill_u32((uint32_t*)c->sc.feat_stamp, n, 0, s));
         NRT_TRY(k_fill_u32((uint32_t*)c->flags, (n + 64) / 4, 0, s));
         NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
+        NRT_TRY(k_fill_u64(c->cmp_state, c->cmp_state_len, 0, s));
         for (int l = 0; l < c->L; ++l) {
             const int kin = c->kind == NRT_MONET ? c->monet_J : (concat_self(c->kind) ? 2 : 1) * c->dims[l];
             NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
@@ -1112,6 +1119,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         p.count = n_slots_dev;
         p.off64 = c->plan_off64; p.cursor = c->plan_cursor; p.tmp = c->plan_tmp;
         p.total = (uint64_t*)(g->dev_ctrs + CTR_PLAN_TOTAL);
+        p.cmp_state = c->cmp_state; p.cmp_state_len = c->cmp_state_len;
         NRT_TRY(k_batch_plan(p, c->plan_scan, c->plan_scan_len, s));
     }
     c->sc.plan_slot_of = c->slot_dd;
@@ -1208,8 +1216,14 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
 
     // ---- sources of change for layer 1 (replaced features; for GCN also the re-normalised destinations)
     const int64_t n0_bound = b->n_feat + (gcn ? b->n_ins + b->n_del : 0);
-    NRT_TRY(k_compact(nullptr, c->bm_feat, gcn ? c->bm_ddst : nullptr, c->bm[0], n, c->list[0], c->slot[0], g->scan_tmp,
-                      g->scan_tmp_len, &c->lc[0].count, s));
+    CompactExtra cx;
+    memset(&cx, 0, sizeof(cx));
+    cx.err = &c->lc[0].pad[0];
+    cx.coarse_shift = c->coarse_shift;
+    cx.coarse_words = c->coarse_words;
+    cx.coarse = c->coarse_shift <= 10 ? c->coarse[0] : nullptr;
+    NRT_TRY(k_compact(nullptr, c->bm_feat, gcn ? c->bm_ddst : nullptr, c->bm[0], n, c->list[0], c->slot[0], c->cmp_state,
+                      c->cmp_state_len, &c->lc[0].count, s, nullptr, &cx));
     {
         DeltaArgs da;
         memset(&da, 0, sizeof(da));
@@ -1244,8 +1258,11 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(k_expand_frontier(g->out, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->flags, &c->lc[l - 1],
                                   c->xhub_list, c->xhub_cap, g->in, pull, s));
         NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
-        NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], g->scan_tmp,
-                          g->scan_tmp_len, &c->lc[l].count, s));
+        cx.coarse = c->coarse_shift <= 10 ? c->coarse[cur] : nullptr;
+        cx.list2 = l == c->L ? affected_ids : nullptr;              // the last set is also the caller's list
+        cx.cap2 = capacity;
+        NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], c->cmp_state,
+                          c->cmp_state_len, &c->lc[l].count, s, nullptr, &cx));
         if (c->lazy) {                                     // on-demand mode: A_l only becomes stale
             // h^0 is never stale, so neither may be what layer 1 caches of it by vertex: message rows, z and the
             // attention scalars, inverse norms, gate projections
@@ -1304,12 +1321,12 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             NRT_TRY(k_gather_rows(affected_rows, c->H[c->L], c->list[c->L], &c->lc[c->L].count, capacity, n, c->dims[c->L], s));
         NRT_TRY(prof_mark(c, TAG_UPDATE, c->L, s));
     }
-    NRT_TRY(k_copy_counted_i32(affected_ids, c->list[c->L], &c->lc[c->L].count, capacity, n, s));
     HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
     if (c->profiling)
         HIP_TRY(hipMemcpyAsync(c->pair_host, c->pair_ctr, 1024 * NRT_MAX_LAYERS * sizeof(unsigned long long),
                                hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
+    if (c->lc_host[0].pad[0]) { nrt_set_error("internal: a compaction wait gave up"); return NRT_ERR_DEVICE; }
     for (int l = 0; l <= c->L; ++l) c->n_list[l] = (int64_t)c->lc_host[l].count;
     c->have_history = true;
     for (int l = 1; l <= c->L; ++l) {
@@ -1435,7 +1452,7 @@ extern "C" nrt_status nrt_set_lazy(nrt_cache* c, int32_t on, void* stream) {
         const int64_t n = g->n;
         NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
         for (int l = 1; l <= c->L; ++l)
-            NRT_TRY(k_compact(nullptr, c->stale[l], nullptr, c->bm[0], n, c->list[l], nullptr, g->scan_tmp, g->scan_tmp_len,
+            NRT_TRY(k_compact(nullptr, c->stale[l], nullptr, c->bm[0], n, c->list[l], nullptr, c->cmp_state, c->cmp_state_len,
                               &c->lc[l].count, s));
         NRT_TRY(recompute_listed(c, s));
         NRT_TRY(finish_recompute(c, nullptr, s));
@@ -1462,7 +1479,7 @@ extern "C" nrt_status nrt_query(nrt_cache* c, const int32_t* query_ids, int64_t 
         NRT_TRY(k_fill_u32(c->bm_feat, nw, 0, s));
         NRT_TRY(k_mark_ids(c->bm_feat, query_ids, n_query, n, (int32_t*)&spare->in_edges[0], s));
         int cur = 0;
-        NRT_TRY(k_compact(nullptr, c->bm_feat, nullptr, c->bm[cur], n, c->list[c->L], nullptr, g->scan_tmp, g->scan_tmp_len,
+        NRT_TRY(k_compact(nullptr, c->bm_feat, nullptr, c->bm[cur], n, c->list[c->L], nullptr, c->cmp_state, c->cmp_state_len,
                           &c->lc[c->L].count, s, c->stale[c->L]));
         PullArgs no_pull;
         memset(&no_pull, 0, sizeof(no_pull));
@@ -1470,8 +1487,8 @@ extern "C" nrt_status nrt_query(nrt_cache* c, const int32_t* query_ids, int64_t 
             // the in-lists play the part of out-lists: flags[u] = 1 for every in-neighbour u of need_l
             NRT_TRY(k_expand_frontier(g->in, c->list[l], &c->lc[l].count, n, c->flags, &c->lc[l], c->xhub_list, c->xhub_cap,
                                       g->out, no_pull, s));
-            NRT_TRY(k_compact(c->flags, c->bm[cur], nullptr, c->bm[1 - cur], n, c->list[l - 1], nullptr, g->scan_tmp,
-                              g->scan_tmp_len, &c->lc[l - 1].count, s, c->stale[l - 1]));
+            NRT_TRY(k_compact(c->flags, c->bm[cur], nullptr, c->bm[1 - cur], n, c->list[l - 1], nullptr, c->cmp_state,
+                              c->cmp_state_len, &c->lc[l - 1].count, s, c->stale[l - 1]));
             cur = 1 - cur;
         }
         NRT_TRY(recompute_listed(c, s));

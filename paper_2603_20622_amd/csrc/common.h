@@ -114,13 +114,20 @@ nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_
 // bm_a |= ids of a0 and a1, bm_b |= ids of b0, one launch; ids outside [0, n) are skipped
 nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
                         const int32_t* b0, int64_t nb0, int64_t n, hipStream_t s);
-// Compaction of a vertex set into a sorted id list.  The set is the union of the byte flags (one byte per vertex,
-// may be null; they are cleared on the way), and up to two bitmaps or_a, or_b (may be null), intersected with
-// and_mask when given.  Writes the set as bitmap `out_bm`, its sorted ids to `list`, slot[id] = position (slot may
-// be null), *count = size.
+// Compaction of a vertex set into a sorted id list, in one launch.  The set is the union of the byte flags (one byte
+// per vertex, may be null; they are cleared on the way), and up to two bitmaps or_a, or_b (may be null), intersected
+// with and_mask when given.  Writes the set as bitmap `out_bm`, its sorted ids to `list`, slot[id] = position (slot
+// may be null), *count = size.  `state` (state_len >= n / 32768 + 3 cells, zero before its first use, used by nothing
+// else) carries the look-back of the workgroups from call to call.
+struct CompactExtra {
+    int32_t* list2; int64_t cap2;     // second copy of the first cap2 ids (the caller's output buffer), or null
+    uint32_t* coarse;                 // coarse copy of the set for the sparse gather's LDS filter, or null
+    int coarse_shift; int64_t coarse_words;
+    uint64_t* err;                    // raised if a look-back wait gave up (device), or null
+};
 nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm, int64_t n,
-                     int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s,
-                     const uint32_t* and_mask = nullptr);
+                     int32_t* list, int32_t* slot, uint64_t* state, int64_t state_len, uint64_t* count, hipStream_t s,
+                     const uint32_t* and_mask = nullptr, const CompactExtra* extra = nullptr);
 // dst[i][:] = src[ids[i]][:] for i < n_ids (host count); an id outside [0, n) reads row 0
 nrt_status k_gather_rows_checked(float* dst, const float* src, const int32_t* ids, int64_t n_ids, int64_t n, int D,
                                  hipStream_t s);
@@ -231,6 +238,7 @@ struct PlanArgs {   // the batch's edge updates grouped by destination in a fixe
     int32_t* cursor;               // [updates]
     int32_t* tmp;                  // [updates]
     uint64_t* total;               // device: updates that entered the plan
+    uint64_t* cmp_state; int64_t cmp_state_len;   // look-back cells of the compaction (k_compact)
 };
 nrt_status k_batch_plan(const PlanArgs& a, uint64_t* scan_tmp, int64_t scan_tmp_len, hipStream_t s);
 

@@ -204,7 +204,7 @@ nrt_status k_batch_plan(const PlanArgs& a, uint64_t* scan_tmp, int64_t scan_tmp_
         return NRT_OK;
     }
     // slots from the bitmap of destinations (sorted list, vertex -> slot), then count / scan / fill / rank
-    NRT_TRY(k_compact(nullptr, a.dst_bitmap, nullptr, a.scratch_bm, a.n, a.list, a.slot_of, scan_tmp, scan_tmp_len, a.count, s));
+    NRT_TRY(k_compact(nullptr, a.dst_bitmap, nullptr, a.scratch_bm, a.n, a.list, a.slot_of, a.cmp_state, a.cmp_state_len, a.count, s));
     const int grid = (int)cdiv(nops, 256);
     plan_count_kernel<<<grid, 256, 0, s>>>(a);
     LAUNCH_CHECK();

@@ -174,26 +174,6 @@ __device__ inline uint32_t pack_flags(uint8_t* flags, int64_t w, int64_t n) {
     }
     return bits;
 }
-__global__ void set_count_kernel(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, const uint32_t* and_mask,
-                                 uint32_t* out_bm, int64_t n, int64_t nw, uint64_t* tmp) {
-    const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
-    uint64_t s = 0;
-#pragma unroll
-    for (int j = 0; j < EPT; ++j) {
-        const int64_t w = base + j;
-        if (w < nw) {
-            uint32_t bits = flags ? pack_flags(flags, w, n) : 0u;
-            if (or_a) bits |= or_a[w];
-            if (or_b) bits |= or_b[w];
-            if (and_mask) bits &= and_mask[w];
-            out_bm[w] = bits;
-            s += __popc(bits);
-        }
-    }
-    uint64_t tot;
-    block_excl_scan(s, &tot);
-    if (threadIdx.x == 0) tmp[blockIdx.x] = tot;
-}
 // bm |= ids (ids outside [0, n) raise *bad instead)
 __global__ void mark_ids_kernel(uint32_t* bm, const int32_t* ids, int64_t n_ids, int64_t n, int32_t* bad) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -212,27 +192,135 @@ __global__ void clear_listed_bits_kernel(uint32_t* bm, const int32_t* list, cons
         atomicAnd(&bm[v >> 5], ~(1u << (v & 31)));
     }
 }
-__global__ void bm_emit_kernel(const uint32_t* bm, int64_t nw, const uint64_t* tmp, int32_t* list, int32_t* slot) {
-    const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
+// Single-pass compaction.  A workgroup takes a ticket (so that every workgroup with a smaller ticket is already
+// running), builds its 1024 words of the set and counts them, publishes the count, finds the number of set bits in
+// front of it by looking back over its predecessors' published counts and running totals (one 64-bit cell per
+// workgroup: status, call number, value; a cell of an earlier call reads as "not there yet", so nothing is cleared
+// between calls), and emits its ids.  Layout of `state`: [0] ticket counter, [1] number of the last finished call,
+// [2 + t] the cell of ticket t.  Every wait is on a workgroup that already runs and publishes before it waits itself;
+// as a last resort a wait gives up after about a million polls and raises *err.
+constexpr uint64_t CS_AGG = 1ULL << 62, CS_PREFIX = 2ULL << 62, CS_STATUS = 3ULL << 62, CS_VALUE = (1ULL << 40) - 1;
+constexpr int CS_SPIN_LIMIT = 1 << 20;
+struct CompactArgs {
+    uint8_t* flags; const uint32_t *or_a, *or_b, *and_mask;
+    uint32_t* out_bm; int64_t n, nw, nb;
+    int32_t *list, *slot;
+    unsigned long long* state; uint64_t* count;
+    CompactExtra x;
+};
+__global__ void __launch_bounds__(TPB) compact_kernel(CompactArgs a) {
+    __shared__ uint64_t s_excl;
+    __shared__ uint32_t s_words[EPB];
+    __shared__ int64_t s_ticket;
+    __shared__ uint32_t s_call;
+    const int tid = threadIdx.x, lane = tid & 63;
+    if (tid == 0) {
+        // acquire: the ticket below must not be taken before this value has arrived (the last ticket's workgroup rewrites it)
+        s_call = ((uint32_t)__hip_atomic_load(&a.state[1], __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT) + 1u) & 0x3fffffu;
+        s_ticket = (int64_t)atomicAdd(&a.state[0], 1ULL);
+    }
+    __syncthreads();
+    const int64_t t = s_ticket;
+    const uint64_t call_tag = (uint64_t)s_call << 40;
+    const int64_t base = t * EPB + (int64_t)tid * EPT;
     uint32_t w[EPT];
-    uint64_t s = 0;
+    uint64_t cnt = 0;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-        w[j] = base + j < nw ? bm[base + j] : 0u;
-        s += __popc(w[j]);
+        const int64_t wi = base + j;
+        uint32_t bits = 0;
+        if (wi < a.nw) {
+            bits = a.flags ? pack_flags(a.flags, wi, a.n) : 0u;
+            if (a.or_a) bits |= a.or_a[wi];
+            if (a.or_b) bits |= a.or_b[wi];
+            if (a.and_mask) bits &= a.and_mask[wi];
+            a.out_bm[wi] = bits;
+        }
+        w[j] = bits;
+        s_words[tid * EPT + j] = bits;
+        cnt += __popc(bits);
     }
     uint64_t tot;
-    uint64_t pos = block_excl_scan(s, &tot) + tmp[blockIdx.x];
+    const uint64_t ex = block_excl_scan(cnt, &tot);
+    if (tid < 64) {
+        unsigned long long* cell = &a.state[2 + t];
+        uint64_t excl = 0;
+        if (t == 0) {
+            if (lane == 0) __hip_atomic_store(cell, CS_PREFIX | call_tag | tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            if (lane == 0) __hip_atomic_store(cell, CS_AGG | call_tag | tot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            int64_t look = t - 1;                       // lane i looks at ticket look - i
+            bool failed = false;
+            while (true) {
+                const int64_t p = look - lane;
+                uint64_t cellv = CS_PREFIX | call_tag;  // in front of ticket 0: a running total of 0
+                int spins = 0;
+                if (p >= 0) {
+                    while (true) {
+                        cellv = __hip_atomic_load(&a.state[2 + p], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        if ((cellv & CS_STATUS) != 0 && (cellv & ~(CS_STATUS | CS_VALUE)) == call_tag) break;
+                        if (++spins > CS_SPIN_LIMIT) { failed = true; cellv = CS_PREFIX | call_tag; break; }
+                        __builtin_amdgcn_s_sleep(2);
+                    }
+                }
+                const unsigned long long has_prefix = __ballot((cellv & CS_STATUS) == CS_PREFIX);
+                const int first = has_prefix ? __ffsll((long long)has_prefix) - 1 : 64;     // nearest predecessor with a running total
+                uint64_t v = lane <= first ? (cellv & CS_VALUE) : 0;
+#pragma unroll
+                for (int sft = 32; sft >= 1; sft >>= 1) v += __shfl_xor((unsigned long long)v, sft, 64);
+                excl += v;
+                if (has_prefix) break;
+                look -= 64;
+            }
+            if (__ballot(failed) && lane == 0 && a.x.err) *a.x.err = 1;
+            if (lane == 0) __hip_atomic_store(cell, CS_PREFIX | call_tag | ((excl + tot) & CS_VALUE), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        if (lane == 0) {
+            s_excl = excl;
+            if (t == a.nb - 1) {        // every other workgroup has read the call number and taken its ticket by now
+                *a.count = excl + tot;
+                __hip_atomic_store(&a.state[1], (unsigned long long)s_call, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(&a.state[0], 0ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    __syncthreads();
+    uint64_t pos = s_excl + ex;
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
         uint32_t bits = w[j];
         while (bits) {
-            int b = __ffs(bits) - 1;
+            const int b = __ffs(bits) - 1;
             bits &= bits - 1;
-            int32_t v = (int32_t)((base + j) * 32 + b);
-            list[pos] = v;
-            if (slot) slot[v] = (int32_t)pos;
+            const int32_t v = (int32_t)((base + j) * 32 + b);
+            a.list[pos] = v;
+            if (a.slot) a.slot[v] = (int32_t)pos;
+            if (a.x.list2 && (int64_t)pos < a.x.cap2) a.x.list2[pos] = v;
             ++pos;
+        }
+    }
+    // coarse copy of the set: bit i covers vertices [i << shift, (i + 1) << shift); the words of this workgroup cover
+    // 32768 consecutive vertices, i.e. whole coarse words as long as a coarse word spans at most that many
+    if (a.x.coarse) {
+        const int sh = a.x.coarse_shift;                         // at most 10 here
+        const int per_block = EPB >> sh;                         // coarse words of this workgroup (shift <= 5: EPB * (32 >> sh) / 32)
+        for (int cw = tid; cw < per_block; cw += TPB) {
+            uint32_t out = 0;
+            for (int i = 0; i < 32; ++i) {
+                const int v0 = (cw * 32 + i) << sh;              // first vertex of the bit's group, relative to the workgroup
+                uint32_t any = 0;
+                if (sh <= 5) {
+                    const uint32_t word = s_words[v0 >> 5];
+                    const uint32_t mask = sh == 5 ? 0xffffffffu : (((1u << (1 << sh)) - 1u) << (v0 & 31));
+                    any = word & mask;
+                } else {
+                    const int w0 = v0 >> 5, nwg = 1 << (sh - 5);
+                    for (int k = 0; k < nwg; ++k) any |= s_words[w0 + k];
+                }
+                if (any) out |= 1u << i;
+            }
+            const int64_t gcw = t * per_block + cw;
+            if (gcw < a.x.coarse_words) a.x.coarse[gcw] = out;
         }
     }
 }
@@ -389,15 +477,25 @@ nrt_status k_clear_listed_bits(uint32_t* bm, const int32_t* list, const uint64_t
     return NRT_OK;
 }
 nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm, int64_t n,
-                     int32_t* list, int32_t* slot, uint64_t* tmp, int64_t tmp_len, uint64_t* count, hipStream_t s,
-                     const uint32_t* and_mask) {
+                     int32_t* list, int32_t* slot, uint64_t* state, int64_t state_len, uint64_t* count, hipStream_t s,
+                     const uint32_t* and_mask, const CompactExtra* extra) {
     const int64_t nw = cdiv(n, 32);
     const int64_t nb = nw > 0 ? cdiv(nw, EPB) : 0;
-    if (nb > tmp_len) { nrt_set_error("scan scratch too small"); return NRT_ERR_INVALID_ARG; }
-    if (nb > 0) { set_count_kernel<<<(int)nb, TPB, 0, s>>>(flags, or_a, or_b, and_mask, out_bm, n, nw, tmp); LAUNCH_CHECK(); }
-    scan_top_kernel<<<1, TPB, 0, s>>>(tmp, nb, count);
+    if (nb + 2 > state_len) { nrt_set_error("compaction state too small"); return NRT_ERR_INVALID_ARG; }
+    if (nb <= 0) return k_fill_u64(count, 1, 0, s);
+    CompactArgs a;
+    memset(&a, 0, sizeof(a));
+    a.flags = flags; a.or_a = or_a; a.or_b = or_b; a.and_mask = and_mask;
+    a.out_bm = out_bm; a.n = n; a.nw = nw; a.nb = nb;
+    a.list = list; a.slot = slot;
+    a.state = (unsigned long long*)state; a.count = count;
+    if (extra) a.x = *extra;
+    if (a.x.coarse && a.x.coarse_shift > 10) {      // a coarse word would span several workgroups: built by its own kernel
+        nrt_set_error("internal: coarse shift beyond the compaction's reach");
+        return NRT_ERR_INVALID_ARG;
+    }
+    compact_kernel<<<(int)nb, TPB, 0, s>>>(a);
     LAUNCH_CHECK();
-    if (nb > 0) { bm_emit_kernel<<<(int)nb, TPB, 0, s>>>(out_bm, nw, tmp, list, slot); LAUNCH_CHECK(); }
     return NRT_OK;
 }
 
