@@ -3,6 +3,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -66,6 +67,7 @@ struct nrt_cache {
     LayerCtrs* lc_use;                  // counters the layer steps read instead of lc[l] (null: lc[l])
     int mode;                           // nrt_mode
     bool have_history;                  // n_list holds the set sizes of a previous batch (hints for kernel choice)
+    bool have_history_prev;             // while a batch runs: lc_host still holds the counters of the batch before it
     int lazy;                           // on-demand mode: batches only record what became stale
     uint32_t* stale[NRT_MAX_LAYERS + 1]; // per layer: vertices whose cached aggregate / embedding is out of date
     LayerCtrs* lc_host;                 // pinned mirror, followed by the mirror of pair_ctr (profiling)
@@ -467,7 +469,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     for (int l = 1; l <= c->L; ++l) c->stale[l] = b.take<uint32_t>(nw);
     c->coarse[0] = b.take<uint32_t>(NRT_COARSE_WORDS);
     c->coarse[1] = b.take<uint32_t>(NRT_COARSE_WORDS);
-    c->cmp_state_len = cdiv(nw, 1024) + 8;
+    c->cmp_state_len = cdiv(nw, 256) + 8;
     c->cmp_state = b.take<uint64_t>(c->cmp_state_len);
     c->coarse_shift = 0;
     while ((((n + ((int64_t)1 << c->coarse_shift) - 1) >> c->coarse_shift) + 31) / 32 > NRT_COARSE_WORDS) ++c->coarse_shift;
@@ -572,6 +574,10 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
     a.S = c->S[l];
     a.n_vertices = g->n;
     if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
+    if (c->have_history_prev && !c->lc_use) {    // what the previous batch had at this layer sizes the grids
+        a.units_hint = (int64_t)(c->lc_host[l].count + c->lc_host[l].n_items) + 1;
+        a.hubs_hint = (int64_t)c->lc_host[l].n_hubs;
+    }
     GatherArgs full = a;                         // full-neighbour aggregation from h^{l-1} (Eq. 1)
     full.P = payload_rows(c, l - 1);
     full.src_scale_gcn = c->kind == NRT_GCN;
@@ -1071,6 +1077,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     for (int l = 0; l <= c->L; ++l) { prev_n_list[l] = c->n_list[l]; c->n_list[l] = 0; }
     const bool had_history = c->have_history;
     c->have_history = false;
+    c->have_history_prev = had_history;
     NRT_TRY(prof_mark(c, TAG_START, 0, s));
 
     // ---- validate (no state change yet)
@@ -1086,6 +1093,8 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             f.add(c->plan_off64, 2 * (b->n_ins + b->n_del + 1));
             f.add(c->plan_cursor, b->n_ins + b->n_del);
         }
+        c->sc.bm_dst = c->bm_ddst;                            // the batch's sets are marked by the validation kernels
+        c->sc.bm_feat = c->bm_feat;
         NRT_TRY(graph_validate_batch(g, b, c->sc, &f, s));
     }
     // The verdict travels to the host while the device goes on with work that touches only per-batch scratch and
@@ -1102,7 +1111,6 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     bool may_rec[NRT_MAX_LAYERS + 2];
     for (int l = 0; l <= c->L + 1; ++l)
         may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && !agnn_family(c->kind) && !c->agg_only && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
-    if (!empty_batch) NRT_TRY(k_mark_batch(c->bm_ddst, b->ins_dst, b->n_ins, b->del_dst, b->n_del, c->bm_feat, b->feat_ids, b->n_feat, n, s));
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     uint64_t* n_slots_dev = (uint64_t*)(g->dev_ctrs + CTR_COUNT);
     if (b->n_ins + b->n_del > 0) {
@@ -1398,6 +1406,7 @@ extern "C" nrt_status nrt_get_layer_affected(const nrt_cache* c, int32_t layer, 
 static nrt_status recompute_listed(nrt_cache* c, hipStream_t s) {
     nrt_graph* g = c->g;
     const int64_t n = g->n;
+    c->have_history_prev = false;            // the sizes of a query say nothing about the last batch's (no grid hints)
     for (int l = 1; l <= c->L; ++l) {
         NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, nullptr, s));
         if (c->kind == NRT_GAT || agnn_family(c->kind)) {

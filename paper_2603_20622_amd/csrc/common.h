@@ -111,13 +111,10 @@ nrt_status k_copy_f32(float* dst, const float* src, int64_t n, hipStream_t s);
 nrt_status k_copy_counted_i32(int32_t* dst, const int32_t* src, const uint64_t* count, int64_t cap, int64_t bound, hipStream_t s);
 // exclusive scan of n uint64 values in place; writes the total to *total (device)
 nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_t tmp_len, uint64_t* total, hipStream_t s);
-// bm_a |= ids of a0 and a1, bm_b |= ids of b0, one launch; ids outside [0, n) are skipped
-nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
-                        const int32_t* b0, int64_t nb0, int64_t n, hipStream_t s);
 // Compaction of a vertex set into a sorted id list, in one launch.  The set is the union of the byte flags (one byte
 // per vertex, may be null; they are cleared on the way), and up to two bitmaps or_a, or_b (may be null), intersected
 // with and_mask when given.  Writes the set as bitmap `out_bm`, its sorted ids to `list`, slot[id] = position (slot
-// may be null), *count = size.  `state` (state_len >= n / 32768 + 3 cells, zero before its first use, used by nothing
+// may be null), *count = size.  `state` (state_len >= n / 8192 + 3 cells, zero before its first use, used by nothing
 // else) carries the look-back of the workgroups from call to call.
 struct CompactExtra {
     int32_t* list2; int64_t cap2;     // second copy of the first cap2 ids (the caller's output buffer), or null
@@ -208,6 +205,10 @@ struct GatherArgs {
     // auto_role 2: this launch recomputes and runs only then; 0: no test.  auto_src_dev: the changed-source count.
     int auto_role;
     const uint64_t* auto_src_dev;
+    // What the previous batch had at this layer (0: unknown).  The kernels stride over their work with whatever grid they
+    // get; on small layers a grid sized to the expected work saves the time a large one takes merely to start and exit.
+    int64_t units_hint;        // destinations + hub items
+    int64_t hubs_hint;         // destinations with long in-lists
     const uint32_t* coarse;    // coarse copy of src_bitmap: bit i covers vertices [i << coarse_shift, (i+1) << coarse_shift)
     int coarse_shift;
     int coarse_words;          // at most NRT_COARSE_WORDS
@@ -423,6 +424,9 @@ struct BatchScratch {
     int32_t* err;                               // device error flags [8] (inside the counter block)
     int32_t* feat_index;                        // [N] position of a vertex in the batch's feature list
     int32_t* feat_stamp;                        // [N] epoch stamps that detect repeated feature ids
+    // the sets of the batch, marked while it is validated (both cleared by the validation's fill launch; null: not wanted)
+    uint32_t* bm_dst;                           // destinations of the edge updates
+    uint32_t* bm_feat;                          // vertices whose feature row is replaced
     // from the batch plan: where an inserted in-edge goes in its destination's list (reproducible list order)
     const int32_t* plan_slot_of;                // [N] vertex -> plan slot
     const int32_t* plan_ins_cnt;                // [slots] inserts per destination

@@ -853,13 +853,20 @@ nrt_status k_dst_records(const int32_t* list, int64_t bound, const Adj& in, DstR
 
 template <int LPR, int NV>
 static void launch_gather(const GatherArgs& a, hipStream_t s) {
-    const int nb = 8192;                        // a fixed grid strides over the work; sizes are read on the device
+    // a fixed grid strides over the work (sizes are read on the device); sized to the previous batch's work when known
+    int nb = 8192, sp_blocks = SP_BLOCKS;
+    if (a.units_hint > 0) {
+        const int64_t want = cdiv(a.units_hint + a.units_hint / 4 + 64, WAVES_PER_BLOCK);
+        nb = (int)(want < 128 ? 128 : (want > 8192 ? 8192 : want));
+        const int64_t want_sp = cdiv(a.units_hint + a.units_hint / 4 + 64, 4 * SP_WAVES);
+        sp_blocks = (int)(want_sp < 64 ? 64 : (want_sp > SP_BLOCKS ? SP_BLOCKS : want_sp));
+    }
     const int threads = WAVES_PER_BLOCK * 64;
     const bool filter = a.src_bitmap != nullptr;
     const bool coef = a.use_weights || a.src_scale_gcn;
     if (NV == 1 && a.sparse_ok == 2) {
-        if (coef) gather_sparse_kernel<LPR, true><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
-        else gather_sparse_kernel<LPR, false><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
+        if (coef) gather_sparse_kernel<LPR, true><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
+        else gather_sparse_kernel<LPR, false><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
         return;
     }
     if (filter && coef) gather_kernel<LPR, NV, true, true><<<nb, threads, 0, s>>>(a);
@@ -868,8 +875,8 @@ static void launch_gather(const GatherArgs& a, hipStream_t s) {
     else gather_kernel<LPR, NV, false, false><<<nb, threads, 0, s>>>(a);
     if (NV == 1 && a.sparse_ok) {
         ++nrt_launch_count;                     // the second launch of this call
-        if (coef) gather_sparse_kernel<LPR, true><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
-        else gather_sparse_kernel<LPR, false><<<SP_BLOCKS, SP_WAVES * 64, 0, s>>>(a);
+        if (coef) gather_sparse_kernel<LPR, true><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
+        else gather_sparse_kernel<LPR, false><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
     }
 }
 
@@ -891,7 +898,12 @@ nrt_status k_coarse_bitmap(const uint32_t* fine, int64_t n, int shift, uint32_t*
 }
 
 nrt_status k_combine_partials(const GatherArgs& a, hipStream_t s) {
-    combine_kernel<<<2048, 256, 0, s>>>(a);
+    int nb = 2048;                              // one wave per hub, strided
+    if (a.units_hint > 0) {
+        const int64_t want = cdiv(a.hubs_hint + a.hubs_hint / 4 + 16, 4);
+        nb = (int)(want < 16 ? 16 : (want > 2048 ? 2048 : want));
+    }
+    combine_kernel<<<nb, 256, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }

@@ -206,6 +206,7 @@ struct ValArgs {
     float* del_w;
     int32_t* err;
     int32_t *inscnt0, *inscnt1, *delcnt0, *delcnt1;
+    uint32_t* bm_dst;          // set of the destinations of the batch's edge updates (cleared by the launch before), or null
 };
 
 // records the update in the batch's set of (src, dst) keys; a key met twice is a repeated entry
@@ -242,7 +243,10 @@ __device__ inline void validate_by_workgroup(const ValArgs& A, int64_t op, bool 
     const int32_t v = is_del ? A.del_dst[i] : A.ins_dst[i];
     if (u < 0 || u >= A.n || v < 0 || v >= A.n) { if (lead) A.err[0] = 1; return; }
     if (u == v) { if (lead) A.err[1] = 1; return; }
-    if (lead && with_key) note_key(A, u, v);
+    if (lead && with_key) {
+        note_key(A, u, v);
+        if (A.bm_dst) atomicOr(&A.bm_dst[v >> 5], 1u << (v & 31));
+    }
     if (is_del) {
         const int64_t po = find_in_list(A.out, u, v, s_pos);
         const int64_t pi = find_in_list(A.in, v, u, s_pos);
@@ -304,7 +308,10 @@ __global__ void __launch_bounds__(VAL_THREADS) validate_edges_packed_kernel(ValA
         } else if (u == v) {
             if (lane == 0) A.err[1] = 1;
         } else {
-            if (lane == 0) note_key(A, u, v);
+            if (lane == 0) {
+                note_key(A, u, v);
+                if (A.bm_dst) atomicOr(&A.bm_dst[v >> 5], 1u << (v & 31));
+            }
             const int32_t du = A.out.deg[u], dv = A.in.deg[v];
             if (is_del) {
                 if (du > WAVE_LIST_MAX || dv > WAVE_LIST_MAX) {
@@ -333,11 +340,12 @@ __global__ void __launch_bounds__(VAL_THREADS) validate_edges_packed_kernel(ValA
 }
 
 __global__ void validate_feats_kernel(int64_t n, int64_t n_feat, const int32_t* ids, int32_t* feat_index,
-                                      int32_t* feat_stamp, int32_t epoch, int32_t* err) {
+                                      int32_t* feat_stamp, int32_t epoch, int32_t* err, uint32_t* bm_feat) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n_feat) return;
     int32_t v = ids[i];
     if (v < 0 || v >= n) { err[0] = 1; return; }
+    if (bm_feat) atomicOr(&bm_feat[v >> 5], 1u << (v & 31));
     int32_t old = atomicMax(&feat_stamp[v], epoch);
     if (old >= epoch) { err[5] = 1; return; }
     feat_index[v] = (int32_t)i;
@@ -730,7 +738,7 @@ nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& 
     NRT_TRY(k_multi_fill(f, s));
     if (b->n_feat > 0) {
         validate_feats_kernel<<<(int)cdiv(b->n_feat, 256), 256, 0, s>>>(g->n, b->n_feat, b->feat_ids, sc.feat_index,
-                                                                       sc.feat_stamp, g->epoch, sc.err);
+                                                                       sc.feat_stamp, g->epoch, sc.err, sc.bm_feat);
         LAUNCH_CHECK();
     }
     if (nops == 0) return NRT_OK;
@@ -741,6 +749,7 @@ nrt_status graph_validate_batch(nrt_graph* g, const nrt_batch* b, BatchScratch& 
     va.hash = sc.hash_keys; va.hash_cap = sc.hash_cap;
     va.pos_out = sc.pos_out; va.pos_in = sc.pos_in; va.del_w = sc.del_w; va.err = sc.err;
     va.inscnt0 = g->inscnt[0]; va.inscnt1 = g->inscnt[1]; va.delcnt0 = g->delcnt[0]; va.delcnt1 = g->delcnt[1];
+    va.bm_dst = sc.bm_dst;
     if (nops > PACKED_MIN_OPS) validate_edges_packed_kernel<<<(unsigned)cdiv(nops, VAL_THREADS / 64), VAL_THREADS, 0, s>>>(va);
     else validate_edges_kernel<<<(unsigned)nops, VAL_THREADS, 0, s>>>(va);
     LAUNCH_CHECK();

@@ -95,19 +95,6 @@ __global__ void copy_u32_kernel(uint32_t* dst, const uint32_t* src, int64_t n) {
     for (; i < n; i += stride) dst[i] = src[i];
 }
 
-__global__ void mark_batch_kernel(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1,
-                                  uint32_t* bm_b, const int32_t* b0, int64_t nb0, int64_t n) {
-    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    uint32_t* bm = bm_a;
-    int32_t v;
-    if (i < na0) v = a0[i];
-    else if ((i -= na0) < na1) v = a1[i];
-    else if ((i -= na1) < nb0) { v = b0[i]; bm = bm_b; }
-    else return;
-    if (v < 0 || v >= n) return;          // runs before the batch's verdict is known: a bad id must not be dereferenced
-    atomicOr(&bm[v >> 5], 1u << (v & 31));
-}
-
 // ---- scan ----
 __global__ void scan_reduce_kernel(const uint64_t* data, int64_t n, uint64_t* tmp) {
     const int64_t base = (int64_t)blockIdx.x * EPB + (int64_t)threadIdx.x * EPT;
@@ -208,9 +195,13 @@ struct CompactArgs {
     unsigned long long* state; uint64_t* count;
     CompactExtra x;
 };
+// CEPT words per thread: 1 for sets over up to four million vertices (more, smaller workgroups: the ids of a word are
+// emitted one after the other by its thread), 4 beyond
+template <int CEPT>
 __global__ void __launch_bounds__(TPB) compact_kernel(CompactArgs a) {
+    constexpr int CEPB = TPB * CEPT;
     __shared__ uint64_t s_excl;
-    __shared__ uint32_t s_words[EPB];
+    __shared__ uint32_t s_words[CEPB];
     __shared__ int64_t s_ticket;
     __shared__ uint32_t s_call;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -222,11 +213,11 @@ __global__ void __launch_bounds__(TPB) compact_kernel(CompactArgs a) {
     __syncthreads();
     const int64_t t = s_ticket;
     const uint64_t call_tag = (uint64_t)s_call << 40;
-    const int64_t base = t * EPB + (int64_t)tid * EPT;
-    uint32_t w[EPT];
+    const int64_t base = t * CEPB + (int64_t)tid * CEPT;
+    uint32_t w[CEPT];
     uint64_t cnt = 0;
 #pragma unroll
-    for (int j = 0; j < EPT; ++j) {
+    for (int j = 0; j < CEPT; ++j) {
         const int64_t wi = base + j;
         uint32_t bits = 0;
         if (wi < a.nw) {
@@ -237,7 +228,7 @@ __global__ void __launch_bounds__(TPB) compact_kernel(CompactArgs a) {
             a.out_bm[wi] = bits;
         }
         w[j] = bits;
-        s_words[tid * EPT + j] = bits;
+        s_words[tid * CEPT + j] = bits;
         cnt += __popc(bits);
     }
     uint64_t tot;
@@ -287,7 +278,7 @@ __global__ void __launch_bounds__(TPB) compact_kernel(CompactArgs a) {
     __syncthreads();
     uint64_t pos = s_excl + ex;
 #pragma unroll
-    for (int j = 0; j < EPT; ++j) {
+    for (int j = 0; j < CEPT; ++j) {
         uint32_t bits = w[j];
         while (bits) {
             const int b = __ffs(bits) - 1;
@@ -300,10 +291,10 @@ __global__ void __launch_bounds__(TPB) compact_kernel(CompactArgs a) {
         }
     }
     // coarse copy of the set: bit i covers vertices [i << shift, (i + 1) << shift); the words of this workgroup cover
-    // 32768 consecutive vertices, i.e. whole coarse words as long as a coarse word spans at most that many
+    // 32 * CEPB consecutive vertices, i.e. whole coarse words as long as a coarse word spans at most that many
     if (a.x.coarse) {
-        const int sh = a.x.coarse_shift;                         // at most 10 here
-        const int per_block = EPB >> sh;                         // coarse words of this workgroup (shift <= 5: EPB * (32 >> sh) / 32)
+        const int sh = a.x.coarse_shift;                         // a coarse word spans at most this workgroup (checked by the host)
+        const int per_block = CEPB >> sh;                        // coarse words of this workgroup
         for (int cw = tid; cw < per_block; cw += TPB) {
             uint32_t out = 0;
             for (int i = 0; i < 32; ++i) {
@@ -445,15 +436,6 @@ nrt_status k_stream_read(float* b, const float* a, int64_t n_floats, hipStream_t
     return NRT_OK;
 }
 
-nrt_status k_mark_batch(uint32_t* bm_a, const int32_t* a0, int64_t na0, const int32_t* a1, int64_t na1, uint32_t* bm_b,
-                        const int32_t* b0, int64_t nb0, int64_t nv, hipStream_t s) {
-    const int64_t n = na0 + na1 + nb0;
-    if (n <= 0) return NRT_OK;
-    mark_batch_kernel<<<(int)cdiv(n, 256), 256, 0, s>>>(bm_a, a0, na0, a1, na1, bm_b, b0, nb0, nv);
-    LAUNCH_CHECK();
-    return NRT_OK;
-}
-
 nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_t tmp_len, uint64_t* total, hipStream_t s) {
     const int64_t nb = n > 0 ? cdiv(n, EPB) : 0;
     if (nb > tmp_len) { nrt_set_error("scan scratch too small"); return NRT_ERR_INVALID_ARG; }
@@ -480,7 +462,8 @@ nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b,
                      int32_t* list, int32_t* slot, uint64_t* state, int64_t state_len, uint64_t* count, hipStream_t s,
                      const uint32_t* and_mask, const CompactExtra* extra) {
     const int64_t nw = cdiv(n, 32);
-    const int64_t nb = nw > 0 ? cdiv(nw, EPB) : 0;
+    const int cept = nw <= 131072 ? 1 : 4;
+    const int64_t nb = nw > 0 ? cdiv(nw, (int64_t)TPB * cept) : 0;
     if (nb + 2 > state_len) { nrt_set_error("compaction state too small"); return NRT_ERR_INVALID_ARG; }
     if (nb <= 0) return k_fill_u64(count, 1, 0, s);
     CompactArgs a;
@@ -490,11 +473,12 @@ nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b,
     a.list = list; a.slot = slot;
     a.state = (unsigned long long*)state; a.count = count;
     if (extra) a.x = *extra;
-    if (a.x.coarse && a.x.coarse_shift > 10) {      // a coarse word would span several workgroups: built by its own kernel
+    if (a.x.coarse && (1 << a.x.coarse_shift) > TPB * cept) {   // a coarse word would span several workgroups: built by its own kernel
         nrt_set_error("internal: coarse shift beyond the compaction's reach");
         return NRT_ERR_INVALID_ARG;
     }
-    compact_kernel<<<(int)nb, TPB, 0, s>>>(a);
+    if (cept == 1) compact_kernel<1><<<(int)nb, TPB, 0, s>>>(a);
+    else compact_kernel<4><<<(int)nb, TPB, 0, s>>>(a);
     LAUNCH_CHECK();
     return NRT_OK;
 }
