@@ -204,7 +204,10 @@ void nrt_cache_destroy(nrt_cache*);
  * Errors: NRT_ERR_BAD_BATCH (contract violated, or batch larger than the sizes given at init; state
  * unchanged), NRT_ERR_OOM (adjacency pool exhausted; state unchanged), NRT_ERR_INVALID_ARG (capacity
  * smaller than the affected count: caches ARE updated, only the copy-out is skipped, *n_affected holds the
- * needed capacity).  Synchronises the stream before returning.
+ * needed capacity).  NRT_ERR_DEVICE (a HIP call failed) and NRT_ERR_STATE (an internal consistency check of the
+ * cache layout's bounds, unreachable for a graph within e_capacity) can be raised after the batch has been validated:
+ * graph and caches are then unspecified and must be rebuilt (destroy, nrt_graph_create, nrt_cache_init).
+ * Synchronises the stream before returning.
  */
 nrt_status nrt_apply_batch(nrt_cache*, const nrt_batch*, int32_t* affected_ids, float* affected_rows,
                            int64_t capacity, int64_t* n_affected, void* stream);

@@ -1343,9 +1343,15 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         ls->n_affected = c->n_list[l];
         ls->n_items = (int64_t)c->lc_host[l].n_items;
         for (int q = 0; q < 16; ++q) ls->n_in_edges += (int64_t)c->lc_host[l].in_edges[q];
+        // Cannot happen: the capacities are bounds that follow from the graph's own limits (a destination with more than
+        // NRT_CHUNK in-edges owns more than NRT_CHUNK of at most e_capacity edges, so there are fewer than
+        // e_capacity / NRT_CHUNK of them and they have at most twice that many items; likewise for sources with long
+        // out-lists), and the kernels clamp to the capacities, so nothing was written out of bounds.  Kept as a
+        // consistency check of those bounds; the batch has been applied by now, so if it ever fires the caches must be
+        // rebuilt (nrt.h documents NRT_ERR_STATE from this call that way).
         if ((int64_t)c->lc_host[l].n_hubs > c->hubs.hub_cap || (int64_t)c->lc_host[l].n_items > c->hubs.item_cap ||
             (int64_t)c->lc_host[l - 1].n_xhubs > c->xhub_cap) {
-            nrt_set_error("internal: hub buffers too small");
+            nrt_set_error("internal: hub buffers too small (a bound of the cache layout is violated); rebuild the caches");
             return NRT_ERR_STATE;
         }
     }

@@ -37,8 +37,8 @@ def assert_parity(kind, gpu, ref, what, fresh=None):
     single elements are differences of terms 1e3-1e6 times larger than the result; fp32 caches cannot hold such an
     element to 1e-4 of max(|oracle|, 1) (a cached row of magnitude 1e6 already carries 0.06 of absolute rounding).
     What gates these models here is the row-normalised 1e-4 and, against drift of the incremental path, an
-    element-wise error no worse than 3x (GIN) or 10x (the other plain-sum models) that of a from-scratch fp32
-    forward on the GPU (`fresh`) when the test supplies one.  The stated element-wise bar is NOT replaced: every
+    element-wise error no worse than 3x (6x for G-GCN) that of a from-scratch fp32 forward on the GPU (`fresh`) when
+    the test supplies one.  The stated element-wise bar is NOT replaced: every
     such check is logged in ELEMENTWISE_LOG and test_gpu_random.py ends with a test, expected to fail, that holds
     the logged errors to 1e-4."""
     if kind not in UNNORMALISED:
@@ -49,10 +49,10 @@ def assert_parity(kind, gpu, ref, what, fresh=None):
     floor = None if fresh is None else rel_err(fresh, ref)
     ELEMENTWISE_LOG.append((what, err, floor))
     if fresh is not None:
-        # GIN (a configured model) is held to 3x; for the Table II models added on top the from-scratch forward is one
-        # draw of the same rounding noise (its own error moves by that much with the order of summation), so the
-        # element-wise check only guards against gross errors there
-        factor = 3.0 if kind == wl.GIN else 10.0
+        # 3x for every plain-sum model but G-GCN, whose saturating gate amplifies the rounding of its un-normalised
+        # sums: its worst measured ratio over this suite is 4.6 (3.0e-4 against 6.5e-5), the others stay below 2.2.
+        # The summation order is fixed (no atomics), so these ratios are reproducible, not a draw of scheduling noise.
+        factor = 6.0 if kind == wl.GGCN else 3.0
         assert err <= max(TOL, factor * floor), what
 
 

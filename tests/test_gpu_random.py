@@ -4,7 +4,8 @@ Every case draws a model kind (all nine), a graph size and density, 1-3 layers w
 chain of batches with random sizes (including none of a kind, and batches large enough for the packed ingest path),
 random modes and, where the model allows it, the on-demand mode with queries.  Bar as in test_gpu_parity: affected
 lists bit-exact; embeddings element-wise 1e-4 for the normalised models, row-normalised 1e-4 for the plain-sum
-models (their element-wise error is additionally compared with a from-scratch fp32 forward when it exceeds 1e-4)."""
+models (their element-wise error is additionally held to 3x, G-GCN 6x, that of a from-scratch fp32 forward when it
+exceeds 1e-4)."""
 import numpy as np
 import pytest
 
@@ -39,7 +40,7 @@ def _check_layers(S, oracle, ses, spec, params, n, cur, L, what):
             if fresh is None:
                 fresh = S.Session(spec, params, n, *cur, max_batch_edges=64, max_batch_feats=64)
             floor = rel_err(fresh.layer(l).cpu().numpy(), ref[l - 1])
-            assert err <= max(TOL, 10.0 * floor), (what, l)
+            assert err <= max(TOL, (6.0 if spec.kind == wl.GGCN else 3.0) * floor), (what, l)
         ELEMENTWISE_LOG.append(((what, l), err, floor))
     return ref
 
@@ -109,6 +110,9 @@ def test_elementwise_bar_of_the_plain_sum_models():
     plain-sum model that this process ran before (test_gpu_fullsize, test_gpu_parity and the cases above log them).
     Those checks gate on the row-normalised reading; this test keeps the element-wise reading visible: it prints the
     worst cases with the error of a from-scratch fp32 forward beside them and is expected to fail."""
+    ratios = sorted(((err / floor, err, floor, what) for what, err, floor in ELEMENTWISE_LOG if floor and err > TOL), key=lambda t: -t[0])[:6]
+    for ratio, err, floor, what in ratios:
+        print("incremental / from-scratch element-wise error %.2f (%.3e / %.3e)  %s" % (ratio, err, floor, what))
     worst = sorted(ELEMENTWISE_LOG, key=lambda t: -t[1])[:8]
     for what, err, floor in worst:
         print("element-wise %.3e (from-scratch fp32 forward: %s)  %s" % (err, "n/a" if floor is None else "%.3e" % floor, what))
