@@ -256,6 +256,23 @@ nrt_status nrt_set_mode(nrt_cache*, int32_t mode);
 nrt_status nrt_set_lazy(nrt_cache*, int32_t on, void* stream);
 nrt_status nrt_query(nrt_cache*, const int32_t* query_ids, int64_t n_query, float* rows, int64_t* n_recomputed /*host*/,
                      void* stream);
+/* A batch and a query in one call, on-demand mode only (Section IV-D: the computation graph of an on-demand batch is
+ * the affected subgraph intersected with the K-hop subgraph of the queried vertices).  The batch is applied as by
+ * nrt_apply_batch in on-demand mode (graph, features, affected sets, stale marks; affected_ids is filled), then the
+ * final-layer rows of query_ids are returned as by nrt_query.  The difference lies in how the needed vertices are
+ * brought up to date: one that was up to date before this batch takes the incremental layer (Algorithm 1: delta
+ * messages of its changed in-neighbours, the batch's inserted and deleted edges) instead of being summed again over its
+ * whole in-neighbourhood; one that an earlier batch had already left stale is recomputed.  Folding is done for the
+ * models whose message is h itself and does not read the destination (GCN, GraphSAGE, GIN, CommNet); the others
+ * recompute every needed vertex, as nrt_query does.
+ *   query_ids device, n_query > 0 ids in [0, N), repeats allowed;  query_rows device [n_query][d_L]
+ *   n_updated  host, may be NULL: vertices brought up to date, summed over the layers
+ *   n_recomputed host, may be NULL: those of them recomputed over their whole in-neighbourhood
+ * Errors: as nrt_apply_batch; NRT_ERR_INVALID_ARG for a query id out of range (nothing is changed, like a bad batch);
+ * NRT_ERR_STATE when the on-demand mode is off.  Synchronises the stream. */
+nrt_status nrt_apply_batch_query(nrt_cache*, const nrt_batch*, int32_t* affected_ids, int64_t capacity, int64_t* n_affected /*host*/,
+                                 const int32_t* query_ids, int64_t n_query, float* query_rows,
+                                 int64_t* n_updated /*host*/, int64_t* n_recomputed /*host*/, void* stream);
 nrt_status nrt_set_profiling(nrt_cache*, int32_t on);
 nrt_status nrt_get_stats(const nrt_cache*, nrt_stats* out /*host*/);
 

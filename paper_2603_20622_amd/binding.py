@@ -63,7 +63,7 @@ class NrtError(RuntimeError):
 EXPORTS = ["nrt_graph_workspace_bytes", "nrt_graph_create", "nrt_graph_destroy", "nrt_graph_num_edges",
            "nrt_graph_export_csc", "nrt_graph_export_csc_static", "nrt_cache_workspace_bytes", "nrt_cache_init", "nrt_cache_destroy",
            "nrt_apply_batch", "nrt_get_layer", "nrt_get_aggregate", "nrt_get_layer_affected", "nrt_set_profiling",
-           "nrt_set_mode", "nrt_set_lazy", "nrt_query", "nrt_get_stats", "nrt_measure_stream", "nrt_last_error", "nrt_version"]
+           "nrt_set_mode", "nrt_set_lazy", "nrt_query", "nrt_apply_batch_query", "nrt_get_stats", "nrt_measure_stream", "nrt_last_error", "nrt_version"]
 
 _lib = None
 
@@ -95,6 +95,7 @@ def lib() -> ctypes.CDLL:
         L.nrt_set_mode.argtypes = [c_fp, i32]
         L.nrt_set_lazy.argtypes = [c_fp, i32, c_fp]
         L.nrt_query.argtypes = [c_fp, c_fp, i64, c_fp, P(i64), c_fp]
+        L.nrt_apply_batch_query.argtypes = [c_fp, P(nrt_batch), c_fp, i64, P(i64), c_fp, i64, c_fp, P(i64), P(i64), c_fp]
         L.nrt_get_stats.argtypes = [c_fp, P(nrt_stats)]
         L.nrt_measure_stream.argtypes = [i32, c_fp, c_fp, i64, i32, c_fp, P(ctypes.c_float)]
         L.nrt_last_error.restype = ctypes.c_char_p
@@ -301,6 +302,15 @@ def nrt_query(c: Cache, query_ids: torch.Tensor, rows: torch.Tensor) -> int:
     n = ctypes.c_int64(0)
     _check(lib().nrt_query(c.handle, _ptr(query_ids), int(query_ids.numel()), _ptr(rows), ctypes.byref(n), _stream()))
     return int(n.value)
+
+
+def nrt_apply_batch_query(c: Cache, batch: nrt_batch, affected_ids: torch.Tensor, query_ids: torch.Tensor, rows: torch.Tensor):
+    """(n_affected, n_updated, n_recomputed); rows[i] = final-layer embedding of query_ids[i] after the batch."""
+    na, nu, nr = ctypes.c_int64(0), ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().nrt_apply_batch_query(c.handle, ctypes.byref(batch), _ptr(affected_ids), affected_ids.numel(), ctypes.byref(na),
+                                       _ptr(query_ids), int(query_ids.numel()), _ptr(rows), ctypes.byref(nu), ctypes.byref(nr),
+                                       _stream()))
+    return int(na.value), int(nu.value), int(nr.value)
 
 
 def nrt_set_profiling(c: Cache, on: bool) -> None:

@@ -30,6 +30,11 @@ extern "C" const char* nrt_version(void) { return "nrt 0.1 (gfx950)"; }
 
 // ------------------------------------------------------------------ cache handle
 constexpr int MAX_EVENTS = 16 + 8 * NRT_MAX_LAYERS;
+// device counter blocks of a cache: [0 .. NRT_MAX_LAYERS] the per-layer sets of a batch, [NRT_MAX_LAYERS + 1] whole-graph
+// passes, then three groups of NRT_MAX_LAYERS + 1 for a batch served together with a query (the vertices the query needs,
+// those of them that were up to date before the batch, those that were already stale)
+constexpr int LC_BATCH = NRT_MAX_LAYERS + 2;
+constexpr int LC_TOTAL = LC_BATCH + 3 * (NRT_MAX_LAYERS + 1);
 
 struct nrt_cache {
     nrt_graph* g;
@@ -63,13 +68,23 @@ struct nrt_cache {
     uint32_t *bm_ddst, *bm_feat, *bm[2];
     int64_t nw_pad;
     uint8_t* flags;                     // one byte per vertex: the set an expansion hop is building
-    LayerCtrs* lc;                      // device, [NRT_MAX_LAYERS + 2]; the last one serves whole-graph passes of a batch
+    LayerCtrs* lc;                      // device, [LC_TOTAL]
     LayerCtrs* lc_use;                  // counters the layer steps read instead of lc[l] (null: lc[l])
     int mode;                           // nrt_mode
     bool have_history;                  // n_list holds the set sizes of a previous batch (hints for kernel choice)
     bool have_history_prev;             // while a batch runs: lc_host still holds the counters of the batch before it
     int lazy;                           // on-demand mode: batches only record what became stale
     uint32_t* stale[NRT_MAX_LAYERS + 1]; // per layer: vertices whose cached aggregate / embedding is out of date
+    // a batch served together with a query (nrt_apply_batch_query): the stale sets as they were before the batch, the sets
+    // the query needs per layer ([0]: the sources of change of layer 1), their lists, the two classes of a layer, the
+    // bitmap of the queried vertices
+    uint32_t* stale_prev[NRT_MAX_LAYERS + 1];
+    uint32_t* need_bm[NRT_MAX_LAYERS + 1];
+    int32_t* need_list[NRT_MAX_LAYERS + 1];
+    int32_t *list_fresh, *list_redo;
+    uint32_t* bm_q;
+    // sources of a fold given explicitly instead of the previous layer's set of the batch (null: not in use)
+    const uint32_t* ov_bm; const int32_t* ov_slot; const float* ov_dp; const uint64_t* ov_count; const uint32_t* ov_coarse;
     LayerCtrs* lc_host;                 // pinned mirror, followed by the mirror of pair_ctr (profiling)
     unsigned long long* pair_host;
     int32_t* xhub_list;
@@ -452,7 +467,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->xhub_cap = g->e_capacity / 512 + 64;                    // sources with more than 512 live out-edges
     c->xhub_list = b.take<int32_t>(c->xhub_cap);
     c->flags = b.take<uint8_t>(n + 64);
-    c->lc = b.take<LayerCtrs>(NRT_MAX_LAYERS + 2);
+    c->lc = b.take<LayerCtrs>(LC_TOTAL);
     c->sc.max_edges = c->max_edges;
     int64_t hc = 16;
     while (hc < 2 * (c->max_edges + 1)) hc <<= 1;
@@ -467,6 +482,14 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->pair_ctr = b.take<unsigned long long>(1024 * NRT_MAX_LAYERS);
     c->pull_list = b.take<int32_t>(n);
     for (int l = 1; l <= c->L; ++l) c->stale[l] = b.take<uint32_t>(nw);
+    for (int l = 0; l <= c->L; ++l) {
+        c->stale_prev[l] = l >= 1 ? b.take<uint32_t>(nw) : nullptr;
+        c->need_bm[l] = b.take<uint32_t>(nw);
+        c->need_list[l] = l >= 1 ? b.take<int32_t>(n) : nullptr;
+    }
+    c->list_fresh = b.take<int32_t>(n);
+    c->list_redo = b.take<int32_t>(n);
+    c->bm_q = b.take<uint32_t>(nw);
     c->coarse[0] = b.take<uint32_t>(NRT_COARSE_WORDS);
     c->coarse[1] = b.take<uint32_t>(NRT_COARSE_WORDS);
     c->cmp_state_len = cdiv(nw, 256) + 8;
@@ -583,10 +606,10 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
     full.src_scale_gcn = c->kind == NRT_GCN;
     full.accumulate = 0;
     if (incremental) {
-        a.P = c->DP[prev];
-        a.src_bitmap = c->bm[prev];
-        a.src_slot = c->slot[prev];
-        a.n_src_dev = &c->lc[l - 1].count;
+        a.P = c->ov_bm ? c->ov_dp : c->DP[prev];
+        a.src_bitmap = c->ov_bm ? c->ov_bm : c->bm[prev];
+        a.src_slot = c->ov_bm ? c->ov_slot : c->slot[prev];
+        a.n_src_dev = c->ov_bm ? c->ov_count : &c->lc[l - 1].count;
         a.src_scale_gcn = 0;
         a.accumulate = 1;
         a.sd = c->SD[l];
@@ -596,11 +619,11 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
         a.Pfull = payload_rows(c, l - 1);
         a.full_scale_gcn = c->kind == NRT_GCN;
         a.sparse_ok = (sparse_hint == 2 && a.D > 256) ? 1 : sparse_hint;    // rows wider than 256 floats: pipelined kernel only
-        a.coarse = c->coarse[prev];                  // written by the compaction that produced bm[prev]
+        a.coarse = c->ov_bm ? c->ov_coarse : c->coarse[prev];   // written by the compaction that produced the source set
         a.coarse_shift = c->coarse_shift;
         a.coarse_words = c->coarse_words;
         if (c->coarse_shift > 10)                    // beyond 200M vertices a coarse word spans several compaction workgroups
-            NRT_TRY(k_coarse_bitmap(c->bm[prev], g->n, c->coarse_shift, c->coarse[prev], c->coarse_words, s));
+            NRT_TRY(k_coarse_bitmap(a.src_bitmap, g->n, c->coarse_shift, const_cast<uint32_t*>(a.coarse), c->coarse_words, s));
         if (may_recompute) {                     // the device counters pick one of the two (GatherArgs::auto_role)
             a.auto_role = 1;
             a.auto_src_dev = &c->lc[l - 1].count;
@@ -975,7 +998,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     cache_fill(c, g, d, max_batch_edges, max_batch_feats);
     Bump b{static_cast<char*>(workspace), 0};
     cache_layout(b, c);
-    const size_t lc_bytes = ((NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) + 255) & ~size_t(255);
+    const size_t lc_bytes = (LC_TOTAL * sizeof(LayerCtrs) + 255) & ~size_t(255);
     if (hipHostMalloc((void**)&c->lc_host, lc_bytes + 1024 * NRT_MAX_LAYERS * sizeof(unsigned long long),
                       hipHostMallocDefault) != hipSuccess) {
         delete c;
@@ -988,7 +1011,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         NRT_TRY(k_copy_f32(c->H[0], features, n * c->dims[0], s));
         NRT_TRY(k_fill_u32((uint32_t*)c->sc.feat_stamp, n, 0, s));
         NRT_TRY(k_fill_u32((uint32_t*)c->flags, (n + 64) / 4, 0, s));
-        NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
+        NRT_TRY(k_fill_u64((uint64_t*)c->lc, LC_TOTAL * sizeof(LayerCtrs) / 8, 0, s));
         NRT_TRY(k_fill_u64(c->cmp_state, c->cmp_state_len, 0, s));
         for (int l = 0; l < c->L; ++l) {
             const int kin = c->kind == NRT_MONET ? c->monet_J : (concat_self(c->kind) ? 2 : 1) * c->dims[l];
@@ -1047,8 +1070,14 @@ extern "C" void nrt_cache_destroy(nrt_cache* c) {
 }
 
 // ------------------------------------------------------------------ apply batch
-extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t* affected_ids, float* affected_rows,
-                                      int64_t capacity, int64_t* n_affected, void* stream) {
+struct QueryArgs {                  // the query served together with a batch in on-demand mode (ids null: none)
+    const int32_t* ids; int64_t n; float* rows;
+    int64_t *n_updated, *n_recomputed;      // host, may be null
+};
+static nrt_status serve_query_after_batch(nrt_cache* c, const QueryArgs& q, bool fold, hipStream_t s);
+
+static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* affected_ids, float* affected_rows,
+                                   int64_t capacity, int64_t* n_affected, const QueryArgs& q, void* stream) {
     REQUIRE(c && b && n_affected, "null argument");
     REQUIRE(b->n_ins >= 0 && b->n_del >= 0 && b->n_feat >= 0, "negative batch count");
     REQUIRE(capacity >= 0 && (capacity == 0 || affected_ids), "affected_ids is null");
@@ -1087,12 +1116,13 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         FillJobs f;
         memset(&f, 0, sizeof(f));
         f.add(c->bm_ddst, 2 * c->nw_pad);                     // bm_ddst and bm_feat are adjacent
-        f.add(c->lc, (int64_t)((NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 4));
+        f.add(c->lc, (int64_t)(LC_TOTAL * sizeof(LayerCtrs) / 4));
         if (c->profiling) f.add(c->pair_ctr, 2 * 1024 * NRT_MAX_LAYERS);
         if (b->n_ins + b->n_del > 2048) {                     // scratch of the batch plan's counting form
             f.add(c->plan_off64, 2 * (b->n_ins + b->n_del + 1));
             f.add(c->plan_cursor, b->n_ins + b->n_del);
         }
+        if (q.ids) f.add(c->bm_q, (n + 31) / 32);
         c->sc.bm_dst = c->bm_ddst;                            // the batch's sets are marked by the validation kernels
         c->sc.bm_feat = c->bm_feat;
         NRT_TRY(graph_validate_batch(g, b, c->sc, &f, s));
@@ -1100,12 +1130,19 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     // The verdict travels to the host while the device goes on with work that touches only per-batch scratch and
     // tolerates a bad batch (ids are range-checked there, caches are only read): the host waits for the event, not
     // for the stream, so the queue never runs dry between validation and mutation.
+    if (q.ids)                                                // the queried set; an id out of range rejects the call like a bad batch
+        NRT_TRY(k_mark_ids(c->bm_q, q.ids, q.n, n, (int32_t*)(g->dev_ctrs + CTR_ERR) + 6, s));
     HIP_TRY(hipMemcpyAsync(g->host_pinned, g->dev_ctrs, NRT_NCTRS * sizeof(int64_t), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipEventRecord(c->ev_validated, s));
     const bool empty_batch = b->n_ins + b->n_del + b->n_feat == 0;
     // ---- sets of the batch, structural terms on the old caches (scratch only)
     const bool gcn = c->kind == NRT_GCN;
-    const bool inc = !c->lazy && (c->mode == NRT_MODE_INCREMENTAL || c->mode == NRT_MODE_AUTO);
+    // a query served with the batch folds deltas into the vertices that were up to date before the batch (the models
+    // whose messages are h itself and do not read the destination); that needs the same structural terms and layer-0
+    // deltas as eager incremental maintenance
+    const bool foldq = c->lazy && q.ids && !empty_batch &&
+                       (c->kind == NRT_GCN || c->kind == NRT_SAGE_MEAN || c->kind == NRT_GIN || c->kind == NRT_COMMNET);
+    const bool inc = foldq || (!c->lazy && (c->mode == NRT_MODE_INCREMENTAL || c->mode == NRT_MODE_AUTO));
     // layers that may switch to recomputation on the device: only where the previous batch had a large source set
     // (no extra launches for small frontiers); the device counters of this batch take the decision
     bool may_rec[NRT_MAX_LAYERS + 2];
@@ -1202,6 +1239,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         else if (err[3]) msg = "deleted edge not present";
         nrt_status bad = NRT_OK;
         if (msg) { nrt_set_error("%s", msg); bad = NRT_ERR_BAD_BATCH; }
+        else if (err[6]) { nrt_set_error("query id out of range"); bad = NRT_ERR_INVALID_ARG; }
         else if (g->host_pinned[CTR_HEAD_OUT] + g->host_pinned[CTR_GROW] > g->out.pool_cap ||
                  g->host_pinned[CTR_HEAD_IN] + g->host_pinned[CTR_GROW + 1] > g->in.pool_cap) {
             nrt_set_error("adjacency pool exhausted");
@@ -1216,6 +1254,12 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
     if (b->n_ins + b->n_del + b->n_feat == 0) {
         NRT_TRY(graph_mutate(g, b, c->sc, s));
         *n_affected = 0;
+        if (q.ids) {                                          // nothing changed: the query alone
+            int64_t nr = 0;
+            NRT_TRY(nrt_query(c, q.ids, q.n, q.rows, &nr, stream));
+            if (q.n_updated) *q.n_updated = nr;
+            if (q.n_recomputed) *q.n_recomputed = nr;
+        }
         return NRT_OK;
     }
 
@@ -1248,6 +1292,7 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         da.store_old = agnn_family(c->kind);
         NRT_TRY(k_layer0_delta(da, s));
     }
+    if (q.ids) NRT_TRY(k_copy_i32((int32_t*)c->need_bm[0], (const int32_t*)c->bm[0], (n + 31) / 32, s));   // bm[0] is reused by the hops
     NRT_TRY(prof_mark(c, TAG_INGEST, 0, s));
 
     // ---- layers: no host round trip, every size stays on the device
@@ -1266,12 +1311,13 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(k_expand_frontier(g->out, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->flags, &c->lc[l - 1],
                                   c->xhub_list, c->xhub_cap, g->in, pull, s));
         NRT_TRY(prof_mark(c, TAG_EXPAND, l, s));
-        cx.coarse = c->coarse_shift <= 10 ? c->coarse[cur] : nullptr;
-        cx.list2 = l == c->L ? affected_ids : nullptr;              // the last set is also the caller's list
-        cx.cap2 = capacity;
-        NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->slot[cur], c->cmp_state,
-                          c->cmp_state_len, &c->lc[l].count, s, nullptr, &cx));
+        cx.coarse = (c->coarse_shift <= 10 && !c->lazy) ? c->coarse[cur] : nullptr;   // on-demand mode: the set only becomes
+        cx.list2 = l == c->L ? affected_ids : nullptr;              // stale; slot map and coarse copy of layer 1's sources stay
+        cx.cap2 = capacity;                                         // (the last set is also the caller's list)
+        NRT_TRY(k_compact(c->flags, c->bm_ddst, c->bm[prev], c->bm[cur], n, c->list[l], c->lazy ? nullptr : c->slot[cur],
+                          c->cmp_state, c->cmp_state_len, &c->lc[l].count, s, nullptr, &cx));
         if (c->lazy) {                                     // on-demand mode: A_l only becomes stale
+            if (q.ids) NRT_TRY(k_copy_i32((int32_t*)c->stale_prev[l], (const int32_t*)c->stale[l], (n + 31) / 32, s));
             // h^0 is never stale, so neither may be what layer 1 caches of it by vertex: message rows, z and the
             // attention scalars, inverse norms, gate projections
             if (has_message_cache(c->kind) && l == 1)
@@ -1323,13 +1369,14 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         NRT_TRY(prof_mark(c, TAG_UPDATE, l, s));
         prev = cur;
     }
+    if (c->lazy && q.ids) NRT_TRY(serve_query_after_batch(c, q, foldq, s));
     if (c->mode == NRT_MODE_FULL && !c->lazy) {
         NRT_TRY(full_forward(c, s));
         if (affected_rows)
             NRT_TRY(k_gather_rows(affected_rows, c->H[c->L], c->list[c->L], &c->lc[c->L].count, capacity, n, c->dims[c->L], s));
         NRT_TRY(prof_mark(c, TAG_UPDATE, c->L, s));
     }
-    HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, LC_TOTAL * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
     if (c->profiling)
         HIP_TRY(hipMemcpyAsync(c->pair_host, c->pair_ctr, 1024 * NRT_MAX_LAYERS * sizeof(unsigned long long),
                                hipMemcpyDeviceToHost, s));
@@ -1362,6 +1409,25 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
             return NRT_ERR_STATE;
         }
     }
+    if (c->lazy && q.ids) {
+        const LayerCtrs* need = c->lc_host + LC_BATCH;
+        const LayerCtrs* redo = need + 2 * (NRT_MAX_LAYERS + 1);
+        int64_t nu = 0, nr = 0;
+        for (int l = 1; l <= c->L; ++l) {
+            nu += (int64_t)need[l].count;
+            nr += foldq ? (int64_t)redo[l].count : (int64_t)need[l].count;
+            for (int k = 0; k < 3; ++k) {
+                const LayerCtrs& t = need[k * (NRT_MAX_LAYERS + 1) + l];
+                if ((int64_t)t.n_hubs > c->hubs.hub_cap || (int64_t)t.n_items > c->hubs.item_cap || (int64_t)t.n_xhubs > c->xhub_cap) {
+                    nrt_set_error("internal: hub buffers too small (a bound of the cache layout is violated); rebuild the caches");
+                    return NRT_ERR_STATE;
+                }
+            }
+        }
+        if (q.n_updated) *q.n_updated = nu;
+        if (q.n_recomputed) *q.n_recomputed = nr;
+        c->have_history = false;                          // the sets of this call are not those of an eager batch
+    }
     c->stats.n_launches = nrt_launch_count;
     NRT_TRY(prof_collect(c));
     if (c->profiling) {
@@ -1378,6 +1444,25 @@ extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t*
         return NRT_ERR_INVALID_ARG;
     }
     return NRT_OK;
+}
+
+extern "C" nrt_status nrt_apply_batch(nrt_cache* c, const nrt_batch* b, int32_t* affected_ids, float* affected_rows,
+                                      int64_t capacity, int64_t* n_affected, void* stream) {
+    QueryArgs none;
+    memset(&none, 0, sizeof(none));
+    return apply_batch_impl(c, b, affected_ids, affected_rows, capacity, n_affected, none, stream);
+}
+
+extern "C" nrt_status nrt_apply_batch_query(nrt_cache* c, const nrt_batch* b, int32_t* affected_ids, int64_t capacity,
+                                            int64_t* n_affected, const int32_t* query_ids, int64_t n_query, float* query_rows,
+                                            int64_t* n_updated, int64_t* n_recomputed, void* stream) {
+    REQUIRE(c && query_ids && query_rows && n_query > 0, "null argument or empty query");
+    if (!c->lazy) { nrt_set_error("nrt_apply_batch_query needs the on-demand mode (nrt_set_lazy)"); return NRT_ERR_STATE; }
+    if (n_updated) *n_updated = 0;
+    if (n_recomputed) *n_recomputed = 0;
+    QueryArgs q;
+    q.ids = query_ids; q.n = n_query; q.rows = query_rows; q.n_updated = n_updated; q.n_recomputed = n_recomputed;
+    return apply_batch_impl(c, b, affected_ids, nullptr, capacity, n_affected, q, stream);
 }
 
 // ------------------------------------------------------------------ views, stats
@@ -1439,7 +1524,7 @@ static nrt_status recompute_listed(nrt_cache* c, hipStream_t s) {
 }
 
 static nrt_status finish_recompute(nrt_cache* c, int64_t* n_recomputed, hipStream_t s) {
-    HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipMemcpyAsync(c->lc_host, c->lc, LC_TOTAL * sizeof(LayerCtrs), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipStreamSynchronize(s));
     int64_t tot = 0;
     for (int l = 1; l <= c->L; ++l) {
@@ -1455,6 +1540,100 @@ static nrt_status finish_recompute(nrt_cache* c, int64_t* n_recomputed, hipStrea
     return NRT_OK;
 }
 
+// The query of nrt_apply_batch_query, after the batch's hops have marked A_l stale (Section IV-D: the computation graph
+// of an on-demand batch is the affected subgraph intersected with the K-hop subgraph of the queried vertices).
+//   backwards  need_L = Q and stale_L;  need_{l-1} = stale_{l-1} and (need_l or in-neighbours(need_l))
+//   forwards   a needed vertex that was up to date before the batch (`fold`, models whose message is h itself) takes the
+//              incremental layer of Algorithm 1: its changed in-neighbours are all needed one layer below, where their
+//              payload deltas were just produced, and the batch's structural terms are ready; a needed vertex that was
+//              already stale is summed again over its whole in-neighbourhood.  Both kinds then run the dense update,
+//              which also leaves the payload deltas for the next layer, and lose their stale mark.
+// An up-to-date vertex has only up-to-date in-neighbours (the stale sets are closed under "out-neighbour at the next
+// layer"), so what its cached aggregate holds of a source is exactly the cached row the delta is taken against.
+static nrt_status serve_query_after_batch(nrt_cache* c, const QueryArgs& q, bool fold, hipStream_t s) {
+    nrt_graph* g = c->g;
+    const int64_t n = g->n;
+    LayerCtrs* need = c->lc + LC_BATCH;
+    LayerCtrs* fresh = need + (NRT_MAX_LAYERS + 1);
+    LayerCtrs* redo = fresh + (NRT_MAX_LAYERS + 1);
+    c->have_history_prev = false;
+    CompactExtra cx;
+    memset(&cx, 0, sizeof(cx));
+    cx.err = &c->lc[0].pad[0];
+    cx.coarse_shift = c->coarse_shift;
+    cx.coarse_words = c->coarse_words;
+    // ---- backwards: what the queried rows depend on
+    NRT_TRY(k_compact(nullptr, c->bm_q, nullptr, c->need_bm[c->L], n, c->need_list[c->L], nullptr, c->cmp_state, c->cmp_state_len,
+                      &need[c->L].count, s, c->stale[c->L], &cx));
+    PullArgs no_pull;
+    memset(&no_pull, 0, sizeof(no_pull));
+    for (int l = c->L; l >= 2; --l) {
+        NRT_TRY(k_expand_frontier(g->in, c->need_list[l], &need[l].count, n, c->flags, &need[l], c->xhub_list, c->xhub_cap, g->out,
+                                  no_pull, s));
+        NRT_TRY(k_compact(c->flags, c->need_bm[l], nullptr, c->need_bm[l - 1], n, c->need_list[l - 1], nullptr, c->cmp_state,
+                          c->cmp_state_len, &need[l - 1].count, s, c->stale[l - 1], &cx));
+    }
+    // ---- forwards
+    int prev = 0;
+    for (int l = 1; l <= c->L; ++l) {
+        const int cur = 1 - prev;
+        // the needed set once more, now with its slot map and coarse copy (the next layer's sources)
+        cx.coarse = c->coarse_shift <= 10 ? c->coarse[cur] : nullptr;
+        NRT_TRY(k_compact(nullptr, c->need_bm[l], nullptr, c->bm[cur], n, c->need_list[l], c->slot[cur], c->cmp_state,
+                          c->cmp_state_len, &need[l].count, s, nullptr, &cx));
+        cx.coarse = nullptr;
+        if (fold) {
+            cx.and_invert = 1;
+            NRT_TRY(k_compact(nullptr, c->need_bm[l], nullptr, c->bm[1 - cur], n, c->list_fresh, nullptr, c->cmp_state,
+                              c->cmp_state_len, &fresh[l].count, s, c->stale_prev[l], &cx));
+            cx.and_invert = 0;
+            NRT_TRY(k_compact(nullptr, c->need_bm[l], nullptr, c->bm[1 - cur], n, c->list_redo, nullptr, c->cmp_state,
+                              c->cmp_state_len, &redo[l].count, s, c->stale_prev[l], &cx));
+            // up to date before the batch: fold the deltas of the changed in-neighbours and the structural terms
+            NRT_TRY(k_dst_records(c->list_fresh, n, g->in, c->recs, c->hubs, &fresh[l], false, nullptr, s));
+            c->lc_use = &fresh[l];
+            c->ov_bm = c->need_bm[l - 1];
+            c->ov_slot = c->slot[prev];
+            c->ov_dp = c->DP[prev];
+            c->ov_count = l == 1 ? &c->lc[0].count : &need[l - 1].count;
+            c->ov_coarse = c->coarse[prev];
+            nrt_status st = run_gather(c, l, true, prev, false, 1, s);
+            c->ov_bm = nullptr;
+            if (st == NRT_OK) {                      // already stale: the whole in-neighbourhood again
+                st = k_dst_records(c->list_redo, n, g->in, c->recs, c->hubs, &redo[l], false, nullptr, s);
+                c->lc_use = &redo[l];
+                if (st == NRT_OK) st = run_gather(c, l, false, 0, false, 0, s);
+            }
+            c->lc_use = nullptr;
+            NRT_TRY(st);
+            NRT_TRY(run_update(c, l, c->need_list[l], n, &need[l].count, true, cur, nullptr, 0, false, s));
+        } else {
+            NRT_TRY(k_dst_records(c->need_list[l], n, g->in, c->recs, c->hubs, &need[l], false, nullptr, s));
+            c->lc_use = &need[l];
+            nrt_status st = NRT_OK;
+            if (c->kind == NRT_GAT || agnn_family(c->kind)) {
+                const int64_t sb = l == 1 ? 0 : n;   // layer 1 reads h^0, whose projections every batch keeps current
+                if (c->kind == NRT_GAT)
+                    st = run_gat_layer(c, l, c->need_list[l - 1], &need[l - 1].count, sb, c->need_list[l], &need[l].count, n, true,
+                                       false, 0, nullptr, 0, s);
+                else
+                    st = run_agnn_layer(c, l, c->need_list[l - 1], &need[l - 1].count, sb, c->need_list[l], &need[l].count, n, false,
+                                        0, 0, nullptr, 0, s);
+            } else {
+                st = run_gather(c, l, false, 0, false, 0, s);
+                if (st == NRT_OK) st = run_update(c, l, c->need_list[l], n, &need[l].count, false, 0, nullptr, 0, false, s);
+                if (st == NRT_OK && has_message_cache(c->kind) && l < c->L)
+                    st = run_transform(c, l, c->need_list[l], n, &need[l].count, nullptr, false, s);
+            }
+            c->lc_use = nullptr;
+            NRT_TRY(st);
+        }
+        NRT_TRY(k_clear_listed_bits(c->stale[l], c->need_list[l], &need[l].count, n, s));
+        prev = cur;
+    }
+    return k_gather_rows_checked(q.rows, c->H[c->L], q.ids, q.n, n, c->dims[c->L], s);
+}
+
 extern "C" nrt_status nrt_set_lazy(nrt_cache* c, int32_t on, void* stream) {
     REQUIRE(c, "null argument");
     if (c->agg_only) {
@@ -1465,7 +1644,7 @@ extern "C" nrt_status nrt_set_lazy(nrt_cache* c, int32_t on, void* stream) {
     if (c->lazy && !on) {            // bring every stale vertex up to date before batches are applied eagerly again
         nrt_graph* g = c->g;
         const int64_t n = g->n;
-        NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
+        NRT_TRY(k_fill_u64((uint64_t*)c->lc, LC_TOTAL * sizeof(LayerCtrs) / 8, 0, s));
         for (int l = 1; l <= c->L; ++l)
             NRT_TRY(k_compact(nullptr, c->stale[l], nullptr, c->bm[0], n, c->list[l], nullptr, c->cmp_state, c->cmp_state_len,
                               &c->lc[l].count, s));
@@ -1486,7 +1665,7 @@ extern "C" nrt_status nrt_query(nrt_cache* c, const int32_t* query_ids, int64_t 
     const int64_t n = g->n;
     const int64_t nw = (n + 31) / 32;
     LayerCtrs* spare = &c->lc[NRT_MAX_LAYERS + 1];          // count = n_query for the final row gather; in_edges[0] = bad-id flag
-    NRT_TRY(k_fill_u64((uint64_t*)c->lc, (NRT_MAX_LAYERS + 2) * sizeof(LayerCtrs) / 8, 0, s));
+    NRT_TRY(k_fill_u64((uint64_t*)c->lc, LC_TOTAL * sizeof(LayerCtrs) / 8, 0, s));
     NRT_TRY(k_fill_u64(&spare->count, 1, (uint64_t)n_query, s));
     if (c->lazy) {
         // ---- which stale vertices do the queried embeddings depend on?  Backwards from the last layer:

@@ -121,6 +121,7 @@ struct CompactExtra {
     uint32_t* coarse;                 // coarse copy of the set for the sparse gather's LDS filter, or null
     int coarse_shift; int64_t coarse_words;
     uint64_t* err;                    // raised if a look-back wait gave up (device), or null
+    int and_invert;                   // intersect with the complement of and_mask instead
 };
 nrt_status k_compact(uint8_t* flags, const uint32_t* or_a, const uint32_t* or_b, uint32_t* out_bm, int64_t n,
                      int32_t* list, int32_t* slot, uint64_t* state, int64_t state_len, uint64_t* count, hipStream_t s,

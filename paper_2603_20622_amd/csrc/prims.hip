@@ -224,7 +224,7 @@ __global__ void __launch_bounds__(TPB) compact_kernel(CompactArgs a) {
             bits = a.flags ? pack_flags(a.flags, wi, a.n) : 0u;
             if (a.or_a) bits |= a.or_a[wi];
             if (a.or_b) bits |= a.or_b[wi];
-            if (a.and_mask) bits &= a.and_mask[wi];
+            if (a.and_mask) bits &= a.x.and_invert ? ~a.and_mask[wi] : a.and_mask[wi];
             a.out_bm[wi] = bits;
         }
         w[j] = bits;

@@ -92,6 +92,14 @@ class Session:
         n = nb.nrt_query(self.cache, q, rows)
         return rows, n
 
+    def apply_query(self, batch, ids: np.ndarray):
+        """A batch and a query in one call (on-demand mode): (rows, n_affected, n_updated, n_recomputed)."""
+        db = batch if isinstance(batch, DeviceBatch) else DeviceBatch(batch)
+        q = _dev(np.asarray(ids, dtype=np.int32))
+        rows = torch.empty((len(ids), self.spec.dims[-1]), dtype=torch.float32, device="cuda")
+        na, nu, nr = nb.nrt_apply_batch_query(self.cache, db.struct, self.ids, q, rows)
+        return rows, na, nu, nr
+
     def profiling(self, on: bool):
         nb.nrt_set_profiling(self.cache, on)
 

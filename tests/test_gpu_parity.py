@@ -777,6 +777,83 @@ def test_on_demand_queries_match_oracle(S, oracle, kind):
 
 
 @pytest.mark.parametrize("kind", KINDS)
+def test_batches_served_with_a_query_match_oracle(S, oracle, kind):
+    """On-demand mode, a batch and a query in one call (Section IV-D): the rows returned equal a full recomputation on
+    the post-update snapshot, the affected list is the structural one, vertices that were up to date before the batch
+    are folded rather than recomputed (GCN, GraphSAGE, GIN, CommNet), and whatever mixture of folded, recomputed and
+    still stale vertices the calls leave behind, flushing it gives caches that eager incremental batches can build on."""
+    from paper_2603_20622_amd import binding as nb
+    n, e = 6000, 30000
+    src, dst, sampler = wl.rmat_graph(n, e, 202)
+    weighted = kind in WEIGHTED
+    w = wl.edge_weights(e, 202) if weighted else None
+    if kind == wl.GAT:
+        spec = wl.ModelSpec(kind, [16, 24, 24, 24], heads=2, head_dim=12)
+    else:
+        spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted, monet_kernels=20)
+    params = wl.make_params(spec, 202, bias=True)
+    x = wl.features(n, 16, 202)
+    stream = wl.BatchStream(n, src, dst, w, sampler, 16, 202)
+    ses = S.Session(spec, params, n, src, dst, w, x)
+    cur = (src, dst, w, x)
+    rng = np.random.default_rng(11)
+    folds = kind in (wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.COMMNET)
+    with pytest.raises(nb.NrtError) as ei:                           # only in on-demand mode
+        ses.apply_query(wl.empty_batch(16, weighted), np.array([1, 2], np.int32))
+    assert ei.value.status == nb.NRT_ERR_STATE
+    ses.lazy(True)
+    prev_aff = np.empty(0, np.int32)
+    folded = 0
+    for k in range(6):
+        b = stream.next_batch(int(rng.choice([0, 3, 8])), int(rng.choice([0, 3, 8])), int(rng.choice([0, 2])))
+        q = np.concatenate([rng.choice(n, 30, replace=False), prev_aff[:10], b.ins_dst[:3], b.del_dst[:3]]).astype(np.int32)
+        if k == 3:                                                   # a batch without a query in between: more stays stale
+            ses.apply(b, want_rows=False)
+            cur = oracle.apply_batch(n, *cur, b)
+            continue
+        rows, na, n_upd, n_rec = ses.apply_query(b, q)
+        cur = oracle.apply_batch(n, *cur, b)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
+        ids = ses.ids[:na].cpu().numpy()
+        assert np.array_equal(ids, sets[-1]), (kind, k)
+        ref = oracle.forward(spec, params, n, *cur)
+        assert_parity(kind, rows.cpu().numpy(), ref[-1][q], (kind, "batch+query", k))
+        assert 0 <= n_rec <= n_upd
+        folded += n_upd - n_rec
+        if k == 0 and b.n_edge_updates + len(b.feat_ids) > 0:
+            assert n_rec == (0 if folds else n_upd), (kind, n_rec, n_upd)   # nothing was stale before the first batch
+        prev_aff = ids
+    assert (folded > 0) == folds, (kind, folded)
+    # a query id out of range rejects the whole call: graph and stale marks as before
+    e_before = nb.nrt_graph_num_edges(ses.graph)
+    b_bad = stream.next_batch(4, 4, 1)
+    with pytest.raises(nb.NrtError) as ei:
+        ses.apply_query(b_bad, np.array([5, n + 3], np.int32))
+    assert ei.value.status == nb.NRT_ERR_INVALID_ARG and nb.nrt_graph_num_edges(ses.graph) == e_before
+    rows, na, _, _ = ses.apply_query(b_bad, np.array([5, 6], np.int32))      # the same batch is still applicable
+    cur = oracle.apply_batch(n, *cur, b_bad)
+    ref = oracle.forward(spec, params, n, *cur)
+    assert_parity(kind, rows.cpu().numpy(), ref[-1][[5, 6]], (kind, "after the rejected call"))
+    # an empty batch with a query is the query alone
+    rows, na, _, _ = ses.apply_query(wl.empty_batch(16, weighted), np.arange(50, dtype=np.int32))
+    assert na == 0
+    assert_parity(kind, rows.cpu().numpy(), ref[-1][:50], (kind, "empty batch + query"))
+    # everything, then back to eager maintenance on top of what the mixed calls left
+    rows, _ = ses.query(np.arange(n, dtype=np.int32))
+    assert_parity(kind, rows.cpu().numpy(), ref[-1], (kind, "all"))
+    ses.lazy(False)
+    for l in range(1, spec.n_layers + 1):
+        assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "flush", l))
+    for k in range(2):
+        b = stream.next_batch(6, 6, 2)
+        ses.apply(b)
+        cur = oracle.apply_batch(n, *cur, b)
+    ref = oracle.forward(spec, params, n, *cur)
+    for l in range(1, spec.n_layers + 1):
+        assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "eager again", l))
+
+
+@pytest.mark.parametrize("kind", KINDS)
 def test_two_runs_of_a_chain_give_identical_bits(S, oracle, kind):
     """Nothing on the batch path may depend on how the GPU schedules threads: the same chain applied to two fresh
     sessions must leave bit-identical caches and in-lists.  The batches put many updates on few destinations (runs of

@@ -83,14 +83,20 @@ def test_random_case(S, oracle, seed):
         if n_ins > (n * (n - 1) - len(stream.edges()[0])) // 2:
             n_ins = 0
         b = stream.next_batch(n_ins, n_del, min(n_feat, n))
-        na = ses.apply(b, want_rows=not lazy)
+        together = lazy and rng.random() < 0.5                   # the batch and its query in one call
+        q = rng.choice(n, min(n, 25), replace=False).astype(np.int32)
+        if together:
+            rows, na, n_upd, n_rec = ses.apply_query(b, q)
+            assert 0 <= n_rec <= n_upd, (seed, k)
+        else:
+            na = ses.apply(b, want_rows=not lazy)
         cur = oracle.apply_batch(n, *cur, b)
         sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
         ids = ses.ids[:na].cpu().numpy()
         assert np.array_equal(ids, sets[-1]), (seed, k)
         if lazy:
-            q = rng.choice(n, min(n, 25), replace=False).astype(np.int32)
-            rows, _ = ses.query(q)
+            if not together:
+                rows, _ = ses.query(q)
             ref = oracle.forward(spec, params, n, *cur)[-1]
             got = rows.cpu().numpy()
             err = row_err(got, ref[q]) if kind in UNNORMALISED else rel_err(got, ref[q])
