@@ -50,6 +50,16 @@ Readings taken where the paper is silent or garbled (the GPU path takes the same
   * GAT: z = x W viewed [heads][head_dim]; e_uv = LeakyReLU(a_dst . z_v + a_src . z_u)
     (destination first, as in Eq. 3); softmax over N(v) U {v}; heads concatenated; ELU on
     hidden layers.
+  * RGCN, RGAT (typed edges): every edge <u,v> carries one relation id r(u,v) in 0..R-1, held in the edge weight
+    array; an ordered pair of vertices has at most one edge, hence one relation.
+  * RGCN: its Table II row: message W_r h_u, count context, a_v = (1/|N(v)|) sum_u W_{r(u,v)} h_u with the count
+    taken over all in-neighbours (the row prints one nct_v, not one per relation), update sigma(W_o h_v + a_v);
+    a bias is added before sigma; an empty neighbourhood gives a_v = 0.
+  * RGAT: its Table II row: per relation r a projection z^r = W_r h, attention parameters a_r and a softmax group of
+    its own (the row's context is indexed by the relation of the edge), a_v = sum_u alpha_uv z^{r(u,v)}_u summed over
+    all in-edges, update sigma(a_v).  Logit, LeakyReLU, ELU and destination-first order as in the GAT reading; as
+    there, every softmax group also holds v itself (under that relation's projection), so no group is empty and a
+    vertex affected at layer l-1 stays affected at layer l.
   * A batch is a set applied atomically: inserted edges must be absent, deleted edges present.
 """
 from __future__ import annotations
@@ -62,7 +72,7 @@ from typing import List, Optional, Sequence
 import numpy as np
 from scipy.special import expit
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET, GGCN = 1, 2, 3, 4, 5, 6, 7, 8, 9
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET, GGCN, RGCN, RGAT = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "librtec_oracle.so")
@@ -250,6 +260,33 @@ def layer(spec, params, l: int, n: int, src, dst, w, x: np.ndarray) -> np.ndarra
         y = _act_relu(hmid) @ W[1]
         if b[1] is not None:
             y = y + b[1]
+    elif spec.kind == RGCN:
+        # Table II RGCN row: message W_r h_u, sum, divide by the neighbour count, update sigma(W_o h_v + a_v).
+        R, dout = spec.n_relations, W[0].shape[1]
+        rel = np.asarray(w).astype(np.int64)
+        cnt = np.bincount(dst, minlength=n).astype(np.float64)
+        s = np.zeros((n, dout))
+        for r in range(R):
+            sel = rel == r
+            s += in_sum(n, src[sel], dst[sel], None, x @ W[1][:, r * dout:(r + 1) * dout])
+        a = np.where(cnt[:, None] > 0, s / np.maximum(cnt, 1.0)[:, None], 0.0)
+        y = x @ W[0] + a
+        if b[0] is not None:
+            y = y + b[0]
+    elif spec.kind == RGAT:
+        # Table II RGAT row: one attention softmax per relation (Eq. 3-4 on the edges of that relation), outputs summed.
+        R, hd = spec.n_relations, spec.head_dim
+        rel = np.asarray(w).astype(np.int64)
+        y = np.zeros((n, hd))
+        for r in range(R):
+            sel = rel == r
+            z = x @ W[0][:, r * hd:(r + 1) * hd]
+            a_s = z @ _f64(params.att_src[l - 1])[r]
+            a_d = z @ _f64(params.att_dst[l - 1])[r]
+            y += gat_attend(n, src[sel], dst[sel], 1, hd, z, a_s[:, None], a_d[:, None], spec.leaky_slope)
+        if b[0] is not None:
+            y = y + b[0]
+        return y if last else _elu(y)
     elif spec.kind == GAT:
         # Eq. 3-4 / Algorithm 2.
         H, hd = spec.heads, spec.head_dim

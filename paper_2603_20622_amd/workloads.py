@@ -18,13 +18,15 @@ from typing import Dict, List, Optional
 
 import numpy as np
 
-GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET, GGCN = 1, 2, 3, 4, 5, 6, 7, 8, 9
-KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage", AGNN: "agnn", MONET: "monet", GGCN: "ggcn"}
+GCN, SAGE_MEAN, GIN, GAT, COMMNET, PINSAGE, AGNN, MONET, GGCN, RGCN, RGAT = 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11
+KIND_NAMES = {GCN: "gcn", SAGE_MEAN: "sage_mean", GIN: "gin", GAT: "gat", COMMNET: "commnet", PINSAGE: "pinsage", AGNN: "agnn", MONET: "monet", GGCN: "ggcn",
+              RGCN: "rgcn", RGAT: "rgat"}
+RELATIONAL = (RGCN, RGAT)           # typed edges: the edge weight array holds the relation id of every edge
 
 
 @dataclass
 class ModelSpec:
-    """Shape of an L-layer GNN.  dims = [d_0, ..., d_L] (GAT: heads*head_dim for l>=1)."""
+    """Shape of an L-layer GNN.  dims = [d_0, ..., d_L] (GAT: heads*head_dim for l>=1; RGAT: head_dim for l>=1)."""
     kind: int
     dims: List[int]
     heads: int = 1
@@ -35,6 +37,7 @@ class ModelSpec:
     agnn_beta: float = 1.0          # A-GNN: the scalar in front of the cosine (the same at every layer)
     monet_kernels: int = 0          # MoNet: Gaussian kernels per layer (the width of its aggregate)
     agg_only: bool = False          # GCN: keep only the aggregates of hidden layers (storage option of the cache)
+    n_relations: int = 0            # RGCN, RGAT: number of edge types (relation ids are 0 .. n_relations-1)
 
     @property
     def n_layers(self) -> int:
@@ -130,6 +133,13 @@ def edge_weights(e: int, seed: int = 0) -> np.ndarray:
     return np.random.default_rng([seed, 31]).random(e, dtype=np.float32)
 
 
+def relation_ids(e: int, n_relations: int, seed: int = 0) -> np.ndarray:
+    """One relation id per edge, as the float32 edge weight array carries it; skewed like real typed graphs
+    (relation r is about twice as frequent as relation r+1)."""
+    p = 0.5 ** np.arange(n_relations)
+    return np.random.default_rng([seed, 37]).choice(n_relations, size=e, p=p / p.sum()).astype(np.float32)
+
+
 def _glorot(rng, fan_in: int, fan_out: int, shape) -> np.ndarray:
     lim = np.sqrt(6.0 / (fan_in + fan_out))
     return rng.uniform(-lim, lim, size=shape).astype(np.float32)
@@ -151,9 +161,15 @@ def make_params(spec: ModelSpec, seed: int = 0, bias: bool = False) -> Params:
             Ws.append(_glorot(rng, din, din, (din, din)))
         if spec.kind == GGCN:                                   # [W_1; W_2], the gate's two projections
             Ws.append(_glorot(rng, 2 * din, din, (2 * din, din)))
+        if spec.kind == RGCN:                                   # W[0] = W_o; W[1] = [W_0 | ... | W_{R-1}], one column block per relation
+            Ws.append(_glorot(rng, din, dout, (din, spec.n_relations * dout)))
+        if spec.kind == RGAT:                                   # W[0] = [W_0 | ... | W_{R-1}], each d_in x head_dim
+            Ws = [_glorot(rng, din, spec.head_dim, (din, spec.n_relations * spec.head_dim))]
         bs: List[Optional[np.ndarray]] = []
-        for W in Ws:
-            bs.append(rng.uniform(-0.1, 0.1, size=W.shape[1]).astype(np.float32) if bias else None)
+        for i, W in enumerate(Ws):
+            width = dout if spec.kind == RGAT else W.shape[1]
+            with_bias = bias and not (spec.kind == RGCN and i == 1)     # relation messages carry no bias
+            bs.append(rng.uniform(-0.1, 0.1, size=width).astype(np.float32) if with_bias else None)
         p.W.append(Ws)
         p.b.append(bs)
         if spec.kind == MONET:
@@ -163,9 +179,10 @@ def make_params(spec: ModelSpec, seed: int = 0, bias: bool = False) -> Params:
         else:
             p.monet_mu.append(None)
             p.monet_prec.append(None)
-        if spec.kind == GAT:
-            p.att_src.append(_glorot(rng, 2 * spec.head_dim, 1, (spec.heads, spec.head_dim)))
-            p.att_dst.append(_glorot(rng, 2 * spec.head_dim, 1, (spec.heads, spec.head_dim)))
+        if spec.kind in (GAT, RGAT):
+            groups = spec.heads if spec.kind == GAT else spec.n_relations
+            p.att_src.append(_glorot(rng, 2 * spec.head_dim, 1, (groups, spec.head_dim)))
+            p.att_dst.append(_glorot(rng, 2 * spec.head_dim, 1, (groups, spec.head_dim)))
         else:
             p.att_src.append(None)
             p.att_dst.append(None)
@@ -178,8 +195,9 @@ class BatchStream:
     disjoint, feature replacements hit distinct vertices."""
 
     def __init__(self, n: int, src: np.ndarray, dst: np.ndarray, w: Optional[np.ndarray],
-                 sampler: EdgeSampler, d0: int, seed: int = 0):
+                 sampler: EdgeSampler, d0: int, seed: int = 0, n_relations: int = 0):
         self.n = n
+        self.n_relations = n_relations          # > 0: w holds relation ids and inserted edges draw one
         keys = src.astype(np.int64) * n + dst.astype(np.int64)
         order = np.argsort(keys, kind="stable")
         self.keys = keys[order]
@@ -216,6 +234,8 @@ class BatchStream:
             ins_keys = merged[np.sort(first)]            # keep draw order, drop duplicates
         ins_keys = ins_keys[:n_ins]
         ins_w = rng.random(n_ins, dtype=np.float32) if self.w is not None else None
+        if self.w is not None and self.n_relations:
+            ins_w = rng.integers(0, self.n_relations, size=n_ins).astype(np.float32)
         feat_ids = rng.choice(self.n, size=n_feat, replace=False).astype(np.int32) if n_feat else \
             np.empty(0, dtype=np.int32)
         feat_rows = rng.standard_normal((n_feat, self.d0), dtype=np.float32)
@@ -293,8 +313,11 @@ def build(wl: Workload, seed: int = 0):
     """Graph, features, parameters and a batch stream for a workload."""
     src, dst, sampler = rmat_graph(wl.n, wl.e, seed)
     w = edge_weights(wl.e, seed) if wl.spec.weighted else None
+    if wl.spec.kind in RELATIONAL:
+        w = relation_ids(wl.e, wl.spec.n_relations, seed)
     x = features(wl.n, wl.spec.dims[0], seed)
     params = make_params(wl.spec, seed)
     ins_sampler = EdgeSampler(wl.n, sampler.perm, uniform=wl.uniform_inserts)
-    stream = BatchStream(wl.n, src, dst, w, ins_sampler, wl.spec.dims[0], seed)
+    stream = BatchStream(wl.n, src, dst, w, ins_sampler, wl.spec.dims[0], seed,
+                         wl.spec.n_relations if wl.spec.kind in RELATIONAL else 0)
     return src, dst, w, x, params, stream

@@ -1,7 +1,7 @@
 """Pins for the CPU oracle: things other than the oracle itself that fix its values.
 
   * brute force: a per-vertex recursive evaluation of the message-aggregate-update layer (Eq. 1)
-    from hand-written adjacency lists, in Python floats, for all nine models;
+    from hand-written adjacency lists, in Python floats, for all eleven models;
   * the dense-matrix closed forms the models reduce to (normalised adjacency products);
   * closed forms on special graphs / parameters (cycle, constant features, zero attention,
     two-term softmax, star hub);
@@ -18,6 +18,7 @@ import pytest
 from paper_2603_20622_amd import workloads as wl
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+ALL_KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN, wl.RGCN, wl.RGAT]
 
 
 # ------------------------------------------------------------------ brute force from adjacency lists
@@ -99,6 +100,35 @@ def brute_embedding(spec, params, in_nbrs, x, v, l):
                 tot[k] += hu[u][k]
         y = _lin(hv + tot, W[0], b[0])
         act = "relu"
+    elif spec.kind == wl.RGCN:
+        dout = len(W[0][0])
+        a = [0.0] * dout
+        for u, r in in_nbrs[v]:                                  # the second entry of a pair is the relation id
+            Wr = [row[int(r) * dout:(int(r) + 1) * dout] for row in W[1]]
+            mu = _lin(hu[u], Wr)
+            for k in range(dout):
+                a[k] += mu[k] / len(in_nbrs[v])
+        own = _lin(hv, W[0], b[0])
+        y = [own[k] + a[k] for k in range(dout)]
+        act = "relu"
+    elif spec.kind == wl.RGAT:
+        hd = spec.head_dim
+        a_s, a_d = params.att_src[l - 1], params.att_dst[l - 1]
+        y = [0.0] * hd
+        for r in range(spec.n_relations):
+            Wr = [row[r * hd:(r + 1) * hd] for row in W[0]]
+            members = [v] + [u for u, rr in in_nbrs[v] if int(rr) == r]
+            zs = {u: _lin(hv if u == v else hu[u], Wr) for u in members}
+            ad = sum(float(a_d[r][c]) * zs[v][c] for c in range(hd))
+            ex = []
+            for u in members:
+                t = ad + sum(float(a_s[r][c]) * zs[u][c] for c in range(hd))
+                ex.append(math.exp(t if t > 0 else spec.leaky_slope * t))
+            for c in range(hd):
+                y[c] += sum(ex[i] / sum(ex) * zs[u][c] for i, u in enumerate(members))
+        if b[0] is not None:
+            y = [y[j] + float(b[0][j]) for j in range(hd)]
+        act = "elu"
     elif spec.kind == wl.GIN:
         t = [(1.0 + spec.gin_eps) * hv[k] for k in range(d)]
         for u, w in in_nbrs[v]:
@@ -145,9 +175,17 @@ def _tiny(kind, L, seed, bias=True):
     dst = np.array([e[1] for e in TINY_EDGES], dtype=np.int32)
     rng = np.random.default_rng(seed)
     w = rng.random(src.size, dtype=np.float32) if kind in (wl.GIN, wl.PINSAGE) else None
+    if kind in wl.RELATIONAL:
+        w = (np.arange(src.size) * 7 % 3).astype(np.float32)        # relation ids 0, 1, 2, all present, mixed per destination
     if kind == wl.GAT:
         dims = [3] + [4] * L
         spec = wl.ModelSpec(kind, dims, heads=2, head_dim=2)
+    elif kind == wl.RGAT:
+        dims = [3] + [4] * L
+        spec = wl.ModelSpec(kind, dims, head_dim=4, weighted=True, n_relations=3)
+    elif kind == wl.RGCN:
+        dims = [3, 5, 4, 2][: L + 1]
+        spec = wl.ModelSpec(kind, dims, weighted=True, n_relations=3)
     else:
         dims = [3, 5, 4, 2][: L + 1]
         spec = wl.ModelSpec(kind, dims, weighted=(kind in (wl.GIN, wl.PINSAGE)), agnn_beta=0.7, monet_kernels=4)
@@ -163,7 +201,7 @@ def _in_lists(n, src, dst, w):
     return lists
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN])
+@pytest.mark.parametrize("kind", ALL_KINDS)
 @pytest.mark.parametrize("L", [1, 2, 3])
 def test_forward_matches_brute_force(oracle, kind, L):
     n, src, dst, w, x, spec, params = _tiny(kind, L, seed=3 + L)
@@ -462,6 +500,119 @@ def test_ggcn_zero_gate_weights_halve_commnet_sum(oracle):
     np.testing.assert_allclose(got[:, 0], [0.0, 5 * 2 / (1 + math.exp(1.0))], rtol=1e-14)
 
 
+def test_rgcn_is_sum_of_relation_adjacency_products(oracle):
+    """h = ReLU(X W_o + D^-1 sum_r A_r X W_r + b) with D the in-degree over all relations."""
+    n, e, R = 45, 280, 3
+    src, dst, _ = wl.rmat_graph(n, e, seed=21)
+    rel = wl.relation_ids(e, R, 21)
+    assert len(set(rel.tolist())) == R
+    spec = wl.ModelSpec(wl.RGCN, [4, 5, 3], weighted=True, n_relations=R)
+    params = wl.make_params(spec, 12, bias=True)
+    f = lambda a: a.astype(np.float64)
+    deg = _dense_adj(n, src, dst).sum(axis=1)
+    assert (deg == 0).any()
+    h = f(wl.features(n, 4, 12))
+    x = h.copy()
+    for l in range(2):
+        dout = spec.dims[l + 1]
+        tot = np.zeros((n, dout))
+        for r in range(R):
+            Ar = _dense_adj(n, src[rel == r], dst[rel == r])
+            tot += Ar @ h @ f(params.W[l][1])[:, r * dout:(r + 1) * dout]
+        h = h @ f(params.W[l][0]) + tot / np.maximum(deg, 1)[:, None] + f(params.b[l][0])
+        if l == 0:
+            h = np.maximum(h, 0)
+    outs = oracle.forward(spec, params, n, src, dst, rel, x)
+    np.testing.assert_allclose(outs[1], h, rtol=1e-11, atol=1e-12)
+
+
+def test_rgcn_with_equal_relation_weights_is_graphsage(oracle):
+    """When every relation shares one matrix W_r = W_n the relation ids cannot matter and the layer is the
+    GraphSAGE-mean layer with the stacked weight [W_o; W_n]."""
+    n, e, R = 40, 230, 4
+    src, dst, _ = wl.rmat_graph(n, e, seed=22)
+    rel = wl.relation_ids(e, R, 22)
+    sage = wl.ModelSpec(wl.SAGE_MEAN, [5, 5, 5])
+    ps = wl.make_params(sage, 13, bias=True)
+    spec = wl.ModelSpec(wl.RGCN, [5, 5, 5], weighted=True, n_relations=R)
+    pr = wl.Params(W=[[ps.W[l][0][:5], np.tile(ps.W[l][0][5:], (1, R))] for l in range(2)],
+                   b=[[ps.b[l][0], None] for l in range(2)], att_src=[None] * 2, att_dst=[None] * 2,
+                   monet_mu=[None] * 2, monet_prec=[None] * 2)
+    x = wl.features(n, 5, 13)
+    a = oracle.forward(spec, pr, n, src, dst, rel, x)
+    b = oracle.forward(sage, ps, n, src, dst, None, x)
+    np.testing.assert_allclose(a[1], b[1], rtol=1e-11, atol=1e-12)
+    # and a permutation of the relation ids changes nothing then, while it does with distinct matrices
+    c = oracle.forward(spec, pr, n, src, dst, (rel + 1) % R, x)
+    np.testing.assert_allclose(c[1], a[1], rtol=1e-11, atol=1e-12)
+    pd = wl.make_params(spec, 14)
+    assert not np.allclose(oracle.forward(spec, pd, n, src, dst, rel, x)[1],
+                           oracle.forward(spec, pd, n, src, dst, (rel + 1) % R, x)[1])
+
+
+def test_rgcn_two_edges_by_hand(oracle):
+    """Edges 0 -> 2 (relation 1) and 1 -> 2 (relation 0); width 1; W_o = 3, W_0 = 2, W_1 = -5, bias 0.5.
+    h_2 = 3 x_2 + (2 x_1 - 5 x_0) / 2 + 0.5; vertices without in-edges: 3 x + 0.5."""
+    spec = wl.ModelSpec(wl.RGCN, [1, 1], weighted=True, n_relations=2)
+    params = wl.Params(W=[[np.array([[3.0]], np.float32), np.array([[2.0, -5.0]], np.float32)]],
+                       b=[[np.array([0.5], np.float32), None]], att_src=[None], att_dst=[None],
+                       monet_mu=[None], monet_prec=[None])
+    x = np.array([[0.25], [-1.5], [2.0]], np.float32)
+    out = oracle.forward(spec, params, 3, np.array([0, 1], np.int32), np.array([2, 2], np.int32),
+                         np.array([1.0, 0.0], np.float32), x)[0]
+    np.testing.assert_allclose(out[:, 0], [1.25, -4.0, 6.0 + (2 * -1.5 - 5 * 0.25) / 2 + 0.5], rtol=1e-14)
+
+
+def test_rgat_with_one_relation_is_single_head_gat(oracle):
+    n, e = 30, 150
+    src, dst, _ = wl.rmat_graph(n, e, seed=23)
+    gat = wl.ModelSpec(wl.GAT, [3, 4, 4], heads=1, head_dim=4)
+    pg = wl.make_params(gat, 15, bias=True)
+    spec = wl.ModelSpec(wl.RGAT, [3, 4, 4], head_dim=4, weighted=True, n_relations=1)
+    x = wl.features(n, 3, 15)
+    a = oracle.forward(spec, pg, n, src, dst, np.zeros(e, np.float32), x)
+    b = oracle.forward(gat, pg, n, src, dst, None, x)
+    np.testing.assert_allclose(a[1], b[1], rtol=1e-11, atol=1e-12)
+
+
+def test_rgat_zero_attention_is_sum_of_relation_means_with_self(oracle):
+    n, e, R = 28, 140, 3
+    src, dst, _ = wl.rmat_graph(n, e, seed=24)
+    rel = wl.relation_ids(e, R, 24)
+    spec = wl.ModelSpec(wl.RGAT, [3, 2], head_dim=2, weighted=True, n_relations=R)
+    params = wl.make_params(spec, 16)
+    params.att_src[0][:] = 0
+    params.att_dst[0][:] = 0
+    x = wl.features(n, 3, 16).astype(np.float64)
+    expect = np.zeros((n, 2))
+    for r in range(R):
+        A = _dense_adj(n, src[rel == r], dst[rel == r]) + np.eye(n)
+        expect += (A / A.sum(axis=1, keepdims=True)) @ (x @ params.W[0][0].astype(np.float64)[:, 2 * r:2 * r + 2])
+    out = oracle.forward(spec, params, n, src, dst, rel, x)[0]
+    np.testing.assert_allclose(out, expect, rtol=1e-12, atol=1e-13)
+
+
+def test_rgat_two_relations_by_hand(oracle):
+    """Edges 0 -> 2 (relation 0) and 1 -> 2 (relation 1); width 1; W_0 = 1, W_1 = 2; a_src = (2, 1), a_dst = (-1, 0.5);
+    slope 0.2.  Vertex 2 mixes {2, 0} under relation 0 and {2, 1} under relation 1, and the two results add."""
+    spec = wl.ModelSpec(wl.RGAT, [1, 1], head_dim=1, weighted=True, n_relations=2, leaky_slope=0.2)
+    params = wl.Params(W=[[np.array([[1.0, 2.0]], np.float32)]], b=[[None]],
+                       att_src=[np.array([[2.0], [1.0]], np.float32)], att_dst=[np.array([[-1.0], [0.5]], np.float32)],
+                       monet_mu=[None], monet_prec=[None])
+    x = np.array([[-1.5], [0.75], [0.5]], np.float32)
+    out = oracle.forward(spec, params, 3, np.array([0, 1], np.int32), np.array([2, 2], np.int32),
+                         np.array([0.0, 1.0], np.float32), x)[0]
+    lk = lambda t: t if t > 0 else 0.2 * t
+    # relation 0: z = x; logits self L(-0.5 + 1.0), from 0 L(-0.5 - 3.0)
+    e_s, e_0 = math.exp(lk(0.5)), math.exp(lk(-3.5))
+    r0 = (e_s * 0.5 + e_0 * -1.5) / (e_s + e_0)
+    # relation 1: z = 2x; logits self L(0.5*1.0 + 1*1.0), from 1 L(0.5*1.0 + 1*1.5)
+    f_s, f_1 = math.exp(lk(1.5)), math.exp(lk(2.0))
+    r1 = (f_s * 1.0 + f_1 * 1.5) / (f_s + f_1)
+    np.testing.assert_allclose(out[2, 0], r0 + r1, rtol=1e-14)
+    np.testing.assert_allclose(out[0, 0], -1.5 + -3.0, rtol=1e-14)     # no in-edges: itself under both relations
+
+
 def test_commnet_single_edge_by_hand(oracle):
     """Edge 0 -> 1, scalar feature, W_1 = 2, W_2 = -3:  h_0 = 2 x_0,  h_1 = 2 x_1 - 3 x_0."""
     spec = wl.ModelSpec(wl.COMMNET, [1, 1])
@@ -631,7 +782,7 @@ def test_affected_sets_hand_enumerated(oracle):
         assert [a.tolist() for a in got] == [[3, 4], [3, 4]]
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN])
+@pytest.mark.parametrize("kind", ALL_KINDS)
 def test_affected_sets_match_reachability_powers(oracle, kind):
     n, e = 70, 260
     src, dst, sampler = wl.rmat_graph(n, e, seed=12)
@@ -655,15 +806,20 @@ def test_affected_sets_match_reachability_powers(oracle, kind):
 
 
 # ------------------------------------------------------------------ invariants
-@pytest.mark.parametrize("kind", [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN])
+@pytest.mark.parametrize("kind", ALL_KINDS)
 def test_batch_invariants(oracle, kind):
     n, e = 200, 1500
     src, dst, sampler = wl.rmat_graph(n, e, seed=13)
-    weighted = kind in (wl.GIN, wl.PINSAGE)
+    weighted = kind in (wl.GIN, wl.PINSAGE) or kind in wl.RELATIONAL
     w = wl.edge_weights(e, 13) if weighted else None
-    spec = wl.ModelSpec(kind, [6, 8, 4], heads=2, head_dim=4 if kind == wl.GAT else 0, weighted=weighted, monet_kernels=8)
+    if kind in wl.RELATIONAL:
+        w = wl.relation_ids(e, 3, 13)
+    spec = wl.ModelSpec(kind, [6, 8, 4], heads=2, head_dim=4 if kind == wl.GAT else 0, weighted=weighted, monet_kernels=8,
+                        n_relations=3)
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [6, 8, 8], heads=2, head_dim=4)
+    if kind == wl.RGAT:
+        spec = wl.ModelSpec(kind, [6, 8, 8], head_dim=8, weighted=True, n_relations=3)
     params = wl.make_params(spec, 9)
     x = wl.features(n, 6, 9)
     base = oracle.forward(spec, params, n, src, dst, w, x)[-1]
@@ -675,7 +831,7 @@ def test_batch_invariants(oracle, kind):
     assert all(a.size == 0 for a in oracle.affected_sets(spec, n, s2, d2, eb))
 
     # a real batch: rows that changed value are inside the structural affected set
-    stream = wl.BatchStream(n, src, dst, w, sampler, 6, seed=2)
+    stream = wl.BatchStream(n, src, dst, w, sampler, 6, seed=2, n_relations=3 if kind in wl.RELATIONAL else 0)
     b = stream.next_batch(10, 10, 3)
     s3, d3, w3, x3 = oracle.apply_batch(n, src, dst, w, x, b)
     after = oracle.forward(spec, params, n, s3, d3, w3, x3)[-1]
