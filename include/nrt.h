@@ -51,7 +51,7 @@ typedef enum {
     NRT_ERR_UNSUPPORTED = 6  /* model shape outside what the kernels cover                            */
 } nrt_status;
 
-typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7, NRT_MONET = 8, NRT_GGCN = 9 } nrt_model_kind;
+typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7, NRT_MONET = 8, NRT_GGCN = 9, NRT_RGCN = 10 } nrt_model_kind;
 
 typedef struct nrt_graph nrt_graph;
 typedef struct nrt_cache nrt_cache;
@@ -83,6 +83,13 @@ typedef struct nrt_cache nrt_cache;
  *   NRT_GGCN      (Table II row G-GCN)  a_v = sum_{u in N(v)} sigmoid(x_u W_1 + x_v W_2) * x_u element by element, with
  *                 W[l][1] = [W_1; W_2] of shape [2 d_{l-1}][d_{l-1}];  h_v = act( a_v W[l][0] + b[l][0] ).  Constrained
  *                 like NRT_AGNN (the gate reads the destination's own row)
+ *   NRT_RGCN      (Table II row RGCN)  typed edges: the graph is weighted and the weight of edge <u,v> is its relation id
+ *                 r(u,v), an integer in [0, n_relations) stored as a float (an ordered pair of vertices has one edge, hence
+ *                 one relation).  W[l][1] = [W_0 | ... | W_{R-1}] of shape [d_{l-1}][R d_l], one column block per relation;
+ *                 a_v = (sum_{u in N(v)} x_u W_{r(u,v)}) / |N(v)|  (the count runs over all in-neighbours, a_v = 0 if there
+ *                 are none);  h_v = act( x_v W[l][0] + a_v + b[l][0] ),  W[l][0] = W_o is [d_{l-1}][d_l].
+ *                 n_relations * d_l <= 4096, vertices * n_relations < 2^31.  nrt_cache_init returns NRT_ERR_INVALID_ARG
+ *                 when an edge weight is not such an id, nrt_apply_batch NRT_ERR_BAD_BATCH for an inserted edge
  * W, b, att_* are device pointers, row-major [in][out] / [heads][head_dim]; b entries may be NULL (zero).
  * They are copied at nrt_cache_init.
  */
@@ -107,6 +114,7 @@ typedef struct {
                                            workspace; such a cache refuses nrt_get_layer for hidden layers,
                                            NRT_MODE_RECOMPUTE, NRT_MODE_FULL and the on-demand mode, whose kernels
                                            read those rows.                                                        */
+    int32_t n_relations;                /* RGCN only: number of edge types R                                        */
 } nrt_model_desc;
 
 /*

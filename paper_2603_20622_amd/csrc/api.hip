@@ -60,6 +60,7 @@ struct nrt_cache {
     float* MP[NRT_MAX_LAYERS + 1];      // PinSAGE, MoNet: message payload of layer l's rows (ReLU(h^l Q + q); the Gaussian
                                         // kernel responses of h^l), null otherwise
     int monet_J;                        // MoNet: kernels per layer = width of its payload and aggregate
+    int n_rel;                          // RGCN: relations; MP[l] then holds n_rel message rows W_r h^l per vertex
     float* muT[NRT_MAX_LAYERS];         // MoNet: [d_l][J] transposed means / precisions of layer l+1
     float* precT[NRT_MAX_LAYERS];
     float* Wt[NRT_MAX_LAYERS][2];
@@ -325,15 +326,15 @@ extern "C" nrt_status nrt_graph_export_csc_static(const nrt_graph* g, int64_t* i
 static inline bool concat_self(int kind) { return kind == NRT_SAGE_MEAN || kind == NRT_COMMNET || kind == NRT_PINSAGE; }
 
 // models that aggregate a per-vertex transform of h instead of h itself, cached by vertex
-static inline bool has_message_cache(int kind) { return kind == NRT_PINSAGE || kind == NRT_MONET; }
+static inline bool has_message_cache(int kind) { return kind == NRT_PINSAGE || kind == NRT_MONET || kind == NRT_RGCN; }
 // constrained models served by the kernels of agnn.hip
 static inline bool agnn_family(int kind) { return kind == NRT_AGNN || kind == NRT_GGCN; }
-// models whose messages carry the edge weight
-static inline bool weighted_messages(int kind) { return kind == NRT_GIN || kind == NRT_PINSAGE; }
+// models whose messages read the edge weight (RGCN: as the relation id)
+static inline bool weighted_messages(int kind) { return kind == NRT_GIN || kind == NRT_PINSAGE || kind == NRT_RGCN; }
 
 static nrt_status check_desc(const nrt_model_desc* d) {
     REQUIRE(d, "model desc is null");
-    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_GGCN, "unknown model kind");
+    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_RGCN, "unknown model kind");
     REQUIRE(d->n_layers >= 1 && d->n_layers <= NRT_MAX_LAYERS, "n_layers out of range");
     for (int l = 0; l <= d->n_layers; ++l) {
         if (d->dims[l] <= 0 || d->dims[l] % 4 || d->dims[l] > 1024) {
@@ -344,6 +345,17 @@ static nrt_status check_desc(const nrt_model_desc* d) {
     if (d->kind == NRT_MONET && (d->monet_kernels < 4 || d->monet_kernels % 4 || d->monet_kernels > 1024)) {
         nrt_set_error("MoNet needs monet_kernels a multiple of 4 in [4, 1024]");
         return NRT_ERR_UNSUPPORTED;
+    }
+    if (d->kind == NRT_RGCN) {
+        if (d->n_relations < 1 || d->n_relations > 64) {
+            nrt_set_error("RGCN needs n_relations in [1, 64]");
+            return NRT_ERR_UNSUPPORTED;
+        }
+        for (int l = 1; l <= d->n_layers; ++l)
+            if ((int64_t)d->n_relations * d->dims[l] > 4096) {
+                nrt_set_error("RGCN: n_relations * layer width must not exceed 4096");
+                return NRT_ERR_UNSUPPORTED;
+            }
     }
     if (d->agg_only && d->kind != NRT_GCN) {
         nrt_set_error("aggregate-only storage is available for GCN");
@@ -370,6 +382,8 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     int maxd = 0;
     for (int l = 0; l <= c->L; ++l) maxd = c->dims[l] > maxd ? c->dims[l] : maxd;
     if (c->kind == NRT_MONET && c->monet_J > maxd) maxd = c->monet_J;
+    if (c->kind == NRT_RGCN)                 // the message deltas of a changed row are n_rel rows of the next layer's width
+        for (int l = 1; l <= c->L; ++l) maxd = c->n_rel * c->dims[l] > maxd ? c->n_rel * c->dims[l] : maxd;
     c->maxd = maxd;
     for (int l = 0; l <= c->L; ++l) {
         const bool hidden = l >= 1 && l < c->L;
@@ -380,6 +394,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     for (int l = 0; l <= c->L; ++l) {
         c->MP[l] = nullptr;
         if (c->kind == NRT_PINSAGE && l < c->L) c->MP[l] = b.take<float>(n * c->dims[l]);
+        if (c->kind == NRT_RGCN && l < c->L) c->MP[l] = b.take<float>(n * c->n_rel * c->dims[l + 1]);
         if (c->kind == NRT_MONET && l < c->L) {
             c->MP[l] = b.take<float>(n * c->monet_J);
             c->muT[l] = b.take<float>((size_t)c->dims[l] * c->monet_J);
@@ -398,7 +413,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->S[0] = nullptr;
     const bool gat = c->kind == NRT_GAT;
     for (int l = 1; l <= c->L; ++l) {
-        c->dagg[l] = gat ? c->dims[l] : (c->kind == NRT_MONET ? c->monet_J : c->dims[l - 1]);
+        c->dagg[l] = (gat || c->kind == NRT_RGCN) ? c->dims[l] : (c->kind == NRT_MONET ? c->monet_J : c->dims[l - 1]);
         c->S[l] = b.take<float>(n * c->dagg[l]);
         if (gat) {
             c->Z[l] = b.take<float>(n * c->dims[l]);
@@ -437,6 +452,9 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         } else if (c->kind == NRT_PINSAGE || c->kind == NRT_GGCN) {
             c->Wt[l][1] = b.take<float>((size_t)c->dims[l] * c->dims[l]);
             c->bias[l][1] = b.take<float>(c->dims[l]);
+        } else if (c->kind == NRT_RGCN) {                      // the relation matrices side by side, transposed
+            c->Wt[l][1] = b.take<float>((size_t)c->dims[l] * c->n_rel * c->dims[l + 1]);
+            c->bias[l][1] = nullptr;
         } else {
             c->Wt[l][1] = nullptr;
             c->bias[l][1] = nullptr;
@@ -513,6 +531,7 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     for (int l = 0; l < c->L; ++l) c->agnn_beta[l] = d->agnn_beta[l];
     c->agg_only = d->agg_only ? 1 : 0;
     c->monet_J = d->kind == NRT_MONET ? d->monet_kernels : 0;
+    c->n_rel = d->kind == NRT_RGCN ? d->n_relations : 0;
     c->max_edges = max_edges;
     c->max_feats = max_feats;
     return NRT_OK;
@@ -541,7 +560,8 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
 // what the in-neighbours of layer l+1 aggregate: h^l itself, or its transform for PinSAGE
 static inline const float* payload_rows(const nrt_cache* c, int l) { return has_message_cache(c->kind) ? c->MP[l] : c->H[l]; }
 
-// PinSAGE, MoNet (Table II): the message of a vertex (ReLU(h^l Q + q); Gaussian kernel responses of h^l) on the listed rows
+// PinSAGE, MoNet, RGCN (Table II): the message of a vertex (ReLU(h^l Q + q); Gaussian kernel responses of h^l; W_r h^l
+// for every relation r) on the listed rows
 // (null: all n rows); with `dp` the compact rows new - old that the gather of layer l+1 folds
 static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_t M, const uint64_t* M_dev, float* dp,
                                 bool skip_dp_when_large, hipStream_t s) {
@@ -573,6 +593,10 @@ static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_
     a.Wt = c->Wt[l][1];
     a.bias = c->bias[l][1];
     a.act = 1;
+    if (c->kind == NRT_RGCN) {             // h^l [W_0 | ... | W_{R-1}]: row v of the product is the R message rows of v
+        a.N = c->n_rel * c->dims[l + 1];
+        a.act = 0;
+    }
     a.H = c->MP[l];
     a.DP = dp;
     a.dp_skip_large = skip_dp_when_large;
@@ -593,6 +617,7 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
     a.in = g->in;
     a.D = c->dagg[l];
     a.use_weights = (weighted_messages(c->kind) && g->weighted) ? 1 : 0;
+    a.rel_R = c->n_rel;
     a.self_pair = c->kind == NRT_GCN;
     a.S = c->S[l];
     a.n_vertices = g->n;
@@ -664,6 +689,20 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.P0 = c->S[l];
         a.ldp = c->monet_J;
         a.K = c->monet_J;
+        a.Wt = c->Wt[l - 1][0];
+        a.bias = c->bias[l - 1][0];
+        a.act = last ? 0 : 1;
+        a.H = c->H[l];
+        a.n_vertices = g->n;
+        a.out_compact = last ? out_rows : nullptr;
+        a.out_cap = out_cap;
+        NRT_TRY(k_gemm(a, s));
+    } else if (c->kind == NRT_RGCN) {       // sigma(W_o h_v + a_v), a_v = cached sum of relation messages / neighbour count
+        a.a_mode = A_PLAIN_ADD;
+        a.P0 = c->H[l - 1];
+        a.K = c->dims[l - 1];
+        a.add = c->S[l];
+        a.add_indeg = g->in.deg;
         a.Wt = c->Wt[l - 1][0];
         a.bias = c->bias[l - 1][0];
         a.act = last ? 0 : 1;
@@ -984,11 +1023,16 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     NRT_TRY(nrt_cache_workspace_bytes(g, d, max_batch_edges, max_batch_feats, &need));
     REQUIRE(workspace_bytes >= need, "cache workspace too small");
     if (g->has_cache) { nrt_set_error("graph already has a cache"); return NRT_ERR_STATE; }
+    if (d->kind == NRT_RGCN) {
+        REQUIRE(g->weighted, "RGCN needs a weighted graph: the edge weights are the relation ids");
+        REQUIRE(g->n * d->n_relations <= (int64_t)INT32_MAX, "RGCN: vertices * relations must fit 31 bits");
+    }
     for (int l = 0; l < d->n_layers; ++l) {
         REQUIRE(d->W[l][0], "W[l][0] is null");
         if (d->kind == NRT_GIN) REQUIRE(d->W[l][1], "GIN needs W[l][1]");
         if (d->kind == NRT_PINSAGE) REQUIRE(d->W[l][1], "PinSAGE needs W[l][1]");
         if (d->kind == NRT_GGCN) REQUIRE(d->W[l][1], "G-GCN needs W[l][1] = [W_1; W_2]");
+        if (d->kind == NRT_RGCN) REQUIRE(d->W[l][1], "RGCN needs W[l][1] = [W_0 | ... | W_{R-1}]");
         if (d->kind == NRT_MONET) REQUIRE(d->monet_mu[l] && d->monet_prec[l], "MoNet needs monet_mu[l] and monet_prec[l]");
         if (d->kind == NRT_GAT) REQUIRE(d->att_src[l] && d->att_dst[l], "GAT needs att_src[l] and att_dst[l]");
     }
@@ -1031,6 +1075,8 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
                 NRT_TRY(k_copy_f32(c->att_src[l], d->att_src[l], (int64_t)c->heads * c->head_dim, s));
                 NRT_TRY(k_copy_f32(c->att_dst[l], d->att_dst[l], (int64_t)c->heads * c->head_dim, s));
             }
+            if (c->kind == NRT_RGCN)
+                NRT_TRY(k_transpose(d->W[l][1], c->Wt[l][1], c->dims[l], c->n_rel * c->dims[l + 1], s));
             if (c->kind == NRT_GIN || c->kind == NRT_PINSAGE) {
                 const int dq = c->kind == NRT_GIN ? c->dims[l + 1] : c->dims[l];
                 NRT_TRY(k_transpose(d->W[l][1], c->Wt[l][1], dq, dq, s));
@@ -1040,6 +1086,16 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         }
         for (int l = 1; l <= c->L; ++l)
             if (c->stale[l]) NRT_TRY(k_fill_u32(c->stale[l], (n + 31) / 32, 0, s));
+        if (c->n_rel) {                                        // typed edges: every edge weight must be a relation id
+            int32_t* bad = (int32_t*)(g->dev_ctrs + CTR_ERR) + 7;
+            NRT_TRY(k_fill_u32((uint32_t*)bad, 1, 0, s));
+            NRT_TRY(k_check_list_relations(g->in, n, c->n_rel, bad, s));
+            NRT_TRY(read_ctrs(g, s));
+            if (((const int32_t*)(g->host_pinned + CTR_ERR))[7]) {
+                nrt_set_error("an edge weight is not a relation id in [0, n_relations)");
+                return NRT_ERR_INVALID_ARG;
+            }
+        }
         NRT_TRY(full_forward(c, s));
         HIP_TRY(hipStreamSynchronize(s));
         return NRT_OK;
@@ -1132,6 +1188,8 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
     // for the stream, so the queue never runs dry between validation and mutation.
     if (q.ids)                                                // the queried set; an id out of range rejects the call like a bad batch
         NRT_TRY(k_mark_ids(c->bm_q, q.ids, q.n, n, (int32_t*)(g->dev_ctrs + CTR_ERR) + 6, s));
+    if (c->n_rel)                                             // typed edges: the inserted edges' relation ids
+        NRT_TRY(k_check_relations(b->ins_w, b->n_ins, c->n_rel, (int32_t*)(g->dev_ctrs + CTR_ERR) + 7, s));
     HIP_TRY(hipMemcpyAsync(g->host_pinned, g->dev_ctrs, NRT_NCTRS * sizeof(int64_t), hipMemcpyDeviceToHost, s));
     HIP_TRY(hipEventRecord(c->ev_validated, s));
     const bool empty_batch = b->n_ins + b->n_del + b->n_feat == 0;
@@ -1207,6 +1265,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
         f.n_ins = b->n_ins; f.n_del = b->n_del;
         f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
         if (weighted_messages(c->kind) && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
+        f.rel_R = c->n_rel;
         if (c->agg_only && c->L > 1 && b->n_ins + b->n_del > 0) {
             // the hidden rows of the updated edges' sources are not kept: recompute them from the (old) aggregates
             const int64_t nops = b->n_ins + b->n_del;
@@ -1237,6 +1296,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
         else if (err[5]) msg = "feature id repeated inside the batch";
         else if (err[2]) msg = "inserted edge already present";
         else if (err[3]) msg = "deleted edge not present";
+        else if (err[7]) msg = "relation id of an inserted edge out of range";
         nrt_status bad = NRT_OK;
         if (msg) { nrt_set_error("%s", msg); bad = NRT_ERR_BAD_BATCH; }
         else if (err[6]) { nrt_set_error("query id out of range"); bad = NRT_ERR_INVALID_ARG; }

@@ -131,6 +131,9 @@ nrt_status k_gather_rows_checked(float* dst, const float* src, const int32_t* id
                                  hipStream_t s);
 // bm |= ids; an id outside [0, n) sets *bad (device) instead
 nrt_status k_mark_ids(uint32_t* bm, const int32_t* ids, int64_t n_ids, int64_t n, int32_t* bad, hipStream_t s);
+// typed edges: *bad = 1 when a weight is not an integer relation id in [0, R) (w: a plain array; a: the live list entries)
+nrt_status k_check_relations(const float* w, int64_t count, int R, int32_t* bad, hipStream_t s);
+nrt_status k_check_list_relations(const Adj& a, int64_t n, int R, int32_t* bad, hipStream_t s);
 // bm &= ~(list[0 .. *count))
 nrt_status k_clear_listed_bits(uint32_t* bm, const int32_t* list, const uint64_t* count, int64_t bound, hipStream_t s);
 
@@ -169,6 +172,12 @@ struct HubWork {
     int64_t hub_cap, item_cap;
     float* partial;        // [item_cap][D] one partial row per item
 };
+// relation id held in an edge weight, clamped into [0, R) so that a bad id can never address outside the table
+__host__ __device__ inline int nrt_rel_of(float w, int R) {
+    int r = (int)w;
+    return r < 0 ? 0 : (r >= R ? R - 1 : r);
+}
+
 struct GatherArgs {
     const DstRec* recs;        // [*count]
     HubWork hubs;
@@ -181,6 +190,8 @@ struct GatherArgs {
     const uint64_t* n_src_dev; // number of changed sources; the launch does nothing when it is 0 (null: not checked)
     int src_scale_gcn;         // multiply each source row by 1/sqrt(indeg[u]+1) (full forward, GCN)
     int use_weights;           // multiply by the edge weight
+    int rel_R;                 // > 0 (RGCN): the edge weight holds a relation id r and source row i is row i * rel_R + r of P,
+                               // taken with coefficient 1 (P holds rel_R message rows per source)
     int self_pair;             // GCN: the destination's own row is one more neighbour
     int accumulate;            // 1: S[v] += sum, 0: S[v] = sum
     float* S;                  // [N][D]
@@ -251,6 +262,7 @@ struct FoldArgs {   // structural terms of a batch, evaluated on the pre-update 
     const int32_t* ord;
     const int32_t *ins_src, *ins_dst, *del_src, *del_dst;
     const float *ins_w, *del_w;  // null when unweighted
+    int rel_R;                   // > 0 (RGCN): the weights are relation ids and pick one of rel_R rows per source, coefficient 1
     int n_layers;                // blockIdx.y walks the layers
     const float* Hprev[NRT_MAX_LAYERS];   // h^{l-1} (old)
     float* SD[NRT_MAX_LAYERS];            // compact structural-delta rows, one per destination of an updated edge (plan slot)
@@ -270,7 +282,7 @@ struct DeltaArgs {  // layer-0 delta payloads and feature scatter
 nrt_status k_layer0_delta(const DeltaArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------- gemm.hip
-enum { A_PLAIN = 0, A_SCALE_GCN = 1, A_CONCAT_MEAN = 2, A_AXPY = 3 };
+enum { A_PLAIN = 0, A_SCALE_GCN = 1, A_CONCAT_MEAN = 2, A_AXPY = 3, A_PLAIN_ADD = 4 };
 struct GemmArgs {
     int64_t M; int K; int N;        // K = total inner width (CONCAT: 2*K0); M is a bound when M_dev is given
     const uint64_t* M_dev;          // number of rows on the device, or null
@@ -280,6 +292,8 @@ struct GemmArgs {
     int a_mode;
     const float* P0; const float* P1; int ldp;   // source rows (width ldp each)
     float axpy_c;                   // A_AXPY: c*P0 + P1
+    const float* add;               // A_PLAIN_ADD: before the activation y += add[v][:] / add_indeg[v] (RGCN: W_o h_v + mean message);
+    const int32_t* add_indeg;       // rows of width N by vertex; a zero count adds nothing; null add_indeg: the rows themselves
     const int32_t* indeg;           // for A_SCALE_GCN / A_CONCAT_MEAN
     const float* Wt;                // transposed weights [N][K]
     const float* bias;              // [N] or null

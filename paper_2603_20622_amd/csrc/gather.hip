@@ -183,6 +183,8 @@ __device__ inline void full_row(const GatherArgs& a, int32_t v, int64_t off, int
         float c = 1.0f;
         if (u >= 0 && a.use_weights) c = a.in.wts[off + jj];
         if (u >= 0 && a.full_scale_gcn) c *= gcn_scale(a.in.deg[u]);
+        int32_t ur = u;                                        // row of the source (relation-typed edges: one of its rel_R rows)
+        if (u >= 0 && a.rel_R) { ur = u * a.rel_R + nrt_rel_of(c, a.rel_R); c = 1.0f; }
         unsigned long long m = __ballot(u >= 0);
         while (m) {
             int32_t rr = -1;
@@ -192,7 +194,7 @@ __device__ inline void full_row(const GatherArgs& a, int32_t v, int64_t off, int
                 if (m) {
                     const int bit = __ffsll((long long)m) - 1;
                     m &= m - 1;
-                    const int32_t rs = __builtin_amdgcn_readlane(u, bit);
+                    const int32_t rs = __builtin_amdgcn_readlane(ur, bit);
                     const float cs = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, c), bit));
                     if (sub == t) { rr = rs; cc = cs; }
                 }
@@ -407,6 +409,10 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
             } else {
                 slC = uC;
                 if (COEF && a.src_scale_gcn && uC >= 0) cC *= gcn_scale((int32_t)xC);
+            }
+            if (COEF && a.rel_R) {                               // typed edge: the relation's row of the source, coefficient 1
+                if (slC >= 0) slC = slC * a.rel_R + nrt_rel_of(cC, a.rel_R);
+                cC = 1.0f;
             }
             if (i >= 2 && i - 2 < n_steps && a.accumulate) {
                 const int f = __builtin_amdgcn_readlane(t_flags, i - 2);
@@ -646,6 +652,13 @@ __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs
             int32_t sl[5];
 #pragma unroll
             for (int k = 0; k < 5; ++k) sl[k] = ((bw[k] >> (e[k] & 31)) & 1u) ? a.src_slot[(uint32_t)e[k]] : -1;
+            if (COEF && a.rel_R) {                               // typed edge: the relation's row of the source, coefficient 1
+#pragma unroll
+                for (int k = 0; k < 4; ++k) {
+                    if (sl[k] >= 0) sl[k] = sl[k] * a.rel_R + nrt_rel_of(wv[k], a.rel_R);
+                    wv[k] = 1.0f;
+                }
+            }
             // ---- pack the survivors of each group, in in-list order
             int32_t nq = 0;
 #pragma unroll

@@ -7,6 +7,8 @@
 //   A_CONCAT_MEAN  [ P0[v] || P1[v] / indeg(v) ]           (GraphSAGE: self row, mean = cached sum / count;
 //                                                           CommNet: indeg == nullptr, the cached sum itself)
 //   A_AXPY         c * P0[v] + P1[v]                       (GIN: (1+eps) x_v + cached weighted sum)
+//   A_PLAIN_ADD    P0[v], and add[v] / count(v) joins the product before the activation
+//                                                          (RGCN: W_o h_v + mean of the relation messages)
 // The epilogue is the cache write-back: it stores the new row into h^l[v] and, for the next layer, the
 // change of the source payload dp = y_new*cn - y_old*co (cn = co = 1 except for GCN, where the payload is
 // y / sqrt(d_v) and the degree may have changed), so no separate pass re-reads the rows.
@@ -36,7 +38,7 @@ __device__ inline void load_a(const GemmArgs& g, int64_t v, float sc, int k, boo
     const bool live = ok && k < g.K;
     const int kc = k < g.K ? k : g.K - 4;
     float m = 1.0f;
-    if (AMODE == A_PLAIN) {
+    if (AMODE == A_PLAIN || AMODE == A_PLAIN_ADD) {
         raw = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
     } else if (AMODE == A_SCALE_GCN) {
         raw = *reinterpret_cast<const float4*>(g.P0 + v * g.ldp + kc);
@@ -171,7 +173,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int rb = 0; rb < 16; rb += 4) {
             int64_t mrow[4], vrow[4];
-            float cn[4], co[4], oldv[4][TN];
+            float cn[4], co[4], oldv[4][TN], addv[4][AMODE == A_PLAIN_ADD ? TN : 1];
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = rb + rr;
@@ -180,10 +182,16 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
                 vrow[rr] = ok ? (g.rows ? (int64_t)g.rows[mrow[rr]] : mrow[rr]) : 0;
                 cn[rr] = 1.0f; co[rr] = 1.0f;
                 if (ok && DPout && g.dp_scale_gcn) { cn[rr] = gcn_scale(g.indeg[vrow[rr]]); co[rr] = gcn_scale(g.indeg_old[vrow[rr]]); }
+                float as = 0.f;                                   // scale of the row added before the activation
+                if (AMODE == A_PLAIN_ADD && ok) {
+                    as = 1.0f;
+                    if (g.add_indeg) { const int32_t dg = g.add_indeg[vrow[rr]]; as = dg > 0 ? 1.0f / (float)dg : 0.0f; }
+                }
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
                     const int n = col_base + (wn * TN + j) * 32 + l32;
                     const int nc = n < g.N ? n : g.N - 1;
+                    if (AMODE == A_PLAIN_ADD) addv[rr][j] = g.add[vrow[rr] * g.N + nc] * as;
                     if (g.H) oldv[rr][j] = DPout ? g.H[vrow[rr] * g.N + nc] : 0.f;   // vrow is 0 for rows past M: always in range
                     else oldv[rr][j] = (DPout && g.dp_no_h == 2) ? DPout[(ok ? mrow[rr] : 0) * g.N + nc] : 0.f;
                 }
@@ -196,6 +204,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
                     const int n = col_base + (wn * TN + j) * 32 + l32;
                     if (n >= g.N) continue;
                     float y = acc[i][j][rb + rr] + bias[j];
+                    if (AMODE == A_PLAIN_ADD) y += addv[rr][j];
                     if (g.act == 1) y = fmaxf(y, 0.f);
                     else if (g.act == 2) y = y > 0.f ? y : expm1f(y);
                     if (g.out_compact && mrow[rr] < g.out_cap) g.out_compact[mrow[rr] * g.N + n] = y;
@@ -242,6 +251,10 @@ nrt_status k_gemm(const GemmArgs& g, hipStream_t s) {
     case A_PLAIN: launch_gemm<A_PLAIN>(g, s); break;
     case A_SCALE_GCN: launch_gemm<A_SCALE_GCN>(g, s); break;
     case A_CONCAT_MEAN: launch_gemm<A_CONCAT_MEAN>(g, s); break;
+    case A_PLAIN_ADD:
+        if (!g.add) { nrt_set_error("gemm: the added rows are missing"); return NRT_ERR_INVALID_ARG; }
+        launch_gemm<A_PLAIN_ADD>(g, s);
+        break;
     default: launch_gemm<A_AXPY>(g, s); break;
     }
     LAUNCH_CHECK();

@@ -185,7 +185,12 @@ __global__ void structural_fold_kernel(FoldArgs a) {
                 if (is_del && a.del_w) c *= a.del_w[i];
                 if (!is_del && a.ins_w) c *= a.ins_w[i];
                 if (a.indeg_old) c *= 1.0f / sqrtf((float)(a.indeg_old[u] + 1));
-                const float4 x = *reinterpret_cast<const float4*>(a.Hprev[l] + (a.compact_src[l] ? (int64_t)op : (int64_t)u) * D + col);
+                int64_t row = a.compact_src[l] ? (int64_t)op : (int64_t)u;
+                if (a.rel_R) {                                   // typed edge: the relation's message row of the source
+                    row = (int64_t)u * a.rel_R + nrt_rel_of(is_del ? a.del_w[i] : a.ins_w[i], a.rel_R);
+                    c = is_del ? -1.0f : 1.0f;
+                }
+                const float4 x = *reinterpret_cast<const float4*>(a.Hprev[l] + row * D + col);
                 acc.x = fmaf(c, x.x, acc.x); acc.y = fmaf(c, x.y, acc.y); acc.z = fmaf(c, x.z, acc.z); acc.w = fmaf(c, x.w, acc.w);
             }
             *reinterpret_cast<float4*>(dst + col) = acc;

@@ -461,6 +461,43 @@ nrt_status k_exclusive_scan_u64(uint64_t* data, int64_t n, uint64_t* tmp, int64_
     return NRT_OK;
 }
 
+namespace {
+
+// relation ids held as edge weights: integers in [0, R); anything else raises *bad
+__device__ inline bool bad_relation(float w, int R) { return !(w >= 0.0f && w < (float)R && w == (float)(int)w); }
+
+__global__ void check_relations_kernel(const float* w, int64_t count, int R, int32_t* bad) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count && bad_relation(w[i], R)) *bad = 1;
+}
+
+// the same over the live entries of every adjacency list: one wave per vertex, strided
+__global__ void check_list_relations_kernel(Adj a, int64_t n, int R, int32_t* bad) {
+    const int lane = threadIdx.x & 63;
+    const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
+    for (int64_t v = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; v < n; v += waves) {
+        const int64_t off = a.off[v];
+        const int32_t deg = a.deg[v];
+        for (int32_t j = lane; j < deg; j += 64)
+            if (bad_relation(a.wts[off + j], R)) *bad = 1;
+    }
+}
+
+}  // namespace
+
+nrt_status k_check_relations(const float* w, int64_t count, int R, int32_t* bad, hipStream_t s) {
+    if (count <= 0) return NRT_OK;
+    check_relations_kernel<<<(int)cdiv(count, 256), 256, 0, s>>>(w, count, R, bad);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+nrt_status k_check_list_relations(const Adj& a, int64_t n, int R, int32_t* bad, hipStream_t s) {
+    if (n <= 0) return NRT_OK;
+    check_list_relations_kernel<<<grid_for(n * 64, 256, 4096), 256, 0, s>>>(a, n, R, bad);
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
 nrt_status k_mark_ids(uint32_t* bm, const int32_t* ids, int64_t n_ids, int64_t n, int32_t* bad, hipStream_t s) {
     if (n_ids <= 0) return NRT_OK;
     mark_ids_kernel<<<(int)cdiv(n_ids, 256), 256, 0, s>>>(bm, ids, n_ids, n, bad);

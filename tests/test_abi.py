@@ -78,8 +78,8 @@ def test_model_kinds_agree_between_header_generators_and_oracle():
     enum = re.search(r"typedef enum \{([^}]*)\} nrt_model_kind;", text).group(1)
     header = {k: int(v) for k, v in re.findall(r"(NRT_[A-Z_]+)\s*=\s*(\d+)", enum)}
     names = {"NRT_GCN": "GCN", "NRT_SAGE_MEAN": "SAGE_MEAN", "NRT_GIN": "GIN", "NRT_GAT": "GAT", "NRT_COMMNET": "COMMNET",
-             "NRT_PINSAGE": "PINSAGE", "NRT_AGNN": "AGNN", "NRT_MONET": "MONET", "NRT_GGCN": "GGCN"}
+             "NRT_PINSAGE": "PINSAGE", "NRT_AGNN": "AGNN", "NRT_MONET": "MONET", "NRT_GGCN": "GGCN", "NRT_RGCN": "RGCN"}
     assert set(header) == set(names)
     for c_name, py_name in names.items():
         assert header[c_name] == getattr(wl, py_name) == getattr(orc, py_name), c_name
-    assert sorted(header.values()) == list(range(1, 10))
+    assert sorted(header.values()) == list(range(1, len(names) + 1))

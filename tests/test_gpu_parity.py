@@ -67,21 +67,35 @@ def S():
 def small_case(kind, seed=0, n=3000, e=40000, dims=None, bias=False, L=2):
     src, dst, sampler = wl.rmat_graph(n, e, seed)
     weighted = kind in WEIGHTED
-    w = wl.edge_weights(e, seed) if weighted else None
+    w = edge_values(kind, e, seed)
     if dims is None:
         dims = [64, 128, 32] if L == 2 else [32, 64, 64, 16]
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [dims[0]] + [64] * L, heads=4, head_dim=16)
     else:
-        spec = wl.ModelSpec(kind, dims, weighted=weighted, monet_kernels=24)
+        spec = wl.ModelSpec(kind, dims, weighted=weighted, monet_kernels=24, n_relations=N_REL)
     params = wl.make_params(spec, seed, bias=bias)
     x = wl.features(n, dims[0], seed)
-    stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], seed)
+    stream = batch_stream(kind, n, src, dst, w, sampler, dims[0], seed)
     return n, src, dst, w, x, spec, params, stream
 
 
-KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN]
-WEIGHTED = (wl.GIN, wl.PINSAGE)           # models whose messages carry the edge weight
+KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN, wl.RGCN]
+WEIGHTED = (wl.GIN, wl.PINSAGE, wl.RGCN)  # models whose messages read the edge weight (RGCN: as the relation id)
+N_REL = 3                                 # relations of the typed-edge models in these tests
+
+
+def edge_values(kind, e, seed, rng=None):
+    """The weight array of a test graph: relation ids for the typed-edge models, weights in (0, 1) for GIN / PinSAGE."""
+    if kind in wl.RELATIONAL:
+        return wl.relation_ids(e, N_REL, seed) if rng is None else rng.integers(0, N_REL, e).astype(np.float32)
+    if kind in WEIGHTED:
+        return wl.edge_weights(e, seed) if rng is None else rng.random(e).astype(np.float32)
+    return None
+
+
+def batch_stream(kind, n, src, dst, w, sampler, d0, seed):
+    return wl.BatchStream(n, src, dst, w, sampler, d0, seed, N_REL if kind in wl.RELATIONAL else 0)
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -271,6 +285,8 @@ def test_gin_cancellation_is_guarded(S, oracle):
     (wl.AGNN, [300, 520, 8], 1, 0),             # cosine rows of two and of four 16-byte pieces per lane
     (wl.MONET, [36, 132, 8], 1, 0),             # 260 kernels: wider than every layer
     (wl.GGCN, [260, 36, 8], 1, 0),              # gate rows of two 16-byte pieces per lane
+    (wl.RGCN, [20, 132, 8], 1, 0),              # message rows of 132 floats, 3 x 132 per source
+    (wl.RGCN, [260, 12, 4], 1, 0),              # narrowest message rows
     (wl.GAT, [24, 512, 512], 8, 64),            # 512-wide attention rows, 8 heads
     (wl.GAT, [12, 8, 8], 2, 4),                 # smallest head width
 ])
@@ -278,11 +294,11 @@ def test_unusual_widths(S, oracle, kind, dims, heads, head_dim):
     n, e = 1500, 20000
     src, dst, sampler = wl.rmat_graph(n, e, 31)
     weighted = kind in WEIGHTED
-    w = wl.edge_weights(e, 31) if weighted else None
-    spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=head_dim, weighted=weighted, monet_kernels=260)
+    w = edge_values(kind, e, 31)
+    spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=head_dim, weighted=weighted, monet_kernels=260, n_relations=N_REL)
     params = wl.make_params(spec, 31, bias=True)
     x = wl.features(n, dims[0], 31)
-    stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], 31)
+    stream = batch_stream(kind, n, src, dst, w, sampler, dims[0], 31)
     ses = S.Session(spec, params, n, src, dst, w, x)
     ref = oracle.forward(spec, params, n, src, dst, w, x)
     for l in range(1, 3):
@@ -605,11 +621,11 @@ def test_in_degrees_at_the_item_boundaries(S, oracle, kind):
     _, first = np.unique(src.astype(np.int64) * n + dst, return_index=True)
     src, dst = src[np.sort(first)], dst[np.sort(first)]
     weighted = kind in WEIGHTED
-    w = rng.random(len(src)).astype(np.float32) if weighted else None
+    w = edge_values(kind, len(src), 0, rng)
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [12, 32, 32], heads=2, head_dim=16)
     else:
-        spec = wl.ModelSpec(kind, [12, 32, 8], weighted=weighted, monet_kernels=16)
+        spec = wl.ModelSpec(kind, [12, 32, 8], weighted=weighted, monet_kernels=16, n_relations=N_REL)
     params = wl.make_params(spec, 78, bias=True)
     x = wl.features(n, 12, 78)
     ses = S.Session(spec, params, n, src, dst, w, x, max_batch_edges=4096)
@@ -642,7 +658,7 @@ def test_in_degrees_at_the_item_boundaries(S, oracle, kind):
             new = [p for p in new if per.setdefault(p[1], 0) < 2 and not per.update({p[1]: per[p[1]] + 1})]
             b.ins_src = np.array([p[0] for p in new], np.int32); b.ins_dst = np.array([p[1] for p in new], np.int32)
             if weighted:
-                b.ins_w = rng.random(len(new)).astype(np.float32)
+                b.ins_w = edge_values(kind, len(new), 0, rng)
             have |= set(new)
         else:
             gone = []
@@ -716,14 +732,14 @@ def test_on_demand_queries_match_oracle(S, oracle, kind):
     n, e = 6000, 30000
     src, dst, sampler = wl.rmat_graph(n, e, 101)
     weighted = kind in WEIGHTED
-    w = wl.edge_weights(e, 101) if weighted else None
+    w = edge_values(kind, e, 101)
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [16, 24, 24, 24], heads=2, head_dim=12)
     else:
-        spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted, monet_kernels=20)
+        spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted, monet_kernels=20, n_relations=N_REL)
     params = wl.make_params(spec, 101, bias=True)
     x = wl.features(n, 16, 101)
-    stream = wl.BatchStream(n, src, dst, w, sampler, 16, 101)
+    stream = batch_stream(kind, n, src, dst, w, sampler, 16, 101)
     ses = S.Session(spec, params, n, src, dst, w, x)
     cur = (src, dst, w, x)
     rng = np.random.default_rng(7)
@@ -786,14 +802,14 @@ def test_batches_served_with_a_query_match_oracle(S, oracle, kind):
     n, e = 6000, 30000
     src, dst, sampler = wl.rmat_graph(n, e, 202)
     weighted = kind in WEIGHTED
-    w = wl.edge_weights(e, 202) if weighted else None
+    w = edge_values(kind, e, 202)
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [16, 24, 24, 24], heads=2, head_dim=12)
     else:
-        spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted, monet_kernels=20)
+        spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted, monet_kernels=20, n_relations=N_REL)
     params = wl.make_params(spec, 202, bias=True)
     x = wl.features(n, 16, 202)
-    stream = wl.BatchStream(n, src, dst, w, sampler, 16, 202)
+    stream = batch_stream(kind, n, src, dst, w, sampler, 16, 202)
     ses = S.Session(spec, params, n, src, dst, w, x)
     cur = (src, dst, w, x)
     rng = np.random.default_rng(11)
@@ -853,6 +869,33 @@ def test_batches_served_with_a_query_match_oracle(S, oracle, kind):
         assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "eager again", l))
 
 
+def test_typed_edges_reject_bad_relation_ids(S, oracle):
+    """RGCN reads the edge weight as a relation id: a weight that is not an integer in [0, R) is refused when the caches
+    are built, and in a batch it rejects the batch with graph and caches unchanged."""
+    from paper_2603_20622_amd import binding as nb
+    n, src, dst, w, x, spec, params, stream = small_case(wl.RGCN, seed=12, n=500, e=4000)
+    for bad_value in (float(N_REL), 0.5, -1.0):
+        wb = w.copy()
+        wb[1234] = bad_value
+        with pytest.raises(nb.NrtError) as ei:
+            S.Session(spec, params, n, src, dst, wb, x)
+        assert ei.value.status == nb.NRT_ERR_INVALID_ARG
+    ses = S.Session(spec, params, n, src, dst, w, x)
+    base = ses.layer(2).cpu().numpy().copy()
+    b = stream.next_batch(20, 20, 3)
+    good_w = b.ins_w.copy()
+    b.ins_w = good_w.copy()
+    b.ins_w[7] = float(N_REL)
+    with pytest.raises(nb.NrtError) as ei:
+        ses.apply(b)
+    assert ei.value.status == nb.NRT_ERR_BAD_BATCH
+    assert np.array_equal(ses.layer(2).cpu().numpy(), base)
+    b.ins_w = good_w
+    ses.apply(b)
+    cur = oracle.apply_batch(n, src, dst, w, x, b)
+    assert_parity(wl.RGCN, ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1], "after the rejected batch")
+
+
 @pytest.mark.parametrize("kind", KINDS)
 def test_two_runs_of_a_chain_give_identical_bits(S, oracle, kind):
     """Nothing on the batch path may depend on how the GPU schedules threads: the same chain applied to two fresh
@@ -865,7 +908,7 @@ def test_two_runs_of_a_chain_give_identical_bits(S, oracle, kind):
     outs = []
     for run in range(2):
         _, _, sampler = wl.rmat_graph(n, 30000, 31)
-        stream = wl.BatchStream(n, src, dst, w, sampler, spec.dims[0], seed=31)
+        stream = batch_stream(kind, n, src, dst, w, sampler, spec.dims[0], 31)
         ses = S.Session(spec, params, n, src, dst, w, x, max_batch_edges=4096, max_batch_feats=128)
         cur = (src, dst, w, x)
         for n_ins, n_del, n_feat in sizes:

@@ -15,6 +15,7 @@ from tests.test_gpu_parity import ELEMENTWISE_LOG, TOL, UNNORMALISED, rel_err, r
 pytestmark = pytest.mark.gpu
 
 KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN]
+TYPED = [wl.RGCN]                   # seeds from 90 on: the typed-edge models
 CONSTRAINED = (wl.GAT, wl.AGNN, wl.GGCN)
 
 
@@ -45,10 +46,10 @@ def _check_layers(S, oracle, ses, spec, params, n, cur, L, what):
     return ref
 
 
-@pytest.mark.parametrize("seed", range(90))
+@pytest.mark.parametrize("seed", range(102))
 def test_random_case(S, oracle, seed):
     rng = np.random.default_rng([seed, 2603])
-    kind = KINDS[seed % len(KINDS)]
+    kind = KINDS[seed % len(KINDS)] if seed < 90 else TYPED[(seed - 90) % len(TYPED)]
     n = int(rng.choice([60, 300, 2000, 6000]))
     e = int(min(n * (n - 1) // 4, n * int(rng.choice([1, 5, 15, 30]))))
     L = int(rng.integers(1, 4))
@@ -59,13 +60,16 @@ def test_random_case(S, oracle, seed):
     else:
         dims = [int(rng.choice([4, 8, 12, 32, 68, 128])) for _ in range(L + 1)]
     weighted = kind in (wl.GIN, wl.PINSAGE) and bool(rng.integers(0, 2))
+    n_rel = int(rng.choice([1, 2, 5])) if kind in wl.RELATIONAL else 0
     src, dst, sampler = wl.rmat_graph(n, e, seed)
     w = wl.edge_weights(e, seed) if weighted else None
+    if n_rel:
+        weighted, w = True, wl.relation_ids(e, n_rel, seed)
     spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=hd, weighted=weighted, agnn_beta=0.8,
-                        monet_kernels=int(rng.choice([4, 12, 40])))
+                        monet_kernels=int(rng.choice([4, 12, 40])), n_relations=n_rel)
     params = wl.make_params(spec, seed, bias=bool(rng.integers(0, 2)))
     x = wl.features(n, dims[0], seed)
-    stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], seed)
+    stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], seed, n_rel)
     ses = S.Session(spec, params, n, src, dst, w, x, max_batch_edges=16384, max_batch_feats=512)
     cur = (src, dst, w, x)
     _check_layers(S, oracle, ses, spec, params, n, cur, L, ("init", seed))
