@@ -51,7 +51,7 @@ typedef enum {
     NRT_ERR_UNSUPPORTED = 6  /* model shape outside what the kernels cover                            */
 } nrt_status;
 
-typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7, NRT_MONET = 8, NRT_GGCN = 9, NRT_RGCN = 10 } nrt_model_kind;
+typedef enum { NRT_GCN = 1, NRT_SAGE_MEAN = 2, NRT_GIN = 3, NRT_GAT = 4, NRT_COMMNET = 5, NRT_PINSAGE = 6, NRT_AGNN = 7, NRT_MONET = 8, NRT_GGCN = 9, NRT_RGCN = 10, NRT_RGAT = 11 } nrt_model_kind;
 
 typedef struct nrt_graph nrt_graph;
 typedef struct nrt_cache nrt_cache;
@@ -90,6 +90,13 @@ typedef struct nrt_cache nrt_cache;
  *                 are none);  h_v = act( x_v W[l][0] + a_v + b[l][0] ),  W[l][0] = W_o is [d_{l-1}][d_l].
  *                 n_relations * d_l <= 4096, vertices * n_relations < 2^31.  nrt_cache_init returns NRT_ERR_INVALID_ARG
  *                 when an edge weight is not such an id, nrt_apply_batch NRT_ERR_BAD_BATCH for an inserted edge
+ *   NRT_RGAT      (Table II row RGAT)  typed edges as for NRT_RGCN.  W[l][0] = [W_0 | ... | W_{R-1}] of shape
+ *                 [d_{l-1}][R head_dim], att_src[l] and att_dst[l] are [R][head_dim], dims[l] = head_dim for l >= 1.  Per
+ *                 relation r: z^r = x W_r, e_uv = LeakyReLU_slope(att_dst[l][r] . z^r_v + att_src[l][r] . z^r_u) and one
+ *                 softmax over { u in N(v) : r(u,v) = r } U {v} (as for NRT_GAT the self-loop is a member of every group);
+ *                 h_v = act( sum_r sum_u alpha^r_uv z^r_u + b[l][0] ), ELU on hidden layers.  R head_dim <= 1024.
+ *                 Constrained like NRT_GAT: where z of the destination changed its groups are recomputed (Algorithm 2),
+ *                 elsewhere Algorithm 3 exchanges terms inside the group of each changed edge
  * W, b, att_* are device pointers, row-major [in][out] / [heads][head_dim]; b entries may be NULL (zero).
  * They are copied at nrt_cache_init.
  */
@@ -97,13 +104,13 @@ typedef struct {
     int32_t kind;                       /* nrt_model_kind */
     int32_t n_layers;                   /* 1..NRT_MAX_LAYERS */
     int32_t dims[NRT_MAX_LAYERS + 1];   /* d_0..d_L */
-    int32_t heads, head_dim;            /* GAT only */
+    int32_t heads, head_dim;            /* GAT; RGAT reads head_dim (its groups are the relations) */
     float gin_eps;                      /* GIN only */
-    float leaky_slope;                  /* GAT only */
+    float leaky_slope;                  /* GAT, RGAT */
     const float* W[NRT_MAX_LAYERS][2];  /* device */
     const float* b[NRT_MAX_LAYERS][2];  /* device or NULL */
-    const float* att_src[NRT_MAX_LAYERS]; /* device, GAT only */
-    const float* att_dst[NRT_MAX_LAYERS]; /* device, GAT only */
+    const float* att_src[NRT_MAX_LAYERS]; /* device, GAT and RGAT */
+    const float* att_dst[NRT_MAX_LAYERS]; /* device, GAT and RGAT */
     float agnn_beta[NRT_MAX_LAYERS];    /* A-GNN only: the scalar of layer l+1 (host values) */
     int32_t monet_kernels;              /* MoNet only: J, a multiple of 4 in [4, 1024] */
     const float* monet_mu[NRT_MAX_LAYERS];   /* device, MoNet only */
@@ -114,7 +121,7 @@ typedef struct {
                                            workspace; such a cache refuses nrt_get_layer for hidden layers,
                                            NRT_MODE_RECOMPUTE, NRT_MODE_FULL and the on-demand mode, whose kernels
                                            read those rows.                                                        */
-    int32_t n_relations;                /* RGCN only: number of edge types R                                        */
+    int32_t n_relations;                /* RGCN, RGAT: number of edge types R                                       */
 } nrt_model_desc;
 
 /*

@@ -101,7 +101,8 @@ struct nrt_cache {
     float *att_src[NRT_MAX_LAYERS], *att_dst[NRT_MAX_LAYERS];
     float* AS_old;
     float *part_m, *part_den;
-    bool is_gat;
+    bool is_gat;                        // GAT or RGAT: the kernels of gat.hip serve the layer
+    int zdim;                           // their projected width heads * head_dim (RGAT: relations * head_dim, output head_dim)
     float* SD[NRT_MAX_LAYERS + 1];      // structural-delta rows of a batch, [max_edges][dagg[l]]
     float* SDden[NRT_MAX_LAYERS + 1];   // GAT: their attention-sum part, [max_edges][heads]
     int32_t* ins_cnt;                   // inserted in-edges per destination of an updated edge, [max_edges]
@@ -334,7 +335,7 @@ static inline bool weighted_messages(int kind) { return kind == NRT_GIN || kind 
 
 static nrt_status check_desc(const nrt_model_desc* d) {
     REQUIRE(d, "model desc is null");
-    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_RGCN, "unknown model kind");
+    REQUIRE(d->kind >= NRT_GCN && d->kind <= NRT_RGAT, "unknown model kind");
     REQUIRE(d->n_layers >= 1 && d->n_layers <= NRT_MAX_LAYERS, "n_layers out of range");
     for (int l = 0; l <= d->n_layers; ++l) {
         if (d->dims[l] <= 0 || d->dims[l] % 4 || d->dims[l] > 1024) {
@@ -345,6 +346,17 @@ static nrt_status check_desc(const nrt_model_desc* d) {
     if (d->kind == NRT_MONET && (d->monet_kernels < 4 || d->monet_kernels % 4 || d->monet_kernels > 1024)) {
         nrt_set_error("MoNet needs monet_kernels a multiple of 4 in [4, 1024]");
         return NRT_ERR_UNSUPPORTED;
+    }
+    if (d->kind == NRT_RGAT) {
+        if (d->n_relations < 1 || d->head_dim < 4 || d->head_dim % 4 || (int64_t)d->n_relations * d->head_dim > 1024) {
+            nrt_set_error("RGAT needs n_relations >= 1, head_dim a multiple of 4 and n_relations * head_dim <= 1024");
+            return NRT_ERR_UNSUPPORTED;
+        }
+        for (int l = 1; l <= d->n_layers; ++l)
+            if (d->dims[l] != d->head_dim) {
+                nrt_set_error("RGAT layer widths must equal head_dim");
+                return NRT_ERR_UNSUPPORTED;
+            }
     }
     if (d->kind == NRT_RGCN) {
         if (d->n_relations < 1 || d->n_relations > 64) {
@@ -384,6 +396,8 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     if (c->kind == NRT_MONET && c->monet_J > maxd) maxd = c->monet_J;
     if (c->kind == NRT_RGCN)                 // the message deltas of a changed row are n_rel rows of the next layer's width
         for (int l = 1; l <= c->L; ++l) maxd = c->n_rel * c->dims[l] > maxd ? c->n_rel * c->dims[l] : maxd;
+    c->zdim = c->heads * c->head_dim;
+    if (c->kind == NRT_RGAT && c->zdim > maxd) maxd = c->zdim;      // old z rows and partial rows are zdim wide
     c->maxd = maxd;
     for (int l = 0; l <= c->L; ++l) {
         const bool hidden = l >= 1 && l < c->L;
@@ -411,12 +425,12 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     }
     c->old_p1 = c->kind == NRT_GGCN ? b.take<float>(n * maxd) : nullptr;
     c->S[0] = nullptr;
-    const bool gat = c->kind == NRT_GAT;
+    const bool gat = c->kind == NRT_GAT || c->kind == NRT_RGAT;
     for (int l = 1; l <= c->L; ++l) {
-        c->dagg[l] = (gat || c->kind == NRT_RGCN) ? c->dims[l] : (c->kind == NRT_MONET ? c->monet_J : c->dims[l - 1]);
+        c->dagg[l] = gat ? c->zdim : (c->kind == NRT_RGCN ? c->dims[l] : (c->kind == NRT_MONET ? c->monet_J : c->dims[l - 1]));
         c->S[l] = b.take<float>(n * c->dagg[l]);
         if (gat) {
-            c->Z[l] = b.take<float>(n * c->dims[l]);
+            c->Z[l] = b.take<float>(n * c->zdim);
             c->AS[l] = b.take<float>(n * c->heads);
             c->AD[l] = b.take<float>(n * c->heads);
             c->M[l] = b.take<float>(n * c->heads);
@@ -444,7 +458,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->is_gat = gat;
     for (int l = 0; l < c->L; ++l) {
         const int kin = c->kind == NRT_MONET ? c->monet_J : (concat_self(c->kind) ? 2 : 1) * c->dims[l];
-        c->Wt[l][0] = b.take<float>((size_t)kin * c->dims[l + 1]);
+        c->Wt[l][0] = b.take<float>((size_t)kin * (gat ? c->zdim : c->dims[l + 1]));
         c->bias[l][0] = b.take<float>(c->dims[l + 1]);
         if (c->kind == NRT_GIN) {
             c->Wt[l][1] = b.take<float>((size_t)c->dims[l + 1] * c->dims[l + 1]);
@@ -531,7 +545,8 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     for (int l = 0; l < c->L; ++l) c->agnn_beta[l] = d->agnn_beta[l];
     c->agg_only = d->agg_only ? 1 : 0;
     c->monet_J = d->kind == NRT_MONET ? d->monet_kernels : 0;
-    c->n_rel = d->kind == NRT_RGCN ? d->n_relations : 0;
+    c->n_rel = (d->kind == NRT_RGCN || d->kind == NRT_RGAT) ? d->n_relations : 0;
+    if (d->kind == NRT_RGAT) c->heads = d->n_relations;          // one softmax group per relation
     c->max_edges = max_edges;
     c->max_feats = max_feats;
     return NRT_OK;
@@ -788,7 +803,7 @@ static nrt_status run_gat_project(nrt_cache* c, int l, const int32_t* src_rows, 
     z.P0 = c->H[l - 1];
     z.ldp = c->dims[l - 1];
     z.K = c->dims[l - 1];
-    z.N = c->dims[l];
+    z.N = c->zdim;
     z.Wt = c->Wt[l - 1][0];
     z.H = c->Z[l];
     if (incremental) { z.DP = c->DP[0]; z.dp_store_old = 1; }     // keep the old z rows, compact, for Algorithm 3
@@ -798,6 +813,7 @@ static nrt_status run_gat_project(nrt_cache* c, int l, const int32_t* src_rows, 
     a.n = g->n;
     a.heads = c->heads;
     a.head_dim = c->head_dim;
+    a.rel = c->kind == NRT_RGAT;
     a.slope = c->leaky_slope;
     a.att_src = c->att_src[l - 1];
     a.att_dst = c->att_dst[l - 1];
@@ -994,7 +1010,7 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
     if (c->agg_only)                       // hidden rows live in the two delta buffers while the aggregates are built
         for (int l = 1; l < c->L; ++l) c->H[l] = c->DP[l & 1];
     for (int l = 1; l <= c->L && st == NRT_OK; ++l) {
-        if (c->kind == NRT_GAT) {
+        if (c->is_gat) {
             st = run_gat_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, false, 0, nullptr, 0, s);
             continue;
         }
@@ -1023,10 +1039,10 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
     NRT_TRY(nrt_cache_workspace_bytes(g, d, max_batch_edges, max_batch_feats, &need));
     REQUIRE(workspace_bytes >= need, "cache workspace too small");
     if (g->has_cache) { nrt_set_error("graph already has a cache"); return NRT_ERR_STATE; }
-    if (d->kind == NRT_RGCN) {
-        REQUIRE(g->weighted, "RGCN needs a weighted graph: the edge weights are the relation ids");
+    if (d->kind == NRT_RGCN || d->kind == NRT_RGAT)
+        REQUIRE(g->weighted, "RGCN and RGAT need a weighted graph: the edge weights are the relation ids");
+    if (d->kind == NRT_RGCN)
         REQUIRE(g->n * d->n_relations <= (int64_t)INT32_MAX, "RGCN: vertices * relations must fit 31 bits");
-    }
     for (int l = 0; l < d->n_layers; ++l) {
         REQUIRE(d->W[l][0], "W[l][0] is null");
         if (d->kind == NRT_GIN) REQUIRE(d->W[l][1], "GIN needs W[l][1]");
@@ -1034,7 +1050,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         if (d->kind == NRT_GGCN) REQUIRE(d->W[l][1], "G-GCN needs W[l][1] = [W_1; W_2]");
         if (d->kind == NRT_RGCN) REQUIRE(d->W[l][1], "RGCN needs W[l][1] = [W_0 | ... | W_{R-1}]");
         if (d->kind == NRT_MONET) REQUIRE(d->monet_mu[l] && d->monet_prec[l], "MoNet needs monet_mu[l] and monet_prec[l]");
-        if (d->kind == NRT_GAT) REQUIRE(d->att_src[l] && d->att_dst[l], "GAT needs att_src[l] and att_dst[l]");
+        if (d->kind == NRT_GAT || d->kind == NRT_RGAT) REQUIRE(d->att_src[l] && d->att_dst[l], "GAT and RGAT need att_src[l] and att_dst[l]");
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     nrt_cache* c = new (std::nothrow) nrt_cache;
@@ -1059,7 +1075,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
         NRT_TRY(k_fill_u64(c->cmp_state, c->cmp_state_len, 0, s));
         for (int l = 0; l < c->L; ++l) {
             const int kin = c->kind == NRT_MONET ? c->monet_J : (concat_self(c->kind) ? 2 : 1) * c->dims[l];
-            NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->dims[l + 1], s));
+            NRT_TRY(k_transpose(d->W[l][0], c->Wt[l][0], kin, c->is_gat ? c->zdim : c->dims[l + 1], s));
             if (d->b[l][0]) NRT_TRY(k_copy_f32(c->bias[l][0], d->b[l][0], c->dims[l + 1], s));
             else NRT_TRY(k_fill_u32((uint32_t*)c->bias[l][0], c->dims[l + 1], 0, s));
             if (c->kind == NRT_GGCN) {                     // W[l][1] is [2 d][d]: W_1 on top of W_2
@@ -1071,7 +1087,7 @@ extern "C" nrt_status nrt_cache_init(nrt_graph* g, const nrt_model_desc* d, cons
                 NRT_TRY(k_transpose(d->monet_mu[l], c->muT[l], c->monet_J, c->dims[l], s));
                 NRT_TRY(k_transpose(d->monet_prec[l], c->precT[l], c->monet_J, c->dims[l], s));
             }
-            if (c->kind == NRT_GAT) {
+            if (c->is_gat) {
                 NRT_TRY(k_copy_f32(c->att_src[l], d->att_src[l], (int64_t)c->heads * c->head_dim, s));
                 NRT_TRY(k_copy_f32(c->att_dst[l], d->att_dst[l], (int64_t)c->heads * c->head_dim, s));
             }
@@ -1205,7 +1221,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
     // (no extra launches for small frontiers); the device counters of this batch take the decision
     bool may_rec[NRT_MAX_LAYERS + 2];
     for (int l = 0; l <= c->L + 1; ++l)
-        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && c->kind != NRT_GAT && !agnn_family(c->kind) && !c->agg_only && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
+        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && !c->is_gat && !agnn_family(c->kind) && !c->agg_only && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     uint64_t* n_slots_dev = (uint64_t*)(g->dev_ctrs + CTR_COUNT);
     if (b->n_ins + b->n_del > 0) {
@@ -1230,11 +1246,12 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
     c->sc.plan_ins_rank = c->ins_rank;
 
     // ---- structural terms on the old caches, all layers in one launch
-    if (inc && c->kind == NRT_GAT) {
+    if (inc && c->is_gat) {
         GatFoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
         f.del_src = b->del_src; f.del_dst = b->del_dst;
+        f.del_w = c->kind == NRT_RGAT ? c->sc.del_w : nullptr;
         f.n_slots = n_slots_dev; f.off = c->plan_off; f.ord = c->plan_ord; f.list = c->list_dd;
         f.n = n;
         f.n_layers = c->L; f.heads = c->heads; f.head_dim = c->head_dim; f.slope = c->leaky_slope;
@@ -1259,7 +1276,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
         f.gate = c->kind == NRT_GGCN;
         NRT_TRY(k_agnn_structural_fold(f, s));
     }
-    if (inc && c->kind != NRT_GAT && !agnn_family(c->kind)) {
+    if (inc && !c->is_gat && !agnn_family(c->kind)) {
         FoldArgs f;
         memset(&f, 0, sizeof(f));
         f.n_ins = b->n_ins; f.n_del = b->n_del;
@@ -1382,7 +1399,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
             // attention scalars, inverse norms, gate projections
             if (has_message_cache(c->kind) && l == 1)
                 NRT_TRY(run_transform(c, 0, c->list[0], src_bound, &c->lc[0].count, nullptr, false, s));
-            if (c->kind == NRT_GAT && l == 1)
+            if (c->is_gat && l == 1)
                 NRT_TRY(run_gat_project(c, 1, c->list[0], &c->lc[0].count, src_bound, true, false, nullptr, s));
             if (agnn_family(c->kind) && l == 1)
                 NRT_TRY(run_agnn_project(c, 1, c->list[0], &c->lc[0].count, src_bound, false, s));
@@ -1398,9 +1415,9 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
         // GAT with only edge updates in the layer (no z changed): every destination takes the O(#updates) path of
         // Algorithm 3, also those with long in-lists, so no items are cut
         NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false,
-                              (c->kind == NRT_GAT && inc) ? &c->lc[l - 1].count : nullptr, s));
+                              (c->is_gat && inc) ? &c->lc[l - 1].count : nullptr, s));
         NRT_TRY(prof_mark(c, TAG_COMPACT, l, s));
-        if (c->kind == NRT_GAT) {
+        if (c->is_gat) {
             NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, src_bound, c->list[l], &c->lc[l].count, n, true,
                                   inc, prev, l == c->L ? affected_rows : nullptr, capacity, s));
         } else if (agnn_family(c->kind)) {
@@ -1560,12 +1577,12 @@ static nrt_status recompute_listed(nrt_cache* c, hipStream_t s) {
     c->have_history_prev = false;            // the sizes of a query say nothing about the last batch's (no grid hints)
     for (int l = 1; l <= c->L; ++l) {
         NRT_TRY(k_dst_records(c->list[l], n, g->in, c->recs, c->hubs, &c->lc[l], false, nullptr, s));
-        if (c->kind == NRT_GAT || agnn_family(c->kind)) {
+        if (c->is_gat || agnn_family(c->kind)) {
             // constrained models (Section III-D): the rows of h^{l-1} brought up to date one layer below are re-projected
             // (layer 1 reads h^0, whose projections every batch keeps current), then the listed destinations are summed
             // over their whole in-neighbourhoods
             const int64_t sb = l == 1 ? 0 : n;
-            if (c->kind == NRT_GAT)
+            if (c->is_gat)
                 NRT_TRY(run_gat_layer(c, l, c->list[l - 1], &c->lc[l - 1].count, sb, c->list[l], &c->lc[l].count, n, true, false,
                                       0, nullptr, 0, s));
             else
@@ -1671,9 +1688,9 @@ static nrt_status serve_query_after_batch(nrt_cache* c, const QueryArgs& q, bool
             NRT_TRY(k_dst_records(c->need_list[l], n, g->in, c->recs, c->hubs, &need[l], false, nullptr, s));
             c->lc_use = &need[l];
             nrt_status st = NRT_OK;
-            if (c->kind == NRT_GAT || agnn_family(c->kind)) {
+            if (c->is_gat || agnn_family(c->kind)) {
                 const int64_t sb = l == 1 ? 0 : n;   // layer 1 reads h^0, whose projections every batch keeps current
-                if (c->kind == NRT_GAT)
+                if (c->is_gat)
                     st = run_gat_layer(c, l, c->need_list[l - 1], &need[l - 1].count, sb, c->need_list[l], &need[l].count, n, true,
                                        false, 0, nullptr, 0, s);
                 else

@@ -320,6 +320,8 @@ struct GatArgs {
     int64_t rows_bound;             // launch bound for the listed rows
     int64_t n;
     int heads, head_dim;
+    int rel;                        // 1 (RGAT): the heads are relations, an edge joins only the group of its relation (its
+                                    // weight), and the layer output is the sum of the groups (width head_dim)
     float slope;
     const float* att_src; const float* att_dst;   // [heads][head_dim]
     float* Z;                       // [N][D] current z = x W
@@ -346,7 +348,7 @@ struct GatArgs {
     unsigned long long* pair_ctr;   // null or 1024 counters: z rows fetched by the gather (a statistic)
     float* M; float* DEN;           // [N][heads]
     float* S;                       // [N][D]
-    float* Hout;                    // [N][D] layer output
+    float* Hout;                    // [N][D] layer output ([N][head_dim] with rel)
     const float* bias; int act;
     float* out_rows; int64_t out_cap;
 };
@@ -354,6 +356,7 @@ nrt_status k_gat_scalars(const GatArgs& a, hipStream_t s);
 struct GatFoldArgs {   // structural terms of a batch for GAT, evaluated on the pre-update caches, all layers in one launch
     int64_t n_ins, n_del, n;
     const int32_t *del_src, *del_dst;
+    const float* del_w;         // RGAT: relation ids of the deleted edges (a deleted edge leaves only its relation's group), else null
     const uint64_t* n_slots;    // the batch plan: destinations, their runs of updates (inserts first)
     const int32_t* off;
     const int32_t* ord;

@@ -22,6 +22,11 @@
 //   and the combine kernel merges them; when no z changed (edge updates only) such a destination takes the same
 //   O(#updates) path as the others.
 // One wave per destination; lane = 4 consecutive columns of the row, a head = head_dim/4 neighbouring lanes.
+//
+// RGAT (Table II row RGAT; template argument REL): the heads are the relations.  Every edge carries a relation id
+// (its weight) and enters only the softmax group of that relation, so a lane skips the entries whose relation is not
+// its head's; the self-loop belongs to every group; the layer output is the sum of the groups' results instead of
+// their concatenation (width head_dim), formed through a row of LDS per wave.
 #include "common.h"
 
 namespace {
@@ -75,6 +80,7 @@ __global__ void gat_structural_fold_kernel(GatFoldArgs a) {
             for (int32_t j = b; j < e; ++j) {
                 const int32_t op = a.ord[j];
                 if (op < a.n_ins) continue;                            // inserts come first in the run
+                if (a.del_w && nrt_rel_of(a.del_w[op - a.n_ins], H) != k) continue;   // typed edge: its relation's group only
                 const int32_t u = a.del_src[op - a.n_ins];
                 const float w = __expf(leaky(adv + a.AS[l][(int64_t)u * H + k], a.slope) - mv);   // at most 1: m bounds every cached logit of v
                 const float4 z = *reinterpret_cast<const float4*>(a.Z[l] + (int64_t)u * D + col);
@@ -90,7 +96,7 @@ __global__ void gat_structural_fold_kernel(GatFoldArgs a) {
 // ------------------------------------------------------------------ gather
 // Softmax aggregate over `cnt` in-list entries starting at pool position `base`, optionally with the self-loop
 // of v, all with current values (Algorithm 2).  Two passes: largest logit, then the shifted sums.
-template <int NV>
+template <int NV, bool REL>
 __device__ inline void gat_full_pass(const GatArgs& a, int32_t v, int64_t base, int32_t cnt, bool with_self, int lane,
                                      const int (&col)[NV], const int (&head)[NV], const bool (&live)[NV],
                                      const float (&adv)[NV], float (&mcur)[NV], float (&den)[NV], float4 (&acc)[NV]) {
@@ -102,14 +108,16 @@ __device__ inline void gat_full_pass(const GatArgs& a, int32_t v, int64_t base, 
     for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
         const int32_t jj = j0 + lane;
         const int32_t u = jj < cnt ? a.in.idx[base + jj] : -1;
+        const int32_t rl = (REL && jj < cnt) ? nrt_rel_of(a.in.wts[base + jj], H) : -1;
         unsigned long long mask = __ballot(u >= 0);
         while (mask) {
             const int bit = __ffsll((long long)mask) - 1;
             mask &= mask - 1;
             const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+            const int32_t rr = REL ? __builtin_amdgcn_readlane(rl, bit) : -1;
 #pragma unroll
             for (int q = 0; q < NV; ++q)
-                if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+                if (live[q] && (!REL || head[q] == rr)) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
         }
     }
 #pragma unroll
@@ -126,25 +134,30 @@ __device__ inline void gat_full_pass(const GatArgs& a, int32_t v, int64_t base, 
     for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
         const int32_t jj = j0 + lane;
         const int32_t u = jj < cnt ? a.in.idx[base + jj] : -1;
+        const int32_t rl = (REL && jj < cnt) ? nrt_rel_of(a.in.wts[base + jj], H) : -1;
         unsigned long long mask = __ballot(u >= 0);
         while (mask) {
             const int b0 = __ffsll((long long)mask) - 1;
             mask &= mask - 1;
             const int32_t u0 = __builtin_amdgcn_readlane(u, b0);
-            int32_t u1 = -1;
+            const int32_t r0 = REL ? __builtin_amdgcn_readlane(rl, b0) : -1;
+            int32_t u1 = -1, r1 = -1;
             if (mask) {
                 const int b1 = __ffsll((long long)mask) - 1;
                 mask &= mask - 1;
                 u1 = __builtin_amdgcn_readlane(u, b1);
+                if (REL) r1 = __builtin_amdgcn_readlane(rl, b1);
             }
 #pragma unroll
             for (int q = 0; q < NV; ++q) {
                 if (!live[q]) continue;
-                const float c0 = __expf(leaky(adv[q] + a.AS[(int64_t)u0 * H + head[q]], slope) - mcur[q]);
-                const float4 z0 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u0 * D + col[q]);
-                float c1 = 0.f;
-                float4 z1 = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (u1 >= 0) {
+                float c0 = 0.f, c1 = 0.f;
+                float4 z0 = make_float4(0.f, 0.f, 0.f, 0.f), z1 = z0;
+                if (!REL || head[q] == r0) {
+                    c0 = __expf(leaky(adv[q] + a.AS[(int64_t)u0 * H + head[q]], slope) - mcur[q]);
+                    z0 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u0 * D + col[q]);
+                }
+                if (u1 >= 0 && (!REL || head[q] == r1)) {
                     c1 = __expf(leaky(adv[q] + a.AS[(int64_t)u1 * H + head[q]], slope) - mcur[q]);
                     z1 = *reinterpret_cast<const float4*>(a.Z + (int64_t)u1 * D + col[q]);
                 }
@@ -156,12 +169,48 @@ __device__ inline void gat_full_pass(const GatArgs& a, int32_t v, int64_t base, 
     }
 }
 
-// store context, aggregate and layer output h = act(S / den + b) of vertex v (list position s)
-template <int NV>
+// store context, aggregate and layer output h = act(S / den + b) of vertex v (list position s).  REL: the output is the
+// sum over the heads (relations) of S / den, formed in `red`, a row of heads * head_dim floats of LDS owned by the wave.
+template <int NV, bool REL>
 __device__ inline void gat_store(const GatArgs& a, int32_t v, int64_t s, const int (&col)[NV], const int (&head)[NV],
                                  const bool (&live)[NV], const float (&mcur)[NV], const float (&den)[NV],
-                                 const float4 (&acc)[NV]) {
+                                 const float4 (&acc)[NV], float* red, int lane) {
     const int H = a.heads, hd = a.head_dim, D = H * hd;
+    if (REL) {
+#pragma unroll
+        for (int q = 0; q < NV; ++q) {
+            if (!live[q]) continue;
+            if ((col[q] % hd) == 0) {
+                a.M[(int64_t)v * H + head[q]] = mcur[q];
+                a.DEN[(int64_t)v * H + head[q]] = den[q];
+            }
+            *reinterpret_cast<float4*>(a.S + (int64_t)v * D + col[q]) = acc[q];
+            const float inv = 1.0f / den[q];             // every group holds the self-loop: den > 0
+            *reinterpret_cast<float4*>(red + col[q]) = make_float4(acc[q].x * inv, acc[q].y * inv, acc[q].z * inv, acc[q].w * inv);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        for (int c = lane * 4; c < hd; c += 256) {
+            float4 y = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int r = 0; r < H; ++r) {
+                const float4 t = *reinterpret_cast<const float4*>(red + r * hd + c);
+                y.x += t.x; y.y += t.y; y.z += t.z; y.w += t.w;
+            }
+            float yy[4] = {y.x, y.y, y.z, y.w};
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                if (a.bias) yy[t] += a.bias[c + t];
+                if (a.act == 2) yy[t] = yy[t] > 0.f ? yy[t] : expm1f(yy[t]);
+            }
+            const float4 yo = make_float4(yy[0], yy[1], yy[2], yy[3]);
+            *reinterpret_cast<float4*>(a.Hout + (int64_t)v * hd + c) = yo;
+            if (a.out_rows && s < a.out_cap) *reinterpret_cast<float4*>(a.out_rows + s * hd + c) = yo;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();                 // the row is free for the wave's next destination
+        return;
+    }
 #pragma unroll
     for (int q = 0; q < NV; ++q) {
         if (!live[q]) continue;
@@ -186,8 +235,10 @@ __device__ inline void gat_store(const GatArgs& a, int32_t v, int64_t s, const i
 // Units [0, n_items): hub items (NRT_CHUNK in-list entries of a destination with a long in-list; they write partial
 // (bound, sum, row) triples of the full sums or of the exchange).  Units
 // [n_items, n_items + n_dst): the destinations themselves, hubs skipped.
-template <int NV>
+template <int NV, bool REL>
 __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
+    __shared__ __attribute__((aligned(16))) float s_red[REL ? 4 * NV * 256 : 4];
+    float* red = &s_red[REL ? (threadIdx.x >> 6) * NV * 256 : 0];
     const int lane = threadIdx.x & 63;
     const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     const int64_t n_dst = (int64_t)a.lc->count;
@@ -218,7 +269,7 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
             for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)v * H + head[q]] : 0.f;
             const bool own = a.src_bitmap ? ((a.src_bitmap[v >> 5] >> (v & 31)) & 1u) != 0 : true;
             if (own) {                                        // every logit of v changed: its share of the full sums
-                gat_full_pass<NV>(a, v, base, cnt, false, lane, col, head, live, adv, mcur, den, acc);
+                gat_full_pass<NV, REL>(a, v, base, cnt, false, lane, col, head, live, adv, mcur, den, acc);
                 rows_read += cnt;
             } else {
                 // Algorithm 3 on this part of the in-list, relative to a bound of its own (the cached bound of v raised
@@ -231,15 +282,17 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
                     const int32_t jj = j0 + lane;
                     const int32_t u = jj < cnt ? a.in.idx[base + jj] : -1;
+                    const int32_t rl = (REL && jj < cnt) ? nrt_rel_of(a.in.wts[base + jj], H) : -1;
                     const bool ok = u >= 0 && (jj >= first_new || ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u));
                     unsigned long long mask = __ballot(ok);
                     while (mask) {
                         const int bit = __ffsll((long long)mask) - 1;
                         mask &= mask - 1;
                         const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+                        const int32_t rr = REL ? __builtin_amdgcn_readlane(rl, bit) : -1;
 #pragma unroll
                         for (int q = 0; q < NV; ++q)
-                            if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+                            if (live[q] && (!REL || head[q] == rr)) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
                     }
                 }
 #pragma unroll
@@ -247,6 +300,7 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 for (int32_t j0 = 0; j0 < cnt; j0 += 64) {
                     const int32_t jj = j0 + lane;
                     const int32_t u = jj < cnt ? a.in.idx[base + jj] : -1;
+                    const int32_t rl = (REL && jj < cnt) ? nrt_rel_of(a.in.wts[base + jj], H) : -1;
                     const bool fresh = jj >= first_new;
                     const bool ok = u >= 0 && (fresh || ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u));
                     const int32_t sl = (ok && !fresh) ? a.src_slot[u] : -1;
@@ -256,10 +310,11 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                         mask &= mask - 1;
                         const int32_t uu = __builtin_amdgcn_readlane(u, bit);
                         const int32_t ss = __builtin_amdgcn_readlane(sl, bit);     // -1: an inserted in-edge, new term only
+                        const int32_t rr = REL ? __builtin_amdgcn_readlane(rl, bit) : -1;
                         rows_read += ss >= 0 ? 2 : 1;
 #pragma unroll
                         for (int q = 0; q < NV; ++q) {
-                            if (!live[q]) continue;
+                            if (!live[q] || (REL && head[q] != rr)) continue;
                             const float cn = __expf(leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope) - mcur[q]);
                             const float4 zn = *reinterpret_cast<const float4*>(a.Z + (int64_t)uu * D + col[q]);
                             den[q] += cn;
@@ -315,28 +370,32 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
             for (int32_t j0 = n_kept; j0 < deg; j0 += 64) {
                 const int32_t jj = j0 + lane;
                 const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                const int32_t rl = (REL && jj < deg) ? nrt_rel_of(a.in.wts[off + jj], H) : -1;
                 unsigned long long mask = __ballot(u >= 0);
                 while (mask) {
                     const int bit = __ffsll((long long)mask) - 1;
                     mask &= mask - 1;
                     const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+                    const int32_t rr = REL ? __builtin_amdgcn_readlane(rl, bit) : -1;
 #pragma unroll
                     for (int q = 0; q < NV; ++q)
-                        if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+                        if (live[q] && (!REL || head[q] == rr)) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
                 }
             }
             for (int32_t j0 = 0; j0 < scan_end; j0 += 64) {
                 const int32_t jj = j0 + lane;
                 int32_t u = jj < scan_end ? a.in.idx[off + jj] : -1;
                 bool ok = u >= 0 && ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u);
+                const int32_t rl = (REL && ok) ? nrt_rel_of(a.in.wts[off + jj], H) : -1;
                 unsigned long long mask = __ballot(ok);
                 while (mask) {
                     const int bit = __ffsll((long long)mask) - 1;
                     mask &= mask - 1;
                     const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+                    const int32_t rr = REL ? __builtin_amdgcn_readlane(rl, bit) : -1;
 #pragma unroll
                     for (int q = 0; q < NV; ++q)
-                        if (live[q]) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
+                        if (live[q] && (!REL || head[q] == rr)) mcur[q] = fmaxf(mcur[q], leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope));
                 }
             }
             bool redo = false;
@@ -361,15 +420,17 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
             for (int32_t j0 = n_kept; j0 < deg; j0 += 64) {
                 const int32_t jj = j0 + lane;
                 const int32_t u = jj < deg ? a.in.idx[off + jj] : -1;
+                const int32_t rl = (REL && jj < deg) ? nrt_rel_of(a.in.wts[off + jj], H) : -1;
                 unsigned long long mask = __ballot(u >= 0);
                 rows_read += __popcll(mask);
                 while (mask) {
                     const int bit = __ffsll((long long)mask) - 1;
                     mask &= mask - 1;
                     const int32_t uu = __builtin_amdgcn_readlane(u, bit);
+                    const int32_t rr = REL ? __builtin_amdgcn_readlane(rl, bit) : -1;
 #pragma unroll
                     for (int q = 0; q < NV; ++q) {
-                        if (!live[q]) continue;
+                        if (!live[q] || (REL && head[q] != rr)) continue;
                         const float cn = __expf(leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope) - mcur[q]);
                         const float4 zn = *reinterpret_cast<const float4*>(a.Z + (int64_t)uu * D + col[q]);
                         den[q] += cn;
@@ -383,6 +444,7 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                 int32_t u = jj < scan_end ? a.in.idx[off + jj] : -1;
                 bool ok = u >= 0 && ((a.src_bitmap[(uint32_t)u >> 5] >> (u & 31)) & 1u);
                 int32_t sl = ok ? a.src_slot[u] : -1;
+                const int32_t rl = (REL && ok) ? nrt_rel_of(a.in.wts[off + jj], H) : -1;
                 unsigned long long mask = __ballot(ok);
                 rows_read += 2 * __popcll(mask);
                 while (mask) {
@@ -390,9 +452,10 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
                     mask &= mask - 1;
                     const int32_t uu = __builtin_amdgcn_readlane(u, bit);
                     const int32_t ss = __builtin_amdgcn_readlane(sl, bit);
+                    const int32_t rr = REL ? __builtin_amdgcn_readlane(rl, bit) : -1;
 #pragma unroll
                     for (int q = 0; q < NV; ++q) {
-                        if (!live[q]) continue;
+                        if (!live[q] || (REL && head[q] != rr)) continue;
                         const float en = leaky(adv[q] + a.AS[(int64_t)uu * H + head[q]], slope);
                         const float eo = leaky(adv[q] + a.AS_old[(int64_t)ss * H + head[q]], slope);
                         const float cn = __expf(en - mcur[q]), co = __expf(eo - mcur[q]);
@@ -410,17 +473,19 @@ __global__ void __launch_bounds__(256) gat_gather_kernel(GatArgs a) {
             full = __ballot(redo) != 0ULL;        // cancellation: recompute this destination over all its neighbours
         }
         if (full) {
-            gat_full_pass<NV>(a, v, off, deg, true, lane, col, head, live, adv, mcur, den, acc);
+            gat_full_pass<NV, REL>(a, v, off, deg, true, lane, col, head, live, adv, mcur, den, acc);
             rows_read += deg + 1;
         }
-        gat_store<NV>(a, v, s, col, head, live, mcur, den, acc);
+        gat_store<NV, REL>(a, v, s, col, head, live, mcur, den, acc, red, lane);
     }
     if (a.pair_ctr && lane == 0 && rows_read) atomicAdd(&a.pair_ctr[blockIdx.x & 1023], (unsigned long long)rows_read);
 }
 
 // one wave per hub: merge the partial triples of its items and its self-loop
-template <int NV>
+template <int NV, bool REL>
 __global__ void __launch_bounds__(256) gat_combine_kernel(GatArgs a) {
+    __shared__ __attribute__((aligned(16))) float s_red[REL ? 4 * NV * 256 : 4];
+    float* red = &s_red[REL ? (threadIdx.x >> 6) * NV * 256 : 0];
     const int lane = threadIdx.x & 63;
     const int64_t waves = ((int64_t)gridDim.x * blockDim.x) >> 6;
     int64_t nh = (int64_t)a.lc->n_hubs;
@@ -489,9 +554,9 @@ __global__ void __launch_bounds__(256) gat_combine_kernel(GatArgs a) {
                 float adv[NV];
 #pragma unroll
                 for (int q = 0; q < NV; ++q) adv[q] = live[q] ? a.AD[(int64_t)v * H + head[q]] : 0.f;
-                gat_full_pass<NV>(a, v, rec.off, rec.deg, true, lane, col, head, live, adv, mcur, den, acc);
+                gat_full_pass<NV, REL>(a, v, rec.off, rec.deg, true, lane, col, head, live, adv, mcur, den, acc);
             }
-            gat_store<NV>(a, v, s, col, head, live, mcur, den, acc);
+            gat_store<NV, REL>(a, v, s, col, head, live, mcur, den, acc, red, lane);
             continue;
         }
 #pragma unroll
@@ -524,7 +589,7 @@ __global__ void __launch_bounds__(256) gat_combine_kernel(GatArgs a) {
                 acc[q].x += f * p.x; acc[q].y += f * p.y; acc[q].z += f * p.z; acc[q].w += f * p.w;
             }
         }
-        gat_store<NV>(a, rec.v, s, col, head, live, mcur, den, acc);
+        gat_store<NV, REL>(a, rec.v, s, col, head, live, mcur, den, acc, red, lane);
     }
 }
 
@@ -551,9 +616,17 @@ nrt_status k_gat_structural_fold(const GatFoldArgs& a, hipStream_t s) {
 nrt_status k_gat_gather(const GatArgs& a, hipStream_t s) {
     const int D = a.heads * a.head_dim;
     const int g = 8192;                     // fixed grid: sizes are read on the device
-    if (D <= 256) { gat_gather_kernel<1><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<1><<<2048, 256, 0, s>>>(a); }
-    else if (D <= 512) { gat_gather_kernel<2><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<2><<<2048, 256, 0, s>>>(a); }
-    else { gat_gather_kernel<4><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<4><<<2048, 256, 0, s>>>(a); }
+    if (a.rel) {
+        if (!a.in.wts) { nrt_set_error("typed edges need a weighted graph"); return NRT_ERR_INVALID_ARG; }
+        if (D <= 256) { gat_gather_kernel<1, true><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<1, true><<<2048, 256, 0, s>>>(a); }
+        else if (D <= 512) { gat_gather_kernel<2, true><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<2, true><<<2048, 256, 0, s>>>(a); }
+        else { gat_gather_kernel<4, true><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<4, true><<<2048, 256, 0, s>>>(a); }
+        LAUNCH_CHECK();
+        return NRT_OK;
+    }
+    if (D <= 256) { gat_gather_kernel<1, false><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<1, false><<<2048, 256, 0, s>>>(a); }
+    else if (D <= 512) { gat_gather_kernel<2, false><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<2, false><<<2048, 256, 0, s>>>(a); }
+    else { gat_gather_kernel<4, false><<<g, 256, 0, s>>>(a); LAUNCH_CHECK(); gat_combine_kernel<4, false><<<2048, 256, 0, s>>>(a); }
     LAUNCH_CHECK();
     return NRT_OK;
 }

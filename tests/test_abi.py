@@ -45,7 +45,7 @@ def test_argument_errors_without_gpu():
 def test_struct_sizes_match_header():
     from paper_2603_20622_amd import binding as nb
     # int32*2 + int32*5 + int32*2 + float*2 = 44 bytes, padded to 48, then 8+8+4+4 pointers, then 4 floats, an int32 (padded to 8),
-    # 4+4 more pointers and an int32 (padded to 8)
+    # 4+4 more pointers and two int32
     assert ctypes.sizeof(nb.nrt_model_desc) == 48 + 8 * (8 + 8 + 4 + 4) + 4 * 4 + 8 + 8 * (4 + 4) + 8
     assert ctypes.sizeof(nb.nrt_batch) == 10 * 8
     assert ctypes.sizeof(nb.nrt_layer_stats) == 5 * 8 + 6 * 4
@@ -78,7 +78,7 @@ def test_model_kinds_agree_between_header_generators_and_oracle():
     enum = re.search(r"typedef enum \{([^}]*)\} nrt_model_kind;", text).group(1)
     header = {k: int(v) for k, v in re.findall(r"(NRT_[A-Z_]+)\s*=\s*(\d+)", enum)}
     names = {"NRT_GCN": "GCN", "NRT_SAGE_MEAN": "SAGE_MEAN", "NRT_GIN": "GIN", "NRT_GAT": "GAT", "NRT_COMMNET": "COMMNET",
-             "NRT_PINSAGE": "PINSAGE", "NRT_AGNN": "AGNN", "NRT_MONET": "MONET", "NRT_GGCN": "GGCN", "NRT_RGCN": "RGCN"}
+             "NRT_PINSAGE": "PINSAGE", "NRT_AGNN": "AGNN", "NRT_MONET": "MONET", "NRT_GGCN": "GGCN", "NRT_RGCN": "RGCN", "NRT_RGAT": "RGAT"}
     assert set(header) == set(names)
     for c_name, py_name in names.items():
         assert header[c_name] == getattr(wl, py_name) == getattr(orc, py_name), c_name

@@ -72,6 +72,8 @@ def small_case(kind, seed=0, n=3000, e=40000, dims=None, bias=False, L=2):
         dims = [64, 128, 32] if L == 2 else [32, 64, 64, 16]
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [dims[0]] + [64] * L, heads=4, head_dim=16)
+    elif kind == wl.RGAT:
+        spec = wl.ModelSpec(kind, [dims[0]] + [32] * L, head_dim=32, weighted=True, n_relations=N_REL)
     else:
         spec = wl.ModelSpec(kind, dims, weighted=weighted, monet_kernels=24, n_relations=N_REL)
     params = wl.make_params(spec, seed, bias=bias)
@@ -80,8 +82,8 @@ def small_case(kind, seed=0, n=3000, e=40000, dims=None, bias=False, L=2):
     return n, src, dst, w, x, spec, params, stream
 
 
-KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN, wl.RGCN]
-WEIGHTED = (wl.GIN, wl.PINSAGE, wl.RGCN)  # models whose messages read the edge weight (RGCN: as the relation id)
+KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN, wl.RGCN, wl.RGAT]
+WEIGHTED = (wl.GIN, wl.PINSAGE, wl.RGCN, wl.RGAT)  # models that read the edge weight (RGCN, RGAT: as the relation id)
 N_REL = 3                                 # relations of the typed-edge models in these tests
 
 
@@ -287,6 +289,8 @@ def test_gin_cancellation_is_guarded(S, oracle):
     (wl.GGCN, [260, 36, 8], 1, 0),              # gate rows of two 16-byte pieces per lane
     (wl.RGCN, [20, 132, 8], 1, 0),              # message rows of 132 floats, 3 x 132 per source
     (wl.RGCN, [260, 12, 4], 1, 0),              # narrowest message rows
+    (wl.RGAT, [24, 256, 256], 1, 256),          # 3 relations x 256: 768-wide projected rows
+    (wl.RGAT, [12, 4, 4], 1, 4),                # smallest group width
     (wl.GAT, [24, 512, 512], 8, 64),            # 512-wide attention rows, 8 heads
     (wl.GAT, [12, 8, 8], 2, 4),                 # smallest head width
 ])
@@ -624,6 +628,8 @@ def test_in_degrees_at_the_item_boundaries(S, oracle, kind):
     w = edge_values(kind, len(src), 0, rng)
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [12, 32, 32], heads=2, head_dim=16)
+    elif kind == wl.RGAT:
+        spec = wl.ModelSpec(kind, [12, 16, 16], head_dim=16, weighted=True, n_relations=N_REL)
     else:
         spec = wl.ModelSpec(kind, [12, 32, 8], weighted=weighted, monet_kernels=16, n_relations=N_REL)
     params = wl.make_params(spec, 78, bias=True)
@@ -735,6 +741,8 @@ def test_on_demand_queries_match_oracle(S, oracle, kind):
     w = edge_values(kind, e, 101)
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [16, 24, 24, 24], heads=2, head_dim=12)
+    elif kind == wl.RGAT:
+        spec = wl.ModelSpec(kind, [16, 12, 12, 12], head_dim=12, weighted=True, n_relations=N_REL)
     else:
         spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted, monet_kernels=20, n_relations=N_REL)
     params = wl.make_params(spec, 101, bias=True)
@@ -805,6 +813,8 @@ def test_batches_served_with_a_query_match_oracle(S, oracle, kind):
     w = edge_values(kind, e, 202)
     if kind == wl.GAT:
         spec = wl.ModelSpec(kind, [16, 24, 24, 24], heads=2, head_dim=12)
+    elif kind == wl.RGAT:
+        spec = wl.ModelSpec(kind, [16, 12, 12, 12], head_dim=12, weighted=True, n_relations=N_REL)
     else:
         spec = wl.ModelSpec(kind, [16, 24, 24, 8], weighted=weighted, monet_kernels=20, n_relations=N_REL)
     params = wl.make_params(spec, 202, bias=True)
@@ -869,11 +879,12 @@ def test_batches_served_with_a_query_match_oracle(S, oracle, kind):
         assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "eager again", l))
 
 
-def test_typed_edges_reject_bad_relation_ids(S, oracle):
-    """RGCN reads the edge weight as a relation id: a weight that is not an integer in [0, R) is refused when the caches
+@pytest.mark.parametrize("kind", [wl.RGCN, wl.RGAT])
+def test_typed_edges_reject_bad_relation_ids(S, oracle, kind):
+    """RGCN and RGAT read the edge weight as a relation id: a weight that is not an integer in [0, R) is refused when the caches
     are built, and in a batch it rejects the batch with graph and caches unchanged."""
     from paper_2603_20622_amd import binding as nb
-    n, src, dst, w, x, spec, params, stream = small_case(wl.RGCN, seed=12, n=500, e=4000)
+    n, src, dst, w, x, spec, params, stream = small_case(kind, seed=12, n=500, e=4000)
     for bad_value in (float(N_REL), 0.5, -1.0):
         wb = w.copy()
         wb[1234] = bad_value
@@ -893,7 +904,7 @@ def test_typed_edges_reject_bad_relation_ids(S, oracle):
     b.ins_w = good_w
     ses.apply(b)
     cur = oracle.apply_batch(n, src, dst, w, x, b)
-    assert_parity(wl.RGCN, ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1], "after the rejected batch")
+    assert_parity(kind, ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1], "after the rejected batch")
 
 
 @pytest.mark.parametrize("kind", KINDS)

@@ -15,7 +15,7 @@ from tests.test_gpu_parity import ELEMENTWISE_LOG, TOL, UNNORMALISED, rel_err, r
 pytestmark = pytest.mark.gpu
 
 KINDS = [wl.GCN, wl.SAGE_MEAN, wl.GIN, wl.GAT, wl.COMMNET, wl.PINSAGE, wl.AGNN, wl.MONET, wl.GGCN]
-TYPED = [wl.RGCN]                   # seeds from 90 on: the typed-edge models
+TYPED = [wl.RGCN, wl.RGAT]                   # seeds from 90 on: the typed-edge models
 CONSTRAINED = (wl.GAT, wl.AGNN, wl.GGCN)
 
 
@@ -57,6 +57,9 @@ def test_random_case(S, oracle, seed):
     if kind == wl.GAT:
         heads, hd = int(rng.choice([1, 2, 4])), int(rng.choice([4, 8, 16]))
         dims = [int(rng.choice([4, 8, 20]))] + [heads * hd] * L
+    elif kind == wl.RGAT:
+        hd = int(rng.choice([4, 8, 16, 68]))
+        dims = [int(rng.choice([4, 8, 20]))] + [hd] * L
     else:
         dims = [int(rng.choice([4, 8, 12, 32, 68, 128])) for _ in range(L + 1)]
     weighted = kind in (wl.GIN, wl.PINSAGE) and bool(rng.integers(0, 2))
