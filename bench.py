@@ -61,8 +61,13 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
 
     cfg = wl.config(index, args.scale)
     if args.model:
-        kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE, "agnn": wl.AGNN, "monet": wl.MONET, "ggcn": wl.GGCN}[args.model]
-        cfg.spec = wl.ModelSpec(kind, list(cfg.spec.dims), weighted=kind == wl.PINSAGE, monet_kernels=64)
+        kind = {"commnet": wl.COMMNET, "pinsage": wl.PINSAGE, "agnn": wl.AGNN, "monet": wl.MONET, "ggcn": wl.GGCN,
+                "rgcn": wl.RGCN, "rgat": wl.RGAT}[args.model]
+        mdims = list(cfg.spec.dims)
+        if kind == wl.RGAT:                                     # every layer as wide as the last: the group width
+            mdims = [mdims[0]] + [mdims[-1]] * (len(mdims) - 1)
+        cfg.spec = wl.ModelSpec(kind, mdims, weighted=kind in (wl.PINSAGE, wl.RGCN, wl.RGAT), monet_kernels=64,
+                                head_dim=mdims[-1] if kind == wl.RGAT else 0, n_relations=4)
         cfg.name = cfg.name + "_as_" + args.model
     if args.agg_only:
         cfg.spec.agg_only = True
@@ -127,7 +132,7 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
             # algorithmic bytes of the gather launch: per delta message its in-list id and slot-map entry (8 B);
             # the delta rows: every changed source row once (4*d) while the delta buffer fits the 256 MB Infinity
             # Cache, else one row per delta message; every affected aggregate row read and written (8*d)
-            d_agg = dims[l + 1] if cfg.spec.kind == wl.GAT else (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)
+            d_agg = dims[l + 1] if cfg.spec.kind in (wl.GAT, wl.RGCN, wl.RGAT) else (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)
             row_fetches = ls.n_src if ls.n_src * 4.0 * d_agg <= INFINITY_CACHE_BYTES else ls.n_pairs
             gbytes = ls.n_pairs * 8.0 + row_fetches * 4.0 * d_agg + ls.n_affected * 8.0 * d_agg if ls.n_src else 0.0
             kin = (2 if cfg.spec.kind in (wl.SAGE_MEAN, wl.COMMNET, wl.PINSAGE) else 1) * d_in
@@ -138,14 +143,22 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
                 flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]
             if cfg.spec.kind == wl.PINSAGE:                      # message transform of the changed rows (timed under "items")
                 flop += 2.0 * ls.n_src * d_in * d_in
+            if cfg.spec.kind == wl.RGCN:                         # its R message rows per changed source, likewise
+                flop += 2.0 * ls.n_src * d_in * cfg.spec.n_relations * dims[l + 1]
             upd_ms = ls.ms_update
+            if cfg.spec.kind == wl.RGAT:
+                # the GAT path with the relations as groups: z is R groups wide, a fetched row is one group's part
+                zdim = cfg.spec.n_relations * dims[l + 1]
+                flop = 2.0 * ls.n_src * d_in * zdim
+                upd_ms = ls.ms_items
+                gbytes = ls.n_pairs * (4.0 * d_agg + 16.0) + ls.n_affected * (8.0 * zdim + 4.0 * d_agg)
             if cfg.spec.kind == wl.GAT:
                 flop = 2.0 * ls.n_src * d_in * dims[l + 1]       # z = x W on the rows whose input changed,
                 upd_ms = ls.ms_items                             # timed (with the attention scalars) before the gather
                 # GAT gather: every fetched z row (full recomputation of constrained destinations, old and new
                 # rows of exchanged terms) with its id and attention scalars; aggregate rows read and written
                 gbytes = ls.n_pairs * (4.0 * d_agg + 8.0 + 4.0 * cfg.spec.heads) + ls.n_affected * 12.0 * d_agg
-            if ls.n_src or (cfg.spec.kind == wl.GAT and ls.n_affected):
+            if ls.n_src or (cfg.spec.kind in (wl.GAT, wl.RGAT) and ls.n_affected):
                 agg["gather_ms"] += ls.ms_gather
                 agg["gather_bytes"] += gbytes
                 agg["gather_launches"] += 1
@@ -239,7 +252,7 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
     g_avg_bytes = agg["gather_bytes"] / nl
     achieved = (g_avg_bytes / 1e9) / (g_avg_ms / 1e3) if g_avg_ms > 0 else 0.0
     kname = ("gat_gather_kernel (attention gather: Algorithm 3 exchange / constrained full recomputation)"
-             if cfg.spec.kind == wl.GAT else
+             if cfg.spec.kind in (wl.GAT, wl.RGAT) else
              "delta-message gather + fold (gather_sparse_kernel on layers with few changed sources, gather_kernel otherwise)")
     roofline = {"kernel": kname, "bound": "hbm",
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -334,7 +347,7 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
-    ap.add_argument("--model", choices=["commnet", "pinsage", "agnn", "monet", "ggcn"], default=None,
+    ap.add_argument("--model", choices=["commnet", "pinsage", "agnn", "monet", "ggcn", "rgcn", "rgat"], default=None,
                     help="run another Table II model on the chosen config's graph, widths and batches (implies --only)")
     ap.add_argument("--agg-only", action="store_true",
                     help="GCN configs: keep only the aggregates of hidden layers (storage option; implies --only)")

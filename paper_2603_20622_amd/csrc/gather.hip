@@ -169,7 +169,8 @@ dst_records_kernel(const int32_t* list, int64_t n_all, Adj in, DstRec* recs, Hub
 //      (rows narrower than 256 floats put RPI = 2 or 4 survivors into one load, one per LPR-lane sub-group);
 //      on the last step of a unit reduce the sub-groups and write the row.
 // Rebuild the aggregate row of v from its whole in-neighbourhood with current values (the full-neighbour
-// definition, Eq. 1): the fallback when an incremental fold has cancelled the leading digits of a row.
+// definition, Eq. 1): the fallback when an incremental fold has cancelled the leading digits of a row.  (Only the
+// un-normalised models carry that guard; typed edges never reach this function, k_gather refuses the combination.)
 template <int LPR, int NV>
 __device__ inline void full_row(const GatherArgs& a, int32_t v, int64_t off, int32_t deg, int lane, float4 (&acc)[NV]) {
     constexpr int RPI = 64 / LPR;
@@ -183,8 +184,6 @@ __device__ inline void full_row(const GatherArgs& a, int32_t v, int64_t off, int
         float c = 1.0f;
         if (u >= 0 && a.use_weights) c = a.in.wts[off + jj];
         if (u >= 0 && a.full_scale_gcn) c *= gcn_scale(a.in.deg[u]);
-        int32_t ur = u;                                        // row of the source (relation-typed edges: one of its rel_R rows)
-        if (u >= 0 && a.rel_R) { ur = u * a.rel_R + nrt_rel_of(c, a.rel_R); c = 1.0f; }
         unsigned long long m = __ballot(u >= 0);
         while (m) {
             int32_t rr = -1;
@@ -194,7 +193,7 @@ __device__ inline void full_row(const GatherArgs& a, int32_t v, int64_t off, int
                 if (m) {
                     const int bit = __ffsll((long long)m) - 1;
                     m &= m - 1;
-                    const int32_t rs = __builtin_amdgcn_readlane(ur, bit);
+                    const int32_t rs = __builtin_amdgcn_readlane(u, bit);
                     const float cs = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, c), bit));
                     if (sub == t) { rr = rs; cc = cs; }
                 }
@@ -249,7 +248,9 @@ __device__ inline bool layer_goes_to_other_role(const GatherArgs& a) {
 // Step flags kept in the per-wave step table.
 enum { SF_FIRST = 1, SF_LAST = 2, SF_PART = 4, SF_SELF = 8, SF_DD = 16 };
 
-template <int LPR, int NV, bool FILTER, bool COEF>
+// COEF: 0 every term has coefficient 1; 1 edge weights and / or the GCN source scale; 2 typed edges: the weight is a
+// relation id that picks one of the source's rel_R rows (coefficient 1)
+template <int LPR, int NV, bool FILTER, int COEF>
 __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs a) {
     constexpr int RPI = 64 / LPR;
     constexpr int MAX_UPW = 8;                       // units per wave; 8 units * 4 steps fit the 64-lane step table
@@ -410,7 +411,7 @@ __global__ void __launch_bounds__(WAVES_PER_BLOCK * 64) gather_kernel(GatherArgs
                 slC = uC;
                 if (COEF && a.src_scale_gcn && uC >= 0) cC *= gcn_scale((int32_t)xC);
             }
-            if (COEF && a.rel_R) {                               // typed edge: the relation's row of the source, coefficient 1
+            if (COEF == 2) {                                     // typed edge: the relation's row of the source, coefficient 1
                 if (slC >= 0) slC = slC * a.rel_R + nrt_rel_of(cC, a.rel_R);
                 cC = 1.0f;
             }
@@ -547,7 +548,7 @@ __global__ void coarse_bitmap_kernel(const uint32_t* fine, int64_t n, int shift,
     coarse[cw] = out;
 }
 
-template <int LPR, bool COEF>
+template <int LPR, int COEF>
 __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs a) {
     constexpr int RPI = 64 / LPR;          // units served by one row load
     constexpr int NPASS = 4 / RPI;         // row passes over the four units of a round
@@ -652,7 +653,7 @@ __global__ void __launch_bounds__(SP_WAVES * 64) gather_sparse_kernel(GatherArgs
             int32_t sl[5];
 #pragma unroll
             for (int k = 0; k < 5; ++k) sl[k] = ((bw[k] >> (e[k] & 31)) & 1u) ? a.src_slot[(uint32_t)e[k]] : -1;
-            if (COEF && a.rel_R) {                               // typed edge: the relation's row of the source, coefficient 1
+            if (COEF == 2) {                                     // typed edge: the relation's row of the source, coefficient 1
 #pragma unroll
                 for (int k = 0; k < 4; ++k) {
                     if (sl[k] >= 0) sl[k] = sl[k] * a.rel_R + nrt_rel_of(wv[k], a.rel_R);
@@ -876,24 +877,36 @@ static void launch_gather(const GatherArgs& a, hipStream_t s) {
     }
     const int threads = WAVES_PER_BLOCK * 64;
     const bool filter = a.src_bitmap != nullptr;
-    const bool coef = a.use_weights || a.src_scale_gcn;
+    const int coef = a.rel_R ? 2 : ((a.use_weights || a.src_scale_gcn) ? 1 : 0);
+    auto sparse = [&]() {
+        if (coef == 2) gather_sparse_kernel<LPR, 2><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
+        else if (coef) gather_sparse_kernel<LPR, 1><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
+        else gather_sparse_kernel<LPR, 0><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
+    };
     if (NV == 1 && a.sparse_ok == 2) {
-        if (coef) gather_sparse_kernel<LPR, true><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
-        else gather_sparse_kernel<LPR, false><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
+        sparse();
         return;
     }
-    if (filter && coef) gather_kernel<LPR, NV, true, true><<<nb, threads, 0, s>>>(a);
-    else if (filter) gather_kernel<LPR, NV, true, false><<<nb, threads, 0, s>>>(a);
-    else if (coef) gather_kernel<LPR, NV, false, true><<<nb, threads, 0, s>>>(a);
-    else gather_kernel<LPR, NV, false, false><<<nb, threads, 0, s>>>(a);
+    if (filter) {
+        if (coef == 2) gather_kernel<LPR, NV, true, 2><<<nb, threads, 0, s>>>(a);
+        else if (coef) gather_kernel<LPR, NV, true, 1><<<nb, threads, 0, s>>>(a);
+        else gather_kernel<LPR, NV, true, 0><<<nb, threads, 0, s>>>(a);
+    } else {
+        if (coef == 2) gather_kernel<LPR, NV, false, 2><<<nb, threads, 0, s>>>(a);
+        else if (coef) gather_kernel<LPR, NV, false, 1><<<nb, threads, 0, s>>>(a);
+        else gather_kernel<LPR, NV, false, 0><<<nb, threads, 0, s>>>(a);
+    }
     if (NV == 1 && a.sparse_ok) {
         ++nrt_launch_count;                     // the second launch of this call
-        if (coef) gather_sparse_kernel<LPR, true><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
-        else gather_sparse_kernel<LPR, false><<<sp_blocks, SP_WAVES * 64, 0, s>>>(a);
+        sparse();
     }
 }
 
 nrt_status k_gather(const GatherArgs& a, hipStream_t s) {
+    if (a.rel_R && (a.guard || a.self_pair || a.src_scale_gcn)) {
+        nrt_set_error("gather: typed edges combine with neither the cancellation guard nor the GCN terms");
+        return NRT_ERR_INVALID_ARG;
+    }
     if (a.D <= 64) launch_gather<16, 1>(a, s);
     else if (a.D <= 128) launch_gather<32, 1>(a, s);
     else if (a.D <= 256) launch_gather<64, 1>(a, s);

@@ -1,6 +1,6 @@
 """Randomised parity: seeded random models, graphs, batch mixes and modes through the C ABI against the fp64 oracle.
 
-Every case draws a model kind (all nine), a graph size and density, 1-3 layers with random widths, and a short
+Every case draws a model kind (all eleven), a graph size and density, 1-3 layers with random widths, and a short
 chain of batches with random sizes (including none of a kind, and batches large enough for the packed ingest path),
 random modes and, where the model allows it, the on-demand mode with queries.  Bar as in test_gpu_parity: affected
 lists bit-exact; embeddings element-wise 1e-4 for the normalised models, row-normalised 1e-4 for the plain-sum
