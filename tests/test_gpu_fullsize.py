@@ -1,4 +1,4 @@
-"""The five configurations at full size, in the launch configuration bench.py times: chained batches, then the whole
+"""The five configurations at full size (and the typed-edge models on config 2's graph), in the launch configuration bench.py times: chained batches, then the whole
 final-layer cache against one fp64 full-neighbour forward of the oracle on the final snapshot, and the affected
 list of the last batch bit-exact for every model.  Config 2 runs its 100 chained batches.  Each case prints its
 steps (generation and the oracle forward of the 100M-200M edge graphs take tens of seconds each)."""
@@ -14,7 +14,10 @@ pytestmark = pytest.mark.gpu
 
 
 def run_config(S, oracle, index, batch_sizes):
-    cfg = wl.config(index - 1)
+    run_workload(S, oracle, wl.config(index - 1), batch_sizes)
+
+
+def run_workload(S, oracle, cfg, batch_sizes):
     t0 = time.time()
     src, dst, w, x, params, stream = wl.build(cfg, seed=0)
     print("[%s] generated in %.0fs" % (cfg.name, time.time() - t0), flush=True)
@@ -85,3 +88,15 @@ def test_config4_full_size(S, oracle):
 
 def test_config5_full_size(S, oracle):
     run_config(S, oracle, 5, [50000, 50000])
+
+
+@pytest.mark.parametrize("name", ["rgcn", "rgat"])
+def test_typed_edge_models_at_config2_size(S, oracle, name):
+    """The typed-edge models of Table II have no configuration of their own: they run on config 2's graph (1 M vertices,
+    20 M edges, four relations) and batches, 20 chained batches, with the same checks as the five configurations."""
+    if name == "rgcn":
+        spec = wl.ModelSpec(wl.RGCN, [128, 128, 64], weighted=True, n_relations=4)
+    else:
+        spec = wl.ModelSpec(wl.RGAT, [128, 64, 64], head_dim=64, weighted=True, n_relations=4)
+    cfg = wl.Workload("cfg2_as_" + name, spec, 1_000_000, 20_000_000, 500, 500, 100, 20)
+    run_workload(S, oracle, cfg, [1000] * 20)
