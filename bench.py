@@ -72,6 +72,9 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
     if args.agg_only:
         cfg.spec.agg_only = True
         cfg.name = cfg.name + "_agg_only"
+    if args.aggregate_first:
+        cfg.spec.aggregate_first = True
+        cfg.name = cfg.name + "_aggregate_first"
     if args.batch_edges:
         frac = cfg.n_ins / max(1, cfg.n_ins + cfg.n_del)
         cfg.n_ins = int(round(args.batch_edges * frac))
@@ -132,7 +135,12 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
             # algorithmic bytes of the gather launch: per delta message its in-list id and slot-map entry (8 B);
             # the delta rows: every changed source row once (4*d) while the delta buffer fits the 256 MB Infinity
             # Cache, else one row per delta message; every affected aggregate row read and written (8*d)
-            d_agg = dims[l + 1] if cfg.spec.kind in (wl.GAT, wl.RGCN, wl.RGAT) else (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)
+            # GCN and GIN layers that narrow apply their (first) weight matrix to the messages before the aggregation:
+            # the gathered rows and the cached aggregate are then as wide as the layer's output
+            weights_first = (cfg.spec.kind in (wl.GCN, wl.GIN) and dims[l + 1] < d_in and not cfg.spec.agg_only
+                             and not cfg.spec.aggregate_first)
+            d_agg = dims[l + 1] if cfg.spec.kind in (wl.GAT, wl.RGCN, wl.RGAT) or weights_first else \
+                (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)
             row_fetches = ls.n_src if ls.n_src * 4.0 * d_agg <= INFINITY_CACHE_BYTES else ls.n_pairs
             gbytes = ls.n_pairs * 8.0 + row_fetches * 4.0 * d_agg + ls.n_affected * 8.0 * d_agg if ls.n_src else 0.0
             kin = (2 if cfg.spec.kind in (wl.SAGE_MEAN, wl.COMMNET, wl.PINSAGE) else 1) * d_in
@@ -146,6 +154,13 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
             if cfg.spec.kind == wl.RGCN:                         # its R message rows per changed source, likewise
                 flop += 2.0 * ls.n_src * d_in * cfg.spec.n_relations * dims[l + 1]
             upd_ms = ls.ms_update
+            if weights_first:
+                # x W on the rows whose input changed (timed before the gather, under "items"); GCN has no product left
+                # in its update, GIN its second one
+                flop = 2.0 * ls.n_src * d_in * dims[l + 1]
+                if cfg.spec.kind == wl.GIN:
+                    flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]
+                upd_ms = ls.ms_update + ls.ms_items
             if cfg.spec.kind == wl.RGAT:
                 # the GAT path with the relations as groups: z is R groups wide, a fetched row is one group's part
                 zdim = cfg.spec.n_relations * dims[l + 1]
@@ -241,7 +256,7 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
     # HBM bytes per launch measured with rocprofv3 counters on this workload: bench.py cannot run the profiler on
     # itself, so the figure is read from the committed summary of the same command (profiles/), which is named
     traffic, traffic_source = None, None
-    if args.scale == 1.0 and not args.batch_edges and not args.model and not args.agg_only:
+    if args.scale == 1.0 and not args.batch_edges and not args.model and not args.agg_only and not args.aggregate_first:
         for tpath in sorted(glob.glob(os.path.join(ROOT, "profiles", "*_%s_*.txt" % cfg.name))):
             for line in open(tpath):
                 if line.startswith("traffic_bytes_per_launch:"):
@@ -349,6 +364,8 @@ def main():
     ap.add_argument("--batch-edges", type=int, default=0, help="override the batch size (edges, config 3 sweep)")
     ap.add_argument("--model", choices=["commnet", "pinsage", "agnn", "monet", "ggcn", "rgcn", "rgat"], default=None,
                     help="run another Table II model on the chosen config's graph, widths and batches (implies --only)")
+    ap.add_argument("--aggregate-first", action="store_true",
+                    help="GCN / GIN configs: never apply a layer's weights before its aggregation (implies --only)")
     ap.add_argument("--agg-only", action="store_true",
                     help="GCN configs: keep only the aggregates of hidden layers (storage option; implies --only)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -364,7 +381,7 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(3)
-    only = args.only or args.model is not None or args.agg_only or args.batch_edges > 0 or args.scale != 1.0
+    only = args.only or args.model is not None or args.agg_only or args.aggregate_first or args.batch_edges > 0 or args.scale != 1.0
     t_all = time.time()
     ceilings = stream_ceilings(torch, nb)
     log("stream ceilings: read %.0f GB/s, copy %.0f GB/s" % (ceilings["read_GBps"], ceilings["copy_GBps_read_plus_write"]))

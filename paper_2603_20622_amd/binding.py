@@ -34,7 +34,7 @@ class nrt_model_desc(ctypes.Structure):
                 ("att_src", c_fp * NRT_MAX_LAYERS), ("att_dst", c_fp * NRT_MAX_LAYERS),
                 ("agnn_beta", ctypes.c_float * NRT_MAX_LAYERS), ("monet_kernels", ctypes.c_int32),
                 ("monet_mu", c_fp * NRT_MAX_LAYERS), ("monet_prec", c_fp * NRT_MAX_LAYERS), ("agg_only", ctypes.c_int32),
-                ("n_relations", ctypes.c_int32)]
+                ("n_relations", ctypes.c_int32), ("aggregate_first", ctypes.c_int32)]
 
 
 class nrt_batch(ctypes.Structure):
@@ -202,6 +202,7 @@ def make_desc(spec, dev_params) -> nrt_model_desc:
     d.agg_only = int(bool(getattr(spec, "agg_only", False)))
     d.monet_kernels = int(getattr(spec, "monet_kernels", 0))
     d.n_relations = int(getattr(spec, "n_relations", 0))
+    d.aggregate_first = int(bool(getattr(spec, "aggregate_first", False)))
     for l, (mu, prec) in enumerate(zip(dev_params.get("monet_mu", []), dev_params.get("monet_prec", []))):
         if mu is not None:
             d.monet_mu[l], d.monet_prec[l] = mu.data_ptr(), prec.data_ptr()

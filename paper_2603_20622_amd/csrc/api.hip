@@ -61,6 +61,12 @@ struct nrt_cache {
                                         // kernel responses of h^l), null otherwise
     int monet_J;                        // MoNet: kernels per layer = width of its payload and aggregate
     int n_rel;                          // RGCN: relations; MP[l] then holds n_rel message rows W_r h^l per vertex
+    // GCN, GIN: layer l applies its (first) weight matrix to the messages before the aggregation when that makes the
+    // aggregated rows narrower (d_l < d_{l-1}): sum_u c_uv (x_u W) = (sum_u c_uv x_u) W.  MP[l-1] = H^{l-1} W then plays
+    // the part of PinSAGE's message table, the cached aggregate S^l is d_l wide, and the update has no (GCN) or one
+    // product less (GIN).  Index: the destination layer l = 1..L.
+    bool tf[NRT_MAX_LAYERS + 1];
+    int no_reorder;
     float* muT[NRT_MAX_LAYERS];         // MoNet: [d_l][J] transposed means / precisions of layer l+1
     float* precT[NRT_MAX_LAYERS];
     float* Wt[NRT_MAX_LAYERS][2];
@@ -409,6 +415,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         c->MP[l] = nullptr;
         if (c->kind == NRT_PINSAGE && l < c->L) c->MP[l] = b.take<float>(n * c->dims[l]);
         if (c->kind == NRT_RGCN && l < c->L) c->MP[l] = b.take<float>(n * c->n_rel * c->dims[l + 1]);
+        if (l < c->L && c->tf[l + 1]) c->MP[l] = b.take<float>(n * c->dims[l + 1]);
         if (c->kind == NRT_MONET && l < c->L) {
             c->MP[l] = b.take<float>(n * c->monet_J);
             c->muT[l] = b.take<float>((size_t)c->dims[l] * c->monet_J);
@@ -427,7 +434,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->S[0] = nullptr;
     const bool gat = c->kind == NRT_GAT || c->kind == NRT_RGAT;
     for (int l = 1; l <= c->L; ++l) {
-        c->dagg[l] = gat ? c->zdim : (c->kind == NRT_RGCN ? c->dims[l] : (c->kind == NRT_MONET ? c->monet_J : c->dims[l - 1]));
+        c->dagg[l] = gat ? c->zdim : ((c->kind == NRT_RGCN || c->tf[l]) ? c->dims[l] : (c->kind == NRT_MONET ? c->monet_J : c->dims[l - 1]));
         c->S[l] = b.take<float>(n * c->dagg[l]);
         if (gat) {
             c->Z[l] = b.take<float>(n * c->zdim);
@@ -547,6 +554,9 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     c->monet_J = d->kind == NRT_MONET ? d->monet_kernels : 0;
     c->n_rel = (d->kind == NRT_RGCN || d->kind == NRT_RGAT) ? d->n_relations : 0;
     if (d->kind == NRT_RGAT) c->heads = d->n_relations;          // one softmax group per relation
+    c->no_reorder = d->aggregate_first ? 1 : 0;
+    for (int l = 1; l <= c->L; ++l)
+        c->tf[l] = (d->kind == NRT_GCN || d->kind == NRT_GIN) && !d->agg_only && !d->aggregate_first && d->dims[l] < d->dims[l - 1];
     c->max_edges = max_edges;
     c->max_feats = max_feats;
     return NRT_OK;
@@ -573,7 +583,7 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
 }
 
 // what the in-neighbours of layer l+1 aggregate: h^l itself, or its transform for PinSAGE
-static inline const float* payload_rows(const nrt_cache* c, int l) { return has_message_cache(c->kind) ? c->MP[l] : c->H[l]; }
+static inline const float* payload_rows(const nrt_cache* c, int l) { return c->MP[l] ? c->MP[l] : c->H[l]; }
 
 // PinSAGE, MoNet, RGCN (Table II): the message of a vertex (ReLU(h^l Q + q); Gaussian kernel responses of h^l; W_r h^l
 // for every relation r) on the listed rows
@@ -608,6 +618,17 @@ static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_
     a.Wt = c->Wt[l][1];
     a.bias = c->bias[l][1];
     a.act = 1;
+    if (c->tf[l + 1]) {                    // GCN, GIN: h^l W, the layer's (first) matrix applied before the aggregation
+        a.N = c->dims[l + 1];
+        a.Wt = c->Wt[l][0];
+        a.bias = nullptr;
+        a.act = 0;
+        if (c->kind == NRT_GCN) {          // the payload is the row over sqrt(d): its delta carries the degree change
+            a.indeg = c->g->in.deg;
+            a.indeg_old = c->indeg_old;
+            a.dp_scale_gcn = 1;
+        }
+    }
     if (c->kind == NRT_RGCN) {             // h^l [W_0 | ... | W_{R-1}]: row v of the product is the R message rows of v
         a.N = c->n_rel * c->dims[l + 1];
         a.act = 0;
@@ -698,7 +719,7 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
     a.ldp = c->dims[l - 1];
     a.N = c->dims[l];
     // PinSAGE: the next layer's payload deltas come from the transform of the changed rows, not from here
-    float* dp = (incremental && !last && !has_message_cache(c->kind)) ? c->DP[cur] : nullptr;
+    float* dp = (incremental && !last && !c->MP[l]) ? c->DP[cur] : nullptr;
     if (c->kind == NRT_MONET) {
         a.a_mode = A_PLAIN;
         a.P0 = c->S[l];
@@ -708,6 +729,36 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.bias = c->bias[l - 1][0];
         a.act = last ? 0 : 1;
         a.H = c->H[l];
+        a.n_vertices = g->n;
+        a.out_compact = last ? out_rows : nullptr;
+        a.out_cap = out_cap;
+        NRT_TRY(k_gemm(a, s));
+    } else if (c->tf[l] && c->kind == NRT_GCN) {   // the weights went into the messages: act(S_v / sqrt(d_v) + b), no product left
+        a.P0 = c->S[l];
+        a.bias = c->bias[l - 1][0];
+        a.act = last ? 0 : 1;
+        a.H = c->H[l];
+        a.DP = dp;
+        a.dp_skip_large = next_may_recompute;
+        a.n_vertices = g->n;
+        a.dp_scale_gcn = 1;
+        a.out_compact = last ? out_rows : nullptr;
+        a.out_cap = out_cap;
+        NRT_TRY(k_rowwise_update(a, s));
+    } else if (c->tf[l] && c->kind == NRT_GIN) {   // ReLU((1+eps) x_v W_a + sum_u w_uv x_u W_a + b_a) W_b + b_b: one product
+        a.a_mode = A_AXPY_BIAS_RELU;
+        a.P0 = c->MP[l - 1];
+        a.P1 = c->S[l];
+        a.axpy_c = 1.0f + c->gin_eps;
+        a.a_bias = c->bias[l - 1][0];
+        a.ldp = c->dims[l];
+        a.K = c->dims[l];
+        a.Wt = c->Wt[l - 1][1];
+        a.bias = c->bias[l - 1][1];
+        a.act = last ? 0 : 1;
+        a.H = c->H[l];
+        a.DP = dp;
+        a.dp_skip_large = next_may_recompute;
         a.n_vertices = g->n;
         a.out_compact = last ? out_rows : nullptr;
         a.out_cap = out_cap;
@@ -1018,7 +1069,7 @@ static nrt_status full_forward(nrt_cache* c, hipStream_t s) {
             st = run_agnn_layer(c, l, nullptr, nullptr, n, nullptr, nullptr, n, false, 0, 0, nullptr, 0, s);
             continue;
         }
-        if (has_message_cache(c->kind)) st = run_transform(c, l - 1, nullptr, n, nullptr, nullptr, false, s);
+        if (c->MP[l - 1]) st = run_transform(c, l - 1, nullptr, n, nullptr, nullptr, false, s);
         if (st == NRT_OK) st = run_gather(c, l, false, 0, false, 0, s);
         if (st == NRT_OK) st = run_update(c, l, nullptr, n, nullptr, false, 0, nullptr, 0, false, s);
     }
@@ -1397,8 +1448,8 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
             if (q.ids) NRT_TRY(k_copy_i32((int32_t*)c->stale_prev[l], (const int32_t*)c->stale[l], (n + 31) / 32, s));
             // h^0 is never stale, so neither may be what layer 1 caches of it by vertex: message rows, z and the
             // attention scalars, inverse norms, gate projections
-            if (has_message_cache(c->kind) && l == 1)
-                NRT_TRY(run_transform(c, 0, c->list[0], src_bound, &c->lc[0].count, nullptr, false, s));
+            if (c->MP[0] && l == 1)                        // (a query folded with this batch takes the rows' deltas from DP[0])
+                NRT_TRY(run_transform(c, 0, c->list[0], src_bound, &c->lc[0].count, foldq ? c->DP[0] : nullptr, false, s));
             if (c->is_gat && l == 1)
                 NRT_TRY(run_gat_project(c, 1, c->list[0], &c->lc[0].count, src_bound, true, false, nullptr, s));
             if (agnn_family(c->kind) && l == 1)
@@ -1428,7 +1479,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
             // clearly dense layer launches one kernel, in between both are launched and the device counter decides
             const int64_t pn = prev_n_list[l - 1];
             const int sparse_hint = !had_history ? 1 : (pn * 64 <= n ? 2 : (pn * 4 > n ? 0 : 1));
-            if (has_message_cache(c->kind))
+            if (c->MP[l - 1])
                 NRT_TRY(run_transform(c, l - 1, c->list[l - 1], src_bound, &c->lc[l - 1].count, inc ? c->DP[prev] : nullptr,
                                       may_rec[l], s));
             if (c->agg_only && l < c->L) {
@@ -1593,7 +1644,7 @@ static nrt_status recompute_listed(nrt_cache* c, hipStream_t s) {
         }
         NRT_TRY(run_gather(c, l, false, 0, false, 0, s));
         NRT_TRY(run_update(c, l, c->list[l], n, &c->lc[l].count, false, 0, nullptr, 0, false, s));
-        if (has_message_cache(c->kind) && l < c->L)        // message rows follow every h row that is brought up to date
+        if (c->MP[l] && l < c->L)                           // message rows follow every h row that is brought up to date
             NRT_TRY(run_transform(c, l, c->list[l], n, &c->lc[l].count, nullptr, false, s));
         NRT_TRY(k_clear_listed_bits(c->stale[l], c->list[l], &c->lc[l].count, n, s));
     }
@@ -1666,6 +1717,10 @@ static nrt_status serve_query_after_batch(nrt_cache* c, const QueryArgs& q, bool
             cx.and_invert = 0;
             NRT_TRY(k_compact(nullptr, c->need_bm[l], nullptr, c->bm[1 - cur], n, c->list_redo, nullptr, c->cmp_state,
                               c->cmp_state_len, &redo[l].count, s, c->stale_prev[l], &cx));
+            // layers that aggregate transformed rows: the rows brought up to date one layer below are transformed again
+            // and leave the deltas the fold reads (layer 1: done with the batch, on the rows the batch replaced)
+            if (c->MP[l - 1] && l >= 2)
+                NRT_TRY(run_transform(c, l - 1, c->need_list[l - 1], n, &need[l - 1].count, c->DP[prev], false, s));
             // up to date before the batch: fold the deltas of the changed in-neighbours and the structural terms
             NRT_TRY(k_dst_records(c->list_fresh, n, g->in, c->recs, c->hubs, &fresh[l], false, nullptr, s));
             c->lc_use = &fresh[l];
@@ -1699,7 +1754,7 @@ static nrt_status serve_query_after_batch(nrt_cache* c, const QueryArgs& q, bool
             } else {
                 st = run_gather(c, l, false, 0, false, 0, s);
                 if (st == NRT_OK) st = run_update(c, l, c->need_list[l], n, &need[l].count, false, 0, nullptr, 0, false, s);
-                if (st == NRT_OK && has_message_cache(c->kind) && l < c->L)
+                if (st == NRT_OK && c->MP[l] && l < c->L)
                     st = run_transform(c, l, c->need_list[l], n, &need[l].count, nullptr, false, s);
             }
             c->lc_use = nullptr;

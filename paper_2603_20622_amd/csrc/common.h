@@ -282,7 +282,7 @@ struct DeltaArgs {  // layer-0 delta payloads and feature scatter
 nrt_status k_layer0_delta(const DeltaArgs& a, hipStream_t s);
 
 // ---------------------------------------------------------------- gemm.hip
-enum { A_PLAIN = 0, A_SCALE_GCN = 1, A_CONCAT_MEAN = 2, A_AXPY = 3, A_PLAIN_ADD = 4 };
+enum { A_PLAIN = 0, A_SCALE_GCN = 1, A_CONCAT_MEAN = 2, A_AXPY = 3, A_PLAIN_ADD = 4, A_AXPY_BIAS_RELU = 5 };
 struct GemmArgs {
     int64_t M; int K; int N;        // K = total inner width (CONCAT: 2*K0); M is a bound when M_dev is given
     const uint64_t* M_dev;          // number of rows on the device, or null
@@ -292,6 +292,7 @@ struct GemmArgs {
     int a_mode;
     const float* P0; const float* P1; int ldp;   // source rows (width ldp each)
     float axpy_c;                   // A_AXPY: c*P0 + P1
+    const float* a_bias;            // A_AXPY_BIAS_RELU: [K], the operand is ReLU(c*P0 + P1 + a_bias)
     const float* add;               // A_PLAIN_ADD: before the activation y += add[v][:] / add_indeg[v] (RGCN: W_o h_v + mean message);
     const int32_t* add_indeg;       // rows of width N by vertex; a zero count adds nothing; null add_indeg: the rows themselves
     const int32_t* indeg;           // for A_SCALE_GCN / A_CONCAT_MEAN
@@ -311,6 +312,9 @@ struct GemmArgs {
     int64_t n_vertices;
 };
 nrt_status k_gemm(const GemmArgs& a, hipStream_t s);
+// The write-back of k_gemm without a product: y = act(P0[v] / sqrt(indeg(v)+1) + bias) on the listed rows, P0 of width N
+// (a GCN layer whose weights were applied to the messages before the aggregation); H, DP, out_compact as for k_gemm
+nrt_status k_rowwise_update(const GemmArgs& a, hipStream_t s);
 nrt_status k_transpose(const float* W, float* Wt, int K, int N, hipStream_t s);   // Wt[n][k] = W[k][n]
 
 // ---------------------------------------------------------------- gat.hip

@@ -9,6 +9,8 @@
 //   A_AXPY         c * P0[v] + P1[v]                       (GIN: (1+eps) x_v + cached weighted sum)
 //   A_PLAIN_ADD    P0[v], and add[v] / count(v) joins the product before the activation
 //                                                          (RGCN: W_o h_v + mean of the relation messages)
+//   A_AXPY_BIAS_RELU  ReLU(c * P0[v] + P1[v] + a_bias)     (GIN with its first product applied to the messages before
+//                                                           the aggregation: P0 = x W_a by vertex, P1 = cached sum of those)
 // The epilogue is the cache write-back: it stores the new row into h^l[v] and, for the next layer, the
 // change of the source payload dp = y_new*cn - y_old*co (cn = co = 1 except for GCN, where the payload is
 // y / sqrt(d_v) and the degree may have changed), so no separate pass re-reads the rows.
@@ -33,6 +35,8 @@ __device__ inline float gcn_scale(int32_t indeg) { return 1.0f / sqrtf((float)(i
 // Branch-free on purpose: the address is clamped into the row, the raw value stays in registers and the mask /
 // scale `mul` is applied only when the slice is written to LDS one iteration later, so that the loads of a slice
 // are issued back to back and nothing waits for them before the MFMAs of the current slice have been issued.
+constexpr bool two_sources(int amode) { return amode == A_AXPY || amode == A_AXPY_BIAS_RELU; }
+
 template <int AMODE>
 __device__ inline void load_a(const GemmArgs& g, int64_t v, float sc, int k, bool ok, float4& raw, float4& raw2, float& mul) {
     const bool live = ok && k < g.K;
@@ -101,11 +105,11 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    float4 ra[A_LOADS], ra2[AMODE == A_AXPY ? A_LOADS : 1], rb[B_LOADS];
+    float4 ra[A_LOADS], ra2[two_sources(AMODE) ? A_LOADS : 1], rb[B_LOADS];
     float am[A_LOADS], bmul[B_LOADS];
     auto fetch = [&](int k0) {
 #pragma unroll
-        for (int p = 0; p < A_LOADS; ++p) load_a<AMODE>(g, av[p], asc[p], k0 + lk, aok[p], ra[p], ra2[AMODE == A_AXPY ? p : 0], am[p]);
+        for (int p = 0; p < A_LOADS; ++p) load_a<AMODE>(g, av[p], asc[p], k0 + lk, aok[p], ra[p], ra2[two_sources(AMODE) ? p : 0], am[p]);
 #pragma unroll
         for (int p = 0; p < B_LOADS; ++p) {
             const int n = col_base + lr + RPP * p;
@@ -122,10 +126,16 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
 #pragma unroll
         for (int p = 0; p < A_LOADS; ++p) {
             float4 t = ra[p];
-            if (AMODE == A_AXPY) {
+            if (two_sources(AMODE)) {
                 const float4 q = ra2[p];
                 t.x = fmaf(g.axpy_c, t.x, q.x); t.y = fmaf(g.axpy_c, t.y, q.y);
                 t.z = fmaf(g.axpy_c, t.z, q.z); t.w = fmaf(g.axpy_c, t.w, q.w);
+            }
+            if (AMODE == A_AXPY_BIAS_RELU) {                 // the slice's k range is k0 + lk .. +3 (clamped like the loads)
+                const int kb = k0 + lk < g.K ? k0 + lk : g.K - 4;
+                const float4 ab = *reinterpret_cast<const float4*>(g.a_bias + kb);
+                t.x = fmaxf(t.x + ab.x, 0.f); t.y = fmaxf(t.y + ab.y, 0.f);
+                t.z = fmaxf(t.z + ab.z, 0.f); t.w = fmaxf(t.w + ab.w, 0.f);
             }
             t.x *= am[p]; t.y *= am[p]; t.z *= am[p]; t.w *= am[p];
             *reinterpret_cast<float4*>(&As[(lr + RPP * p) * LDS_STRIDE + lk]) = t;
@@ -222,6 +232,40 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
   }
 }
 
+// y = act(P0[v] * gcn_scale(v) + bias) with the same write-back as the GEMM's epilogue; a thread owns four columns of a row
+__global__ void rowwise_update_kernel(GemmArgs g) {
+    const int64_t M = g.M_dev ? (int64_t)*g.M_dev : g.M;
+    float* const DPout = (g.dp_skip_large && 4 * M > g.n_vertices) ? nullptr : g.DP;
+    const int nq = g.N >> 2;
+    const int64_t total = M * nq, stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const int64_t m = i / nq;
+        const int n = (int)(i - m * nq) << 2;
+        const int64_t v = g.rows ? (int64_t)g.rows[m] : m;
+        const float sc = gcn_scale(g.indeg[v]);
+        const float4 x = *reinterpret_cast<const float4*>(g.P0 + v * g.N + n);
+        float y[4] = {x.x * sc, x.y * sc, x.z * sc, x.w * sc};
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            if (g.bias) y[t] += g.bias[n + t];
+            if (g.act == 1) y[t] = fmaxf(y[t], 0.f);
+            else if (g.act == 2) y[t] = y[t] > 0.f ? y[t] : expm1f(y[t]);
+        }
+        const float4 yo = make_float4(y[0], y[1], y[2], y[3]);
+        if (g.out_compact && m < g.out_cap) *reinterpret_cast<float4*>(g.out_compact + m * g.N + n) = yo;
+        if (g.H) {
+            if (DPout) {
+                const float4 o = *reinterpret_cast<const float4*>(g.H + v * g.N + n);
+                float cn = 1.0f, co = 1.0f;
+                if (g.dp_scale_gcn) { cn = sc; co = gcn_scale(g.indeg_old[v]); }
+                const float4 d = g.dp_store_old ? o : make_float4(yo.x * cn - o.x * co, yo.y * cn - o.y * co, yo.z * cn - o.z * co, yo.w * cn - o.w * co);
+                *reinterpret_cast<float4*>(DPout + m * g.N + n) = d;
+            }
+            *reinterpret_cast<float4*>(g.H + v * g.N + n) = yo;
+        }
+    }
+}
+
 __global__ void transpose_kernel(const float* W, float* Wt, int K, int N) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < K * N) {
@@ -255,8 +299,22 @@ nrt_status k_gemm(const GemmArgs& g, hipStream_t s) {
         if (!g.add) { nrt_set_error("gemm: the added rows are missing"); return NRT_ERR_INVALID_ARG; }
         launch_gemm<A_PLAIN_ADD>(g, s);
         break;
+    case A_AXPY_BIAS_RELU:
+        if (!g.a_bias) { nrt_set_error("gemm: the operand bias is missing"); return NRT_ERR_INVALID_ARG; }
+        launch_gemm<A_AXPY_BIAS_RELU>(g, s);
+        break;
     default: launch_gemm<A_AXPY>(g, s); break;
     }
+    LAUNCH_CHECK();
+    return NRT_OK;
+}
+
+nrt_status k_rowwise_update(const GemmArgs& g, hipStream_t s) {
+    if (g.M <= 0) return NRT_OK;
+    if (g.N % 4 || !g.P0 || !g.indeg) { nrt_set_error("rowwise update: bad arguments"); return NRT_ERR_INVALID_ARG; }
+    int64_t blocks = cdiv(g.M * (g.N / 4), 256);
+    if (blocks > 8192) blocks = 8192;
+    rowwise_update_kernel<<<(unsigned)blocks, 256, 0, s>>>(g);
     LAUNCH_CHECK();
     return NRT_OK;
 }

@@ -175,7 +175,9 @@ __global__ void structural_fold_kernel(FoldArgs a) {
         const int32_t b = a.off[s], e = a.off[s + 1];
         float* dst = a.SD[l] + s * D;
         for (int col = lane * 4; col < D; col += 256) {
-            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            // a destination can collect hundreds of terms of one batch and they are added one after the other, so the sum
+            // is compensated (Kahan): its error stays that of a single rounding instead of growing with the run's length
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f), comp = acc;
             for (int32_t j = b; j < e; ++j) {
                 const int32_t op = a.ord[j];
                 const bool is_del = op >= a.n_ins;
@@ -191,7 +193,10 @@ __global__ void structural_fold_kernel(FoldArgs a) {
                     c = is_del ? -1.0f : 1.0f;
                 }
                 const float4 x = *reinterpret_cast<const float4*>(a.Hprev[l] + row * D + col);
-                acc.x = fmaf(c, x.x, acc.x); acc.y = fmaf(c, x.y, acc.y); acc.z = fmaf(c, x.z, acc.z); acc.w = fmaf(c, x.w, acc.w);
+                const float4 y = make_float4(fmaf(c, x.x, -comp.x), fmaf(c, x.y, -comp.y), fmaf(c, x.z, -comp.z), fmaf(c, x.w, -comp.w));
+                const float4 t = make_float4(acc.x + y.x, acc.y + y.y, acc.z + y.z, acc.w + y.w);
+                comp = make_float4((t.x - acc.x) - y.x, (t.y - acc.y) - y.y, (t.z - acc.z) - y.z, (t.w - acc.w) - y.w);
+                acc = t;
             }
             *reinterpret_cast<float4*>(dst + col) = acc;
         }

@@ -45,8 +45,8 @@ def test_argument_errors_without_gpu():
 def test_struct_sizes_match_header():
     from paper_2603_20622_amd import binding as nb
     # int32*2 + int32*5 + int32*2 + float*2 = 44 bytes, padded to 48, then 8+8+4+4 pointers, then 4 floats, an int32 (padded to 8),
-    # 4+4 more pointers and two int32
-    assert ctypes.sizeof(nb.nrt_model_desc) == 48 + 8 * (8 + 8 + 4 + 4) + 4 * 4 + 8 + 8 * (4 + 4) + 8
+    # 4+4 more pointers and three int32 (padded to 16)
+    assert ctypes.sizeof(nb.nrt_model_desc) == 48 + 8 * (8 + 8 + 4 + 4) + 4 * 4 + 8 + 8 * (4 + 4) + 16
     assert ctypes.sizeof(nb.nrt_batch) == 10 * 8
     assert ctypes.sizeof(nb.nrt_layer_stats) == 5 * 8 + 6 * 4
 

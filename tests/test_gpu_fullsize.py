@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from paper_2603_20622_amd import workloads as wl
-from tests.test_gpu_parity import TOL, assert_parity, rel_err, row_err
+from tests.test_gpu_parity import TOL, assert_parity, plain_order, rel_err, row_err
 
 pytestmark = pytest.mark.gpu
 
@@ -49,9 +49,9 @@ def run_workload(S, oracle, cfg, batch_sizes):
     del ses
     fresh = None
     if cfg.spec.kind == wl.GIN:
-        # the fp32 floor of the un-normalised model at this size: a from-scratch forward of the same library on the
-        # final snapshot against the same oracle rows
-        ses2 = S.Session(cfg.spec, params, cfg.n, fs, fd, fw, cur_x, max_batch_edges=1024, max_batch_feats=64)
+        # the fp32 floor of the un-normalised model at this size: a from-scratch forward of the same library, in the plain
+        # operation order, on the final snapshot against the same oracle rows
+        ses2 = S.Session(plain_order(cfg.spec), params, cfg.n, fs, fd, fw, cur_x, max_batch_edges=1024, max_batch_feats=64)
         fresh = ses2.layer(cfg.spec.n_layers).cpu().numpy()
         ses2.close()
         del ses2

@@ -37,8 +37,8 @@ def assert_parity(kind, gpu, ref, what, fresh=None):
     single elements are differences of terms 1e3-1e6 times larger than the result; fp32 caches cannot hold such an
     element to 1e-4 of max(|oracle|, 1) (a cached row of magnitude 1e6 already carries 0.06 of absolute rounding).
     What gates these models here is the row-normalised 1e-4 and, against drift of the incremental path, an
-    element-wise error no worse than 3x (6x for G-GCN) that of a from-scratch fp32 forward on the GPU (`fresh`) when
-    the test supplies one.  The stated element-wise bar is NOT replaced: every
+    element-wise error no worse than 3x (6x for G-GCN) that of a from-scratch fp32 forward on the GPU (`fresh`, taken
+    in the plain operation order, see plain_order) when the test supplies one.  The stated element-wise bar is NOT replaced: every
     such check is logged in ELEMENTWISE_LOG and test_gpu_random.py ends with a test, expected to fail, that holds
     the logged errors to 1e-4."""
     if kind not in UNNORMALISED:
@@ -54,6 +54,14 @@ def assert_parity(kind, gpu, ref, what, fresh=None):
         # The summation order is fixed (no atomics), so these ratios are reproducible, not a draw of scheduling noise.
         factor = 6.0 if kind == wl.GGCN else 3.0
         assert err <= max(TOL, factor * floor), what
+
+
+def plain_order(spec):
+    """The same model with every layer computed in the order its definition is written (aggregate, then apply the
+    weights): the from-scratch fp32 forward that serves as the rounding floor of a plain-sum model is taken in that
+    order, so that the floor does not move when the library reorders a layer's arithmetic."""
+    import dataclasses
+    return dataclasses.replace(spec, aggregate_first=True)
 
 
 @pytest.fixture(scope="module")
@@ -128,7 +136,7 @@ def test_chained_batches_match_oracle(S, oracle, kind, L):
         sets = oracle.affected_sets(spec, n, cur[0], cur[1], batch)
         ids = ses.ids[:na].cpu().numpy()
         assert np.array_equal(ids, sets[-1]), "final affected list differs"
-        fresh = S.Session(spec, params, n, *cur) if kind in UNNORMALISED else None
+        fresh = S.Session(plain_order(spec), params, n, *cur) if kind in UNNORMALISED else None
         for l in range(1, L + 1):
             assert np.array_equal(ses.affected(l), sets[l - 1]), "layer %d affected list differs" % l
             got = ses.layer(l).cpu().numpy()
@@ -287,6 +295,8 @@ def test_gin_cancellation_is_guarded(S, oracle):
     (wl.AGNN, [300, 520, 8], 1, 0),             # cosine rows of two and of four 16-byte pieces per lane
     (wl.MONET, [36, 132, 8], 1, 0),             # 260 kernels: wider than every layer
     (wl.GGCN, [260, 36, 8], 1, 0),              # gate rows of two 16-byte pieces per lane
+    (wl.GCN, [1024, 512, 260], 1, 0),           # weights applied before the aggregation at both layers; 512-wide message rows
+    (wl.GIN, [36, 260, 8], 1, 0),               # wider, then narrower: aggregate x at layer 1, x W_a at layer 2
     (wl.RGCN, [20, 132, 8], 1, 0),              # message rows of 132 floats, 3 x 132 per source
     (wl.RGCN, [260, 12, 4], 1, 0),              # narrowest message rows
     (wl.RGAT, [24, 256, 256], 1, 256),          # 3 relations x 256: 768-wide projected rows
@@ -511,7 +521,7 @@ def test_large_batches_pack_updates_per_wave(S, oracle, kind):
         sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
         assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1]), k
         ref = oracle.forward(spec, params, n, *cur)
-        fresh = S.Session(spec, params, n, *cur) if kind in UNNORMALISED else None
+        fresh = S.Session(plain_order(spec), params, n, *cur) if kind in UNNORMALISED else None
         assert_parity(kind, ses.layer(2).cpu().numpy(), ref[-1], ("packed", k),
                       None if fresh is None else fresh.layer(2).cpu().numpy())
     # one bad update among thousands: an absent edge deleted, a present edge inserted, a repeated entry; the same on
@@ -562,7 +572,8 @@ def test_gcn_aggregate_only_storage(S, oracle):
     n, src, dst, w, x, spec, params, stream = small_case(wl.GCN, seed=9, L=3)
     lean_spec = dataclasses.replace(spec, agg_only=True)
     ses = S.Session(lean_spec, params, n, src, dst, w, x)
-    kept = nb.nrt_cache_workspace_bytes(ses.graph, nb.make_desc(spec, ses.dev_params), 1 << 16, 1 << 12)
+    # against the cache that keeps the hidden rows and aggregates in the same (plain) order
+    kept = nb.nrt_cache_workspace_bytes(ses.graph, nb.make_desc(plain_order(spec), ses.dev_params), 1 << 16, 1 << 12)
     lean = nb.nrt_cache_workspace_bytes(ses.graph, ses.desc, 1 << 16, 1 << 12)
     hidden_bytes = 4 * n * (spec.dims[1] + spec.dims[2])
     edge_rows_bytes = 4 * ((1 << 16) + 1) * (spec.dims[1] + spec.dims[2] + 1)
@@ -639,7 +650,7 @@ def test_in_degrees_at_the_item_boundaries(S, oracle, kind):
 
     def check(what):
         ref = oracle.forward(spec, params, n, *cur)
-        fresh = S.Session(spec, params, n, *cur) if kind in UNNORMALISED else None
+        fresh = S.Session(plain_order(spec), params, n, *cur) if kind in UNNORMALISED else None
         for l in (1, 2):
             assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (what, l),
                           None if fresh is None else fresh.layer(l).cpu().numpy())
@@ -691,7 +702,7 @@ def test_batches_at_and_beyond_the_declared_bounds(S, oracle):
     cur = oracle.apply_batch(n, src, dst, w, x, b)
     assert np.array_equal(ses.ids[:na].cpu().numpy(), oracle.affected_sets(spec, n, cur[0], cur[1], b)[-1])
     ref = oracle.forward(spec, params, n, *cur)
-    fresh = S.Session(spec, params, n, *cur)
+    fresh = S.Session(plain_order(spec), params, n, *cur)
     assert_parity(wl.GIN, ses.layer(2).cpu().numpy(), ref[-1], "at the bounds", fresh.layer(2).cpu().numpy())
     base = ses.layer(2).cpu().numpy().copy()
     for what, (ni, nd, nf), status in (("edges", (151, 150, 0), nb.NRT_ERR_BAD_BATCH),
@@ -879,6 +890,33 @@ def test_batches_served_with_a_query_match_oracle(S, oracle, kind):
         assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "eager again", l))
 
 
+@pytest.mark.parametrize("kind", [wl.GCN, wl.GIN])
+@pytest.mark.parametrize("L", [2, 3])
+def test_aggregate_first_option_matches_oracle(S, oracle, kind, L):
+    """GCN and GIN layers whose output is narrower than their input apply their weights to the messages before the
+    aggregation (the cached aggregate is then as wide as the layer's output); aggregate_first switches that off.  Both
+    ways give the oracle's rows, the same affected lists, and differ from each other only by rounding."""
+    n, src, dst, w, x, spec, params, stream = small_case(kind, seed=40 + L, L=L)
+    dims = spec.dims
+    assert dims[L] < dims[L - 1]                          # the last layer of small_case narrows
+    plain = wl.ModelSpec(kind, list(dims), weighted=spec.weighted, aggregate_first=True)
+    a = S.Session(spec, params, n, src, dst, w, x)
+    b = S.Session(plain, params, n, src, dst, w, x)
+    assert a.aggregate(L).shape[1] == dims[L] and b.aggregate(L).shape[1] == dims[L - 1]
+    cur = (src, dst, w, x)
+    for k in range(4):
+        batch = stream.next_batch(40, 40, 8 if k % 2 == 0 else 0)
+        na, nb_ = a.apply(batch), b.apply(batch)
+        cur = oracle.apply_batch(n, *cur, batch)
+        ref = oracle.forward(spec, params, n, *cur)
+        assert na == nb_ and np.array_equal(a.ids[:na].cpu().numpy(), b.ids[:nb_].cpu().numpy())
+        fresh = S.Session(plain_order(spec), params, n, *cur) if kind in UNNORMALISED else None
+        for l in range(1, L + 1):
+            f = None if fresh is None else fresh.layer(l).cpu().numpy()
+            assert_parity(kind, a.layer(l).cpu().numpy(), ref[l - 1], (kind, "weights first", k, l), f)
+            assert_parity(kind, b.layer(l).cpu().numpy(), ref[l - 1], (kind, "aggregate first", k, l), f)
+
+
 @pytest.mark.parametrize("kind", [wl.RGCN, wl.RGAT])
 def test_typed_edges_reject_bad_relation_ids(S, oracle, kind):
     """RGCN and RGAT read the edge weight as a relation id: a weight that is not an integer in [0, R) is refused when the caches
@@ -986,6 +1024,6 @@ def test_derived_direction_has_a_fixed_order(S, oracle, give):
     cur = oracle.apply_batch(n, src, dst, w, x, b)
     sets = oracle.affected_sets(spec, n, cur[0], cur[1], b)
     assert np.array_equal(ses.ids[:na].cpu().numpy(), sets[-1])
-    fresh2 = S.Session(spec, params, n, *cur)
+    fresh2 = S.Session(plain_order(spec), params, n, *cur)
     assert_parity(wl.GIN, ses.layer(2).cpu().numpy(), oracle.forward(spec, params, n, *cur)[-1], ("derived batch", give),
                   fresh2.layer(2).cpu().numpy())
