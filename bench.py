@@ -137,8 +137,8 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
             # Cache, else one row per delta message; every affected aggregate row read and written (8*d)
             # GCN and GIN layers that narrow apply their (first) weight matrix to the messages before the aggregation:
             # the gathered rows and the cached aggregate are then as wide as the layer's output
-            weights_first = (cfg.spec.kind in (wl.GCN, wl.GIN) and dims[l + 1] < d_in and not cfg.spec.agg_only
-                             and not cfg.spec.aggregate_first)
+            weights_first = (cfg.spec.kind in (wl.GCN, wl.GIN, wl.SAGE_MEAN, wl.COMMNET) and dims[l + 1] < d_in
+                             and not cfg.spec.agg_only and not cfg.spec.aggregate_first)
             d_agg = dims[l + 1] if cfg.spec.kind in (wl.GAT, wl.RGCN, wl.RGAT) or weights_first else \
                 (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)
             row_fetches = ls.n_src if ls.n_src * 4.0 * d_agg <= INFINITY_CACHE_BYTES else ls.n_pairs
@@ -160,6 +160,8 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
                 flop = 2.0 * ls.n_src * d_in * dims[l + 1]
                 if cfg.spec.kind == wl.GIN:
                     flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]
+                if cfg.spec.kind in (wl.SAGE_MEAN, wl.COMMNET):      # the self half of the update stays a product
+                    flop += 2.0 * ls.n_affected * d_in * dims[l + 1]
                 upd_ms = ls.ms_update + ls.ms_items
             if cfg.spec.kind == wl.RGAT:
                 # the GAT path with the relations as groups: z is R groups wide, a fetched row is one group's part

@@ -61,10 +61,11 @@ struct nrt_cache {
                                         // kernel responses of h^l), null otherwise
     int monet_J;                        // MoNet: kernels per layer = width of its payload and aggregate
     int n_rel;                          // RGCN: relations; MP[l] then holds n_rel message rows W_r h^l per vertex
-    // GCN, GIN: layer l applies its (first) weight matrix to the messages before the aggregation when that makes the
-    // aggregated rows narrower (d_l < d_{l-1}): sum_u c_uv (x_u W) = (sum_u c_uv x_u) W.  MP[l-1] = H^{l-1} W then plays
-    // the part of PinSAGE's message table, the cached aggregate S^l is d_l wide, and the update has no (GCN) or one
-    // product less (GIN).  Index: the destination layer l = 1..L.
+    // GCN, GIN, GraphSAGE, CommNet: layer l applies its (first / neighbour-side) weight matrix to the messages before the
+    // aggregation when that makes the aggregated rows narrower (d_l < d_{l-1}): sum_u c_uv (x_u W) = (sum_u c_uv x_u) W.
+    // MP[l-1] = H^{l-1} W then plays the part of PinSAGE's message table, the cached aggregate S^l is d_l wide, and the
+    // update has no product left (GCN), one less (GIN) or one of half the depth (GraphSAGE, CommNet: x_v W_1 + S_v).
+    // Index: the destination layer l = 1..L.
     bool tf[NRT_MAX_LAYERS + 1];
     int no_reorder;
     float* muT[NRT_MAX_LAYERS];         // MoNet: [d_l][J] transposed means / precisions of layer l+1
@@ -556,7 +557,8 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     if (d->kind == NRT_RGAT) c->heads = d->n_relations;          // one softmax group per relation
     c->no_reorder = d->aggregate_first ? 1 : 0;
     for (int l = 1; l <= c->L; ++l)
-        c->tf[l] = (d->kind == NRT_GCN || d->kind == NRT_GIN) && !d->agg_only && !d->aggregate_first && d->dims[l] < d->dims[l - 1];
+        c->tf[l] = (d->kind == NRT_GCN || d->kind == NRT_GIN || d->kind == NRT_SAGE_MEAN || d->kind == NRT_COMMNET) &&
+                   !d->agg_only && !d->aggregate_first && d->dims[l] < d->dims[l - 1];
     c->max_edges = max_edges;
     c->max_feats = max_feats;
     return NRT_OK;
@@ -627,6 +629,10 @@ static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_
             a.indeg = c->g->in.deg;
             a.indeg_old = c->indeg_old;
             a.dp_scale_gcn = 1;
+        }
+        if (concat_self(c->kind)) {        // W = [W_1; W_2]: the neighbour half, a column block of the transposed matrix
+            a.Wt = c->Wt[l][0] + c->dims[l];
+            a.ldw = 2 * c->dims[l];
         }
     }
     if (c->kind == NRT_RGCN) {             // h^l [W_0 | ... | W_{R-1}]: row v of the product is the R message rows of v
@@ -755,6 +761,23 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.K = c->dims[l];
         a.Wt = c->Wt[l - 1][1];
         a.bias = c->bias[l - 1][1];
+        a.act = last ? 0 : 1;
+        a.H = c->H[l];
+        a.DP = dp;
+        a.dp_skip_large = next_may_recompute;
+        a.n_vertices = g->n;
+        a.out_compact = last ? out_rows : nullptr;
+        a.out_cap = out_cap;
+        NRT_TRY(k_gemm(a, s));
+    } else if (c->tf[l] && concat_self(c->kind)) {  // act(x_v W_1 + S_v / count + b), S_v = cached sum of x_u W_2 (CommNet: no count)
+        a.a_mode = A_PLAIN_ADD;
+        a.P0 = c->H[l - 1];
+        a.K = c->dims[l - 1];
+        a.add = c->S[l];
+        a.add_indeg = c->kind == NRT_COMMNET ? nullptr : g->in.deg;
+        a.Wt = c->Wt[l - 1][0];
+        a.ldw = 2 * c->dims[l - 1];
+        a.bias = c->bias[l - 1][0];
         a.act = last ? 0 : 1;
         a.H = c->H[l];
         a.DP = dp;

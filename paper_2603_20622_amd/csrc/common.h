@@ -297,6 +297,7 @@ struct GemmArgs {
     const int32_t* add_indeg;       // rows of width N by vertex; a zero count adds nothing; null add_indeg: the rows themselves
     const int32_t* indeg;           // for A_SCALE_GCN / A_CONCAT_MEAN
     const float* Wt;                // transposed weights [N][K]
+    int ldw;                        // floats between consecutive rows of Wt (0: K); a column block of a wider matrix otherwise
     const float* bias;              // [N] or null
     int act;                        // 0 none, 1 relu, 2 elu
     // epilogue

@@ -74,6 +74,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WN, wn = wave % WN;
     const int col_base = blockIdx.y * BN;
+    const int ldw = g.ldw ? g.ldw : g.K;
     const int64_t M = g.M_dev ? (int64_t)*g.M_dev : g.M;      // rows known only on the device: stride over the tiles
     // the next layer recomputes its aggregates from h when these rows are a large part of the graph: no payload deltas then
     float* const DPout = (g.dp_skip_large && 4 * M > g.n_vertices) ? nullptr : g.DP;
@@ -115,7 +116,7 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
             const int n = col_base + lr + RPP * p;
             const int k = k0 + lk;
             const int nc = n < g.N ? n : g.N - 1, kc = k < g.K ? k : g.K - 4;
-            rb[p] = *reinterpret_cast<const float4*>(g.Wt + (int64_t)nc * g.K + kc);
+            rb[p] = *reinterpret_cast<const float4*>(g.Wt + (int64_t)nc * ldw + kc);
             bmul[p] = (n < g.N && k < g.K) ? 1.0f : 0.0f;
         }
     };
@@ -290,7 +291,7 @@ static void launch_gemm(const GemmArgs& g, hipStream_t s) {
 
 nrt_status k_gemm(const GemmArgs& g, hipStream_t s) {
     if (g.M <= 0) return NRT_OK;
-    if (g.K % 4 || g.ldp % 4) { nrt_set_error("gemm: widths must be multiples of 4"); return NRT_ERR_UNSUPPORTED; }
+    if (g.K % 4 || g.ldp % 4 || g.ldw % 4) { nrt_set_error("gemm: widths must be multiples of 4"); return NRT_ERR_UNSUPPORTED; }
     switch (g.a_mode) {
     case A_PLAIN: launch_gemm<A_PLAIN>(g, s); break;
     case A_SCALE_GCN: launch_gemm<A_SCALE_GCN>(g, s); break;

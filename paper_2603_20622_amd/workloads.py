@@ -38,7 +38,7 @@ class ModelSpec:
     monet_kernels: int = 0          # MoNet: Gaussian kernels per layer (the width of its aggregate)
     agg_only: bool = False          # GCN: keep only the aggregates of hidden layers (storage option of the cache)
     n_relations: int = 0            # RGCN, RGAT: number of edge types (relation ids are 0 .. n_relations-1)
-    aggregate_first: bool = False   # GCN, GIN: never apply a layer's weights before its aggregation (option of the cache)
+    aggregate_first: bool = False   # GCN, GIN, GraphSAGE, CommNet: never apply a layer's weights before its aggregation
 
     @property
     def n_layers(self) -> int:

@@ -297,6 +297,8 @@ def test_gin_cancellation_is_guarded(S, oracle):
     (wl.GGCN, [260, 36, 8], 1, 0),              # gate rows of two 16-byte pieces per lane
     (wl.GCN, [1024, 512, 260], 1, 0),           # weights applied before the aggregation at both layers; 512-wide message rows
     (wl.GIN, [36, 260, 8], 1, 0),               # wider, then narrower: aggregate x at layer 1, x W_a at layer 2
+    (wl.SAGE_MEAN, [1024, 132, 36], 1, 0),      # the neighbour half of a 2048-deep matrix applied before the aggregation
+    (wl.COMMNET, [260, 36, 8], 1, 0),
     (wl.RGCN, [20, 132, 8], 1, 0),              # message rows of 132 floats, 3 x 132 per source
     (wl.RGCN, [260, 12, 4], 1, 0),              # narrowest message rows
     (wl.RGAT, [24, 256, 256], 1, 256),          # 3 relations x 256: 768-wide projected rows
@@ -890,10 +892,10 @@ def test_batches_served_with_a_query_match_oracle(S, oracle, kind):
         assert_parity(kind, ses.layer(l).cpu().numpy(), ref[l - 1], (kind, "eager again", l))
 
 
-@pytest.mark.parametrize("kind", [wl.GCN, wl.GIN])
+@pytest.mark.parametrize("kind", [wl.GCN, wl.GIN, wl.SAGE_MEAN, wl.COMMNET])
 @pytest.mark.parametrize("L", [2, 3])
 def test_aggregate_first_option_matches_oracle(S, oracle, kind, L):
-    """GCN and GIN layers whose output is narrower than their input apply their weights to the messages before the
+    """GCN, GIN, GraphSAGE and CommNet layers whose output is narrower than their input apply their weights to the messages before the
     aggregation (the cached aggregate is then as wide as the layer's output); aggregate_first switches that off.  Both
     ways give the oracle's rows, the same affected lists, and differ from each other only by rounding."""
     n, src, dst, w, x, spec, params, stream = small_case(kind, seed=40 + L, L=L)
