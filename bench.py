@@ -137,7 +137,8 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
             # Cache, else one row per delta message; every affected aggregate row read and written (8*d)
             # GCN and GIN layers that narrow apply their (first) weight matrix to the messages before the aggregation:
             # the gathered rows and the cached aggregate are then as wide as the layer's output
-            weights_first = (cfg.spec.kind in (wl.GCN, wl.GIN, wl.SAGE_MEAN, wl.COMMNET) and dims[l + 1] < d_in
+            weights_first = (cfg.spec.kind in (wl.GCN, wl.GIN, wl.SAGE_MEAN, wl.COMMNET)
+                             and (dims[l + 1] < d_in or (dims[l + 1] == d_in and cfg.spec.kind != wl.GCN))
                              and not cfg.spec.agg_only and not cfg.spec.aggregate_first)
             d_agg = dims[l + 1] if cfg.spec.kind in (wl.GAT, wl.RGCN, wl.RGAT) or weights_first else \
                 (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)

@@ -122,8 +122,8 @@ typedef struct {
                                            NRT_MODE_RECOMPUTE, NRT_MODE_FULL and the on-demand mode, whose kernels
                                            read those rows.                                                        */
     int32_t n_relations;                /* RGCN, RGAT: number of edge types R                                       */
-    int32_t aggregate_first;            /* GCN, GIN, GraphSAGE, CommNet.  0 (default): a layer whose output is narrower
-                                           than its input (d_l < d_{l-1}) applies its weight matrix (GIN: the first one;
+    int32_t aggregate_first;            /* GCN, GIN, GraphSAGE, CommNet.  0 (default): a layer whose output is not wider
+                                           than its input (d_l <= d_{l-1}; GCN: d_l < d_{l-1}) applies its weight matrix (GIN: the first one;
                                            GraphSAGE, CommNet: the neighbour half W_2) to the messages before the
                                            aggregation, sum_u c_uv (x_u W) = (sum_u c_uv x_u) W: the rows that the
                                            gather moves and the cached aggregate (nrt_get_aggregate) are then d_l wide,

@@ -62,7 +62,10 @@ struct nrt_cache {
     int monet_J;                        // MoNet: kernels per layer = width of its payload and aggregate
     int n_rel;                          // RGCN: relations; MP[l] then holds n_rel message rows W_r h^l per vertex
     // GCN, GIN, GraphSAGE, CommNet: layer l applies its (first / neighbour-side) weight matrix to the messages before the
-    // aggregation when that makes the aggregated rows narrower (d_l < d_{l-1}): sum_u c_uv (x_u W) = (sum_u c_uv x_u) W.
+    // aggregation unless that would widen the aggregated rows (d_l <= d_{l-1}): sum_u c_uv (x_u W) = (sum_u c_uv x_u) W.
+    // With equal widths the gather moves the same bytes, but the product runs over the changed source rows, not over the
+    // (usually far more numerous) affected rows; GCN is left out of that case, because its update would turn from one
+    // fused product into a product plus a separate pass over the affected rows.
     // MP[l-1] = H^{l-1} W then plays the part of PinSAGE's message table, the cached aggregate S^l is d_l wide, and the
     // update has no product left (GCN), one less (GIN) or one of half the depth (GraphSAGE, CommNet: x_v W_1 + S_v).
     // Index: the destination layer l = 1..L.
@@ -558,7 +561,8 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     c->no_reorder = d->aggregate_first ? 1 : 0;
     for (int l = 1; l <= c->L; ++l)
         c->tf[l] = (d->kind == NRT_GCN || d->kind == NRT_GIN || d->kind == NRT_SAGE_MEAN || d->kind == NRT_COMMNET) &&
-                   !d->agg_only && !d->aggregate_first && d->dims[l] < d->dims[l - 1];
+                   !d->agg_only && !d->aggregate_first &&
+                   (d->dims[l] < d->dims[l - 1] || (d->dims[l] == d->dims[l - 1] && d->kind != NRT_GCN));
     c->max_edges = max_edges;
     c->max_feats = max_feats;
     return NRT_OK;
