@@ -278,6 +278,15 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
                 "frac_of_stream_read_ceiling": round(achieved / ceilings["read_GBps"], 4) if ceilings else None,
                 "avg_launch_ms": round(g_avg_ms, 4), "avg_launch_bytes": round(g_avg_bytes),
                 "launches_per_step": agg["gather_launches"] / K}
+    # the launch that takes the longest (one layer): achieved / frac above average over all gather launches of a step,
+    # which mixes the bandwidth-bound layers with the small, latency- or cache-bound ones
+    heavy = max(range(L), key=lambda l: per_layer[l]["gather_ms"])
+    if per_layer[heavy]["gather_ms"] > 0:
+        hv = per_layer[heavy]
+        hv_gbps = (hv["bytes"] / 1e9) / (hv["gather_ms"] / 1e3)
+        roofline["longest_launch"] = {"layer": heavy + 1, "avg_launch_ms": round(hv["gather_ms"] / K, 4),
+                                      "avg_launch_bytes": round(hv["bytes"] / K),
+                                      "achieved": round(hv_gbps, 1), "frac": round(hv_gbps / HBM_PEAK_GBS, 4)}
     upd_tflops = (agg["update_flop"] / 1e12) / (agg["update_ms"] / 1e3) if agg["update_ms"] > 0 else 0.0
 
     out = {
