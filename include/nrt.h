@@ -238,7 +238,10 @@ nrt_status nrt_apply_batch(nrt_cache*, const nrt_batch*, int32_t* affected_ids, 
 /* Borrowed device view of the cached layer output h^l (l = 0: current features), row-major, ld floats per row. */
 nrt_status nrt_get_layer(const nrt_cache*, int32_t layer, const float** rows, int64_t* n_rows, int64_t* ld);
 /* Borrowed device view of the cached aggregate of layer l = 1..L in context-free form (the sum before
- * msg_cbn is applied: Algorithm 1's a-hat), width floats per row. */
+ * msg_cbn is applied: Algorithm 1's a-hat), width floats per row.  What is summed depends on the model and the
+ * layer: h^{l-1} rows (width d_{l-1}), or the messages the layer aggregates when those are not h itself (PinSAGE,
+ * MoNet, RGCN, GAT, RGAT, and the layers of GCN, GIN, GraphSAGE and CommNet that apply their weights before the
+ * aggregation, see nrt_model_desc.aggregate_first): *width tells. */
 nrt_status nrt_get_aggregate(const nrt_cache*, int32_t layer, const float** rows, int64_t* n_rows, int64_t* width);
 /* Per-layer affected list A_l (l = 1..L) of the last batch: borrowed device int32 array, ascending. */
 nrt_status nrt_get_layer_affected(const nrt_cache*, int32_t layer, const int32_t** ids, int64_t* n);
