@@ -201,7 +201,7 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
     mode_ms = {}
     at = W + 2 * K
     for name, mode in (("incremental_every_layer", 0), ("recompute_affected", 1), ("full_graph", 2)):
-        if args.agg_only and mode != 0:                  # recomputation reads hidden rows, which this cache does not keep
+        if args.agg_only and mode != 0 and cfg.spec.kind == wl.GCN:   # recomputation reads hidden rows, which this cache does not keep
             mode_ms[name] = None
             continue
         ses.mode(mode)

@@ -117,10 +117,11 @@ typedef struct {
     const float* monet_prec[NRT_MAX_LAYERS]; /* device, MoNet only */
     int32_t agg_only;                   /* 1: keep only the aggregates of the hidden layers and recompute their rows when
                                            a batch needs them (Section IV, "Recomputation-based embedding storage
-                                           optimization").  GCN only.  Saves N * (d_1 + ... + d_{L-1}) floats of the
-                                           workspace; such a cache refuses nrt_get_layer for hidden layers,
-                                           NRT_MODE_RECOMPUTE, NRT_MODE_FULL and the on-demand mode, whose kernels
-                                           read those rows.                                                        */
+                                           optimization").  GCN, GAT and RGAT, whose update reads the aggregate
+                                           alone.  Saves N * (d_1 + ... + d_{L-1}) floats of the workspace; such a
+                                           cache refuses nrt_get_layer for hidden layers and the on-demand mode, a
+                                           GCN one also NRT_MODE_RECOMPUTE and NRT_MODE_FULL, whose kernels read
+                                           those rows (GAT and RGAT recompute from the cached projections).       */
     int32_t n_relations;                /* RGCN, RGAT: number of edge types R                                       */
     int32_t aggregate_first;            /* GCN, GIN, GraphSAGE, CommNet.  0 (default): a layer whose output is not wider
                                            than its input (d_l <= d_{l-1}; GCN: d_l < d_{l-1}) applies its weight matrix (GIN: the first one;
@@ -258,7 +259,8 @@ nrt_status nrt_get_layer_affected(const nrt_cache*, int32_t layer, const int32_t
  *                         of the vertices (nearly every in-edge of its affected vertices then carries a delta)
  *                         is served as in NRT_MODE_RECOMPUTE; decided per layer on the device.  GAT layers are
  *                         always incremental.
- * Errors: NRT_ERR_INVALID_ARG (null cache, unknown mode). */
+ * Errors: NRT_ERR_INVALID_ARG (null cache, unknown mode), NRT_ERR_UNSUPPORTED (NRT_MODE_RECOMPUTE or NRT_MODE_FULL on
+ * a GCN cache with aggregate-only storage). */
 typedef enum { NRT_MODE_INCREMENTAL = 0, NRT_MODE_RECOMPUTE = 1, NRT_MODE_FULL = 2, NRT_MODE_AUTO = 3 } nrt_mode;
 nrt_status nrt_set_mode(nrt_cache*, int32_t mode);
 /* On-demand embedding computation (Section IV-D): serve a small set of query vertices without keeping every

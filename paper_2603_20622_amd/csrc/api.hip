@@ -47,9 +47,9 @@ struct nrt_cache {
     int maxd;
     float* H[NRT_MAX_LAYERS + 1];
     float* S[NRT_MAX_LAYERS + 1];
-    int agg_only;                       // hidden-layer rows h^l are not kept, only the aggregates (GCN)
-    float* ES[NRT_MAX_LAYERS + 1];      // agg_only: h^l of the sources of the batch's updated edges, one row per update
-    int32_t* es_rows;                   // agg_only: those sources, inserts first
+    int agg_only;                       // hidden-layer rows h^l are not kept, only the aggregates (GCN, GAT, RGAT)
+    float* ES[NRT_MAX_LAYERS + 1];      // agg_only, GCN: h^l of the sources of the batch's updated edges, one row per update
+    int32_t* es_rows;                   // agg_only, GCN: those sources, inserts first
     float* R[NRT_MAX_LAYERS + 1];       // A-GNN: inverse norms of the rows of h^l (null otherwise)
     float* P1[NRT_MAX_LAYERS + 1];      // G-GCN: W_1 h^l and W_2 h^l by vertex (null otherwise)
     float* P2[NRT_MAX_LAYERS + 1];
@@ -379,8 +379,8 @@ static nrt_status check_desc(const nrt_model_desc* d) {
                 return NRT_ERR_UNSUPPORTED;
             }
     }
-    if (d->agg_only && d->kind != NRT_GCN) {
-        nrt_set_error("aggregate-only storage is available for GCN");
+    if (d->agg_only && d->kind != NRT_GCN && d->kind != NRT_GAT && d->kind != NRT_RGAT) {
+        nrt_set_error("aggregate-only storage is available for the models whose update reads only the aggregate: GCN, GAT, RGAT");
         return NRT_ERR_UNSUPPORTED;
     }
     if (d->kind == NRT_GAT) {
@@ -412,9 +412,9 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     for (int l = 0; l <= c->L; ++l) {
         const bool hidden = l >= 1 && l < c->L;
         c->H[l] = (c->agg_only && hidden) ? nullptr : b.take<float>(n * c->dims[l]);
-        c->ES[l] = (c->agg_only && hidden) ? b.take<float>((size_t)(c->max_edges + 1) * c->dims[l]) : nullptr;
+        c->ES[l] = (c->agg_only && hidden && c->kind == NRT_GCN) ? b.take<float>((size_t)(c->max_edges + 1) * c->dims[l]) : nullptr;
     }
-    c->es_rows = c->agg_only ? b.take<int32_t>(c->max_edges + 1) : nullptr;
+    c->es_rows = (c->agg_only && c->kind == NRT_GCN) ? b.take<int32_t>(c->max_edges + 1) : nullptr;
     for (int l = 0; l <= c->L; ++l) {
         c->MP[l] = nullptr;
         if (c->kind == NRT_PINSAGE && l < c->L) c->MP[l] = b.take<float>(n * c->dims[l]);
@@ -880,6 +880,13 @@ static nrt_status run_gat_project(nrt_cache* c, int l, const int32_t* src_rows, 
     z.a_mode = A_PLAIN;
     z.P0 = c->H[l - 1];
     z.ldp = c->dims[l - 1];
+    if (!c->H[l - 1]) {
+        // aggregate-only storage: the rows of h^{l-1} that changed were left, in list order, in DP[1] by the layer below
+        // (the rows of a layer's affected list are the next layer's changed sources)
+        if (!listed) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+        z.P0 = c->DP[1];
+        z.a_is_compact = 1;
+    }
     z.K = c->dims[l - 1];
     z.N = c->zdim;
     z.Wt = c->Wt[l - 1][0];
@@ -943,6 +950,11 @@ static nrt_status run_gat_layer(nrt_cache* c, int l, const int32_t* src_rows, co
     a.act = last ? 0 : 2;
     a.out_rows = last ? out_rows : nullptr;
     a.out_cap = out_cap;
+    if (!last && !c->H[l]) {                 // aggregate-only storage: this layer's rows go compact to the next layer's product
+        if (!listed) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+        a.out_rows = c->DP[1];               // (read by this layer's own product above, which has finished)
+        a.out_cap = g->n;
+    }
     if (c->profiling) a.pair_ctr = c->pair_ctr + (size_t)(l - 1) * 1024;
     NRT_TRY(k_gat_gather(a, s));
     NRT_TRY(prof_mark(c, TAG_GATHER, l, s));
@@ -1864,7 +1876,8 @@ extern "C" nrt_status nrt_set_mode(nrt_cache* c, int32_t mode) {
     REQUIRE(c, "null argument");
     REQUIRE(mode == NRT_MODE_INCREMENTAL || mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL || mode == NRT_MODE_AUTO,
             "unknown mode");
-    if (c->agg_only && (mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL)) {
+    // (GAT and RGAT recompute from the cached projections z, which are kept for every vertex)
+    if (c->agg_only && !c->is_gat && (mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL)) {
         nrt_set_error("with aggregate-only storage the hidden rows that recomputation reads are not kept");
         return NRT_ERR_UNSUPPORTED;
     }

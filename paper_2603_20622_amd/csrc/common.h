@@ -353,7 +353,8 @@ struct GatArgs {
     unsigned long long* pair_ctr;   // null or 1024 counters: z rows fetched by the gather (a statistic)
     float* M; float* DEN;           // [N][heads]
     float* S;                       // [N][D]
-    float* Hout;                    // [N][D] layer output ([N][head_dim] with rel)
+    float* Hout;                    // [N][D] layer output ([N][head_dim] with rel); null: the rows are not kept by vertex
+                                    // (aggregate-only storage), out_rows then carries them to the next layer
     const float* bias; int act;
     float* out_rows; int64_t out_cap;
 };

@@ -204,7 +204,7 @@ __device__ inline void gat_store(const GatArgs& a, int32_t v, int64_t s, const i
                 if (a.act == 2) yy[t] = yy[t] > 0.f ? yy[t] : expm1f(yy[t]);
             }
             const float4 yo = make_float4(yy[0], yy[1], yy[2], yy[3]);
-            *reinterpret_cast<float4*>(a.Hout + (int64_t)v * hd + c) = yo;
+            if (a.Hout) *reinterpret_cast<float4*>(a.Hout + (int64_t)v * hd + c) = yo;
             if (a.out_rows && s < a.out_cap) *reinterpret_cast<float4*>(a.out_rows + s * hd + c) = yo;
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -227,7 +227,7 @@ __device__ inline void gat_store(const GatArgs& a, int32_t v, int64_t s, const i
             if (a.act == 2) y[t] = y[t] > 0.f ? y[t] : expm1f(y[t]);
         }
         const float4 yo = make_float4(y[0], y[1], y[2], y[3]);
-        *reinterpret_cast<float4*>(a.Hout + (int64_t)v * D + col[q]) = yo;
+        if (a.Hout) *reinterpret_cast<float4*>(a.Hout + (int64_t)v * D + col[q]) = yo;
         if (a.out_rows && s < a.out_cap) *reinterpret_cast<float4*>(a.out_rows + s * D + col[q]) = yo;
     }
 }

@@ -611,10 +611,52 @@ def test_gcn_aggregate_only_storage(S, oracle):
             call()
         assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
     ses.mode(nb.NRT_MODE_INCREMENTAL)
-    # only GCN has the option
+    # the models whose update reads the layer's own input beside the aggregate do not have the option
     n2, s2, d2, w2, x2, spec2, params2, _ = small_case(wl.SAGE_MEAN, seed=9)
     with pytest.raises(nb.NrtError) as ei:
         S.Session(dataclasses.replace(spec2, agg_only=True), params2, n2, s2, d2, w2, x2)
+    assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
+
+
+@pytest.mark.parametrize("kind", [wl.GAT, wl.RGAT])
+def test_attention_models_aggregate_only_storage(S, oracle, kind):
+    """The same storage option for the attention models, whose update also reads only the cached aggregate (the
+    normalised sum): the hidden rows h^l are not kept by vertex; a batch hands the rows it recomputes at one layer to
+    the next layer's projection in affected-set order.  The projections z^l are cached for every vertex, so every
+    processing mode still works; what is refused is reading a hidden layer and the on-demand mode."""
+    import dataclasses
+    from paper_2603_20622_amd import binding as nb
+    n, src, dst, w, x, spec, params, stream = small_case(kind, seed=13, bias=True, L=3)
+    assert np.bincount(dst, minlength=n).max() > 600          # a destination cut into several items
+    lean_spec = dataclasses.replace(spec, agg_only=True)
+    ses = S.Session(lean_spec, params, n, src, dst, w, x)
+    kept = nb.nrt_cache_workspace_bytes(ses.graph, nb.make_desc(spec, ses.dev_params), 1 << 16, 1 << 12)
+    lean = nb.nrt_cache_workspace_bytes(ses.graph, ses.desc, 1 << 16, 1 << 12)
+    assert lean <= kept - 4 * n * (spec.dims[1] + spec.dims[2]) + 4096
+    cur = (src, dst, w, x)
+    ref = oracle.forward(spec, params, n, *cur)
+    assert rel_err(ses.layer(3).cpu().numpy(), ref[-1]) <= TOL
+    modes = [nb.NRT_MODE_INCREMENTAL] * 4 + [nb.NRT_MODE_RECOMPUTE, nb.NRT_MODE_AUTO, nb.NRT_MODE_FULL, nb.NRT_MODE_INCREMENTAL]
+    for k, mode in enumerate(modes):
+        ses.mode(mode)
+        # edge-only, feature-only, mixed and large batches (the large one makes most vertices affected)
+        n_ins, n_del, n_feat = [(40, 40, 12), (30, 30, 0), (0, 0, 25), (900, 700, 60)][k % 4]
+        batch = stream.next_batch(n_ins, n_del, n_feat)
+        na = ses.apply(batch)
+        cur = oracle.apply_batch(n, *cur, batch)
+        ref = oracle.forward(spec, params, n, *cur)
+        sets = oracle.affected_sets(spec, n, cur[0], cur[1], batch)
+        ids = ses.ids[:na].cpu().numpy()
+        assert np.array_equal(ids, sets[-1]), k
+        got = ses.layer(3).cpu().numpy()
+        assert rel_err(got, ref[-1]) <= TOL, (k, mode)
+        assert np.array_equal(ses.rows[:na].cpu().numpy(), got[ids]), k
+    for l in (1, 2):
+        with pytest.raises(nb.NrtError) as ei:
+            ses.layer(l)
+        assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
+    with pytest.raises(nb.NrtError) as ei:
+        ses.lazy(True)
     assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
 
 
