@@ -81,7 +81,11 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
         cfg.n_del = args.batch_edges - cfg.n_ins
     t0 = time.time()
     src, dst, w, x, params, stream = wl.build(cfg, args.seed)
-    n_total = 2 * K + W + 3 * k_modes + (k_modes if with_on_demand else 0)
+    # legs a cache with aggregate-only storage refuses are left out, and so are their batches: the final snapshot that
+    # the parity check recomputes is the one after exactly the batches applied
+    with_on_demand = with_on_demand and not args.agg_only
+    n_mode_legs = 1 if (args.agg_only and cfg.spec.kind == wl.GCN) else 3
+    n_total = 2 * K + W + n_mode_legs * k_modes + (k_modes if with_on_demand else 0)
     batches = [stream.next_batch(cfg.n_ins, cfg.n_del, cfg.n_feat) for _ in range(n_total)]
     final_edges = stream.edges()
     del stream
@@ -139,7 +143,7 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
             # the gathered rows and the cached aggregate are then as wide as the layer's output
             weights_first = (cfg.spec.kind in (wl.GCN, wl.GIN, wl.SAGE_MEAN, wl.COMMNET)
                              and (dims[l + 1] < d_in or (dims[l + 1] == d_in and cfg.spec.kind != wl.GCN))
-                             and not cfg.spec.agg_only and not cfg.spec.aggregate_first)
+                             and (not cfg.spec.agg_only or cfg.spec.kind == wl.GIN) and not cfg.spec.aggregate_first)
             d_agg = dims[l + 1] if cfg.spec.kind in (wl.GAT, wl.RGCN, wl.RGAT) or weights_first else \
                 (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)
             row_fetches = ls.n_src if ls.n_src * 4.0 * d_agg <= INFINITY_CACHE_BYTES else ls.n_pairs
@@ -218,7 +222,7 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
     # ---- on-demand leg (Section IV-D): batches only mark vertices stale, each is followed by a query for the
     # final-layer rows of 1000 random vertices, which brings the stale part of their L-hop in-neighbourhood up to date
     on_demand = None
-    if with_on_demand and not args.agg_only:
+    if with_on_demand:
         rng = np.random.default_rng(args.seed + 77)
         ses.lazy(True)
         t_apply = t_query = t_both = 0.0

@@ -118,10 +118,13 @@ typedef struct {
     int32_t agg_only;                   /* 1: keep only the aggregates of the hidden layers and recompute their rows when
                                            a batch needs them (Section IV, "Recomputation-based embedding storage
                                            optimization").  GCN, GAT and RGAT, whose update reads the aggregate
-                                           alone.  Saves N * (d_1 + ... + d_{L-1}) floats of the workspace; such a
-                                           cache refuses nrt_get_layer for hidden layers and the on-demand mode, a
-                                           GCN one also NRT_MODE_RECOMPUTE and NRT_MODE_FULL, whose kernels read
-                                           those rows (GAT and RGAT recompute from the cached projections).       */
+                                           alone, and GIN when aggregate_first is 0 and d_l <= d_{l-1} for every
+                                           layer above the first (the row is then read only through the message
+                                           table h W_a); NRT_ERR_UNSUPPORTED otherwise.  Saves
+                                           N * (d_1 + ... + d_{L-1}) floats of the workspace; such a cache refuses
+                                           nrt_get_layer for hidden layers and the on-demand mode, a GCN one also
+                                           NRT_MODE_RECOMPUTE and NRT_MODE_FULL, whose kernels read those rows (the
+                                           others recompute from the cached projections / message tables).       */
     int32_t n_relations;                /* RGCN, RGAT: number of edge types R                                       */
     int32_t aggregate_first;            /* GCN, GIN, GraphSAGE, CommNet.  0 (default): a layer whose output is not wider
                                            than its input (d_l <= d_{l-1}; GCN: d_l < d_{l-1}) applies its weight matrix (GIN: the first one;

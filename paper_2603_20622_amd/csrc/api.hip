@@ -379,9 +379,19 @@ static nrt_status check_desc(const nrt_model_desc* d) {
                 return NRT_ERR_UNSUPPORTED;
             }
     }
-    if (d->agg_only && d->kind != NRT_GCN && d->kind != NRT_GAT && d->kind != NRT_RGAT) {
-        nrt_set_error("aggregate-only storage is available for the models whose update reads only the aggregate: GCN, GAT, RGAT");
+    if (d->agg_only && d->kind != NRT_GCN && d->kind != NRT_GAT && d->kind != NRT_RGAT && d->kind != NRT_GIN) {
+        nrt_set_error("aggregate-only storage is available for GCN, GAT, RGAT, and for GIN with weights-first layers");
         return NRT_ERR_UNSUPPORTED;
+    }
+    if (d->agg_only && d->kind == NRT_GIN) {
+        // a layer that applies W_a before the aggregation reads h^{l-1} only through the message table h^{l-1} W_a;
+        // one that does not reads the row itself in its update
+        bool ok = !d->aggregate_first;
+        for (int l = 2; l <= d->n_layers; ++l) ok = ok && d->dims[l] <= d->dims[l - 1];
+        if (!ok) {
+            nrt_set_error("GIN: aggregate-only storage needs aggregate_first = 0 and d_l <= d_{l-1} for every layer above the first");
+            return NRT_ERR_UNSUPPORTED;
+        }
     }
     if (d->kind == NRT_GAT) {
         if (d->heads < 1 || d->head_dim < 4 || d->head_dim % 4) {
@@ -561,7 +571,7 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     c->no_reorder = d->aggregate_first ? 1 : 0;
     for (int l = 1; l <= c->L; ++l)
         c->tf[l] = (d->kind == NRT_GCN || d->kind == NRT_GIN || d->kind == NRT_SAGE_MEAN || d->kind == NRT_COMMNET) &&
-                   !d->agg_only && !d->aggregate_first &&
+                   (!d->agg_only || d->kind == NRT_GIN) && !d->aggregate_first &&
                    (d->dims[l] < d->dims[l - 1] || (d->dims[l] == d->dims[l - 1] && d->kind != NRT_GCN));
     c->max_edges = max_edges;
     c->max_feats = max_feats;
@@ -619,6 +629,13 @@ static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_
     a.a_mode = A_PLAIN;
     a.P0 = c->H[l];
     a.ldp = c->dims[l];
+    if (!c->H[l]) {
+        // aggregate-only storage (GIN): the update of layer l left the rows of its affected list, which are these rows,
+        // compact and in list order in `mid`
+        if (!rows) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+        a.P0 = c->mid;
+        a.a_is_compact = 1;
+    }
     a.K = c->dims[l];
     a.N = c->dims[l];
     a.Wt = c->Wt[l][1];
@@ -772,6 +789,11 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.n_vertices = g->n;
         a.out_compact = last ? out_rows : nullptr;
         a.out_cap = out_cap;
+        if (!last && !c->H[l]) {           // aggregate-only storage: the rows go compact to the next layer's message product
+            if (!rows) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+            a.out_compact = c->mid;
+            a.out_cap = g->n;
+        }
         NRT_TRY(k_gemm(a, s));
     } else if (c->tf[l] && concat_self(c->kind)) {  // act(x_v W_1 + S_v / count + b), S_v = cached sum of x_u W_2 (CommNet: no count)
         a.a_mode = A_PLAIN_ADD;
@@ -836,7 +858,12 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.Wt = c->Wt[l - 1][0];
         a.bias = c->bias[l - 1][0];
         a.act = 1;
-        a.out_compact = c->mid;
+        // aggregate-only storage keeps `mid` for this layer's output rows; the intermediate then goes through the delta
+        // buffer this layer would fill, which is free because the next layer's deltas come from its message product
+        const bool unkept = !last && !c->H[l];
+        if (unkept && (!rows || dp)) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+        float* mid = unkept ? c->DP[cur] : c->mid;
+        a.out_compact = mid;
         a.out_cap = g->n;
         NRT_TRY(k_gemm(a, s));
         GemmArgs b2;
@@ -846,7 +873,7 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         b2.rows = rows;
         b2.a_is_compact = 1;
         b2.a_mode = A_PLAIN;
-        b2.P0 = c->mid;
+        b2.P0 = mid;
         b2.ldp = c->dims[l];
         b2.K = c->dims[l];
         b2.N = c->dims[l];
@@ -857,8 +884,8 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         b2.DP = dp;
         b2.dp_skip_large = next_may_recompute;
         b2.n_vertices = g->n;
-        b2.out_compact = last ? out_rows : nullptr;
-        b2.out_cap = out_cap;
+        b2.out_compact = last ? out_rows : (unkept ? c->mid : nullptr);
+        b2.out_cap = last ? out_cap : g->n;
         NRT_TRY(k_gemm(b2, s));
     }
     return NRT_OK;
@@ -1311,7 +1338,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
     // (no extra launches for small frontiers); the device counters of this batch take the decision
     bool may_rec[NRT_MAX_LAYERS + 2];
     for (int l = 0; l <= c->L + 1; ++l)
-        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && !c->is_gat && !agnn_family(c->kind) && !c->agg_only && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
+        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && !c->is_gat && !agnn_family(c->kind) && (!c->agg_only || c->kind == NRT_GIN) && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     uint64_t* n_slots_dev = (uint64_t*)(g->dev_ctrs + CTR_COUNT);
     if (b->n_ins + b->n_del > 0) {
@@ -1373,7 +1400,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
         f.ins_src = b->ins_src; f.ins_dst = b->ins_dst; f.del_src = b->del_src; f.del_dst = b->del_dst;
         if (weighted_messages(c->kind) && g->weighted) { f.ins_w = b->ins_w; f.del_w = c->sc.del_w; }
         f.rel_R = c->n_rel;
-        if (c->agg_only && c->L > 1 && b->n_ins + b->n_del > 0) {
+        if (c->agg_only && gcn && c->L > 1 && b->n_ins + b->n_del > 0) {
             // the hidden rows of the updated edges' sources are not kept: recompute them from the (old) aggregates
             const int64_t nops = b->n_ins + b->n_del;
             NRT_TRY(k_concat_ids(c->es_rows, b->ins_src, b->n_ins, b->del_src, b->n_del, n, s));
@@ -1386,7 +1413,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
         f.n_slots = n_slots_dev; f.off = c->plan_off; f.ord = c->plan_ord;
         for (int l = 1; l <= c->L; ++l) {
             f.Hprev[l - 1] = payload_rows(c, l - 1);
-            if (c->agg_only && l - 1 >= 1) { f.Hprev[l - 1] = c->ES[l - 1]; f.compact_src[l - 1] = 1; }
+            if (c->agg_only && gcn && l - 1 >= 1) { f.Hprev[l - 1] = c->ES[l - 1]; f.compact_src[l - 1] = 1; }
             f.SD[l - 1] = c->SD[l];
             f.D[l - 1] = c->dagg[l];
         }
@@ -1521,7 +1548,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
             if (c->MP[l - 1])
                 NRT_TRY(run_transform(c, l - 1, c->list[l - 1], src_bound, &c->lc[l - 1].count, inc ? c->DP[prev] : nullptr,
                                       may_rec[l], s));
-            if (c->agg_only && l < c->L) {
+            if (c->agg_only && gcn && l < c->L) {
                 // the layer's rows are not kept: the payload deltas of its affected rows are minus the old payload,
                 // computed from the aggregate before the fold, plus the new one, computed after it
                 NRT_TRY(run_update_unkept(c, l, c->list[l], n, &c->lc[l].count, c->indeg_old, nullptr, 0, c->DP[cur], 1, s));
@@ -1876,8 +1903,8 @@ extern "C" nrt_status nrt_set_mode(nrt_cache* c, int32_t mode) {
     REQUIRE(c, "null argument");
     REQUIRE(mode == NRT_MODE_INCREMENTAL || mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL || mode == NRT_MODE_AUTO,
             "unknown mode");
-    // (GAT and RGAT recompute from the cached projections z, which are kept for every vertex)
-    if (c->agg_only && !c->is_gat && (mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL)) {
+    // (GAT and RGAT recompute from the cached projections z, GIN from the message tables, which are kept for every vertex)
+    if (c->agg_only && c->kind == NRT_GCN && (mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL)) {
         nrt_set_error("with aggregate-only storage the hidden rows that recomputation reads are not kept");
         return NRT_ERR_UNSUPPORTED;
     }
