@@ -143,7 +143,7 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
             # the gathered rows and the cached aggregate are then as wide as the layer's output
             weights_first = (cfg.spec.kind in (wl.GCN, wl.GIN, wl.SAGE_MEAN, wl.COMMNET)
                              and (dims[l + 1] < d_in or (dims[l + 1] == d_in and cfg.spec.kind != wl.GCN))
-                             and (not cfg.spec.agg_only or cfg.spec.kind == wl.GIN) and not cfg.spec.aggregate_first)
+                             and (not cfg.spec.agg_only or cfg.spec.kind != wl.GCN) and not cfg.spec.aggregate_first)
             d_agg = dims[l + 1] if cfg.spec.kind in (wl.GAT, wl.RGCN, wl.RGAT) or weights_first else \
                 (cfg.spec.monet_kernels if cfg.spec.kind == wl.MONET else d_in)
             row_fetches = ls.n_src if ls.n_src * 4.0 * d_agg <= INFINITY_CACHE_BYTES else ls.n_pairs
@@ -165,8 +165,8 @@ def run_config(args, index, K, W, k_modes, ceilings, with_cpu, with_on_demand):
                 flop = 2.0 * ls.n_src * d_in * dims[l + 1]
                 if cfg.spec.kind == wl.GIN:
                     flop += 2.0 * ls.n_affected * dims[l + 1] * dims[l + 1]
-                if cfg.spec.kind in (wl.SAGE_MEAN, wl.COMMNET):      # the self half of the update stays a product
-                    flop += 2.0 * ls.n_affected * d_in * dims[l + 1]
+                if cfg.spec.kind in (wl.SAGE_MEAN, wl.COMMNET):      # both halves [W_1 | W_2] on the changed rows; no product
+                    flop *= 2.0                                      # is left in the update
                 upd_ms = ls.ms_update + ls.ms_items
             if cfg.spec.kind == wl.RGAT:
                 # the GAT path with the relations as groups: z is R groups wide, a fetched row is one group's part

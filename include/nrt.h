@@ -118,9 +118,9 @@ typedef struct {
     int32_t agg_only;                   /* 1: keep only the aggregates of the hidden layers and recompute their rows when
                                            a batch needs them (Section IV, "Recomputation-based embedding storage
                                            optimization").  GCN, GAT and RGAT, whose update reads the aggregate
-                                           alone, and GIN when aggregate_first is 0 and d_l <= d_{l-1} for every
-                                           layer above the first (the row is then read only through the message
-                                           table h W_a); NRT_ERR_UNSUPPORTED otherwise.  Saves
+                                           alone, and GIN, GraphSAGE, CommNet when aggregate_first is 0 and
+                                           d_l <= d_{l-1} for every layer above the first (the row is then read only
+                                           through the cached products h W); NRT_ERR_UNSUPPORTED otherwise.  Saves
                                            N * (d_1 + ... + d_{L-1}) floats of the workspace; such a cache refuses
                                            nrt_get_layer for hidden layers and the on-demand mode, a GCN one also
                                            NRT_MODE_RECOMPUTE and NRT_MODE_FULL, whose kernels read those rows (the
@@ -131,7 +131,8 @@ typedef struct {
                                            GraphSAGE, CommNet: the neighbour half W_2) to the messages before the
                                            aggregation, sum_u c_uv (x_u W) = (sum_u c_uv x_u) W: the rows that the
                                            gather moves and the cached aggregate (nrt_get_aggregate) are then d_l wide,
-                                           at the price of one more N x d_l table per such layer.  1: always aggregate
+                                           at the price of one more N x d_l table per such layer (GraphSAGE, CommNet:
+                                           two, the self half x W_1 is cached as well).  1: always aggregate
                                            x itself, as Eq. 1-2 and Fig. 4 are written.  The results agree up to
                                            rounding.                                                               */
 } nrt_model_desc;

@@ -59,6 +59,8 @@ struct nrt_cache {
     float agnn_beta[NRT_MAX_LAYERS];
     float* MP[NRT_MAX_LAYERS + 1];      // PinSAGE, MoNet: message payload of layer l's rows (ReLU(h^l Q + q); the Gaussian
                                         // kernel responses of h^l), null otherwise
+    float* MS[NRT_MAX_LAYERS + 1];      // GraphSAGE, CommNet on a weights-first layer l+1: h^l W_1 by vertex, the self half of
+                                        // that layer's update (the neighbour half h^l W_2 is MP[l]); null otherwise
     int monet_J;                        // MoNet: kernels per layer = width of its payload and aggregate
     int n_rel;                          // RGCN: relations; MP[l] then holds n_rel message rows W_r h^l per vertex
     // GCN, GIN, GraphSAGE, CommNet: layer l applies its (first / neighbour-side) weight matrix to the messages before the
@@ -379,17 +381,18 @@ static nrt_status check_desc(const nrt_model_desc* d) {
                 return NRT_ERR_UNSUPPORTED;
             }
     }
-    if (d->agg_only && d->kind != NRT_GCN && d->kind != NRT_GAT && d->kind != NRT_RGAT && d->kind != NRT_GIN) {
-        nrt_set_error("aggregate-only storage is available for GCN, GAT, RGAT, and for GIN with weights-first layers");
+    const bool by_tables = d->kind == NRT_GIN || d->kind == NRT_SAGE_MEAN || d->kind == NRT_COMMNET;
+    if (d->agg_only && d->kind != NRT_GCN && d->kind != NRT_GAT && d->kind != NRT_RGAT && !by_tables) {
+        nrt_set_error("aggregate-only storage is available for GCN, GAT, RGAT, and for GIN, GraphSAGE and CommNet with weights-first layers");
         return NRT_ERR_UNSUPPORTED;
     }
-    if (d->agg_only && d->kind == NRT_GIN) {
-        // a layer that applies W_a before the aggregation reads h^{l-1} only through the message table h^{l-1} W_a;
-        // one that does not reads the row itself in its update
+    if (d->agg_only && by_tables) {
+        // a layer that applies its weights before the aggregation reads h^{l-1} only through the cached products
+        // (h^{l-1} W_a; h^{l-1} W_1 and h^{l-1} W_2); one that does not reads the row itself in its update
         bool ok = !d->aggregate_first;
         for (int l = 2; l <= d->n_layers; ++l) ok = ok && d->dims[l] <= d->dims[l - 1];
         if (!ok) {
-            nrt_set_error("GIN: aggregate-only storage needs aggregate_first = 0 and d_l <= d_{l-1} for every layer above the first");
+            nrt_set_error("GIN, GraphSAGE, CommNet: aggregate-only storage needs aggregate_first = 0 and d_l <= d_{l-1} for every layer above the first");
             return NRT_ERR_UNSUPPORTED;
         }
     }
@@ -430,6 +433,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         if (c->kind == NRT_PINSAGE && l < c->L) c->MP[l] = b.take<float>(n * c->dims[l]);
         if (c->kind == NRT_RGCN && l < c->L) c->MP[l] = b.take<float>(n * c->n_rel * c->dims[l + 1]);
         if (l < c->L && c->tf[l + 1]) c->MP[l] = b.take<float>(n * c->dims[l + 1]);
+        c->MS[l] = (l < c->L && c->tf[l + 1] && concat_self(c->kind)) ? b.take<float>(n * c->dims[l + 1]) : nullptr;
         if (c->kind == NRT_MONET && l < c->L) {
             c->MP[l] = b.take<float>(n * c->monet_J);
             c->muT[l] = b.take<float>((size_t)c->dims[l] * c->monet_J);
@@ -506,7 +510,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
     c->slot[1] = b.take<int32_t>(n);
     c->DP[0] = b.take<float>(n * maxd);
     c->DP[1] = b.take<float>(n * maxd);
-    c->mid = c->kind == NRT_GIN ? b.take<float>(n * maxd) : nullptr;
+    c->mid = c->kind == NRT_GIN ? b.take<float>(n * maxd) : nullptr;      // the rows between its two products
     c->recs = b.take<DstRec>(n);
     c->hubs.hub_cap = g->e_capacity / NRT_CHUNK + 64;          // a hub has more than NRT_CHUNK live in-edges
     c->hubs.item_cap = 2 * (g->e_capacity / NRT_CHUNK) + 64;   // sum of ceil(deg/NRT_CHUNK) over hubs
@@ -571,7 +575,7 @@ static nrt_status cache_fill(nrt_cache* c, const nrt_graph* g, const nrt_model_d
     c->no_reorder = d->aggregate_first ? 1 : 0;
     for (int l = 1; l <= c->L; ++l)
         c->tf[l] = (d->kind == NRT_GCN || d->kind == NRT_GIN || d->kind == NRT_SAGE_MEAN || d->kind == NRT_COMMNET) &&
-                   (!d->agg_only || d->kind == NRT_GIN) && !d->aggregate_first &&
+                   (!d->agg_only || d->kind != NRT_GCN) && !d->aggregate_first &&
                    (d->dims[l] < d->dims[l - 1] || (d->dims[l] == d->dims[l - 1] && d->kind != NRT_GCN));
     c->max_edges = max_edges;
     c->max_feats = max_feats;
@@ -597,6 +601,14 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
     HIP_TRY(hipStreamSynchronize(s));
     return NRT_OK;
 }
+
+// Aggregate-only storage of GIN, GraphSAGE, CommNet: the two delta buffers have fixed roles instead of alternating with
+// the layers.  DP[0] holds the compact payload deltas a layer's gather folds; DP[1] the compact rows h^l that the update
+// of layer l hands to the message products of layer l+1 (written after those products of layer l have read it).
+static inline bool rows_by_tables(const nrt_cache* c) {
+    return c->agg_only && (c->kind == NRT_GIN || c->kind == NRT_SAGE_MEAN || c->kind == NRT_COMMNET);
+}
+static inline float* delta_buf(nrt_cache* c, int prev) { return rows_by_tables(c) ? c->DP[0] : c->DP[prev]; }
 
 // what the in-neighbours of layer l+1 aggregate: h^l itself, or its transform for PinSAGE
 static inline const float* payload_rows(const nrt_cache* c, int l) { return c->MP[l] ? c->MP[l] : c->H[l]; }
@@ -630,10 +642,10 @@ static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_
     a.P0 = c->H[l];
     a.ldp = c->dims[l];
     if (!c->H[l]) {
-        // aggregate-only storage (GIN): the update of layer l left the rows of its affected list, which are these rows,
-        // compact and in list order in `mid`
+        // aggregate-only storage (GIN, GraphSAGE, CommNet): the update of layer l left the rows of its affected list, which are these rows,
+        // compact and in list order in DP[1]
         if (!rows) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
-        a.P0 = c->mid;
+        a.P0 = c->DP[1];
         a.a_is_compact = 1;
     }
     a.K = c->dims[l];
@@ -664,7 +676,15 @@ static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_
     a.DP = dp;
     a.dp_skip_large = skip_dp_when_large;
     a.n_vertices = c->g->n;
-    return k_gemm(a, s);
+    NRT_TRY(k_gemm(a, s));
+    if (c->MS[l]) {                        // the self half h^l W_1 of the same rows; nobody folds its deltas
+        a.Wt = c->Wt[l][0];
+        a.H = c->MS[l];
+        a.DP = nullptr;
+        a.dp_skip_large = 0;
+        NRT_TRY(k_gemm(a, s));
+    }
+    return NRT_OK;
 }
 
 // gather + fold of layer l over the destinations described by c->recs and the hub items built from them;
@@ -694,7 +714,7 @@ static nrt_status run_gather(nrt_cache* c, int l, bool incremental, int prev, bo
     full.src_scale_gcn = c->kind == NRT_GCN;
     full.accumulate = 0;
     if (incremental) {
-        a.P = c->ov_bm ? c->ov_dp : c->DP[prev];
+        a.P = c->ov_bm ? c->ov_dp : delta_buf(c, prev);
         a.src_bitmap = c->ov_bm ? c->ov_bm : c->bm[prev];
         a.src_slot = c->ov_bm ? c->ov_slot : c->slot[prev];
         a.n_src_dev = c->ov_bm ? c->ov_count : &c->lc[l - 1].count;
@@ -791,18 +811,15 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.out_cap = out_cap;
         if (!last && !c->H[l]) {           // aggregate-only storage: the rows go compact to the next layer's message product
             if (!rows) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
-            a.out_compact = c->mid;
+            a.out_compact = c->DP[1];
             a.out_cap = g->n;
         }
         NRT_TRY(k_gemm(a, s));
-    } else if (c->tf[l] && concat_self(c->kind)) {  // act(x_v W_1 + S_v / count + b), S_v = cached sum of x_u W_2 (CommNet: no count)
-        a.a_mode = A_PLAIN_ADD;
-        a.P0 = c->H[l - 1];
-        a.K = c->dims[l - 1];
+    } else if (c->tf[l] && concat_self(c->kind)) {  // act(x_v W_1 + S_v / count + b) from the two cached products: S_v is the
+        a.P0 = c->MS[l - 1];                        // sum of x_u W_2 (CommNet: no count), x_v W_1 a cached row; no product left
+        a.indeg = nullptr;
         a.add = c->S[l];
         a.add_indeg = c->kind == NRT_COMMNET ? nullptr : g->in.deg;
-        a.Wt = c->Wt[l - 1][0];
-        a.ldw = 2 * c->dims[l - 1];
         a.bias = c->bias[l - 1][0];
         a.act = last ? 0 : 1;
         a.H = c->H[l];
@@ -811,7 +828,12 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.n_vertices = g->n;
         a.out_compact = last ? out_rows : nullptr;
         a.out_cap = out_cap;
-        NRT_TRY(k_gemm(a, s));
+        if (!last && !c->H[l]) {           // aggregate-only storage: the rows go compact to the next layer's products
+            if (!rows) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+            a.out_compact = c->DP[1];
+            a.out_cap = g->n;
+        }
+        NRT_TRY(k_rowwise_update(a, s));
     } else if (c->kind == NRT_RGCN) {       // sigma(W_o h_v + a_v), a_v = cached sum of relation messages / neighbour count
         a.a_mode = A_PLAIN_ADD;
         a.P0 = c->H[l - 1];
@@ -848,6 +870,11 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.dp_scale_gcn = c->kind == NRT_GCN;
         a.out_compact = last ? out_rows : nullptr;
         a.out_cap = out_cap;
+        if (!last && !c->H[l] && c->kind != NRT_GCN) {   // aggregate-only storage of GraphSAGE, CommNet (a first layer that widens)
+            if (!rows || dp) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+            a.out_compact = c->DP[1];
+            a.out_cap = g->n;
+        }
         NRT_TRY(k_gemm(a, s));
     } else {   // GIN: two chained products
         a.a_mode = A_AXPY;
@@ -858,11 +885,9 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.Wt = c->Wt[l - 1][0];
         a.bias = c->bias[l - 1][0];
         a.act = 1;
-        // aggregate-only storage keeps `mid` for this layer's output rows; the intermediate then goes through the delta
-        // buffer this layer would fill, which is free because the next layer's deltas come from its message product
-        const bool unkept = !last && !c->H[l];
+        const bool unkept = !last && !c->H[l];   // aggregate-only storage: the rows go compact to the next layer's message product
         if (unkept && (!rows || dp)) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
-        float* mid = unkept ? c->DP[cur] : c->mid;
+        float* mid = c->mid;
         a.out_compact = mid;
         a.out_cap = g->n;
         NRT_TRY(k_gemm(a, s));
@@ -884,7 +909,7 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         b2.DP = dp;
         b2.dp_skip_large = next_may_recompute;
         b2.n_vertices = g->n;
-        b2.out_compact = last ? out_rows : (unkept ? c->mid : nullptr);
+        b2.out_compact = last ? out_rows : (unkept ? c->DP[1] : nullptr);
         b2.out_cap = last ? out_cap : g->n;
         NRT_TRY(k_gemm(b2, s));
     }
@@ -1338,7 +1363,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
     // (no extra launches for small frontiers); the device counters of this batch take the decision
     bool may_rec[NRT_MAX_LAYERS + 2];
     for (int l = 0; l <= c->L + 1; ++l)
-        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && !c->is_gat && !agnn_family(c->kind) && (!c->agg_only || c->kind == NRT_GIN) && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
+        may_rec[l] = !c->lazy && c->mode == NRT_MODE_AUTO && !c->is_gat && !agnn_family(c->kind) && (!c->agg_only || c->kind != NRT_GCN) && l >= 1 && l <= c->L && prev_n_list[l - 1] * 8 > n;
     if (gcn && inc && !empty_batch) NRT_TRY(k_copy_i32(c->indeg_old, g->in.deg, n, s));
     uint64_t* n_slots_dev = (uint64_t*)(g->dev_ctrs + CTR_COUNT);
     if (b->n_ins + b->n_del > 0) {
@@ -1546,7 +1571,7 @@ static nrt_status apply_batch_impl(nrt_cache* c, const nrt_batch* b, int32_t* af
             const int64_t pn = prev_n_list[l - 1];
             const int sparse_hint = !had_history ? 1 : (pn * 64 <= n ? 2 : (pn * 4 > n ? 0 : 1));
             if (c->MP[l - 1])
-                NRT_TRY(run_transform(c, l - 1, c->list[l - 1], src_bound, &c->lc[l - 1].count, inc ? c->DP[prev] : nullptr,
+                NRT_TRY(run_transform(c, l - 1, c->list[l - 1], src_bound, &c->lc[l - 1].count, inc ? delta_buf(c, prev) : nullptr,
                                       may_rec[l], s));
             if (c->agg_only && gcn && l < c->L) {
                 // the layer's rows are not kept: the payload deltas of its affected rows are minus the old payload,
@@ -1903,7 +1928,7 @@ extern "C" nrt_status nrt_set_mode(nrt_cache* c, int32_t mode) {
     REQUIRE(c, "null argument");
     REQUIRE(mode == NRT_MODE_INCREMENTAL || mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL || mode == NRT_MODE_AUTO,
             "unknown mode");
-    // (GAT and RGAT recompute from the cached projections z, GIN from the message tables, which are kept for every vertex)
+    // (GAT and RGAT recompute from the cached projections z, GIN, GraphSAGE and CommNet from the message tables, which are kept for every vertex)
     if (c->agg_only && c->kind == NRT_GCN && (mode == NRT_MODE_RECOMPUTE || mode == NRT_MODE_FULL)) {
         nrt_set_error("with aggregate-only storage the hidden rows that recomputation reads are not kept");
         return NRT_ERR_UNSUPPORTED;

@@ -313,8 +313,10 @@ struct GemmArgs {
     int64_t n_vertices;
 };
 nrt_status k_gemm(const GemmArgs& a, hipStream_t s);
-// The write-back of k_gemm without a product: y = act(P0[v] / sqrt(indeg(v)+1) + bias) on the listed rows, P0 of width N
-// (a GCN layer whose weights were applied to the messages before the aggregation); H, DP, out_compact as for k_gemm
+// The write-back of k_gemm without a product, on the listed rows, P0 of width N: y = act(P0[v] / sqrt(indeg(v)+1) + bias)
+// with a degree vector (a GCN layer whose weights were applied to the messages before the aggregation), or
+// y = act(P0[v] + bias + add[v] / add_indeg(v)) without one (GraphSAGE, CommNet: both halves of the weights applied
+// before the aggregation); H, DP, out_compact as for k_gemm
 nrt_status k_rowwise_update(const GemmArgs& a, hipStream_t s);
 nrt_status k_transpose(const float* W, float* Wt, int K, int N, hipStream_t s);   // Wt[n][k] = W[k][n]
 

@@ -233,7 +233,8 @@ __global__ void __launch_bounds__(WM * WN * 64) gemm_kernel(GemmArgs g) {
   }
 }
 
-// y = act(P0[v] * gcn_scale(v) + bias) with the same write-back as the GEMM's epilogue; a thread owns four columns of a row
+// y = act(P0[v] * scale(v) + bias + add[v] / count(v)) with the same write-back as the GEMM's epilogue; scale is the GCN
+// normalisation when a degree vector is given, else 1; the added row is optional; a thread owns four columns of a row
 __global__ void rowwise_update_kernel(GemmArgs g) {
     const int64_t M = g.M_dev ? (int64_t)*g.M_dev : g.M;
     float* const DPout = (g.dp_skip_large && 4 * M > g.n_vertices) ? nullptr : g.DP;
@@ -243,12 +244,20 @@ __global__ void rowwise_update_kernel(GemmArgs g) {
         const int64_t m = i / nq;
         const int n = (int)(i - m * nq) << 2;
         const int64_t v = g.rows ? (int64_t)g.rows[m] : m;
-        const float sc = gcn_scale(g.indeg[v]);
+        const float sc = g.indeg ? gcn_scale(g.indeg[v]) : 1.0f;
         const float4 x = *reinterpret_cast<const float4*>(g.P0 + v * g.N + n);
         float y[4] = {x.x * sc, x.y * sc, x.z * sc, x.w * sc};
+        float ad[4] = {0.f, 0.f, 0.f, 0.f};
+        if (g.add) {                      // same order as the GEMM epilogue that this replaces: (product + bias) + added row
+            float as = 1.0f;
+            if (g.add_indeg) { const int32_t dg = g.add_indeg[v]; as = dg > 0 ? 1.0f / (float)dg : 0.0f; }
+            const float4 q = *reinterpret_cast<const float4*>(g.add + v * g.N + n);
+            ad[0] = q.x * as; ad[1] = q.y * as; ad[2] = q.z * as; ad[3] = q.w * as;
+        }
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             if (g.bias) y[t] += g.bias[n + t];
+            if (g.add) y[t] += ad[t];
             if (g.act == 1) y[t] = fmaxf(y[t], 0.f);
             else if (g.act == 2) y[t] = y[t] > 0.f ? y[t] : expm1f(y[t]);
         }
@@ -312,7 +321,7 @@ nrt_status k_gemm(const GemmArgs& g, hipStream_t s) {
 
 nrt_status k_rowwise_update(const GemmArgs& g, hipStream_t s) {
     if (g.M <= 0) return NRT_OK;
-    if (g.N % 4 || !g.P0 || !g.indeg) { nrt_set_error("rowwise update: bad arguments"); return NRT_ERR_INVALID_ARG; }
+    if (g.N % 4 || !g.P0 || (!g.indeg && !g.add)) { nrt_set_error("rowwise update: bad arguments"); return NRT_ERR_INVALID_ARG; }
     int64_t blocks = cdiv(g.M * (g.N / 4), 256);
     if (blocks > 8192) blocks = 8192;
     rowwise_update_kernel<<<(unsigned)blocks, 256, 0, s>>>(g);

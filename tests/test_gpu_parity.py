@@ -611,22 +611,25 @@ def test_gcn_aggregate_only_storage(S, oracle):
             call()
         assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
     ses.mode(nb.NRT_MODE_INCREMENTAL)
-    # the models whose update reads the layer's own input beside the aggregate do not have the option
-    n2, s2, d2, w2, x2, spec2, params2, _ = small_case(wl.SAGE_MEAN, seed=9)
+    # a model whose update reads the layer's own input row beside the aggregate does not have the option
+    n2, s2, d2, w2, x2, spec2, params2, _ = small_case(wl.PINSAGE, seed=9)
     with pytest.raises(nb.NrtError) as ei:
         S.Session(dataclasses.replace(spec2, agg_only=True), params2, n2, s2, d2, w2, x2)
     assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
 
 
-@pytest.mark.parametrize("kind,dims", [(wl.GAT, None), (wl.RGAT, None), (wl.GIN, [32, 64, 64, 16]), (wl.GIN, [64, 64, 32, 32])])
+@pytest.mark.parametrize("kind,dims", [(wl.GAT, None), (wl.RGAT, None), (wl.GIN, [32, 64, 64, 16]), (wl.GIN, [64, 64, 32, 32]),
+                                       (wl.SAGE_MEAN, [32, 64, 64, 16]), (wl.SAGE_MEAN, [64, 64, 32, 32]),
+                                       (wl.COMMNET, [32, 64, 64, 16]), (wl.COMMNET, [64, 64, 32, 32])])
 def test_aggregate_only_storage_where_neighbours_read_a_message_table(S, oracle, kind, dims):
     """The same storage option for the models in which a vertex's row h^l reaches the next layer only through a table
     that is cached for every vertex anyway: the projections z of the attention models (whose update reads the
-    normalised sum alone), and GIN's messages h^l W_a on layers that apply W_a before the aggregation (whose update
-    reads the vertex's own message row and the aggregate).  The hidden rows are not kept by vertex; a batch hands the
+    normalised sum alone), GIN's messages h^l W_a on layers that apply W_a before the aggregation (whose update
+    reads the vertex's own message row and the aggregate), and the two products h^l W_1, h^l W_2 of GraphSAGE and
+    CommNet on such layers (the update adds the vertex's own row of the first to the aggregate of the second).  The hidden rows are not kept by vertex; a batch hands the
     rows it recomputes at one layer to the next layer's product in affected-set order.  Every processing mode still
-    works; what is refused is reading a hidden layer and the on-demand mode.  GIN cases: a first layer that widens (its
-    update is the two chained products on h^0) and one that does not."""
+    works; what is refused is reading a hidden layer and the on-demand mode.  Two shapes each: a first layer that widens
+    (its update is the written form on h^0) and one that does not."""
     import dataclasses
     from paper_2603_20622_amd import binding as nb
     n, src, dst, w, x, spec, params, stream = small_case(kind, seed=13, bias=True, L=3, dims=dims)
@@ -666,7 +669,7 @@ def test_aggregate_only_storage_where_neighbours_read_a_message_table(S, oracle,
     with pytest.raises(nb.NrtError) as ei:
         ses.lazy(True)
     assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
-    if kind == wl.GIN:
+    if dims is not None:
         # a layer above the first that widens, or the plain operation order, reads the hidden row itself: refused
         for bad in (dataclasses.replace(lean_spec, dims=[32, 64, 128, 16]), dataclasses.replace(lean_spec, aggregate_first=True)):
             with pytest.raises(nb.NrtError) as ei:
