@@ -117,8 +117,8 @@ typedef struct {
     const float* monet_prec[NRT_MAX_LAYERS]; /* device, MoNet only */
     int32_t agg_only;                   /* 1: keep only the aggregates of the hidden layers and recompute their rows when
                                            a batch needs them (Section IV, "Recomputation-based embedding storage
-                                           optimization").  GCN, GAT and RGAT, whose update reads the aggregate
-                                           alone, and GIN, GraphSAGE, CommNet when aggregate_first is 0 and
+                                           optimization").  GCN, GAT, RGAT and MoNet, whose update reads the
+                                           aggregate alone, RGCN, and GIN, GraphSAGE, CommNet when aggregate_first is 0 and
                                            d_l <= d_{l-1} for every layer above the first (the row is then read only
                                            through the cached products h W); NRT_ERR_UNSUPPORTED otherwise.  Saves
                                            N * (d_1 + ... + d_{L-1}) floats of the workspace; such a cache refuses

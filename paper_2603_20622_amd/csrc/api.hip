@@ -60,7 +60,7 @@ struct nrt_cache {
     float* MP[NRT_MAX_LAYERS + 1];      // PinSAGE, MoNet: message payload of layer l's rows (ReLU(h^l Q + q); the Gaussian
                                         // kernel responses of h^l), null otherwise
     float* MS[NRT_MAX_LAYERS + 1];      // GraphSAGE, CommNet on a weights-first layer l+1: h^l W_1 by vertex, the self half of
-                                        // that layer's update (the neighbour half h^l W_2 is MP[l]); null otherwise
+                                        // that layer's update (the neighbour half h^l W_2 is MP[l]); RGCN: h^l W_o; else null
     int monet_J;                        // MoNet: kernels per layer = width of its payload and aggregate
     int n_rel;                          // RGCN: relations; MP[l] then holds n_rel message rows W_r h^l per vertex
     // GCN, GIN, GraphSAGE, CommNet: layer l applies its (first / neighbour-side) weight matrix to the messages before the
@@ -382,8 +382,9 @@ static nrt_status check_desc(const nrt_model_desc* d) {
             }
     }
     const bool by_tables = d->kind == NRT_GIN || d->kind == NRT_SAGE_MEAN || d->kind == NRT_COMMNET;
-    if (d->agg_only && d->kind != NRT_GCN && d->kind != NRT_GAT && d->kind != NRT_RGAT && !by_tables) {
-        nrt_set_error("aggregate-only storage is available for GCN, GAT, RGAT, and for GIN, GraphSAGE and CommNet with weights-first layers");
+    if (d->agg_only && d->kind != NRT_GCN && d->kind != NRT_GAT && d->kind != NRT_RGAT && d->kind != NRT_RGCN &&
+        d->kind != NRT_MONET && !by_tables) {
+        nrt_set_error("aggregate-only storage is available for GCN, GAT, RGAT, RGCN, MoNet, and for GIN, GraphSAGE and CommNet with weights-first layers");
         return NRT_ERR_UNSUPPORTED;
     }
     if (d->agg_only && by_tables) {
@@ -433,7 +434,7 @@ static void cache_layout(Bump& b, nrt_cache* c) {
         if (c->kind == NRT_PINSAGE && l < c->L) c->MP[l] = b.take<float>(n * c->dims[l]);
         if (c->kind == NRT_RGCN && l < c->L) c->MP[l] = b.take<float>(n * c->n_rel * c->dims[l + 1]);
         if (l < c->L && c->tf[l + 1]) c->MP[l] = b.take<float>(n * c->dims[l + 1]);
-        c->MS[l] = (l < c->L && c->tf[l + 1] && concat_self(c->kind)) ? b.take<float>(n * c->dims[l + 1]) : nullptr;
+        c->MS[l] = (l < c->L && ((c->tf[l + 1] && concat_self(c->kind)) || c->kind == NRT_RGCN)) ? b.take<float>(n * c->dims[l + 1]) : nullptr;
         if (c->kind == NRT_MONET && l < c->L) {
             c->MP[l] = b.take<float>(n * c->monet_J);
             c->muT[l] = b.take<float>((size_t)c->dims[l] * c->monet_J);
@@ -602,11 +603,12 @@ static nrt_status read_ctrs(nrt_graph* g, hipStream_t s) {
     return NRT_OK;
 }
 
-// Aggregate-only storage of GIN, GraphSAGE, CommNet: the two delta buffers have fixed roles instead of alternating with
+// Aggregate-only storage of GIN, GraphSAGE, CommNet, RGCN, MoNet: the two delta buffers have fixed roles instead of alternating with
 // the layers.  DP[0] holds the compact payload deltas a layer's gather folds; DP[1] the compact rows h^l that the update
 // of layer l hands to the message products of layer l+1 (written after those products of layer l have read it).
 static inline bool rows_by_tables(const nrt_cache* c) {
-    return c->agg_only && (c->kind == NRT_GIN || c->kind == NRT_SAGE_MEAN || c->kind == NRT_COMMNET);
+    return c->agg_only && (c->kind == NRT_GIN || c->kind == NRT_SAGE_MEAN || c->kind == NRT_COMMNET || c->kind == NRT_RGCN ||
+                           c->kind == NRT_MONET);
 }
 static inline float* delta_buf(nrt_cache* c, int prev) { return rows_by_tables(c) ? c->DP[0] : c->DP[prev]; }
 
@@ -625,6 +627,11 @@ static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_
         m.count_dev = M_dev;
         m.bound = M;
         m.H = c->H[l];
+        if (!c->H[l]) {                    // aggregate-only storage: the rows the update of layer l handed over, in list order
+            if (!rows) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+            m.H = c->DP[1];
+            m.h_is_compact = 1;
+        }
         m.d = c->dims[l];
         m.muT = c->muT[l];
         m.precT = c->precT[l];
@@ -677,8 +684,10 @@ static nrt_status run_transform(nrt_cache* c, int l, const int32_t* rows, int64_
     a.dp_skip_large = skip_dp_when_large;
     a.n_vertices = c->g->n;
     NRT_TRY(k_gemm(a, s));
-    if (c->MS[l]) {                        // the self half h^l W_1 of the same rows; nobody folds its deltas
+    if (c->MS[l]) {                        // the self half h^l W_1 (RGCN: h^l W_o) of the same rows; nobody folds its deltas
+        a.N = c->dims[l + 1];
         a.Wt = c->Wt[l][0];
+        if (c->kind == NRT_RGCN) a.ldw = 0;
         a.H = c->MS[l];
         a.DP = nullptr;
         a.dp_skip_large = 0;
@@ -779,6 +788,11 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
         a.n_vertices = g->n;
         a.out_compact = last ? out_rows : nullptr;
         a.out_cap = out_cap;
+        if (!last && !c->H[l]) {           // aggregate-only storage: the rows go compact to the next layer's kernel responses
+            if (!rows) { nrt_set_error("hidden rows are not kept"); return NRT_ERR_STATE; }
+            a.out_compact = c->DP[1];
+            a.out_cap = g->n;
+        }
         NRT_TRY(k_gemm(a, s));
     } else if (c->tf[l] && c->kind == NRT_GCN) {   // the weights went into the messages: act(S_v / sqrt(d_v) + b), no product left
         a.P0 = c->S[l];
@@ -815,8 +829,10 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
             a.out_cap = g->n;
         }
         NRT_TRY(k_gemm(a, s));
-    } else if (c->tf[l] && concat_self(c->kind)) {  // act(x_v W_1 + S_v / count + b) from the two cached products: S_v is the
-        a.P0 = c->MS[l - 1];                        // sum of x_u W_2 (CommNet: no count), x_v W_1 a cached row; no product left
+    } else if ((c->tf[l] && concat_self(c->kind)) || c->kind == NRT_RGCN) {
+        // act(x_v W_1 + S_v / count + b) from the two cached products: S_v is the sum of x_u W_2 (CommNet: no count), x_v W_1
+        // a cached row; RGCN: sigma(x_v W_o + a_v), a_v = cached sum of relation messages / neighbour count.  No product left.
+        a.P0 = c->MS[l - 1];
         a.indeg = nullptr;
         a.add = c->S[l];
         a.add_indeg = c->kind == NRT_COMMNET ? nullptr : g->in.deg;
@@ -834,20 +850,6 @@ static nrt_status run_update(nrt_cache* c, int l, const int32_t* rows, int64_t M
             a.out_cap = g->n;
         }
         NRT_TRY(k_rowwise_update(a, s));
-    } else if (c->kind == NRT_RGCN) {       // sigma(W_o h_v + a_v), a_v = cached sum of relation messages / neighbour count
-        a.a_mode = A_PLAIN_ADD;
-        a.P0 = c->H[l - 1];
-        a.K = c->dims[l - 1];
-        a.add = c->S[l];
-        a.add_indeg = g->in.deg;
-        a.Wt = c->Wt[l - 1][0];
-        a.bias = c->bias[l - 1][0];
-        a.act = last ? 0 : 1;
-        a.H = c->H[l];
-        a.n_vertices = g->n;
-        a.out_compact = last ? out_rows : nullptr;
-        a.out_cap = out_cap;
-        NRT_TRY(k_gemm(a, s));
     } else if (c->kind == NRT_GCN || concat_self(c->kind)) {
         if (c->kind == NRT_GCN) {
             a.a_mode = A_SCALE_GCN;

@@ -431,6 +431,7 @@ struct MonetArgs {
     const uint64_t* count_dev;      // their number on the device (with rows)
     int64_t bound;
     const float* H; int d;          // [N][d] layer input
+    int h_is_compact;               // H holds the listed rows only, in list order (rows[] addresses G alone)
     const float* muT; const float* precT;   // [d][J] transposed means and diagonal precisions
     int J;
     float* G;                       // [N][J] kernel responses, by vertex

@@ -19,7 +19,8 @@ __global__ void __launch_bounds__(MN_WAVES * 64) monet_transform_kernel(MonetArg
     const int d = a.d, J = a.J;
     for (int64_t m = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6; m < count; m += waves) {
         const int64_t v = a.rows ? (int64_t)a.rows[m] : m;
-        for (int k = lane; k < d; k += 64) s_row[w][k] = a.H[v * d + k];
+        const int64_t hr = a.h_is_compact ? m : v;        // compact input: row m belongs to vertex rows[m]
+        for (int k = lane; k < d; k += 64) s_row[w][k] = a.H[hr * d + k];
         __builtin_amdgcn_wave_barrier();
         for (int j = lane; j < J; j += 64) {
             float q = 0.f;

@@ -620,13 +620,16 @@ def test_gcn_aggregate_only_storage(S, oracle):
 
 @pytest.mark.parametrize("kind,dims", [(wl.GAT, None), (wl.RGAT, None), (wl.GIN, [32, 64, 64, 16]), (wl.GIN, [64, 64, 32, 32]),
                                        (wl.SAGE_MEAN, [32, 64, 64, 16]), (wl.SAGE_MEAN, [64, 64, 32, 32]),
-                                       (wl.COMMNET, [32, 64, 64, 16]), (wl.COMMNET, [64, 64, 32, 32])])
+                                       (wl.COMMNET, [32, 64, 64, 16]), (wl.COMMNET, [64, 64, 32, 32]),
+                                       (wl.RGCN, [32, 64, 128, 16]), (wl.MONET, [32, 64, 128, 16])])
 def test_aggregate_only_storage_where_neighbours_read_a_message_table(S, oracle, kind, dims):
     """The same storage option for the models in which a vertex's row h^l reaches the next layer only through a table
     that is cached for every vertex anyway: the projections z of the attention models (whose update reads the
     normalised sum alone), GIN's messages h^l W_a on layers that apply W_a before the aggregation (whose update
     reads the vertex's own message row and the aggregate), and the two products h^l W_1, h^l W_2 of GraphSAGE and
-    CommNet on such layers (the update adds the vertex's own row of the first to the aggregate of the second).  The hidden rows are not kept by vertex; a batch hands the
+    CommNet on such layers (the update adds the vertex's own row of the first to the aggregate of the second), the
+    relation messages and the self product h^l W_o of RGCN, and MoNet's kernel responses (its update reads the
+    aggregate alone).  The hidden rows are not kept by vertex; a batch hands the
     rows it recomputes at one layer to the next layer's product in affected-set order.  Every processing mode still
     works; what is refused is reading a hidden layer and the on-demand mode.  Two shapes each: a first layer that widens
     (its update is the written form on h^0) and one that does not."""
@@ -669,7 +672,7 @@ def test_aggregate_only_storage_where_neighbours_read_a_message_table(S, oracle,
     with pytest.raises(nb.NrtError) as ei:
         ses.lazy(True)
     assert ei.value.status == nb.NRT_ERR_UNSUPPORTED
-    if dims is not None:
+    if kind in (wl.GIN, wl.SAGE_MEAN, wl.COMMNET):
         # a layer above the first that widens, or the plain operation order, reads the hidden row itself: refused
         for bad in (dataclasses.replace(lean_spec, dims=[32, 64, 128, 16]), dataclasses.replace(lean_spec, aggregate_first=True)):
             with pytest.raises(nb.NrtError) as ei:

@@ -116,13 +116,13 @@ def test_random_case(S, oracle, seed):
         _check_layers(S, oracle, ses, spec, params, n, cur, L, (seed, "flush"))
 
 
-AGG_ONLY_KINDS = [wl.GCN, wl.GAT, wl.RGAT, wl.GIN, wl.SAGE_MEAN, wl.COMMNET]
+AGG_ONLY_KINDS = [wl.GCN, wl.GAT, wl.RGAT, wl.GIN, wl.SAGE_MEAN, wl.COMMNET, wl.RGCN, wl.MONET]
 
 
 @pytest.mark.parametrize("seed", range(48))
 def test_random_case_with_aggregate_only_storage(S, oracle, seed):
     """The storage option of Section IV ("recomputation-based embedding storage optimization") on random cases: the
-    hidden rows are not kept by vertex, everything else as in test_random_case.  Models that have the option; for GIN,
+    hidden rows are not kept by vertex, everything else as in test_random_case.  The eight models that have the option; for GIN,
     GraphSAGE and CommNet the widths above the first layer do not grow (the condition of the option).  Checked after
     every batch: affected set, final layer against the oracle, the returned rows."""
     import dataclasses
@@ -138,8 +138,9 @@ def test_random_case_with_aggregate_only_storage(S, oracle, seed):
     elif kind == wl.RGAT:
         hd, n_rel = int(rng.choice([4, 8, 16, 68])), int(rng.choice([1, 2, 5]))
         dims = [int(rng.choice([4, 8, 20]))] + [hd] * L
-    elif kind == wl.GCN:
+    elif kind in (wl.GCN, wl.RGCN, wl.MONET):
         dims = [int(rng.choice([4, 8, 12, 32, 68, 128])) for _ in range(L + 1)]
+        n_rel = int(rng.choice([1, 2, 5])) if kind == wl.RGCN else 0
     else:
         widths = sorted((int(rng.choice([4, 8, 12, 32, 68, 128])) for _ in range(L)), reverse=True)
         dims = [int(rng.choice([4, 8, 32, 128]))] + widths
@@ -148,7 +149,8 @@ def test_random_case_with_aggregate_only_storage(S, oracle, seed):
     w = wl.edge_weights(e, seed) if weighted else None
     if n_rel:
         weighted, w = True, wl.relation_ids(e, n_rel, seed)
-    spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=hd, weighted=weighted, n_relations=n_rel)
+    spec = wl.ModelSpec(kind, dims, heads=heads, head_dim=hd, weighted=weighted, n_relations=n_rel,
+                        monet_kernels=int(rng.choice([4, 12, 40])))
     params = wl.make_params(spec, seed, bias=bool(rng.integers(0, 2)))
     x = wl.features(n, dims[0], seed)
     stream = wl.BatchStream(n, src, dst, w, sampler, dims[0], seed, n_rel)
