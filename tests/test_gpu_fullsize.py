@@ -90,6 +90,17 @@ def test_config5_full_size(S, oracle):
     run_config(S, oracle, 5, [50000, 50000])
 
 
+@pytest.mark.parametrize("index", [2, 5])
+def test_full_size_with_aggregate_only_storage(S, oracle, index):
+    """Configs 2 (GraphSAGE) and 5 (GAT) at full size on a cache that does not keep its hidden rows (Section IV,
+    "recomputation-based embedding storage optimization"): same checks as with the rows kept."""
+    import dataclasses
+    cfg = wl.config(index - 1, 1.0)
+    cfg.spec = dataclasses.replace(cfg.spec, agg_only=True)
+    cfg.name += "_agg_only"
+    run_workload(S, oracle, cfg, [cfg.n_ins + cfg.n_del] * (20 if index == 2 else 2))
+
+
 @pytest.mark.parametrize("name", ["rgcn", "rgat"])
 def test_typed_edge_models_at_config2_size(S, oracle, name):
     """The typed-edge models of Table II have no configuration of their own: they run on config 2's graph (1 M vertices,
